@@ -1,0 +1,283 @@
+"""CPU float64 oracle for the NTP shard hot path.  TEST INFRASTRUCTURE ONLY.
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may use
+this module.  The product (the HIP library and its Python binding) never
+imports it, and this module imports nothing from the product.
+
+Everything is the plain definition written out with numpy in float64:
+a sharded layer is an exact re-association of the unsharded one (Sec. 3.1,
+Eq. 1-6), and a reshard is a permutation of elements.  numpy's matmul is
+used as a library step; there is no tiling, fusion or reordering here.
+
+Notation (Sec. 3.1): X is the input [M x H]; A [H x n] is column-partitioned
+into A_i, B [n x H] is row-partitioned into B_i; t is the full TP degree and
+t' the reduced one.  The oracle keeps the paper's orientation of A and B.
+All functions take and return float64 arrays unless they move opaque bits.
+
+Every function here is pinned by tests/test_oracle_*.py against values the
+paper prints, closed forms, brute force or finite differences; none is
+"parity unpinned".
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+from scipy.special import erf as _erf
+
+GELU_ERF = 0   # x * Phi(x), the exact form
+GELU_TANH = 1  # the tanh approximation
+
+
+# ----------------------------------------------------------------------------
+# Shard plans (Sec. 3.1, last paragraph of "Attention blocks": the partition
+# dimension may not divide evenly; units are split as evenly as possible and
+# the remainder goes to the lowest ranks).
+# ----------------------------------------------------------------------------
+def shard_plan(dim: int, tp: int, rank: int) -> tuple[int, int]:
+    """(offset, width) of `rank`'s contiguous slice when `dim` units are split over `tp` ranks."""
+    if dim < 0 or tp < 1 or not (0 <= rank < tp):
+        raise ValueError("bad shard_plan arguments")
+    base, rem = divmod(dim, tp)
+    width = base + (1 if rank < rem else 0)
+    offset = rank * base + min(rank, rem)
+    return offset, width
+
+
+def attn_shard_plan(n_q: int, n_kv: int, tp: int, rank: int) -> dict:
+    """Head-granular plan.  Query heads are the partition unit (Eq. 4-6: the
+    W_Q, W_K, W_V, W_O of a head are co-located); with grouped KV heads a rank
+    holds every KV head that one of its query heads reads."""
+    if n_kv < 1 or n_q % n_kv != 0:
+        raise ValueError("n_q must be a multiple of n_kv")
+    group = n_q // n_kv
+    q_off, q_cnt = shard_plan(n_q, tp, rank)
+    if q_cnt == 0:
+        return dict(q_off=q_off, q_cnt=0, kv_off=0, kv_cnt=0)
+    kv_first = q_off // group
+    kv_last = (q_off + q_cnt - 1) // group
+    return dict(q_off=q_off, q_cnt=q_cnt, kv_off=kv_first, kv_cnt=kv_last - kv_first + 1)
+
+
+def overlap_segments(dim: int, src_tp: int, dst_tp: int) -> list[tuple[int, int, int, int]]:
+    """Sub-shards made by overlaying two contiguous plans of the same `dim`
+    (Sec. 3.1, the paragraph with the hidden-size-12K example).
+    Returns (src_rank, dst_rank, first_unit, length) for every non-empty overlap."""
+    segs = []
+    for r in range(src_tp):
+        so, sw = shard_plan(dim, src_tp, r)
+        for s in range(dst_tp):
+            do, dw = shard_plan(dim, dst_tp, s)
+            lo, hi = max(so, do), min(so + sw, do + dw)
+            if hi > lo:
+                segs.append((r, s, lo, hi - lo))
+    return segs
+
+
+# ----------------------------------------------------------------------------
+# GeLU and its derivative.
+# ----------------------------------------------------------------------------
+def gelu(x: np.ndarray, mode: int = GELU_ERF) -> np.ndarray:
+    x = np.asarray(x, dtype=np.float64)
+    if mode == GELU_ERF:
+        return x * 0.5 * (1.0 + _erf(x / math.sqrt(2.0)))
+    if mode == GELU_TANH:
+        u = math.sqrt(2.0 / math.pi) * (x + 0.044715 * x ** 3)
+        return 0.5 * x * (1.0 + np.tanh(u))
+    raise ValueError("unknown gelu mode")
+
+
+def gelu_grad(x: np.ndarray, mode: int = GELU_ERF) -> np.ndarray:
+    x = np.asarray(x, dtype=np.float64)
+    if mode == GELU_ERF:
+        cdf = 0.5 * (1.0 + _erf(x / math.sqrt(2.0)))
+        pdf = np.exp(-0.5 * x * x) / math.sqrt(2.0 * math.pi)
+        return cdf + x * pdf
+    if mode == GELU_TANH:
+        c = math.sqrt(2.0 / math.pi)
+        u = c * (x + 0.044715 * x ** 3)
+        th = np.tanh(u)
+        du = c * (1.0 + 3.0 * 0.044715 * x * x)
+        return 0.5 * (1.0 + th) + 0.5 * x * (1.0 - th * th) * du
+    raise ValueError("unknown gelu mode")
+
+
+# ----------------------------------------------------------------------------
+# MLP block (Eq. 1-3).
+# ----------------------------------------------------------------------------
+def mlp_unsharded_fwd(X, A, B, mode=GELU_ERF):
+    """Eq. 1: Z = GeLU(X A) B.  Returns (P, Y, Z) with P = X A."""
+    P = X @ A
+    Y = gelu(P, mode)
+    return P, Y, Y @ B
+
+
+def mlp_unsharded_bwd(dZ, X, A, B, mode=GELU_ERF):
+    """Gradients of L = sum(Z * dZ) for Eq. 1.  Returns (dX, dA, dB)."""
+    P = X @ A
+    Y = gelu(P, mode)
+    dP = (dZ @ B.T) * gelu_grad(P, mode)
+    return dP @ A.T, X.T @ dP, Y.T @ dZ
+
+
+def mlp_shard_fwd(X, A_i, B_i, mode=GELU_ERF):
+    """Eq. 3 then Eq. 2 for one shard: P_i = X A_i, Y_i = GeLU(P_i), Zhat_i = Y_i B_i.
+    A_i is [H x n_r] (columns of A), B_i is [n_r x H] (rows of B)."""
+    P = X @ A_i
+    Y = gelu(P, mode)
+    return P, Y, Y @ B_i
+
+
+def mlp_shard_bwd(dZ, X, A_i, B_i, mode=GELU_ERF):
+    """Chain rule on Eq. 2-3 for one shard.  The gradients have the shape and
+    partition of A_i / B_i (Sec. 3.1).  Returns (dP_i, dXhat_i, dA_i, dB_i);
+    dXhat_i is this shard's partial sum of dX."""
+    P = X @ A_i
+    Y = gelu(P, mode)
+    dY = dZ @ B_i.T
+    dP = dY * gelu_grad(P, mode)
+    dB = Y.T @ dZ
+    dA = X.T @ dP
+    dX = dP @ A_i.T
+    return dP, dX, dA, dB
+
+
+# ----------------------------------------------------------------------------
+# Attention block projections (Eq. 4-6) and, for the invariants only, the
+# attention core of Eq. 5.
+# ----------------------------------------------------------------------------
+def attention_core(Q, K, V):
+    """softmax(Q K^T / sqrt(d)) V for one head; Q, K, V are [M x d].  Not on the hot path."""
+    d = Q.shape[1]
+    S = (Q @ K.T) / math.sqrt(d)
+    S = S - S.max(axis=1, keepdims=True)
+    E = np.exp(S)
+    return (E / E.sum(axis=1, keepdims=True)) @ V
+
+
+def attn_shard_weights(Wq, Wk, Wv, Wo, n_q, n_kv, d, tp, rank):
+    """Cut one rank's W_qkv,i [H x (q_cnt + 2 kv_cnt) d] (columns ordered
+    [Q heads | K heads | V heads]) and W_O,i [q_cnt d x H] out of the full
+    Wq [H x n_q d], Wk, Wv [H x n_kv d], Wo [n_q d x H]."""
+    p = attn_shard_plan(n_q, n_kv, tp, rank)
+    qs = slice(p["q_off"] * d, (p["q_off"] + p["q_cnt"]) * d)
+    ks = slice(p["kv_off"] * d, (p["kv_off"] + p["kv_cnt"]) * d)
+    Wqkv_i = np.concatenate([Wq[:, qs], Wk[:, ks], Wv[:, ks]], axis=1)
+    return p, Wqkv_i, Wo[qs, :]
+
+
+def attn_proj_shard_fwd(X, Wqkv_i, C_i, Wo_i):
+    """Eq. 6: [Q_i K_i V_i] = X W_qkv,i ; Eq. 4: Zhat_i = C_i W_O,i where C_i is
+    the attention output of this rank's heads (an input here)."""
+    return X @ Wqkv_i, C_i @ Wo_i
+
+
+def attn_proj_shard_bwd(dZ, dQKV_i, X, C_i, Wqkv_i, Wo_i):
+    """Adjoint of the two projections.  Returns (dC_i, dXhat_i, dWqkv_i, dWo_i)."""
+    dC = dZ @ Wo_i.T
+    dWo = C_i.T @ dZ
+    dX = dQKV_i @ Wqkv_i.T
+    dWqkv = X.T @ dQKV_i
+    return dC, dX, dWqkv, dWo
+
+
+def attn_unsharded_fwd(X, Wq, Wk, Wv, Wo, n_q, n_kv, d):
+    """Eq. 4-6 for the whole layer with grouped KV heads (query head h reads KV head h // (n_q/n_kv))."""
+    group = n_q // n_kv
+    Q, K, V = X @ Wq, X @ Wk, X @ Wv
+    heads = []
+    for h in range(n_q):
+        g = h // group
+        heads.append(attention_core(Q[:, h * d:(h + 1) * d], K[:, g * d:(g + 1) * d], V[:, g * d:(g + 1) * d]))
+    return np.concatenate(heads, axis=1) @ Wo
+
+
+def attn_shard_layer_fwd(X, Wq, Wk, Wv, Wo, n_q, n_kv, d, tp, rank):
+    """One rank's partial sum Zhat_i of the attention layer, going through the
+    shard's own projections and the attention core on its local heads."""
+    group = n_q // n_kv
+    p, Wqkv_i, Wo_i = attn_shard_weights(Wq, Wk, Wv, Wo, n_q, n_kv, d, tp, rank)
+    if p["q_cnt"] == 0:
+        return np.zeros((X.shape[0], Wo.shape[1]))
+    QKV = X @ Wqkv_i
+    qw, kw = p["q_cnt"] * d, p["kv_cnt"] * d
+    Ql, Kl, Vl = QKV[:, :qw], QKV[:, qw:qw + kw], QKV[:, qw + kw:]
+    heads = []
+    for j in range(p["q_cnt"]):
+        g = (p["q_off"] + j) // group - p["kv_off"]
+        heads.append(attention_core(Ql[:, j * d:(j + 1) * d], Kl[:, g * d:(g + 1) * d], Vl[:, g * d:(g + 1) * d]))
+    C_i = np.concatenate(heads, axis=1)
+    _, Z = attn_proj_shard_fwd(X, Wqkv_i, C_i, Wo_i)
+    return Z
+
+
+# ----------------------------------------------------------------------------
+# Gradient reshard (Sec. 3.1 "Shard-mapping algorithm", Appendix hook): both
+# layouts are views of one logical tensor partitioned along `partition_dim`
+# in units of `unit` elements.
+# ----------------------------------------------------------------------------
+PLAIN = 0
+QKV_GQA = 1
+
+
+def unit_list(kind, n_units, tp, rank, n_q=0, n_kv=0) -> list[int]:
+    """Logical unit ids held by `rank`, in the order they sit in its shard.
+    PLAIN: a contiguous range of `n_units`.  QKV_GQA: logical units are
+    [n_q Q heads | n_kv K heads | n_kv V heads]; a rank holds its Q heads, then
+    the K heads they read, then the same V heads."""
+    if kind == PLAIN:
+        off, w = shard_plan(n_units, tp, rank)
+        return list(range(off, off + w))
+    if kind == QKV_GQA:
+        if n_units != n_q + 2 * n_kv:
+            raise ValueError("n_units must be n_q + 2 n_kv")
+        p = attn_shard_plan(n_q, n_kv, tp, rank)
+        q = list(range(p["q_off"], p["q_off"] + p["q_cnt"]))
+        k = [n_q + g for g in range(p["kv_off"], p["kv_off"] + p["kv_cnt"])]
+        v = [n_q + n_kv + g for g in range(p["kv_off"], p["kv_off"] + p["kv_cnt"])]
+        return q + k + v
+    raise ValueError("unknown kind")
+
+
+def cut_shard(G, partition_dim, unit, kind, tp, rank, n_q=0, n_kv=0):
+    """Cut one rank's shard out of the logical tensor G by fancy indexing."""
+    n_units = G.shape[partition_dim] // unit
+    ids = unit_list(kind, n_units, tp, rank, n_q, n_kv)
+    idx = np.concatenate([np.arange(u * unit, (u + 1) * unit) for u in ids]) if ids else np.zeros(0, dtype=np.int64)
+    return np.take(G, idx, axis=partition_dim)
+
+
+def reshard(src_shards, partition_dim, unit, kind, src_tp, dst_tp, n_units, n_q=0, n_kv=0):
+    """Repack shards of the TP=src_tp layout into the TP=dst_tp layout, unit by
+    unit: destination unit u of rank s is copied from the lowest source rank
+    that holds u.  Moves bits; dtype is whatever the shards carry."""
+    where = {}
+    for r in range(src_tp):
+        for local, u in enumerate(unit_list(kind, n_units, src_tp, r, n_q, n_kv)):
+            where.setdefault(u, (r, local))
+    out = []
+    for s in range(dst_tp):
+        ids = unit_list(kind, n_units, dst_tp, s, n_q, n_kv)
+        shape = list(src_shards[0].shape)
+        shape[partition_dim] = len(ids) * unit
+        D = np.empty(shape, dtype=src_shards[0].dtype)
+        for local, u in enumerate(ids):
+            r, sl = where[u]
+            dsl = [slice(None)] * D.ndim
+            ssl = [slice(None)] * D.ndim
+            dsl[partition_dim] = slice(local * unit, (local + 1) * unit)
+            ssl[partition_dim] = slice(sl * unit, (sl + 1) * unit)
+            D[tuple(dsl)] = src_shards[r][tuple(ssl)]
+        out.append(D)
+    return out
+
+
+def reshard_source_of(kind, n_units, src_tp, dst_tp, dst_rank, dst_local_unit, n_q=0, n_kv=0):
+    """Where one destination unit comes from: (src_rank, src_local_unit).  Used
+    to check sampled outputs at sizes where `reshard` itself is too slow."""
+    u = unit_list(kind, n_units, dst_tp, dst_rank, n_q, n_kv)[dst_local_unit]
+    for r in range(src_tp):
+        ids = unit_list(kind, n_units, src_tp, r, n_q, n_kv)
+        if u in ids:
+            return r, ids.index(u)
+    raise AssertionError("unit not held by any source rank")

@@ -1,0 +1,116 @@
+"""Pins for the oracle's gradient reshard (CPU only)."""
+import numpy as np
+import pytest
+
+from oracle import ntp_oracle as O
+
+
+def _logical(rows, cols, seed=0):
+    # distinct integers so that any misplaced element is visible; viewed as opaque 32-bit words
+    g = np.random.default_rng(seed)
+    return g.permutation(rows * cols).astype(np.uint32).reshape(rows, cols)
+
+
+def _cut_all(G, pd, unit, kind, tp, n_q=0, n_kv=0):
+    return [O.cut_shard(G, pd, unit, kind, tp, r, n_q, n_kv) for r in range(tp)]
+
+
+@pytest.mark.parametrize("pd", [0, 1])
+@pytest.mark.parametrize("unit", [1, 4])
+@pytest.mark.parametrize("n_units,a,b", [(29, 7, 8), (29, 8, 7), (12, 3, 4), (5, 8, 3), (30, 30, 32), (16, 4, 4)])
+def test_reshard_brute_force_index_map(pd, unit, n_units, a, b):
+    other = 6
+    shape = (n_units * unit, other) if pd == 0 else (other, n_units * unit)
+    G = _logical(*shape)
+    src = _cut_all(G, pd, unit, O.PLAIN, a)
+    dst = O.reshard(src, pd, unit, O.PLAIN, a, b, n_units)
+    # brute force: walk every logical element, find its place in both layouts
+    for j in range(n_units * unit):
+        u = j // unit
+        r = next(r for r in range(a) if O.shard_plan(n_units, a, r)[0] <= u < sum(O.shard_plan(n_units, a, r)))
+        s = next(s for s in range(b) if O.shard_plan(n_units, b, s)[0] <= u < sum(O.shard_plan(n_units, b, s)))
+        jl_src = j - O.shard_plan(n_units, a, r)[0] * unit
+        jl_dst = j - O.shard_plan(n_units, b, s)[0] * unit
+        for o in range(other):
+            if pd == 0:
+                assert dst[s][jl_dst, o] == src[r][jl_src, o] == G[j, o]
+            else:
+                assert dst[s][o, jl_dst] == src[r][o, jl_src] == G[o, j]
+    # shapes: shard widths follow the plan
+    for s in range(b):
+        assert dst[s].shape[pd] == O.shard_plan(n_units, b, s)[1] * unit
+
+
+@pytest.mark.parametrize("pd", [0, 1])
+def test_reshard_equals_cutting_the_logical_tensor(pd):
+    G = _logical(120, 6) if pd == 0 else _logical(6, 120)
+    for a, b in [(7, 8), (8, 7), (30, 32), (5, 5), (1, 9)]:
+        dst = O.reshard(_cut_all(G, pd, 1, O.PLAIN, a), pd, 1, O.PLAIN, a, b, 120)
+        for s, want in enumerate(_cut_all(G, pd, 1, O.PLAIN, b)):
+            assert np.array_equal(dst[s], want)
+
+
+def test_reshard_round_trip_and_composition():
+    G = _logical(8, 213)
+    src = _cut_all(G, 1, 1, O.PLAIN, 8)
+    a = 8
+    for b in (7, 9, 3):
+        mid = O.reshard(src, 1, 1, O.PLAIN, a, b, 213)
+        back = O.reshard(mid, 1, 1, O.PLAIN, b, a, 213)
+        assert all(np.array_equal(x, y) for x, y in zip(back, src))
+    ab = O.reshard(src, 1, 1, O.PLAIN, 8, 7, 213)
+    abc = O.reshard(ab, 1, 1, O.PLAIN, 7, 5, 213)
+    ac = O.reshard(src, 1, 1, O.PLAIN, 8, 5, 213)
+    assert all(np.array_equal(x, y) for x, y in zip(abc, ac))
+    same = O.reshard(src, 1, 1, O.PLAIN, 8, 8, 213)
+    assert all(np.array_equal(x, y) for x, y in zip(same, src))
+
+
+def test_reshard_preserves_bits():
+    # NaN payloads, -0 and denormals travel unchanged (32-bit words, not floats)
+    words = np.array([0x7FC00001, 0xFFC12345, 0x80000000, 0x00000001, 0x7F800000, 0x3F800000], dtype=np.uint32)
+    G = np.tile(words, (2, 1)).view(np.float32)
+    src = _cut_all(G, 1, 1, O.PLAIN, 2)
+    dst = O.reshard(src, 1, 1, O.PLAIN, 2, 3, 6)
+    got = np.concatenate([d.view(np.uint32) for d in dst], axis=1)
+    assert np.array_equal(got, np.tile(words, (2, 1)))
+
+
+@pytest.mark.parametrize("pd", [0, 1])
+def test_reshard_qkv_gqa(pd):
+    n_q, n_kv, d, other = 8, 2, 3, 5
+    n_units = n_q + 2 * n_kv
+    G = _logical(n_units * d, other) if pd == 0 else _logical(other, n_units * d)
+    for a, b in [(3, 4), (4, 3), (5, 8), (8, 5), (2, 2)]:
+        src = _cut_all(G, pd, d, O.QKV_GQA, a, n_q, n_kv)
+        dst = O.reshard(src, pd, d, O.QKV_GQA, a, b, n_units, n_q, n_kv)
+        for s, want in enumerate(_cut_all(G, pd, d, O.QKV_GQA, b, n_q, n_kv)):
+            assert np.array_equal(dst[s], want)
+        back = O.reshard(dst, pd, d, O.QKV_GQA, b, a, n_units, n_q, n_kv)
+        assert all(np.array_equal(x, y) for x, y in zip(back, src))
+
+
+def test_reshard_gqa_reads_lowest_source_rank():
+    # KV head 0 is replicated on ranks 0 and 1 (4 query heads, 1 KV head, TP 2); make the
+    # replicas differ and check that the destination takes rank 0's copy.
+    n_q, n_kv, d = 4, 1, 2
+    n_units = 6
+    G = _logical(3, n_units * d)
+    src = _cut_all(G, 1, d, O.QKV_GQA, 2, n_q, n_kv)
+    src[1] = src[1].copy()
+    src[1][:, 2 * d:] = 0xDEAD  # rank 1's K and V copies
+    dst = O.reshard(src, 1, d, O.QKV_GQA, 2, 4, n_units, n_q, n_kv)
+    for s in range(4):
+        assert np.array_equal(dst[s][:, d:2 * d], G[:, 4 * d:5 * d])  # K head from the logical tensor
+        assert np.array_equal(dst[s][:, 2 * d:], G[:, 5 * d:6 * d])
+        assert O.reshard_source_of(O.QKV_GQA, n_units, 2, 4, s, 1, n_q, n_kv) == (0, 2)
+
+
+def test_reshard_source_of_agrees_with_reshard():
+    G = _logical(4, 97)
+    src = _cut_all(G, 1, 1, O.PLAIN, 7)
+    dst = O.reshard(src, 1, 1, O.PLAIN, 7, 8, 97)
+    for s in range(8):
+        for lu in range(dst[s].shape[1]):
+            r, sl = O.reshard_source_of(O.PLAIN, 97, 7, 8, s, lu)
+            assert np.array_equal(dst[s][:, lu], src[r][:, sl])
