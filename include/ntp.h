@@ -1,0 +1,208 @@
+/*
+ * ntp.h -- C ABI of the MI355X (gfx950) shard hot path of Nonuniform Tensor
+ * Parallelism (NTP).
+ *
+ * A data-parallel replica that lost GPUs runs at a reduced tensor-parallel
+ * degree t' < t, so each surviving GPU computes an uneven shard of every
+ * transformer layer, and weight gradients have to be repacked between the
+ * TP = t' and TP = t layouts around the data-parallel sync.  This library is
+ * one GPU's part of that: the shard plan, the shard's MLP and attention
+ * projection GEMMs (forward and backward), and the gradient reshard.
+ *
+ * Conventions shared by every call
+ *   - "device" pointers are HIP device memory owned by the caller; "host"
+ *     pointers are ordinary process memory.  The library allocates nothing,
+ *     keeps no pointer after a call returns, and never synchronises: kernels
+ *     are enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and the call returns at once.
+ *   - Matrices are row-major with an explicit leading dimension `ld*` counted
+ *     in ELEMENTS.  bf16 matrices need a 16-byte aligned base pointer and
+ *     ld % 8 == 0; fp32 gradient matrices need a 16-byte aligned base and
+ *     ld % 4 == 0.  A violated requirement returns NTP_ERR_ALIGNMENT; nothing
+ *     is launched.
+ *   - Return value: NTP_OK (0) or a negative NTP_ERR_* code; no C++ exception
+ *     crosses the boundary.  ntp_status_string() names a code.
+ *   - bf16 = bfloat16 bit patterns (uint16_t storage), rounded to nearest even
+ *     on output; all contractions accumulate in fp32 on the matrix cores.
+ *
+ * Storage of the partitioned weights.  The paper writes the MLP as
+ * Z = GeLU(X A) B with A split by columns and B by rows (Sec. 3.1, Eq. 1-3).
+ * Both shards are held here with the partitioned dimension OUTERMOST:
+ *     A_t  [n_r x H]   row j = column j of A_i      (fc1, column-parallel)
+ *     B    [n_r x H]   row j = row    j of B_i      (fc2, row-parallel)
+ *     Wqkv [w_qkv x H] row j = column j of W_qkv,i  (Eq. 6, rows ordered
+ *                      [Q heads | K heads | V heads] of this rank)
+ *     Wo   [w_o x H]   row j = row j of W_O,i       (Eq. 4)
+ * so a ragged shard width never lands on a contiguous axis of a weight or of
+ * its gradient, and gradients come out shaped exactly like their weights.
+ */
+#ifndef NTP_H_
+#define NTP_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define NTP_OK 0
+#define NTP_ERR_INVALID_ARG (-1) /* null pointer, negative size, rank out of range, aliasing ... */
+#define NTP_ERR_ALIGNMENT (-2)   /* base pointer or leading dimension not aligned as required   */
+#define NTP_ERR_LAUNCH (-3)      /* the HIP runtime refused a kernel launch                      */
+#define NTP_ERR_UNSUPPORTED (-4) /* a size beyond what the kernels index (see each call)         */
+
+#define NTP_GELU_ERF 0  /* x * Phi(x)                                  */
+#define NTP_GELU_TANH 1 /* 0.5 x (1 + tanh(sqrt(2/pi)(x + 0.044715 x^3))) */
+
+/* Library version, major * 10000 + minor * 100 + patch. */
+int ntp_version(void);
+
+/* Static string naming a status code.  Never NULL. */
+const char* ntp_status_string(int status);
+
+/* ---------------------------------------------------------------------------
+ * Shard plan (Sec. 3.1, closing paragraph of "Attention blocks": the partition
+ * dimension need not divide by the TP degree, the shards are then uneven).
+ * `dim` units are cut into `tp` contiguous slices whose widths differ by at
+ * most one, the `dim % tp` lowest ranks holding the wider ones:
+ *     width  = dim / tp + (rank < dim % tp)
+ *     offset = rank * (dim / tp) + min(rank, dim % tp)
+ * Host-only, pure.  tp > dim is legal (trailing ranks get width 0).
+ * Errors: dim < 0, tp < 1, rank outside [0, tp), NULL output -> INVALID_ARG.
+ */
+int ntp_shard_plan(int64_t dim, int32_t tp, int32_t rank, int64_t* offset, int64_t* width);
+
+/* Head-granular plan for an attention block (Sec. 3.1, Eq. 4-6: the W_Q, W_K,
+ * W_V, W_O of a head stay together).  Query heads are the partition unit and
+ * are split by ntp_shard_plan(n_q, tp, rank).  With grouped KV heads
+ * (n_kv < n_q, n_q % n_kv == 0) a rank holds every KV head one of its query
+ * heads reads, so a KV head may be replicated on neighbouring ranks.
+ *     w_qkv = (q_cnt + 2 kv_cnt) * head_dim   width of this rank's QKV output
+ *     w_o   = q_cnt * head_dim                rows of this rank's W_O,i
+ * Host-only.  Errors: n_q % n_kv != 0, non-positive sizes, bad rank, NULL. */
+typedef struct ntp_attn_plan {
+  int32_t q_off, q_cnt;   /* first query head and number of query heads */
+  int32_t kv_off, kv_cnt; /* first KV head and number of KV heads       */
+  int32_t head_dim;
+  int32_t w_qkv, w_o;
+} ntp_attn_plan_t;
+int ntp_attn_shard_plan(int32_t n_q, int32_t n_kv, int32_t head_dim, int32_t tp, int32_t rank,
+                        ntp_attn_plan_t* out);
+
+/* ---------------------------------------------------------------------------
+ * MLP shard (Sec. 3.1, Eq. 2-3).  M tokens, hidden H, this rank's width n_r.
+ * H % 8 == 0 is required; M and n_r are arbitrary (n_r = 0 is a no-op that
+ * still zero-fills Zpart / dXpart). */
+typedef struct ntp_mlp_shape {
+  int64_t M, H, n_r;
+  int32_t gelu_mode; /* NTP_GELU_ERF or NTP_GELU_TANH */
+} ntp_mlp_shape_t;
+
+/* Forward: P_i = X A_i, Y_i = GeLU(P_i) (Eq. 3), Zpart = Y_i B_i (Eq. 2, this
+ * rank's partial sum; the TP all-reduce is the caller's).
+ *   in   X [M x H] bf16, A_t [n_r x H] bf16, B [n_r x H] bf16        (device)
+ *   out  P, Y [M x n_r] bf16 with ldp, ldy >= n_r and % 8 == 0; columns from
+ *        n_r up to the next multiple of 8 are written with zeros      (device)
+ *   out  Zpart [M x H] bf16                                           (device)
+ * P and Y are kept for the backward call.  No buffer may alias another. */
+int ntp_mlp_shard_fwd(const ntp_mlp_shape_t* shape, const void* X, int64_t ldx, const void* A_t,
+                      int64_t lda, const void* B, int64_t ldb, void* P, int64_t ldp, void* Y,
+                      int64_t ldy, void* Zpart, int64_t ldz, void* stream);
+
+/* Backward (chain rule on Eq. 2-3; gradients are shaped and partitioned like
+ * A_i and B_i, Sec. 3.1):
+ *   dP_i   = (dZ B_i^T) .* GeLU'(P_i)      [M x n_r] bf16, output / workspace
+ *   dB     = Y_i^T dZ                      [n_r x H] fp32
+ *   dA_t   = dP_i^T X                      [n_r x H] fp32 (= (X^T dP_i)^T)
+ *   dXpart = dP_i A_i^T                    [M x H]  bf16, partial sum
+ * in: dZ [M x H] bf16 and X, A_t, B, P, Y as in the forward call (P, Y as it
+ * wrote them).  accumulate != 0 adds into dA_t / dB instead of overwriting
+ * (gradient accumulation over micro-batches before the reshard, Sec. 4.1). */
+int ntp_mlp_shard_bwd(const ntp_mlp_shape_t* shape, const void* dZ, int64_t lddz, const void* X,
+                      int64_t ldx, const void* A_t, int64_t lda, const void* B, int64_t ldb,
+                      const void* P, int64_t ldp, const void* Y, int64_t ldy, void* dP,
+                      int64_t lddp, void* dXpart, int64_t lddx, float* dA_t, int64_t ldda,
+                      float* dB, int64_t lddb, int32_t accumulate, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Attention projections of one shard (Sec. 3.1, Eq. 4 and 6).  The attention
+ * core (Eq. 5) sits between the two halves and is the caller's.  w_qkv and
+ * w_o come from ntp_attn_shard_plan and must be multiples of 8; H % 8 == 0. */
+typedef struct ntp_attn_shape {
+  int64_t M, H;
+  int64_t w_qkv, w_o;
+} ntp_attn_shape_t;
+
+/* Forward.  Column-parallel half: QKV = X Wqkv^T   [M x w_qkv] bf16 (Eq. 6);
+ * row-parallel half: Zpart = C Wo [M x H] bf16 (Eq. 4) with C [M x w_o] the
+ * attention output of this rank's heads.  A half is skipped when its output
+ * pointer (QKV resp. Zpart) is NULL. */
+int ntp_attn_proj_shard_fwd(const ntp_attn_shape_t* shape, const void* X, int64_t ldx,
+                            const void* Wqkv, int64_t ldwqkv, void* QKV, int64_t ldqkv,
+                            const void* C, int64_t ldc, const void* Wo, int64_t ldwo, void* Zpart,
+                            int64_t ldz, void* stream);
+
+/* Backward.  Row-parallel half (skipped when dZ is NULL):
+ *   dC = dZ Wo^T [M x w_o] bf16,  dWo = C^T dZ [w_o x H] fp32.
+ * Column-parallel half (skipped when dQKV is NULL):
+ *   dXpart = dQKV Wqkv [M x H] bf16 (partial sum),  dWqkv = dQKV^T X [w_qkv x H] fp32.
+ * The dW of a KV head replicated on several ranks is each rank's partial sum.
+ * accumulate != 0 adds into dWqkv / dWo. */
+int ntp_attn_proj_shard_bwd(const ntp_attn_shape_t* shape, const void* dZ, int64_t lddz,
+                            const void* dQKV, int64_t lddqkv, const void* X, int64_t ldx,
+                            const void* C, int64_t ldc, const void* Wqkv, int64_t ldwqkv,
+                            const void* Wo, int64_t ldwo, void* dC, int64_t lddc, void* dXpart,
+                            int64_t lddx, float* dWqkv, int64_t lddwqkv, float* dWo, int64_t lddwo,
+                            int32_t accumulate, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Gradient reshard (Sec. 3.1 "Shard-mapping algorithm"; Appendix, the
+ * pre-sync hook and the post-sync reshard): repack a partitioned tensor from
+ * the TP = src_tp layout into the TP = dst_tp layout.  Both layouts are views
+ * of one logical [rows x cols] tensor cut along `partition_dim` in units of
+ * `unit` elements (1 for an MLP weight, head_dim for an attention weight).
+ * Pure data movement, bit-exact, element type opaque (elem_size 2 or 4). */
+#define NTP_KIND_PLAIN 0   /* contiguous ranges of units per ntp_shard_plan                 */
+#define NTP_KIND_QKV_GQA 1 /* units = [n_q Q heads | n_kv K heads | n_kv V heads]; a rank
+                              holds [its Q heads | the K heads they read | the same V heads] */
+typedef struct ntp_tensor_spec {
+  int64_t rows, cols;    /* logical (unsharded) shape                                   */
+  int32_t partition_dim; /* 0: shards are row blocks, 1: shards are column blocks       */
+  int32_t unit;          /* elements per partition unit along partition_dim             */
+  int32_t elem_size;     /* bytes per element: 2 or 4                                   */
+  int32_t kind;          /* NTP_KIND_*                                                  */
+  int32_t n_q, n_kv;     /* QKV_GQA only; the partitioned extent is (n_q + 2 n_kv)*unit */
+} ntp_tensor_spec_t;
+
+/* One sub-shard: `units` consecutive units that sit in source rank `src_rank`
+ * starting at its local unit `src_unit` and go to destination rank `dst_rank`
+ * at local unit `dst_unit` (the overlap of two shards, Sec. 3.1). */
+typedef struct ntp_segment {
+  int32_t src_rank, dst_rank;
+  int64_t src_unit, dst_unit, units;
+} ntp_segment_t;
+
+/* Host-only: list the sub-shards of spec for src_tp -> dst_tp, in destination
+ * order.  Writes at most `max_segments` entries to `out` (may be NULL when
+ * max_segments is 0) and the full count to *count.  A unit held by several
+ * source ranks (replicated KV head) is taken from the lowest such rank. */
+int ntp_reshard_segments(const ntp_tensor_spec_t* spec, int32_t src_tp, int32_t dst_tp,
+                         ntp_segment_t* out, int64_t max_segments, int64_t* count);
+
+/* Enqueue the copy.  src_shards[src_tp] / dst_shards[dst_tp] are HOST arrays of
+ * DEVICE pointers, one per rank, each a row-major matrix shaped like that
+ * rank's shard with leading dimension src_ld[r] / dst_ld[s] (host arrays,
+ * elements).  A NULL shard pointer means "not on this GPU": every sub-shard
+ * that touches it is skipped, which is how one GPU's share of the exchange is
+ * expressed; shards of width 0 may be NULL.  src_tp and dst_tp may be in
+ * either order.  Source and destination must not overlap (checked: INVALID_ARG).
+ * Only 2-byte alignment (elem_size 2) or 4-byte alignment (elem_size 4) of
+ * pointers is required; 16-byte aligned rows copy fastest. */
+int ntp_reshard_grad(const ntp_tensor_spec_t* spec, int32_t src_tp, int32_t dst_tp,
+                     const void* const* src_shards, const int64_t* src_ld,
+                     void* const* dst_shards, const int64_t* dst_ld, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NTP_H_ */

@@ -1,0 +1,12 @@
+"""MI355X-native shard hot path of Nonuniform Tensor Parallelism (arXiv 2504.06095).
+
+The product is libntp.so (HIP kernels behind the C ABI of include/ntp.h); `binding`
+marshals arguments to it and `inputs` makes seeded synthetic data.  Importing the
+package loads nothing; the first call into `binding` loads the library and raises
+if it has not been built.
+"""
+from . import binding  # noqa: F401
+from .binding import (  # noqa: F401
+    NtpError, ntp_attn_proj_shard_bwd, ntp_attn_proj_shard_fwd, ntp_attn_shard_plan, ntp_mlp_shard_bwd,
+    ntp_mlp_shard_fwd, ntp_reshard_grad, ntp_reshard_segments, ntp_shard_plan, ntp_version, tensor_spec,
+)

@@ -1,0 +1,214 @@
+"""ctypes binding of libntp.so: argument marshalling only.
+
+Each function has the name of the C entry point it calls (include/ntp.h).  Tensors
+are torch tensors used as device memory; the current torch stream is passed through.
+There is no fallback: if the library is not built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libntp.so")
+
+NTP_OK = 0
+NTP_ERR_INVALID_ARG = -1
+NTP_ERR_ALIGNMENT = -2
+NTP_ERR_LAUNCH = -3
+NTP_ERR_UNSUPPORTED = -4
+NTP_GELU_ERF = 0
+NTP_GELU_TANH = 1
+NTP_KIND_PLAIN = 0
+NTP_KIND_QKV_GQA = 1
+
+EXPORTS = (
+    "ntp_version", "ntp_status_string", "ntp_shard_plan", "ntp_attn_shard_plan", "ntp_mlp_shard_fwd",
+    "ntp_mlp_shard_bwd", "ntp_attn_proj_shard_fwd", "ntp_attn_proj_shard_bwd", "ntp_reshard_segments",
+    "ntp_reshard_grad",
+)
+
+
+class NtpError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+class AttnPlan(C.Structure):
+    _fields_ = [("q_off", C.c_int32), ("q_cnt", C.c_int32), ("kv_off", C.c_int32), ("kv_cnt", C.c_int32),
+                ("head_dim", C.c_int32), ("w_qkv", C.c_int32), ("w_o", C.c_int32)]
+
+
+class MlpShape(C.Structure):
+    _fields_ = [("M", C.c_int64), ("H", C.c_int64), ("n_r", C.c_int64), ("gelu_mode", C.c_int32)]
+
+
+class AttnShape(C.Structure):
+    _fields_ = [("M", C.c_int64), ("H", C.c_int64), ("w_qkv", C.c_int64), ("w_o", C.c_int64)]
+
+
+class TensorSpec(C.Structure):
+    _fields_ = [("rows", C.c_int64), ("cols", C.c_int64), ("partition_dim", C.c_int32), ("unit", C.c_int32),
+                ("elem_size", C.c_int32), ("kind", C.c_int32), ("n_q", C.c_int32), ("n_kv", C.c_int32)]
+
+
+class Segment(C.Structure):
+    _fields_ = [("src_rank", C.c_int32), ("dst_rank", C.c_int32), ("src_unit", C.c_int64),
+                ("dst_unit", C.c_int64), ("units", C.c_int64)]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded library.  Raises if it has not been built (python -m paper_2504_06095_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2504_06095_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        L.ntp_version.restype = C.c_int
+        L.ntp_status_string.restype = C.c_char_p
+        L.ntp_status_string.argtypes = [C.c_int]
+        L.ntp_shard_plan.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+        L.ntp_attn_shard_plan.argtypes = [C.c_int32] * 5 + [C.POINTER(AttnPlan)]
+        vp, i64 = C.c_void_p, C.c_int64
+        L.ntp_mlp_shard_fwd.argtypes = [C.POINTER(MlpShape)] + [vp, i64] * 6 + [vp]
+        L.ntp_mlp_shard_bwd.argtypes = [C.POINTER(MlpShape)] + [vp, i64] * 10 + [C.c_int32, vp]
+        L.ntp_attn_proj_shard_fwd.argtypes = [C.POINTER(AttnShape)] + [vp, i64] * 6 + [vp]
+        L.ntp_attn_proj_shard_bwd.argtypes = [C.POINTER(AttnShape)] + [vp, i64] * 10 + [C.c_int32, vp]
+        L.ntp_reshard_segments.argtypes = [C.POINTER(TensorSpec), C.c_int32, C.c_int32, C.POINTER(Segment), i64,
+                                           C.POINTER(i64)]
+        L.ntp_reshard_grad.argtypes = [C.POINTER(TensorSpec), C.c_int32, C.c_int32, C.POINTER(vp), C.POINTER(i64),
+                                       C.POINTER(vp), C.POINTER(i64), vp]
+        for name in EXPORTS:
+            getattr(L, name)  # AttributeError if a declared symbol is not exported
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().ntp_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != NTP_OK:
+        raise NtpError(status, where)
+
+
+def _stream() -> int:
+    import torch
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+def _mat(t, dtype=None):
+    """(device pointer, leading dimension in elements) of a 2-D row-major tensor, or (None, 0)."""
+    if t is None:
+        return None, 0
+    if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+        raise ValueError("expected a row-major 2-D tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"expected {dtype}, got {t.dtype}")
+    if not t.is_cuda:
+        raise ValueError("expected a device tensor")
+    return t.data_ptr(), int(t.stride(0))
+
+
+# ---- host-only calls -------------------------------------------------------------
+def ntp_version() -> int:
+    return int(lib().ntp_version())
+
+
+def ntp_shard_plan(dim: int, tp: int, rank: int) -> tuple[int, int]:
+    off, w = C.c_int64(), C.c_int64()
+    _check(lib().ntp_shard_plan(dim, tp, rank, C.byref(off), C.byref(w)), "ntp_shard_plan")
+    return off.value, w.value
+
+
+def ntp_attn_shard_plan(n_q: int, n_kv: int, head_dim: int, tp: int, rank: int) -> dict:
+    p = AttnPlan()
+    _check(lib().ntp_attn_shard_plan(n_q, n_kv, head_dim, tp, rank, C.byref(p)), "ntp_attn_shard_plan")
+    return {k: getattr(p, k) for k, _ in AttnPlan._fields_}
+
+
+def tensor_spec(rows, cols, partition_dim, unit=1, elem_size=4, kind=NTP_KIND_PLAIN, n_q=0, n_kv=0) -> TensorSpec:
+    return TensorSpec(rows, cols, partition_dim, unit, elem_size, kind, n_q, n_kv)
+
+
+def ntp_reshard_segments(spec: TensorSpec, src_tp: int, dst_tp: int) -> list[tuple[int, int, int, int, int]]:
+    """[(src_rank, dst_rank, src_unit, dst_unit, units)] in destination order."""
+    n = C.c_int64()
+    _check(lib().ntp_reshard_segments(C.byref(spec), src_tp, dst_tp, None, 0, C.byref(n)), "ntp_reshard_segments")
+    buf = (Segment * max(1, n.value))()
+    _check(lib().ntp_reshard_segments(C.byref(spec), src_tp, dst_tp, buf, n.value, C.byref(n)),
+           "ntp_reshard_segments")
+    return [(s.src_rank, s.dst_rank, s.src_unit, s.dst_unit, s.units) for s in buf[: n.value]]
+
+
+# ---- device calls ----------------------------------------------------------------
+def ntp_mlp_shard_fwd(X, A_t, B, P, Y, Zpart, n_r: int, gelu_mode: int = NTP_GELU_ERF) -> None:
+    """X [M,H], A_t [n_r,H], B [n_r,H] bf16 -> P, Y [M, >=n_r] and Zpart [M,H] bf16 (all preallocated)."""
+    import torch
+    bf = torch.bfloat16
+    shape = MlpShape(X.shape[0], X.shape[1], n_r, gelu_mode)
+    args = []
+    for t in (X, A_t, B, P, Y, Zpart):
+        args += list(_mat(t, bf))
+    _check(lib().ntp_mlp_shard_fwd(C.byref(shape), *args, _stream()), "ntp_mlp_shard_fwd")
+
+
+def ntp_mlp_shard_bwd(dZ, X, A_t, B, P, Y, dP, dXpart, dA_t, dB, n_r: int, gelu_mode: int = NTP_GELU_ERF,
+                      accumulate: bool = False) -> None:
+    import torch
+    bf, f32 = torch.bfloat16, torch.float32
+    shape = MlpShape(X.shape[0], X.shape[1], n_r, gelu_mode)
+    args = []
+    for t in (dZ, X, A_t, B, P, Y, dP, dXpart):
+        args += list(_mat(t, bf))
+    for t in (dA_t, dB):
+        args += list(_mat(t, f32))
+    _check(lib().ntp_mlp_shard_bwd(C.byref(shape), *args, int(bool(accumulate)), _stream()), "ntp_mlp_shard_bwd")
+
+
+def ntp_attn_proj_shard_fwd(M, H, w_qkv, w_o, X=None, Wqkv=None, QKV=None, C_=None, Wo=None, Zpart=None) -> None:
+    import torch
+    bf = torch.bfloat16
+    shape = AttnShape(M, H, w_qkv, w_o)
+    args = []
+    for t in (X, Wqkv, QKV, C_, Wo, Zpart):
+        args += list(_mat(t, bf))
+    _check(lib().ntp_attn_proj_shard_fwd(C.byref(shape), *args, _stream()), "ntp_attn_proj_shard_fwd")
+
+
+def ntp_attn_proj_shard_bwd(M, H, w_qkv, w_o, dZ=None, dQKV=None, X=None, C_=None, Wqkv=None, Wo=None, dC=None,
+                            dXpart=None, dWqkv=None, dWo=None, accumulate: bool = False) -> None:
+    import torch
+    bf, f32 = torch.bfloat16, torch.float32
+    shape = AttnShape(M, H, w_qkv, w_o)
+    args = []
+    for t in (dZ, dQKV, X, C_, Wqkv, Wo, dC, dXpart):
+        args += list(_mat(t, bf))
+    for t in (dWqkv, dWo):
+        args += list(_mat(t, f32))
+    _check(lib().ntp_attn_proj_shard_bwd(C.byref(shape), *args, int(bool(accumulate)), _stream()),
+           "ntp_attn_proj_shard_bwd")
+
+
+def ntp_reshard_grad(spec: TensorSpec, src_tp: int, dst_tp: int, src_shards, dst_shards) -> None:
+    """src_shards / dst_shards: lists of 2-D device tensors (or None for "not on this GPU")."""
+    vp, i64 = C.c_void_p, C.c_int64
+    sp, sl = (vp * src_tp)(), (i64 * src_tp)()
+    dp, dl = (vp * dst_tp)(), (i64 * dst_tp)()
+    if len(src_shards) != src_tp or len(dst_shards) != dst_tp:
+        raise ValueError("one entry per rank expected")
+    for arr_p, arr_l, shards in ((sp, sl, src_shards), (dp, dl, dst_shards)):
+        for i, t in enumerate(shards):
+            if t is None or t.numel() == 0:
+                arr_p[i], arr_l[i] = None, 0
+                continue
+            if t.element_size() != spec.elem_size:
+                raise TypeError("element size of a shard differs from the spec")
+            p, ld = _mat(t)
+            arr_p[i], arr_l[i] = p, ld
+    _check(lib().ntp_reshard_grad(C.byref(spec), src_tp, dst_tp, sp, sl, dp, dl, _stream()), "ntp_reshard_grad")

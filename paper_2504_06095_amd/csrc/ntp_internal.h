@@ -1,0 +1,62 @@
+// Declarations shared by the translation units of the NTP library (not part of the ABI).
+#ifndef NTP_INTERNAL_H_
+#define NTP_INTERNAL_H_
+
+#include <stdint.h>
+
+#include <vector>
+
+#include "ntp.h"
+
+namespace ntp {
+
+// `count` consecutive logical units starting at `first`, stored from local unit `local` of a shard.
+struct Run {
+  int64_t first, count, local;
+};
+
+int check_spec(const ntp_tensor_spec_t* spec, int32_t src_tp, int32_t dst_tp, int64_t* n_units);
+int rank_runs(const ntp_tensor_spec_t* spec, int64_t n_units, int32_t tp, int32_t rank,
+              std::vector<Run>* runs);
+int shard_units(const ntp_tensor_spec_t* spec, int64_t n_units, int32_t tp, int32_t rank,
+                int64_t* units);
+int build_segments(const ntp_tensor_spec_t* spec, int32_t src_tp, int32_t dst_tp,
+                   std::vector<ntp_segment_t>* segs);
+
+// ---- GEMM family -------------------------------------------------------------
+// C[M x N] = op(A) op(B), bf16 operands, fp32 accumulation on the matrix cores.
+// An operand is "K-contiguous" when consecutive k sit next to each other in memory:
+//   a_kc: A stored [M x K] (row m, ld lda)   else stored [K x M]
+//   b_kc: B stored [N x K] (row n, ld ldb)   else stored [K x N]
+enum Epilogue : int32_t {
+  EPI_BF16 = 0,        // C = bf16(acc)
+  EPI_GELU = 1,        // C = bf16(acc), C2 = bf16(gelu(acc))
+  EPI_DGELU = 2,       // C = bf16(acc * gelu'(AUX))
+  EPI_F32 = 3,         // C = acc            (fp32)
+  EPI_F32_ACCUM = 4,   // C += acc           (fp32)
+};
+
+struct GemmDesc {
+  const void* A;
+  int64_t lda;
+  const void* B;
+  int64_t ldb;
+  int64_t M, N, K;
+  bool a_kc, b_kc;
+  int32_t epilogue;
+  void* C;
+  int64_t ldc;
+  void* C2;  // EPI_GELU second output
+  int64_t ldc2;
+  const void* AUX;  // EPI_DGELU pre-activation, bf16 [M x N]
+  int64_t ldaux;
+  int32_t gelu_mode;
+  bool zero_pad_n;  // bf16 outputs: also write zeros to columns [N, round_up(N, 8))
+};
+
+// Validates and enqueues one GEMM on `stream`.  Returns an NTP_* status.
+int gemm_launch(const GemmDesc& d, void* stream);
+
+}  // namespace ntp
+
+#endif  // NTP_INTERNAL_H_

@@ -1,0 +1,143 @@
+// ABI entry points of the shard layers: argument checks and the sequence of GEMMs.
+// Every step runs in the GEMM kernels; nothing is computed on the host.
+#include "ntp_internal.h"
+
+using ntp::GemmDesc;
+
+namespace {
+
+GemmDesc gemm(const void* A, int64_t lda, bool a_kc, const void* B, int64_t ldb, bool b_kc, int64_t M,
+              int64_t N, int64_t K, int32_t epilogue, void* C, int64_t ldc) {
+  GemmDesc d{};
+  d.A = A;
+  d.lda = lda;
+  d.a_kc = a_kc;
+  d.B = B;
+  d.ldb = ldb;
+  d.b_kc = b_kc;
+  d.M = M;
+  d.N = N;
+  d.K = K;
+  d.epilogue = epilogue;
+  d.C = C;
+  d.ldc = ldc;
+  return d;
+}
+
+bool bad_mlp_shape(const ntp_mlp_shape_t* s) {
+  return !s || s->M < 0 || s->H < 0 || s->n_r < 0 ||
+         (s->gelu_mode != NTP_GELU_ERF && s->gelu_mode != NTP_GELU_TANH);
+}
+
+}  // namespace
+
+// Eq. 3 then Eq. 2 for this rank's shard.
+extern "C" int ntp_mlp_shard_fwd(const ntp_mlp_shape_t* s, const void* X, int64_t ldx, const void* A_t,
+                                 int64_t lda, const void* B, int64_t ldb, void* P, int64_t ldp, void* Y,
+                                 int64_t ldy, void* Zpart, int64_t ldz, void* stream) {
+  if (bad_mlp_shape(s)) return NTP_ERR_INVALID_ARG;
+  if (s->H % 8) return NTP_ERR_ALIGNMENT;
+  if (s->M == 0 || s->H == 0) return NTP_OK;
+  if (!X || !Zpart || (s->n_r > 0 && (!A_t || !B || !P || !Y))) return NTP_ERR_INVALID_ARG;
+  int st = NTP_OK;
+  if (s->n_r > 0) {
+    // P = X A_i (A_t holds A_i's columns as rows), Y = GeLU(P); pad columns zeroed
+    GemmDesc d = gemm(X, ldx, true, A_t, lda, true, s->M, s->n_r, s->H, ntp::EPI_GELU, P, ldp);
+    d.C2 = Y;
+    d.ldc2 = ldy;
+    d.gelu_mode = s->gelu_mode;
+    d.zero_pad_n = true;
+    if ((st = ntp::gemm_launch(d, stream)) != NTP_OK) return st;
+  }
+  // Zpart = Y B_i, contraction over the ragged shard width
+  GemmDesc d2 = gemm(Y, ldy, true, B, ldb, false, s->M, s->H, s->n_r, ntp::EPI_BF16, Zpart, ldz);
+  return ntp::gemm_launch(d2, stream);
+}
+
+extern "C" int ntp_mlp_shard_bwd(const ntp_mlp_shape_t* s, const void* dZ, int64_t lddz, const void* X,
+                                 int64_t ldx, const void* A_t, int64_t lda, const void* B, int64_t ldb,
+                                 const void* P, int64_t ldp, const void* Y, int64_t ldy, void* dP,
+                                 int64_t lddp, void* dXpart, int64_t lddx, float* dA_t, int64_t ldda,
+                                 float* dB, int64_t lddb, int32_t accumulate, void* stream) {
+  if (bad_mlp_shape(s)) return NTP_ERR_INVALID_ARG;
+  if (s->H % 8) return NTP_ERR_ALIGNMENT;
+  if (s->H == 0) return NTP_OK;
+  if (s->n_r > 0 && (!A_t || !B || !dA_t || !dB)) return NTP_ERR_INVALID_ARG;
+  if (s->M > 0 && (!dZ || !X || !dXpart || (s->n_r > 0 && (!P || !Y || !dP)))) return NTP_ERR_INVALID_ARG;
+  const int32_t wepi = accumulate ? ntp::EPI_F32_ACCUM : ntp::EPI_F32;
+  int st = NTP_OK;
+  if (s->n_r > 0 && s->M > 0) {
+    // dP = (dZ B_i^T) .* GeLU'(P)
+    GemmDesc d = gemm(dZ, lddz, true, B, ldb, true, s->M, s->n_r, s->H, ntp::EPI_DGELU, dP, lddp);
+    d.AUX = P;
+    d.ldaux = ldp;
+    d.gelu_mode = s->gelu_mode;
+    d.zero_pad_n = true;
+    if ((st = ntp::gemm_launch(d, stream)) != NTP_OK) return st;
+  }
+  if (s->n_r > 0) {
+    // dB = Y^T dZ and dA_t = dP^T X: contraction over tokens, both operands token-major
+    GemmDesc db = gemm(Y, ldy, false, dZ, lddz, false, s->n_r, s->H, s->M, wepi, dB, lddb);
+    if ((st = ntp::gemm_launch(db, stream)) != NTP_OK) return st;
+    GemmDesc da = gemm(dP, lddp, false, X, ldx, false, s->n_r, s->H, s->M, wepi, dA_t, ldda);
+    if ((st = ntp::gemm_launch(da, stream)) != NTP_OK) return st;
+  }
+  if (s->M == 0) return NTP_OK;
+  // dXpart = dP A_i^T, contraction over the ragged shard width
+  GemmDesc dx = gemm(dP, lddp, true, A_t, lda, false, s->M, s->H, s->n_r, ntp::EPI_BF16, dXpart, lddx);
+  return ntp::gemm_launch(dx, stream);
+}
+
+namespace {
+bool bad_attn_shape(const ntp_attn_shape_t* s) {
+  return !s || s->M < 0 || s->H < 0 || s->w_qkv < 0 || s->w_o < 0;
+}
+}  // namespace
+
+// Eq. 6 (column-parallel QKV) and Eq. 4 (row-parallel output projection).
+extern "C" int ntp_attn_proj_shard_fwd(const ntp_attn_shape_t* s, const void* X, int64_t ldx,
+                                       const void* Wqkv, int64_t ldwqkv, void* QKV, int64_t ldqkv,
+                                       const void* C, int64_t ldc, const void* Wo, int64_t ldwo,
+                                       void* Zpart, int64_t ldz, void* stream) {
+  if (bad_attn_shape(s)) return NTP_ERR_INVALID_ARG;
+  if (s->H % 8 || s->w_qkv % 8 || s->w_o % 8) return NTP_ERR_ALIGNMENT;
+  int st = NTP_OK;
+  if (QKV) {
+    if (s->M > 0 && s->w_qkv > 0 && s->H > 0 && (!X || !Wqkv)) return NTP_ERR_INVALID_ARG;
+    GemmDesc d = gemm(X, ldx, true, Wqkv, ldwqkv, true, s->M, s->w_qkv, s->H, ntp::EPI_BF16, QKV, ldqkv);
+    if ((st = ntp::gemm_launch(d, stream)) != NTP_OK) return st;
+  }
+  if (Zpart) {
+    if (s->M > 0 && s->w_o > 0 && s->H > 0 && (!C || !Wo)) return NTP_ERR_INVALID_ARG;
+    GemmDesc d = gemm(C, ldc, true, Wo, ldwo, false, s->M, s->H, s->w_o, ntp::EPI_BF16, Zpart, ldz);
+    if ((st = ntp::gemm_launch(d, stream)) != NTP_OK) return st;
+  }
+  return NTP_OK;
+}
+
+extern "C" int ntp_attn_proj_shard_bwd(const ntp_attn_shape_t* s, const void* dZ, int64_t lddz,
+                                       const void* dQKV, int64_t lddqkv, const void* X, int64_t ldx,
+                                       const void* C, int64_t ldc, const void* Wqkv, int64_t ldwqkv,
+                                       const void* Wo, int64_t ldwo, void* dC, int64_t lddc, void* dXpart,
+                                       int64_t lddx, float* dWqkv, int64_t lddwqkv, float* dWo,
+                                       int64_t lddwo, int32_t accumulate, void* stream) {
+  if (bad_attn_shape(s)) return NTP_ERR_INVALID_ARG;
+  if (s->H % 8 || s->w_qkv % 8 || s->w_o % 8) return NTP_ERR_ALIGNMENT;
+  const int32_t wepi = accumulate ? ntp::EPI_F32_ACCUM : ntp::EPI_F32;
+  int st = NTP_OK;
+  if (dZ) {
+    if (!Wo || !C || !dC || !dWo) return NTP_ERR_INVALID_ARG;
+    GemmDesc d = gemm(dZ, lddz, true, Wo, ldwo, true, s->M, s->w_o, s->H, ntp::EPI_BF16, dC, lddc);
+    if ((st = ntp::gemm_launch(d, stream)) != NTP_OK) return st;
+    GemmDesc w = gemm(C, ldc, false, dZ, lddz, false, s->w_o, s->H, s->M, wepi, dWo, lddwo);
+    if ((st = ntp::gemm_launch(w, stream)) != NTP_OK) return st;
+  }
+  if (dQKV) {
+    if (!Wqkv || !X || !dXpart || !dWqkv) return NTP_ERR_INVALID_ARG;
+    GemmDesc d = gemm(dQKV, lddqkv, true, Wqkv, ldwqkv, false, s->M, s->H, s->w_qkv, ntp::EPI_BF16, dXpart, lddx);
+    if ((st = ntp::gemm_launch(d, stream)) != NTP_OK) return st;
+    GemmDesc w = gemm(dQKV, lddqkv, false, X, ldx, false, s->w_qkv, s->H, s->M, wepi, dWqkv, lddwqkv);
+    if ((st = ntp::gemm_launch(w, stream)) != NTP_OK) return st;
+  }
+  return NTP_OK;
+}

@@ -1,0 +1,151 @@
+// Host-only part of the NTP library: status strings, shard plans and the
+// sub-shard (segment) list of a reshard.  Pure integer arithmetic.
+#include <algorithm>
+#include <vector>
+
+#include "ntp_internal.h"
+
+extern "C" int ntp_version(void) { return 100; }
+
+extern "C" const char* ntp_status_string(int status) {
+  switch (status) {
+    case NTP_OK: return "ok";
+    case NTP_ERR_INVALID_ARG: return "invalid argument";
+    case NTP_ERR_ALIGNMENT: return "pointer or leading dimension not aligned as required";
+    case NTP_ERR_LAUNCH: return "HIP kernel launch failed";
+    case NTP_ERR_UNSUPPORTED: return "size not supported";
+    default: return "unknown status";
+  }
+}
+
+// Sec. 3.1: even-as-possible contiguous split, remainder on the lowest ranks.
+extern "C" int ntp_shard_plan(int64_t dim, int32_t tp, int32_t rank, int64_t* offset,
+                              int64_t* width) {
+  if (dim < 0 || tp < 1 || rank < 0 || rank >= tp || !offset || !width) return NTP_ERR_INVALID_ARG;
+  const int64_t base = dim / tp, rem = dim % tp;
+  *width = base + (rank < rem ? 1 : 0);
+  *offset = rank * base + std::min<int64_t>(rank, rem);
+  return NTP_OK;
+}
+
+// Sec. 3.1, Eq. 4-6: heads are the unit; KV heads follow the query heads that read them.
+extern "C" int ntp_attn_shard_plan(int32_t n_q, int32_t n_kv, int32_t head_dim, int32_t tp,
+                                   int32_t rank, ntp_attn_plan_t* out) {
+  if (!out || n_q < 1 || n_kv < 1 || head_dim < 1 || n_q % n_kv != 0) return NTP_ERR_INVALID_ARG;
+  int64_t off = 0, cnt = 0;
+  const int st = ntp_shard_plan(n_q, tp, rank, &off, &cnt);
+  if (st != NTP_OK) return st;
+  const int32_t group = n_q / n_kv;
+  out->q_off = (int32_t)off;
+  out->q_cnt = (int32_t)cnt;
+  out->head_dim = head_dim;
+  if (cnt == 0) {
+    out->kv_off = 0;
+    out->kv_cnt = 0;
+  } else {
+    const int32_t first = (int32_t)(off / group);
+    const int32_t last = (int32_t)((off + cnt - 1) / group);
+    out->kv_off = first;
+    out->kv_cnt = last - first + 1;
+  }
+  out->w_qkv = (out->q_cnt + 2 * out->kv_cnt) * head_dim;
+  out->w_o = out->q_cnt * head_dim;
+  return NTP_OK;
+}
+
+namespace ntp {
+
+int check_spec(const ntp_tensor_spec_t* spec, int32_t src_tp, int32_t dst_tp, int64_t* n_units) {
+  if (!spec || src_tp < 1 || dst_tp < 1 || spec->rows < 0 || spec->cols < 0 || spec->unit < 1)
+    return NTP_ERR_INVALID_ARG;
+  if (spec->partition_dim != 0 && spec->partition_dim != 1) return NTP_ERR_INVALID_ARG;
+  if (spec->elem_size != 2 && spec->elem_size != 4) return NTP_ERR_INVALID_ARG;
+  const int64_t extent = spec->partition_dim == 0 ? spec->rows : spec->cols;
+  if (extent % spec->unit != 0) return NTP_ERR_INVALID_ARG;
+  *n_units = extent / spec->unit;
+  if (spec->kind == NTP_KIND_QKV_GQA) {
+    if (spec->n_q < 1 || spec->n_kv < 1 || spec->n_q % spec->n_kv != 0) return NTP_ERR_INVALID_ARG;
+    if (*n_units != (int64_t)spec->n_q + 2 * (int64_t)spec->n_kv) return NTP_ERR_INVALID_ARG;
+  } else if (spec->kind != NTP_KIND_PLAIN) {
+    return NTP_ERR_INVALID_ARG;
+  }
+  return NTP_OK;
+}
+
+// A rank's shard as runs of consecutive logical units, in shard order.
+int rank_runs(const ntp_tensor_spec_t* spec, int64_t n_units, int32_t tp, int32_t rank,
+              std::vector<Run>* runs) {
+  runs->clear();
+  if (spec->kind == NTP_KIND_PLAIN) {
+    int64_t off, w;
+    const int st = ntp_shard_plan(n_units, tp, rank, &off, &w);
+    if (st != NTP_OK) return st;
+    if (w > 0) runs->push_back({off, w, 0});
+    return NTP_OK;
+  }
+  ntp_attn_plan_t p;
+  const int st = ntp_attn_shard_plan(spec->n_q, spec->n_kv, 1, tp, rank, &p);
+  if (st != NTP_OK) return st;
+  if (p.q_cnt > 0) {
+    runs->push_back({p.q_off, p.q_cnt, 0});
+    runs->push_back({(int64_t)spec->n_q + p.kv_off, p.kv_cnt, p.q_cnt});
+    runs->push_back({(int64_t)spec->n_q + spec->n_kv + p.kv_off, p.kv_cnt, (int64_t)p.q_cnt + p.kv_cnt});
+  }
+  return NTP_OK;
+}
+
+int shard_units(const ntp_tensor_spec_t* spec, int64_t n_units, int32_t tp, int32_t rank,
+                int64_t* units) {
+  std::vector<Run> runs;
+  const int st = rank_runs(spec, n_units, tp, rank, &runs);
+  if (st != NTP_OK) return st;
+  int64_t total = 0;
+  for (const Run& r : runs) total += r.count;
+  *units = total;
+  return NTP_OK;
+}
+
+int build_segments(const ntp_tensor_spec_t* spec, int32_t src_tp, int32_t dst_tp,
+                   std::vector<ntp_segment_t>* segs) {
+  int64_t n_units = 0;
+  int st = check_spec(spec, src_tp, dst_tp, &n_units);
+  if (st != NTP_OK) return st;
+  std::vector<std::vector<Run>> src(src_tp);
+  for (int32_t r = 0; r < src_tp; ++r)
+    if ((st = rank_runs(spec, n_units, src_tp, r, &src[r])) != NTP_OK) return st;
+  segs->clear();
+  std::vector<Run> dst;
+  for (int32_t s = 0; s < dst_tp; ++s) {
+    if ((st = rank_runs(spec, n_units, dst_tp, s, &dst)) != NTP_OK) return st;
+    for (const Run& d : dst) {
+      // cover [cur, end) from source ranks in ascending order: the first rank that
+      // holds `cur` is the lowest one, which is the copy a replicated unit is read from
+      int64_t cur = d.first;
+      const int64_t end = d.first + d.count;
+      for (int32_t r = 0; r < src_tp && cur < end; ++r) {
+        for (const Run& a : src[r]) {
+          if (a.first <= cur && cur < a.first + a.count) {
+            const int64_t stop = std::min(end, a.first + a.count);
+            segs->push_back({r, s, a.local + (cur - a.first), d.local + (cur - d.first), stop - cur});
+            cur = stop;
+          }
+        }
+      }
+      if (cur != end) return NTP_ERR_INVALID_ARG;  // cannot happen: every unit has a source rank
+    }
+  }
+  return NTP_OK;
+}
+
+}  // namespace ntp
+
+extern "C" int ntp_reshard_segments(const ntp_tensor_spec_t* spec, int32_t src_tp, int32_t dst_tp,
+                                    ntp_segment_t* out, int64_t max_segments, int64_t* count) {
+  if (!count || max_segments < 0 || (max_segments > 0 && !out)) return NTP_ERR_INVALID_ARG;
+  std::vector<ntp_segment_t> segs;
+  const int st = ntp::build_segments(spec, src_tp, dst_tp, &segs);
+  if (st != NTP_OK) return st;
+  *count = (int64_t)segs.size();
+  for (int64_t i = 0; i < std::min<int64_t>(max_segments, (int64_t)segs.size()); ++i) out[i] = segs[i];
+  return NTP_OK;
+}

@@ -1,0 +1,172 @@
+"""Parity of the HIP path against the CPU oracle, through the C ABI, on a real MI355X.
+
+Small cases compare every output element; they span several tiles and ragged tails in
+all three positions where a shard width can land (N, K and the rows of a weight gradient).
+"""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import ntp_oracle as O
+from tests.helpers import TOL, AttnCase, MlpCase, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(f"[gpu-case] {msg}", file=sys.stderr, flush=True)
+
+
+def _check_all(got, want, names, tol=TOL):
+    for k in names:
+        assert got[k].shape == want[k].shape, k
+        assert np.isfinite(got[k]).all(), f"{k}: non-finite output"
+        e = rel_err(got[k], want[k])
+        assert e <= tol, f"{k}: rel err {e:.3e} > {tol}"
+
+
+MLP_NAMES = ["P", "Y", "Z", "dP", "dX", "dA_t", "dB"]
+
+MLP_CASES = [
+    # M, H, n, tp, rank  -> n_r
+    (512, 1024, 4096, 7, 0),    # config 1: n_r = 586
+    (512, 1024, 4096, 7, 6),    # n_r = 585 (odd)
+    (512, 1024, 4096, 8, 3),    # full TP, n_r = 512
+    (300, 256, 1000, 3, 0),     # ragged M, n_r = 334
+    (129, 136, 77, 2, 1),       # everything ragged: n_r = 38, H = 136
+    (1, 64, 40, 3, 2),          # single token, n_r = 13
+    (257, 512, 9, 2, 0),        # n_r = 5: narrower than a vector
+    (64, 128, 130, 1, 0),       # n_r = 130: one full tile plus 2 columns
+]
+
+
+@pytest.mark.parametrize("M,H,n,tp,rank", MLP_CASES)
+def test_mlp_shard_parity(M, H, n, tp, rank):
+    _say(f"mlp M={M} H={H} n={n} tp={tp} rank={rank}")
+    case = MlpCase(M, H, n, tp, rank)
+    got, raw = case.run_gpu()
+    _check_all(got, case.oracle(), MLP_NAMES)
+    # columns between n_r and the next multiple of 8 are written with zeros
+    n_r, pad_end = case.n_r, (case.n_r + 7) // 8 * 8
+    for name in ("P", "Y", "dP"):
+        pad = raw[name][:, n_r:pad_end].float().cpu().numpy()
+        assert (pad == 0).all(), f"{name}: pad columns not zero"
+
+
+def test_mlp_shard_tanh_gelu_mode():
+    _say("mlp tanh mode")
+    case = MlpCase(200, 256, 1000, 3, 1)
+    got, _ = case.run_gpu(mode=1)
+    _check_all(got, case.oracle(O.GELU_TANH), MLP_NAMES)
+
+
+def _bf16_round_safe(v):
+    """bf16 bits of v (float64) and whether v sits well away from a rounding boundary."""
+    from paper_2504_06095_amd import inputs as I
+    bits = I.round_to_bf16_bits(v.astype(np.float32))
+    lo = I.bf16_bits_to_f32(bits).astype(np.float64)
+    ulp = np.maximum(np.abs(lo), 2.0 ** -120) * 2.0 ** -8
+    safe = np.abs(np.abs(v - lo) / ulp) < 0.4  # at most 0.4 ulp from the chosen value (a tie is 0.5)
+    return bits, safe
+
+
+def test_gelu_mode_is_honoured_on_device():
+    # The two GeLU forms differ by < 1e-3, far inside the GEMM tolerance, so the mode switch is pinned
+    # separately: identity weights make P = X exactly, then Y = bf16(gelu(X)).  Inputs are the bf16
+    # values on which the two forms round to DIFFERENT bf16 numbers, both clear of a rounding tie.
+    import torch
+    import paper_2504_06095_amd as N
+    from paper_2504_06095_amd import inputs as I
+    _say("gelu mode pin")
+    H = 64
+    allbits = np.arange(0, 1 << 16, dtype=np.uint16)
+    xs = I.bf16_bits_to_f32(allbits).astype(np.float64)
+    ok = np.isfinite(xs) & (np.abs(xs) < 4.0) & (np.abs(xs) > 2.0 ** -6)
+    xs, xb = xs[ok], allbits[ok]
+    be, se = _bf16_round_safe(O.gelu(xs, O.GELU_ERF))
+    bt, st = _bf16_round_safe(O.gelu(xs, O.GELU_TANH))
+    pick = (be != bt) & se & st
+    assert pick.sum() >= 30
+    xb, be, bt = xb[pick], be[pick], bt[pick]
+    rows = (len(xb) + H - 1) // H
+    grid = np.zeros(rows * H, dtype=np.uint16)
+    grid[: len(xb)] = xb
+    X = torch.from_numpy(grid.view(np.int16).reshape(rows, H)).cuda().view(torch.bfloat16)
+    At = torch.eye(H, dtype=torch.bfloat16, device="cuda")
+    B = torch.zeros(H, H, dtype=torch.bfloat16, device="cuda")
+    for mode, want in ((0, be), (1, bt)):
+        P, Y, Z = (torch.empty(rows, H, dtype=torch.bfloat16, device="cuda") for _ in range(3))
+        N.ntp_mlp_shard_fwd(X, At, B, P, Y, Z, H, mode)
+        torch.cuda.synchronize()
+        assert torch.equal(P.view(torch.int16), X.view(torch.int16))
+        got = Y.view(torch.int16).cpu().numpy().view(np.uint16).reshape(-1)[: len(xb)]
+        assert np.array_equal(got, want), f"mode {mode}: {np.count_nonzero(got != want)} of {len(want)} differ"
+
+
+def test_mlp_gradient_accumulation():
+    _say("mlp accumulate")
+    case = MlpCase(192, 256, 600, 3, 2)
+    got, _ = case.run_gpu(accumulate_twice=True)
+    want = case.oracle()
+    assert rel_err(got["dA_t"], 2 * want["dA_t"]) <= TOL
+    assert rel_err(got["dB"], 2 * want["dB"]) <= TOL
+
+
+def test_mlp_zero_width_shard():
+    import torch
+    import paper_2504_06095_amd as N
+    _say("mlp n_r = 0")
+    M, H = 70, 64
+    X = torch.randn(M, H, device="cuda").to(torch.bfloat16)
+    Z = torch.full((M, H), float("nan"), dtype=torch.bfloat16, device="cuda")
+    dX = torch.full((M, H), float("nan"), dtype=torch.bfloat16, device="cuda")
+    e = torch.empty(0, H, dtype=torch.bfloat16, device="cuda")
+    ef = torch.empty(0, H, dtype=torch.float32, device="cuda")
+    act = torch.empty(M, 8, dtype=torch.bfloat16, device="cuda")[:, :0]
+    N.ntp_mlp_shard_fwd(X, e, e, act, act, Z, 0)
+    N.ntp_mlp_shard_bwd(X, X, e, e, act, act, act, dX, ef, ef, 0)
+    torch.cuda.synchronize()
+    assert (Z == 0).all() and (dX == 0).all()  # an empty shard contributes a zero partial sum
+
+
+def test_mlp_rejects_misaligned_leading_dimension():
+    import torch
+    import paper_2504_06095_amd as N
+    M, H, n_r = 16, 64, 12
+    bf = dict(dtype=torch.bfloat16, device="cuda")
+    X, At, B = torch.zeros(M, H, **bf), torch.zeros(n_r, H, **bf), torch.zeros(n_r, H, **bf)
+    P = torch.zeros(M, 12, **bf)  # ld = 12 is not a multiple of 8
+    Y, Z = torch.zeros(M, 16, **bf), torch.zeros(M, H, **bf)
+    with pytest.raises(N.NtpError) as ei:
+        N.ntp_mlp_shard_fwd(X, At, B, P, Y[:, :n_r], Z, n_r)
+    assert ei.value.status == N.binding.NTP_ERR_ALIGNMENT
+
+
+ATTN_CASES = [
+    # M, H, n_q, n_kv, d, tp, rank
+    (256, 512, 8, 2, 64, 3, 0),    # 3 q heads, 1 kv head
+    (256, 512, 8, 2, 64, 3, 1),    # straddles two kv heads
+    (100, 256, 4, 4, 32, 3, 2),    # MHA, ragged M
+    (300, 1024, 16, 2, 128, 5, 4),
+]
+
+
+@pytest.mark.parametrize("M,H,n_q,n_kv,d,tp,rank", ATTN_CASES)
+def test_attn_proj_shard_parity(M, H, n_q, n_kv, d, tp, rank):
+    _say(f"attn M={M} H={H} heads={n_q}/{n_kv} d={d} tp={tp} rank={rank}")
+    case = AttnCase(M, H, n_q, n_kv, d, tp, rank)
+    _check_all(case.run_gpu(), case.oracle(), ["QKV", "Z", "dC", "dX", "dWqkv", "dWo"])
+
+
+def test_attn_halves_can_be_skipped():
+    import torch
+    import paper_2504_06095_amd as N
+    _say("attn skip halves")
+    case = AttnCase(128, 256, 8, 2, 32, 3, 0)
+    from tests.helpers import dev_bf16_to_f64, to_dev_bf16
+    X, Wqkv = to_dev_bf16(case.X_bits), to_dev_bf16(case.Wqkv_bits)
+    QKV = torch.full((128, case.w_qkv), float("nan"), dtype=torch.bfloat16, device="cuda")
+    N.ntp_attn_proj_shard_fwd(128, 256, case.w_qkv, case.w_o, X, Wqkv, QKV, None, None, None)
+    torch.cuda.synchronize()
+    assert rel_err(dev_bf16_to_f64(QKV), case.oracle()["QKV"]) <= TOL

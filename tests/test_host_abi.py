@@ -1,0 +1,144 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every declared symbol, and its
+host logic (plans, sub-shard lists, argument checks) agrees with the oracle.  No kernel runs here."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2504_06095_amd as N
+from oracle import ntp_oracle as O
+from paper_2504_06095_amd import binding as Bd
+from tests.helpers import apply_segments_on_host
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "ntp.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(ntp_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(Bd.EXPORTS)
+    lib = Bd.lib()
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert N.ntp_version() >= 100
+    assert Bd.status_string(0) == "ok" and "align" in Bd.status_string(Bd.NTP_ERR_ALIGNMENT)
+
+
+def test_shard_plan_matches_oracle_exhaustively():
+    for dim in list(range(0, 70)) + [586, 4096, 12000, 49152, 53248]:
+        for tp in list(range(1, 41)) + [71, 72]:
+            for r in range(tp):
+                assert N.ntp_shard_plan(dim, tp, r) == O.shard_plan(dim, tp, r)
+
+
+def test_shard_plan_errors():
+    lib = Bd.lib()
+    off, w = C.c_int64(), C.c_int64()
+    assert lib.ntp_shard_plan(-1, 2, 0, C.byref(off), C.byref(w)) == Bd.NTP_ERR_INVALID_ARG
+    assert lib.ntp_shard_plan(4, 0, 0, C.byref(off), C.byref(w)) == Bd.NTP_ERR_INVALID_ARG
+    assert lib.ntp_shard_plan(4, 2, 2, C.byref(off), C.byref(w)) == Bd.NTP_ERR_INVALID_ARG
+    assert lib.ntp_shard_plan(4, 2, -1, C.byref(off), C.byref(w)) == Bd.NTP_ERR_INVALID_ARG
+    assert lib.ntp_shard_plan(4, 2, 0, None, C.byref(w)) == Bd.NTP_ERR_INVALID_ARG
+    with pytest.raises(N.NtpError):
+        N.ntp_shard_plan(4, 2, 5)
+
+
+def test_attn_plan_matches_oracle():
+    for n_q, n_kv in [(64, 8), (128, 8), (96, 96), (8, 2), (4, 1), (32, 4)]:
+        for tp in [1, 2, 3, 5, 7, 8, 30, 32, 71, 72]:
+            for r in range(tp):
+                got = N.ntp_attn_shard_plan(n_q, n_kv, 128, tp, r)
+                want = O.attn_shard_plan(n_q, n_kv, tp, r)
+                assert {k: got[k] for k in want} == want
+                assert got["w_qkv"] == (want["q_cnt"] + 2 * want["kv_cnt"]) * 128
+                assert got["w_o"] == want["q_cnt"] * 128
+    with pytest.raises(N.NtpError):
+        N.ntp_attn_shard_plan(6, 4, 128, 2, 0)
+
+
+def test_segments_reproduce_paper_example():
+    # Sec. 3.1: hidden 12K, TP32 vs TP30 -> sub-shards of 375 and 25
+    segs = N.ntp_reshard_segments(N.tensor_spec(12000, 8, 0), 30, 32)
+    assert segs[0] == (0, 0, 0, 0, 375) and segs[1] == (0, 1, 375, 0, 25)
+    want = sorted(O.overlap_segments(12000, 30, 32))
+    got = sorted((r, s, O.shard_plan(12000, 30, r)[0] + su, n) for (r, s, su, du, n) in segs)
+    assert got == want
+
+
+@pytest.mark.parametrize("pd", [0, 1])
+@pytest.mark.parametrize("kind", ["plain", "gqa"])
+def test_segments_carried_out_on_host_equal_oracle_reshard(pd, kind):
+    rng = np.random.default_rng(0)
+    if kind == "plain":
+        cases = [(37, 1, 7, 8), (37, 1, 8, 7), (64, 4, 30, 32), (5, 2, 8, 3), (12, 1, 4, 4), (71, 3, 71, 72)]
+    else:
+        cases = [((8, 2), 3, 3, 4), ((8, 2), 3, 8, 5), ((16, 4), 2, 6, 7), ((4, 1), 5, 2, 4), ((12, 12), 2, 5, 7)]
+    for nu, unit, a, b in cases:
+        n_q = n_kv = 0
+        k = O.PLAIN
+        if kind == "gqa":
+            (n_q, n_kv), k = nu, O.QKV_GQA
+            nu = n_q + 2 * n_kv
+        other = 5
+        shape = (nu * unit, other) if pd == 0 else (other, nu * unit)
+        G = rng.integers(0, 2 ** 32, size=shape, dtype=np.uint32)
+        src = [O.cut_shard(G, pd, unit, k, a, r, n_q, n_kv) for r in range(a)]
+        want = O.reshard(src, pd, unit, k, a, b, nu, n_q, n_kv)
+        spec = N.tensor_spec(shape[0], shape[1], pd, unit, 4, Bd.NTP_KIND_QKV_GQA if kind == "gqa" else Bd.NTP_KIND_PLAIN,
+                             n_q, n_kv)
+        segs = N.ntp_reshard_segments(spec, a, b)
+        got, cover = apply_segments_on_host(segs, pd, unit, src, [w.shape for w in want], np.uint32)
+        for s in range(b):
+            assert (cover[s] == 1).all()  # every destination unit written exactly once
+            assert np.array_equal(got[s], want[s])
+        if kind == "plain":
+            assert len(segs) <= a + b - 1
+
+
+def test_segments_at_config_sizes():
+    # 405B-shape layer, TP 71 <-> 72: bounded number of sub-shards, full coverage
+    for dim, unit in [(53248, 1), (128, 128)]:
+        for a, b in [(71, 72), (72, 71)]:
+            segs = N.ntp_reshard_segments(N.tensor_spec(dim * unit, 16, 0, unit), a, b)
+            assert len(segs) <= a + b - 1
+            assert sum(n for *_, n in segs) == dim
+    spec = N.tensor_spec(16, (128 + 16) * 128, 1, 128, 4, Bd.NTP_KIND_QKV_GQA, 128, 8)
+    segs = N.ntp_reshard_segments(spec, 71, 72)
+    per_dst = {}
+    for r, s, su, du, n in segs:
+        per_dst[s] = per_dst.get(s, 0) + n
+    for s in range(72):
+        p = O.attn_shard_plan(128, 8, 72, s)
+        assert per_dst[s] == p["q_cnt"] + 2 * p["kv_cnt"]
+
+
+def test_reshard_argument_errors_without_launch():
+    lib = Bd.lib()
+    n = C.c_int64()
+    bad = [N.tensor_spec(10, 4, 2), N.tensor_spec(10, 4, 0, 3), N.tensor_spec(10, 4, 0, 1, 3),
+           N.tensor_spec(10, 4, 0, 1, 4, 7), N.tensor_spec(10, 4, 0, 1, 4, Bd.NTP_KIND_QKV_GQA, 4, 2),
+           N.tensor_spec(-1, 4, 0)]
+    for spec in bad:
+        assert lib.ntp_reshard_segments(C.byref(spec), 2, 3, None, 0, C.byref(n)) == Bd.NTP_ERR_INVALID_ARG
+    ok = N.tensor_spec(10, 4, 0)
+    assert lib.ntp_reshard_segments(C.byref(ok), 0, 3, None, 0, C.byref(n)) == Bd.NTP_ERR_INVALID_ARG
+    assert lib.ntp_reshard_segments(C.byref(ok), 2, 3, None, 0, None) == Bd.NTP_ERR_INVALID_ARG
+    # null arrays are rejected before anything touches the GPU
+    assert lib.ntp_reshard_grad(C.byref(ok), 2, 3, None, None, None, None, None) == Bd.NTP_ERR_INVALID_ARG
+
+
+def test_layer_argument_errors_without_launch():
+    lib = Bd.lib()
+    shape = Bd.MlpShape(4, 12, 3, 0)  # H not a multiple of 8
+    z = [None, 0] * 6
+    assert lib.ntp_mlp_shard_fwd(C.byref(shape), *z, None) == Bd.NTP_ERR_ALIGNMENT
+    shape = Bd.MlpShape(4, 16, 3, 9)  # unknown GeLU mode
+    assert lib.ntp_mlp_shard_fwd(C.byref(shape), *z, None) == Bd.NTP_ERR_INVALID_ARG
+    shape = Bd.MlpShape(4, 16, 3, 0)  # null tensors
+    assert lib.ntp_mlp_shard_fwd(C.byref(shape), *z, None) == Bd.NTP_ERR_INVALID_ARG
+    assert lib.ntp_mlp_shard_fwd(None, *z, None) == Bd.NTP_ERR_INVALID_ARG
+    ashape = Bd.AttnShape(4, 16, 12, 8)  # w_qkv not a multiple of 8
+    assert lib.ntp_attn_proj_shard_fwd(C.byref(ashape), *z, None) == Bd.NTP_ERR_ALIGNMENT
