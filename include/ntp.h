@@ -202,6 +202,25 @@ int ntp_reshard_grad(const ntp_tensor_spec_t* spec, int32_t src_tp, int32_t dst_
                      const void* const* src_shards, const int64_t* src_ld,
                      void* const* dst_shards, const int64_t* dst_ld, void* stream);
 
+/* ---------------------------------------------------------------------------
+ * Measurement aid (not part of the method).  When enabled, every kernel the
+ * library enqueues is bracketed by two HIP events on the caller's stream and
+ * recorded with its algorithmic work: flops = 2 M N K on the logical GEMM
+ * dimensions, bytes = bytes read + bytes written by a reshard launch.  This is
+ * the only part of the library that creates HIP objects (events); it is off by
+ * default.  ntp_kernel_timing_read waits for the recorded kernels, writes at
+ * most max_records entries (launch order), stores the number of launches
+ * recorded in *count and clears the list. */
+typedef struct ntp_kernel_time {
+  char name[48]; /* kernel family and variant, e.g. "gemm_tn_f32"  */
+  double flops;  /* algorithmic flops of this launch (0 for copies)  */
+  double bytes;  /* algorithmic bytes of this launch (0 for GEMMs)   */
+  float ms;      /* duration between the two events                  */
+  int32_t pad_;
+} ntp_kernel_time_t;
+int ntp_kernel_timing_enable(int32_t on);
+int ntp_kernel_timing_read(ntp_kernel_time_t* out, int64_t max_records, int64_t* count);
+
 #ifdef __cplusplus
 }
 #endif

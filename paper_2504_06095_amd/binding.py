@@ -25,7 +25,7 @@ NTP_KIND_QKV_GQA = 1
 EXPORTS = (
     "ntp_version", "ntp_status_string", "ntp_shard_plan", "ntp_attn_shard_plan", "ntp_mlp_shard_fwd",
     "ntp_mlp_shard_bwd", "ntp_attn_proj_shard_fwd", "ntp_attn_proj_shard_bwd", "ntp_reshard_segments",
-    "ntp_reshard_grad",
+    "ntp_reshard_grad", "ntp_kernel_timing_enable", "ntp_kernel_timing_read",
 )
 
 
@@ -58,6 +58,11 @@ class Segment(C.Structure):
                 ("dst_unit", C.c_int64), ("units", C.c_int64)]
 
 
+class KernelTime(C.Structure):
+    _fields_ = [("name", C.c_char * 48), ("flops", C.c_double), ("bytes", C.c_double), ("ms", C.c_float),
+                ("pad_", C.c_int32)]
+
+
 _lib = None
 
 
@@ -82,6 +87,8 @@ def lib() -> C.CDLL:
                                            C.POINTER(i64)]
         L.ntp_reshard_grad.argtypes = [C.POINTER(TensorSpec), C.c_int32, C.c_int32, C.POINTER(vp), C.POINTER(i64),
                                        C.POINTER(vp), C.POINTER(i64), vp]
+        L.ntp_kernel_timing_enable.argtypes = [C.c_int32]
+        L.ntp_kernel_timing_read.argtypes = [C.POINTER(KernelTime), i64, C.POINTER(i64)]
         for name in EXPORTS:
             getattr(L, name)  # AttributeError if a declared symbol is not exported
         _lib = L
@@ -212,3 +219,16 @@ def ntp_reshard_grad(spec: TensorSpec, src_tp: int, dst_tp: int, src_shards, dst
             p, ld = _mat(t)
             arr_p[i], arr_l[i] = p, ld
     _check(lib().ntp_reshard_grad(C.byref(spec), src_tp, dst_tp, sp, sl, dp, dl, _stream()), "ntp_reshard_grad")
+
+
+# ---- measurement aid ---------------------------------------------------------------
+def ntp_kernel_timing_enable(on: bool) -> None:
+    _check(lib().ntp_kernel_timing_enable(int(bool(on))), "ntp_kernel_timing_enable")
+
+
+def ntp_kernel_timing_read(max_records: int = 4096) -> list[dict]:
+    """Waits for the recorded launches; returns [{name, flops, bytes, ms}] in launch order."""
+    buf = (KernelTime * max_records)()
+    n = C.c_int64()
+    _check(lib().ntp_kernel_timing_read(buf, max_records, C.byref(n)), "ntp_kernel_timing_read")
+    return [dict(name=r.name.decode(), flops=r.flops, bytes=r.bytes, ms=r.ms) for r in buf[: min(n.value, max_records)]]

@@ -9,7 +9,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libntp.so")
 
-SOURCES = ["ntp_plan.cpp", "ntp_layers.cpp", "ntp_gemm.hip", "ntp_reshard.hip"]
+SOURCES = ["ntp_plan.cpp", "ntp_layers.cpp", "ntp_timing.cpp", "ntp_gemm.hip", "ntp_reshard.hip"]
 
 # -packed-fp32-ops is switched off: the compiler must not form packed fp32 VALU ops.
 HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",

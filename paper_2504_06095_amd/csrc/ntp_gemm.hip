@@ -8,6 +8,10 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <type_traits>
 
 #include "ntp_internal.h"
 
@@ -219,18 +223,296 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const GemmArgs g) {
       }
 }
 
-template <bool AKC, bool BKC>
-int launch_generic(const GemmArgs& g, int epi, hipStream_t s) {
-  const dim3 grid(uint32_t(g.tiles_m) * uint32_t(g.tiles_n)), block(256);
+// ------------------------------------------------------------------------------
+// Fast kernel: BM x BN x 64 tile, 8 wavefronts (WGM x WGN), register-staged double
+// buffering in LDS (one barrier per K tile).
+//   K-contiguous operand:  LDS [row][k], 144-byte rows  -> ds_read_b128 fragments
+//   K-strided operand:     LDS [k][row], (R + 32)-element rows -> two transposing
+//                          64-bit LDS reads per fragment (no register shuffles)
+// Row strides are chosen so that the 16 lanes served together hit distinct banks.
+// Rows past the edge are clamped to the last valid row (their products are never
+// stored); the K tail tile is loaded with element masks so that it contributes zeros.
+constexpr int FK = 64;
+constexpr int FAST_THREADS = 512;
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+template <bool KC, int R>
+struct FastOperand {
+  static constexpr int LD = KC ? (FK + 8) : (R + 32);
+  static constexpr int STAGE = KC ? R * LD : FK * LD;  // elements per pipeline stage
+  static constexpr int CHUNKS = R / 64;                // 16-byte chunks per thread per tile
+  static_assert(R % 64 == 0, "tile extent must be a multiple of 64");
+
+  const uint16_t* ptr[CHUNKS];  // this thread's chunk addresses in K tile 0
+  u16x8 v[CHUNKS];
+  int64_t kstep;                // elements between consecutive K tiles
+
+  __device__ __forceinline__ void init(const uint16_t* base, int64_t ld, int row0, int lim, int tid) {
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i) {
+      const int id = tid + FAST_THREADS * i;
+      if constexpr (KC) {
+        const int r = id >> 3, c = (id & 7) * 8;
+        const int row = min(row0 + r, lim - 1);
+        ptr[i] = base + int64_t(row) * ld + c;
+      } else {
+        constexpr int CPR = R / 8;  // chunks per k row
+        const int k = id / CPR, c = (id % CPR) * 8;
+        const int col = min(row0 + c, ((lim - 1) >> 3) << 3);
+        ptr[i] = base + int64_t(k) * ld + col;
+      }
+    }
+    kstep = KC ? FK : FK * ld;
+  }
+
+  __device__ __forceinline__ void load_full(int kt) {
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i) v[i] = *reinterpret_cast<const u16x8*>(ptr[i] + kt * kstep);
+  }
+
+  // K tile that crosses the end of K: everything at k >= K reads as zero
+  __device__ __forceinline__ void load_tail(int kt, int K, int tid) {
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i) {
+      const int id = tid + FAST_THREADS * i;
+      u16x8 val = {0, 0, 0, 0, 0, 0, 0, 0};
+      if constexpr (KC) {
+        const int k = kt * FK + (id & 7) * 8;
+        if (k < K) {
+          val = *reinterpret_cast<const u16x8*>(ptr[i] + kt * kstep);
+#pragma unroll
+          for (int j = 0; j < 8; ++j)
+            if (k + j >= K) val[j] = 0;
+        }
+      } else {
+        constexpr int CPR = R / 8;
+        const int k = kt * FK + id / CPR;
+        if (k < K) val = *reinterpret_cast<const u16x8*>(ptr[i] + kt * kstep);
+      }
+      v[i] = val;
+    }
+  }
+
+  __device__ __forceinline__ void store(uint16_t* lds, int tid) const {
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i) {
+      const int id = tid + FAST_THREADS * i;
+      if constexpr (KC) {
+        *reinterpret_cast<u16x8*>(lds + (id >> 3) * LD + (id & 7) * 8) = v[i];
+      } else {
+        constexpr int CPR = R / 8;
+        *reinterpret_cast<u16x8*>(lds + (id / CPR) * LD + (id % CPR) * 8) = v[i];
+      }
+    }
+  }
+
+  // 32 rows x 16 k fragment in MFMA operand layout: lane l holds row (l % 32), k = 8 (l / 32) + 0..7
+  __device__ __forceinline__ static bf16x8 frag(const uint16_t* lds, int rbase, int ks, int lane) {
+    if constexpr (KC) {
+      return *reinterpret_cast<const bf16x8*>(lds + (rbase + (lane & 31)) * LD + ks * 16 + (lane >> 5) * 8);
+    } else {
+      // Transposing read: in each 16-lane group, lane s points at 4 consecutive rows of
+      // k-line (s / 4); the group hands lane L the 4 k-values of row L.
+      const int g = lane >> 4, s = lane & 15;
+      const int krow = ks * 16 + (g >> 1) * 8 + (s >> 2);
+      const int col = rbase + (g & 1) * 16 + (s & 3) * 4;
+      typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+      const uint16_t* p = lds + krow * LD + col;
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * LD));
+      const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      return __builtin_bit_cast(bf16x8, both);
+    }
+  }
+};
+
+template <bool AKC, bool BKC, int EPI, int BM_, int BN_, int WGM, int WGN>
+__global__ __launch_bounds__(FAST_THREADS) void gemm_fast_kernel(const GemmArgs g) {
+  static_assert(WGM * WGN == 8, "8 wavefronts");
+  constexpr int TM = BM_ / WGM, TN = BN_ / WGN;  // wavefront tile
+  constexpr int MI = TM / 32, NI = TN / 32;
+  static_assert(TM % 32 == 0 && TN % 32 == 0, "wavefront tile must be made of 32x32 blocks");
+  using OpA = FastOperand<AKC, BM_>;
+  using OpB = FastOperand<BKC, BN_>;
+  __shared__ __attribute__((aligned(16))) uint16_t sA[2][OpA::STAGE];
+  __shared__ __attribute__((aligned(16))) uint16_t sB[2][OpB::STAGE];
+
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63;
+  const int wm = wave / WGN, wn = wave % WGN;
+
+  // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): give every XCD a
+  // contiguous range of tiles, walked in groups of 8 tile rows so that neighbours share operands.
+  const int nblk = g.tiles_m * g.tiles_n;
+  const int xq = nblk >> 3, xr = nblk & 7, xcd = blockIdx.x & 7;
+  const int L = xcd * xq + min(xcd, xr) + (blockIdx.x >> 3);
+  constexpr int GM = 8;
+  const int width = GM * g.tiles_n;
+  const int first_m = (L / width) * GM;
+  const int gsz = min(g.tiles_m - first_m, GM);
+  const int tile_m = first_m + (L % width) % gsz, tile_n = (L % width) / gsz;
+  const int row0 = tile_m * BM_, col0 = tile_n * BN_;
+
+  f32x16 acc[MI][NI];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  OpA a;
+  OpB b;
+  a.init(g.A, g.lda, row0, g.M, tid);
+  b.init(g.B, g.ldb, col0, g.N, tid);
+  const int ktiles = (g.K + FK - 1) / FK;
+  const int kfull = g.K / FK;  // tiles below this index need no masking
+
+  auto load = [&](int kt) {
+    if (kt < kfull) {
+      a.load_full(kt);
+      b.load_full(kt);
+    } else {
+      a.load_tail(kt, g.K, tid);
+      b.load_tail(kt, g.K, tid);
+    }
+  };
+
+  if (ktiles > 0) {
+    load(0);
+    a.store(sA[0], tid);
+    b.store(sB[0], tid);
+    __syncthreads();
+    if (ktiles > 1) load(1);
+  }
+  for (int kt = 0; kt < ktiles; ++kt) {
+    const uint16_t* cA = sA[kt & 1];
+    const uint16_t* cB = sB[kt & 1];
+#pragma unroll
+    for (int ks = 0; ks < FK / 16; ++ks) {
+      bf16x8 fa[MI], fb[NI];
+#pragma unroll
+      for (int i = 0; i < MI; ++i) fa[i] = OpA::frag(cA, wm * TM + i * 32, ks, lane);
+#pragma unroll
+      for (int j = 0; j < NI; ++j) fb[j] = OpB::frag(cB, wn * TN + j * 32, ks, lane);
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < ktiles) {
+      a.store(sA[(kt + 1) & 1], tid);
+      b.store(sB[(kt + 1) & 1], tid);
+      if (kt + 2 < ktiles) load(kt + 2);
+    }
+    __syncthreads();
+  }
+
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int m = row0 + wm * TM + i * 32 + (lane & 31);
+        const int n0 = col0 + wn * TN + j * 32 + q * 8 + (lane >> 5) * 4;
+        f32x4 v = {acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
+        store4<EPI>(g, m, n0, v);
+      }
+}
+
+template <typename F>
+int dispatch_epilogue(int epi, F&& f) {
   switch (epi) {
-    case ntp::EPI_BF16: hipLaunchKernelGGL((gemm_generic_kernel<AKC, BKC, ntp::EPI_BF16>), grid, block, 0, s, g); break;
-    case ntp::EPI_GELU: hipLaunchKernelGGL((gemm_generic_kernel<AKC, BKC, ntp::EPI_GELU>), grid, block, 0, s, g); break;
-    case ntp::EPI_DGELU: hipLaunchKernelGGL((gemm_generic_kernel<AKC, BKC, ntp::EPI_DGELU>), grid, block, 0, s, g); break;
-    case ntp::EPI_F32: hipLaunchKernelGGL((gemm_generic_kernel<AKC, BKC, ntp::EPI_F32>), grid, block, 0, s, g); break;
-    case ntp::EPI_F32_ACCUM: hipLaunchKernelGGL((gemm_generic_kernel<AKC, BKC, ntp::EPI_F32_ACCUM>), grid, block, 0, s, g); break;
+    case ntp::EPI_BF16: return f(std::integral_constant<int, ntp::EPI_BF16>{});
+    case ntp::EPI_GELU: return f(std::integral_constant<int, ntp::EPI_GELU>{});
+    case ntp::EPI_DGELU: return f(std::integral_constant<int, ntp::EPI_DGELU>{});
+    case ntp::EPI_F32: return f(std::integral_constant<int, ntp::EPI_F32>{});
+    case ntp::EPI_F32_ACCUM: return f(std::integral_constant<int, ntp::EPI_F32_ACCUM>{});
     default: return NTP_ERR_INVALID_ARG;
   }
-  return hipGetLastError() == hipSuccess ? NTP_OK : NTP_ERR_LAUNCH;
+}
+
+template <bool AKC, bool BKC>
+int launch_generic(GemmArgs g, int epi, hipStream_t s) {
+  g.tiles_m = (g.M + BM - 1) / BM;
+  g.tiles_n = (g.n_store + BN - 1) / BN;
+  if (int64_t(g.tiles_m) * g.tiles_n > 0x7fffffff) return NTP_ERR_UNSUPPORTED;
+  const dim3 grid(uint32_t(g.tiles_m) * uint32_t(g.tiles_n)), block(256);
+  return dispatch_epilogue(epi, [&](auto e) {
+    hipLaunchKernelGGL((gemm_generic_kernel<AKC, BKC, decltype(e)::value>), grid, block, 0, s, g);
+    return hipGetLastError() == hipSuccess ? NTP_OK : NTP_ERR_LAUNCH;
+  });
+}
+
+template <bool AKC, bool BKC, int BM_, int BN_, int WGM, int WGN>
+int launch_fast(GemmArgs g, int epi, hipStream_t s) {
+  g.tiles_m = (g.M + BM_ - 1) / BM_;
+  g.tiles_n = (g.n_store + BN_ - 1) / BN_;
+  if (int64_t(g.tiles_m) * g.tiles_n > 0x7fffffff) return NTP_ERR_UNSUPPORTED;
+  const dim3 grid(uint32_t(g.tiles_m) * uint32_t(g.tiles_n)), block(FAST_THREADS);
+  return dispatch_epilogue(epi, [&](auto e) {
+    hipLaunchKernelGGL((gemm_fast_kernel<AKC, BKC, decltype(e)::value, BM_, BN_, WGM, WGN>), grid, block, 0, s, g);
+    return hipGetLastError() == hipSuccess ? NTP_OK : NTP_ERR_LAUNCH;
+  });
+}
+
+// Tile shapes of the fast kernel, widest first.
+struct TileChoice {
+  int bm, bn;
+  double rate;  // relative throughput of one tile of this shape at full occupancy
+};
+constexpr TileChoice kTiles[] = {{256, 256, 1.0}, {128, 256, 0.85}, {256, 128, 0.85}, {128, 128, 0.7}};
+
+// Pick the tile shape with the least estimated time: rounds of 256 workgroups times tile area over rate.
+int choose_tile(int64_t M, int64_t N) {
+  int best = 0;
+  double best_t = 1e300;
+  for (int i = 0; i < int(sizeof(kTiles) / sizeof(kTiles[0])); ++i) {
+    const int64_t tiles = ((M + kTiles[i].bm - 1) / kTiles[i].bm) * ((N + kTiles[i].bn - 1) / kTiles[i].bn);
+    const int64_t rounds = (tiles + 255) / 256;
+    const double t = double(rounds) * kTiles[i].bm * kTiles[i].bn / kTiles[i].rate;
+    if (t < best_t) {
+      best_t = t;
+      best = i;
+    }
+  }
+  return best;
+}
+
+// Variant used for a shape: -1 = generic kernel, else an index into kTiles.  The environment
+// variable NTP_GEMM_TILE (generic | 256x256 | 128x256 | 256x128 | 128x128) overrides the choice;
+// it exists so that tests and tuning runs can reach every variant at any size.
+int choose_variant(const GemmArgs& g) {
+  if (const char* f = getenv("NTP_GEMM_TILE")) {
+    if (!strcmp(f, "generic")) return -1;
+    if (!strcmp(f, "256x256")) return 0;
+    if (!strcmp(f, "128x256")) return 1;
+    if (!strcmp(f, "256x128")) return 2;
+    if (!strcmp(f, "128x128")) return 3;
+  }
+  // small problems: the generic 128x128x32 kernel (4 wavefronts) has less fixed cost
+  if (int64_t(g.M) * g.N < 128 * 128 * 64 || g.K < 128) return -1;
+  return choose_tile(g.M, g.n_store);
+}
+
+const char* variant_name(int v) {
+  static const char* const kName[] = {"generic128", "256x256", "128x256", "256x128", "128x128"};
+  return kName[v + 1];
+}
+
+template <bool AKC, bool BKC>
+int launch_any(const GemmArgs& g, int epi, hipStream_t s, int variant) {
+  switch (variant) {
+    case 0: return launch_fast<AKC, BKC, 256, 256, 2, 4>(g, epi, s);
+    case 1: return launch_fast<AKC, BKC, 128, 256, 2, 4>(g, epi, s);
+    case 2: return launch_fast<AKC, BKC, 256, 128, 4, 2>(g, epi, s);
+    case 3: return launch_fast<AKC, BKC, 128, 128, 2, 4>(g, epi, s);
+    default: return launch_generic<AKC, BKC>(g, epi, s);
+  }
 }
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
@@ -283,14 +565,22 @@ int gemm_launch(const GemmDesc& d, void* stream) {
   g.K = int32_t(d.K);
   g.n_store = int32_t(n_store);
   g.gelu_mode = d.gelu_mode;
-  g.tiles_m = int32_t((d.M + BM - 1) / BM);
-  g.tiles_n = int32_t((n_store + BN - 1) / BN);
-  if (int64_t(g.tiles_m) * g.tiles_n > 0x7fffffff) return NTP_ERR_UNSUPPORTED;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (d.a_kc && d.b_kc) return launch_generic<true, true>(g, d.epilogue, s);
-  if (d.a_kc && !d.b_kc) return launch_generic<true, false>(g, d.epilogue, s);
-  if (!d.a_kc && !d.b_kc) return launch_generic<false, false>(g, d.epilogue, s);
-  return launch_generic<false, true>(g, d.epilogue, s);
+  static const char* const kEpiName[] = {"bf16", "gelu", "dgelu", "f32", "f32acc"};
+  const int variant = choose_variant(g);
+  if (ntp::timing_on()) {
+    char name[48];
+    snprintf(name, sizeof(name), "gemm_%c%c_%s_%s", d.a_kc ? 'n' : 't', d.b_kc ? 't' : 'n', kEpiName[d.epilogue],
+             variant_name(variant));
+    ntp::timing_begin(stream, name, 2.0 * double(d.M) * double(d.N) * double(d.K), 0.0);
+  }
+  int st;
+  if (d.a_kc && d.b_kc) st = launch_any<true, true>(g, d.epilogue, s, variant);
+  else if (d.a_kc && !d.b_kc) st = launch_any<true, false>(g, d.epilogue, s, variant);
+  else if (!d.a_kc && !d.b_kc) st = launch_any<false, false>(g, d.epilogue, s, variant);
+  else st = launch_any<false, true>(g, d.epilogue, s, variant);
+  ntp::timing_end(stream);
+  return st;
 }
 
 }  // namespace ntp

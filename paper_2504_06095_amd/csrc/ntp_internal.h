@@ -23,6 +23,11 @@ int shard_units(const ntp_tensor_spec_t* spec, int64_t n_units, int32_t tp, int3
 int build_segments(const ntp_tensor_spec_t* spec, int32_t src_tp, int32_t dst_tp,
                    std::vector<ntp_segment_t>* segs);
 
+// ---- optional per-kernel timing (measurement aid) ------------------------------
+bool timing_on();
+void timing_begin(void* stream, const char* name, double flops, double bytes);
+void timing_end(void* stream);
+
 // ---- GEMM family -------------------------------------------------------------
 // C[M x N] = op(A) op(B), bf16 operands, fp32 accumulation on the matrix cores.
 // An operand is "K-contiguous" when consecutive k sit next to each other in memory:

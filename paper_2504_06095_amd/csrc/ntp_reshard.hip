@@ -224,8 +224,15 @@ extern "C" int ntp_reshard_grad(const ntp_tensor_spec_t* spec, int32_t src_tp, i
       batch.seg[i] = c;
     }
     if (blocks == 0) continue;
+    if (ntp::timing_on()) {
+      double bytes = 0.0;
+      for (int i = 0; i < batch.nseg; ++i) bytes += 2.0 * double(batch.seg[i].rows) * double(batch.seg[i].row_bytes);
+      ntp::timing_begin(stream, "reshard_copy", 0.0, bytes);
+    }
     hipLaunchKernelGGL(reshard_copy_kernel, dim3(uint32_t(blocks)), dim3(kThreads), 0, hs, batch);
-    if (hipGetLastError() != hipSuccess) return NTP_ERR_LAUNCH;
+    const bool ok = hipGetLastError() == hipSuccess;
+    ntp::timing_end(stream);
+    if (!ok) return NTP_ERR_LAUNCH;
   }
   return NTP_OK;
 }

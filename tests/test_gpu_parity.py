@@ -170,3 +170,36 @@ def test_attn_halves_can_be_skipped():
     N.ntp_attn_proj_shard_fwd(128, 256, case.w_qkv, case.w_o, X, Wqkv, QKV, None, None, None)
     torch.cuda.synchronize()
     assert rel_err(dev_bf16_to_f64(QKV), case.oracle()["QKV"]) <= TOL
+
+
+# ---- every GEMM tile variant, reached through the tuning override, on ragged shapes --------------
+@pytest.mark.parametrize("variant", ["generic", "256x256", "128x256", "256x128", "128x128"])
+def test_mlp_every_tile_variant_ragged(variant, monkeypatch):
+    # M = 777 (ragged rows), H = 1096 = 17 * 64 + 8 (K tail of 8), n_r = 1001 (odd: ragged N, K and dW rows)
+    _say(f"mlp variant {variant}")
+    monkeypatch.setenv("NTP_GEMM_TILE", variant)
+    case = MlpCase(777, 1096, 2003, 2, 1)
+    assert case.n_r == 1001
+    got, raw = case.run_gpu()
+    _check_all(got, case.oracle(), MLP_NAMES)
+    for name in ("P", "Y", "dP"):
+        assert (raw[name][:, 1001:1008].float().cpu().numpy() == 0).all()
+
+
+@pytest.mark.parametrize("variant", ["256x256", "128x256", "256x128", "128x128"])
+def test_attn_every_tile_variant(variant, monkeypatch):
+    _say(f"attn variant {variant}")
+    monkeypatch.setenv("NTP_GEMM_TILE", variant)
+    case = AttnCase(520, 1032, 16, 2, 64, 5, 0)  # 4 q heads + 2 x 1 kv heads: w_qkv = 384, w_o = 256
+    _check_all(case.run_gpu(), case.oracle(), ["QKV", "Z", "dC", "dX", "dWqkv", "dWo"])
+
+
+def test_mlp_tiny_k_and_single_rows_on_fast_tiles(monkeypatch):
+    # degenerate extents through the wide-tile kernel: K = 8, M = 1, n_r = 1
+    for variant in ("256x256", "128x128"):
+        monkeypatch.setenv("NTP_GEMM_TILE", variant)
+        for (M, H, n, tp, rank) in [(1, 8, 3, 3, 0), (3, 72, 17, 1, 0), (65, 64, 64, 1, 0)]:
+            _say(f"mlp degenerate {variant} M={M} H={H} n={n}")
+            case = MlpCase(M, H, n, tp, rank)
+            got, _ = case.run_gpu()
+            _check_all(got, case.oracle(), MLP_NAMES)
