@@ -1,0 +1,280 @@
+#!/usr/bin/env python3
+"""Benchmark of the NTP shard hot path on one MI355X.
+
+One step = one pass of the whole hot path over one batch of synthetic input, at the
+GPT-3-175B-shape configuration with the replica degraded from TP 8 to TP 7, rank 0:
+  shard plans (host) -> MLP shard forward + backward (6 GEMMs, fused GeLU / GeLU')
+  -> attention projection shard forward + backward (6 GEMMs)
+  -> reshard of this rank's four weight gradients into the TP-8 layout.
+`value` is the GEMM work of a step (logical 2*M*N*K flops) divided by the wall time of
+the whole step, inputs resident in HBM.  Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+BF16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E peak
+
+# workload: GPT-3-175B-shape layer, full TP 8, degraded to TP 7, this GPU = rank 0
+M, H, FFN, HEADS, HEAD_DIM, T_FULL, T_RED, RANK = 2048, 12288, 49152, 96, 128, 8, 7, 0
+
+
+def build_state(torch, N):
+    """Allocate and fill every buffer of the step (synthetic N(0,1) activations, N(0,0.02) weights)."""
+    from paper_2504_06095_amd import inputs as I
+    dev = "cuda"
+    _, n_r = N.ntp_shard_plan(FFN, T_RED, RANK)
+    ap = N.ntp_attn_shard_plan(HEADS, HEADS, HEAD_DIM, T_RED, RANK)
+    wq, wo = ap["w_qkv"], ap["w_o"]
+    ld = (n_r + 7) // 8 * 8
+
+    def bf(name, shape, std):
+        bits, _ = I.normal_bf16(0, "bench." + name, shape, std)
+        return torch.from_numpy(bits.view("int16")).to(dev).view(torch.bfloat16)
+
+    s = dict(n_r=n_r, wq=wq, wo=wo, ld=ld, ap=ap)
+    s["X"], s["dZ"] = bf("X", (M, H), I.ACT_STD), bf("dZ", (M, H), I.ACT_STD)
+    s["A_t"], s["B"] = bf("A_t", (n_r, H), I.WEIGHT_STD), bf("B", (n_r, H), I.WEIGHT_STD)
+    s["Wqkv"], s["Wo"] = bf("Wqkv", (wq, H), I.WEIGHT_STD), bf("Wo", (wo, H), I.WEIGHT_STD)
+    s["C"], s["dQKV"] = bf("C", (M, wo), I.ACT_STD), bf("dQKV", (M, wq), I.ACT_STD)
+    e = lambda r, c, dt=torch.bfloat16: torch.empty(r, c, dtype=dt, device=dev)
+    s["P"], s["Y"], s["dP"] = e(M, ld)[:, :n_r], e(M, ld)[:, :n_r], e(M, ld)[:, :n_r]
+    s["Z"], s["dX"], s["Z2"], s["dX2"] = e(M, H), e(M, H), e(M, H), e(M, H)
+    s["QKV"], s["dC"] = e(M, wq), e(M, wo)
+    f32 = torch.float32
+    s["dA_t"], s["dB"], s["dWqkv"], s["dWo"] = e(n_r, H, f32), e(n_r, H, f32), e(wq, H, f32), e(wo, H, f32)
+
+    # reshard plan of this rank's gradients: TP 7 (only rank 0 present) -> TP 8 (ranks 0 and 1 receive)
+    def reshard_job(src, rows, unit, kind, n_q=0, n_kv=0):
+        spec = N.tensor_spec(rows, H, 0, unit, 4, kind, n_q, n_kv)
+        srcs = [None] * T_RED
+        srcs[RANK] = src
+        dsts = [None] * T_FULL
+        touched = {seg[1] for seg in N.ntp_reshard_segments(spec, T_RED, T_FULL) if seg[0] == RANK}
+        for d in touched:
+            if kind == N.binding.NTP_KIND_QKV_GQA:
+                p = N.ntp_attn_shard_plan(n_q, n_kv, unit, T_FULL, d)
+                w = p["w_qkv"]
+            else:
+                w = N.ntp_shard_plan(rows // unit, T_FULL, d)[1] * unit
+            dsts[d] = e(w, H, f32)
+        return spec, srcs, dsts
+
+    K = N.binding
+    s["reshard_jobs"] = [
+        reshard_job(s["dA_t"], FFN, 1, K.NTP_KIND_PLAIN),
+        reshard_job(s["dB"], FFN, 1, K.NTP_KIND_PLAIN),
+        reshard_job(s["dWqkv"], 3 * HEADS * HEAD_DIM, HEAD_DIM, K.NTP_KIND_QKV_GQA, HEADS, HEADS),
+        reshard_job(s["dWo"], HEADS * HEAD_DIM, HEAD_DIM, K.NTP_KIND_PLAIN),
+    ]
+    s["gemm_flops"] = 12.0 * M * H * n_r + 6.0 * M * H * (wq + wo)
+    s["mlp_flops"] = 12.0 * M * H * n_r
+    s["reshard_bytes"] = 2.0 * 4.0 * H * (2 * n_r + wq + wo)
+    return s
+
+
+def step(N, s):
+    # a0: plans (host, pure)
+    N.ntp_shard_plan(FFN, T_RED, RANK)
+    N.ntp_attn_shard_plan(HEADS, HEADS, HEAD_DIM, T_RED, RANK)
+    n_r, wq, wo = s["n_r"], s["wq"], s["wo"]
+    # a1-a6: MLP shard
+    N.ntp_mlp_shard_fwd(s["X"], s["A_t"], s["B"], s["P"], s["Y"], s["Z"], n_r)
+    N.ntp_mlp_shard_bwd(s["dZ"], s["X"], s["A_t"], s["B"], s["P"], s["Y"], s["dP"], s["dX"], s["dA_t"], s["dB"], n_r)
+    # a7-a9: attention projections
+    N.ntp_attn_proj_shard_fwd(M, H, wq, wo, s["X"], s["Wqkv"], s["QKV"], s["C"], s["Wo"], s["Z2"])
+    N.ntp_attn_proj_shard_bwd(M, H, wq, wo, s["dZ"], s["dQKV"], s["X"], s["C"], s["Wqkv"], s["Wo"], s["dC"], s["dX2"],
+                              s["dWqkv"], s["dWo"])
+    # a10: reshard this rank's gradients TP 7 -> TP 8
+    for spec, srcs, dsts in s["reshard_jobs"]:
+        N.ntp_reshard_grad(spec, T_RED, T_FULL, srcs, dsts)
+
+
+def timed(torch, fn, steps):
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def kernel_table(N, torch, fn, steps):
+    """Per-kernel average duration over `steps` steps, from HIP events on the launch stream."""
+    torch.cuda.synchronize()
+    N.ntp_kernel_timing_enable(True)
+    for _ in range(steps):
+        fn()
+    recs = N.ntp_kernel_timing_read(1 << 16)
+    N.ntp_kernel_timing_enable(False)
+    table = {}
+    for r in recs:
+        t = table.setdefault(r["name"], dict(launches=0, ms=0.0, flops=0.0, bytes=0.0))
+        t["launches"] += 1
+        t["ms"] += r["ms"]
+        t["flops"] += r["flops"]
+        t["bytes"] += r["bytes"]
+    return table
+
+
+def cpu_baseline(s):
+    """The oracle's MLP shard forward + backward on the host cores, same inputs, all tokens."""
+    import numpy as np
+    from oracle import ntp_oracle as O
+    f64 = lambda t: t.float().cpu().numpy().astype(np.float64)
+    X, dZ, A_i, B_i = f64(s["X"]), f64(s["dZ"]), f64(s["A_t"]).T.copy(), f64(s["B"])
+    t0 = time.perf_counter()
+    P, Y, Z = O.mlp_shard_fwd(X, A_i, B_i)
+    dP, dX, dA, dB = O.mlp_shard_bwd(dZ, X, A_i, B_i)
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    # oracle flops: forward 2 GEMMs, backward recomputes P (1) + 4 GEMMs = 7 GEMMs; report on the 6 algorithmic ones
+    err = {}
+    for name, want, got in (("Z", Z, s["Z"]), ("dX", dX, s["dX"]), ("dA_t", dA.T, s["dA_t"]), ("dB", dB, s["dB"]),
+                            ("Y", Y, s["Y"]), ("dP", dP, s["dP"])):
+        g = got.float().cpu().numpy().astype(np.float64)
+        err[name] = float(np.abs(g - want).max() / np.abs(want).max())
+    return dict(value=s["mlp_flops"] / dt / 1e12, unit="TFLOP/s", cores=int(cores), kind="oracle",
+                sample=f"MLP shard fwd+bwd of the step (all {M} tokens, float64, {dt:.1f} s); attention projections "
+                       "and reshard not included", seconds=dt), err
+
+
+def reshard_stress(torch, N):
+    """Config 5: all ranks of one 405B-shape layer's fp32 weight gradients, TP 71 -> 72 and back.
+    fc1 and QKV gradients in the paper's orientation [H x width] (column blocks, odd widths),
+    fc2 and out-proj gradients as row blocks."""
+    Hh, F, nq, nkv, d, a, b = 16384, 53248, 128, 8, 128, 71, 72
+    K = N.binding
+    tensors = [  # rows, cols, partition_dim, unit, kind, n_q, n_kv
+        (Hh, F, 1, 1, K.NTP_KIND_PLAIN, 0, 0),                      # fc1 dA
+        (F, Hh, 0, 1, K.NTP_KIND_PLAIN, 0, 0),                      # fc2 dB
+        (Hh, (nq + 2 * nkv) * d, 1, d, K.NTP_KIND_QKV_GQA, nq, nkv),  # QKV dW
+        (nq * d, Hh, 0, d, K.NTP_KIND_PLAIN, 0, 0),                 # out-proj dW
+    ]
+    jobs = []
+    total = {(a, b): 0.0, (b, a): 0.0}
+    for rows, cols, pd, unit, kind, q, kv in tensors:
+        spec = N.tensor_spec(rows, cols, pd, unit, 4, kind, q, kv)
+
+        def width(tp, r):
+            if kind == K.NTP_KIND_QKV_GQA:
+                return N.ntp_attn_shard_plan(q, kv, unit, tp, r)["w_qkv"]
+            return N.ntp_shard_plan((cols if pd else rows) // unit, tp, r)[1] * unit
+
+        def shards(tp):
+            return [torch.empty((rows, width(tp, r)) if pd else (width(tp, r), cols), dtype=torch.float32,
+                                device="cuda").normal_(0, 1e-3) for r in range(tp)]
+        sa, sb = shards(a), shards(b)
+        jobs.append((spec, sa, sb))
+        total[(a, b)] += 2.0 * 4 * sum(t.numel() for t in sb)
+        total[(b, a)] += 2.0 * 4 * sum(t.numel() for t in sa)
+
+    def run(fwd):
+        for spec, sa, sb in jobs:
+            if fwd:
+                N.ntp_reshard_grad(spec, a, b, sa, sb)
+            else:
+                N.ntp_reshard_grad(spec, b, a, sb, sa)
+    out = {}
+    for key, fwd in (((a, b), True), ((b, a), False)):
+        for _ in range(2):
+            run(fwd)
+        ms = timed(torch, lambda: run(fwd), 5)
+        out[f"tp{key[0]}_to_tp{key[1]}"] = dict(ms=ms, GBps=total[key] / ms / 1e6, bytes=total[key])
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-reshard-stress", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the shard hot path of a single rank); --gpus must be 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2504_06095_amd as N
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    s = build_state(torch, N)
+    fn = lambda: step(N, s)
+    for _ in range(args.warmup):
+        fn()
+    ms = timed(torch, fn, args.steps)
+    value = s["gemm_flops"] / ms / 1e9
+
+    # per-kernel durations over the same number of steps (HIP events on the launch stream)
+    table = kernel_table(N, torch, fn, args.steps)
+    gemms = {k: v for k, v in table.items() if k.startswith("gemm_")}
+    dom_name = max(gemms, key=lambda k: gemms[k]["ms"])
+    dom = gemms[dom_name]
+    achieved = dom["flops"] / dom["ms"] / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(dom_name)
+        except Exception:
+            traffic = None
+    roofline = dict(bound="mfma", kernel=dom_name, achieved=achieved, peak=BF16_MFMA_PEAK_TFLOPS, unit="TFLOP/s",
+                    frac=achieved / BF16_MFMA_PEAK_TFLOPS, traffic=traffic, launches_per_step=dom["launches"] / args.steps,
+                    avg_launch_ms=dom["ms"] / dom["launches"], flops_per_launch=dom["flops"] / dom["launches"])
+    gemm_ms = sum(v["ms"] for v in gemms.values()) / args.steps
+    rs = table.get("reshard_copy")
+    parts = dict(gemm_ms_per_step=gemm_ms, gemm_TFLOPs=s["gemm_flops"] / gemm_ms / 1e9,
+                 gemm_frac_of_peak=s["gemm_flops"] / gemm_ms / 1e9 / BF16_MFMA_PEAK_TFLOPS)
+    if rs:
+        rms = rs["ms"] / args.steps
+        parts.update(reshard_ms_per_step=rms, reshard_GBps=rs["bytes"] / args.steps / rms / 1e6)
+    kernels = {k: dict(avg_ms=v["ms"] / v["launches"], launches_per_step=v["launches"] / args.steps,
+                       TFLOPs=(v["flops"] / v["ms"] / 1e9) if v["flops"] else None,
+                       GBps=(v["bytes"] / v["ms"] / 1e6) if v["bytes"] else None) for k, v in table.items()}
+
+    out = {
+        "metric": "shard fwd+bwd TFLOP/s (% bf16 MFMA peak); reshard GB/s (% HBM peak)",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "c2-gpt3-175b-shape layer shard, TP 8 degraded to TP 7, rank 0: MLP 2048x12288x7022 "
+                               "fwd+bwd + attention projections (96 heads x 128, 14 on this rank) fwd+bwd + reshard "
+                               "of the rank's dW (fp32) into the TP-8 layout",
+                   "tokens": M, "hidden": H, "ffn": FFN, "n_r": s["n_r"], "w_qkv": s["wq"], "w_o": s["wo"],
+                   "full_tp": T_FULL, "reduced_tp": T_RED, "rank": RANK},
+        "frac_of_bf16_peak": value / BF16_MFMA_PEAK_TFLOPS,
+        "roofline": roofline, "parts": parts, "kernels": kernels,
+    }
+    if not args.no_reshard_stress:
+        st = reshard_stress(torch, N)
+        worst = min(st.values(), key=lambda v: v["GBps"])
+        out["reshard_roofline"] = dict(bound="hbm", workload="c5: 405B-shape layer dW fp32, all ranks, TP 71<->72",
+                                       achieved=worst["GBps"], peak=HBM_PEAK_GBPS, unit="GB/s",
+                                       frac=worst["GBps"] / HBM_PEAK_GBPS, traffic=None, directions=st)
+    if not args.no_cpu_baseline:
+        fn()  # make sure the device buffers hold this step's results
+        torch.cuda.synchronize()
+        cb, err = cpu_baseline(s)
+        out["cpu_baseline"] = cb
+        out["parity_max_rel_err_vs_oracle"] = err
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
