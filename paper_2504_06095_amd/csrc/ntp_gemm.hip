@@ -62,9 +62,11 @@ struct TileChoice {
   int bm, bn;
   double rate;  // relative throughput of one tile of this shape at full occupancy
 };
-constexpr TileChoice kTiles[] = {{256, 256, 1.0}, {128, 256, 0.85}, {256, 128, 0.85}, {128, 128, 0.7}};
+constexpr TileChoice kTiles[] = {{256, 256, 1.0}, {128, 256, 0.73}, {256, 128, 0.72}, {128, 128, 0.72}};
 
-// Pick the tile shape with the least estimated time: rounds of 256 workgroups times tile area over rate.
+// Pick the tile shape with the least estimated time: rounds of 256 workgroups times tile area over
+// rate.  The rates are measured per-tile throughputs relative to 256 x 256 (more LDS and L2 traffic
+// per flop on the smaller shapes).
 int choose_tile(int64_t M, int64_t N) {
   int best = 0;
   double best_t = 1e300;
