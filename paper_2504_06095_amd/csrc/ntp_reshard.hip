@@ -3,10 +3,13 @@
 //
 // The host turns the two shard plans into sub-shards (segments); each segment is a
 // 2-D copy: `rows` rows of `row_bytes` bytes with independent source / destination
-// strides.  One kernel launch copies up to kMaxSegs segments.  A wavefront copies a
-// row (or an 8 KiB piece of a long row) with 16-byte stores that are always aligned
-// on the destination side; source loads are 16 bytes wide at element alignment, so
-// the two layouts may be misaligned against each other (odd shard widths).
+// strides.  One kernel launch copies up to kMaxSegs segments.  A workgroup takes about
+// 64 KiB of a segment (a block of rows, or 8 KiB pieces of long rows) and deals all
+// its 16-byte chunks to the threads as one flat list, so short rows (small sub-shards)
+// and long rows use the lanes equally well.  The 16-byte accesses need only 4-byte
+// alignment, so the two layouts may be misaligned against each other (odd shard
+// widths); loads are non-temporal, stores too when the destination rows are 16-byte
+// aligned.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -42,52 +45,78 @@ struct CopyBatch {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
 
-// Copy `n` bytes from s to d with one wavefront.  d and s are aligned to ESZ and
-// (s - d) % 4 == 0 when WIDE.  Stores of the body are 16-byte aligned.
-template <int ESZ, bool WIDE>
-__device__ __forceinline__ void wave_copy(const char* __restrict__ s, char* __restrict__ d, int64_t n,
-                                          int lane) {
-  if constexpr (WIDE) {
-    const int64_t head = std::min<int64_t>(n, (16 - (reinterpret_cast<uintptr_t>(d) & 15)) & 15);
-    const int64_t body = (n - head) & ~int64_t(15);
-    const int64_t tail = n - head - body;
-    if (lane * ESZ < head) {
+constexpr int kUnroll = 4;  // independent 16-byte transfers per lane in flight
+
+// Exact n / d by a multiply-high with m = ceil(2^32 / d), valid for d >= 2 and n * d <= 2^32
+// (d = 1 would need m = 2^32: fast_div passes n through).
+__device__ __forceinline__ uint32_t div_magic(uint32_t d) { return uint32_t(((uint64_t(1) << 32) + d - 1) / d); }
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, uint32_t d, uint32_t magic) {
+  return d == 1 ? n : __umulhi(n, magic);
+}
+
+// A workgroup copies `nrows` row pieces of `n` bytes each (row i at s + i * ss -> d + i * ds).
+// The pieces are cut into 16-byte chunks counted from the piece start and ALL chunks of all rows
+// are dealt to the threads as one flat list (item -> row, chunk by a multiply-high), so that short
+// pieces (a few elements per row: the small sub-shards) keep every lane busy just like long ones.
+// The 16-byte accesses need only 4-byte alignment, so source and destination may be misaligned
+// against each other (odd shard widths).  What is left of each piece (n % 16 bytes) is copied
+// element by element from a second flat list.
+template <int ESZ, bool NT_STORE>
+__device__ __forceinline__ void block_copy(const char* __restrict__ s, int64_t ss, char* __restrict__ d, int64_t ds,
+                                           uint32_t nrows, uint32_t n, uint32_t tid) {
+  const uint32_t cpr = n >> 4;  // whole chunks per row piece
+  if (cpr > 0) {
+    const uint32_t magic = div_magic(cpr), nitems = nrows * cpr;
+    for (uint32_t base = tid; base < nitems; base += kThreads * kUnroll) {
+      u32x4 v[kUnroll];
+      uint32_t row[kUnroll], off[kUnroll];
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        const uint32_t item = base + u * kThreads;
+        row[u] = fast_div(item, cpr, magic);
+        off[u] = (item - row[u] * cpr) << 4;
+        if (item < nitems)
+          v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_a4*>(s + int64_t(row[u]) * ss + off[u]));
+      }
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        if (base + u * kThreads < nitems) {
+          char* p = d + int64_t(row[u]) * ds + off[u];
+          if constexpr (NT_STORE)
+            __builtin_nontemporal_store(v[u], reinterpret_cast<u32x4*>(p));
+          else
+            *reinterpret_cast<u32x4_a4*>(p) = v[u];
+        }
+      }
+    }
+  }
+  const uint32_t te = (n & 15) / ESZ;  // leftover elements per row piece
+  if (te > 0) {
+    const uint32_t magic = div_magic(te), nitems = nrows * te, t0 = cpr << 4;
+    for (uint32_t item = tid; item < nitems; item += kThreads) {
+      const uint32_t row = fast_div(item, te, magic);
+      const uint32_t o = t0 + (item - row * te) * ESZ;
       if constexpr (ESZ == 4)
-        *reinterpret_cast<uint32_t*>(d + lane * 4) = *reinterpret_cast<const uint32_t*>(s + lane * 4);
+        *reinterpret_cast<uint32_t*>(d + int64_t(row) * ds + o) = *reinterpret_cast<const uint32_t*>(s + int64_t(row) * ss + o);
       else
-        *reinterpret_cast<uint16_t*>(d + lane * 2) = *reinterpret_cast<const uint16_t*>(s + lane * 2);
+        *reinterpret_cast<uint16_t*>(d + int64_t(row) * ds + o) = *reinterpret_cast<const uint16_t*>(s + int64_t(row) * ss + o);
     }
-    const char* sb = s + head;
-    char* db = d + head;
-    int64_t o = int64_t(lane) * 16;
-    // two independent 16-byte transfers per lane in flight
-    for (; o + 1024 < body; o += 2048) {
-      const u32x4 v0 = *reinterpret_cast<const u32x4_a4*>(sb + o);
-      const u32x4 v1 = *reinterpret_cast<const u32x4_a4*>(sb + o + 1024);
-      __builtin_nontemporal_store(v0, reinterpret_cast<u32x4*>(db + o));
-      __builtin_nontemporal_store(v1, reinterpret_cast<u32x4*>(db + o + 1024));
-    }
-    if (o < body) {
-      const u32x4 v0 = *reinterpret_cast<const u32x4_a4*>(sb + o);
-      __builtin_nontemporal_store(v0, reinterpret_cast<u32x4*>(db + o));
-    }
-    if (lane * ESZ < tail) {
-      const int64_t t = head + body + lane * ESZ;
-      if constexpr (ESZ == 4)
-        *reinterpret_cast<uint32_t*>(d + t) = *reinterpret_cast<const uint32_t*>(s + t);
-      else
-        *reinterpret_cast<uint16_t*>(d + t) = *reinterpret_cast<const uint16_t*>(s + t);
-    }
-  } else {
-    // 2-byte elements whose source and destination differ by an odd number of
-    // halfwords: element-wise copy
-    for (int64_t o = int64_t(lane) * 2; o < n; o += 128)
-      *reinterpret_cast<uint16_t*>(d + o) = *reinterpret_cast<const uint16_t*>(s + o);
+  }
+}
+
+// 2-byte elements whose addresses are only 2-byte aligned: element-wise copy
+__device__ __forceinline__ void block_copy_halfwords(const char* __restrict__ s, int64_t ss, char* __restrict__ d, int64_t ds,
+                                                     uint32_t nrows, uint32_t n, uint32_t tid) {
+  const uint32_t epr = n >> 1, magic = div_magic(epr), nitems = nrows * epr;
+  for (uint32_t item = tid; item < nitems; item += kThreads) {
+    const uint32_t row = fast_div(item, epr, magic);
+    const uint32_t o = (item - row * epr) << 1;
+    *reinterpret_cast<uint16_t*>(d + int64_t(row) * ds + o) = *reinterpret_cast<const uint16_t*>(s + int64_t(row) * ss + o);
   }
 }
 
 __global__ __launch_bounds__(kThreads) void reshard_copy_kernel(const CopyBatch batch) {
-  // find this workgroup's segment (segments are few; the table sits in scalar registers / kernarg)
+  // find this workgroup's segment (segments are few; the table sits in the kernel arguments)
   const uint32_t b = blockIdx.x;
   int si = 0;
   for (int i = 1; i < batch.nseg; ++i)
@@ -97,22 +126,25 @@ __global__ __launch_bounds__(kThreads) void reshard_copy_kernel(const CopyBatch 
   const uint32_t rg = lb / sg.col_chunks;
   const uint32_t cc = lb - rg * sg.col_chunks;
   const int64_t c0 = int64_t(cc) * kColChunk;
-  const int64_t nbytes = std::min<int64_t>(kColChunk, sg.row_bytes - c0);
+  const uint32_t nbytes = uint32_t(std::min<int64_t>(kColChunk, sg.row_bytes - c0));
   const int64_t r0 = int64_t(rg) * sg.rows_per_block;
-  const int64_t r1 = std::min<int64_t>(sg.rows, r0 + sg.rows_per_block);
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const bool wide =
-      batch.elem_size == 4 || (((reinterpret_cast<uintptr_t>(sg.src) - reinterpret_cast<uintptr_t>(sg.dst)) & 3) == 0 &&
-                               ((sg.src_stride - sg.dst_stride) & 3) == 0);
-  for (int64_t r = r0 + wave; r < r1; r += kWaves) {
-    const char* s = sg.src + r * sg.src_stride + c0;
-    char* d = sg.dst + r * sg.dst_stride + c0;
-    if (batch.elem_size == 4)
-      wave_copy<4, true>(s, d, nbytes, lane);
-    else if (wide)
-      wave_copy<2, true>(s, d, nbytes, lane);
+  const uint32_t nrows = uint32_t(std::min<int64_t>(sg.rows - r0, sg.rows_per_block));
+  const char* s = sg.src + r0 * sg.src_stride + c0;
+  char* d = sg.dst + r0 * sg.dst_stride + c0;
+  const uintptr_t sa = reinterpret_cast<uintptr_t>(sg.src), da = reinterpret_cast<uintptr_t>(sg.dst);
+  // 16-byte accesses need 4-byte aligned rows on both sides (always true for 4-byte elements)
+  const bool wide = batch.elem_size == 4 || (((sa | da | uintptr_t(sg.src_stride) | uintptr_t(sg.dst_stride)) & 3) == 0);
+  const bool dst16 = ((da | uintptr_t(sg.dst_stride)) & 15) == 0;
+  const uint32_t tid = threadIdx.x;
+  if (batch.elem_size == 4) {
+    if (dst16)
+      block_copy<4, true>(s, sg.src_stride, d, sg.dst_stride, nrows, nbytes, tid);
     else
-      wave_copy<2, false>(s, d, nbytes, lane);
+      block_copy<4, false>(s, sg.src_stride, d, sg.dst_stride, nrows, nbytes, tid);
+  } else if (wide) {
+    block_copy<2, false>(s, sg.src_stride, d, sg.dst_stride, nrows, nbytes, tid);
+  } else {
+    block_copy_halfwords(s, sg.src_stride, d, sg.dst_stride, nrows, nbytes, tid);
   }
 }
 
@@ -214,8 +246,8 @@ extern "C" int ntp_reshard_grad(const ntp_tensor_spec_t* spec, int32_t src_tp, i
       CopySeg c = copies[base + i];
       c.col_chunks = uint32_t((c.row_bytes + kColChunk - 1) / kColChunk);
       const int64_t per_row = std::min<int64_t>(c.row_bytes, kColChunk);
-      int64_t rpb = std::max<int64_t>(kWaves, kBlockBytes / per_row);
-      rpb = (rpb + kWaves - 1) / kWaves * kWaves;
+      // about kBlockBytes per workgroup; rows * elements-per-row stays far below 2^32 (exact multiply-high division)
+      int64_t rpb = std::max<int64_t>(1, std::min<int64_t>(kBlockBytes / per_row, 16384));
       c.rows_per_block = uint32_t(std::min<int64_t>(rpb, std::max<int64_t>(c.rows, 1)));
       const uint64_t row_groups = uint64_t((c.rows + c.rows_per_block - 1) / c.rows_per_block);
       c.first_block = uint32_t(blocks);
