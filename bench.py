@@ -203,6 +203,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-reshard-stress", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB dense copy (calibration_copy_kernel): the yardstick for profiler byte counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the shard hot path of a single rank); --gpus must be 1",
@@ -261,6 +263,15 @@ def main():
         "frac_of_bf16_peak": value / BF16_MFMA_PEAK_TFLOPS,
         "roofline": roofline, "parts": parts, "kernels": kernels,
     }
+    if args.calibrate_copy:
+        a = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        b = torch.empty_like(a)
+        for _ in range(3):
+            N.ntp_calibration_copy(b, a)
+        cms = timed(torch, lambda: N.ntp_calibration_copy(b, a), 5)
+        out["calibration_copy"] = dict(bytes_read=a.numel() * 4, bytes_written=a.numel() * 4, ms=cms,
+                                       GBps=2.0 * a.numel() * 4 / cms / 1e6)
+        del a, b
     if not args.no_reshard_stress:
         st = reshard_stress(torch, N)
         worst = min(st.values(), key=lambda v: v["GBps"])

@@ -221,6 +221,12 @@ typedef struct ntp_kernel_time {
 int ntp_kernel_timing_enable(int32_t on);
 int ntp_kernel_timing_read(ntp_kernel_time_t* out, int64_t max_records, int64_t* count);
 
+/* Measurement aid: a plain dense device-to-device copy of `bytes` bytes (dst, src:
+ * device, 16-byte aligned, bytes % 16 == 0, not overlapping) by a kernel named
+ * calibration_copy_kernel.  Its known traffic (bytes read, bytes written) is what
+ * the profiler's HBM byte counters are scaled by when a kernel's traffic is reported. */
+int ntp_calibration_copy(void* dst, const void* src, int64_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -25,7 +25,7 @@ NTP_KIND_QKV_GQA = 1
 EXPORTS = (
     "ntp_version", "ntp_status_string", "ntp_shard_plan", "ntp_attn_shard_plan", "ntp_mlp_shard_fwd",
     "ntp_mlp_shard_bwd", "ntp_attn_proj_shard_fwd", "ntp_attn_proj_shard_bwd", "ntp_reshard_segments",
-    "ntp_reshard_grad", "ntp_kernel_timing_enable", "ntp_kernel_timing_read",
+    "ntp_reshard_grad", "ntp_kernel_timing_enable", "ntp_kernel_timing_read", "ntp_calibration_copy",
 )
 
 
@@ -89,6 +89,7 @@ def lib() -> C.CDLL:
                                        C.POINTER(vp), C.POINTER(i64), vp]
         L.ntp_kernel_timing_enable.argtypes = [C.c_int32]
         L.ntp_kernel_timing_read.argtypes = [C.POINTER(KernelTime), i64, C.POINTER(i64)]
+        L.ntp_calibration_copy.argtypes = [vp, vp, i64, vp]
         for name in EXPORTS:
             getattr(L, name)  # AttributeError if a declared symbol is not exported
         _lib = L
@@ -232,3 +233,11 @@ def ntp_kernel_timing_read(max_records: int = 4096) -> list[dict]:
     n = C.c_int64()
     _check(lib().ntp_kernel_timing_read(buf, max_records, C.byref(n)), "ntp_kernel_timing_read")
     return [dict(name=r.name.decode(), flops=r.flops, bytes=r.bytes, ms=r.ms) for r in buf[: min(n.value, max_records)]]
+
+
+def ntp_calibration_copy(dst, src) -> None:
+    """Plain dense copy src -> dst (contiguous device tensors of equal byte size)."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes or not (src.is_contiguous() and dst.is_contiguous()):
+        raise ValueError("expected two contiguous tensors of equal byte size")
+    _check(lib().ntp_calibration_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream()), "ntp_calibration_copy")

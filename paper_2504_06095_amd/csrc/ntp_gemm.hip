@@ -13,8 +13,8 @@
 #include <cstring>
 #include <type_traits>
 
-#include "ntp_gemm_dma.h"
 #include "ntp_gemm_kernels.h"
+#include "ntp_gemm_launch.h"
 #include "ntp_internal.h"
 
 namespace {
@@ -45,35 +45,21 @@ int launch_generic(GemmArgs g, int epi, hipStream_t s) {
   });
 }
 
-template <bool AKC, bool BKC, int BM_, int BN_, int WGM, int WGN>
-int launch_fast(GemmArgs g, int epi, hipStream_t s) {
-  g.tiles_m = (g.M + BM_ - 1) / BM_;
-  g.tiles_n = (g.n_store + BN_ - 1) / BN_;
-  if (int64_t(g.tiles_m) * g.tiles_n > 0x7fffffff) return NTP_ERR_UNSUPPORTED;
-  const dim3 grid(uint32_t(g.tiles_m) * uint32_t(g.tiles_n)), block(64 * WGM * WGN);
-  return dispatch_epilogue(epi, [&](auto e) {
-    hipLaunchKernelGGL((gemm_dma_kernel<AKC, BKC, decltype(e)::value, BM_, BN_, WGM, WGN>), grid, block, 0, s, g);
-    return hipGetLastError() == hipSuccess ? NTP_OK : NTP_ERR_LAUNCH;
-  });
-}
+// Relative throughput of one workgroup per tile shape at full occupancy (256 x 256 = 1): smaller
+// wavefront tiles read more LDS fragments per MFMA, smaller workgroup tiles move more bytes per flop.
+constexpr double kTileRate[kNumTileShapes] = {1.0, 0.97, 0.97, 0.93, 0.93, 0.80, 0.80, 0.70};
+constexpr int kComputeUnits = 256;
 
-// Tile shapes of the fast kernel, widest first.
-struct TileChoice {
-  int bm, bn;
-  double rate;  // relative throughput of one tile of this shape at full occupancy
-};
-constexpr TileChoice kTiles[] = {{256, 256, 1.0}, {128, 256, 0.73}, {256, 128, 0.72}, {128, 128, 0.72}};
-
-// Pick the tile shape with the least estimated time: rounds of 256 workgroups times tile area over
-// rate.  The rates are measured per-tile throughputs relative to 256 x 256 (more LDS and L2 traffic
-// per flop on the smaller shapes).
+// Pick the tile shape with the least estimated time: the busiest compute unit's number of
+// workgroups (they are dealt evenly; co-resident ones share its throughput) times tile area over rate.
 int choose_tile(int64_t M, int64_t N) {
   int best = 0;
   double best_t = 1e300;
-  for (int i = 0; i < int(sizeof(kTiles) / sizeof(kTiles[0])); ++i) {
-    const int64_t tiles = ((M + kTiles[i].bm - 1) / kTiles[i].bm) * ((N + kTiles[i].bn - 1) / kTiles[i].bn);
-    const int64_t rounds = (tiles + 255) / 256;
-    const double t = double(rounds) * kTiles[i].bm * kTiles[i].bn / kTiles[i].rate;
+  for (int i = 0; i < kNumTileShapes; ++i) {
+    const TileShape& ts = kTileShapes[i];
+    const int64_t tiles = ((M + ts.bm - 1) / ts.bm) * ((N + ts.bn - 1) / ts.bn);
+    const int64_t cu_load = (tiles + kComputeUnits - 1) / kComputeUnits;
+    const double t = double(cu_load) * ts.bm * ts.bn / kTileRate[i];
     if (t < best_t) {
       best_t = t;
       best = i;
@@ -82,38 +68,36 @@ int choose_tile(int64_t M, int64_t N) {
   return best;
 }
 
-// Variant used for a shape: -1 = generic kernel, else an index into kTiles.  The environment
-// variable NTP_GEMM_TILE (generic | 256x256 | 128x256 | 256x128 | 128x128) overrides the choice;
-// it exists so that tests and tuning runs can reach every variant at any size.
-int choose_variant(const GemmArgs& g, bool dma_ok) {
+// Variant used for a shape: -1 = generic kernel, else an index into kTileShapes.  The environment
+// variable NTP_GEMM_TILE (generic | 256x256 | 256x224 | ...) overrides the choice; it exists so
+// that tests and tuning runs can reach every variant at any size.
+int choose_variant(const GemmArgs& g, bool ring_ok) {
   if (const char* f = getenv("NTP_GEMM_TILE")) {
-    if (!dma_ok) return -1;
-    if (!strcmp(f, "generic")) return -1;
-    if (!strcmp(f, "256x256")) return 0;
-    if (!strcmp(f, "128x256")) return 1;
-    if (!strcmp(f, "256x128")) return 2;
-    if (!strcmp(f, "128x128")) return 3;
+    if (!ring_ok || !strcmp(f, "generic")) return -1;
+    for (int i = 0; i < kNumTileShapes; ++i) {
+      char name[16];
+      snprintf(name, sizeof(name), "%dx%d", kTileShapes[i].bm, kTileShapes[i].bn);
+      if (!strcmp(f, name)) return i;
+    }
   }
   // small problems: the generic 128x128x32 kernel (4 wavefronts) has less fixed cost
   if (int64_t(g.M) * g.N < 128 * 128 * 64 || g.K < 128) return -1;
-  if (!dma_ok) return -1;
+  if (!ring_ok) return -1;
   return choose_tile(g.M, g.n_store);
 }
 
-const char* variant_name(int v) {
-  static const char* const kName[] = {"generic128", "256x256", "128x256", "256x128", "128x128"};
-  return kName[v + 1];
+void variant_name(int v, char* out, size_t n) {
+  if (v < 0) snprintf(out, n, "generic128");
+  else snprintf(out, n, "%dx%d", kTileShapes[v].bm, kTileShapes[v].bn);
 }
 
-template <bool AKC, bool BKC>
-int launch_any(const GemmArgs& g, int epi, hipStream_t s, int variant) {
-  switch (variant) {
-    case 0: return launch_fast<AKC, BKC, 256, 256, 2, 4>(g, epi, s);
-    case 1: return launch_fast<AKC, BKC, 128, 256, 2, 4>(g, epi, s);
-    case 2: return launch_fast<AKC, BKC, 256, 128, 4, 2>(g, epi, s);
-    case 3: return launch_fast<AKC, BKC, 128, 128, 2, 2>(g, epi, s);
-    default: return launch_generic<AKC, BKC>(g, epi, s);
-  }
+// (layout, epilogue) pairs the shard layers use have ring instantiations; anything else runs on
+// the generic kernel
+bool ring_combo(bool a_kc, bool b_kc, int epi) {
+  if (a_kc && b_kc) return epi == ntp::EPI_BF16 || epi == ntp::EPI_GELU || epi == ntp::EPI_DGELU;
+  if (a_kc && !b_kc) return epi == ntp::EPI_BF16;
+  if (!a_kc && !b_kc) return epi == ntp::EPI_F32 || epi == ntp::EPI_F32_ACCUM;
+  return false;
 }
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
@@ -168,21 +152,26 @@ int gemm_launch(const GemmDesc& d, void* stream) {
   g.gelu_mode = d.gelu_mode;
   hipStream_t s = static_cast<hipStream_t>(stream);
   static const char* const kEpiName[] = {"bf16", "gelu", "dgelu", "f32", "f32acc"};
-  // the DMA kernel addresses each operand with 32-bit byte offsets from its base
+  // the ring kernel addresses each operand with 32-bit byte offsets from its base
   const int64_t a_rows = d.a_kc ? d.M : d.K, b_rows = d.b_kc ? d.N : d.K;
-  const bool dma_ok = a_rows * d.lda * 2 < (int64_t(1) << 32) && b_rows * d.ldb * 2 < (int64_t(1) << 32);
-  const int variant = choose_variant(g, dma_ok);
+  const bool ring_ok = ring_combo(d.a_kc, d.b_kc, d.epilogue) && a_rows * d.lda * 2 < (int64_t(1) << 32) &&
+                       b_rows * d.ldb * 2 < (int64_t(1) << 32);
+  const int variant = choose_variant(g, ring_ok);
   if (ntp::timing_on()) {
-    char name[48];
-    snprintf(name, sizeof(name), "gemm_%c%c_%s_%s", d.a_kc ? 'n' : 't', d.b_kc ? 't' : 'n', kEpiName[d.epilogue],
-             variant_name(variant));
+    char name[48], vn[16];
+    variant_name(variant, vn, sizeof(vn));
+    snprintf(name, sizeof(name), "gemm_%c%c_%s_%s", d.a_kc ? 'n' : 't', d.b_kc ? 't' : 'n', kEpiName[d.epilogue], vn);
     ntp::timing_begin(stream, name, 2.0 * double(d.M) * double(d.N) * double(d.K), 0.0);
   }
   int st;
-  if (d.a_kc && d.b_kc) st = launch_any<true, true>(g, d.epilogue, s, variant);
-  else if (d.a_kc && !d.b_kc) st = launch_any<true, false>(g, d.epilogue, s, variant);
-  else if (!d.a_kc && !d.b_kc) st = launch_any<false, false>(g, d.epilogue, s, variant);
-  else st = launch_any<false, true>(g, d.epilogue, s, variant);
+  if (variant >= 0) {
+    if (d.a_kc && d.b_kc) st = launch_ring_nt(g, d.epilogue, variant, s);
+    else if (d.a_kc) st = launch_ring_nn(g, d.epilogue, variant, s);
+    else st = launch_ring_tn(g, d.epilogue, variant, s);
+  } else if (d.a_kc && d.b_kc) st = launch_generic<true, true>(g, d.epilogue, s);
+  else if (d.a_kc && !d.b_kc) st = launch_generic<true, false>(g, d.epilogue, s);
+  else if (!d.a_kc && !d.b_kc) st = launch_generic<false, false>(g, d.epilogue, s);
+  else st = launch_generic<false, true>(g, d.epilogue, s);
   ntp::timing_end(stream);
   return st;
 }

@@ -1,0 +1,71 @@
+// Launch side of the ring GEMM kernel: one translation unit per operand layout instantiates the
+// tile variants it needs (they compile in parallel); ntp_gemm.hip picks a variant and calls in.
+#ifndef NTP_GEMM_LAUNCH_H_
+#define NTP_GEMM_LAUNCH_H_
+
+#include <hip/hip_runtime.h>
+
+#include <type_traits>
+
+#include "ntp_gemm_ring.h"
+#include "ntp_internal.h"
+
+namespace ntp_gemm {
+
+// Tile shapes of the ring kernel.  Wavefront grids are chosen so that a wavefront's tile is
+// 64..128 rows by 48..112 columns (LDS fragment reads per MFMA stay low).
+struct TileShape {
+  int bm, bn, waves;
+};
+constexpr TileShape kTileShapes[] = {
+    {256, 256, 8}, {256, 224, 8}, {224, 256, 8}, {256, 192, 8}, {192, 256, 8}, {256, 128, 8}, {128, 256, 8}, {128, 128, 4},
+};
+constexpr int kNumTileShapes = int(sizeof(kTileShapes) / sizeof(kTileShapes[0]));
+
+// Enqueue the ring kernel for tile shape `tile` (index into kTileShapes).  A is K-contiguous in
+// the "n*" layouts, B in the "*t" layouts.  Returns an NTP_* status; NTP_ERR_UNSUPPORTED if the
+// (layout, epilogue) pair has no ring instantiation.
+int launch_ring_nt(GemmArgs g, int epilogue, int tile, hipStream_t s);  // A [M x K], B [N x K]
+int launch_ring_nn(GemmArgs g, int epilogue, int tile, hipStream_t s);  // A [M x K], B [K x N]
+int launch_ring_tn(GemmArgs g, int epilogue, int tile, hipStream_t s);  // A [K x M], B [K x N]
+
+template <bool AKC, bool BKC, int EPI, int BM_, int BN_, int WGM, int WGN>
+int launch_ring_one(GemmArgs g, hipStream_t s) {
+  g.tiles_m = (g.M + BM_ - 1) / BM_;
+  g.tiles_n = (g.n_store + BN_ - 1) / BN_;
+  if (int64_t(g.tiles_m) * g.tiles_n > 0x7fffffff) return NTP_ERR_UNSUPPORTED;
+  const dim3 grid(uint32_t(g.tiles_m) * uint32_t(g.tiles_n)), block(64 * WGM * WGN);
+  hipLaunchKernelGGL((gemm_ring_kernel<AKC, BKC, EPI, BM_, BN_, WGM, WGN>), grid, block, 0, s, g);
+  return hipGetLastError() == hipSuccess ? NTP_OK : NTP_ERR_LAUNCH;
+}
+
+template <bool AKC, bool BKC, int EPI>
+int launch_ring_tile(const GemmArgs& g, int tile, hipStream_t s) {
+  switch (tile) {
+    case 0: return launch_ring_one<AKC, BKC, EPI, 256, 256, 2, 4>(g, s);
+    case 1: return launch_ring_one<AKC, BKC, EPI, 256, 224, 4, 2>(g, s);
+    case 2: return launch_ring_one<AKC, BKC, EPI, 224, 256, 2, 4>(g, s);
+    case 3: return launch_ring_one<AKC, BKC, EPI, 256, 192, 4, 2>(g, s);
+    case 4: return launch_ring_one<AKC, BKC, EPI, 192, 256, 2, 4>(g, s);
+    case 5: return launch_ring_one<AKC, BKC, EPI, 256, 128, 4, 2>(g, s);
+    case 6: return launch_ring_one<AKC, BKC, EPI, 128, 256, 2, 4>(g, s);
+    case 7: return launch_ring_one<AKC, BKC, EPI, 128, 128, 2, 2>(g, s);
+    default: return NTP_ERR_INVALID_ARG;
+  }
+}
+
+}  // namespace ntp_gemm
+
+// Explicit instantiation of every tile shape for one (layout, epilogue) pair; each translation unit
+// lists the pairs it owns (implicit instantiation alone does not emit all host-side launch stubs).
+#define NTP_RING_INSTANTIATE(AKC, BKC, EPI)                                                        \
+  template __global__ void gemm_ring_kernel<AKC, BKC, EPI, 256, 256, 2, 4>(const GemmArgs);        \
+  template __global__ void gemm_ring_kernel<AKC, BKC, EPI, 256, 224, 4, 2>(const GemmArgs);        \
+  template __global__ void gemm_ring_kernel<AKC, BKC, EPI, 224, 256, 2, 4>(const GemmArgs);        \
+  template __global__ void gemm_ring_kernel<AKC, BKC, EPI, 256, 192, 4, 2>(const GemmArgs);        \
+  template __global__ void gemm_ring_kernel<AKC, BKC, EPI, 192, 256, 2, 4>(const GemmArgs);        \
+  template __global__ void gemm_ring_kernel<AKC, BKC, EPI, 256, 128, 4, 2>(const GemmArgs);        \
+  template __global__ void gemm_ring_kernel<AKC, BKC, EPI, 128, 256, 2, 4>(const GemmArgs);        \
+  template __global__ void gemm_ring_kernel<AKC, BKC, EPI, 128, 128, 2, 2>(const GemmArgs);
+
+#endif  // NTP_GEMM_LAUNCH_H_

@@ -1,0 +1,387 @@
+// Main bf16 MFMA GEMM kernel of the NTP shard layers.  Included by ntp_gemm.hip.
+//
+// Tile BM x BN x 64, WGM x WGN wavefronts, each computing (BM/WGM) x (BN/WGN) with
+// 16x16x32 bf16 MFMAs and fp32 accumulators.  Operands go global -> LDS by direct
+// (DMA) loads, 16 bytes per lane, no staging registers.
+//
+// LDS is a ring of FIVE operand slots (one operand of one K tile each, 5 x 32 KiB for
+// 256-row operands).  K tile t keeps A in slot 2t mod 5 and B in slot 2t+1 mod 5, so
+// while tile t is being multiplied, tile t+1 is complete or landing and A of tile t+2
+// already streams into the fifth slot.  A DMA instruction is issued only every few
+// MFMAs (the vector memory pipeline takes one 1 KiB instruction per ~18 cycles per
+// compute unit; a burst stalls the issuing wavefronts, a trickle does not), and each
+// has between one and two tile times to land.
+//
+// LDS layout of one slot (16-byte chunks stay whole; a wavefront's DMA instruction
+// fills 64 consecutive chunks, so bank spreading is done by permuting chunks):
+//   K-contiguous operand  [R rows][64 k]:  chunk p of row r holds k-chunk  p ^ ((r >> 1) & 7)
+//   K-strided operand     [64 k][R rows]:  chunk p of line k holds row-chunk
+//                                          p ^ (2 * ((k & 3) | ((k >> 3) & 1) << 2))
+// Fragments come out of LDS in MFMA operand layout (lane l: row l & 15, k 8 (l >> 4) + 0..7
+// of a K-step of 32) with one ds_read_b128 (K-contiguous) or two transposing 64-bit
+// reads (K-strided).
+//
+// Pipeline: a K tile is two K-steps of 32; each K-step is split in two halves by A rows.
+// While the MFMAs of one half issue, the A fragments of the next half (and, every other
+// half, the B fragments of the next K-step) are read.  One barrier per K tile, placed in
+// the last half: by then every wavefront has read all its fragments of the tile, and has
+// waited for its own DMA instructions of the next tile.
+#ifndef NTP_GEMM_RING_H_
+#define NTP_GEMM_RING_H_
+
+#include <type_traits>
+
+#include "ntp_gemm_kernels.h"
+
+namespace ntp_gemm {
+
+constexpr int DK = 64;  // K extent of a tile
+
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) const void global_cvoid;
+
+constexpr int vmcnt_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | 0x0F70; }       // s_waitcnt vmcnt(n) alone
+constexpr int vmcnt_lgkm0_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | 0x0070; }  // s_waitcnt vmcnt(n) lgkmcnt(0)
+
+// chunk permutation of a K-strided slot line
+__device__ __forceinline__ constexpr int kline_swz(int k) { return ((k & 3) | (((k >> 3) & 1) << 2)) << 1; }
+
+// One operand (R rows of the tile, rounded up to a multiple of 64) as seen by the DMA.
+template <bool KC, int R, int NW>
+struct DmaOperand {
+  static_assert(R % 64 == 0, "the DMA moves operands in units of 64 rows");
+  static constexpr int SLOT = R * DK;                   // elements per slot
+  static constexpr int NINST = R * DK * 2 / 1024 / NW;  // DMA instructions per wavefront per K tile
+  static_assert((R * DK * 2 / 1024) % NW == 0, "operand must split evenly over the wavefronts");
+  static constexpr int CPL = R / 8;                     // chunks per k line (K-strided layout)
+  static_assert(KC || (CPL >= 16 && (CPL & (CPL - 1)) == 0), "K-strided operands: 128 or 256 rows");
+
+  uint32_t off[NINST];  // byte offset (from the operand base at K tile 0) of this lane's chunk per instruction
+
+  // chunk position `pos` of a slot -> (line, chunk) it holds; see the layout above
+  __device__ __forceinline__ static void slot_src(int pos, int& line, int& chunk) {
+    if constexpr (KC) {
+      line = pos >> 3;
+      chunk = (pos & 7) ^ ((line >> 1) & 7);
+    } else {
+      line = pos / CPL;
+      chunk = (pos % CPL) ^ kline_swz(line);
+    }
+  }
+
+  // row0: first row of the tile, lim: extent of the operand's non-K dimension
+  __device__ __forceinline__ void init(int64_t ld, int row0, int lim, int wave, int lane) {
+#pragma unroll
+    for (int i = 0; i < NINST; ++i) {
+      int line, chunk;
+      slot_src((wave * NINST + i) * 64 + lane, line, chunk);
+      if constexpr (KC) {
+        const int row = min(row0 + line, lim - 1);  // rows past the edge repeat the last one
+        off[i] = uint32_t((int64_t(row) * ld + chunk * 8) * 2);
+      } else {
+        const int col = min(row0 + chunk * 8, ((lim - 1) >> 3) << 3);
+        off[i] = uint32_t((int64_t(line) * ld + col) * 2);
+      }
+    }
+  }
+
+  // start DMA instruction i (0 .. NINST-1) of K tile kt into `slot`: a buffer load whose scalar
+  // offset walks along K, so that no vector ALU work is spent on addresses
+  __device__ __forceinline__ void dma(__amdgpu_buffer_rsrc_t rsrc, uint32_t kstep_bytes, int kt, uint16_t* slot, int wave,
+                                      int i) const {
+    uint16_t* dst = slot + (wave * NINST + i) * 512;  // 64 chunks of 8 elements, wave-uniform
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)dst, 16, off[i], uint32_t(kt) * kstep_bytes, 0, 0);
+  }
+
+  // K tail tile through registers: everything at k >= K becomes zero
+  __device__ __forceinline__ void tail(const uint16_t* base, int64_t kstep, int kt, int K, uint16_t* slot, int wave,
+                                       int lane) const {
+    const char* tile = reinterpret_cast<const char*>(base + int64_t(kt) * kstep);
+#pragma unroll
+    for (int i = 0; i < NINST; ++i) {
+      const int pos = (wave * NINST + i) * 64 + lane;
+      int line, chunk;
+      slot_src(pos, line, chunk);
+      u16x8 val = {0, 0, 0, 0, 0, 0, 0, 0};
+      if constexpr (KC) {
+        const int k = kt * DK + chunk * 8;
+        if (k < K) {
+          val = *reinterpret_cast<const u16x8*>(tile + off[i]);
+#pragma unroll
+          for (int j = 0; j < 8; ++j)
+            if (k + j >= K) val[j] = 0;
+        }
+      } else {
+        if (kt * DK + line < K) val = *reinterpret_cast<const u16x8*>(tile + off[i]);
+      }
+      *reinterpret_cast<u16x8*>(slot + pos * 8) = val;
+    }
+  }
+};
+
+// per-lane LDS element offsets of the fragments of one operand (16 rows x 32 k per fragment)
+template <bool KC, int R, int NF>
+struct FragAddr {
+  uint32_t o[KC ? 2 : NF];
+  __device__ __forceinline__ void init(int rbase, int lane) {
+    if constexpr (KC) {
+      // k-chunk of K-step ks is 4 ks + (l >> 4); its position in the row is that ^ ((row >> 1) & 7),
+      // the same for rows 16 apart
+      const int r = rbase + (lane & 15);
+      const int sw = (r >> 1) & 7;
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) o[ks] = uint32_t(r * DK + (((ks * 4 + (lane >> 4)) ^ sw) * 8));
+    } else {
+      // transposing read: in each 16-lane group g, lane s points at 4 consecutive rows of k line
+      // 8 g + (s >> 2); the group hands lane L the 4 k-values of row L.  A second read 4 lines
+      // further down completes the 8 k-values.
+      const int g = lane >> 4, s = lane & 15;
+      const int k = 8 * g + (s >> 2);  // + 32 ks (+ 4 for the second read): neither changes kline_swz
+#pragma unroll
+      for (int i = 0; i < NF; ++i) {
+        const int col = rbase + i * 16 + (s & 3) * 4;
+        o[i] = uint32_t(k * R + (((col >> 3) ^ kline_swz(k)) * 8) + (col & 7));
+      }
+    }
+  }
+  __device__ __forceinline__ bf16x8 read(const uint16_t* slot, int i, int ks) const {
+    if constexpr (KC) {
+      return *reinterpret_cast<const bf16x8*>(slot + o[ks] + i * 16 * DK);
+    } else {
+      typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+      const uint16_t* p = slot + o[i] + ks * 32 * R;
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * R));
+      const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      return __builtin_bit_cast(bf16x8, both);
+    }
+  }
+};
+
+template <int I>
+using Int = std::integral_constant<int, I>;
+
+template <bool AKC, bool BKC, int EPI, int BM_, int BN_, int WGM, int WGN>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArgs g) {
+  constexpr int NW = WGM * WGN;
+  constexpr int TM = BM_ / WGM, TN = BN_ / WGN;  // wavefront tile
+  constexpr int MI = TM / 16, NI = TN / 16;      // 16 x 16 accumulator blocks
+  static_assert(TM % 16 == 0 && TN % 16 == 0 && MI >= 2, "wavefront tile: 16 x 16 blocks, at least two block rows");
+  constexpr int MH = (MI + 1) / 2;               // block rows in the first half of a K-step
+  // rows moved per operand and K tile: whole DMA instructions; a K-strided slot line must hold a
+  // power-of-two number of chunks for its chunk permutation (rows past the tile are never read)
+  constexpr int RA = AKC ? (BM_ + 63) / 64 * 64 : (BM_ <= 128 ? 128 : 256);
+  constexpr int RB = BKC ? (BN_ + 63) / 64 * 64 : (BN_ <= 128 ? 128 : 256);
+  static_assert(BM_ <= 256 && BN_ <= 256, "tile sides up to 256");
+  using OpA = DmaOperand<AKC, RA, NW>;
+  using OpB = DmaOperand<BKC, RB, NW>;
+  constexpr int NA = OpA::NINST, NB = OpB::NINST;
+  static_assert(NA <= 4 && NB <= 4, "the DMA schedule places at most 4 instructions per operand and tile");
+  constexpr int NB0 = (NB + 1) / 2, NA0 = (NA + 1) / 2;
+  constexpr int SLOT = (RA > RB ? RA : RB) * DK;
+  // distinct objects, so that the compiler can tell which DMA a fragment read depends on
+  __shared__ __attribute__((aligned(1024))) uint16_t r0[SLOT];
+  __shared__ __attribute__((aligned(1024))) uint16_t r1[SLOT];
+  __shared__ __attribute__((aligned(1024))) uint16_t r2[SLOT];
+  __shared__ __attribute__((aligned(1024))) uint16_t r3[SLOT];
+  __shared__ __attribute__((aligned(1024))) uint16_t r4[SLOT];
+  auto slot = [&](auto idx) -> uint16_t* {
+    constexpr int i = decltype(idx)::value;
+    if constexpr (i == 0) return r0;
+    else if constexpr (i == 1) return r1;
+    else if constexpr (i == 2) return r2;
+    else if constexpr (i == 3) return r3;
+    else return r4;
+  };
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WGN, wn = wave % WGN;
+
+  // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): give every XCD a
+  // contiguous range of tiles, walked in groups of 8 tile rows so that neighbours share operands.
+  const int nblk = g.tiles_m * g.tiles_n;
+  const int xq = nblk >> 3, xr = nblk & 7, xcd = blockIdx.x & 7;
+  const int L = xcd * xq + min(xcd, xr) + (blockIdx.x >> 3);
+  constexpr int GM = 8;
+  const int width = GM * g.tiles_n;
+  const int first_m = (L / width) * GM;
+  const int gsz = min(g.tiles_m - first_m, GM);
+  const int tile_m = first_m + (L % width) % gsz, tile_n = (L % width) / gsz;
+  const int row0 = tile_m * BM_, col0 = tile_n * BN_;
+
+  f32x4 acc[MI][NI];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NI; ++j) acc[i][j] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+
+  OpA a;
+  OpB b;
+  a.init(g.lda, row0, g.M, wave, lane);
+  b.init(g.ldb, col0, g.N, wave, lane);
+  const int64_t astep = AKC ? DK : DK * g.lda, bstep = BKC ? DK : DK * g.ldb;  // elements per K tile
+  // buffer views of the operands for the DMA (the host checks that each operand spans < 4 GiB)
+  const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(g.A), 0, -1, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(g.B), 0, -1, 0x00020000);
+  const uint32_t astep_b = uint32_t(astep) * 2, bstep_b = uint32_t(bstep) * 2;
+  FragAddr<AKC, RA, MI> fra;
+  FragAddr<BKC, RB, NI> frb;
+  fra.init(wm * TM, lane);
+  frb.init(wn * TN, lane);
+
+#ifdef NTP_GEMM_CLOCK_PROBE
+  const long long probe_c0 = clock64();
+#endif
+  const int nfull = g.K / DK;  // complete K tiles: all go through the ring
+
+  constexpr int RDA = AKC ? 1 : 2, RDB = BKC ? 1 : 2;  // LDS read instructions per fragment
+  bf16x8 fa[2][MH], fb[2][NI];
+  // A fragments of half h (block rows h MH ...) of K-step ks -> fa[h]
+  auto read_a = [&](int h, const uint16_t* pa, int ks) {
+#pragma unroll
+    for (int i = 0; i < (h ? MI - MH : MH); ++i) fa[h][i] = fra.read(pa, h * MH + i, ks);
+  };
+  auto read_b = [&](int buf, const uint16_t* pb, int ks) {
+#pragma unroll
+    for (int j = 0; j < NI; ++j) fb[buf][j] = frb.read(pb, j, ks);
+  };
+  // MFMAs n0 .. n1-1 of half h (row-major over its block rows x NI); operands swapped so that each
+  // lane ends up with 4 consecutive columns of one row
+  auto mfma_range = [&](int h, int bbuf, int n0, int n1) {
+#pragma unroll
+    for (int n = n0; n < n1; ++n) {
+      const int i = n / NI, j = n % NI;
+      acc[h * MH + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[bbuf][j], fa[h][i], acc[h * MH + i][j], 0, 0, 0);
+    }
+  };
+  // One half of a K-step: `reads` (NR LDS instructions) go out under the first MFMA; up to two
+  // DMA instructions sit at one third and two thirds of the MFMAs.
+  auto half = [&](auto hh, auto bb, auto nr, auto&& reads, auto&& dma0, auto&& dma1) {
+    constexpr int h = decltype(hh)::value, bbuf = decltype(bb)::value, NR = decltype(nr)::value;
+    constexpr int nm = (h ? MI - MH : MH) * NI;
+    constexpr int n1 = nm / 3 > 0 ? nm / 3 : 1, n2 = 2 * nm / 3 > n1 ? 2 * nm / 3 : n1;
+    __builtin_amdgcn_sched_barrier(0);
+    reads();
+    mfma_range(h, bbuf, 0, n1);
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, NR, 0);
+    if constexpr (n1 > 1) __builtin_amdgcn_sched_group_barrier(0x008, n1 - 1, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    dma0();
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_range(h, bbuf, n1, n2);
+    __builtin_amdgcn_sched_barrier(0);
+    dma1();
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_range(h, bbuf, n2, nm);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  constexpr int NRA0 = MH * RDA, NRA1 = (MI - MH) * RDA, NRB = NI * RDB;
+
+  // K tile t, P = t mod 5.  Slots: this tile (2P, 2P+1), next tile (2P+2, 2P+3), all mod 5.
+  // DMA instructions of the period that ends at this tile's barrier (it began at the previous one):
+  //   B of tile t+1 -> slot 2P+3 (second part; the first part went out in the previous tile's last
+  //   half), then A of tile t+2 -> slot 2P+4.
+  // After the barrier this tile's slots are free: B of tile t+2 -> slot 2P starts.
+  auto body = [&](auto p, int t) {
+    constexpr int P = decltype(p)::value;
+    uint16_t* const sa = slot(Int<(2 * P) % 5>{});
+    uint16_t* const sb = slot(Int<(2 * P + 1) % 5>{});
+    uint16_t* const nsa = slot(Int<(2 * P + 2) % 5>{});
+    uint16_t* const nsb = slot(Int<(2 * P + 3) % 5>{});
+    uint16_t* const fsa = slot(Int<(2 * P + 4) % 5>{});
+    // Past the last tile the schedule keeps running on the last tile's data (clamped index): the
+    // slots written are free, nobody reads them, and the instruction counts that the waits rely on
+    // stay the same in every tile.
+    const int t1 = min(t + 1, nfull - 1), t2 = min(t + 2, nfull - 1);
+    auto dmaB1 = [&](int i) { if (i < NB) b.dma(rb, bstep_b, t1, nsb, wave, i); };
+    auto dmaA2 = [&](int i) { if (i < NA) a.dma(ra, astep_b, t2, fsa, wave, i); };
+    auto dmaB2 = [&](int i) { if (i < NB) b.dma(rb, bstep_b, t2, sa, wave, i); };
+    // on entry: fa[0] = A half 0 of K-step 0, fb[0] = B of K-step 0
+    half(Int<0>{}, Int<0>{}, Int<NRA1>{}, [&] { read_a(1, sa, 0); }, [&] { dmaB1(NB0); }, [&] { dmaB1(NB0 + 1); });
+    half(Int<1>{}, Int<0>{}, Int<NRA0 + NRB>{}, [&] { read_a(0, sa, 1); read_b(1, sb, 1); }, [&] { dmaA2(0); }, [&] { dmaA2(1); });
+    half(Int<0>{}, Int<1>{}, Int<NRA1>{}, [&] { read_a(1, sa, 1); }, [&] { dmaA2(NA0); }, [&] { dmaA2(NA0 + 1); });
+    // last half, with the barrier inside
+    constexpr int nm = (MI - MH) * NI;
+    constexpr int n1 = nm / 3 > 0 ? nm / 3 : 1, n2 = 2 * nm / 3 > n1 ? 2 * nm / 3 : n1;
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_range(1, 1, 0, n1);
+    __builtin_amdgcn_sched_barrier(0);
+    // this wavefront's share of tile t+1 has landed (its A instructions of tile t+2 may still fly),
+    // and all its fragment reads of tile t are complete
+    __builtin_amdgcn_s_waitcnt(vmcnt_lgkm0_imm(NA));
+    __builtin_amdgcn_s_barrier();
+    read_a(0, nsa, 0);
+    read_b(0, nsb, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    dmaB2(0);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_range(1, 1, n1, n2);
+    __builtin_amdgcn_sched_barrier(0);
+    dmaB2(1);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_range(1, 1, n2, nm);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  if (nfull > 0) {
+    // prologue: tile 0 whole, A of tile 1 whole, first part of B of tile 1
+#pragma unroll
+    for (int i = 0; i < NA; ++i) a.dma(ra, astep_b, 0, r0, wave, i);
+#pragma unroll
+    for (int i = 0; i < NB; ++i) b.dma(rb, bstep_b, 0, r1, wave, i);
+    const int p1 = min(1, nfull - 1);
+#pragma unroll
+    for (int i = 0; i < NA; ++i) a.dma(ra, astep_b, p1, r2, wave, i);
+#pragma unroll
+    for (int i = 0; i < NB0; ++i) b.dma(rb, bstep_b, p1, r3, wave, i);
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(NA + NB0));
+    __builtin_amdgcn_s_barrier();
+    read_a(0, r0, 0);
+    read_b(0, r1, 0);
+  }
+  for (int t = 0; t < nfull; t += 5) {
+    body(Int<0>{}, t);
+    if (t + 1 < nfull) body(Int<1>{}, t + 1);
+    if (t + 2 < nfull) body(Int<2>{}, t + 2);
+    if (t + 3 < nfull) body(Int<3>{}, t + 3);
+    if (t + 4 < nfull) body(Int<4>{}, t + 4);
+  }
+  __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // the clamped DMA instructions of the last tiles
+  // K tail (K % 64 != 0) through registers with element masks, not overlapped
+  if (nfull * DK < g.K) {
+    __syncthreads();
+    a.tail(g.A, astep, nfull, g.K, r0, wave, lane);
+    b.tail(g.B, bstep, nfull, g.K, r1, wave, lane);
+    __syncthreads();
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      read_b(0, r1, ks);
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        read_a(h, r0, ks);
+        mfma_range(h, 0, 0, (h ? MI - MH : MH) * NI);
+      }
+    }
+  }
+#ifdef NTP_GEMM_CLOCK_PROBE
+  if (g.C2 && lane == 0) reinterpret_cast<long long*>(g.C2)[blockIdx.x * 8 + wave] = clock64() - probe_c0;
+#endif
+
+  // lane l of a 16 x 16 block holds row (l & 15) and columns 4 (l >> 4) + {0..3}
+#pragma unroll
+  for (int i = 0; i < MI; ++i) {
+    const int m = row0 + wm * TM + i * 16 + (lane & 15);
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+      const int n0 = col0 + wn * TN + j * 16 + (lane >> 4) * 4;
+      store4<EPI>(g, m, n0, acc[i][j]);
+    }
+  }
+}
+
+}  // namespace ntp_gemm
+
+#endif  // NTP_GEMM_RING_H_

@@ -1,0 +1,18 @@
+// Ring GEMM instantiations, both operands K-strided: the weight gradients (Y_i^T dZ, dP_i^T X,
+// C_i^T dZ, dQKV_i^T X), contraction over tokens, fp32 store or accumulate.
+#include "ntp_gemm_launch.h"
+
+namespace ntp_gemm {
+
+NTP_RING_INSTANTIATE(false, false, ntp::EPI_F32)
+NTP_RING_INSTANTIATE(false, false, ntp::EPI_F32_ACCUM)
+
+int launch_ring_tn(GemmArgs g, int epilogue, int tile, hipStream_t s) {
+  switch (epilogue) {
+    case ntp::EPI_F32: return launch_ring_tile<false, false, ntp::EPI_F32>(g, tile, s);
+    case ntp::EPI_F32_ACCUM: return launch_ring_tile<false, false, ntp::EPI_F32_ACCUM>(g, tile, s);
+    default: return NTP_ERR_UNSUPPORTED;
+  }
+}
+
+}  // namespace ntp_gemm

@@ -152,7 +152,28 @@ struct Extent {
   uintptr_t lo, hi;
 };
 
+// Plain dense copy of 16-byte words: the yardstick that profiler byte counters are scaled by.
+__global__ __launch_bounds__(256) void calibration_copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst,
+                                                               int64_t words) {
+  const int64_t stride = int64_t(gridDim.x) * blockDim.x;
+  for (int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; i < words; i += stride) dst[i] = src[i];
+}
+
 }  // namespace
+
+extern "C" int ntp_calibration_copy(void* dst, const void* src, int64_t bytes, void* stream) {
+  if (!dst || !src || bytes < 0) return NTP_ERR_INVALID_ARG;
+  if (bytes % 16 || reinterpret_cast<uintptr_t>(dst) % 16 || reinterpret_cast<uintptr_t>(src) % 16) return NTP_ERR_ALIGNMENT;
+  if (bytes == 0) return NTP_OK;
+  const int64_t words = bytes / 16;
+  const uint32_t blocks = uint32_t(std::min<int64_t>((words + 255) / 256, 256 * 32));
+  if (ntp::timing_on()) ntp::timing_begin(stream, "calibration_copy", 0.0, 2.0 * double(bytes));
+  hipLaunchKernelGGL(calibration_copy_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const u32x4*>(src), static_cast<u32x4*>(dst), words);
+  const bool ok = hipGetLastError() == hipSuccess;
+  ntp::timing_end(stream);
+  return ok ? NTP_OK : NTP_ERR_LAUNCH;
+}
 
 extern "C" int ntp_reshard_grad(const ntp_tensor_spec_t* spec, int32_t src_tp, int32_t dst_tp,
                                 const void* const* src_shards, const int64_t* src_ld,

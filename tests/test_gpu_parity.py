@@ -173,7 +173,10 @@ def test_attn_halves_can_be_skipped():
 
 
 # ---- every GEMM tile variant, reached through the tuning override, on ragged shapes --------------
-@pytest.mark.parametrize("variant", ["generic", "256x256", "128x256", "256x128", "128x128"])
+RING_TILES = ["256x256", "256x224", "224x256", "256x192", "192x256", "256x128", "128x256", "128x128"]
+
+
+@pytest.mark.parametrize("variant", ["generic"] + RING_TILES)
 def test_mlp_every_tile_variant_ragged(variant, monkeypatch):
     # M = 777 (ragged rows), H = 1096 = 17 * 64 + 8 (K tail of 8), n_r = 1001 (odd: ragged N, K and dW rows)
     _say(f"mlp variant {variant}")
@@ -186,7 +189,7 @@ def test_mlp_every_tile_variant_ragged(variant, monkeypatch):
         assert (raw[name][:, 1001:1008].float().cpu().numpy() == 0).all()
 
 
-@pytest.mark.parametrize("variant", ["256x256", "128x256", "256x128", "128x128"])
+@pytest.mark.parametrize("variant", RING_TILES)
 def test_attn_every_tile_variant(variant, monkeypatch):
     _say(f"attn variant {variant}")
     monkeypatch.setenv("NTP_GEMM_TILE", variant)
@@ -196,7 +199,7 @@ def test_attn_every_tile_variant(variant, monkeypatch):
 
 def test_mlp_tiny_k_and_single_rows_on_fast_tiles(monkeypatch):
     # degenerate extents through the wide-tile kernel: K = 8, M = 1, n_r = 1
-    for variant in ("256x256", "128x128"):
+    for variant in ("256x256", "224x256", "256x192", "128x128"):
         monkeypatch.setenv("NTP_GEMM_TILE", variant)
         for (M, H, n, tp, rank) in [(1, 8, 3, 3, 0), (3, 72, 17, 1, 0), (65, 64, 64, 1, 0)]:
             _say(f"mlp degenerate {variant} M={M} H={H} n={n}")
