@@ -93,6 +93,19 @@ struct DmaOperand {
     __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)dst, 16, off[i], uint32_t(kt) * kstep_bytes, 0, 0);
   }
 
+  // Byte offset (from the start of a K tile of this operand) of the 128-byte line that `lane` touches
+  // when a wavefront pulls quarter `part` (0..3) of the tile's 256 lines toward L2.
+  __device__ __forceinline__ static uint32_t prefetch_offset(int64_t ld, int row0, int lim, int part, int lane) {
+    if constexpr (KC) {
+      const int row = min(row0 + part * 64 + lane, lim - 1);
+      return uint32_t(int64_t(row) * ld * 2);
+    } else {
+      const int line = part * 16 + (lane >> 2);
+      const int cb = min(row0 * 2 + (lane & 3) * 128, (lim * 2 - 4) & ~3);
+      return uint32_t(int64_t(line) * ld * 2 + cb);
+    }
+  }
+
   // K tail tile through registers: everything at k >= K becomes zero
   __device__ __forceinline__ void tail(const uint16_t* base, int64_t kstep, int kt, int K, uint16_t* slot, int wave,
                                        int lane) const {
@@ -177,7 +190,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
   using OpB = DmaOperand<BKC, RB, NW>;
   constexpr int NA = OpA::NINST, NB = OpB::NINST;
   static_assert(NA <= 4 && NB <= 4, "the DMA schedule places at most 4 instructions per operand and tile");
-  constexpr int NB0 = (NB + 1) / 2, NA0 = (NA + 1) / 2;
   constexpr int SLOT = (RA > RB ? RA : RB) * DK;
   // distinct objects, so that the compiler can tell which DMA a fragment read depends on
   __shared__ __attribute__((aligned(1024))) uint16_t r0[SLOT];
@@ -236,6 +248,33 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
 #endif
   const int nfull = g.K / DK;  // complete K tiles: all go through the ring
 
+  // L2 prefetch, PFD tiles ahead.  An A tile is shared by the workgroups of this XCD that have the
+  // same tile_m (about four, with different tile_n), a B tile by those with the same tile_n (eight
+  // tile rows), so they take turns by K tile: wavefronts 0-3 touch the whole A tile when
+  // (kt & 3) == (tile_n & 3), wavefronts 4-7 the whole B tile when (kt & 7) == (tile_m & 7): one
+  // 4-byte load per 128-byte line.  The DMA instructions issued one to two tiles later then find
+  // their lines in L2 instead of waiting for HBM.  Tiles nobody's turn covers are not prefetched.
+  // Every wavefront issues the load in every tile (off turn: all lanes read the operand's first
+  // word), so that the instruction counts the waits rely on stay static, and the loaded value lands
+  // in a register that nothing else ever uses.
+  constexpr int PFD = 4;
+  constexpr bool PF_ON = NW == 8;
+  uint32_t pf_sink = 0;
+  const bool pf_is_a = wave < 4;
+  const int pf_mask = pf_is_a ? 3 : 7, pf_turn = pf_is_a ? (tile_n & 3) : (tile_m & 7);
+  const bool pf_ok = pf_is_a ? (AKC || g.M >= 2) : (BKC || g.N >= 2);
+  const uint32_t pf_voff = pf_is_a ? OpA::prefetch_offset(g.lda, row0, g.M, wave & 3, lane)
+                                   : OpB::prefetch_offset(g.ldb, col0, g.N, wave & 3, lane);
+  const char* const pf_base = reinterpret_cast<const char*>(pf_is_a ? g.A : g.B);
+  const int64_t pf_step = (pf_is_a ? astep : bstep) * 2;  // bytes per K tile
+  auto prefetch = [&](int t) {
+    const int tp = t + PFD;
+    const bool turn = tp < nfull && ((tp & pf_mask) == pf_turn) && pf_ok;
+    const char* src = turn ? pf_base + int64_t(tp) * pf_step : pf_base;
+    const uint32_t voff = turn ? pf_voff : 0u;
+    asm volatile("global_load_dword %0, %1, %2" : "+v"(pf_sink) : "v"(voff), "s"(src) : "memory");
+  };
+
   constexpr int RDA = AKC ? 1 : 2, RDB = BKC ? 1 : 2;  // LDS read instructions per fragment
   bf16x8 fa[2][MH], fb[2][NI];
   // A fragments of half h (block rows h MH ...) of K-step ks -> fa[h]
@@ -280,64 +319,76 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
   };
   constexpr int NRA0 = MH * RDA, NRA1 = (MI - MH) * RDA, NRB = NI * RDB;
 
-  // K tile t, P = t mod 5.  Slots: this tile (2P, 2P+1), next tile (2P+2, 2P+3), all mod 5.
+  // The two operands play different parts in the DMA schedule: A is requested two tiles ahead ("long",
+  // L below), B one tile ahead ("short", S).
+  // K tile t, P = t mod 5, slots mod 5: this tile A 2P, B 2P+1; next tile A 2P+2, B 2P+3; A of tile t+2 2P+4.
   // DMA instructions of the period that ends at this tile's barrier (it began at the previous one):
   //   B of tile t+1 -> slot 2P+3 (second part; the first part went out in the previous tile's last
-  //   half), then A of tile t+2 -> slot 2P+4.
+  //   half), then A of tile t+2 -> slot 2P+4, then the L2 prefetch.
   // After the barrier this tile's slots are free: B of tile t+2 -> slot 2P starts.
+  constexpr int NL = NA, NS = NB;
+  constexpr int NS0 = (NS + 1) / 2, NL0 = (NL + 1) / 2;
+  auto dmaL = [&](int kt, uint16_t* sl, int i) { a.dma(ra, astep_b, kt, sl, wave, i); };
+  auto dmaS = [&](int kt, uint16_t* sl, int i) { b.dma(rb, bstep_b, kt, sl, wave, i); };
   auto body = [&](auto p, int t) {
     constexpr int P = decltype(p)::value;
-    uint16_t* const sa = slot(Int<(2 * P) % 5>{});
-    uint16_t* const sb = slot(Int<(2 * P + 1) % 5>{});
-    uint16_t* const nsa = slot(Int<(2 * P + 2) % 5>{});
-    uint16_t* const nsb = slot(Int<(2 * P + 3) % 5>{});
-    uint16_t* const fsa = slot(Int<(2 * P + 4) % 5>{});
+    uint16_t* const sl = slot(Int<(2 * P) % 5>{});
+    uint16_t* const ss = slot(Int<(2 * P + 1) % 5>{});
+    uint16_t* const nsl = slot(Int<(2 * P + 2) % 5>{});
+    uint16_t* const nss = slot(Int<(2 * P + 3) % 5>{});
+    uint16_t* const fsl = slot(Int<(2 * P + 4) % 5>{});
+    uint16_t* const sa = sl;
+    uint16_t* const sb = ss;
+    uint16_t* const nsa = nsl;
+    uint16_t* const nsb = nss;
     // Past the last tile the schedule keeps running on the last tile's data (clamped index): the
     // slots written are free, nobody reads them, and the instruction counts that the waits rely on
     // stay the same in every tile.
     const int t1 = min(t + 1, nfull - 1), t2 = min(t + 2, nfull - 1);
-    auto dmaB1 = [&](int i) { if (i < NB) b.dma(rb, bstep_b, t1, nsb, wave, i); };
-    auto dmaA2 = [&](int i) { if (i < NA) a.dma(ra, astep_b, t2, fsa, wave, i); };
-    auto dmaB2 = [&](int i) { if (i < NB) b.dma(rb, bstep_b, t2, sa, wave, i); };
+    auto dmaS1 = [&](int i) { if (i < NS) dmaS(t1, nss, i); };
+    auto dmaL2 = [&](int i) { if (i < NL) dmaL(t2, fsl, i); };
+    auto dmaS2 = [&](int i) { if (i < NS) dmaS(t2, sl, i); };
     // on entry: fa[0] = A half 0 of K-step 0, fb[0] = B of K-step 0
-    half(Int<0>{}, Int<0>{}, Int<NRA1>{}, [&] { read_a(1, sa, 0); }, [&] { dmaB1(NB0); }, [&] { dmaB1(NB0 + 1); });
-    half(Int<1>{}, Int<0>{}, Int<NRA0 + NRB>{}, [&] { read_a(0, sa, 1); read_b(1, sb, 1); }, [&] { dmaA2(0); }, [&] { dmaA2(1); });
-    half(Int<0>{}, Int<1>{}, Int<NRA1>{}, [&] { read_a(1, sa, 1); }, [&] { dmaA2(NA0); }, [&] { dmaA2(NA0 + 1); });
+    half(Int<0>{}, Int<0>{}, Int<NRA1>{}, [&] { read_a(1, sa, 0); }, [&] { dmaS1(NS0); }, [&] { dmaS1(NS0 + 1); });
+    half(Int<1>{}, Int<0>{}, Int<NRA0 + NRB>{}, [&] { read_a(0, sa, 1); read_b(1, sb, 1); }, [&] { dmaL2(0); }, [&] { dmaL2(1); });
+    half(Int<0>{}, Int<1>{}, Int<NRA1>{}, [&] { read_a(1, sa, 1); }, [&] { dmaL2(NL0); }, [&] { dmaL2(NL0 + 1); });
+    // the newest vector memory instruction of the period: the barrier's wait below lets it fly on
+    if constexpr (PF_ON) prefetch(t);
     // last half, with the barrier inside
     constexpr int nm = (MI - MH) * NI;
     constexpr int n1 = nm / 3 > 0 ? nm / 3 : 1, n2 = 2 * nm / 3 > n1 ? 2 * nm / 3 : n1;
     __builtin_amdgcn_sched_barrier(0);
     mfma_range(1, 1, 0, n1);
     __builtin_amdgcn_sched_barrier(0);
-    // this wavefront's share of tile t+1 has landed (its A instructions of tile t+2 may still fly),
+    // this wavefront's share of tile t+1 has landed (its L instructions of tile t+2 may still fly),
     // and all its fragment reads of tile t are complete
-    __builtin_amdgcn_s_waitcnt(vmcnt_lgkm0_imm(NA));
+    __builtin_amdgcn_s_waitcnt(vmcnt_lgkm0_imm(NL + (PF_ON ? 1 : 0)));
     __builtin_amdgcn_s_barrier();
     read_a(0, nsa, 0);
     read_b(0, nsb, 0);
     __builtin_amdgcn_sched_barrier(0);
-    dmaB2(0);
+    dmaS2(0);
     __builtin_amdgcn_sched_barrier(0);
     mfma_range(1, 1, n1, n2);
     __builtin_amdgcn_sched_barrier(0);
-    dmaB2(1);
+    dmaS2(1);
     __builtin_amdgcn_sched_barrier(0);
     mfma_range(1, 1, n2, nm);
     __builtin_amdgcn_sched_barrier(0);
   };
 
   if (nfull > 0) {
-    // prologue: tile 0 whole, A of tile 1 whole, first part of B of tile 1
+    // prologue: tile 0 whole, L of tile 1 whole, first part of S of tile 1
 #pragma unroll
-    for (int i = 0; i < NA; ++i) a.dma(ra, astep_b, 0, r0, wave, i);
+    for (int i = 0; i < NL; ++i) dmaL(0, r0, i);
 #pragma unroll
-    for (int i = 0; i < NB; ++i) b.dma(rb, bstep_b, 0, r1, wave, i);
+    for (int i = 0; i < NS; ++i) dmaS(0, r1, i);
     const int p1 = min(1, nfull - 1);
 #pragma unroll
-    for (int i = 0; i < NA; ++i) a.dma(ra, astep_b, p1, r2, wave, i);
+    for (int i = 0; i < NL; ++i) dmaL(p1, r2, i);
 #pragma unroll
-    for (int i = 0; i < NB0; ++i) b.dma(rb, bstep_b, p1, r3, wave, i);
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(NA + NB0));
+    for (int i = 0; i < NS0; ++i) dmaS(p1, r3, i);
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(NL + NS0));
     __builtin_amdgcn_s_barrier();
     read_a(0, r0, 0);
     read_b(0, r1, 0);
@@ -370,6 +421,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
   if (g.C2 && lane == 0) reinterpret_cast<long long*>(g.C2)[blockIdx.x * 8 + wave] = clock64() - probe_c0;
 #endif
 
+  asm volatile("" : "+v"(pf_sink));  // the prefetch register stays reserved up to here
   // lane l of a 16 x 16 block holds row (l & 15) and columns 4 (l >> 4) + {0..3}
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
