@@ -13,6 +13,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdlib>
 #include <vector>
 
 #include "ntp_internal.h"
@@ -148,9 +149,102 @@ __global__ __launch_bounds__(kThreads) void reshard_copy_kernel(const CopyBatch 
   }
 }
 
+
+// ---- column-partitioned tensors of 4-byte elements: destination-major gather ------------------
+// A job is a block of destination columns of one destination shard together with the pieces
+// (sub-shards) that fill it, each from another source shard.  A workgroup takes a block of
+// destination rows and copies all pieces of those rows, so destination rows are written whole and
+// in order.  Within a piece the 16-byte chunks are aligned on the DESTINATION address (aligned
+// non-temporal stores; the loads tolerate any 4-byte alignment); what lies before the first and
+// after the last aligned chunk of a row piece is copied word by word.
+constexpr int kMaxPieces = 8;
+constexpr int kMaxJobs = 14;  // the argument block stays below 4 KiB
+
+struct Piece {
+  const char* src;      // byte that goes to column `begin` of destination row 0 of the job
+  int64_t src_stride;   // bytes between source rows
+  uint32_t begin, end;  // byte range within the job's destination row
+};
+struct GatherJob {
+  char* dst;            // first byte of the job's column block in destination row 0
+  int64_t dst_stride;
+  uint32_t rows, npieces;
+  Piece piece[kMaxPieces];
+};
+struct GatherBatch {
+  GatherJob job[kMaxJobs];  // all with the same number of rows
+  int32_t njobs;
+  uint32_t rows_per_block;
+};
+
+// One piece of `nrows` destination rows, n bytes per row.  HBM is written in 64-byte units, and a
+// unit written in two parts costs two transactions, so in every row the copy is cut at the 64-byte
+// boundaries of the DESTINATION address: `head` bytes (a multiple of 4 below 64) come before the
+// first boundary.  Pass 1 moves the whole units of all rows as one flat list of 16-byte chunks (four
+// neighbouring lanes fill one unit with one aligned non-temporal store instruction; the loads take
+// any 4-byte alignment); pass 2 moves what is left at the two ends of each row word by word, again as
+// one flat list.  Offsets inside the block fit in 32 bits (the host sees to that).
+__device__ __forceinline__ void piece_copy_aligned(const char* __restrict__ s, uint32_t ss, char* __restrict__ d, uint32_t ds,
+                                                   uint32_t nrows, uint32_t n, uint32_t tid) {
+  const uint32_t dlow = uint32_t(reinterpret_cast<uintptr_t>(d)) & 63u;
+  const uint32_t cpr = (n >> 6) << 2;  // chunks of the most whole units a row can hold
+  if (cpr > 0) {
+    const uint32_t magic = div_magic(cpr), nitems = nrows * cpr;
+    for (uint32_t base = tid; base < nitems; base += kThreads * kUnroll) {
+      u32x4 v[kUnroll];
+      uint32_t doff[kUnroll];
+      bool ok[kUnroll];
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        const uint32_t item = base + u * kThreads;
+        const uint32_t row = nrows == 1 ? 0u : fast_div(item, cpr, magic);
+        const uint32_t k = item - row * cpr;
+        const uint32_t drow = row * ds;
+        const uint32_t head = (0u - (dlow + drow)) & 63u;
+        const uint32_t st = head + (k << 4);
+        ok[u] = item < nitems && head + ((k | 3u) << 4) + 16u <= n;  // the whole unit of this chunk fits
+        doff[u] = drow + st;
+        if (ok[u]) v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_a4*>(s + (row * ss + st)));
+      }
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u)
+        if (ok[u]) __builtin_nontemporal_store(v[u], reinterpret_cast<u32x4*>(d + doff[u]));
+    }
+  }
+  // the ends, one word per item: item = 32 row + 16 (0: before the first boundary, 1: after the last whole unit) + word
+  for (uint32_t item = tid; item < 32 * nrows; item += kThreads) {
+    const uint32_t row = item >> 5, drow = row * ds, w = item & 15u;
+    const uint32_t head = min(n, (0u - (dlow + drow)) & 63u);
+    const uint32_t st = (item & 16u) ? head + ((n - head) & ~63u) : 0u;
+    const uint32_t en = (item & 16u) ? n : head;
+    if (st + 4u * w < en)
+      *reinterpret_cast<uint32_t*>(d + (drow + st + 4u * w)) = *reinterpret_cast<const uint32_t*>(s + (row * ss + st + 4u * w));
+  }
+}
+
+// Workgroup b takes row block b / njobs of job b % njobs: the workgroups that run at the same time
+// cover the same rows of neighbouring destination shards, so the two destination shards that split
+// a source row read it close together in time (its lines are fetched from HBM once).
+__global__ __launch_bounds__(kThreads) void reshard_gather_kernel(const GatherBatch batch) {
+  const uint32_t rbi = blockIdx.x / uint32_t(batch.njobs), ji = blockIdx.x - rbi * uint32_t(batch.njobs);
+  const GatherJob& job = batch.job[ji];
+  const int64_t r0 = int64_t(rbi) * batch.rows_per_block;
+  const uint32_t nrows = uint32_t(std::min<int64_t>(int64_t(job.rows) - r0, batch.rows_per_block));
+  for (uint32_t p = 0; p < job.npieces; ++p) {
+    const Piece& pc = job.piece[p];
+    piece_copy_aligned(pc.src + r0 * pc.src_stride, uint32_t(pc.src_stride), job.dst + r0 * job.dst_stride + pc.begin,
+                       uint32_t(job.dst_stride), nrows, pc.end - pc.begin, threadIdx.x);
+  }
+}
+
 struct Extent {
   uintptr_t lo, hi;
 };
+
+int64_t gather_block_bytes() {
+  if (const char* e = getenv("NTP_RESHARD_BLOCK")) return std::max<int64_t>(1024, atoll(e));
+  return kBlockBytes;
+}
 
 // Plain dense copy of 16-byte words: the yardstick that profiler byte counters are scaled by.
 __global__ __launch_bounds__(256) void calibration_copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst,
@@ -212,6 +306,70 @@ extern "C" int ntp_reshard_grad(const ntp_tensor_spec_t* spec, int32_t src_tp, i
     for (const Extent& b : de)
       if (a.hi > a.lo && b.hi > b.lo && a.lo < b.hi && b.lo < a.hi) return NTP_ERR_INVALID_ARG;
 
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+
+  if (!by_rows && esz == 4) {
+    // destination-major gather: consecutive sub-shards of one destination shard form a job
+    std::vector<GatherJob> jobs;
+    int32_t cur_dst = -1;
+    int64_t cur_end = 0;  // destination column (bytes) where the current job ends
+    int64_t job_col0 = 0;
+    for (const ntp_segment_t& g : segs) {
+      const char* sp = static_cast<const char*>(src_shards[g.src_rank]);
+      char* dp = static_cast<char*>(dst_shards[g.dst_rank]);
+      const int64_t c0 = g.dst_unit * spec->unit * esz, c1 = c0 + g.units * spec->unit * esz;
+      if (!sp || !dp || c1 == c0 || spec->rows == 0) continue;  // not on this GPU, or empty
+      if (spec->rows > 0xffffffffll || c1 - c0 > 0x7fffffffll) return NTP_ERR_UNSUPPORTED;
+      const bool fresh = jobs.empty() || g.dst_rank != cur_dst || c0 != cur_end || jobs.back().npieces == kMaxPieces ||
+                         c1 - job_col0 > 0x7fffffffll;
+      if (fresh) {
+        GatherJob j{};
+        j.dst = dp + c0;
+        j.dst_stride = dst_ld[g.dst_rank] * esz;
+        j.rows = uint32_t(spec->rows);
+        jobs.push_back(j);
+        cur_dst = g.dst_rank;
+        job_col0 = c0;
+      }
+      GatherJob& j = jobs.back();
+      Piece& pc = j.piece[j.npieces++];
+      pc.src = sp + g.src_unit * spec->unit * esz;
+      pc.src_stride = src_ld[g.src_rank] * esz;
+      pc.begin = uint32_t(c0 - job_col0);
+      pc.end = uint32_t(c1 - job_col0);
+      cur_end = c1;
+    }
+    for (size_t base = 0; base < jobs.size(); base += kMaxJobs) {
+      GatherBatch batch{};
+      batch.njobs = int32_t(std::min<size_t>(kMaxJobs, jobs.size() - base));
+      // rows per workgroup: about kBlockBytes of the widest job, and row offsets inside a block that
+      // fit in 32 bits
+      int64_t rpb = spec->rows;
+      double bytes = 0.0;
+      for (int i = 0; i < batch.njobs; ++i) {
+        const GatherJob& j = jobs[base + i];
+        const int64_t row_bytes = j.piece[j.npieces - 1].end;
+        int64_t stride = j.dst_stride;
+        for (uint32_t p = 0; p < j.npieces; ++p) stride = std::max(stride, j.piece[p].src_stride);
+        rpb = std::min(rpb, std::max<int64_t>(1, gather_block_bytes() / row_bytes));
+        rpb = std::min(rpb, std::max<int64_t>(1, (int64_t(1) << 31) / std::max<int64_t>(stride, 1)));
+        bytes += 2.0 * double(j.rows) * double(row_bytes);
+        batch.job[i] = j;
+      }
+      if (rpb > 1 && jobs[base].dst_stride > (int64_t(1) << 31)) return NTP_ERR_UNSUPPORTED;
+      batch.rows_per_block = uint32_t(rpb);
+      const uint64_t blocks = uint64_t((spec->rows + rpb - 1) / rpb) * uint64_t(batch.njobs);
+      if (blocks > 0x7fffffffull) return NTP_ERR_UNSUPPORTED;
+      if (blocks == 0) continue;
+      if (ntp::timing_on()) ntp::timing_begin(stream, "reshard_gather", 0.0, bytes);
+      hipLaunchKernelGGL(reshard_gather_kernel, dim3(uint32_t(blocks)), dim3(kThreads), 0, hs, batch);
+      const bool ok = hipGetLastError() == hipSuccess;
+      ntp::timing_end(stream);
+      if (!ok) return NTP_ERR_LAUNCH;
+    }
+    return NTP_OK;
+  }
+
   // segments -> 2-D copies
   std::vector<CopySeg> copies;
   for (const ntp_segment_t& g : segs) {
@@ -257,7 +415,6 @@ extern "C" int ntp_reshard_grad(const ntp_tensor_spec_t* spec, int32_t src_tp, i
     }
   }
 
-  hipStream_t hs = static_cast<hipStream_t>(stream);
   for (size_t base = 0; base < copies.size(); base += kMaxSegs) {
     CopyBatch batch{};
     batch.nseg = int32_t(std::min<size_t>(kMaxSegs, copies.size() - base));
