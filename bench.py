@@ -240,12 +240,12 @@ def main():
                     frac=achieved / BF16_MFMA_PEAK_TFLOPS, traffic=traffic, launches_per_step=dom["launches"] / args.steps,
                     avg_launch_ms=dom["ms"] / dom["launches"], flops_per_launch=dom["flops"] / dom["launches"])
     gemm_ms = sum(v["ms"] for v in gemms.values()) / args.steps
-    rs = table.get("reshard_copy")
+    rs = [v for k, v in table.items() if k.startswith("reshard_")]
     parts = dict(gemm_ms_per_step=gemm_ms, gemm_TFLOPs=s["gemm_flops"] / gemm_ms / 1e9,
                  gemm_frac_of_peak=s["gemm_flops"] / gemm_ms / 1e9 / BF16_MFMA_PEAK_TFLOPS)
     if rs:
-        rms = rs["ms"] / args.steps
-        parts.update(reshard_ms_per_step=rms, reshard_GBps=rs["bytes"] / args.steps / rms / 1e6)
+        rms = sum(v["ms"] for v in rs) / args.steps
+        parts.update(reshard_ms_per_step=rms, reshard_GBps=sum(v["bytes"] for v in rs) / args.steps / rms / 1e6)
     kernels = {k: dict(avg_ms=v["ms"] / v["launches"], launches_per_step=v["launches"] / args.steps,
                        TFLOPs=(v["flops"] / v["ms"] / 1e9) if v["flops"] else None,
                        GBps=(v["bytes"] / v["ms"] / 1e6) if v["bytes"] else None) for k, v in table.items()}

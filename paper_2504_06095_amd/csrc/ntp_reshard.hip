@@ -237,6 +237,45 @@ __global__ __launch_bounds__(kThreads) void reshard_gather_kernel(const GatherBa
   }
 }
 
+// ---- dense ranges (row-partitioned tensors whose shards are dense): plain streaming copy --------
+constexpr int kMaxRanges = 100;  // 100 x 32 B + header < 4 KiB of kernel arguments
+constexpr int64_t kDenseBlock = 32768;  // bytes per workgroup
+struct DenseRange {
+  const char* src;
+  char* dst;
+  int64_t bytes;         // multiple of 16; both pointers 16-byte aligned
+  uint32_t first_block;
+  uint32_t pad_;
+};
+struct DenseBatch {
+  DenseRange r[kMaxRanges];
+  int32_t n;
+};
+
+__global__ __launch_bounds__(kThreads) void reshard_dense_kernel(const DenseBatch batch) {
+  const uint32_t b = blockIdx.x;
+  int lo = 0, hi = batch.n - 1;  // last range whose first block is <= b
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (batch.r[mid].first_block <= b) lo = mid;
+    else hi = mid - 1;
+  }
+  const DenseRange& rg = batch.r[lo];
+  const int64_t off = int64_t(b - rg.first_block) * kDenseBlock;
+  const uint32_t n16 = uint32_t(std::min<int64_t>(kDenseBlock, rg.bytes - off) >> 4);
+  const u32x4* s = reinterpret_cast<const u32x4*>(rg.src + off);
+  u32x4* d = reinterpret_cast<u32x4*>(rg.dst + off);
+  for (uint32_t base = threadIdx.x; base < n16; base += kThreads * kUnroll) {
+    u32x4 v[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u)
+      if (base + u * kThreads < n16) v[u] = __builtin_nontemporal_load(s + base + u * kThreads);
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u)
+      if (base + u * kThreads < n16) __builtin_nontemporal_store(v[u], d + base + u * kThreads);
+  }
+}
+
 struct Extent {
   uintptr_t lo, hi;
 };
@@ -370,8 +409,9 @@ extern "C" int ntp_reshard_grad(const ntp_tensor_spec_t* spec, int32_t src_tp, i
     return NTP_OK;
   }
 
-  // segments -> 2-D copies
+  // segments -> dense ranges and 2-D copies
   std::vector<CopySeg> copies;
+  std::vector<DenseRange> ranges;
   for (const ntp_segment_t& g : segs) {
     const char* sp = static_cast<const char*>(src_shards[g.src_rank]);
     char* dp = static_cast<char*>(dst_shards[g.dst_rank]);
@@ -392,29 +432,55 @@ extern "C" int ntp_reshard_grad(const ntp_tensor_spec_t* spec, int32_t src_tp, i
     c.src_stride = sld;
     c.dst_stride = dld;
     if (c.rows == 0 || c.row_bytes == 0) continue;
-    if (c.src_stride == c.row_bytes && c.dst_stride == c.row_bytes && c.rows > 1) {
-      // dense on both sides: one long run, recut into 4 KiB rows (plus a remainder)
+    if (c.src_stride == c.row_bytes && c.dst_stride == c.row_bytes) {
+      // dense on both sides: one long run.  The 16-byte aligned middle goes to the streaming kernel,
+      // what is left (misaligned pointers, a few bytes at the end) to the general one.
       const int64_t total = c.rows * c.row_bytes;
-      const int64_t full = total / 4096;
-      if (full > 0) {
+      const bool al = ((reinterpret_cast<uintptr_t>(c.src) | reinterpret_cast<uintptr_t>(c.dst)) & 15) == 0;
+      const int64_t body = al ? total & ~int64_t(15) : 0;
+      if (body > 0) ranges.push_back(DenseRange{c.src, c.dst, body, 0, 0});
+      if (total > body) {
         CopySeg d = c;
-        d.rows = full;
-        d.row_bytes = d.src_stride = d.dst_stride = 4096;
-        copies.push_back(d);
-      }
-      if (total % 4096) {
-        CopySeg d = c;
-        d.src += full * 4096;
-        d.dst += full * 4096;
+        d.src += body;
+        d.dst += body;
         d.rows = 1;
-        d.row_bytes = total % 4096;
-        copies.push_back(d);
+        d.row_bytes = d.src_stride = d.dst_stride = total - body;
+        if (d.row_bytes > (int64_t(1) << 20)) {  // long misaligned run: recut into 4 KiB rows
+          const int64_t full = d.row_bytes / 4096;
+          CopySeg e = d;
+          e.rows = full;
+          e.row_bytes = e.src_stride = e.dst_stride = 4096;
+          copies.push_back(e);
+          d.src += full * 4096;
+          d.dst += full * 4096;
+          d.row_bytes = d.src_stride = d.dst_stride = d.row_bytes - full * 4096;
+        }
+        if (d.row_bytes > 0) copies.push_back(d);
       }
     } else {
       copies.push_back(c);
     }
   }
 
+  for (size_t base = 0; base < ranges.size(); base += kMaxRanges) {
+    DenseBatch batch{};
+    batch.n = int32_t(std::min<size_t>(kMaxRanges, ranges.size() - base));
+    uint64_t blocks = 0;
+    double bytes = 0.0;
+    for (int i = 0; i < batch.n; ++i) {
+      DenseRange r = ranges[base + i];
+      r.first_block = uint32_t(blocks);
+      blocks += uint64_t((r.bytes + kDenseBlock - 1) / kDenseBlock);
+      if (blocks > 0x7fffffffull) return NTP_ERR_UNSUPPORTED;
+      bytes += 2.0 * double(r.bytes);
+      batch.r[i] = r;
+    }
+    if (ntp::timing_on()) ntp::timing_begin(stream, "reshard_dense", 0.0, bytes);
+    hipLaunchKernelGGL(reshard_dense_kernel, dim3(uint32_t(blocks)), dim3(kThreads), 0, hs, batch);
+    const bool ok = hipGetLastError() == hipSuccess;
+    ntp::timing_end(stream);
+    if (!ok) return NTP_ERR_LAUNCH;
+  }
   for (size_t base = 0; base < copies.size(); base += kMaxSegs) {
     CopyBatch batch{};
     batch.nseg = int32_t(std::min<size_t>(kMaxSegs, copies.size() - base));
