@@ -237,9 +237,83 @@ __global__ __launch_bounds__(kThreads) void reshard_gather_kernel(const GatherBa
   }
 }
 
+// Dense destination shards: the destination is treated as ONE flat byte range, cut into blocks at
+// 64-byte boundaries, and every 16-byte chunk of it is stored whole and aligned no matter where rows
+// and pieces begin (odd shard widths).  A chunk that lies inside one piece of one row is read with
+// one (unaligned) 16-byte load; a chunk that straddles a row end or a piece boundary is assembled
+// from four single words.  Needs: destination 64-byte aligned and dense, (kFlatBlock + W) * W <= 2^32
+// for the row width W in bytes (exact multiply-high division), source offsets inside a block < 2^32.
+constexpr uint32_t kFlatBlockMax = 65536;
+
+__global__ __launch_bounds__(kThreads) void reshard_flat_kernel(const GatherBatch batch) {
+  const uint32_t bi = blockIdx.x / uint32_t(batch.njobs), ji = blockIdx.x - bi * uint32_t(batch.njobs);
+  const GatherJob& job = batch.job[ji];
+  const uint32_t np = job.npieces;
+  const uint32_t W = job.piece[np - 1].end;
+  const int64_t T = int64_t(job.rows) * W;
+  const uint32_t kFlatBlock = batch.rows_per_block;  // bytes per block here
+  const int64_t b0 = int64_t(bi) * kFlatBlock;
+  if (b0 >= T) return;
+  const uint32_t nb = uint32_t(std::min<int64_t>(kFlatBlock, T - b0));
+  const int64_t row0 = b0 / W;
+  const uint32_t c0 = uint32_t(b0 - row0 * W);
+  const uint32_t magic = div_magic(W);
+  char* __restrict__ d = job.dst + b0;
+  const uint32_t nchunks = (nb + 15) >> 4;
+  for (uint32_t base = threadIdx.x; base < nchunks; base += kThreads * kUnroll) {
+    u32x4 v[kUnroll];
+    uint32_t len[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const uint32_t k = base + u * kThreads;
+      len[u] = k < nchunks ? min(16u, nb - (k << 4)) : 0u;
+      const uint32_t x = c0 + (k << 4);
+      const uint32_t rr = fast_div(x, W, magic);
+      const uint32_t col = x - rr * W;
+      bool got = len[u] == 0;
+      if (len[u] == 16 && col + 16u <= W) {
+        for (uint32_t p = 0; p < np; ++p) {
+          const Piece& pc = job.piece[p];
+          if (col >= pc.begin && col + 16u <= pc.end) {
+            const char* sb = pc.src + row0 * pc.src_stride;
+            v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_a4*>(sb + (rr * uint32_t(pc.src_stride) + (col - pc.begin))));
+            got = true;
+          }
+        }
+      }
+      if (!got) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          if (uint32_t(w) * 4 >= len[u]) continue;
+          const bool wrap = col + 4u * w >= W;
+          const uint32_t rw = rr + (wrap ? 1u : 0u), cw = col + 4u * w - (wrap ? W : 0u);
+          for (uint32_t p = 0; p < np; ++p) {
+            const Piece& pc = job.piece[p];
+            if (cw >= pc.begin && cw < pc.end) {
+              const char* sb = pc.src + row0 * pc.src_stride;
+              v[u][w] = *reinterpret_cast<const uint32_t*>(sb + (rw * uint32_t(pc.src_stride) + (cw - pc.begin)));
+            }
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      char* dp = d + ((base + u * kThreads) << 4);
+      if (len[u] == 16) {
+        __builtin_nontemporal_store(v[u], reinterpret_cast<u32x4*>(dp));
+      } else {
+#pragma unroll
+        for (int w = 0; w < 3; ++w)
+          if (uint32_t(w) * 4 < len[u]) reinterpret_cast<uint32_t*>(dp)[w] = v[u][w];
+      }
+    }
+  }
+}
+
 // ---- dense ranges (row-partitioned tensors whose shards are dense): plain streaming copy --------
 constexpr int kMaxRanges = 100;  // 100 x 32 B + header < 4 KiB of kernel arguments
-constexpr int64_t kDenseBlock = 32768;  // bytes per workgroup
+constexpr int64_t kDenseBlock = 16384;  // bytes per workgroup
 struct DenseRange {
   const char* src;
   char* dst;
@@ -378,6 +452,41 @@ extern "C" int ntp_reshard_grad(const ntp_tensor_spec_t* spec, int32_t src_tp, i
       pc.end = uint32_t(c1 - job_col0);
       cur_end = c1;
     }
+    // jobs whose destination is a dense, 64-byte aligned shard go to the flat kernel
+    const int64_t kFlatBlock = getenv("NTP_RESHARD_FLAT_BLOCK") ? std::min<int64_t>(kFlatBlockMax, std::max<int64_t>(1024, atoll(getenv("NTP_RESHARD_FLAT_BLOCK")) & ~63ll)) : 16384;
+    std::vector<GatherJob> flat, rowwise;
+    for (const GatherJob& j : jobs) {
+      const int64_t W = j.piece[j.npieces - 1].end;
+      int64_t smax = 0;
+      for (uint32_t p = 0; p < j.npieces; ++p) smax = std::max(smax, j.piece[p].src_stride);
+      const bool ok = j.dst_stride == W && (reinterpret_cast<uintptr_t>(j.dst) & 63) == 0 &&
+                      (int64_t(kFlatBlock) + W) * W <= (int64_t(1) << 32) &&
+                      smax * (int64_t(kFlatBlock) / W + 2) < (int64_t(1) << 32) && !getenv("NTP_RESHARD_NO_FLAT");
+      (ok ? flat : rowwise).push_back(j);
+    }
+    for (size_t base = 0; base < flat.size(); base += kMaxJobs) {
+      GatherBatch batch{};
+      batch.njobs = int32_t(std::min<size_t>(kMaxJobs, flat.size() - base));
+      int64_t nblk = 0;
+      double bytes = 0.0;
+      for (int i = 0; i < batch.njobs; ++i) {
+        const GatherJob& j = flat[base + i];
+        const int64_t total = int64_t(j.rows) * j.piece[j.npieces - 1].end;
+        nblk = std::max(nblk, (total + kFlatBlock - 1) / kFlatBlock);
+        bytes += 2.0 * double(total);
+        batch.job[i] = j;
+      }
+      batch.rows_per_block = uint32_t(kFlatBlock);
+      const uint64_t blocks = uint64_t(nblk) * uint64_t(batch.njobs);
+      if (blocks > 0x7fffffffull) return NTP_ERR_UNSUPPORTED;
+      if (blocks == 0) continue;
+      if (ntp::timing_on()) ntp::timing_begin(stream, "reshard_flat", 0.0, bytes);
+      hipLaunchKernelGGL(reshard_flat_kernel, dim3(uint32_t(blocks)), dim3(kThreads), 0, hs, batch);
+      const bool ok = hipGetLastError() == hipSuccess;
+      ntp::timing_end(stream);
+      if (!ok) return NTP_ERR_LAUNCH;
+    }
+    jobs.swap(rowwise);
     for (size_t base = 0; base < jobs.size(); base += kMaxJobs) {
       GatherBatch batch{};
       batch.njobs = int32_t(std::min<size_t>(kMaxJobs, jobs.size() - base));
