@@ -285,8 +285,7 @@ __global__ __launch_bounds__(kThreads) void reshard_flat_kernel(const GatherBatc
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
           if (uint32_t(w) * 4 >= len[u]) continue;
-          const bool wrap = col + 4u * w >= W;
-          const uint32_t rw = rr + (wrap ? 1u : 0u), cw = col + 4u * w - (wrap ? W : 0u);
+          const uint32_t rw = fast_div(x + 4u * w, W, magic), cw = x + 4u * w - rw * W;  // rows may be shorter than a chunk
           for (uint32_t p = 0; p < np; ++p) {
             const Piece& pc = job.piece[p];
             if (cw >= pc.begin && cw < pc.end) {
@@ -460,7 +459,7 @@ extern "C" int ntp_reshard_grad(const ntp_tensor_spec_t* spec, int32_t src_tp, i
       int64_t smax = 0;
       for (uint32_t p = 0; p < j.npieces; ++p) smax = std::max(smax, j.piece[p].src_stride);
       const bool ok = j.dst_stride == W && (reinterpret_cast<uintptr_t>(j.dst) & 63) == 0 &&
-                      (int64_t(kFlatBlock) + W) * W <= (int64_t(1) << 32) &&
+                      (int64_t(kFlatBlock) + W + 16) * W <= (int64_t(1) << 32) &&
                       smax * (int64_t(kFlatBlock) / W + 2) < (int64_t(1) << 32) && !getenv("NTP_RESHARD_NO_FLAT");
       (ok ? flat : rowwise).push_back(j);
     }

@@ -69,6 +69,11 @@ CASES = [
     (1, 100000, 1, 1, 3, 4, 0, 0, 0),      # a single long row
     (20000, 1, 0, 1, 4, 3, 0, 0, 0),       # a single column
     (256, 256, 1, 1, 4, 4, 0, 0, 0),       # same degree: plain copy
+    (3, 7, 1, 1, 2, 3, 0, 0, 0),           # dense destinations smaller than a 16-byte chunk per row
+    (1000, 5, 1, 1, 2, 3, 0, 0, 0),        # one- and two-element rows: a chunk spans several rows
+    (17, 1001, 1, 1, 3, 2, 0, 0, 0),       # odd widths, total bytes not a multiple of 16
+    (257, 2250, 1, 1, 3, 2, 0, 0, 0),      # several blocks of the flat destination kernel, pieces split mid-chunk
+    (4100, 1500, 1, 1, 2, 2, 0, 0, 0),     # same degree on columns, many blocks
 ]
 
 
