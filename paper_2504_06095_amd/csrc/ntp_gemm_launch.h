@@ -34,7 +34,11 @@ int launch_ring_one(GemmArgs g, hipStream_t s) {
   g.tiles_m = (g.M + BM_ - 1) / BM_;
   g.tiles_n = (g.n_store + BN_ - 1) / BN_;
   if (int64_t(g.tiles_m) * g.tiles_n > 0x7fffffff) return NTP_ERR_UNSUPPORTED;
-  const dim3 grid(uint32_t(g.tiles_m) * uint32_t(g.tiles_n)), block(64 * WGM * WGN);
+  // persistent workgroups: one per compute unit (two for the 4-wavefront tile, whose LDS ring is half
+  // as large), each walking over its share of the output tiles
+  constexpr uint32_t kResident = 256 * (WGM * WGN == 4 ? 2 : 1);
+  const uint32_t nblk = uint32_t(g.tiles_m) * uint32_t(g.tiles_n);
+  const dim3 grid(nblk < kResident ? nblk : kResident), block(64 * WGM * WGN);
   hipLaunchKernelGGL((gemm_ring_kernel<AKC, BKC, EPI, BM_, BN_, WGM, WGN>), grid, block, 0, s, g);
   return hipGetLastError() == hipSuccess ? NTP_OK : NTP_ERR_LAUNCH;
 }

@@ -211,28 +211,30 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WGN, wn = wave % WGN;
 
-  // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): give every XCD a
-  // contiguous range of tiles, walked in groups of 8 tile rows so that neighbours share operands.
+  // The kernel is persistent: workgroup w works on virtual blocks w, w + gridDim, ...  Workgroups are
+  // dealt round-robin to the 8 XCDs (each with its own L2), so virtual block v belongs to XCD v & 7
+  // (the grid is a multiple of 8 whenever a workgroup gets more than one block); every XCD walks a
+  // contiguous range of tiles in groups of 8 tile rows, so that its workgroups share operands.
   const int nblk = g.tiles_m * g.tiles_n;
-  const int xq = nblk >> 3, xr = nblk & 7, xcd = blockIdx.x & 7;
-  const int L = xcd * xq + min(xcd, xr) + (blockIdx.x >> 3);
-  constexpr int GM = 8;
-  const int width = GM * g.tiles_n;
-  const int first_m = (L / width) * GM;
-  const int gsz = min(g.tiles_m - first_m, GM);
-  const int tile_m = first_m + (L % width) % gsz, tile_n = (L % width) / gsz;
-  const int row0 = tile_m * BM_, col0 = tile_n * BN_;
+  int tile_m, tile_n, row0, col0;
+  auto place = [&](int v) {
+    const int xq = nblk >> 3, xr = nblk & 7, xcd = v & 7;
+    const int L = xcd * xq + min(xcd, xr) + (v >> 3);
+    constexpr int GM = 8;
+    const int width = GM * g.tiles_n;
+    const int first_m = (L / width) * GM;
+    const int gsz = min(g.tiles_m - first_m, GM);
+    tile_m = first_m + (L % width) % gsz;
+    tile_n = (L % width) / gsz;
+    row0 = tile_m * BM_;
+    col0 = tile_n * BN_;
+  };
+  int vblk = blockIdx.x;
+  place(vblk);
 
   f32x4 acc[MI][NI];
-#pragma unroll
-  for (int i = 0; i < MI; ++i)
-#pragma unroll
-    for (int j = 0; j < NI; ++j) acc[i][j] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-
   OpA a;
   OpB b;
-  a.init(g.lda, row0, g.M, wave, lane);
-  b.init(g.ldb, col0, g.N, wave, lane);
   const int64_t astep = AKC ? DK : DK * g.lda, bstep = BKC ? DK : DK * g.ldb;  // elements per K tile
   // buffer views of the operands for the DMA (the host checks that each operand spans < 4 GiB)
   const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(g.A), 0, -1, 0x00020000);
@@ -261,12 +263,21 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
   constexpr bool PF_ON = NW == 8;
   uint32_t pf_sink = 0;
   const bool pf_is_a = wave < 4;
-  const int pf_mask = pf_is_a ? 3 : 7, pf_turn = pf_is_a ? (tile_n & 3) : (tile_m & 7);
+  const int pf_mask = pf_is_a ? 3 : 7;
   const bool pf_ok = pf_is_a ? (AKC || g.M >= 2) : (BKC || g.N >= 2);
-  const uint32_t pf_voff = pf_is_a ? OpA::prefetch_offset(g.lda, row0, g.M, wave & 3, lane)
-                                   : OpB::prefetch_offset(g.ldb, col0, g.N, wave & 3, lane);
   const char* const pf_base = reinterpret_cast<const char*>(pf_is_a ? g.A : g.B);
   const int64_t pf_step = (pf_is_a ? astep : bstep) * 2;  // bytes per K tile
+  int pf_turn = 0;
+  uint32_t pf_voff = 0;
+  // per output tile: DMA offsets and prefetch parameters
+  auto setup_tile = [&] {
+    a.init(g.lda, row0, g.M, wave, lane);
+    b.init(g.ldb, col0, g.N, wave, lane);
+    pf_turn = pf_is_a ? (tile_n & 3) : (tile_m & 7);
+    pf_voff = pf_is_a ? OpA::prefetch_offset(g.lda, row0, g.M, wave & 3, lane)
+                      : OpB::prefetch_offset(g.ldb, col0, g.N, wave & 3, lane);
+  };
+  setup_tile();
   auto prefetch = [&](int t) {
     const int tp = t + PFD;
     const bool turn = tp < nfull && ((tp & pf_mask) == pf_turn) && pf_ok;
@@ -377,61 +388,96 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
     __builtin_amdgcn_sched_barrier(0);
   };
 
-  if (nfull > 0) {
-    // prologue: tile 0 whole, L of tile 1 whole, first part of S of tile 1
+  // first DMA instructions of an output tile: K tile 0 whole, A of K tile 1 whole, first part of B of K tile 1
+  auto first_dma = [&] {
+    if (nfull > 0) {
 #pragma unroll
-    for (int i = 0; i < NL; ++i) dmaL(0, r0, i);
+      for (int i = 0; i < NL; ++i) dmaL(0, r0, i);
 #pragma unroll
-    for (int i = 0; i < NS; ++i) dmaS(0, r1, i);
-    const int p1 = min(1, nfull - 1);
+      for (int i = 0; i < NS; ++i) dmaS(0, r1, i);
+      const int p1 = min(1, nfull - 1);
 #pragma unroll
-    for (int i = 0; i < NL; ++i) dmaL(p1, r2, i);
+      for (int i = 0; i < NL; ++i) dmaL(p1, r2, i);
 #pragma unroll
-    for (int i = 0; i < NS0; ++i) dmaS(p1, r3, i);
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(NL + NS0));
-    __builtin_amdgcn_s_barrier();
-    read_a(0, r0, 0);
-    read_b(0, r1, 0);
-  }
-  for (int t = 0; t < nfull; t += 5) {
-    body(Int<0>{}, t);
-    if (t + 1 < nfull) body(Int<1>{}, t + 1);
-    if (t + 2 < nfull) body(Int<2>{}, t + 2);
-    if (t + 3 < nfull) body(Int<3>{}, t + 3);
-    if (t + 4 < nfull) body(Int<4>{}, t + 4);
-  }
-  __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // the clamped DMA instructions of the last tiles
-  // K tail (K % 64 != 0) through registers with element masks, not overlapped
-  if (nfull * DK < g.K) {
-    __syncthreads();
-    a.tail(g.A, astep, nfull, g.K, r0, wave, lane);
-    b.tail(g.B, bstep, nfull, g.K, r1, wave, lane);
-    __syncthreads();
+      for (int i = 0; i < NS0; ++i) dmaS(p1, r3, i);
+    }
+  };
+  // vector memory instructions a wavefront issues in the epilogue of an interior tile
+  constexpr int NEPI = MI * NI * ((EPI == ntp::EPI_BF16 || EPI == ntp::EPI_F32) ? 1 : 2);
+  bool stores_in_flight = false;
+  first_dma();
+  while (true) {
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      read_b(0, r1, ks);
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        read_a(h, r0, ks);
-        mfma_range(h, 0, 0, (h ? MI - MH : MH) * NI);
+      for (int j = 0; j < NI; ++j) acc[i][j] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    if (nfull > 0) {
+      // The first DMA instructions of this output tile have landed.  After the first output tile the
+      // previous tile's stores (and the loads of its epilogue) sit in the same in-order counter,
+      // issued after those DMA instructions: when that tile was an interior one, every wavefront
+      // issued exactly NEPI of them, which may stay in flight and drain while this tile computes.
+      if (stores_in_flight) __builtin_amdgcn_s_waitcnt(vmcnt_imm(NEPI <= 63 ? NEPI : 63));
+      else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+      __builtin_amdgcn_s_barrier();
+      read_a(0, r0, 0);
+      read_b(0, r1, 0);
+    }
+    for (int t = 0; t < nfull; t += 5) {
+      body(Int<0>{}, t);
+      if (t + 1 < nfull) body(Int<1>{}, t + 1);
+      if (t + 2 < nfull) body(Int<2>{}, t + 2);
+      if (t + 3 < nfull) body(Int<3>{}, t + 3);
+      if (t + 4 < nfull) body(Int<4>{}, t + 4);
+    }
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // the clamped DMA instructions of the last tiles
+    // K tail (K % 64 != 0) through registers with element masks, not overlapped
+    if (nfull * DK < g.K) {
+      __syncthreads();
+      a.tail(g.A, astep, nfull, g.K, r0, wave, lane);
+      b.tail(g.B, bstep, nfull, g.K, r1, wave, lane);
+      __syncthreads();
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        read_b(0, r1, ks);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          read_a(h, r0, ks);
+          mfma_range(h, 0, 0, (h ? MI - MH : MH) * NI);
+        }
       }
     }
+    // The next output tile's first DMA instructions go out before this tile's results are stored, so
+    // that their latency hides behind the stores.  The barrier makes sure that no wavefront still
+    // reads LDS and that every wavefront's DMA instructions of this tile have landed.
+    const int erow0 = row0, ecol0 = col0;
+    vblk += gridDim.x;
+    const bool more = vblk < nblk;
+    // interior tile: no lane is masked in the epilogue, so its instruction count is the static one
+    stores_in_flight = NEPI <= 63 && erow0 + BM_ <= g.M && ecol0 + BN_ <= g.N;
+    if (more) {
+      __builtin_amdgcn_s_waitcnt(vmcnt_lgkm0_imm(0));
+      __builtin_amdgcn_s_barrier();
+      place(vblk);
+      setup_tile();
+      first_dma();
+    }
+    __builtin_amdgcn_sched_barrier(0);  // the epilogue's memory instructions stay behind those DMA instructions
+    // lane l of a 16 x 16 block holds row (l & 15) and columns 4 (l >> 4) + {0..3}
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+      const int m = erow0 + wm * TM + i * 16 + (lane & 15);
+#pragma unroll
+      for (int j = 0; j < NI; ++j) {
+        const int n0 = ecol0 + wn * TN + j * 16 + (lane >> 4) * 4;
+        store4<EPI>(g, m, n0, acc[i][j]);
+      }
+    }
+    if (!more) break;
   }
+  asm volatile("" : "+v"(pf_sink));  // the prefetch register stays reserved up to here
 #ifdef NTP_GEMM_CLOCK_PROBE
   if (g.C2 && lane == 0) reinterpret_cast<long long*>(g.C2)[blockIdx.x * 8 + wave] = clock64() - probe_c0;
 #endif
-
-  asm volatile("" : "+v"(pf_sink));  // the prefetch register stays reserved up to here
-  // lane l of a 16 x 16 block holds row (l & 15) and columns 4 (l >> 4) + {0..3}
-#pragma unroll
-  for (int i = 0; i < MI; ++i) {
-    const int m = row0 + wm * TM + i * 16 + (lane & 15);
-#pragma unroll
-    for (int j = 0; j < NI; ++j) {
-      const int n0 = col0 + wn * TN + j * 16 + (lane >> 4) * 4;
-      store4<EPI>(g, m, n0, acc[i][j]);
-    }
-  }
 }
 
 }  // namespace ntp_gemm
