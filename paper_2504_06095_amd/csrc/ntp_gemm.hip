@@ -45,21 +45,26 @@ int launch_generic(GemmArgs g, int epi, hipStream_t s) {
   });
 }
 
-// Relative throughput of one workgroup per tile shape at full occupancy (256 x 256 = 1): smaller
-// wavefront tiles read more LDS fragments per MFMA, smaller workgroup tiles move more bytes per flop.
-constexpr double kTileRate[kNumTileShapes] = {1.0, 0.97, 0.97, 0.93, 0.93, 0.80, 0.80, 0.70};
+// Relative throughput of one workgroup per tile shape at full occupancy, per operand layout (measured
+// on large problems with operands streaming from HBM): smaller wavefront tiles read more LDS fragments
+// per MFMA, smaller workgroup tiles move more bytes per flop, and the K-strided layouts pay two
+// transposing reads per fragment (their 256 x 256 variant is also short of registers).
+//                                             256x256 256x224 224x256 256x192 192x256 256x128 128x256 128x128
+constexpr double kTileRate[3][kNumTileShapes] = {{1.000, 0.957, 0.969, 0.917, 0.923, 0.761, 0.754, 0.65},   // A, B K-contiguous
+                                                 {1.000, 0.929, 0.986, 0.908, 0.944, 0.770, 0.749, 0.65},   // B K-strided
+                                                 {0.923, 0.984, 1.000, 0.956, 0.962, 0.797, 0.779, 0.65}};  // both K-strided
 constexpr int kComputeUnits = 256;
 
 // Pick the tile shape with the least estimated time: the busiest compute unit's number of
 // workgroups (they are dealt evenly; co-resident ones share its throughput) times tile area over rate.
-int choose_tile(int64_t M, int64_t N) {
+int choose_tile(int64_t M, int64_t N, int layout) {
   int best = 0;
   double best_t = 1e300;
   for (int i = 0; i < kNumTileShapes; ++i) {
     const TileShape& ts = kTileShapes[i];
     const int64_t tiles = ((M + ts.bm - 1) / ts.bm) * ((N + ts.bn - 1) / ts.bn);
     const int64_t cu_load = (tiles + kComputeUnits - 1) / kComputeUnits;
-    const double t = double(cu_load) * ts.bm * ts.bn / kTileRate[i];
+    const double t = double(cu_load) * ts.bm * ts.bn / kTileRate[layout][i];
     if (t < best_t) {
       best_t = t;
       best = i;
@@ -71,7 +76,7 @@ int choose_tile(int64_t M, int64_t N) {
 // Variant used for a shape: -1 = generic kernel, else an index into kTileShapes.  The environment
 // variable NTP_GEMM_TILE (generic | 256x256 | 256x224 | ...) overrides the choice; it exists so
 // that tests and tuning runs can reach every variant at any size.
-int choose_variant(const GemmArgs& g, bool ring_ok) {
+int choose_variant(const GemmArgs& g, bool ring_ok, int layout) {
   if (const char* f = getenv("NTP_GEMM_TILE")) {
     if (!ring_ok || !strcmp(f, "generic")) return -1;
     for (int i = 0; i < kNumTileShapes; ++i) {
@@ -83,7 +88,7 @@ int choose_variant(const GemmArgs& g, bool ring_ok) {
   // small problems: the generic 128x128x32 kernel (4 wavefronts) has less fixed cost
   if (int64_t(g.M) * g.N < 128 * 128 * 64 || g.K < 128) return -1;
   if (!ring_ok) return -1;
-  return choose_tile(g.M, g.n_store);
+  return choose_tile(g.M, g.n_store, layout);
 }
 
 void variant_name(int v, char* out, size_t n) {
@@ -156,7 +161,7 @@ int gemm_launch(const GemmDesc& d, void* stream) {
   const int64_t a_rows = d.a_kc ? d.M : d.K, b_rows = d.b_kc ? d.N : d.K;
   const bool ring_ok = ring_combo(d.a_kc, d.b_kc, d.epilogue) && a_rows * d.lda * 2 < (int64_t(1) << 32) &&
                        b_rows * d.ldb * 2 < (int64_t(1) << 32);
-  const int variant = choose_variant(g, ring_ok);
+  const int variant = choose_variant(g, ring_ok, d.a_kc ? (d.b_kc ? 0 : 1) : 2);
   if (ntp::timing_on()) {
     char name[48], vn[16];
     variant_name(variant, vn, sizeof(vn));

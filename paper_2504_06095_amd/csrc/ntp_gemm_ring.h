@@ -216,7 +216,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
   // (the grid is a multiple of 8 whenever a workgroup gets more than one block); every XCD walks a
   // contiguous range of tiles in groups of 8 tile rows, so that its workgroups share operands.
   const int nblk = g.tiles_m * g.tiles_n;
-  int tile_m, tile_n, row0, col0;
+  struct TilePos {
+    int tile_m, tile_n, row0, col0;
+  };
   auto place = [&](int v) {
     const int xq = nblk >> 3, xr = nblk & 7, xcd = v & 7;
     const int L = xcd * xq + min(xcd, xr) + (v >> 3);
@@ -224,13 +226,16 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
     const int width = GM * g.tiles_n;
     const int first_m = (L / width) * GM;
     const int gsz = min(g.tiles_m - first_m, GM);
-    tile_m = first_m + (L % width) % gsz;
-    tile_n = (L % width) / gsz;
-    row0 = tile_m * BM_;
-    col0 = tile_n * BN_;
+    TilePos p;
+    p.tile_m = first_m + (L % width) % gsz;
+    p.tile_n = (L % width) / gsz;
+    p.row0 = p.tile_m * BM_;
+    p.col0 = p.tile_n * BN_;
+    return p;
   };
   int vblk = blockIdx.x;
-  place(vblk);
+  TilePos pos = place(vblk);
+  int row0 = pos.row0, col0 = pos.col0;
 
   f32x4 acc[MI][NI];
   OpA a;
@@ -267,22 +272,29 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
   const bool pf_ok = pf_is_a ? (AKC || g.M >= 2) : (BKC || g.N >= 2);
   const char* const pf_base = reinterpret_cast<const char*>(pf_is_a ? g.A : g.B);
   const int64_t pf_step = (pf_is_a ? astep : bstep) * 2;  // bytes per K tile
-  int pf_turn = 0;
-  uint32_t pf_voff = 0;
+  int pf_turn = 0, pf_turn_next = -1;  // -1: there is no next output tile
+  uint32_t pf_voff = 0, pf_voff_next = 0;
+  auto pf_params = [&](const TilePos& p, int& turn, uint32_t& voff) {
+    turn = pf_is_a ? (p.tile_n & 3) : (p.tile_m & 7);
+    voff = pf_is_a ? OpA::prefetch_offset(g.lda, p.row0, g.M, wave & 3, lane)
+                   : OpB::prefetch_offset(g.ldb, p.col0, g.N, wave & 3, lane);
+  };
   // per output tile: DMA offsets and prefetch parameters
   auto setup_tile = [&] {
     a.init(g.lda, row0, g.M, wave, lane);
     b.init(g.ldb, col0, g.N, wave, lane);
-    pf_turn = pf_is_a ? (tile_n & 3) : (tile_m & 7);
-    pf_voff = pf_is_a ? OpA::prefetch_offset(g.lda, row0, g.M, wave & 3, lane)
-                      : OpB::prefetch_offset(g.ldb, col0, g.N, wave & 3, lane);
+    pf_params(pos, pf_turn, pf_voff);
   };
   setup_tile();
+  // K tile t + PFD of this output tile, or, past its end, the first K tiles of the next output tile
   auto prefetch = [&](int t) {
     const int tp = t + PFD;
-    const bool turn = tp < nfull && ((tp & pf_mask) == pf_turn) && pf_ok;
-    const char* src = turn ? pf_base + int64_t(tp) * pf_step : pf_base;
-    const uint32_t voff = turn ? pf_voff : 0u;
+    const bool own = tp < nfull;
+    const int kp = own ? tp : tp - nfull;
+    const int want = own ? pf_turn : pf_turn_next;
+    const bool turn = kp < nfull && ((kp & pf_mask) == want) && pf_ok;
+    const char* src = turn ? pf_base + int64_t(kp) * pf_step : pf_base;
+    const uint32_t voff = turn ? (own ? pf_voff : pf_voff_next) : 0u;
     asm volatile("global_load_dword %0, %1, %2" : "+v"(pf_sink) : "v"(voff), "s"(src) : "memory");
   };
 
@@ -407,6 +419,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
   bool stores_in_flight = false;
   first_dma();
   while (true) {
+    const int vnext = vblk + int(gridDim.x);
+    const bool more = vnext < nblk;
+    const TilePos npos = more ? place(vnext) : pos;
+    if (more) pf_params(npos, pf_turn_next, pf_voff_next);
+    else pf_turn_next = -1;
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -450,14 +467,15 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
     // that their latency hides behind the stores.  The barrier makes sure that no wavefront still
     // reads LDS and that every wavefront's DMA instructions of this tile have landed.
     const int erow0 = row0, ecol0 = col0;
-    vblk += gridDim.x;
-    const bool more = vblk < nblk;
+    vblk = vnext;
     // interior tile: no lane is masked in the epilogue, so its instruction count is the static one
     stores_in_flight = NEPI <= 63 && erow0 + BM_ <= g.M && ecol0 + BN_ <= g.N;
     if (more) {
       __builtin_amdgcn_s_waitcnt(vmcnt_lgkm0_imm(0));
       __builtin_amdgcn_s_barrier();
-      place(vblk);
+      pos = npos;
+      row0 = pos.row0;
+      col0 = pos.col0;
       setup_tile();
       first_dma();
     }
