@@ -15,8 +15,8 @@ t' the reduced one.  The oracle keeps the paper's orientation of A and B.
 All functions take and return float64 arrays unless they move opaque bits.
 
 Every function here is pinned by tests/test_oracle_*.py against values the
-paper prints, closed forms, brute force or finite differences; none is
-"parity unpinned".
+paper prints, closed forms, brute force, finite differences or the properties
+the paper states for the result; none is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -281,3 +281,97 @@ def reshard_source_of(kind, n_units, src_tp, dst_tp, dst_rank, dst_local_unit, n
         if u in ids:
             return r, ids.index(u)
     raise AssertionError("unit not held by any source rank")
+
+
+# ----------------------------------------------------------------------------
+# Shard mapping of the healthy replica (Sec. 3.1 "Shard-mapping algorithm",
+# Alg. 1 "Comp and Sync Rank Assignment").  The healthy replica computes on all
+# t ranks but synchronises on only t' of them (those match the t' shards of a
+# degraded replica one to one).  Every partition unit therefore has a rank that
+# computes it and a rank that synchronises it.
+#
+# Reading of the algorithm (its printed form mixes up the two rank counts and
+# drops the slice base; the prose fixes what is meant):
+#   * sync ranks are ranks 0 .. t'-1 and hold contiguous, even-as-possible
+#     slices of the k units (the split of shard_plan(k, t', .));
+#   * each sync rank keeps the first k // t units of its slice for its own
+#     computation and offloads the rest;
+#   * the offloaded units of all sync ranks, taken in unit order, are dealt one
+#     by one to the t - t' offload ranks t' .. t-1 in turn, the turn carrying on
+#     from one sync rank to the next, so that every (offload rank, sync rank)
+#     pair moves the same number of units up to one.
+# When t does not divide k the offload ranks absorb the remainder.
+# ----------------------------------------------------------------------------
+def comp_sync_plan(k: int, t_full: int, t_red: int) -> tuple[list[int], list[int]]:
+    """(comp_rank, sync_rank), each a list of k rank numbers."""
+    if k < 0 or t_red < 1 or t_full < t_red:
+        raise ValueError("need k >= 0 and 1 <= t_red <= t_full")
+    comp = [0] * k
+    sync = [0] * k
+    keep = k // t_full
+    n_off = t_full - t_red
+    turn = 0
+    for i in range(t_red):
+        off, w = shard_plan(k, t_red, i)
+        for j in range(w):
+            u = off + j
+            sync[u] = i
+            if j < keep or n_off == 0:
+                comp[u] = i
+            else:
+                comp[u] = t_red + turn
+                turn = (turn + 1) % n_off
+    return comp, sync
+
+
+def units_of_rank(rank_of_unit, tp: int) -> list[list[int]]:
+    """Layout given by a unit -> rank map: rank r holds its units in ascending unit order."""
+    out = [[] for _ in range(tp)]
+    for u, r in enumerate(rank_of_unit):
+        if not (0 <= r < tp):
+            raise ValueError("rank out of range")
+        out[r].append(u)
+    return out
+
+
+def cut_shard_mapped(G, partition_dim, unit, rank_of_unit, tp, rank):
+    """One rank's shard of the logical tensor G under a unit -> rank map."""
+    ids = units_of_rank(rank_of_unit, tp)[rank]
+    idx = np.concatenate([np.arange(u * unit, (u + 1) * unit) for u in ids]) if ids else np.zeros(0, dtype=np.int64)
+    return np.take(G, idx, axis=partition_dim)
+
+
+def reshard_mapped(src_shards, partition_dim, unit, src_rank_of_unit, src_tp, dst_rank_of_unit, dst_tp):
+    """Repack shards between two layouts given by unit -> rank maps, unit by unit
+    (the data movement of the pre-sync hook and of the post-sync reshard in the
+    Appendix, for the layouts of Alg. 1).  Moves bits."""
+    if len(src_rank_of_unit) != len(dst_rank_of_unit):
+        raise ValueError("the two maps must cover the same units")
+    src_ids = units_of_rank(src_rank_of_unit, src_tp)
+    local_in_src = {}
+    for r, ids in enumerate(src_ids):
+        for local, u in enumerate(ids):
+            local_in_src[u] = (r, local)
+    out = []
+    for s, ids in enumerate(units_of_rank(dst_rank_of_unit, dst_tp)):
+        shape = list(src_shards[0].shape)
+        shape[partition_dim] = len(ids) * unit
+        D = np.empty(shape, dtype=src_shards[0].dtype)
+        for local, u in enumerate(ids):
+            r, sl = local_in_src[u]
+            dsl = [slice(None)] * D.ndim
+            ssl = [slice(None)] * D.ndim
+            dsl[partition_dim] = slice(local * unit, (local + 1) * unit)
+            ssl[partition_dim] = slice(sl * unit, (sl + 1) * unit)
+            D[tuple(dsl)] = src_shards[r][tuple(ssl)]
+        out.append(D)
+    return out
+
+
+def transfer_counts(src_rank_of_unit, src_tp, dst_rank_of_unit, dst_tp) -> np.ndarray:
+    """counts[r][s] = units that move from source rank r to destination rank s: row r is rank r's
+    send split, column s is rank s's receive split (the precomputed splits of the Appendix hook)."""
+    c = np.zeros((src_tp, dst_tp), dtype=np.int64)
+    for r, s in zip(src_rank_of_unit, dst_rank_of_unit):
+        c[r, s] += 1
+    return c
