@@ -203,6 +203,73 @@ int ntp_reshard_grad(const ntp_tensor_spec_t* spec, int32_t src_tp, int32_t dst_
                      void* const* dst_shards, const int64_t* dst_ld, void* stream);
 
 /* ---------------------------------------------------------------------------
+ * Comp and sync rank assignment (Sec. 3.1 "Shard-mapping algorithm", Alg. 1).
+ * A healthy replica of TP degree full_tp synchronises gradients with replicas
+ * that run at reduced_tp <= full_tp.  For each of the k partition units:
+ *   sync_rank[u]: the rank (0 .. reduced_tp-1) that holds unit u when gradients
+ *     are synchronised: the contiguous even split of ntp_shard_plan(k, reduced_tp);
+ *   comp_rank[u]: the rank (0 .. full_tp-1) that holds and computes unit u.  A
+ *     sync rank keeps the first k / full_tp (rounded down) units of its slice;
+ *     the others are dealt one by one, in unit order, in turn to the offload
+ *     ranks reduced_tp .. full_tp-1, the turn running on from one sync rank's
+ *     slice to the next, so that all (offload rank, sync rank) pairs carry the
+ *     same number of units to within one.
+ * Host only.  comp_rank / sync_rank: HOST arrays of k entries, written.
+ * reduced_tp == full_tp gives comp_rank == sync_rank.  INVALID_ARG for k < 0,
+ * reduced_tp < 1, full_tp < reduced_tp or a NULL array with k > 0. */
+int ntp_comp_sync_plan(int64_t k, int32_t full_tp, int32_t reduced_tp, int32_t* comp_rank,
+                       int32_t* sync_rank);
+
+/* ---------------------------------------------------------------------------
+ * Reshard between two layouts given unit by unit (Sec. 3.1, Alg. 1; Appendix:
+ * the pre-sync hook and post-sync reshard with split sizes precomputed from the
+ * rank assignment).  A layout is a map unit -> rank; a rank holds its units in
+ * ascending unit order, as one dense-in-units shard shaped like the shards of
+ * ntp_reshard_grad.  A plan is built once from the two maps (host work
+ * proportional to the number of units) and run every step.
+ *
+ * ntp_reshard_plan_create: spec as for ntp_reshard_grad, kind NTP_KIND_PLAIN
+ *   only; src_rank_of_unit / dst_rank_of_unit: HOST arrays of map_len entries,
+ *   one per partition unit (values in [0, src_tp) / [0, dst_tp)), read during
+ *   the call only; map_len must equal the spec's number of units (INVALID_ARG).  *plan receives a handle owned by the library until
+ *   ntp_reshard_plan_destroy.  Host only, touches no GPU.
+ * ntp_reshard_plan_segments: the sub-shards (runs of units that are consecutive
+ *   in both a source and a destination shard) in destination order, as for
+ *   ntp_reshard_segments.
+ * ntp_reshard_plan_splits: units[r * dst_tp + s] = units that source rank r
+ *   sends to destination rank s (row r: send splits of r; column s: receive
+ *   splits of s).  HOST array of src_tp * dst_tp entries, written.
+ * ntp_reshard_plan_table: for every destination unit, destination shards one
+ *   after the other, the source rank and the local unit in its shard.
+ * ntp_reshard_plan_run: enqueue the copy; shard arrays, NULL shards, alignment
+ *   and aliasing rules as for ntp_reshard_grad.  Column-partitioned tensors of
+ *   4-byte elements whose shards are all on this GPU, with dense 64-byte aligned
+ *   destinations, go through a kernel that reads the plan's run table from
+ *   device memory: the FIRST such run allocates the table (2 bytes per unit +
+ *   16 bytes per sub-shard) on the current device and waits for its upload;
+ *   later runs must use the same device (else INVALID_ARG) and allocate
+ *   nothing.  Everything else is copied sub-shard by sub-shard.
+ * ntp_reshard_plan_destroy: frees the handle and its device table; no run of
+ *   the plan may still be in flight.  NULL is accepted. */
+typedef struct ntp_reshard_plan ntp_reshard_plan_t;
+typedef struct ntp_unit_source {
+  int32_t src_rank;
+  int32_t src_unit; /* local unit in the source rank's shard */
+} ntp_unit_source_t;
+int ntp_reshard_plan_create(const ntp_tensor_spec_t* spec, int64_t map_len, int32_t src_tp,
+                            const int32_t* src_rank_of_unit, int32_t dst_tp,
+                            const int32_t* dst_rank_of_unit, ntp_reshard_plan_t** plan);
+int ntp_reshard_plan_segments(const ntp_reshard_plan_t* plan, ntp_segment_t* out,
+                              int64_t max_segments, int64_t* count);
+int ntp_reshard_plan_splits(const ntp_reshard_plan_t* plan, int64_t* units);
+int ntp_reshard_plan_table(const ntp_reshard_plan_t* plan, ntp_unit_source_t* out,
+                           int64_t max_units, int64_t* count);
+int ntp_reshard_plan_run(ntp_reshard_plan_t* plan, const void* const* src_shards,
+                         const int64_t* src_ld, void* const* dst_shards, const int64_t* dst_ld,
+                         void* stream);
+int ntp_reshard_plan_destroy(ntp_reshard_plan_t* plan);
+
+/* ---------------------------------------------------------------------------
  * Measurement aid (not part of the method).  When enabled, every kernel the
  * library enqueues is bracketed by two HIP events on the caller's stream and
  * recorded with its algorithmic work: flops = 2 M N K on the logical GEMM

@@ -26,6 +26,8 @@ EXPORTS = (
     "ntp_version", "ntp_status_string", "ntp_shard_plan", "ntp_attn_shard_plan", "ntp_mlp_shard_fwd",
     "ntp_mlp_shard_bwd", "ntp_attn_proj_shard_fwd", "ntp_attn_proj_shard_bwd", "ntp_reshard_segments",
     "ntp_reshard_grad", "ntp_kernel_timing_enable", "ntp_kernel_timing_read", "ntp_calibration_copy",
+    "ntp_comp_sync_plan", "ntp_reshard_plan_create", "ntp_reshard_plan_segments", "ntp_reshard_plan_splits",
+    "ntp_reshard_plan_table", "ntp_reshard_plan_run", "ntp_reshard_plan_destroy",
 )
 
 
@@ -58,6 +60,10 @@ class Segment(C.Structure):
                 ("dst_unit", C.c_int64), ("units", C.c_int64)]
 
 
+class UnitSource(C.Structure):
+    _fields_ = [("src_rank", C.c_int32), ("src_unit", C.c_int32)]
+
+
 class KernelTime(C.Structure):
     _fields_ = [("name", C.c_char * 48), ("flops", C.c_double), ("bytes", C.c_double), ("ms", C.c_float),
                 ("pad_", C.c_int32)]
@@ -87,6 +93,14 @@ def lib() -> C.CDLL:
                                            C.POINTER(i64)]
         L.ntp_reshard_grad.argtypes = [C.POINTER(TensorSpec), C.c_int32, C.c_int32, C.POINTER(vp), C.POINTER(i64),
                                        C.POINTER(vp), C.POINTER(i64), vp]
+        i32p = C.POINTER(C.c_int32)
+        L.ntp_comp_sync_plan.argtypes = [i64, C.c_int32, C.c_int32, i32p, i32p]
+        L.ntp_reshard_plan_create.argtypes = [C.POINTER(TensorSpec), i64, C.c_int32, i32p, C.c_int32, i32p, C.POINTER(vp)]
+        L.ntp_reshard_plan_segments.argtypes = [vp, C.POINTER(Segment), i64, C.POINTER(i64)]
+        L.ntp_reshard_plan_splits.argtypes = [vp, C.POINTER(i64)]
+        L.ntp_reshard_plan_table.argtypes = [vp, C.POINTER(UnitSource), i64, C.POINTER(i64)]
+        L.ntp_reshard_plan_run.argtypes = [vp, C.POINTER(vp), C.POINTER(i64), C.POINTER(vp), C.POINTER(i64), vp]
+        L.ntp_reshard_plan_destroy.argtypes = [vp]
         L.ntp_kernel_timing_enable.argtypes = [C.c_int32]
         L.ntp_kernel_timing_read.argtypes = [C.POINTER(KernelTime), i64, C.POINTER(i64)]
         L.ntp_calibration_copy.argtypes = [vp, vp, i64, vp]
@@ -203,8 +217,7 @@ def ntp_attn_proj_shard_bwd(M, H, w_qkv, w_o, dZ=None, dQKV=None, X=None, C_=Non
            "ntp_attn_proj_shard_bwd")
 
 
-def ntp_reshard_grad(spec: TensorSpec, src_tp: int, dst_tp: int, src_shards, dst_shards) -> None:
-    """src_shards / dst_shards: lists of 2-D device tensors (or None for "not on this GPU")."""
+def _shard_arrays(spec: TensorSpec, src_tp: int, dst_tp: int, src_shards, dst_shards):
     vp, i64 = C.c_void_p, C.c_int64
     sp, sl = (vp * src_tp)(), (i64 * src_tp)()
     dp, dl = (vp * dst_tp)(), (i64 * dst_tp)()
@@ -219,7 +232,73 @@ def ntp_reshard_grad(spec: TensorSpec, src_tp: int, dst_tp: int, src_shards, dst
                 raise TypeError("element size of a shard differs from the spec")
             p, ld = _mat(t)
             arr_p[i], arr_l[i] = p, ld
+    return sp, sl, dp, dl
+
+
+def ntp_reshard_grad(spec: TensorSpec, src_tp: int, dst_tp: int, src_shards, dst_shards) -> None:
+    """src_shards / dst_shards: lists of 2-D device tensors (or None for "not on this GPU")."""
+    sp, sl, dp, dl = _shard_arrays(spec, src_tp, dst_tp, src_shards, dst_shards)
     _check(lib().ntp_reshard_grad(C.byref(spec), src_tp, dst_tp, sp, sl, dp, dl, _stream()), "ntp_reshard_grad")
+
+
+class ReshardPlan:
+    """Handle of a reshard plan between two unit -> rank maps; the methods carry the names of the
+    entry points they call.  Destroyed with the object (or by destroy())."""
+
+    def __init__(self, spec: TensorSpec, src_tp: int, src_rank_of_unit, dst_tp: int, dst_rank_of_unit):
+        n = len(src_rank_of_unit)
+        if len(dst_rank_of_unit) != n:
+            raise ValueError("the two maps must cover the same units")
+        self.spec, self.src_tp, self.dst_tp, self.n_units = spec, src_tp, dst_tp, n
+        a = (C.c_int32 * max(1, n))(*[int(x) for x in src_rank_of_unit])
+        b = (C.c_int32 * max(1, n))(*[int(x) for x in dst_rank_of_unit])
+        self._h = C.c_void_p()
+        _check(lib().ntp_reshard_plan_create(C.byref(spec), n, src_tp, a, dst_tp, b, C.byref(self._h)),
+               "ntp_reshard_plan_create")
+
+    def ntp_reshard_plan_segments(self) -> list[tuple[int, int, int, int, int]]:
+        n = C.c_int64()
+        _check(lib().ntp_reshard_plan_segments(self._h, None, 0, C.byref(n)), "ntp_reshard_plan_segments")
+        buf = (Segment * max(1, n.value))()
+        _check(lib().ntp_reshard_plan_segments(self._h, buf, n.value, C.byref(n)), "ntp_reshard_plan_segments")
+        return [(s.src_rank, s.dst_rank, s.src_unit, s.dst_unit, s.units) for s in buf[: n.value]]
+
+    def ntp_reshard_plan_splits(self) -> list[list[int]]:
+        buf = (C.c_int64 * max(1, self.src_tp * self.dst_tp))()
+        _check(lib().ntp_reshard_plan_splits(self._h, buf), "ntp_reshard_plan_splits")
+        return [[buf[r * self.dst_tp + s] for s in range(self.dst_tp)] for r in range(self.src_tp)]
+
+    def ntp_reshard_plan_table(self) -> list[tuple[int, int]]:
+        n = C.c_int64()
+        buf = (UnitSource * max(1, self.n_units))()
+        _check(lib().ntp_reshard_plan_table(self._h, buf, self.n_units, C.byref(n)), "ntp_reshard_plan_table")
+        return [(e.src_rank, e.src_unit) for e in buf[: n.value]]
+
+    def ntp_reshard_plan_run(self, src_shards, dst_shards) -> None:
+        sp, sl, dp, dl = _shard_arrays(self.spec, self.src_tp, self.dst_tp, src_shards, dst_shards)
+        _check(lib().ntp_reshard_plan_run(self._h, sp, sl, dp, dl, _stream()), "ntp_reshard_plan_run")
+
+    def destroy(self) -> None:
+        if self._h:
+            _check(lib().ntp_reshard_plan_destroy(self._h), "ntp_reshard_plan_destroy")
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def ntp_comp_sync_plan(k: int, full_tp: int, reduced_tp: int) -> tuple[list[int], list[int]]:
+    """(comp_rank, sync_rank): rank of every unit in the compute and in the synchronisation layout."""
+    comp, sync = (C.c_int32 * max(1, k))(), (C.c_int32 * max(1, k))()
+    _check(lib().ntp_comp_sync_plan(k, full_tp, reduced_tp, comp, sync), "ntp_comp_sync_plan")
+    return list(comp[:k]), list(sync[:k])
+
+
+def ntp_reshard_plan_create(spec: TensorSpec, src_tp: int, src_rank_of_unit, dst_tp: int, dst_rank_of_unit) -> ReshardPlan:
+    return ReshardPlan(spec, src_tp, src_rank_of_unit, dst_tp, dst_rank_of_unit)
 
 
 # ---- measurement aid ---------------------------------------------------------------

@@ -22,6 +22,21 @@ int shard_units(const ntp_tensor_spec_t* spec, int64_t n_units, int32_t tp, int3
                 int64_t* units);
 int build_segments(const ntp_tensor_spec_t* spec, int32_t src_tp, int32_t dst_tp,
                    std::vector<ntp_segment_t>* segs);
+// Sub-shards between two layouts given by unit -> rank maps (each rank holds its units in ascending
+// unit order), in destination order; also the number of units per rank of either layout.
+int build_segments_mapped(int64_t n_units, int32_t src_tp, const int32_t* src_rank_of_unit, int32_t dst_tp,
+                          const int32_t* dst_rank_of_unit, std::vector<ntp_segment_t>* segs,
+                          std::vector<int64_t>* src_units, std::vector<int64_t>* dst_units);
+// Shape, alignment and aliasing checks of the shards of a reshard.
+int check_shards(const ntp_tensor_spec_t* spec, const std::vector<int64_t>& src_units,
+                 const std::vector<int64_t>& dst_units, const void* const* src_shards, const int64_t* src_ld,
+                 void* const* dst_shards, const int64_t* dst_ld);
+// Device side of a reshard: checks the shards (shape, alignment, aliasing) and enqueues the copies
+// of `segs` (destination order).  src_units / dst_units: partition units held by each rank.
+int reshard_launch(const ntp_tensor_spec_t* spec, const std::vector<ntp_segment_t>& segs,
+                   const std::vector<int64_t>& src_units, const std::vector<int64_t>& dst_units,
+                   const void* const* src_shards, const int64_t* src_ld, void* const* dst_shards,
+                   const int64_t* dst_ld, void* stream);
 
 // ---- optional per-kernel timing (measurement aid) ------------------------------
 bool timing_on();

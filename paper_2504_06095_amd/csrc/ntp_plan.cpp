@@ -137,7 +137,68 @@ int build_segments(const ntp_tensor_spec_t* spec, int32_t src_tp, int32_t dst_tp
   return NTP_OK;
 }
 
+int build_segments_mapped(int64_t n_units, int32_t src_tp, const int32_t* src_map, int32_t dst_tp,
+                          const int32_t* dst_map, std::vector<ntp_segment_t>* segs,
+                          std::vector<int64_t>* src_units, std::vector<int64_t>* dst_units) {
+  if (n_units < 0 || src_tp < 1 || dst_tp < 1 || (n_units > 0 && (!src_map || !dst_map))) return NTP_ERR_INVALID_ARG;
+  src_units->assign(src_tp, 0);
+  dst_units->assign(dst_tp, 0);
+  // local position of every unit in its source shard, and the units of every destination shard
+  std::vector<int64_t> src_local(n_units);
+  std::vector<std::vector<int64_t>> dst_ids(dst_tp);
+  for (int64_t u = 0; u < n_units; ++u) {
+    const int32_t r = src_map[u], s = dst_map[u];
+    if (r < 0 || r >= src_tp || s < 0 || s >= dst_tp) return NTP_ERR_INVALID_ARG;
+    src_local[u] = (*src_units)[r]++;
+    dst_ids[s].push_back(u);
+    ++(*dst_units)[s];
+  }
+  segs->clear();
+  for (int32_t s = 0; s < dst_tp; ++s) {
+    const std::vector<int64_t>& ids = dst_ids[s];
+    for (size_t j = 0; j < ids.size(); ++j) {
+      const int64_t u = ids[j];
+      const int32_t r = src_map[u];
+      // extend the previous sub-shard when this unit follows it on both sides
+      if (!segs->empty()) {
+        ntp_segment_t& g = segs->back();
+        if (g.dst_rank == s && g.src_rank == r && g.dst_unit + g.units == int64_t(j) &&
+            g.src_unit + g.units == src_local[u]) {
+          ++g.units;
+          continue;
+        }
+      }
+      segs->push_back({r, s, src_local[u], int64_t(j), 1});
+    }
+  }
+  return NTP_OK;
+}
+
 }  // namespace ntp
+
+// Sec. 3.1 "Shard-mapping algorithm", Alg. 1.
+extern "C" int ntp_comp_sync_plan(int64_t k, int32_t full_tp, int32_t reduced_tp, int32_t* comp_rank,
+                                  int32_t* sync_rank) {
+  if (k < 0 || reduced_tp < 1 || full_tp < reduced_tp || (k > 0 && (!comp_rank || !sync_rank)))
+    return NTP_ERR_INVALID_ARG;
+  const int64_t keep = k / full_tp;
+  const int32_t n_off = full_tp - reduced_tp;
+  int32_t turn = 0;
+  for (int32_t i = 0; i < reduced_tp; ++i) {
+    int64_t off = 0, w = 0;
+    ntp_shard_plan(k, reduced_tp, i, &off, &w);
+    for (int64_t j = 0; j < w; ++j) {
+      sync_rank[off + j] = i;
+      if (j < keep || n_off == 0) {
+        comp_rank[off + j] = i;
+      } else {
+        comp_rank[off + j] = reduced_tp + turn;
+        turn = turn + 1 == n_off ? 0 : turn + 1;
+      }
+    }
+  }
+  return NTP_OK;
+}
 
 extern "C" int ntp_reshard_segments(const ntp_tensor_spec_t* spec, int32_t src_tp, int32_t dst_tp,
                                     ntp_segment_t* out, int64_t max_segments, int64_t* count) {

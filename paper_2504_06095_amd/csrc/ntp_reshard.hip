@@ -349,6 +349,182 @@ __global__ __launch_bounds__(kThreads) void reshard_dense_kernel(const DenseBatc
   }
 }
 
+// ---- layouts given unit by unit (Sec. 3.1, Alg. 1): gather through a run table -------------------
+// The destination shards are dense and are written like the flat kernel writes them: as one flat
+// byte range cut into blocks at 64-byte boundaries, every 16-byte chunk stored whole and aligned.
+// A destination shard is a sequence of runs (units that follow each other in one source shard too);
+// the plan keeps, in device memory, the runs of every destination shard and for every destination
+// unit the number of its run.  A workgroup serves one destination shard: it copies both tables into
+// LDS once (runs joined with this call's source pointers) and then walks over its share of the
+// shard's blocks.  A chunk that lies inside one run is moved by one 16-byte load and store.  The
+// other chunks (they straddle a run boundary or a row end, or are the short last chunk of the
+// shard) are put on a queue that each wavefront keeps in LDS, and are put together word by word when
+// the queue has filled up, so that this slower code runs with most lanes in use even when few
+// chunks need it.  Needs: 4-byte elements, dense 64-byte aligned destinations,
+// (block + W + 16) * W <= 2^32 for the row width W in bytes, source strides below 2^32 bytes, at
+// most kMaxRanks source ranks, at most 65535 runs per shard.
+constexpr int kMaxRanks = 96;
+constexpr int kUnitDsts = 96;               // destination shards per launch (the argument block stays below 4 KiB)
+constexpr uint32_t kUnitLdsMax = 60 << 10;  // bytes of LDS a workgroup may ask for
+constexpr uint32_t kQueueCap = 512;         // queued chunks per wavefront
+constexpr uint32_t kUnitBlocksPerCu = 8;
+
+struct UnitSrc {
+  const char* base;  // first byte of the source shard
+  uint64_t stride;   // bytes between its rows
+};
+struct RunDev {      // one run of a destination shard (plan, device memory)
+  uint32_t begin, end;  // byte range in a destination row
+  uint32_t src_off;     // byte offset in a source row of what goes to `begin`
+  uint32_t rank;        // source rank
+};
+struct RunLds {      // the same, joined with the source pointers of this call
+  uint32_t begin, end, stride, pad_;
+  uint64_t adj;      // source base + src_off - begin: column c of row r is at adj + r * stride + c
+  uint64_t pad2_;
+};
+struct UnitDst {
+  char* dst;
+  uint32_t idx_first, n_units;   // this shard's slice of the unit -> run numbers
+  uint32_t runs_first, n_runs;   // this shard's slice of the runs
+};
+struct UnitBatch {
+  UnitSrc src[kMaxRanks];
+  UnitDst dst[kUnitDsts];
+  const RunDev* runs;
+  const uint16_t* run_of_unit;
+  uint32_t rows, unit_bytes, ndst, block_bytes;
+};
+
+__host__ __device__ inline uint32_t unit_tables_bytes(uint32_t n_runs, uint32_t n_units) {
+  return n_runs * uint32_t(sizeof(RunLds)) + ((n_units * 2u + 15u) & ~15u);
+}
+__host__ __device__ inline uint32_t unit_lds_bytes(uint32_t n_runs, uint32_t n_units) {
+  return unit_tables_bytes(n_runs, n_units) + kWaves * kQueueCap * uint32_t(sizeof(uint2));
+}
+
+__global__ __launch_bounds__(kThreads) void reshard_units_kernel(const UnitBatch batch) {
+  extern __shared__ __align__(16) unsigned char unit_lds[];
+  const uint32_t slot = blockIdx.x / batch.ndst, di = blockIdx.x - slot * batch.ndst;
+  const uint32_t nslots = gridDim.x / batch.ndst;
+  const UnitDst& dd = batch.dst[di];
+  const uint32_t ub = batch.unit_bytes, blk = batch.block_bytes;
+  const uint32_t W = dd.n_units * ub;
+  const int64_t T = int64_t(batch.rows) * W;
+  int64_t b0 = int64_t(slot) * blk;
+  if (b0 >= T) return;  // the whole workgroup leaves: nothing left for it in this shard
+  RunLds* const runs = reinterpret_cast<RunLds*>(unit_lds);
+  uint16_t* const run_of = reinterpret_cast<uint16_t*>(unit_lds + dd.n_runs * sizeof(RunLds));
+  const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
+  uint2* const queue = reinterpret_cast<uint2*>(unit_lds + unit_tables_bytes(dd.n_runs, dd.n_units)) + wave * kQueueCap;
+  for (uint32_t r = threadIdx.x; r < dd.n_runs; r += kThreads) {
+    const RunDev rd = batch.runs[dd.runs_first + r];
+    const UnitSrc sr = batch.src[rd.rank];
+    RunLds o;
+    o.begin = rd.begin;
+    o.end = rd.end;
+    o.stride = uint32_t(sr.stride);
+    o.pad_ = 0;
+    o.adj = uint64_t(reinterpret_cast<uintptr_t>(sr.base)) + rd.src_off - rd.begin;
+    o.pad2_ = 0;
+    runs[r] = o;
+  }
+  for (uint32_t j = threadIdx.x; j < dd.n_units; j += kThreads) run_of[j] = batch.run_of_unit[dd.idx_first + j];
+  __syncthreads();  // the only workgroup-wide wait: from here on the wavefronts run on their own
+
+  // W and the unit size are at least 4: the multiply-high division needs no special case
+  const uint32_t magic_w = div_magic(W), magic_u = div_magic(ub);
+  const char* const dummy = reinterpret_cast<const char*>(batch.runs);  // 16 readable bytes for lanes with nothing to load
+  // queued chunks of this wavefront, word by word
+  uint32_t nq = 0;  // chunks on this wavefront's queue (the same value in all lanes)
+  auto flush = [&]() {
+    // what other lanes have queued becomes visible
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    for (uint32_t i = lane; i < nq; i += 64) {
+      const uint2 e = queue[i];  // {row, byte column} of the chunk's first word
+      const int64_t at = int64_t(e.x) * W + e.y;
+      const uint32_t len = uint32_t(std::min<int64_t>(16, T - at));
+      u32x4 v;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const bool have = uint32_t(w) * 4 < len;
+        const uint32_t xw = e.y + (have ? 4u * w : 0u);
+        const uint32_t rw = __umulhi(xw, magic_w), cw = xw - rw * W;  // rows may be shorter than a chunk
+        const RunLds rn = runs[run_of[__umulhi(cw, magic_u)]];
+        v[w] = *reinterpret_cast<const uint32_t*>(rn.adj + (uint64_t(e.x + rw) * rn.stride + cw));
+      }
+      char* dp = dd.dst + at;
+      if (len == 16) {
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dp));
+      } else {
+#pragma unroll
+        for (int w = 0; w < 3; ++w)
+          if (uint32_t(w) * 4 < len) reinterpret_cast<uint32_t*>(dp)[w] = v[w];
+      }
+    }
+    // the entries have been read before the queue is filled again
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    nq = 0;
+  };
+
+  // this workgroup's blocks: slot, slot + nslots, ...; (row0, c0) = position of the block's first byte
+  const int64_t step = int64_t(nslots) * blk;
+  const uint32_t step_rows = uint32_t(step / W), step_cols = uint32_t(step - int64_t(step_rows) * W);
+  uint32_t row0 = uint32_t(b0 / W);
+  uint32_t c0 = uint32_t(b0 - int64_t(row0) * W);
+  for (; b0 < T; b0 += step) {
+    const uint32_t nb = uint32_t(std::min<int64_t>(blk, T - b0));
+    char* __restrict__ d = dd.dst + b0;
+    const uint32_t nchunks = (nb + 15) >> 4;
+    // the loop bounds are the same for all lanes of a wavefront: every lane takes part in flush()
+    for (uint32_t wbase = wave << 6; wbase < nchunks; wbase += kThreads * kUnroll) {
+      const uint32_t base = wbase + lane;
+      u32x4 v[kUnroll];
+      bool ok[kUnroll], slow[kUnroll];
+      uint32_t rowq[kUnroll], colq[kUnroll];
+      // look every chunk up and start its load; lanes with no chunk, or with a chunk for the slow way,
+      // go through the same steps on chunk 0 and load the dummy bytes (no branches, four loads in flight)
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        const uint32_t k = base + u * kThreads;
+        const bool valid = k < nchunks;
+        const uint32_t kb = valid ? k << 4 : 0u;
+        const uint32_t x = c0 + kb;
+        const uint32_t rr = __umulhi(x, magic_w), col = x - rr * W;
+        const RunLds rn = runs[run_of[__umulhi(col, magic_u)]];
+        ok[u] = valid && kb + 16u <= nb && col + 16u <= rn.end;
+        slow[u] = valid && !ok[u];
+        rowq[u] = row0 + rr;
+        colq[u] = col;
+        const char* p = reinterpret_cast<const char*>(rn.adj + (uint64_t(row0 + rr) * rn.stride + col));
+        v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_a4*>(ok[u] ? p : dummy));
+      }
+      // the chunks that need the slow way go on the queue, in lane order
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        const uint64_t m = __ballot(slow[u]);
+        if (slow[u]) queue[nq + __builtin_amdgcn_mbcnt_hi(uint32_t(m >> 32), __builtin_amdgcn_mbcnt_lo(uint32_t(m), 0u))] = make_uint2(rowq[u], colq[u]);
+        nq += uint32_t(__popcll(m));
+      }
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u)
+        if (ok[u]) __builtin_nontemporal_store(v[u], reinterpret_cast<u32x4*>(d + ((base + u * kThreads) << 4)));
+      // one pass of the loop queues at most 64 * kUnroll chunks per wavefront
+      if (nq > kQueueCap - 64 * kUnroll) flush();
+    }
+    row0 += step_rows;
+    c0 += step_cols;
+    if (c0 >= W) {
+      c0 -= W;
+      ++row0;
+    }
+  }
+  flush();
+}
+
 struct Extent {
   uintptr_t lo, hi;
 };
@@ -390,16 +566,26 @@ extern "C" int ntp_reshard_grad(const ntp_tensor_spec_t* spec, int32_t src_tp, i
   if (st != NTP_OK) return st;
   int64_t n_units = 0;
   ntp::check_spec(spec, src_tp, dst_tp, &n_units);
+  std::vector<int64_t> su(src_tp), du(dst_tp);
+  for (int32_t r = 0; r < src_tp; ++r)
+    if ((st = ntp::shard_units(spec, n_units, src_tp, r, &su[r])) != NTP_OK) return st;
+  for (int32_t r = 0; r < dst_tp; ++r)
+    if ((st = ntp::shard_units(spec, n_units, dst_tp, r, &du[r])) != NTP_OK) return st;
+  return ntp::reshard_launch(spec, segs, su, du, src_shards, src_ld, dst_shards, dst_ld, stream);
+}
+
+int ntp::check_shards(const ntp_tensor_spec_t* spec, const std::vector<int64_t>& src_units,
+                      const std::vector<int64_t>& dst_units, const void* const* src_shards, const int64_t* src_ld,
+                      void* const* dst_shards, const int64_t* dst_ld) {
+  if (!src_shards || !dst_shards || !src_ld || !dst_ld) return NTP_ERR_INVALID_ARG;
   const int64_t esz = spec->elem_size;
   const bool by_rows = spec->partition_dim == 0;
-
-  // shard extents: shape, leading dimension, alignment and aliasing checks
-  auto extents = [&](int32_t tp, const void* const* ptrs, const int64_t* ld, std::vector<Extent>* out) -> int {
+  auto extents = [&](const std::vector<int64_t>& nunits, const void* const* ptrs, const int64_t* ld,
+                     std::vector<Extent>* out) -> int {
+    const int32_t tp = int32_t(nunits.size());
     out->assign(tp, Extent{0, 0});
     for (int32_t r = 0; r < tp; ++r) {
-      int64_t units = 0;
-      const int s2 = ntp::shard_units(spec, n_units, tp, r, &units);
-      if (s2 != NTP_OK) return s2;
+      const int64_t units = nunits[r];
       if (!ptrs[r] || units == 0) continue;
       const int64_t srows = by_rows ? units * spec->unit : spec->rows;
       const int64_t scols = by_rows ? spec->cols : units * spec->unit;
@@ -412,11 +598,23 @@ extern "C" int ntp_reshard_grad(const ntp_tensor_spec_t* spec, int32_t src_tp, i
     return NTP_OK;
   };
   std::vector<Extent> se, de;
-  if ((st = extents(src_tp, src_shards, src_ld, &se)) != NTP_OK) return st;
-  if ((st = extents(dst_tp, reinterpret_cast<const void* const*>(dst_shards), dst_ld, &de)) != NTP_OK) return st;
+  int st;
+  if ((st = extents(src_units, src_shards, src_ld, &se)) != NTP_OK) return st;
+  if ((st = extents(dst_units, reinterpret_cast<const void* const*>(dst_shards), dst_ld, &de)) != NTP_OK) return st;
   for (const Extent& a : se)
     for (const Extent& b : de)
       if (a.hi > a.lo && b.hi > b.lo && a.lo < b.hi && b.lo < a.hi) return NTP_ERR_INVALID_ARG;
+  return NTP_OK;
+}
+
+int ntp::reshard_launch(const ntp_tensor_spec_t* spec, const std::vector<ntp_segment_t>& segs,
+                        const std::vector<int64_t>& src_units, const std::vector<int64_t>& dst_units,
+                        const void* const* src_shards, const int64_t* src_ld, void* const* dst_shards,
+                        const int64_t* dst_ld, void* stream) {
+  const int st = check_shards(spec, src_units, dst_units, src_shards, src_ld, dst_shards, dst_ld);
+  if (st != NTP_OK) return st;
+  const int64_t esz = spec->elem_size;
+  const bool by_rows = spec->partition_dim == 0;
 
   hipStream_t hs = static_cast<hipStream_t>(stream);
 
@@ -614,6 +812,208 @@ extern "C" int ntp_reshard_grad(const ntp_tensor_spec_t* spec, int32_t src_tp, i
       ntp::timing_begin(stream, "reshard_copy", 0.0, bytes);
     }
     hipLaunchKernelGGL(reshard_copy_kernel, dim3(uint32_t(blocks)), dim3(kThreads), 0, hs, batch);
+    const bool ok = hipGetLastError() == hipSuccess;
+    ntp::timing_end(stream);
+    if (!ok) return NTP_ERR_LAUNCH;
+  }
+  return NTP_OK;
+}
+
+// ---- reshard plan between two unit -> rank maps (Sec. 3.1, Alg. 1; Appendix: precomputed splits) -----
+struct ntp_reshard_plan {
+  ntp_tensor_spec_t spec;
+  int32_t src_tp, dst_tp;
+  std::vector<ntp_segment_t> segs;           // destination order
+  std::vector<int64_t> src_units, dst_units;  // units per rank
+  std::vector<int64_t> splits;                // [src_tp x dst_tp] units from rank r to rank s
+  std::vector<ntp_unit_source_t> table;       // per destination unit, destination shards one after the other
+  std::vector<int64_t> dst_first;             // first table entry of each destination shard
+  // run table of the gather kernel (column-partitioned 4-byte elements only)
+  bool runs_ok = false;
+  std::vector<RunDev> runs;                   // runs of all destination shards, one shard after the other
+  std::vector<int64_t> runs_first;            // first run of each destination shard
+  std::vector<uint16_t> run_of_unit;          // per destination unit (indexed like `table`): run number in its shard
+  void* dev_table = nullptr;                  // `runs` then `run_of_unit` on device `dev`, made by the first run
+  int dev = -1;
+};
+
+extern "C" int ntp_reshard_plan_create(const ntp_tensor_spec_t* spec, int64_t map_len, int32_t src_tp,
+                                       const int32_t* src_rank_of_unit, int32_t dst_tp,
+                                       const int32_t* dst_rank_of_unit, ntp_reshard_plan_t** plan) {
+  if (!plan) return NTP_ERR_INVALID_ARG;
+  *plan = nullptr;
+  int64_t n_units = 0;
+  int st = ntp::check_spec(spec, 1, 1, &n_units);
+  if (st != NTP_OK) return st;
+  if (spec->kind != NTP_KIND_PLAIN || n_units > 0x7fffffffll || map_len != n_units) return NTP_ERR_INVALID_ARG;
+  ntp_reshard_plan* p = new ntp_reshard_plan;
+  p->spec = *spec;
+  p->src_tp = src_tp;
+  p->dst_tp = dst_tp;
+  st = ntp::build_segments_mapped(n_units, src_tp, src_rank_of_unit, dst_tp, dst_rank_of_unit, &p->segs, &p->src_units,
+                                  &p->dst_units);
+  if (st != NTP_OK) {
+    delete p;
+    return st;
+  }
+  p->splits.assign(size_t(src_tp) * size_t(dst_tp), 0);
+  p->dst_first.assign(size_t(dst_tp) + 1, 0);
+  for (int32_t s = 0; s < dst_tp; ++s) p->dst_first[s + 1] = p->dst_first[s] + p->dst_units[s];
+  p->table.resize(size_t(n_units));
+  for (const ntp_segment_t& g : p->segs) {
+    p->splits[size_t(g.src_rank) * dst_tp + g.dst_rank] += g.units;
+    for (int64_t i = 0; i < g.units; ++i)
+      p->table[size_t(p->dst_first[g.dst_rank] + g.dst_unit + i)] = ntp_unit_source_t{g.src_rank, int32_t(g.src_unit + i)};
+  }
+  // run table: the sub-shards are the runs
+  if (spec->partition_dim == 1 && spec->elem_size == 4) {
+    const int64_t ub = int64_t(spec->unit) * 4;
+    p->runs_first.assign(size_t(dst_tp) + 1, 0);
+    p->run_of_unit.resize(size_t(n_units));
+    p->runs_ok = true;
+    int32_t cur = 0;
+    for (const ntp_segment_t& g : p->segs) {
+      while (cur < g.dst_rank) p->runs_first[size_t(++cur)] = int64_t(p->runs.size());
+      const int64_t number = int64_t(p->runs.size()) - p->runs_first[size_t(cur)];
+      const int64_t end = (g.dst_unit + g.units) * ub, so = g.src_unit * ub;
+      if (number > 0xffff || end > 0xffffffffll || so > 0xffffffffll) p->runs_ok = false;
+      p->runs.push_back(RunDev{uint32_t(g.dst_unit * ub), uint32_t(end), uint32_t(so), uint32_t(g.src_rank)});
+      for (int64_t i = 0; i < g.units; ++i) p->run_of_unit[size_t(p->dst_first[g.dst_rank] + g.dst_unit + i)] = uint16_t(number);
+    }
+    while (cur < dst_tp) p->runs_first[size_t(++cur)] = int64_t(p->runs.size());
+  }
+  *plan = p;
+  return NTP_OK;
+}
+
+extern "C" int ntp_reshard_plan_destroy(ntp_reshard_plan_t* plan) {
+  if (!plan) return NTP_OK;
+  if (plan->dev_table) {
+    int cur = -1;
+    (void)hipGetDevice(&cur);
+    if (cur != plan->dev) (void)hipSetDevice(plan->dev);
+    (void)hipFree(plan->dev_table);
+    if (cur != plan->dev && cur >= 0) (void)hipSetDevice(cur);
+  }
+  delete plan;
+  return NTP_OK;
+}
+
+extern "C" int ntp_reshard_plan_segments(const ntp_reshard_plan_t* plan, ntp_segment_t* out, int64_t max_segments,
+                                         int64_t* count) {
+  if (!plan || !count || max_segments < 0 || (max_segments > 0 && !out)) return NTP_ERR_INVALID_ARG;
+  *count = int64_t(plan->segs.size());
+  for (int64_t i = 0; i < std::min<int64_t>(max_segments, *count); ++i) out[i] = plan->segs[size_t(i)];
+  return NTP_OK;
+}
+
+extern "C" int ntp_reshard_plan_splits(const ntp_reshard_plan_t* plan, int64_t* units) {
+  if (!plan || !units) return NTP_ERR_INVALID_ARG;
+  std::copy(plan->splits.begin(), plan->splits.end(), units);
+  return NTP_OK;
+}
+
+extern "C" int ntp_reshard_plan_table(const ntp_reshard_plan_t* plan, ntp_unit_source_t* out, int64_t max_units,
+                                      int64_t* count) {
+  if (!plan || !count || max_units < 0 || (max_units > 0 && !out)) return NTP_ERR_INVALID_ARG;
+  *count = int64_t(plan->table.size());
+  for (int64_t i = 0; i < std::min<int64_t>(max_units, *count); ++i) out[i] = plan->table[size_t(i)];
+  return NTP_OK;
+}
+
+namespace {
+
+// Whether the run-table kernel can take this call with blocks of `block` bytes.
+bool units_path_ok(const ntp_reshard_plan* p, const void* const* src_shards, const int64_t* src_ld,
+                   void* const* dst_shards, const int64_t* dst_ld, int64_t block) {
+  const ntp_tensor_spec_t& sp = p->spec;
+  if (!p->runs_ok || sp.rows == 0 || getenv("NTP_RESHARD_NO_TABLE")) return false;
+  if (p->src_tp > kMaxRanks || sp.rows > 0x7fffffffll) return false;
+  for (int32_t r = 0; r < p->src_tp; ++r) {
+    if (p->src_units[r] == 0) continue;
+    if (!src_shards[r] || src_ld[r] * 4 >= (int64_t(1) << 32)) return false;
+  }
+  bool any = false;
+  for (int32_t s = 0; s < p->dst_tp; ++s) {
+    if (p->dst_units[s] == 0 || !dst_shards[s]) continue;
+    const int64_t W = p->dst_units[s] * sp.unit * 4;
+    const int64_t n_runs = p->runs_first[s + 1] - p->runs_first[s];
+    if (dst_ld[s] * 4 != W || (reinterpret_cast<uintptr_t>(dst_shards[s]) & 63) != 0 ||
+        (block + W + 16) * W > (int64_t(1) << 32) ||
+        n_runs * int64_t(sizeof(RunLds)) + p->dst_units[s] * 2 + 16 + int64_t(kWaves * kQueueCap * sizeof(uint2)) > int64_t(kUnitLdsMax))
+      return false;
+    any = true;
+  }
+  return any;
+}
+
+}  // namespace
+
+extern "C" int ntp_reshard_plan_run(ntp_reshard_plan_t* plan, const void* const* src_shards, const int64_t* src_ld,
+                                    void* const* dst_shards, const int64_t* dst_ld, void* stream) {
+  if (!plan) return NTP_ERR_INVALID_ARG;
+  int st = ntp::check_shards(&plan->spec, plan->src_units, plan->dst_units, src_shards, src_ld, dst_shards, dst_ld);
+  if (st != NTP_OK) return st;
+  int64_t block = 16384;
+  if (const char* e = getenv("NTP_RESHARD_TABLE_BLOCK")) block = std::min<int64_t>(1 << 20, std::max<int64_t>(1024, atoll(e) & ~63ll));
+  if (!units_path_ok(plan, src_shards, src_ld, dst_shards, dst_ld, block))
+    return ntp::reshard_launch(&plan->spec, plan->segs, plan->src_units, plan->dst_units, src_shards, src_ld, dst_shards,
+                               dst_ld, stream);
+
+  int cur = -1;
+  if (hipGetDevice(&cur) != hipSuccess) return NTP_ERR_LAUNCH;
+  if (!plan->dev_table) {
+    // first run: the table goes to the current device (allocates and waits for the copy)
+    const size_t runs_bytes = plan->runs.size() * sizeof(RunDev), idx_bytes = plan->run_of_unit.size() * sizeof(uint16_t);
+    if (hipMalloc(&plan->dev_table, runs_bytes + idx_bytes) != hipSuccess) {
+      plan->dev_table = nullptr;
+      return NTP_ERR_LAUNCH;
+    }
+    if (hipMemcpy(plan->dev_table, plan->runs.data(), runs_bytes, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(static_cast<char*>(plan->dev_table) + runs_bytes, plan->run_of_unit.data(), idx_bytes,
+                  hipMemcpyHostToDevice) != hipSuccess) {
+      (void)hipFree(plan->dev_table);
+      plan->dev_table = nullptr;
+      return NTP_ERR_LAUNCH;
+    }
+    plan->dev = cur;
+  } else if (cur != plan->dev) {
+    return NTP_ERR_INVALID_ARG;  // the plan's table lives on another device
+  }
+
+  const ntp_tensor_spec_t& sp = plan->spec;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  UnitBatch batch{};
+  batch.runs = static_cast<const RunDev*>(plan->dev_table);
+  batch.run_of_unit = reinterpret_cast<const uint16_t*>(static_cast<const char*>(plan->dev_table) + plan->runs.size() * sizeof(RunDev));
+  batch.rows = uint32_t(sp.rows);
+  batch.unit_bytes = uint32_t(sp.unit) * 4u;
+  batch.block_bytes = uint32_t(block);
+  for (int32_t r = 0; r < plan->src_tp; ++r)
+    batch.src[r] = UnitSrc{static_cast<const char*>(src_shards[r]), uint64_t(src_ld[r]) * 4u};
+  int32_t s = 0;
+  while (s < plan->dst_tp) {
+    batch.ndst = 0;
+    int64_t nblk = 0;
+    uint32_t lds = 0;
+    double bytes = 0.0;
+    for (; s < plan->dst_tp && batch.ndst < uint32_t(kUnitDsts); ++s) {
+      if (plan->dst_units[s] == 0 || !dst_shards[s]) continue;
+      const int64_t total = sp.rows * plan->dst_units[s] * sp.unit * 4;
+      const uint32_t n_runs = uint32_t(plan->runs_first[s + 1] - plan->runs_first[s]);
+      batch.dst[batch.ndst++] = UnitDst{static_cast<char*>(dst_shards[s]), uint32_t(plan->dst_first[s]), uint32_t(plan->dst_units[s]),
+                                        uint32_t(plan->runs_first[s]), n_runs};
+      nblk = std::max(nblk, (total + block - 1) / block);
+      lds = std::max(lds, unit_lds_bytes(n_runs, uint32_t(plan->dst_units[s])));
+      bytes += 2.0 * double(total);
+    }
+    if (batch.ndst == 0) break;
+    // workgroups per destination shard: enough of them to fill the chip, each walking over several blocks
+    const int64_t per_cu = getenv("NTP_RESHARD_TABLE_WGS") ? std::max(1, atoi(getenv("NTP_RESHARD_TABLE_WGS"))) : int(kUnitBlocksPerCu);
+    const int64_t slots = std::max<int64_t>(1, std::min<int64_t>(nblk, (256 * per_cu + batch.ndst - 1) / batch.ndst));
+    const uint64_t blocks = uint64_t(slots) * batch.ndst;
+    if (ntp::timing_on()) ntp::timing_begin(stream, "reshard_table", 0.0, bytes);
+    hipLaunchKernelGGL(reshard_units_kernel, dim3(uint32_t(blocks)), dim3(kThreads), lds, hs, batch);
     const bool ok = hipGetLastError() == hipSuccess;
     ntp::timing_end(stream);
     if (!ok) return NTP_ERR_LAUNCH;

@@ -1,0 +1,218 @@
+"""Bit-exact parity of the plan-based reshard (layouts of the comp / sync rank assignment, Sec. 3.1,
+Alg. 1) against the oracle's unit-by-unit reshard, and the MLP shard on a non-contiguous set of
+columns, on a real MI355X."""
+import os
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import ntp_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(f"[gpu-case] {msg}", file=sys.stderr, flush=True)
+
+
+def _logical(rows, cols, dtype=np.uint32, seed=0):
+    g = np.random.default_rng(seed)
+    return g.integers(0, np.iinfo(dtype).max, size=(rows, cols), dtype=dtype)
+
+
+def _run(G, pd, unit, smap, src_tp, dmap, dst_tp, pad_src=0, pad_dst=0, misalign=0, absent_src=(), runs=1):
+    """Cut G by smap, reshard to dmap on the GPU; returns (got, want)."""
+    import torch
+    import paper_2504_06095_amd as N
+    src_np = [O.cut_shard_mapped(G, pd, unit, smap, src_tp, r) for r in range(src_tp)]
+    want = O.reshard_mapped(src_np, pd, unit, smap, src_tp, dmap, dst_tp)
+    tdt = {4: torch.int32, 2: torch.int16}[G.dtype.itemsize]
+    sdt = {4: np.int32, 2: np.int16}[G.dtype.itemsize]
+
+    def dev(arr, pad, fill):
+        r, c = arr.shape
+        flat = torch.full((r * (c + pad) + misalign + 8,), fill, dtype=tdt, device="cuda")
+        view = flat[misalign: misalign + r * (c + pad)].view(r, c + pad)[:, :c]
+        if arr.size:
+            view.copy_(torch.from_numpy(np.ascontiguousarray(arr).view(sdt)).cuda())
+        return view, flat
+
+    src = [None if r in absent_src else dev(s, pad_src, 0x11)[0] for r, s in enumerate(src_np)]
+    dst_pairs = [dev(np.zeros_like(w), pad_dst, 0x22) for w in want]
+    dst = [p[0] for p in dst_pairs]
+    spec = N.tensor_spec(G.shape[0], G.shape[1], pd, unit, G.dtype.itemsize)
+    plan = N.ntp_reshard_plan_create(spec, src_tp, smap, dst_tp, dmap)
+    for _ in range(runs):
+        plan.ntp_reshard_plan_run(src, dst)
+    torch.cuda.synchronize()
+    plan.destroy()
+    got = [d.cpu().numpy().view(G.dtype) for d in dst]
+    for (view, flat), w in zip(dst_pairs, want):
+        r, c = w.shape
+        body = flat[misalign: misalign + r * (c + pad_dst)].view(r, c + pad_dst)
+        assert (body[:, c:] == 0x22).all() and (flat[:misalign] == 0x22).all()
+        assert (flat[misalign + r * (c + pad_dst):] == 0x22).all()
+    return got, want
+
+
+# rows, units, unit, full tp, reduced tp, partition dim, pad_src, pad_dst, misalign
+CASES = [
+    (64, 12, 1, 4, 3, 1, 0, 0, 0),        # the hand-worked example
+    (257, 12000, 1, 32, 30, 1, 0, 0, 0),  # the paper's 375 + 25 units per sync rank; table kernel, several blocks
+    (96, 53248, 1, 72, 71, 1, 0, 0, 0),   # config-5 widths
+    (300, 1000, 1, 8, 7, 1, 0, 0, 0),     # k not a multiple of either degree
+    (300, 1000, 1, 8, 5, 1, 0, 0, 0),     # three offload ranks
+    (33, 90, 16, 8, 6, 1, 0, 0, 0),       # units of 16 elements (heads) on columns
+    (40, 90, 3, 8, 6, 1, 0, 0, 0),        # units of 3 elements: chunks span units
+    (1000, 5, 1, 4, 2, 1, 0, 0, 0),       # rows shorter than a 16-byte chunk
+    (3, 7, 1, 3, 2, 1, 0, 0, 0),          # shards smaller than a chunk
+    (128, 1000, 1, 8, 7, 1, 3, 0, 0),     # padded source rows: still the table kernel
+    (128, 1000, 1, 8, 7, 1, 0, 5, 0),     # padded destination rows: sub-shard by sub-shard
+    (128, 1000, 1, 8, 7, 1, 0, 0, 1),     # buffers off 64-byte alignment: sub-shard by sub-shard
+    (12000, 64, 1, 32, 30, 0, 0, 0, 0),   # row-partitioned: dense row ranges
+    (1000, 33, 1, 8, 7, 0, 2, 3, 1),      # row-partitioned, padded and misaligned
+    (24 * 16, 40, 16, 8, 6, 0, 0, 0, 0),  # row-partitioned heads
+    (64, 5, 1, 8, 1, 1, 0, 0, 0),         # fewer units than ranks, one sync rank
+    (64, 100, 1, 8, 8, 1, 0, 0, 0),       # same degree: every unit stays
+]
+
+
+@pytest.mark.parametrize("back", [False, True], ids=["comp-to-sync", "sync-to-comp"])
+@pytest.mark.parametrize("rows,k,unit,t,tr,pd,pad_src,pad_dst,misalign", CASES)
+def test_plan_run_bit_exact(rows, k, unit, t, tr, pd, pad_src, pad_dst, misalign, back):
+    _say(f"plan_run rows={rows} k={k} unit={unit} t={t} t'={tr} pd={pd} pads {pad_src},{pad_dst} mis {misalign} back={back}")
+    comp, sync = O.comp_sync_plan(k, t, tr)
+    smap, a, dmap, b = (sync, tr, comp, t) if back else (comp, t, sync, tr)
+    G = _logical(rows, k * unit) if pd == 1 else _logical(k * unit, rows)
+    got, want = _run(G, pd, unit, smap, a, dmap, b, pad_src, pad_dst, misalign, runs=2)
+    for s in range(b):
+        assert np.array_equal(got[s], want[s]), f"dst rank {s}"
+
+
+def test_plan_run_without_the_table_kernel(monkeypatch):
+    _say("plan_run, table kernel switched off")
+    monkeypatch.setenv("NTP_RESHARD_NO_TABLE", "1")
+    comp, sync = O.comp_sync_plan(1000, 8, 7)
+    G = _logical(200, 1000)
+    got, want = _run(G, 1, 1, comp, 8, sync, 7)
+    for s in range(7):
+        assert np.array_equal(got[s], want[s])
+
+
+@pytest.mark.parametrize("block", [1024, 4096, 65536])
+def test_plan_run_block_sizes(monkeypatch, block):
+    _say(f"plan_run, table kernel block {block}")
+    monkeypatch.setenv("NTP_RESHARD_TABLE_BLOCK", str(block))
+    comp, sync = O.comp_sync_plan(999, 8, 6)
+    G = _logical(123, 999)
+    for smap, a, dmap, b in ((comp, 8, sync, 6), (sync, 6, comp, 8)):
+        got, want = _run(G, 1, 1, smap, a, dmap, b)
+        for s in range(b):
+            assert np.array_equal(got[s], want[s])
+
+
+def test_plan_run_random_maps_and_2byte_elements():
+    _say("plan_run random maps")
+    g = np.random.default_rng(5)
+    for it in range(6):
+        k, a, b = int(g.integers(1, 400)), int(g.integers(1, 9)), int(g.integers(1, 9))
+        smap = [int(x) for x in g.integers(0, a, k)]
+        dmap = [int(x) for x in g.integers(0, b, k)]
+        unit = int(g.integers(1, 5))
+        for pd in (0, 1):
+            for dt in (np.uint32, np.uint16):
+                G = _logical(77, k * unit, dt, it) if pd == 1 else _logical(k * unit, 77, dt, it)
+                got, want = _run(G, pd, unit, smap, a, dmap, b)
+                for s in range(b):
+                    assert np.array_equal(got[s], want[s]), (it, pd, dt, s)
+
+
+def test_plan_run_one_gpu_share():
+    import torch
+    import paper_2504_06095_amd as N
+    _say("plan_run with absent source shards")
+    k, t, tr, rows = 400, 8, 7, 50
+    comp, sync = O.comp_sync_plan(k, t, tr)
+    G = _logical(rows, k)
+    src_np = [O.cut_shard_mapped(G, 1, 1, comp, t, r) for r in range(t)]
+    want = O.reshard_mapped(src_np, 1, 1, comp, t, sync, tr)
+    spec = N.tensor_spec(rows, k, 1, 1, 4)
+    plan = N.ntp_reshard_plan_create(spec, t, comp, tr, sync)
+    # only the offload rank's shard is here: what it sends lands, everything else stays untouched
+    src = [None] * t
+    src[7] = torch.from_numpy(src_np[7].view(np.int32)).cuda()
+    dst = [torch.full(w.shape, -1, dtype=torch.int32, device="cuda") for w in want]
+    plan.ntp_reshard_plan_run(src, dst)
+    torch.cuda.synchronize()
+    ids = O.units_of_rank(sync, tr)
+    for s in range(tr):
+        got = dst[s].cpu().numpy().view(np.uint32)
+        from_7 = np.array([comp[u] == 7 for u in ids[s]])
+        assert np.array_equal(got[:, from_7], want[s][:, from_7])
+        assert (got[:, ~from_7] == 0xFFFFFFFF).all()
+    # overlapping source and destination are refused before anything is enqueued
+    full = [torch.from_numpy(x.view(np.int32)).cuda() for x in src_np]
+    buf = torch.zeros(rows * (want[0].shape[1] + src_np[0].shape[1]), dtype=torch.int32, device="cuda")
+    full[0] = buf[: src_np[0].size].view(src_np[0].shape)
+    dst[0] = buf[: want[0].size].view(want[0].shape)
+    with pytest.raises(N.NtpError) as e:
+        plan.ntp_reshard_plan_run(full, dst)
+    assert e.value.status == N.binding.NTP_ERR_INVALID_ARG
+
+
+def test_mlp_shard_on_the_comp_layout_sums_to_the_layer():
+    """Each rank of the healthy replica computes on the (non-contiguous) columns Alg. 1 gives it: every
+    shard matches the oracle's shard, the partial outputs and input gradients still sum to the unsharded
+    layer (Sec. 3.1: any column may sit in any shard), and the weight-gradient shards, resharded to
+    the sync layout on the GPU, are the sync-layout cut of the unsharded gradients."""
+    import torch
+    import paper_2504_06095_amd as N
+    from paper_2504_06095_amd import inputs as I
+    from tests import helpers as Hh
+    _say("mlp shard fwd/bwd on the comp layout + reshard to the sync layout")
+    M, H, n, t, tr = 384, 256, 1000, 8, 6
+    X_bits, X = I.normal_bf16(3, "map.X", (M, H), I.ACT_STD)
+    At_bits, At = I.normal_bf16(3, "map.A_t", (n, H), I.WEIGHT_STD)
+    B_bits, B = I.normal_bf16(3, "map.B", (n, H), I.WEIGHT_STD)
+    dZ_bits, dZ = I.normal_bf16(3, "map.dZ", (M, H), I.ACT_STD)
+    X64, dZ64, A64, B64 = X.astype(np.float64), dZ.astype(np.float64), At.astype(np.float64).T.copy(), B.astype(np.float64)
+    comp, sync = O.comp_sync_plan(n, t, tr)
+    ids = O.units_of_rank(comp, t)
+    Xd, dZd = Hh.to_dev_bf16(X_bits), Hh.to_dev_bf16(dZ_bits)
+    z_sum, dx_sum = np.zeros((M, H)), np.zeros((M, H))
+    dB_shards = []
+    for r in range(t):
+        idx = np.array(ids[r])
+        nr = len(idx)
+        Atd, Bd = Hh.to_dev_bf16(np.ascontiguousarray(At_bits[idx])), Hh.to_dev_bf16(np.ascontiguousarray(B_bits[idx]))
+        mk = lambda rr, cc: torch.full((rr, cc), float("nan"), dtype=torch.bfloat16, device="cuda")
+        ld = Hh.round_up(nr, 8)  # leading dimensions of bf16 matrices are multiples of 8 elements
+        P, Y, dP, Z, dX = mk(M, ld)[:, :nr], mk(M, ld)[:, :nr], mk(M, ld)[:, :nr], mk(M, H), mk(M, H)
+        dA_t = torch.full((nr, H), float("nan"), dtype=torch.float32, device="cuda")
+        dB = torch.full((nr, H), float("nan"), dtype=torch.float32, device="cuda")
+        N.ntp_mlp_shard_fwd(Xd, Atd, Bd, P, Y, Z, nr)
+        N.ntp_mlp_shard_bwd(dZd, Xd, Atd, Bd, P, Y, dP, dX, dA_t, dB, nr, 0, False)
+        torch.cuda.synchronize()
+        wP, wY, wZ = O.mlp_shard_fwd(X64, A64[:, idx], B64[idx])
+        wdP, wdX, wdA, wdB = O.mlp_shard_bwd(dZ64, X64, A64[:, idx], B64[idx])
+        for name, got, want in (("P", P, wP), ("Y", Y, wY), ("Z", Z, wZ), ("dP", dP, wdP), ("dX", dX, wdX)):
+            assert Hh.rel_err(Hh.dev_bf16_to_f64(got), want) <= Hh.TOL, (r, name)
+        assert Hh.rel_err(dA_t.cpu().numpy().astype(np.float64), wdA.T) <= Hh.TOL, (r, "dA_t")
+        assert Hh.rel_err(dB.cpu().numpy().astype(np.float64), wdB) <= Hh.TOL, (r, "dB")
+        z_sum += Hh.dev_bf16_to_f64(Z)
+        dx_sum += Hh.dev_bf16_to_f64(dX)
+        dB_shards.append(dB)
+    _, _, Zfull = O.mlp_unsharded_fwd(X64, A64, B64)
+    assert Hh.rel_err(z_sum, Zfull) <= Hh.TOL
+    dXfull, _, dBfull = O.mlp_unsharded_bwd(dZ64, X64, A64, B64)
+    assert Hh.rel_err(dx_sum, dXfull) <= Hh.TOL
+    # pre-sync reshard of dB (rows partitioned): comp layout -> sync layout, then compare with the cut of the full gradient
+    spec = N.tensor_spec(n, H, 0, 1, 4)
+    plan = N.ntp_reshard_plan_create(spec, t, comp, tr, sync)
+    dst = [torch.empty(O.shard_plan(n, tr, s)[1], H, dtype=torch.float32, device="cuda") for s in range(tr)]
+    plan.ntp_reshard_plan_run(dB_shards, dst)
+    torch.cuda.synchronize()
+    for s in range(tr):
+        off, w = O.shard_plan(n, tr, s)
+        assert Hh.rel_err(dst[s].cpu().numpy().astype(np.float64), dBfull[off: off + w]) <= Hh.TOL, s
