@@ -355,8 +355,9 @@ __global__ __launch_bounds__(kThreads) void reshard_dense_kernel(const DenseBatc
 // A destination shard is a sequence of runs (units that follow each other in one source shard too);
 // the plan keeps, in device memory, the runs of every destination shard and for every destination
 // unit the number of its run.  A workgroup serves one destination shard: it copies both tables into
-// LDS once (runs joined with this call's source pointers) and then walks over its share of the
-// shard's blocks.  A chunk that lies inside one run is moved by one 16-byte load and store.  The
+// LDS (runs joined with this call's source pointers) and then takes one block of the shard, or walks
+// over several when the shard is very large.  A chunk that lies inside one run is moved by one
+// 16-byte load and store.  The
 // other chunks (they straddle a run boundary or a row end, or are the short last chunk of the
 // shard) are put on a queue that each wavefront keeps in LDS, and are put together word by word when
 // the queue has filled up, so that this slower code runs with most lanes in use even when few
@@ -364,10 +365,10 @@ __global__ __launch_bounds__(kThreads) void reshard_dense_kernel(const DenseBatc
 // (block + W + 16) * W <= 2^32 for the row width W in bytes, source strides below 2^32 bytes, at
 // most kMaxRanks source ranks, at most 65535 runs per shard.
 constexpr int kMaxRanks = 96;
-constexpr int kUnitDsts = 96;               // destination shards per launch (the argument block stays below 4 KiB)
+constexpr int kUnitDsts = 16;               // destination shards per launch: few write streams at a time measured fastest
 constexpr uint32_t kUnitLdsMax = 60 << 10;  // bytes of LDS a workgroup may ask for
 constexpr uint32_t kQueueCap = 512;         // queued chunks per wavefront
-constexpr uint32_t kUnitBlocksPerCu = 8;
+constexpr uint32_t kUnitBlocksPerCu = 256;  // workgroups per compute unit and launch before they start to walk over several blocks
 
 struct UnitSrc {
   const char* base;  // first byte of the source shard
@@ -405,8 +406,9 @@ __host__ __device__ inline uint32_t unit_lds_bytes(uint32_t n_runs, uint32_t n_u
 
 __global__ __launch_bounds__(kThreads) void reshard_units_kernel(const UnitBatch batch) {
   extern __shared__ __align__(16) unsigned char unit_lds[];
-  const uint32_t slot = blockIdx.x / batch.ndst, di = blockIdx.x - slot * batch.ndst;
+  // consecutive workgroups take consecutive blocks of one destination shard
   const uint32_t nslots = gridDim.x / batch.ndst;
+  const uint32_t di = blockIdx.x / nslots, slot = blockIdx.x - di * nslots;
   const UnitDst& dd = batch.dst[di];
   const uint32_t ub = batch.unit_bytes, blk = batch.block_bytes;
   const uint32_t W = dd.n_units * ub;
@@ -1009,8 +1011,9 @@ extern "C" int ntp_reshard_plan_run(ntp_reshard_plan_t* plan, const void* const*
     }
     if (batch.ndst == 0) break;
     // workgroups per destination shard: enough of them to fill the chip, each walking over several blocks
-    const int64_t per_cu = getenv("NTP_RESHARD_TABLE_WGS") ? std::max(1, atoi(getenv("NTP_RESHARD_TABLE_WGS"))) : int(kUnitBlocksPerCu);
-    const int64_t slots = std::max<int64_t>(1, std::min<int64_t>(nblk, (256 * per_cu + batch.ndst - 1) / batch.ndst));
+    // workgroups per destination shard: one per block, or fewer that walk over several blocks each when
+    // the shards are very large (the tables are copied into LDS once per workgroup)
+    const int64_t slots = std::max<int64_t>(1, std::min<int64_t>(nblk, (256 * int64_t(kUnitBlocksPerCu) + batch.ndst - 1) / batch.ndst));
     const uint64_t blocks = uint64_t(slots) * batch.ndst;
     if (ntp::timing_on()) ntp::timing_begin(stream, "reshard_table", 0.0, bytes);
     hipLaunchKernelGGL(reshard_units_kernel, dim3(uint32_t(blocks)), dim3(kThreads), lds, hs, batch);
