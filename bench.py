@@ -126,29 +126,35 @@ def kernel_table(N, torch, fn, steps):
 
 
 def cpu_baseline(s):
-    """The oracle's MLP shard forward + backward on the host cores, same inputs, all tokens."""
+    """The oracle's GEMM work of the step on the host cores, same inputs, all tokens: MLP shard and
+    attention projection shard, forward + backward, in float64.  (The reshard moves bits and is left out.)"""
     import numpy as np
     from oracle import ntp_oracle as O
     f64 = lambda t: t.float().cpu().numpy().astype(np.float64)
     X, dZ, A_i, B_i = f64(s["X"]), f64(s["dZ"]), f64(s["A_t"]).T.copy(), f64(s["B"])
+    Wqkv_i, Wo_i, C, dQKV = f64(s["Wqkv"]).T.copy(), f64(s["Wo"]), f64(s["C"]), f64(s["dQKV"])
     t0 = time.perf_counter()
     P, Y, Z = O.mlp_shard_fwd(X, A_i, B_i)
     dP, dX, dA, dB = O.mlp_shard_bwd(dZ, X, A_i, B_i)
+    QKV, Z2 = O.attn_proj_shard_fwd(X, Wqkv_i, C, Wo_i)
+    dC, dX2, dWqkv, dWo = O.attn_proj_shard_bwd(dZ, dQKV, X, C, Wqkv_i, Wo_i)
     dt = time.perf_counter() - t0
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"] or [1])
     except Exception:
         cores = os.cpu_count() or 1
-    # oracle flops: forward 2 GEMMs, backward recomputes P (1) + 4 GEMMs = 7 GEMMs; report on the 6 algorithmic ones
     err = {}
     for name, want, got in (("Z", Z, s["Z"]), ("dX", dX, s["dX"]), ("dA_t", dA.T, s["dA_t"]), ("dB", dB, s["dB"]),
-                            ("Y", Y, s["Y"]), ("dP", dP, s["dP"])):
+                            ("Y", Y, s["Y"]), ("dP", dP, s["dP"]), ("QKV", QKV, s["QKV"]), ("Zattn", Z2, s["Z2"]),
+                            ("dC", dC, s["dC"]), ("dXattn", dX2, s["dX2"]), ("dWqkv", dWqkv.T, s["dWqkv"]),
+                            ("dWo", dWo, s["dWo"])):
         g = got.float().cpu().numpy().astype(np.float64)
         err[name] = float(np.abs(g - want).max() / np.abs(want).max())
-    return dict(value=s["mlp_flops"] / dt / 1e12, unit="TFLOP/s", cores=int(cores), kind="oracle",
-                sample=f"MLP shard fwd+bwd of the step (all {M} tokens, float64, {dt:.1f} s); attention projections "
-                       "and reshard not included", seconds=dt), err
+    return dict(value=s["gemm_flops"] / dt / 1e12, unit="TFLOP/s", cores=int(cores), kind="oracle",
+                sample=f"all GEMM work of one step (MLP shard + attention projection shard, fwd+bwd, all {M} tokens, "
+                       f"float64, {dt:.1f} s of host time: the whole workload, no sampling needed); reshard not included",
+                seconds=dt), err
 
 
 def reshard_stress(torch, N):
@@ -196,6 +202,48 @@ def reshard_stress(torch, N):
     return out
 
 
+def mapped_reshard_stress(torch, N):
+    """The same 405B-shape fc1 / fc2 / out-proj gradients between the layouts of the comp / sync rank
+    assignment (Sec. 3.1, Alg. 1) for a healthy TP-72 replica that synchronises with TP-71 replicas:
+    compute layout (72 ranks, non-contiguous) -> sync layout (71 contiguous shards) and back.  Plans are
+    built once, outside the timed region."""
+    Hh, F, nq, d, t, tr = 16384, 53248, 128, 128, 72, 71
+    tensors = [(Hh, F, 1, 1), (F, Hh, 0, 1), (nq * d, Hh, 0, d)]  # rows, cols, partition_dim, unit
+    jobs = []
+    total = 0.0
+    for rows, cols, pd, unit in tensors:
+        k = (cols if pd else rows) // unit
+        comp, sync = N.ntp_comp_sync_plan(k, t, tr)
+        spec = N.tensor_spec(rows, cols, pd, unit, 4)
+
+        def shards(rank_of_unit, tp):
+            cnt = [0] * tp
+            for r in rank_of_unit:
+                cnt[r] += 1
+            return [torch.empty((rows, c * unit) if pd else (c * unit, cols), dtype=torch.float32,
+                                device="cuda").normal_(0, 1e-3) for c in cnt]
+        sc, ss = shards(comp, t), shards(sync, tr)
+        jobs.append((N.ntp_reshard_plan_create(spec, t, comp, tr, sync), N.ntp_reshard_plan_create(spec, tr, sync, t, comp),
+                     sc, ss))
+        total += 2.0 * 4 * rows * cols
+    out = {}
+    for key, fwd in (("comp_to_sync", True), ("sync_to_comp", False)):
+        def run():
+            for p_cs, p_sc, sc, ss in jobs:
+                if fwd:
+                    p_cs.ntp_reshard_plan_run(sc, ss)
+                else:
+                    p_sc.ntp_reshard_plan_run(ss, sc)
+        for _ in range(2):
+            run()
+        ms = timed(torch, run, 5)
+        out[key] = dict(ms=ms, GBps=total / ms / 1e6, bytes=total)
+    for j in jobs:
+        j[0].destroy()
+        j[1].destroy()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -203,6 +251,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-reshard-stress", action="store_true")
+    ap.add_argument("--no-mapped-reshard", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB dense copy (calibration_copy_kernel): the yardstick for profiler byte counters")
     args = ap.parse_args()
@@ -278,6 +327,14 @@ def main():
         out["reshard_roofline"] = dict(bound="hbm", workload="c5: 405B-shape layer dW fp32, all ranks, TP 71<->72",
                                        achieved=worst["GBps"], peak=HBM_PEAK_GBPS, unit="GB/s",
                                        frac=worst["GBps"] / HBM_PEAK_GBPS, traffic=None, directions=st)
+    if not args.no_mapped_reshard:
+        st = mapped_reshard_stress(torch, N)
+        worst = min(st.values(), key=lambda v: v["GBps"])
+        out["mapped_reshard_roofline"] = dict(
+            bound="hbm", workload="405B-shape fc1/fc2/out-proj dW fp32, all ranks, comp layout (TP 72) <-> sync layout (TP 71) "
+                                  "of the comp/sync rank assignment",
+            achieved=worst["GBps"], peak=HBM_PEAK_GBPS, unit="GB/s", frac=worst["GBps"] / HBM_PEAK_GBPS, traffic=None,
+            directions=st)
     if not args.no_cpu_baseline:
         fn()  # make sure the device buffers hold this step's results
         torch.cuda.synchronize()
