@@ -98,6 +98,29 @@ def step(N, s):
         N.ntp_reshard_grad(spec, T_RED, T_FULL, srcs, dsts)
 
 
+def fused_state(N, s):
+    """Row segments of this rank's four gradients in the destination (TP 8) shards of the step."""
+    K = N.binding
+    specs = [(FFN, 1, K.NTP_KIND_PLAIN, 0, 0), (FFN, 1, K.NTP_KIND_PLAIN, 0, 0),
+             (3 * HEADS * HEAD_DIM, HEAD_DIM, K.NTP_KIND_QKV_GQA, HEADS, HEADS), (HEADS * HEAD_DIM, HEAD_DIM, K.NTP_KIND_PLAIN, 0, 0)]
+    segs = []
+    for (rows, unit, kind, q, kv), (_, _, dsts) in zip(specs, s["reshard_jobs"]):
+        segs.append(N.ntp_reshard_row_segments(N.tensor_spec(rows, H, 0, unit, 4, kind, q, kv), T_RED, RANK, T_FULL, dsts))
+    return segs
+
+
+def step_fused(N, s, segs):
+    """The same step with the gradient GEMMs storing straight into the TP-8 layout (no separate reshard pass)."""
+    N.ntp_shard_plan(FFN, T_RED, RANK)
+    N.ntp_attn_shard_plan(HEADS, HEADS, HEAD_DIM, T_RED, RANK)
+    n_r, wq, wo = s["n_r"], s["wq"], s["wo"]
+    N.ntp_mlp_shard_fwd(s["X"], s["A_t"], s["B"], s["P"], s["Y"], s["Z"], n_r)
+    N.ntp_mlp_shard_bwd_resharded(s["dZ"], s["X"], s["A_t"], s["B"], s["P"], s["Y"], s["dP"], s["dX"], segs[0], segs[1], n_r)
+    N.ntp_attn_proj_shard_fwd(M, H, wq, wo, s["X"], s["Wqkv"], s["QKV"], s["C"], s["Wo"], s["Z2"])
+    N.ntp_attn_proj_shard_bwd_resharded(M, H, wq, wo, s["dZ"], s["dQKV"], s["X"], s["C"], s["Wqkv"], s["Wo"], s["dC"],
+                                        s["dX2"], segs[2], segs[3])
+
+
 def timed(torch, fn, steps):
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -252,6 +275,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-reshard-stress", action="store_true")
     ap.add_argument("--no-mapped-reshard", action="store_true")
+    ap.add_argument("--no-fused-step", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB dense copy (calibration_copy_kernel): the yardstick for profiler byte counters")
     args = ap.parse_args()
@@ -312,6 +336,29 @@ def main():
         "frac_of_bf16_peak": value / BF16_MFMA_PEAK_TFLOPS,
         "roofline": roofline, "parts": parts, "kernels": kernels,
     }
+    if not args.no_fused_step:
+        # destination shards as the unfused step leaves them (rows fed by other ranks keep a marker), then the
+        # fused step must reproduce them bit for bit
+        def mark():
+            for _, _, dsts in s["reshard_jobs"]:
+                for d in dsts:
+                    if d is not None:
+                        d.fill_(7.0)
+        mark()
+        fn()
+        want = [[None if d is None else d.clone() for d in dsts] for _, _, dsts in s["reshard_jobs"]]
+        mark()
+        segs = fused_state(N, s)
+        ffn = lambda: step_fused(N, s, segs)
+        for _ in range(max(3, args.warmup // 4)):
+            ffn()
+        fms = timed(torch, ffn, args.steps)
+        same = all(torch.equal(d.view(torch.int32), w.view(torch.int32)) for (_, _, dsts), ws in zip(s["reshard_jobs"], want) for d, w in zip(dsts, ws)
+                   if d is not None)
+        out["fused_reshard_step"] = dict(
+            what="same step with the four gradient GEMMs storing straight into the TP-8 layout (no reshard pass)",
+            ms_per_step=fms, value=s["gemm_flops"] / fms / 1e9, unit="TFLOP/s", speedup_vs_step=ms / fms,
+            destination_shards_bit_identical=bool(same))
     if args.calibrate_copy:
         a = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
         b = torch.empty_like(a)

@@ -203,6 +203,57 @@ int ntp_reshard_grad(const ntp_tensor_spec_t* spec, int32_t src_tp, int32_t dst_
                      void* const* dst_shards, const int64_t* dst_ld, void* stream);
 
 /* ---------------------------------------------------------------------------
+ * Weight gradients written straight into the destination layout of the
+ * reshard (Sec. 3.1 "Shard-mapping algorithm"; Appendix, the pre-sync hook):
+ * the gradient GEMMs of a backward call store each output row where the
+ * reshard would have copied it, so the separate pass over HBM is not needed.
+ * Gradients are stored with the partitioned dimension as rows, so a sub-shard
+ * of this rank's gradient is a block of rows.
+ *
+ * ntp_row_segment_t: `rows` rows of the rank's gradient starting at local row
+ *   row_begin go to dst (DEVICE pointer, fp32, 16-byte aligned) with leading
+ *   dimension ld (elements, multiple of 4, >= the gradient's row length).
+ *   A row may be listed in several segments (a KV head held by several
+ *   destination ranks) and is then stored to each.
+ * ntp_reshard_row_segments (host only): the segments of source rank src_rank
+ *   of spec (partition_dim 0, elem_size 4) for src_tp -> dst_tp, given the
+ *   destination shards (HOST array of dst_tp DEVICE pointers and leading
+ *   dimensions, as for ntp_reshard_grad; sub-shards whose destination shard
+ *   is NULL, "not on this GPU", are left out).  Writes at most max_segments
+ *   entries and the full count.
+ * ntp_mlp_shard_bwd_resharded / ntp_attn_proj_shard_bwd_resharded: as
+ *   ntp_mlp_shard_bwd / ntp_attn_proj_shard_bwd, with the gradient outputs
+ *   given as HOST arrays of segments (at most 16 per gradient: UNSUPPORTED
+ *   beyond).  The segments of one gradient must not overlap in memory
+ *   (INVALID_ARG); a row that no segment lists is not stored (a KV head whose
+ *   destination copies are fed by another rank, a destination on another
+ *   GPU).  accumulate != 0 adds into the destinations.  Results are bit-identical to the unfused call followed by
+ *   ntp_reshard_grad. */
+typedef struct ntp_row_segment {
+  int64_t row_begin, rows;
+  float* dst;
+  int64_t ld;
+} ntp_row_segment_t;
+int ntp_reshard_row_segments(const ntp_tensor_spec_t* spec, int32_t src_tp, int32_t src_rank,
+                             int32_t dst_tp, void* const* dst_shards, const int64_t* dst_ld,
+                             ntp_row_segment_t* out, int64_t max_segments, int64_t* count);
+int ntp_mlp_shard_bwd_resharded(const ntp_mlp_shape_t* shape, const void* dZ, int64_t lddz,
+                                const void* X, int64_t ldx, const void* A_t, int64_t lda,
+                                const void* B, int64_t ldb, const void* P, int64_t ldp,
+                                const void* Y, int64_t ldy, void* dP, int64_t lddp, void* dXpart,
+                                int64_t lddx, const ntp_row_segment_t* dA_segs, int32_t n_dA_segs,
+                                const ntp_row_segment_t* dB_segs, int32_t n_dB_segs,
+                                int32_t accumulate, void* stream);
+int ntp_attn_proj_shard_bwd_resharded(const ntp_attn_shape_t* shape, const void* dZ, int64_t lddz,
+                                      const void* dQKV, int64_t lddqkv, const void* X, int64_t ldx,
+                                      const void* C, int64_t ldc, const void* Wqkv, int64_t ldwqkv,
+                                      const void* Wo, int64_t ldwo, void* dC, int64_t lddc,
+                                      void* dXpart, int64_t lddx,
+                                      const ntp_row_segment_t* dWqkv_segs, int32_t n_dWqkv_segs,
+                                      const ntp_row_segment_t* dWo_segs, int32_t n_dWo_segs,
+                                      int32_t accumulate, void* stream);
+
+/* ---------------------------------------------------------------------------
  * Comp and sync rank assignment (Sec. 3.1 "Shard-mapping algorithm", Alg. 1).
  * A healthy replica of TP degree full_tp synchronises gradients with replicas
  * that run at reduced_tp <= full_tp.  For each of the k partition units:

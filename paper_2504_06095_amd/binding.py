@@ -27,7 +27,8 @@ EXPORTS = (
     "ntp_mlp_shard_bwd", "ntp_attn_proj_shard_fwd", "ntp_attn_proj_shard_bwd", "ntp_reshard_segments",
     "ntp_reshard_grad", "ntp_kernel_timing_enable", "ntp_kernel_timing_read", "ntp_calibration_copy",
     "ntp_comp_sync_plan", "ntp_reshard_plan_create", "ntp_reshard_plan_segments", "ntp_reshard_plan_splits",
-    "ntp_reshard_plan_table", "ntp_reshard_plan_run", "ntp_reshard_plan_destroy",
+    "ntp_reshard_plan_table", "ntp_reshard_plan_run", "ntp_reshard_plan_destroy", "ntp_reshard_row_segments",
+    "ntp_mlp_shard_bwd_resharded", "ntp_attn_proj_shard_bwd_resharded",
 )
 
 
@@ -58,6 +59,10 @@ class TensorSpec(C.Structure):
 class Segment(C.Structure):
     _fields_ = [("src_rank", C.c_int32), ("dst_rank", C.c_int32), ("src_unit", C.c_int64),
                 ("dst_unit", C.c_int64), ("units", C.c_int64)]
+
+
+class RowSegment(C.Structure):
+    _fields_ = [("row_begin", C.c_int64), ("rows", C.c_int64), ("dst", C.c_void_p), ("ld", C.c_int64)]
 
 
 class UnitSource(C.Structure):
@@ -101,6 +106,13 @@ def lib() -> C.CDLL:
         L.ntp_reshard_plan_table.argtypes = [vp, C.POINTER(UnitSource), i64, C.POINTER(i64)]
         L.ntp_reshard_plan_run.argtypes = [vp, C.POINTER(vp), C.POINTER(i64), C.POINTER(vp), C.POINTER(i64), vp]
         L.ntp_reshard_plan_destroy.argtypes = [vp]
+        segp = C.POINTER(RowSegment)
+        L.ntp_reshard_row_segments.argtypes = [C.POINTER(TensorSpec), C.c_int32, C.c_int32, C.c_int32, C.POINTER(vp),
+                                               C.POINTER(i64), segp, i64, C.POINTER(i64)]
+        L.ntp_mlp_shard_bwd_resharded.argtypes = ([C.POINTER(MlpShape)] + [vp, i64] * 8 + [segp, C.c_int32, segp, C.c_int32]
+                                                  + [C.c_int32, vp])
+        L.ntp_attn_proj_shard_bwd_resharded.argtypes = ([C.POINTER(AttnShape)] + [vp, i64] * 8
+                                                        + [segp, C.c_int32, segp, C.c_int32] + [C.c_int32, vp])
         L.ntp_kernel_timing_enable.argtypes = [C.c_int32]
         L.ntp_kernel_timing_read.argtypes = [C.POINTER(KernelTime), i64, C.POINTER(i64)]
         L.ntp_calibration_copy.argtypes = [vp, vp, i64, vp]
@@ -215,6 +227,67 @@ def ntp_attn_proj_shard_bwd(M, H, w_qkv, w_o, dZ=None, dQKV=None, X=None, C_=Non
         args += list(_mat(t, f32))
     _check(lib().ntp_attn_proj_shard_bwd(C.byref(shape), *args, int(bool(accumulate)), _stream()),
            "ntp_attn_proj_shard_bwd")
+
+
+def ntp_reshard_row_segments(spec: TensorSpec, src_tp: int, src_rank: int, dst_tp: int, dst_shards):
+    """Row segments (a ctypes array of RowSegment) of source rank src_rank's gradient for src_tp -> dst_tp, given
+    the destination shards (2-D fp32 device tensors; None where this rank sends nothing)."""
+    vp, i64 = C.c_void_p, C.c_int64
+    dp, dl = (vp * dst_tp)(), (i64 * dst_tp)()
+    if len(dst_shards) != dst_tp:
+        raise ValueError("one entry per destination rank expected")
+    for i, t in enumerate(dst_shards):
+        if t is None:
+            dp[i], dl[i] = None, 0
+        elif isinstance(t, tuple):  # (device address, leading dimension)
+            dp[i], dl[i] = t
+        elif t.numel() == 0:
+            dp[i], dl[i] = None, 0
+        else:
+            dp[i], dl[i] = _mat(t)
+    n = i64()
+    _check(lib().ntp_reshard_row_segments(C.byref(spec), src_tp, src_rank, dst_tp, dp, dl, None, 0, C.byref(n)),
+           "ntp_reshard_row_segments")
+    buf = (RowSegment * max(1, n.value))()
+    _check(lib().ntp_reshard_row_segments(C.byref(spec), src_tp, src_rank, dst_tp, dp, dl, buf, n.value, C.byref(n)),
+           "ntp_reshard_row_segments")
+    return (RowSegment * n.value)(*buf[: n.value]) if n.value else (RowSegment * 0)()
+
+
+def row_segments(items):
+    """A ctypes array of RowSegment from [(row_begin, rows, tensor_or_pointer, ld)]."""
+    arr = (RowSegment * len(items))()
+    for i, (b, r, d, ld) in enumerate(items):
+        arr[i] = RowSegment(b, r, d if isinstance(d, int) or d is None else d.data_ptr(), ld)
+    return arr
+
+
+def ntp_mlp_shard_bwd_resharded(dZ, X, A_t, B, P, Y, dP, dXpart, dA_segs, dB_segs, n_r: int,
+                                gelu_mode: int = NTP_GELU_ERF, accumulate: bool = False) -> None:
+    """As ntp_mlp_shard_bwd; dA_segs / dB_segs are ctypes arrays of RowSegment."""
+    import torch
+    bf = torch.bfloat16
+    shape = MlpShape(X.shape[0], X.shape[1], n_r, gelu_mode)
+    args = []
+    for t in (dZ, X, A_t, B, P, Y, dP, dXpart):
+        args += list(_mat(t, bf))
+    _check(lib().ntp_mlp_shard_bwd_resharded(C.byref(shape), *args, dA_segs, len(dA_segs), dB_segs, len(dB_segs),
+                                             int(bool(accumulate)), _stream()), "ntp_mlp_shard_bwd_resharded")
+
+
+def ntp_attn_proj_shard_bwd_resharded(M, H, w_qkv, w_o, dZ=None, dQKV=None, X=None, C_=None, Wqkv=None, Wo=None, dC=None,
+                                      dXpart=None, dWqkv_segs=None, dWo_segs=None, accumulate: bool = False) -> None:
+    """As ntp_attn_proj_shard_bwd; dWqkv_segs / dWo_segs are ctypes arrays of RowSegment."""
+    import torch
+    bf = torch.bfloat16
+    shape = AttnShape(M, H, w_qkv, w_o)
+    args = []
+    for t in (dZ, dQKV, X, C_, Wqkv, Wo, dC, dXpart):
+        args += list(_mat(t, bf))
+    q = dWqkv_segs if dWqkv_segs is not None else (RowSegment * 0)()
+    o = dWo_segs if dWo_segs is not None else (RowSegment * 0)()
+    _check(lib().ntp_attn_proj_shard_bwd_resharded(C.byref(shape), *args, q, len(q), o, len(o), int(bool(accumulate)),
+                                                   _stream()), "ntp_attn_proj_shard_bwd_resharded")
 
 
 def _shard_arrays(spec: TensorSpec, src_tp: int, dst_tp: int, src_shards, dst_shards):

@@ -115,7 +115,8 @@ int gemm_launch(const GemmDesc& d, void* stream) {
   if (d.M < 0 || d.N < 0 || d.K < 0) return NTP_ERR_INVALID_ARG;
   if (d.M == 0 || d.N == 0) return NTP_OK;
   if (d.M > 0x7fffff00 || d.N > 0x7fffff00 || d.K > 0x7fffff00) return NTP_ERR_UNSUPPORTED;
-  if (!d.C || (d.K > 0 && (!d.A || !d.B))) return NTP_ERR_INVALID_ARG;
+  const bool to_segs = d.n_segs > 0;
+  if ((!d.C && !to_segs) || (d.K > 0 && (!d.A || !d.B))) return NTP_ERR_INVALID_ARG;
   const bool f32_out = d.epilogue == EPI_F32 || d.epilogue == EPI_F32_ACCUM;
   if (d.epilogue == EPI_GELU && !d.C2) return NTP_ERR_INVALID_ARG;
   if (d.epilogue == EPI_DGELU && !d.AUX) return NTP_ERR_INVALID_ARG;
@@ -129,17 +130,43 @@ int gemm_launch(const GemmDesc& d, void* stream) {
   int64_t n_store = d.N;
   if (f32_out) {
     if (d.N % 4) return NTP_ERR_ALIGNMENT;
-    if (!aligned16(d.C) || d.ldc % 4) return NTP_ERR_ALIGNMENT;
+    if (!to_segs && (!aligned16(d.C) || d.ldc % 4)) return NTP_ERR_ALIGNMENT;
   } else {
+    if (to_segs) return NTP_ERR_INVALID_ARG;
     if (d.zero_pad_n) n_store = (d.N + 7) / 8 * 8;
     if (n_store % 4) return NTP_ERR_ALIGNMENT;
     if (!aligned16(d.C) || d.ldc % 8) return NTP_ERR_ALIGNMENT;
     if (d.epilogue == EPI_GELU && (!aligned16(d.C2) || d.ldc2 % 8 || d.ldc2 < n_store)) return NTP_ERR_ALIGNMENT;
     if (d.epilogue == EPI_DGELU && (!aligned16(d.AUX) || d.ldaux % 8 || d.ldaux < n_store)) return NTP_ERR_ALIGNMENT;
   }
-  if (d.ldc < n_store) return NTP_ERR_INVALID_ARG;
+  if (!to_segs && d.ldc < n_store) return NTP_ERR_INVALID_ARG;
 
   GemmArgs g{};
+  if (to_segs) {
+    // destinations of the output rows: inside [0, M), aligned, wide enough, not overlapping in memory
+    // (a row that no segment lists is not stored)
+    if (!d.segs || d.n_segs < 0) return NTP_ERR_INVALID_ARG;
+    if (d.n_segs > kMaxRowSegs) return NTP_ERR_UNSUPPORTED;
+    for (int32_t i = 0; i < d.n_segs; ++i) {
+      const ntp_row_segment_t& r = d.segs[i];
+      if (r.row_begin < 0 || r.rows < 0 || r.row_begin + r.rows > d.M) return NTP_ERR_INVALID_ARG;
+      if (r.rows == 0) continue;
+      if (!r.dst || r.ld < d.N) return NTP_ERR_INVALID_ARG;
+      if (!aligned16(r.dst) || r.ld % 4) return NTP_ERR_ALIGNMENT;
+      const uintptr_t lo = reinterpret_cast<uintptr_t>(r.dst), hi = lo + uintptr_t(((r.rows - 1) * r.ld + d.N) * 4);
+      for (int32_t j = 0; j < g.n_segs; ++j) {
+        const uintptr_t lo2 = reinterpret_cast<uintptr_t>(g.seg[j].ptr);
+        const uintptr_t hi2 = lo2 + uintptr_t(((int64_t(g.seg[j].end - g.seg[j].begin) - 1) * g.seg[j].ld + d.N) * 4);
+        if (lo < hi2 && lo2 < hi) return NTP_ERR_INVALID_ARG;
+      }
+      g.seg[g.n_segs].begin = int32_t(r.row_begin);
+      g.seg[g.n_segs].end = int32_t(r.row_begin + r.rows);
+      g.seg[g.n_segs].ptr = r.dst;
+      g.seg[g.n_segs].ld = r.ld;
+      ++g.n_segs;
+    }
+    if (g.n_segs == 0) return NTP_OK;  // no row has a destination: nothing to compute
+  }
   g.A = static_cast<const uint16_t*>(d.A);
   g.B = static_cast<const uint16_t*>(d.B);
   g.C = d.C;

@@ -16,6 +16,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint16_t u16x8 __attribute__((ext_vector_type(8)));
 typedef uint16_t u16x4 __attribute__((ext_vector_type(4)));
 
+constexpr int kMaxRowSegs = 16;
+
 struct GemmArgs {
   const uint16_t* A;
   const uint16_t* B;
@@ -27,6 +29,14 @@ struct GemmArgs {
   int32_t n_store;  // columns stored: N, or N rounded up to 8 with zero fill
   int32_t gelu_mode;
   int32_t tiles_m, tiles_n;
+  // fp32 epilogues only: where the output rows go.  n_segs == 0: to C / ldc.  Otherwise every row m
+  // is stored to each segment with begin <= m < end, at ptr + (m - begin) * ld.
+  int32_t n_segs;
+  struct RowSeg {
+    int32_t begin, end;
+    float* ptr;
+    int64_t ld;
+  } seg[kMaxRowSegs];
 };
 
 __device__ __forceinline__ float gelu_fwd(float x, int mode) {
@@ -122,11 +132,19 @@ __device__ __forceinline__ void store4(const GemmArgs& g, int m, int n0, f32x4 a
 #pragma unroll
   for (int j = 0; j < 4; ++j)
     if (n0 + j >= g.N) acc[j] = 0.0f;
-  if constexpr (EPI == ntp::EPI_F32) {
-    *reinterpret_cast<f32x4*>(static_cast<float*>(g.C) + int64_t(m) * g.ldc + n0) = acc;
-  } else if constexpr (EPI == ntp::EPI_F32_ACCUM) {
-    f32x4* p = reinterpret_cast<f32x4*>(static_cast<float*>(g.C) + int64_t(m) * g.ldc + n0);
-    *p = *p + acc;
+  if constexpr (EPI == ntp::EPI_F32 || EPI == ntp::EPI_F32_ACCUM) {
+    if (g.n_segs == 0) {
+      f32x4* p = reinterpret_cast<f32x4*>(static_cast<float*>(g.C) + int64_t(m) * g.ldc + n0);
+      if constexpr (EPI == ntp::EPI_F32) *p = acc;
+      else *p = *p + acc;
+    } else {
+      for (int s = 0; s < g.n_segs; ++s) {
+        if (m < g.seg[s].begin || m >= g.seg[s].end) continue;
+        f32x4* p = reinterpret_cast<f32x4*>(g.seg[s].ptr + int64_t(m - g.seg[s].begin) * g.seg[s].ld + n0);
+        if constexpr (EPI == ntp::EPI_F32) *p = acc;
+        else *p = *p + acc;
+      }
+    }
   } else {
     if constexpr (EPI == ntp::EPI_DGELU) {
       const u16x4 pre = *reinterpret_cast<const u16x4*>(g.AUX + int64_t(m) * g.ldaux + n0);

@@ -72,6 +72,10 @@ struct GemmDesc {
   int64_t ldaux;
   int32_t gelu_mode;
   bool zero_pad_n;  // bf16 outputs: also write zeros to columns [N, round_up(N, 8))
+  // fp32 epilogues: when n_segs > 0 the output rows go to these destinations instead of C
+  // (host array; a row that no segment lists is not stored)
+  const ntp_row_segment_t* segs;
+  int32_t n_segs;
 };
 
 // Validates and enqueues one GEMM on `stream`.  Returns an NTP_* status.

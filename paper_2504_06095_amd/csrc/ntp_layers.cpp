@@ -54,15 +54,17 @@ extern "C" int ntp_mlp_shard_fwd(const ntp_mlp_shape_t* s, const void* X, int64_
   return ntp::gemm_launch(d2, stream);
 }
 
-extern "C" int ntp_mlp_shard_bwd(const ntp_mlp_shape_t* s, const void* dZ, int64_t lddz, const void* X,
-                                 int64_t ldx, const void* A_t, int64_t lda, const void* B, int64_t ldb,
-                                 const void* P, int64_t ldp, const void* Y, int64_t ldy, void* dP,
-                                 int64_t lddp, void* dXpart, int64_t lddx, float* dA_t, int64_t ldda,
-                                 float* dB, int64_t lddb, int32_t accumulate, void* stream) {
+namespace {
+
+// Backward of the MLP shard; the two weight gradients go to row segments.
+int mlp_bwd(const ntp_mlp_shape_t* s, const void* dZ, int64_t lddz, const void* X, int64_t ldx, const void* A_t,
+            int64_t lda, const void* B, int64_t ldb, const void* P, int64_t ldp, const void* Y, int64_t ldy, void* dP,
+            int64_t lddp, void* dXpart, int64_t lddx, const ntp_row_segment_t* dA_segs, int32_t n_dA,
+            const ntp_row_segment_t* dB_segs, int32_t n_dB, int32_t accumulate, void* stream) {
   if (bad_mlp_shape(s)) return NTP_ERR_INVALID_ARG;
   if (s->H % 8) return NTP_ERR_ALIGNMENT;
   if (s->H == 0) return NTP_OK;
-  if (s->n_r > 0 && (!A_t || !B || !dA_t || !dB)) return NTP_ERR_INVALID_ARG;
+  if (s->n_r > 0 && (!A_t || !B || !dA_segs || !dB_segs || n_dA < 1 || n_dB < 1)) return NTP_ERR_INVALID_ARG;
   if (s->M > 0 && (!dZ || !X || !dXpart || (s->n_r > 0 && (!P || !Y || !dP)))) return NTP_ERR_INVALID_ARG;
   const int32_t wepi = accumulate ? ntp::EPI_F32_ACCUM : ntp::EPI_F32;
   int st = NTP_OK;
@@ -77,15 +79,45 @@ extern "C" int ntp_mlp_shard_bwd(const ntp_mlp_shape_t* s, const void* dZ, int64
   }
   if (s->n_r > 0) {
     // dB = Y^T dZ and dA_t = dP^T X: contraction over tokens, both operands token-major
-    GemmDesc db = gemm(Y, ldy, false, dZ, lddz, false, s->n_r, s->H, s->M, wepi, dB, lddb);
+    GemmDesc db = gemm(Y, ldy, false, dZ, lddz, false, s->n_r, s->H, s->M, wepi, nullptr, 0);
+    db.segs = dB_segs;
+    db.n_segs = n_dB;
     if ((st = ntp::gemm_launch(db, stream)) != NTP_OK) return st;
-    GemmDesc da = gemm(dP, lddp, false, X, ldx, false, s->n_r, s->H, s->M, wepi, dA_t, ldda);
+    GemmDesc da = gemm(dP, lddp, false, X, ldx, false, s->n_r, s->H, s->M, wepi, nullptr, 0);
+    da.segs = dA_segs;
+    da.n_segs = n_dA;
     if ((st = ntp::gemm_launch(da, stream)) != NTP_OK) return st;
   }
   if (s->M == 0) return NTP_OK;
   // dXpart = dP A_i^T, contraction over the ragged shard width
   GemmDesc dx = gemm(dP, lddp, true, A_t, lda, false, s->M, s->H, s->n_r, ntp::EPI_BF16, dXpart, lddx);
   return ntp::gemm_launch(dx, stream);
+}
+
+}  // namespace
+
+extern "C" int ntp_mlp_shard_bwd(const ntp_mlp_shape_t* s, const void* dZ, int64_t lddz, const void* X,
+                                 int64_t ldx, const void* A_t, int64_t lda, const void* B, int64_t ldb,
+                                 const void* P, int64_t ldp, const void* Y, int64_t ldy, void* dP,
+                                 int64_t lddp, void* dXpart, int64_t lddx, float* dA_t, int64_t ldda,
+                                 float* dB, int64_t lddb, int32_t accumulate, void* stream) {
+  if (bad_mlp_shape(s)) return NTP_ERR_INVALID_ARG;
+  if (s->n_r > 0 && s->H > 0 && (!dA_t || !dB)) return NTP_ERR_INVALID_ARG;
+  // the gradients as one block of rows each
+  const ntp_row_segment_t a{0, s->n_r, dA_t, ldda}, b{0, s->n_r, dB, lddb};
+  return mlp_bwd(s, dZ, lddz, X, ldx, A_t, lda, B, ldb, P, ldp, Y, ldy, dP, lddp, dXpart, lddx, &a, 1, &b, 1, accumulate,
+                 stream);
+}
+
+extern "C" int ntp_mlp_shard_bwd_resharded(const ntp_mlp_shape_t* s, const void* dZ, int64_t lddz, const void* X,
+                                           int64_t ldx, const void* A_t, int64_t lda, const void* B, int64_t ldb,
+                                           const void* P, int64_t ldp, const void* Y, int64_t ldy, void* dP,
+                                           int64_t lddp, void* dXpart, int64_t lddx,
+                                           const ntp_row_segment_t* dA_segs, int32_t n_dA_segs,
+                                           const ntp_row_segment_t* dB_segs, int32_t n_dB_segs, int32_t accumulate,
+                                           void* stream) {
+  return mlp_bwd(s, dZ, lddz, X, ldx, A_t, lda, B, ldb, P, ldp, Y, ldy, dP, lddp, dXpart, lddx, dA_segs, n_dA_segs, dB_segs,
+                 n_dB_segs, accumulate, stream);
 }
 
 namespace {
@@ -115,6 +147,40 @@ extern "C" int ntp_attn_proj_shard_fwd(const ntp_attn_shape_t* s, const void* X,
   return NTP_OK;
 }
 
+namespace {
+
+// Backward of the two projections; the two weight gradients go to row segments.
+int attn_bwd(const ntp_attn_shape_t* s, const void* dZ, int64_t lddz, const void* dQKV, int64_t lddqkv, const void* X,
+             int64_t ldx, const void* C, int64_t ldc, const void* Wqkv, int64_t ldwqkv, const void* Wo, int64_t ldwo,
+             void* dC, int64_t lddc, void* dXpart, int64_t lddx, const ntp_row_segment_t* dWqkv_segs, int32_t n_dWqkv,
+             const ntp_row_segment_t* dWo_segs, int32_t n_dWo, int32_t accumulate, void* stream) {
+  if (bad_attn_shape(s)) return NTP_ERR_INVALID_ARG;
+  if (s->H % 8 || s->w_qkv % 8 || s->w_o % 8) return NTP_ERR_ALIGNMENT;
+  const int32_t wepi = accumulate ? ntp::EPI_F32_ACCUM : ntp::EPI_F32;
+  int st = NTP_OK;
+  if (dZ) {
+    if (!Wo || !C || !dC || !dWo_segs || n_dWo < 1) return NTP_ERR_INVALID_ARG;
+    GemmDesc d = gemm(dZ, lddz, true, Wo, ldwo, true, s->M, s->w_o, s->H, ntp::EPI_BF16, dC, lddc);
+    if ((st = ntp::gemm_launch(d, stream)) != NTP_OK) return st;
+    GemmDesc w = gemm(C, ldc, false, dZ, lddz, false, s->w_o, s->H, s->M, wepi, nullptr, 0);
+    w.segs = dWo_segs;
+    w.n_segs = n_dWo;
+    if ((st = ntp::gemm_launch(w, stream)) != NTP_OK) return st;
+  }
+  if (dQKV) {
+    if (!Wqkv || !X || !dXpart || !dWqkv_segs || n_dWqkv < 1) return NTP_ERR_INVALID_ARG;
+    GemmDesc d = gemm(dQKV, lddqkv, true, Wqkv, ldwqkv, false, s->M, s->H, s->w_qkv, ntp::EPI_BF16, dXpart, lddx);
+    if ((st = ntp::gemm_launch(d, stream)) != NTP_OK) return st;
+    GemmDesc w = gemm(dQKV, lddqkv, false, X, ldx, false, s->w_qkv, s->H, s->M, wepi, nullptr, 0);
+    w.segs = dWqkv_segs;
+    w.n_segs = n_dWqkv;
+    if ((st = ntp::gemm_launch(w, stream)) != NTP_OK) return st;
+  }
+  return NTP_OK;
+}
+
+}  // namespace
+
 extern "C" int ntp_attn_proj_shard_bwd(const ntp_attn_shape_t* s, const void* dZ, int64_t lddz,
                                        const void* dQKV, int64_t lddqkv, const void* X, int64_t ldx,
                                        const void* C, int64_t ldc, const void* Wqkv, int64_t ldwqkv,
@@ -122,22 +188,20 @@ extern "C" int ntp_attn_proj_shard_bwd(const ntp_attn_shape_t* s, const void* dZ
                                        int64_t lddx, float* dWqkv, int64_t lddwqkv, float* dWo,
                                        int64_t lddwo, int32_t accumulate, void* stream) {
   if (bad_attn_shape(s)) return NTP_ERR_INVALID_ARG;
-  if (s->H % 8 || s->w_qkv % 8 || s->w_o % 8) return NTP_ERR_ALIGNMENT;
-  const int32_t wepi = accumulate ? ntp::EPI_F32_ACCUM : ntp::EPI_F32;
-  int st = NTP_OK;
-  if (dZ) {
-    if (!Wo || !C || !dC || !dWo) return NTP_ERR_INVALID_ARG;
-    GemmDesc d = gemm(dZ, lddz, true, Wo, ldwo, true, s->M, s->w_o, s->H, ntp::EPI_BF16, dC, lddc);
-    if ((st = ntp::gemm_launch(d, stream)) != NTP_OK) return st;
-    GemmDesc w = gemm(C, ldc, false, dZ, lddz, false, s->w_o, s->H, s->M, wepi, dWo, lddwo);
-    if ((st = ntp::gemm_launch(w, stream)) != NTP_OK) return st;
-  }
-  if (dQKV) {
-    if (!Wqkv || !X || !dXpart || !dWqkv) return NTP_ERR_INVALID_ARG;
-    GemmDesc d = gemm(dQKV, lddqkv, true, Wqkv, ldwqkv, false, s->M, s->H, s->w_qkv, ntp::EPI_BF16, dXpart, lddx);
-    if ((st = ntp::gemm_launch(d, stream)) != NTP_OK) return st;
-    GemmDesc w = gemm(dQKV, lddqkv, false, X, ldx, false, s->w_qkv, s->H, s->M, wepi, dWqkv, lddwqkv);
-    if ((st = ntp::gemm_launch(w, stream)) != NTP_OK) return st;
-  }
-  return NTP_OK;
+  if ((dZ && !dWo) || (dQKV && !dWqkv)) return NTP_ERR_INVALID_ARG;
+  // the gradients as one block of rows each
+  const ntp_row_segment_t q{0, s->w_qkv, dWqkv, lddwqkv}, o{0, s->w_o, dWo, lddwo};
+  return attn_bwd(s, dZ, lddz, dQKV, lddqkv, X, ldx, C, ldc, Wqkv, ldwqkv, Wo, ldwo, dC, lddc, dXpart, lddx, &q, 1, &o, 1,
+                  accumulate, stream);
+}
+
+extern "C" int ntp_attn_proj_shard_bwd_resharded(const ntp_attn_shape_t* s, const void* dZ, int64_t lddz,
+                                                 const void* dQKV, int64_t lddqkv, const void* X, int64_t ldx,
+                                                 const void* C, int64_t ldc, const void* Wqkv, int64_t ldwqkv,
+                                                 const void* Wo, int64_t ldwo, void* dC, int64_t lddc, void* dXpart,
+                                                 int64_t lddx, const ntp_row_segment_t* dWqkv_segs,
+                                                 int32_t n_dWqkv_segs, const ntp_row_segment_t* dWo_segs,
+                                                 int32_t n_dWo_segs, int32_t accumulate, void* stream) {
+  return attn_bwd(s, dZ, lddz, dQKV, lddqkv, X, ldx, C, ldc, Wqkv, ldwqkv, Wo, ldwo, dC, lddc, dXpart, lddx, dWqkv_segs,
+                  n_dWqkv_segs, dWo_segs, n_dWo_segs, accumulate, stream);
 }

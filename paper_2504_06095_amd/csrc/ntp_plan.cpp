@@ -210,3 +210,27 @@ extern "C" int ntp_reshard_segments(const ntp_tensor_spec_t* spec, int32_t src_t
   for (int64_t i = 0; i < std::min<int64_t>(max_segments, (int64_t)segs.size()); ++i) out[i] = segs[i];
   return NTP_OK;
 }
+
+// Where the rows of one source rank's gradient go: its sub-shards joined with the destination shards.
+extern "C" int ntp_reshard_row_segments(const ntp_tensor_spec_t* spec, int32_t src_tp, int32_t src_rank,
+                                        int32_t dst_tp, void* const* dst_shards, const int64_t* dst_ld,
+                                        ntp_row_segment_t* out, int64_t max_segments, int64_t* count) {
+  if (!count || max_segments < 0 || (max_segments > 0 && !out) || !dst_shards || !dst_ld) return NTP_ERR_INVALID_ARG;
+  std::vector<ntp_segment_t> segs;
+  const int st = ntp::build_segments(spec, src_tp, dst_tp, &segs);
+  if (st != NTP_OK) return st;
+  if (src_rank < 0 || src_rank >= src_tp || spec->partition_dim != 0 || spec->elem_size != 4) return NTP_ERR_INVALID_ARG;
+  int64_t n = 0;
+  for (const ntp_segment_t& g : segs) {
+    if (g.src_rank != src_rank || g.units == 0) continue;
+    if (!dst_shards[g.dst_rank]) continue;  // not on this GPU
+    if (dst_ld[g.dst_rank] < spec->cols) return NTP_ERR_INVALID_ARG;
+    if (n < max_segments)
+      out[n] = ntp_row_segment_t{g.src_unit * spec->unit, g.units * spec->unit,
+                                 static_cast<float*>(dst_shards[g.dst_rank]) + g.dst_unit * spec->unit * dst_ld[g.dst_rank],
+                                 dst_ld[g.dst_rank]};
+    ++n;
+  }
+  *count = n;
+  return NTP_OK;
+}
