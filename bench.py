@@ -267,6 +267,67 @@ def mapped_reshard_stress(torch, N):
     return out
 
 
+def imbalance_sweep(torch, N, iters=8):
+    """Second workload (`--imbalance-sweep`): every rank of a replica degraded from TP 8 to TP 7, 6 and 4
+    at the prototype's layer shapes (hidden 6144 / 12288, head dimension 128, FFN 4 x hidden, 4K-16K tokens;
+    Sec. 5.1 "Prototype evaluation").  Per (shape, t'): time of the slowest rank's layer shard (MLP +
+    attention projections, forward + backward) over the mean over ranks, which is what the uneven split
+    costs (Sec. 3.1: imbalance lowers the throughput of the reduced-TP replica), and over the TP-8 rank's
+    time, which is what the lost GPUs cost.  A rank's time depends on its widths only, so each distinct
+    (ffn columns, heads) pair is timed once."""
+    dev = "cuda"
+    out = []
+    cache = {}
+
+    def rank_ms(Mt, Hd, n_r, heads):
+        key = (Mt, Hd, n_r, heads)
+        if key in cache:
+            return cache[key]
+        bf = dict(dtype=torch.bfloat16, device=dev)
+        wq, wo = 3 * heads * HEAD_DIM, heads * HEAD_DIM
+        ld = (n_r + 7) // 8 * 8
+        X, dZ = torch.randn(Mt, Hd, **bf), torch.randn(Mt, Hd, **bf)
+        At, B = torch.randn(n_r, Hd, **bf) * 0.02, torch.randn(n_r, Hd, **bf) * 0.02
+        Wqkv, Wo = torch.randn(wq, Hd, **bf) * 0.02, torch.randn(wo, Hd, **bf) * 0.02
+        Cc, dQKV = torch.randn(Mt, wo, **bf), torch.randn(Mt, wq, **bf)
+        e = lambda r, c, dt=torch.bfloat16: torch.empty(r, c, dtype=dt, device=dev)
+        P, Y, dP = e(Mt, ld)[:, :n_r], e(Mt, ld)[:, :n_r], e(Mt, ld)[:, :n_r]
+        Z, dX, Z2, dX2, QKV, dC = e(Mt, Hd), e(Mt, Hd), e(Mt, Hd), e(Mt, Hd), e(Mt, wq), e(Mt, wo)
+        f32 = torch.float32
+        dA, dB, dWq, dWo = e(n_r, Hd, f32), e(n_r, Hd, f32), e(wq, Hd, f32), e(wo, Hd, f32)
+
+        def run():
+            N.ntp_mlp_shard_fwd(X, At, B, P, Y, Z, n_r)
+            N.ntp_mlp_shard_bwd(dZ, X, At, B, P, Y, dP, dX, dA, dB, n_r)
+            N.ntp_attn_proj_shard_fwd(Mt, Hd, wq, wo, X, Wqkv, QKV, Cc, Wo, Z2)
+            N.ntp_attn_proj_shard_bwd(Mt, Hd, wq, wo, dZ, dQKV, X, Cc, Wqkv, Wo, dC, dX2, dWq, dWo)
+        for _ in range(3):
+            run()
+        cache[key] = timed(torch, run, iters)
+        return cache[key]
+
+    for Hd in (6144, 12288):
+        heads, ffn = Hd // HEAD_DIM, 4 * Hd
+        for Mt in (4096, 8192, 16384):
+            base = rank_ms(Mt, Hd, ffn // T_FULL, heads // T_FULL)
+            flops_layer = 12.0 * Mt * Hd * ffn + 6.0 * Mt * Hd * (4 * heads * HEAD_DIM)
+            for tr in (7, 6, 4):
+                per_rank = []
+                for r in range(tr):
+                    n_r = N.ntp_shard_plan(ffn, tr, r)[1]
+                    q = N.ntp_attn_shard_plan(heads, heads, HEAD_DIM, tr, r)["q_cnt"]
+                    per_rank.append(rank_ms(Mt, Hd, n_r, q))
+                mx, mean = max(per_rank), sum(per_rank) / tr
+                out.append(dict(hidden=Hd, tokens=Mt, full_tp=T_FULL, reduced_tp=tr, full_tp_rank_ms=base,
+                                max_rank_ms=mx, mean_rank_ms=mean, max_over_mean=mx / mean,
+                                slowdown_vs_full_tp=mx / base, ideal_slowdown=T_FULL / tr,
+                                slowest_rank_TFLOPs=flops_layer / tr / mx / 1e9 if mx else None,
+                                widths=sorted({(N.ntp_shard_plan(ffn, tr, r)[1],
+                                                N.ntp_attn_shard_plan(heads, heads, HEAD_DIM, tr, r)["q_cnt"])
+                                               for r in range(tr)})))
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -276,6 +337,9 @@ def main():
     ap.add_argument("--no-reshard-stress", action="store_true")
     ap.add_argument("--no-mapped-reshard", action="store_true")
     ap.add_argument("--no-fused-step", action="store_true")
+    ap.add_argument("--imbalance-sweep", action="store_true",
+                    help="run the second workload instead (all ranks of TP 8 degraded to 7, 6, 4 at the prototype's shapes) "
+                         "and print its own JSON line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB dense copy (calibration_copy_kernel): the yardstick for profiler byte counters")
     args = ap.parse_args()
@@ -289,6 +353,13 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+    if args.imbalance_sweep:
+        rows = imbalance_sweep(torch, N)
+        print(json.dumps({"metric": "layer shard time of the slowest rank over the mean over ranks (MLP + attention "
+                                    "projections, fwd+bwd), all ranks of a TP-8 replica degraded to TP 7/6/4",
+                          "unit": "ratio", "n_gpus": 1, "dtype": "bf16", "data": "synthetic", "higher_is_better": False,
+                          "value": max(r["max_over_mean"] for r in rows), "rows": rows}))
+        return
     s = build_state(torch, N)
     fn = lambda: step(N, s)
     for _ in range(args.warmup):
