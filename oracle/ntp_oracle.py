@@ -143,16 +143,78 @@ def mlp_shard_bwd(dZ, X, A_i, B_i, mode=GELU_ERF):
 
 
 # ----------------------------------------------------------------------------
-# Attention block projections (Eq. 4-6) and, for the invariants only, the
-# attention core of Eq. 5.
+# Attention block: projections (Eq. 4, 6) and the attention core (Eq. 5).
 # ----------------------------------------------------------------------------
-def attention_core(Q, K, V):
-    """softmax(Q K^T / sqrt(d)) V for one head; Q, K, V are [M x d].  Not on the hot path."""
+def attention_core(Q, K, V, causal: bool = False):
+    """Eq. 5 for one head: softmax(Q K^T / sqrt(d)) V; Q, K, V are [S x d] (one sequence).  With
+    `causal`, query t sees keys 0..t only (the paper writes Attention(Q, K, V) without a mask; decoder
+    training masks the future, so both are provided)."""
     d = Q.shape[1]
     S = (Q @ K.T) / math.sqrt(d)
+    if causal:
+        S = np.where(np.tril(np.ones(S.shape, dtype=bool)), S, -np.inf)
     S = S - S.max(axis=1, keepdims=True)
     E = np.exp(S)
     return (E / E.sum(axis=1, keepdims=True)) @ V
+
+
+def attention_core_bwd(Q, K, V, dO, causal: bool = False):
+    """Gradients of L = sum(O * dO) for O = attention_core(Q, K, V): chain rule through the softmax.
+    Returns (dQ, dK, dV)."""
+    d = Q.shape[1]
+    S = (Q @ K.T) / math.sqrt(d)
+    if causal:
+        S = np.where(np.tril(np.ones(S.shape, dtype=bool)), S, -np.inf)
+    S = S - S.max(axis=1, keepdims=True)
+    E = np.exp(S)
+    P = E / E.sum(axis=1, keepdims=True)
+    dV = P.T @ dO
+    dP = dO @ V.T
+    dS = P * (dP - (dP * P).sum(axis=1, keepdims=True))
+    return (dS @ K) / math.sqrt(d), (dS.T @ Q) / math.sqrt(d), dV
+
+
+def _local_kv_head(plan, group, j):
+    """Local KV head read by local query head j of a rank (Sec. 3.1, Eq. 4-6 with grouped KV heads)."""
+    return (plan["q_off"] + j) // group - plan["kv_off"]
+
+
+def attn_core_shard_fwd(QKV, plan, group, d, n_seq, causal=False):
+    """Eq. 5 on one rank's local heads: QKV is [M x (q_cnt + 2 kv_cnt) d] with columns
+    [Q heads | K heads | V heads] and M = n_seq * S tokens (sequence s = rows s*S .. (s+1)*S-1).
+    Returns C [M x q_cnt d], the heads' outputs side by side."""
+    M = QKV.shape[0]
+    S = M // n_seq
+    qc, kc = plan["q_cnt"], plan["kv_cnt"]
+    C = np.zeros((M, qc * d))
+    for s in range(n_seq):
+        rows = slice(s * S, (s + 1) * S)
+        for j in range(qc):
+            g = _local_kv_head(plan, group, j)
+            Q = QKV[rows, j * d:(j + 1) * d]
+            K = QKV[rows, (qc + g) * d:(qc + g + 1) * d]
+            V = QKV[rows, (qc + kc + g) * d:(qc + kc + g + 1) * d]
+            C[rows, j * d:(j + 1) * d] = attention_core(Q, K, V, causal)
+    return C
+
+
+def attn_core_shard_bwd(QKV, dC, plan, group, d, n_seq, causal=False):
+    """Gradient of the above with respect to QKV (same layout); a KV head's gradient is the sum over the
+    local query heads that read it."""
+    M = QKV.shape[0]
+    S = M // n_seq
+    qc, kc = plan["q_cnt"], plan["kv_cnt"]
+    dQKV = np.zeros_like(QKV)
+    for s in range(n_seq):
+        rows = slice(s * S, (s + 1) * S)
+        for j in range(qc):
+            g = _local_kv_head(plan, group, j)
+            qs, ks, vs = slice(j * d, (j + 1) * d), slice((qc + g) * d, (qc + g + 1) * d), slice((qc + kc + g) * d, (qc + kc + g + 1) * d)
+            dQ, dK, dV = attention_core_bwd(QKV[rows, qs], QKV[rows, ks], QKV[rows, vs], dC[rows, qs], causal)
+            dQKV[rows, qs] += dQ
+            dQKV[rows, ks] += dK
+            dQKV[rows, vs] += dV
+    return dQKV
 
 
 def attn_shard_weights(Wq, Wk, Wv, Wo, n_q, n_kv, d, tp, rank):
