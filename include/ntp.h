@@ -203,6 +203,33 @@ int ntp_reshard_grad(const ntp_tensor_spec_t* spec, int32_t src_tp, int32_t dst_
                      void* const* dst_shards, const int64_t* dst_ld, void* stream);
 
 /* ---------------------------------------------------------------------------
+ * Attention core of the rank's local heads (Sec. 3.1, Eq. 5): for every local
+ * query head j and the KV head g(j) it reads,
+ *   C_j = softmax(Q_j K_g^T / sqrt(head_dim)) V_g,   one sequence at a time.
+ * It sits between the two halves of ntp_attn_proj_shard_fwd: QKV is that
+ * call's output [M x (q_cnt + 2 kv_cnt) head_dim] with columns
+ * [Q heads | K heads | V heads], C its input [M x q_cnt head_dim].  The M =
+ * n_seq * seq_len tokens are n_seq sequences of seq_len rows each.  Local
+ * query head j reads local KV head (q_off + j) / group - kv_off (q_off, kv_off,
+ * q_cnt, kv_cnt from ntp_attn_shard_plan; group = query heads per KV head); all
+ * of them must be local (INVALID_ARG).  causal != 0: query t sees keys 0..t of
+ * its sequence (the paper writes the unmasked form; decoder training masks).
+ * head_dim 64 or 128 (UNSUPPORTED otherwise).  bf16 in and out (16-byte aligned,
+ * leading dimensions multiples of 8), fp32 arithmetic for scores and sums.
+ * LSE (DEVICE, fp32 [q_cnt x M], may be NULL in the forward call): per head and
+ * token the natural logarithm of the sum of exp(score) over the visible keys;
+ * the backward call reads it. */
+typedef struct ntp_attn_core_shape {
+  int32_t n_seq, seq_len;
+  int32_t q_cnt, kv_cnt;
+  int32_t q_off, kv_off, group;
+  int32_t head_dim;
+  int32_t causal;
+} ntp_attn_core_shape_t;
+int ntp_attn_core_shard_fwd(const ntp_attn_core_shape_t* shape, const void* QKV, int64_t ldqkv,
+                            void* C, int64_t ldc, float* LSE, void* stream);
+
+/* ---------------------------------------------------------------------------
  * Weight gradients written straight into the destination layout of the
  * reshard (Sec. 3.1 "Shard-mapping algorithm"; Appendix, the pre-sync hook):
  * the gradient GEMMs of a backward call store each output row where the

@@ -158,6 +158,17 @@ def attention_core(Q, K, V, causal: bool = False):
     return (E / E.sum(axis=1, keepdims=True)) @ V
 
 
+def attention_lse(Q, K, causal: bool = False):
+    """Per query row, log of the sum over the visible keys of exp(q.k / sqrt(d)): the normaliser of Eq. 5's
+    softmax, which a forward pass may keep for its backward pass."""
+    d = Q.shape[1]
+    S = (Q @ K.T) / math.sqrt(d)
+    if causal:
+        S = np.where(np.tril(np.ones(S.shape, dtype=bool)), S, -np.inf)
+    m = S.max(axis=1)
+    return m + np.log(np.exp(S - m[:, None]).sum(axis=1))
+
+
 def attention_core_bwd(Q, K, V, dO, causal: bool = False):
     """Gradients of L = sum(O * dO) for O = attention_core(Q, K, V): chain rule through the softmax.
     Returns (dQ, dK, dV)."""

@@ -28,7 +28,7 @@ EXPORTS = (
     "ntp_reshard_grad", "ntp_kernel_timing_enable", "ntp_kernel_timing_read", "ntp_calibration_copy",
     "ntp_comp_sync_plan", "ntp_reshard_plan_create", "ntp_reshard_plan_segments", "ntp_reshard_plan_splits",
     "ntp_reshard_plan_table", "ntp_reshard_plan_run", "ntp_reshard_plan_destroy", "ntp_reshard_row_segments",
-    "ntp_mlp_shard_bwd_resharded", "ntp_attn_proj_shard_bwd_resharded",
+    "ntp_mlp_shard_bwd_resharded", "ntp_attn_proj_shard_bwd_resharded", "ntp_attn_core_shard_fwd",
 )
 
 
@@ -59,6 +59,12 @@ class TensorSpec(C.Structure):
 class Segment(C.Structure):
     _fields_ = [("src_rank", C.c_int32), ("dst_rank", C.c_int32), ("src_unit", C.c_int64),
                 ("dst_unit", C.c_int64), ("units", C.c_int64)]
+
+
+class AttnCoreShape(C.Structure):
+    _fields_ = [("n_seq", C.c_int32), ("seq_len", C.c_int32), ("q_cnt", C.c_int32), ("kv_cnt", C.c_int32),
+                ("q_off", C.c_int32), ("kv_off", C.c_int32), ("group", C.c_int32), ("head_dim", C.c_int32),
+                ("causal", C.c_int32)]
 
 
 class RowSegment(C.Structure):
@@ -113,6 +119,7 @@ def lib() -> C.CDLL:
                                                   + [C.c_int32, vp])
         L.ntp_attn_proj_shard_bwd_resharded.argtypes = ([C.POINTER(AttnShape)] + [vp, i64] * 8
                                                         + [segp, C.c_int32, segp, C.c_int32] + [C.c_int32, vp])
+        L.ntp_attn_core_shard_fwd.argtypes = [C.POINTER(AttnCoreShape), vp, i64, vp, i64, vp, vp]
         L.ntp_kernel_timing_enable.argtypes = [C.c_int32]
         L.ntp_kernel_timing_read.argtypes = [C.POINTER(KernelTime), i64, C.POINTER(i64)]
         L.ntp_calibration_copy.argtypes = [vp, vp, i64, vp]
@@ -227,6 +234,25 @@ def ntp_attn_proj_shard_bwd(M, H, w_qkv, w_o, dZ=None, dQKV=None, X=None, C_=Non
         args += list(_mat(t, f32))
     _check(lib().ntp_attn_proj_shard_bwd(C.byref(shape), *args, int(bool(accumulate)), _stream()),
            "ntp_attn_proj_shard_bwd")
+
+
+def attn_core_shape(n_seq, seq_len, plan: dict, group: int, causal: bool = False) -> AttnCoreShape:
+    """Shape of the attention core call from a rank's ntp_attn_shard_plan and the query heads per KV head."""
+    return AttnCoreShape(n_seq, seq_len, plan["q_cnt"], plan["kv_cnt"], plan["q_off"], plan["kv_off"], group,
+                         plan["head_dim"], int(bool(causal)))
+
+
+def ntp_attn_core_shard_fwd(shape: AttnCoreShape, QKV, C_, LSE=None) -> None:
+    """QKV [M, (q_cnt + 2 kv_cnt) d] bf16 -> C_ [M, q_cnt d] bf16 and LSE [q_cnt, M] fp32 (optional)."""
+    import torch
+    q, ldq = _mat(QKV, torch.bfloat16)
+    c, ldc = _mat(C_, torch.bfloat16)
+    lse = None
+    if LSE is not None:
+        if LSE.dtype != torch.float32 or not LSE.is_contiguous():
+            raise TypeError("LSE: contiguous fp32 expected")
+        lse = LSE.data_ptr()
+    _check(lib().ntp_attn_core_shard_fwd(C.byref(shape), q, ldq, c, ldc, lse, _stream()), "ntp_attn_core_shard_fwd")
 
 
 def ntp_reshard_row_segments(spec: TensorSpec, src_tp: int, src_rank: int, dst_tp: int, dst_shards):

@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libntp.so")
 
 SOURCES = ["ntp_plan.cpp", "ntp_layers.cpp", "ntp_timing.cpp", "ntp_gemm.hip", "ntp_gemm_nt.hip", "ntp_gemm_nn.hip",
-           "ntp_gemm_tn.hip", "ntp_reshard.hip"]
+           "ntp_gemm_tn.hip", "ntp_reshard.hip", "ntp_attn_core.hip"]
 
 # -packed-fp32-ops is switched off: the compiler must not form packed fp32 VALU ops.
 HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",

@@ -1,0 +1,284 @@
+// Attention core of one rank's local heads (Sec. 3.1, Eq. 5): C_j = softmax(Q_j K_g^T / sqrt(d)) V_g for
+// every local query head j and the KV head g it reads, sequence by sequence, forward and backward.
+//
+// Forward: one workgroup (4 wavefronts) takes 128 query rows of one (sequence, head); a wavefront owns
+// 32 of them.  Keys and values stream through LDS in tiles of 64 rows; scores never leave registers
+// (running maximum and sum per query row, output rescaled when the maximum moves).  Both products run
+// on the 16x16x32 bf16 matrix instruction with the query index on the lane axis:
+//   S^T tile = K_tile Q^T  : lane (l % 16) = query row, the lane's 4 values per block = 4 consecutive keys,
+//                            so a row's maximum and sum are mostly in-lane (two cross-lane steps);
+//   O^T     += V_tile^T P^T: the same lane owns the same query row, P goes from the score registers
+//                            straight into the second product (the key order inside a 32-key step is
+//                            permuted the same way on the V side, read transposed from LDS).
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+
+#include "ntp_gemm_kernels.h"
+#include "ntp_internal.h"
+
+namespace {
+
+using ntp_gemm::bf16x8;
+using ntp_gemm::f32x4;
+using ntp_gemm::s16x4;
+using ntp_gemm::s16x8;
+using ntp_gemm::u16x4;
+
+constexpr int kBQ = 128;   // query rows per workgroup
+constexpr int kBKV = 64;   // keys per tile
+constexpr int kThreads = 256;
+
+struct CoreArgs {
+  const uint16_t* QKV;  // [M x ld] bf16: [Q heads | K heads | V heads]
+  uint16_t* C;          // [M x ldc] bf16
+  float* LSE;           // [q_cnt x M] natural-log sum of exponentials of the scaled scores
+  int64_t ld, ldc;
+  int32_t n_seq, seq_len, q_cnt, kv_cnt, q_off, kv_off, group, causal;
+  int32_t q_tiles;      // per sequence
+  float scale_log2;     // log2(e) / sqrt(d)
+};
+
+__device__ __forceinline__ float xor_max(float v) {
+  v = fmaxf(v, __shfl_xor(v, 16));
+  return fmaxf(v, __shfl_xor(v, 32));
+}
+__device__ __forceinline__ float xor_sum(float v) {
+  v += __shfl_xor(v, 16);
+  return v + __shfl_xor(v, 32);
+}
+
+template <int D>
+__global__ __launch_bounds__(kThreads) void attn_core_fwd_kernel(const CoreArgs a) {
+  constexpr int LDT = D + 8;        // LDS row stride (elements): 16 rows x 16 bytes land on distinct banks
+  constexpr int KS = D / 32;        // K-steps of the score product
+  constexpr int DB = D / 16;        // 16-column blocks of the output
+  constexpr int CPR = D / 8;        // 16-byte chunks per tile row
+  constexpr int NLD = kBKV * CPR / kThreads;  // chunks per thread and tile
+  static_assert(D % 32 == 0 && (kBKV * CPR) % kThreads == 0, "tile copy: whole chunks per thread");
+  __shared__ __attribute__((aligned(16))) uint16_t sK[kBKV * LDT];
+  __shared__ __attribute__((aligned(16))) uint16_t sV[kBKV * LDT];
+
+  // workgroup -> (head, sequence, query tile); consecutive workgroups share a head's keys and values
+  const int qt = blockIdx.x % a.q_tiles;
+  const int sh = blockIdx.x / a.q_tiles;
+  const int seq = sh % a.n_seq, head = sh / a.n_seq;
+  const int g = (a.q_off + head) / a.group - a.kv_off;  // local KV head
+  const int S = a.seq_len;
+  const int64_t tok0 = int64_t(seq) * S;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lq = lane & 15, lh = lane >> 4;
+  const int q0 = qt * kBQ + wave * 32;  // first query row (in the sequence) of this wavefront
+
+  const uint16_t* Qp = a.QKV + int64_t(head) * D;
+  const uint16_t* Kp = a.QKV + int64_t(a.q_cnt + g) * D;
+  const uint16_t* Vp = a.QKV + int64_t(a.q_cnt + a.kv_cnt + g) * D;
+
+  // query fragments: operand B[k][j] with j = query row (lane % 16), k = 8 consecutive columns
+  bf16x8 qf[2][KS];
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb) {
+    const int qr = min(q0 + qb * 16 + lq, S - 1);  // rows past the end repeat the last one (never stored)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+      qf[qb][ks] = *reinterpret_cast<const bf16x8*>(Qp + (tok0 + qr) * a.ld + ks * 32 + lh * 8);
+  }
+
+  f32x4 acc[2][DB];
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+    for (int db = 0; db < DB; ++db) acc[qb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+
+  // keys this workgroup needs: all of the sequence, or up to its last query row
+  const int kv_end = a.causal ? min(S, qt * kBQ + kBQ) : S;
+  const int n_tiles = (kv_end + kBKV - 1) / kBKV;
+
+  // tile copy: global -> registers -> LDS, the next tile's loads in flight during the products
+  ntp_gemm::u16x8 rk[NLD], rv[NLD];
+  auto load_tile = [&](int t) {
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const int c = threadIdx.x + i * kThreads;
+      const int row = min(t * kBKV + c / CPR, S - 1);  // rows past the end repeat the last one (masked below)
+      const int64_t off = (tok0 + row) * a.ld + (c % CPR) * 8;
+      rk[i] = *reinterpret_cast<const ntp_gemm::u16x8*>(Kp + off);
+      rv[i] = *reinterpret_cast<const ntp_gemm::u16x8*>(Vp + off);
+    }
+  };
+  auto store_tile = [&]() {
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const int c = threadIdx.x + i * kThreads;
+      const int o = (c / CPR) * LDT + (c % CPR) * 8;
+      *reinterpret_cast<ntp_gemm::u16x8*>(sK + o) = rk[i];
+      *reinterpret_cast<ntp_gemm::u16x8*>(sV + o) = rv[i];
+    }
+  };
+
+  load_tile(0);
+  for (int t = 0; t < n_tiles; ++t) {
+    __syncthreads();  // everyone has finished reading the previous tile
+    store_tile();
+    __syncthreads();
+    if (t + 1 < n_tiles) load_tile(t + 1);
+    const int kv0 = t * kBKV;
+
+    // scores, transposed: st[kb][qb][r] = S[query qb*16 + lane%16][key kv0 + kb*16 + (lane/16)*4 + r]
+    f32x4 st[4][2];
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb) {
+      st[kb][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+      st[kb][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(sK + (kb * 16 + lq) * LDT + ks * 32 + lh * 8);
+        st[kb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[0][ks], st[kb][0], 0, 0, 0);
+        st[kb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[1][ks], st[kb][1], 0, 0, 0);
+      }
+    }
+
+    bf16x8 pf[2][2];  // P as operand B of the second product, per query block and 32-key step
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      const int qrow = q0 + qb * 16 + lq;
+      float mx = -INFINITY;
+#pragma unroll
+      for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int key = kv0 + kb * 16 + lh * 4 + r;
+          float s = st[kb][qb][r] * a.scale_log2;
+          if (key >= S || (a.causal && key > qrow)) s = -INFINITY;
+          st[kb][qb][r] = s;
+          mx = fmaxf(mx, s);
+        }
+      mx = xor_max(mx);
+      const float m_new = fmaxf(m_run[qb], mx);
+      // a row with no visible key yet (only rows past the end of a causal tile's diagonal) keeps m = -inf: use 0 there
+      const float m_use = m_new == -INFINITY ? 0.f : m_new;
+      const float alpha = exp2f(m_run[qb] - m_use);
+      float ls = 0.f;
+      float p[4][4];
+#pragma unroll
+      for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          p[kb][r] = exp2f(st[kb][qb][r] - m_use);
+          ls += p[kb][r];
+        }
+      l_run[qb] = l_run[qb] * alpha + ls;  // per-lane partial sum; the four lane groups are added at the end
+      m_run[qb] = m_new;
+#pragma unroll
+      for (int db = 0; db < DB; ++db) acc[qb][db] *= alpha;
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        bf16x8 f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          f[r] = static_cast<__bf16>(p[2 * s2][r]);
+          f[4 + r] = static_cast<__bf16>(p[2 * s2 + 1][r]);
+        }
+        pf[qb][s2] = f;
+      }
+    }
+
+    // O^T += V^T P^T.  Key slot (lane/16)*8 + t of step s2 is key 32 s2 + 4 (lane/16) + t for t < 4 and
+    // 32 s2 + 16 + 4 (lane/16) + (t - 4) for t >= 4: the order the scores sit in the registers.
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        // transposing read: in a 16-lane group, lane s points at 4 consecutive columns of key line (s >> 2);
+        // the group hands lane L the 4 keys of column L
+        const uint16_t* vp = sV + (s2 * 32 + lh * 4 + (lq >> 2)) * LDT + db * 16 + (lq & 3) * 4;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp + 16 * LDT));
+        const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        const bf16x8 vf = __builtin_bit_cast(bf16x8, both);
+        acc[0][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[0][s2], acc[0][db], 0, 0, 0);
+        acc[1][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[1][s2], acc[1][db], 0, 0, 0);
+      }
+    }
+  }
+
+  // normalise and store: lane holds output columns db*16 + (lane/16)*4 .. +3 of query row lane % 16
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb) {
+    const int qrow = q0 + qb * 16 + lq;
+    const float l = xor_sum(l_run[qb]);
+    const float inv = 1.0f / l;
+    if (qrow < S) {
+      uint16_t* cp = a.C + (tok0 + qrow) * a.ldc + int64_t(head) * D + lh * 4;
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        u16x4 o;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) o[r] = ntp_gemm::f32_to_bf16(acc[qb][db][r] * inv);
+        *reinterpret_cast<u16x4*>(cp + db * 16) = o;
+      }
+      if (lh == 0 && a.LSE) a.LSE[int64_t(head) * (int64_t(a.n_seq) * S) + tok0 + qrow] = (m_run[qb] + log2f(l)) * 0.6931471805599453f;
+    }
+  }
+}
+
+int check_core_shape(const ntp_attn_core_shape_t* s) {
+  if (!s || s->n_seq < 0 || s->seq_len < 0 || s->q_cnt < 0 || s->kv_cnt < 0 || s->group < 1 || s->q_off < 0 || s->kv_off < 0)
+    return NTP_ERR_INVALID_ARG;
+  if (s->head_dim != 64 && s->head_dim != 128) return NTP_ERR_UNSUPPORTED;
+  if (int64_t(s->n_seq) * s->seq_len > 0x7fffffffll) return NTP_ERR_UNSUPPORTED;
+  // every local query head must read a local KV head
+  for (int32_t j = 0; j < s->q_cnt; ++j) {
+    const int64_t g = int64_t(s->q_off + j) / s->group - s->kv_off;
+    if (g < 0 || g >= s->kv_cnt) return NTP_ERR_INVALID_ARG;
+  }
+  return NTP_OK;
+}
+
+}  // namespace
+
+extern "C" int ntp_attn_core_shard_fwd(const ntp_attn_core_shape_t* s, const void* QKV, int64_t ldqkv, void* C,
+                                       int64_t ldc, float* LSE, void* stream) {
+  int st = check_core_shape(s);
+  if (st != NTP_OK) return st;
+  const int64_t M = int64_t(s->n_seq) * s->seq_len;
+  if (M == 0 || s->q_cnt == 0) return NTP_OK;
+  if (!QKV || !C) return NTP_ERR_INVALID_ARG;
+  const int64_t wq = int64_t(s->q_cnt + 2 * s->kv_cnt) * s->head_dim, wo = int64_t(s->q_cnt) * s->head_dim;
+  if (ldqkv < wq || ldc < wo) return NTP_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(QKV) & 15) || (reinterpret_cast<uintptr_t>(C) & 15) || ldqkv % 8 || ldc % 8 ||
+      (reinterpret_cast<uintptr_t>(LSE) & 3))
+    return NTP_ERR_ALIGNMENT;
+  CoreArgs a{};
+  a.QKV = static_cast<const uint16_t*>(QKV);
+  a.C = static_cast<uint16_t*>(C);
+  a.LSE = LSE;
+  a.ld = ldqkv;
+  a.ldc = ldc;
+  a.n_seq = s->n_seq;
+  a.seq_len = s->seq_len;
+  a.q_cnt = s->q_cnt;
+  a.kv_cnt = s->kv_cnt;
+  a.q_off = s->q_off;
+  a.kv_off = s->kv_off;
+  a.group = s->group;
+  a.causal = s->causal ? 1 : 0;
+  a.q_tiles = (s->seq_len + kBQ - 1) / kBQ;
+  a.scale_log2 = float(1.4426950408889634 / std::sqrt(double(s->head_dim)));
+  const int64_t blocks = int64_t(a.q_tiles) * s->n_seq * s->q_cnt;
+  if (blocks > 0x7fffffffll) return NTP_ERR_UNSUPPORTED;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  if (ntp::timing_on())
+    ntp::timing_begin(stream, s->causal ? "attn_core_fwd_causal" : "attn_core_fwd",
+                      (s->causal ? 2.0 : 4.0) * double(s->n_seq) * double(s->seq_len) * double(s->seq_len) * s->head_dim * s->q_cnt, 0.0);
+  if (s->head_dim == 128)
+    hipLaunchKernelGGL(attn_core_fwd_kernel<128>, dim3(uint32_t(blocks)), dim3(kThreads), 0, hs, a);
+  else
+    hipLaunchKernelGGL(attn_core_fwd_kernel<64>, dim3(uint32_t(blocks)), dim3(kThreads), 0, hs, a);
+  const bool ok = hipGetLastError() == hipSuccess;
+  ntp::timing_end(stream);
+  return ok ? NTP_OK : NTP_ERR_LAUNCH;
+}

@@ -1,0 +1,96 @@
+"""Parity of the attention core (Eq. 5) on a rank's local heads against the oracle, on a real MI355X:
+forward output and log-sum-exp, uneven head counts, grouped KV heads, ragged sequence lengths, causal and
+unmasked."""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import ntp_oracle as O
+from paper_2504_06095_amd import inputs as I
+from tests import helpers as Hh
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(f"[gpu-case] {msg}", file=sys.stderr, flush=True)
+
+
+def _case(n_q, n_kv, tp, rank, d, n_seq, S, causal, seed=0, pad=0, std=1.0):
+    import torch
+    import paper_2504_06095_amd as N
+    plan = N.ntp_attn_shard_plan(n_q, n_kv, d, tp, rank)
+    oplan = O.attn_shard_plan(n_q, n_kv, tp, rank)
+    group = n_q // n_kv
+    M = n_seq * S
+    wq, wo = plan["w_qkv"], plan["w_o"]
+    bits, vals = I.normal_bf16(seed, f"core.QKV.{n_q}.{n_kv}.{tp}.{rank}.{d}.{M}", (M, wq), std)
+    QKV = Hh.to_dev_bf16(bits, wq + pad)
+    C = torch.full((M, wo + pad), float("nan"), dtype=torch.bfloat16, device="cuda")[:, :wo]
+    LSE = torch.full((plan["q_cnt"], M), float("nan"), dtype=torch.float32, device="cuda")
+    shape = N.attn_core_shape(n_seq, S, plan, group, causal)
+    N.ntp_attn_core_shard_fwd(shape, QKV, C, LSE)
+    torch.cuda.synchronize()
+    if wo == 0:
+        return 0.0  # a rank without heads: the call is a no-op
+    x = vals.astype(np.float64)
+    want = O.attn_core_shard_fwd(x, oplan, group, d, n_seq, causal)
+    got = Hh.dev_bf16_to_f64(C)
+    assert np.isfinite(got).all()
+    assert Hh.rel_err(got, want) <= Hh.TOL, Hh.rel_err(got, want)
+    qc, kc = oplan["q_cnt"], oplan["kv_cnt"]
+    lse = LSE.cpu().numpy().astype(np.float64)
+    for s in range(n_seq):
+        rows = slice(s * S, (s + 1) * S)
+        for j in range(qc):
+            g = (oplan["q_off"] + j) // group - oplan["kv_off"]
+            w = O.attention_lse(x[rows, j * d:(j + 1) * d], x[rows, (qc + g) * d:(qc + g + 1) * d], causal)
+            assert np.abs(lse[j, rows] - w).max() <= 2e-2 * max(1.0, np.abs(w).max()), (s, j)
+    return Hh.rel_err(got, want)
+
+
+CASES = [
+    # n_q, n_kv, tp, rank, d, n_seq, S
+    (8, 2, 3, 0, 128, 2, 200),    # 3 local heads over 1-2 KV heads, ragged length, two sequences
+    (8, 2, 3, 2, 128, 1, 129),    # 2 local heads; one row past a 128-row tile
+    (64, 8, 30, 3, 128, 1, 512),  # config-3 head plan (3 heads), several key tiles
+    (64, 8, 30, 29, 128, 1, 384), # a rank with 2 heads
+    (6, 6, 4, 1, 128, 3, 64),     # no grouping, exactly one key tile
+    (4, 4, 2, 0, 64, 2, 100),     # head dimension 64
+    (4, 1, 4, 3, 128, 1, 1),      # a single token
+    (4, 2, 8, 6, 128, 1, 50),     # more ranks than heads: this rank has none
+]
+
+
+@pytest.mark.parametrize("causal", [False, True], ids=["full", "causal"])
+@pytest.mark.parametrize("n_q,n_kv,tp,rank,d,n_seq,S", CASES)
+def test_attn_core_fwd_matches_oracle(n_q, n_kv, tp, rank, d, n_seq, S, causal):
+    _say(f"attn core fwd n_q={n_q} n_kv={n_kv} tp={tp} rank={rank} d={d} n_seq={n_seq} S={S} causal={causal}")
+    _case(n_q, n_kv, tp, rank, d, n_seq, S, causal)
+
+
+def test_attn_core_fwd_padded_rows_and_peaked_scores():
+    _say("attn core fwd: padded leading dimensions, large scores")
+    _case(8, 2, 3, 1, 128, 1, 300, True, seed=3, pad=8)
+    # scores with a standard deviation of ~30: the softmax is nearly one-hot, the running maximum moves a lot
+    _case(8, 2, 3, 1, 128, 1, 300, False, seed=4, std=5.0)
+
+
+def test_attn_core_rejects_bad_arguments():
+    import torch
+    import paper_2504_06095_amd as N
+    _say("attn core: error paths")
+    K = N.binding
+    plan = dict(q_cnt=2, kv_cnt=1, q_off=0, kv_off=0, head_dim=128)
+    QKV = torch.zeros(64, 4 * 128, dtype=torch.bfloat16, device="cuda")
+    Cc = torch.zeros(64, 2 * 128, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(N.NtpError) as e:  # head dimension not built
+        N.ntp_attn_core_shard_fwd(N.attn_core_shape(1, 64, dict(plan, head_dim=96), 2), QKV, Cc)
+    assert e.value.status == K.NTP_ERR_UNSUPPORTED
+    with pytest.raises(N.NtpError) as e:  # a query head whose KV head is not local
+        N.ntp_attn_core_shard_fwd(N.attn_core_shape(1, 64, dict(plan, q_off=2), 2), QKV, Cc)
+    assert e.value.status == K.NTP_ERR_INVALID_ARG
+    with pytest.raises(N.NtpError) as e:  # QKV narrower than the heads need
+        N.ntp_attn_core_shard_fwd(N.attn_core_shape(1, 64, plan, 2), torch.zeros(64, 384, dtype=torch.bfloat16, device="cuda"), Cc)
+    assert e.value.status == K.NTP_ERR_INVALID_ARG

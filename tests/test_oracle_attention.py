@@ -51,6 +51,21 @@ def test_softmax_invariances():
     assert np.isfinite(O.attention_core(300.0 * Q, 300.0 * K, V)).all()
 
 
+@pytest.mark.parametrize("causal", [False, True])
+def test_lse_is_the_softmax_normaliser(causal):
+    g = _rng(8)
+    S, d = 6, 4
+    Q, K, V = g.standard_normal((S, d)), g.standard_normal((S, d)), g.standard_normal((S, d))
+    lse = O.attention_lse(Q, K, causal)
+    W = np.exp((Q @ K.T) / math.sqrt(d) - lse[:, None])
+    if causal:
+        W = np.tril(W)
+    np.testing.assert_allclose(W.sum(1), 1.0, atol=1e-13)
+    np.testing.assert_allclose(W @ V, O.attention_core(Q, K, V, causal), atol=1e-13)
+    # one visible key: the normaliser is that key's score
+    np.testing.assert_allclose(O.attention_lse(Q[:1], K[:1]), (Q[:1] @ K[:1].T)[0] / math.sqrt(d), atol=1e-14)
+
+
 def test_scale_is_one_over_sqrt_d():
     # two keys, scores q.k / sqrt(d): closed-form logistic weight, for d = 4 and d = 16
     for d in (4, 16):
