@@ -228,6 +228,17 @@ typedef struct ntp_attn_core_shape {
 } ntp_attn_core_shape_t;
 int ntp_attn_core_shard_fwd(const ntp_attn_core_shape_t* shape, const void* QKV, int64_t ldqkv,
                             void* C, int64_t ldc, float* LSE, void* stream);
+/* Gradient of the above: given dC [M x q_cnt head_dim] (what ntp_attn_proj_shard_bwd
+ * returns), the forward call's QKV, C and LSE, writes dQKV [M x (q_cnt + 2 kv_cnt)
+ * head_dim] in QKV's layout (what ntp_attn_proj_shard_bwd takes); the gradient of a
+ * KV head is the sum over the local query heads that read it, and zero for a KV head
+ * that none reads.  Delta: DEVICE scratch, fp32 [q_cnt x M], overwritten (per head
+ * and token the dot product of the rows of dC and C).  All matrices bf16, 16-byte
+ * aligned, leading dimensions multiples of 8; QKV and dQKV must not overlap. */
+int ntp_attn_core_shard_bwd(const ntp_attn_core_shape_t* shape, const void* QKV, int64_t ldqkv,
+                            const void* C, int64_t ldc, const void* dC, int64_t lddc,
+                            const float* LSE, float* Delta, void* dQKV, int64_t lddqkv,
+                            void* stream);
 
 /* ---------------------------------------------------------------------------
  * Weight gradients written straight into the destination layout of the

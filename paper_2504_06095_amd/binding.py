@@ -28,7 +28,7 @@ EXPORTS = (
     "ntp_reshard_grad", "ntp_kernel_timing_enable", "ntp_kernel_timing_read", "ntp_calibration_copy",
     "ntp_comp_sync_plan", "ntp_reshard_plan_create", "ntp_reshard_plan_segments", "ntp_reshard_plan_splits",
     "ntp_reshard_plan_table", "ntp_reshard_plan_run", "ntp_reshard_plan_destroy", "ntp_reshard_row_segments",
-    "ntp_mlp_shard_bwd_resharded", "ntp_attn_proj_shard_bwd_resharded", "ntp_attn_core_shard_fwd",
+    "ntp_mlp_shard_bwd_resharded", "ntp_attn_proj_shard_bwd_resharded", "ntp_attn_core_shard_fwd", "ntp_attn_core_shard_bwd",
 )
 
 
@@ -120,6 +120,7 @@ def lib() -> C.CDLL:
         L.ntp_attn_proj_shard_bwd_resharded.argtypes = ([C.POINTER(AttnShape)] + [vp, i64] * 8
                                                         + [segp, C.c_int32, segp, C.c_int32] + [C.c_int32, vp])
         L.ntp_attn_core_shard_fwd.argtypes = [C.POINTER(AttnCoreShape), vp, i64, vp, i64, vp, vp]
+        L.ntp_attn_core_shard_bwd.argtypes = [C.POINTER(AttnCoreShape), vp, i64, vp, i64, vp, i64, vp, vp, vp, i64, vp]
         L.ntp_kernel_timing_enable.argtypes = [C.c_int32]
         L.ntp_kernel_timing_read.argtypes = [C.POINTER(KernelTime), i64, C.POINTER(i64)]
         L.ntp_calibration_copy.argtypes = [vp, vp, i64, vp]
@@ -253,6 +254,22 @@ def ntp_attn_core_shard_fwd(shape: AttnCoreShape, QKV, C_, LSE=None) -> None:
             raise TypeError("LSE: contiguous fp32 expected")
         lse = LSE.data_ptr()
     _check(lib().ntp_attn_core_shard_fwd(C.byref(shape), q, ldq, c, ldc, lse, _stream()), "ntp_attn_core_shard_fwd")
+
+
+def ntp_attn_core_shard_bwd(shape: AttnCoreShape, QKV, C_, dC, LSE, Delta, dQKV) -> None:
+    """Gradient of the attention core: dQKV (QKV's layout) from dC; LSE from the forward call, Delta scratch
+    (both contiguous fp32 [q_cnt, M])."""
+    import torch
+    bf = torch.bfloat16
+    q, ldq = _mat(QKV, bf)
+    c, ldc = _mat(C_, bf)
+    g, ldg = _mat(dC, bf)
+    d, ldd = _mat(dQKV, bf)
+    for t in (LSE, Delta):
+        if t.dtype != torch.float32 or not t.is_contiguous() or not t.is_cuda:
+            raise TypeError("LSE / Delta: contiguous fp32 device tensors expected")
+    _check(lib().ntp_attn_core_shard_bwd(C.byref(shape), q, ldq, c, ldc, g, ldg, LSE.data_ptr(), Delta.data_ptr(), d, ldd,
+                                         _stream()), "ntp_attn_core_shard_bwd")
 
 
 def ntp_reshard_row_segments(spec: TensorSpec, src_tp: int, src_rank: int, dst_tp: int, dst_shards):

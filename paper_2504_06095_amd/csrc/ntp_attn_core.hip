@@ -225,6 +225,354 @@ __global__ __launch_bounds__(kThreads) void attn_core_fwd_kernel(const CoreArgs 
   }
 }
 
+// ---- backward ---------------------------------------------------------------------------------
+// With P = softmax rows (rebuilt from the saved log-sum-exp), dP = dC V^T and
+// delta_i = sum_d dC_id C_id:  dS = P .* (dP - delta),  dQ = dS K / sqrt(d),  dK = dS^T Q / sqrt(d),
+// dV = P^T dC.  Two kernels, no atomics: one owns query rows and walks over the keys (dQ, and delta on
+// the way), one owns keys and walks over the query rows of every local query head that reads them
+// (dK, dV).  Both keep the owned index on the lane axis like the forward kernel.
+struct CoreBwdArgs {
+  const uint16_t* QKV;
+  const uint16_t* C;
+  const uint16_t* dC;
+  const float* LSE;
+  float* Delta;
+  uint16_t* dQKV;
+  int64_t ld, ldc, lddc, ldd;
+  int32_t n_seq, seq_len, q_cnt, kv_cnt, q_off, kv_off, group, causal;
+  int32_t tiles;        // query tiles (dQ kernel) or key tiles (dK/dV kernel) per sequence
+  float scale_log2;     // log2(e) / sqrt(d)
+  float scale;          // 1 / sqrt(d)
+};
+
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4_t;
+
+// Operand A[i = column c0 + lane%16][k = row slot] of a row-major LDS tile: rows 4 (lane/16) .. + 3 from
+// r0 on for slots 0..3 and the same 16 rows further down for slots 4..7 (see the forward kernel).
+__device__ __forceinline__ bf16x8 tr_frag(const uint16_t* tile, int ldt, int r0, int c0, int lq, int lh) {
+  const uint16_t* vp = tile + (r0 + lh * 4 + (lq >> 2)) * ldt + c0 + (lq & 3) * 4;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(vp));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(vp + 16 * ldt));
+  const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  return __builtin_bit_cast(bf16x8, both);
+}
+
+// dQ (and delta): a workgroup takes 128 query rows of one (sequence, head), a wavefront 32 of them.
+template <int D>
+__global__ __launch_bounds__(kThreads) void attn_core_bwd_dq_kernel(const CoreBwdArgs a) {
+  constexpr int LDT = D + 8, KS = D / 32, DB = D / 16, CPR = D / 8, NLD = kBKV * CPR / kThreads;
+  __shared__ __attribute__((aligned(16))) uint16_t sK[kBKV * LDT];
+  __shared__ __attribute__((aligned(16))) uint16_t sV[kBKV * LDT];
+  const int qt = blockIdx.x % a.tiles;
+  const int sh = blockIdx.x / a.tiles;
+  const int seq = sh % a.n_seq, head = sh / a.n_seq;
+  const int g = (a.q_off + head) / a.group - a.kv_off;
+  const int S = a.seq_len;
+  const int64_t tok0 = int64_t(seq) * S, Mtot = int64_t(a.n_seq) * S;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lq = lane & 15, lh = lane >> 4;
+  const int q0 = qt * kBQ + wave * 32;
+  const uint16_t* Qp = a.QKV + int64_t(head) * D;
+  const uint16_t* Kp = a.QKV + int64_t(a.q_cnt + g) * D;
+  const uint16_t* Vp = a.QKV + int64_t(a.q_cnt + a.kv_cnt + g) * D;
+
+  // query and output-gradient fragments (operand B: j = query row), delta and the log-sum-exp of the rows
+  bf16x8 qf[2][KS], gf[2][KS];
+  float lse2[2], delta[2];
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb) {
+    const int qr = min(q0 + qb * 16 + lq, S - 1);
+    float part = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      qf[qb][ks] = *reinterpret_cast<const bf16x8*>(Qp + (tok0 + qr) * a.ld + ks * 32 + lh * 8);
+      gf[qb][ks] = *reinterpret_cast<const bf16x8*>(a.dC + (tok0 + qr) * a.lddc + int64_t(head) * D + ks * 32 + lh * 8);
+      const bf16x8 of = *reinterpret_cast<const bf16x8*>(a.C + (tok0 + qr) * a.ldc + int64_t(head) * D + ks * 32 + lh * 8);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) part += float(gf[qb][ks][e]) * float(of[e]);
+    }
+    delta[qb] = xor_sum(part);
+    lse2[qb] = a.LSE[int64_t(head) * Mtot + tok0 + qr] * 1.4426950408889634f;
+    if (lh == 0 && q0 + qb * 16 + lq < S) a.Delta[int64_t(head) * Mtot + tok0 + qr] = delta[qb];
+  }
+
+  f32x4 acc[2][DB];
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+    for (int db = 0; db < DB; ++db) acc[qb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const int kv_end = a.causal ? min(S, qt * kBQ + kBQ) : S;
+  const int n_tiles = (kv_end + kBKV - 1) / kBKV;
+  ntp_gemm::u16x8 rk[NLD], rv[NLD];
+  auto load_tile = [&](int t) {
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const int c = threadIdx.x + i * kThreads;
+      const int row = min(t * kBKV + c / CPR, S - 1);
+      const int64_t off = (tok0 + row) * a.ld + (c % CPR) * 8;
+      rk[i] = *reinterpret_cast<const ntp_gemm::u16x8*>(Kp + off);
+      rv[i] = *reinterpret_cast<const ntp_gemm::u16x8*>(Vp + off);
+    }
+  };
+  auto store_tile = [&]() {
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const int c = threadIdx.x + i * kThreads;
+      const int o = (c / CPR) * LDT + (c % CPR) * 8;
+      *reinterpret_cast<ntp_gemm::u16x8*>(sK + o) = rk[i];
+      *reinterpret_cast<ntp_gemm::u16x8*>(sV + o) = rv[i];
+    }
+  };
+
+  load_tile(0);
+  for (int t = 0; t < n_tiles; ++t) {
+    __syncthreads();
+    store_tile();
+    __syncthreads();
+    if (t + 1 < n_tiles) load_tile(t + 1);
+    const int kv0 = t * kBKV;
+    // S^T and dP^T blocks: [key kb*16 + (lane/16)*4 + r][query qb*16 + lane%16]
+    f32x4 st[4][2], dpt[4][2];
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb) {
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) {
+        st[kb][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        dpt[kb][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
+      }
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(sK + (kb * 16 + lq) * LDT + ks * 32 + lh * 8);
+        const bf16x8 vf = *reinterpret_cast<const bf16x8*>(sV + (kb * 16 + lq) * LDT + ks * 32 + lh * 8);
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+          st[kb][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[qb][ks], st[kb][qb], 0, 0, 0);
+          dpt[kb][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, gf[qb][ks], dpt[kb][qb], 0, 0, 0);
+        }
+      }
+    }
+    bf16x8 dsf[2][2];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      const int qrow = q0 + qb * 16 + lq;
+      float ds[4][4];
+#pragma unroll
+      for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int key = kv0 + kb * 16 + lh * 4 + r;
+          const bool seen = key < S && !(a.causal && key > qrow);
+          const float p = seen ? exp2f(st[kb][qb][r] * a.scale_log2 - lse2[qb]) : 0.f;
+          ds[kb][r] = p * (dpt[kb][qb][r] - delta[qb]);
+        }
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        bf16x8 f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          f[r] = static_cast<__bf16>(ds[2 * s2][r]);
+          f[4 + r] = static_cast<__bf16>(ds[2 * s2 + 1][r]);
+        }
+        dsf[qb][s2] = f;
+      }
+    }
+    // dQ^T += K^T dS^T
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const bf16x8 kt = tr_frag(sK, LDT, s2 * 32, db * 16, lq, lh);
+        acc[0][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kt, dsf[0][s2], acc[0][db], 0, 0, 0);
+        acc[1][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kt, dsf[1][s2], acc[1][db], 0, 0, 0);
+      }
+  }
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb) {
+    const int qrow = q0 + qb * 16 + lq;
+    if (qrow >= S) continue;
+    uint16_t* op = a.dQKV + (tok0 + qrow) * a.ldd + int64_t(head) * D + lh * 4;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      u16x4 o;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) o[r] = ntp_gemm::f32_to_bf16(acc[qb][db][r] * a.scale);
+      *reinterpret_cast<u16x4*>(op + db * 16) = o;
+    }
+  }
+}
+
+// dK and dV: a workgroup takes 128 keys of one (sequence, KV head), a wavefront 32 of them, and walks over
+// the query rows (tiles of 64) of every local query head that reads this KV head.
+template <int D>
+__global__ __launch_bounds__(kThreads) void attn_core_bwd_dkv_kernel(const CoreBwdArgs a) {
+  constexpr int LDT = D + 8, KS = D / 32, DB = D / 16, CPR = D / 8, NLD = kBKV * CPR / kThreads;
+  __shared__ __attribute__((aligned(16))) uint16_t sQ[kBKV * LDT];
+  __shared__ __attribute__((aligned(16))) uint16_t sG[kBKV * LDT];
+  __shared__ __attribute__((aligned(16))) float sL[kBKV];
+  __shared__ __attribute__((aligned(16))) float sD[kBKV];
+  const int kt = blockIdx.x % a.tiles;
+  const int sh = blockIdx.x / a.tiles;
+  const int seq = sh % a.n_seq, g = sh / a.n_seq;  // g: local KV head
+  const int S = a.seq_len;
+  const int64_t tok0 = int64_t(seq) * S, Mtot = int64_t(a.n_seq) * S;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lq = lane & 15, lh = lane >> 4;
+  const int k0 = kt * kBQ + wave * 32;  // first key of this wavefront
+  const uint16_t* Kp = a.QKV + int64_t(a.q_cnt + g) * D;
+  const uint16_t* Vp = a.QKV + int64_t(a.q_cnt + a.kv_cnt + g) * D;
+
+  // key and value fragments (operand B: j = key)
+  bf16x8 kf[2][KS], vf[2][KS];
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb) {
+    const int kr = min(k0 + kb * 16 + lq, S - 1);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      kf[kb][ks] = *reinterpret_cast<const bf16x8*>(Kp + (tok0 + kr) * a.ld + ks * 32 + lh * 8);
+      vf[kb][ks] = *reinterpret_cast<const bf16x8*>(Vp + (tok0 + kr) * a.ld + ks * 32 + lh * 8);
+    }
+  }
+  f32x4 dk[2][DB], dv[2][DB];
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      dk[kb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
+      dv[kb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+  // query tiles this workgroup needs: all, or from the tile that holds its first key on
+  const int q_first = a.causal ? (kt * kBQ) / kBKV : 0;
+  const int q_tiles = (S + kBKV - 1) / kBKV;
+  ntp_gemm::u16x8 rq[NLD], rg[NLD];
+  float rl = 0.f, rd = 0.f;
+  for (int head = 0; head < a.q_cnt; ++head) {
+    if ((a.q_off + head) / a.group - a.kv_off != g) continue;  // the same for the whole workgroup
+    const uint16_t* Qp = a.QKV + int64_t(head) * D;
+    const uint16_t* Gp = a.dC + int64_t(head) * D;
+    auto load_tile = [&](int t) {
+#pragma unroll
+      for (int i = 0; i < NLD; ++i) {
+        const int c = threadIdx.x + i * kThreads;
+        const int row = min(t * kBKV + c / CPR, S - 1);
+        rq[i] = *reinterpret_cast<const ntp_gemm::u16x8*>(Qp + (tok0 + row) * a.ld + (c % CPR) * 8);
+        rg[i] = *reinterpret_cast<const ntp_gemm::u16x8*>(Gp + (tok0 + row) * a.lddc + (c % CPR) * 8);
+      }
+      if (threadIdx.x < kBKV) {
+        const int row = min(t * kBKV + int(threadIdx.x), S - 1);
+        rl = a.LSE[int64_t(head) * Mtot + tok0 + row] * 1.4426950408889634f;
+        rd = a.Delta[int64_t(head) * Mtot + tok0 + row];
+      }
+    };
+    auto store_tile = [&]() {
+#pragma unroll
+      for (int i = 0; i < NLD; ++i) {
+        const int c = threadIdx.x + i * kThreads;
+        const int o = (c / CPR) * LDT + (c % CPR) * 8;
+        *reinterpret_cast<ntp_gemm::u16x8*>(sQ + o) = rq[i];
+        *reinterpret_cast<ntp_gemm::u16x8*>(sG + o) = rg[i];
+      }
+      if (threadIdx.x < kBKV) {
+        sL[threadIdx.x] = rl;
+        sD[threadIdx.x] = rd;
+      }
+    };
+    if (q_first >= q_tiles) continue;
+    load_tile(q_first);
+    for (int t = q_first; t < q_tiles; ++t) {
+      __syncthreads();
+      store_tile();
+      __syncthreads();
+      if (t + 1 < q_tiles) load_tile(t + 1);
+      const int qbase = t * kBKV;
+      // S and dP blocks: [query qb*16 + (lane/16)*4 + r][key kb*16 + lane%16]
+      f32x4 sc[4][2], dp[4][2];
+#pragma unroll
+      for (int qb = 0; qb < 4; ++qb) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+          sc[qb][kb] = f32x4{0.f, 0.f, 0.f, 0.f};
+          dp[qb][kb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          const bf16x8 qa = *reinterpret_cast<const bf16x8*>(sQ + (qb * 16 + lq) * LDT + ks * 32 + lh * 8);
+          const bf16x8 ga = *reinterpret_cast<const bf16x8*>(sG + (qb * 16 + lq) * LDT + ks * 32 + lh * 8);
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb) {
+            sc[qb][kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa, kf[kb][ks], sc[qb][kb], 0, 0, 0);
+            dp[qb][kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ga, vf[kb][ks], dp[qb][kb], 0, 0, 0);
+          }
+        }
+      }
+      bf16x8 pf[2][2], dsf[2][2];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        const int key = k0 + kb * 16 + lq;
+        float p[4][4], ds[4][4];
+#pragma unroll
+        for (int qb = 0; qb < 4; ++qb) {
+          const f32x4 l4 = *reinterpret_cast<const f32x4*>(sL + qb * 16 + lh * 4);
+          const f32x4 d4 = *reinterpret_cast<const f32x4*>(sD + qb * 16 + lh * 4);
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int qrow = qbase + qb * 16 + lh * 4 + r;
+            const bool seen = qrow < S && key < S && !(a.causal && key > qrow);
+            p[qb][r] = seen ? exp2f(sc[qb][kb][r] * a.scale_log2 - l4[r]) : 0.f;
+            ds[qb][r] = p[qb][r] * (dp[qb][kb][r] - d4[r]);
+          }
+        }
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          bf16x8 f, h;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            f[r] = static_cast<__bf16>(p[2 * s2][r]);
+            f[4 + r] = static_cast<__bf16>(p[2 * s2 + 1][r]);
+            h[r] = static_cast<__bf16>(ds[2 * s2][r]);
+            h[4 + r] = static_cast<__bf16>(ds[2 * s2 + 1][r]);
+          }
+          pf[kb][s2] = f;
+          dsf[kb][s2] = h;
+        }
+      }
+      // dV^T += dC^T P, dK^T += Q^T dS (query slots in the order the scores sit in the registers)
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          const bf16x8 gt = tr_frag(sG, LDT, s2 * 32, db * 16, lq, lh);
+          const bf16x8 qt2 = tr_frag(sQ, LDT, s2 * 32, db * 16, lq, lh);
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb) {
+            dv[kb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(gt, pf[kb][s2], dv[kb][db], 0, 0, 0);
+            dk[kb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qt2, dsf[kb][s2], dk[kb][db], 0, 0, 0);
+          }
+        }
+    }
+    __syncthreads();  // the next head's first tile overwrites LDS
+  }
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb) {
+    const int key = k0 + kb * 16 + lq;
+    if (key >= S) continue;
+    uint16_t* kp = a.dQKV + (tok0 + key) * a.ldd + int64_t(a.q_cnt + g) * D + lh * 4;
+    uint16_t* vp = a.dQKV + (tok0 + key) * a.ldd + int64_t(a.q_cnt + a.kv_cnt + g) * D + lh * 4;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      u16x4 ok, ov;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        ok[r] = ntp_gemm::f32_to_bf16(dk[kb][db][r] * a.scale);
+        ov[r] = ntp_gemm::f32_to_bf16(dv[kb][db][r]);
+      }
+      *reinterpret_cast<u16x4*>(kp + db * 16) = ok;
+      *reinterpret_cast<u16x4*>(vp + db * 16) = ov;
+    }
+  }
+}
+
 int check_core_shape(const ntp_attn_core_shape_t* s) {
   if (!s || s->n_seq < 0 || s->seq_len < 0 || s->q_cnt < 0 || s->kv_cnt < 0 || s->group < 1 || s->q_off < 0 || s->kv_off < 0)
     return NTP_ERR_INVALID_ARG;
@@ -280,5 +628,70 @@ extern "C" int ntp_attn_core_shard_fwd(const ntp_attn_core_shape_t* s, const voi
     hipLaunchKernelGGL(attn_core_fwd_kernel<64>, dim3(uint32_t(blocks)), dim3(kThreads), 0, hs, a);
   const bool ok = hipGetLastError() == hipSuccess;
   ntp::timing_end(stream);
+  return ok ? NTP_OK : NTP_ERR_LAUNCH;
+}
+
+extern "C" int ntp_attn_core_shard_bwd(const ntp_attn_core_shape_t* s, const void* QKV, int64_t ldqkv, const void* C,
+                                       int64_t ldc, const void* dC, int64_t lddc, const float* LSE, float* Delta,
+                                       void* dQKV, int64_t lddqkv, void* stream) {
+  int st = check_core_shape(s);
+  if (st != NTP_OK) return st;
+  const int64_t M = int64_t(s->n_seq) * s->seq_len;
+  if (M == 0 || (s->q_cnt == 0 && s->kv_cnt == 0)) return NTP_OK;
+  if (!QKV || !dQKV || (s->q_cnt > 0 && (!C || !dC || !LSE || !Delta))) return NTP_ERR_INVALID_ARG;
+  const int64_t wq = int64_t(s->q_cnt + 2 * s->kv_cnt) * s->head_dim, wo = int64_t(s->q_cnt) * s->head_dim;
+  if (ldqkv < wq || lddqkv < wq || ldc < wo || lddc < wo) return NTP_ERR_INVALID_ARG;
+  auto mis = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) != 0; };
+  if (mis(QKV) || mis(dQKV) || mis(C) || mis(dC) || ldqkv % 8 || lddqkv % 8 || ldc % 8 || lddc % 8 ||
+      (reinterpret_cast<uintptr_t>(LSE) & 3) || (reinterpret_cast<uintptr_t>(Delta) & 3))
+    return NTP_ERR_ALIGNMENT;
+  CoreBwdArgs a{};
+  a.QKV = static_cast<const uint16_t*>(QKV);
+  a.C = static_cast<const uint16_t*>(C);
+  a.dC = static_cast<const uint16_t*>(dC);
+  a.LSE = LSE;
+  a.Delta = Delta;
+  a.dQKV = static_cast<uint16_t*>(dQKV);
+  a.ld = ldqkv;
+  a.ldc = ldc;
+  a.lddc = lddc;
+  a.ldd = lddqkv;
+  a.n_seq = s->n_seq;
+  a.seq_len = s->seq_len;
+  a.q_cnt = s->q_cnt;
+  a.kv_cnt = s->kv_cnt;
+  a.q_off = s->q_off;
+  a.kv_off = s->kv_off;
+  a.group = s->group;
+  a.causal = s->causal ? 1 : 0;
+  a.tiles = (s->seq_len + kBQ - 1) / kBQ;
+  a.scale = float(1.0 / std::sqrt(double(s->head_dim)));
+  a.scale_log2 = float(1.4426950408889634 / std::sqrt(double(s->head_dim)));
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  const double pair_flops = (s->causal ? 1.0 : 2.0) * double(s->n_seq) * double(s->seq_len) * double(s->seq_len) * s->head_dim * s->q_cnt;
+  bool ok = true;
+  const int64_t bq = int64_t(a.tiles) * s->n_seq * s->q_cnt, bk = int64_t(a.tiles) * s->n_seq * s->kv_cnt;
+  if (bq > 0x7fffffffll || bk > 0x7fffffffll) return NTP_ERR_UNSUPPORTED;
+  if (bq > 0) {
+    // dQ and delta: three products per (query, key) pair
+    if (ntp::timing_on()) ntp::timing_begin(stream, "attn_core_bwd_dq", 3.0 * pair_flops, 0.0);
+    if (s->head_dim == 128)
+      hipLaunchKernelGGL(attn_core_bwd_dq_kernel<128>, dim3(uint32_t(bq)), dim3(kThreads), 0, hs, a);
+    else
+      hipLaunchKernelGGL(attn_core_bwd_dq_kernel<64>, dim3(uint32_t(bq)), dim3(kThreads), 0, hs, a);
+    ok = hipGetLastError() == hipSuccess;
+    ntp::timing_end(stream);
+    if (!ok) return NTP_ERR_LAUNCH;
+  }
+  if (bk > 0) {
+    // dK and dV: four products per pair
+    if (ntp::timing_on()) ntp::timing_begin(stream, "attn_core_bwd_dkv", 4.0 * pair_flops, 0.0);
+    if (s->head_dim == 128)
+      hipLaunchKernelGGL(attn_core_bwd_dkv_kernel<128>, dim3(uint32_t(bk)), dim3(kThreads), 0, hs, a);
+    else
+      hipLaunchKernelGGL(attn_core_bwd_dkv_kernel<64>, dim3(uint32_t(bk)), dim3(kThreads), 0, hs, a);
+    ok = hipGetLastError() == hipSuccess;
+    ntp::timing_end(stream);
+  }
   return ok ? NTP_OK : NTP_ERR_LAUNCH;
 }

@@ -70,6 +70,52 @@ def test_attn_core_fwd_matches_oracle(n_q, n_kv, tp, rank, d, n_seq, S, causal):
     _case(n_q, n_kv, tp, rank, d, n_seq, S, causal)
 
 
+def _bwd_case(n_q, n_kv, tp, rank, d, n_seq, S, causal, seed=1, pad=0):
+    import torch
+    import paper_2504_06095_amd as N
+    plan = N.ntp_attn_shard_plan(n_q, n_kv, d, tp, rank)
+    oplan = O.attn_shard_plan(n_q, n_kv, tp, rank)
+    group = n_q // n_kv
+    M = n_seq * S
+    wq, wo = plan["w_qkv"], plan["w_o"]
+    qc, kc = plan["q_cnt"], plan["kv_cnt"]
+    bits, vals = I.normal_bf16(seed, f"coreb.QKV.{n_q}.{n_kv}.{tp}.{rank}.{d}.{M}", (M, wq), 1.0)
+    gbits, gvals = I.normal_bf16(seed, f"coreb.dC.{n_q}.{n_kv}.{tp}.{rank}.{d}.{M}", (M, wo), 1.0)
+    QKV, dC = Hh.to_dev_bf16(bits, wq + pad), Hh.to_dev_bf16(gbits, wo + pad)
+    nanbf = lambda r, c: torch.full((r, c + pad), float("nan"), dtype=torch.bfloat16, device="cuda")[:, :c]
+    C, dQKV = nanbf(M, wo), nanbf(M, wq)
+    LSE = torch.full((qc, M), float("nan"), dtype=torch.float32, device="cuda")
+    Delta = torch.full((qc, M), float("nan"), dtype=torch.float32, device="cuda")
+    shape = N.attn_core_shape(n_seq, S, plan, group, causal)
+    N.ntp_attn_core_shard_fwd(shape, QKV, C, LSE)
+    N.ntp_attn_core_shard_bwd(shape, QKV, C, dC, LSE, Delta, dQKV)
+    torch.cuda.synchronize()
+    x, gC = vals.astype(np.float64), gvals.astype(np.float64)
+    want = O.attn_core_shard_bwd(x, gC, oplan, group, d, n_seq, causal)
+    got = Hh.dev_bf16_to_f64(dQKV)
+    assert np.isfinite(got).all()
+    for name, lo, hi in (("dQ", 0, qc * d), ("dK", qc * d, (qc + kc) * d), ("dV", (qc + kc) * d, (qc + 2 * kc) * d)):
+        assert Hh.rel_err(got[:, lo:hi], want[:, lo:hi]) <= Hh.TOL, (name, Hh.rel_err(got[:, lo:hi], want[:, lo:hi]))
+    # the scratch holds rowsum(dC .* C) per head and token
+    Cw = O.attn_core_shard_fwd(x, oplan, group, d, n_seq, causal)
+    dl = Delta.cpu().numpy().astype(np.float64)
+    for j in range(qc):
+        w = (gC[:, j * d:(j + 1) * d] * Cw[:, j * d:(j + 1) * d]).sum(1)
+        assert np.abs(dl[j] - w).max() <= 2e-2 * max(1.0, np.abs(w).max()), j
+
+
+@pytest.mark.parametrize("causal", [False, True], ids=["full", "causal"])
+@pytest.mark.parametrize("n_q,n_kv,tp,rank,d,n_seq,S", CASES[:7])
+def test_attn_core_bwd_matches_oracle(n_q, n_kv, tp, rank, d, n_seq, S, causal):
+    _say(f"attn core bwd n_q={n_q} n_kv={n_kv} tp={tp} rank={rank} d={d} n_seq={n_seq} S={S} causal={causal}")
+    _bwd_case(n_q, n_kv, tp, rank, d, n_seq, S, causal)
+
+
+def test_attn_core_bwd_padded_rows():
+    _say("attn core bwd: padded leading dimensions")
+    _bwd_case(8, 2, 3, 1, 128, 1, 300, True, seed=3, pad=8)
+
+
 def test_attn_core_fwd_padded_rows_and_peaked_scores():
     _say("attn core fwd: padded leading dimensions, large scores")
     _case(8, 2, 3, 1, 128, 1, 300, True, seed=3, pad=8)
