@@ -328,6 +328,34 @@ def imbalance_sweep(torch, N, iters=8):
     return out
 
 
+def attn_core_bench(torch, N):
+    """Attention core (Eq. 5) of this rank's 14 local heads at the step's shape (one sequence of 2048 tokens),
+    and at 8192 tokens where the quadratic part dominates; causal and unmasked, forward and backward."""
+    out = {}
+    for tokens in (M, 8192):
+        for causal in (False, True):
+            plan = N.ntp_attn_shard_plan(HEADS, HEADS, HEAD_DIM, T_RED, RANK)
+            q = plan["q_cnt"]
+            QKV = torch.randn(tokens, plan["w_qkv"], dtype=torch.bfloat16, device="cuda")
+            Cc = torch.empty(tokens, plan["w_o"], dtype=torch.bfloat16, device="cuda")
+            dC = torch.randn_like(Cc)
+            dQKV = torch.empty_like(QKV)
+            LSE = torch.empty(q, tokens, dtype=torch.float32, device="cuda")
+            Delta = torch.empty_like(LSE)
+            shp = N.attn_core_shape(1, tokens, plan, 1, causal)
+            fwd = lambda: N.ntp_attn_core_shard_fwd(shp, QKV, Cc, LSE)
+            bwd = lambda: N.ntp_attn_core_shard_bwd(shp, QKV, Cc, dC, LSE, Delta, dQKV)
+            for _ in range(3):
+                fwd()
+                bwd()
+            tf, tb = timed(torch, fwd, 10), timed(torch, bwd, 10)
+            pair = (1.0 if causal else 2.0) * tokens * tokens * HEAD_DIM * q  # flops of one product over the visible pairs
+            out[f"{tokens}_tokens_{'causal' if causal else 'full'}"] = dict(
+                fwd_ms=tf, fwd_TFLOPs=2 * pair / tf / 1e9, bwd_ms=tb, bwd_TFLOPs=5 * pair / tb / 1e9,
+                bwd_executed_TFLOPs=7 * pair / tb / 1e9)
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -337,6 +365,7 @@ def main():
     ap.add_argument("--no-reshard-stress", action="store_true")
     ap.add_argument("--no-mapped-reshard", action="store_true")
     ap.add_argument("--no-fused-step", action="store_true")
+    ap.add_argument("--no-attn-core", action="store_true")
     ap.add_argument("--imbalance-sweep", action="store_true",
                     help="run the second workload instead (all ranks of TP 8 degraded to 7, 6, 4 at the prototype's shapes) "
                          "and print its own JSON line")
@@ -453,6 +482,14 @@ def main():
                                   "of the comp/sync rank assignment",
             achieved=worst["GBps"], peak=HBM_PEAK_GBPS, unit="GB/s", frac=worst["GBps"] / HBM_PEAK_GBPS, traffic=None,
             directions=st)
+    if not args.no_attn_core:
+        ac = attn_core_bench(torch, N)
+        best = max(v["fwd_TFLOPs"] for v in ac.values())
+        out["attn_core_roofline"] = dict(
+            bound="mfma", workload="attention core of the rank's 14 heads x 128, one sequence; algorithmic flops: 2 products "
+                                   "forward, 5 backward over the visible (query, key) pairs (the backward executes 7)",
+            achieved=best, peak=BF16_MFMA_PEAK_TFLOPS, unit="TFLOP/s", frac=best / BF16_MFMA_PEAK_TFLOPS, traffic=None,
+            cases=ac)
     if not args.no_cpu_baseline:
         fn()  # make sure the device buffers hold this step's results
         torch.cuda.synchronize()

@@ -49,8 +49,9 @@ __device__ __forceinline__ float xor_sum(float v) {
   return v + __shfl_xor(v, 32);
 }
 
+// (two wavefronts per SIMD: one's softmax arithmetic overlaps the other's matrix instructions)
 template <int D>
-__global__ __launch_bounds__(kThreads) void attn_core_fwd_kernel(const CoreArgs a) {
+__global__ __launch_bounds__(kThreads, 2) void attn_core_fwd_kernel(const CoreArgs a) {
   constexpr int LDT = D + 8;        // LDS row stride (elements): 16 rows x 16 bytes land on distinct banks
   constexpr int KS = D / 32;        // K-steps of the score product
   constexpr int DB = D / 16;        // 16-column blocks of the output
@@ -60,8 +61,9 @@ __global__ __launch_bounds__(kThreads) void attn_core_fwd_kernel(const CoreArgs 
   __shared__ __attribute__((aligned(16))) uint16_t sK[kBKV * LDT];
   __shared__ __attribute__((aligned(16))) uint16_t sV[kBKV * LDT];
 
-  // workgroup -> (head, sequence, query tile); consecutive workgroups share a head's keys and values
-  const int qt = blockIdx.x % a.q_tiles;
+  // workgroup -> (head, sequence, query tile); consecutive workgroups share a head's keys and values.
+  // With the causal mask the late tiles have the most keys: they go first.
+  const int qt = a.causal ? a.q_tiles - 1 - int(blockIdx.x % a.q_tiles) : int(blockIdx.x % a.q_tiles);
   const int sh = blockIdx.x / a.q_tiles;
   const int seq = sh % a.n_seq, head = sh / a.n_seq;
   const int g = (a.q_off + head) / a.group - a.kv_off;  // local KV head
@@ -259,11 +261,11 @@ __device__ __forceinline__ bf16x8 tr_frag(const uint16_t* tile, int ldt, int r0,
 
 // dQ (and delta): a workgroup takes 128 query rows of one (sequence, head), a wavefront 32 of them.
 template <int D>
-__global__ __launch_bounds__(kThreads) void attn_core_bwd_dq_kernel(const CoreBwdArgs a) {
+__global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dq_kernel(const CoreBwdArgs a) {
   constexpr int LDT = D + 8, KS = D / 32, DB = D / 16, CPR = D / 8, NLD = kBKV * CPR / kThreads;
   __shared__ __attribute__((aligned(16))) uint16_t sK[kBKV * LDT];
   __shared__ __attribute__((aligned(16))) uint16_t sV[kBKV * LDT];
-  const int qt = blockIdx.x % a.tiles;
+  const int qt = a.causal ? a.tiles - 1 - int(blockIdx.x % a.tiles) : int(blockIdx.x % a.tiles);
   const int sh = blockIdx.x / a.tiles;
   const int seq = sh % a.n_seq, head = sh / a.n_seq;
   const int g = (a.q_off + head) / a.group - a.kv_off;

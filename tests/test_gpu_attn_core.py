@@ -123,6 +123,38 @@ def test_attn_core_fwd_padded_rows_and_peaked_scores():
     _case(8, 2, 3, 1, 128, 1, 300, False, seed=4, std=5.0)
 
 
+def test_attention_layer_end_to_end_sums_to_the_unsharded_layer():
+    """Projection, core, projection on every rank of an uneven head split (3, 3, 2 heads): the partial
+    outputs sum to the unsharded attention layer (Eq. 4-6)."""
+    import torch
+    import paper_2504_06095_amd as N
+    _say("attention layer end to end, all ranks of TP 3 with 8 heads")
+    n_q, n_kv, d, tp, H, S = 8, 2, 64, 3, 256, 160
+    group = n_q // n_kv
+    Xb, X = I.normal_bf16(9, "layer.X", (S, H), 1.0)
+    ws = {}
+    for name, shape in (("Wq", (H, n_q * d)), ("Wk", (H, n_kv * d)), ("Wv", (H, n_kv * d)), ("Wo", (n_q * d, H))):
+        ws[name] = I.normal_bf16(9, "layer." + name, shape, 0.05)
+    f = lambda k: ws[k][1].astype(np.float64)
+    want = O.attn_unsharded_fwd(X.astype(np.float64), f("Wq"), f("Wk"), f("Wv"), f("Wo"), n_q, n_kv, d)
+    Xd = Hh.to_dev_bf16(Xb)
+    total = np.zeros((S, H))
+    for r in range(tp):
+        plan = N.ntp_attn_shard_plan(n_q, n_kv, d, tp, r)
+        _, Wqkv_i, Wo_i = O.attn_shard_weights(ws["Wq"][0], ws["Wk"][0], ws["Wv"][0], ws["Wo"][0], n_q, n_kv, d, tp, r)
+        wq, wo = plan["w_qkv"], plan["w_o"]
+        Wqkv = Hh.to_dev_bf16(np.ascontiguousarray(Wqkv_i.T))  # stored [w_qkv x H]
+        Wo = Hh.to_dev_bf16(np.ascontiguousarray(Wo_i))
+        mk = lambda rr, cc: torch.full((rr, cc), float("nan"), dtype=torch.bfloat16, device="cuda")
+        QKV, Cc, Z = mk(S, wq), mk(S, wo), mk(S, H)
+        N.ntp_attn_proj_shard_fwd(S, H, wq, wo, Xd, Wqkv, QKV, None, None, None)
+        N.ntp_attn_core_shard_fwd(N.attn_core_shape(1, S, plan, group, False), QKV, Cc, None)
+        N.ntp_attn_proj_shard_fwd(S, H, wq, wo, None, None, None, Cc, Wo, Z)
+        torch.cuda.synchronize()
+        total += Hh.dev_bf16_to_f64(Z)
+    assert Hh.rel_err(total, want) <= Hh.TOL, Hh.rel_err(total, want)
+
+
 def test_attn_core_rejects_bad_arguments():
     import torch
     import paper_2504_06095_amd as N
