@@ -404,9 +404,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dq_kernel(const Cor
   }
 }
 
-// dK and dV: a workgroup takes 128 keys of one (sequence, KV head), a wavefront 32 of them, and walks over
-// the query rows (tiles of 64) of every local query head that reads this KV head.
-template <int D>
+// dK and dV: a workgroup takes 64 KB keys of one (sequence, KV head), a wavefront 16 KB of them, and walks
+// over the query rows (tiles of 64) of every local query head that reads this KV head.  KB = 2 does twice
+// the matrix work per LDS read; KB = 1 gives twice the workgroups when there are few heads.
+template <int D, int KB>
 __global__ __launch_bounds__(kThreads) void attn_core_bwd_dkv_kernel(const CoreBwdArgs a) {
   constexpr int LDT = D + 8, KS = D / 32, DB = D / 16, CPR = D / 8, NLD = kBKV * CPR / kThreads;
   __shared__ __attribute__((aligned(16))) uint16_t sQ[kBKV * LDT];
@@ -420,14 +421,14 @@ __global__ __launch_bounds__(kThreads) void attn_core_bwd_dkv_kernel(const CoreB
   const int64_t tok0 = int64_t(seq) * S, Mtot = int64_t(a.n_seq) * S;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lq = lane & 15, lh = lane >> 4;
-  const int k0 = kt * kBQ + wave * 32;  // first key of this wavefront
+  const int k0 = kt * (64 * KB) + wave * (16 * KB);  // first key of this wavefront
   const uint16_t* Kp = a.QKV + int64_t(a.q_cnt + g) * D;
   const uint16_t* Vp = a.QKV + int64_t(a.q_cnt + a.kv_cnt + g) * D;
 
   // key and value fragments (operand B: j = key)
-  bf16x8 kf[2][KS], vf[2][KS];
+  bf16x8 kf[KB][KS], vf[KB][KS];
 #pragma unroll
-  for (int kb = 0; kb < 2; ++kb) {
+  for (int kb = 0; kb < KB; ++kb) {
     const int kr = min(k0 + kb * 16 + lq, S - 1);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
@@ -435,9 +436,9 @@ __global__ __launch_bounds__(kThreads) void attn_core_bwd_dkv_kernel(const CoreB
       vf[kb][ks] = *reinterpret_cast<const bf16x8*>(Vp + (tok0 + kr) * a.ld + ks * 32 + lh * 8);
     }
   }
-  f32x4 dk[2][DB], dv[2][DB];
+  f32x4 dk[KB][DB], dv[KB][DB];
 #pragma unroll
-  for (int kb = 0; kb < 2; ++kb)
+  for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
       dk[kb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -445,7 +446,7 @@ __global__ __launch_bounds__(kThreads) void attn_core_bwd_dkv_kernel(const CoreB
     }
 
   // query tiles this workgroup needs: all, or from the tile that holds its first key on
-  const int q_first = a.causal ? (kt * kBQ) / kBKV : 0;
+  const int q_first = a.causal ? (kt * (64 * KB)) / kBKV : 0;
   const int q_tiles = (S + kBKV - 1) / kBKV;
   ntp_gemm::u16x8 rq[NLD], rg[NLD];
   float rl = 0.f, rd = 0.f;
@@ -489,11 +490,11 @@ __global__ __launch_bounds__(kThreads) void attn_core_bwd_dkv_kernel(const CoreB
       if (t + 1 < q_tiles) load_tile(t + 1);
       const int qbase = t * kBKV;
       // S and dP blocks: [query qb*16 + (lane/16)*4 + r][key kb*16 + lane%16]
-      f32x4 sc[4][2], dp[4][2];
+      f32x4 sc[4][KB], dp[4][KB];
 #pragma unroll
       for (int qb = 0; qb < 4; ++qb) {
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
+        for (int kb = 0; kb < KB; ++kb) {
           sc[qb][kb] = f32x4{0.f, 0.f, 0.f, 0.f};
           dp[qb][kb] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
@@ -502,15 +503,15 @@ __global__ __launch_bounds__(kThreads) void attn_core_bwd_dkv_kernel(const CoreB
           const bf16x8 qa = *reinterpret_cast<const bf16x8*>(sQ + (qb * 16 + lq) * LDT + ks * 32 + lh * 8);
           const bf16x8 ga = *reinterpret_cast<const bf16x8*>(sG + (qb * 16 + lq) * LDT + ks * 32 + lh * 8);
 #pragma unroll
-          for (int kb = 0; kb < 2; ++kb) {
+          for (int kb = 0; kb < KB; ++kb) {
             sc[qb][kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa, kf[kb][ks], sc[qb][kb], 0, 0, 0);
             dp[qb][kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ga, vf[kb][ks], dp[qb][kb], 0, 0, 0);
           }
         }
       }
-      bf16x8 pf[2][2], dsf[2][2];
+      bf16x8 pf[KB][2], dsf[KB][2];
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
+      for (int kb = 0; kb < KB; ++kb) {
         const int key = k0 + kb * 16 + lq;
         float p[4][4], ds[4][4];
 #pragma unroll
@@ -547,7 +548,7 @@ __global__ __launch_bounds__(kThreads) void attn_core_bwd_dkv_kernel(const CoreB
           const bf16x8 gt = tr_frag(sG, LDT, s2 * 32, db * 16, lq, lh);
           const bf16x8 qt2 = tr_frag(sQ, LDT, s2 * 32, db * 16, lq, lh);
 #pragma unroll
-          for (int kb = 0; kb < 2; ++kb) {
+          for (int kb = 0; kb < KB; ++kb) {
             dv[kb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(gt, pf[kb][s2], dv[kb][db], 0, 0, 0);
             dk[kb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qt2, dsf[kb][s2], dk[kb][db], 0, 0, 0);
           }
@@ -556,7 +557,7 @@ __global__ __launch_bounds__(kThreads) void attn_core_bwd_dkv_kernel(const CoreB
     __syncthreads();  // the next head's first tile overwrites LDS
   }
 #pragma unroll
-  for (int kb = 0; kb < 2; ++kb) {
+  for (int kb = 0; kb < KB; ++kb) {
     const int key = k0 + kb * 16 + lq;
     if (key >= S) continue;
     uint16_t* kp = a.dQKV + (tok0 + key) * a.ldd + int64_t(a.q_cnt + g) * D + lh * 4;
@@ -667,12 +668,16 @@ extern "C" int ntp_attn_core_shard_bwd(const ntp_attn_core_shape_t* s, const voi
   a.group = s->group;
   a.causal = s->causal ? 1 : 0;
   a.tiles = (s->seq_len + kBQ - 1) / kBQ;
+  // keys per workgroup of the dK/dV kernel: 128, or 64 when 128 would leave CUs without a workgroup
+  const int64_t wide_blocks = int64_t((s->seq_len + 127) / 128) * s->n_seq * s->kv_cnt;
+  const int kb = wide_blocks >= 256 ? 2 : 1;
+  const int32_t key_tiles = (s->seq_len + 64 * kb - 1) / (64 * kb);
   a.scale = float(1.0 / std::sqrt(double(s->head_dim)));
   a.scale_log2 = float(1.4426950408889634 / std::sqrt(double(s->head_dim)));
   hipStream_t hs = static_cast<hipStream_t>(stream);
   const double pair_flops = (s->causal ? 1.0 : 2.0) * double(s->n_seq) * double(s->seq_len) * double(s->seq_len) * s->head_dim * s->q_cnt;
   bool ok = true;
-  const int64_t bq = int64_t(a.tiles) * s->n_seq * s->q_cnt, bk = int64_t(a.tiles) * s->n_seq * s->kv_cnt;
+  const int64_t bq = int64_t(a.tiles) * s->n_seq * s->q_cnt, bk = int64_t(key_tiles) * s->n_seq * s->kv_cnt;
   if (bq > 0x7fffffffll || bk > 0x7fffffffll) return NTP_ERR_UNSUPPORTED;
   if (bq > 0) {
     // dQ and delta: three products per (query, key) pair
@@ -688,10 +693,15 @@ extern "C" int ntp_attn_core_shard_bwd(const ntp_attn_core_shape_t* s, const voi
   if (bk > 0) {
     // dK and dV: four products per pair
     if (ntp::timing_on()) ntp::timing_begin(stream, "attn_core_bwd_dkv", 4.0 * pair_flops, 0.0);
-    if (s->head_dim == 128)
-      hipLaunchKernelGGL(attn_core_bwd_dkv_kernel<128>, dim3(uint32_t(bk)), dim3(kThreads), 0, hs, a);
+    a.tiles = key_tiles;
+    if (s->head_dim == 128 && kb == 2)
+      hipLaunchKernelGGL((attn_core_bwd_dkv_kernel<128, 2>), dim3(uint32_t(bk)), dim3(kThreads), 0, hs, a);
+    else if (s->head_dim == 128)
+      hipLaunchKernelGGL((attn_core_bwd_dkv_kernel<128, 1>), dim3(uint32_t(bk)), dim3(kThreads), 0, hs, a);
+    else if (kb == 2)
+      hipLaunchKernelGGL((attn_core_bwd_dkv_kernel<64, 2>), dim3(uint32_t(bk)), dim3(kThreads), 0, hs, a);
     else
-      hipLaunchKernelGGL(attn_core_bwd_dkv_kernel<64>, dim3(uint32_t(bk)), dim3(kThreads), 0, hs, a);
+      hipLaunchKernelGGL((attn_core_bwd_dkv_kernel<64, 1>), dim3(uint32_t(bk)), dim3(kThreads), 0, hs, a);
     ok = hipGetLastError() == hipSuccess;
     ntp::timing_end(stream);
   }
