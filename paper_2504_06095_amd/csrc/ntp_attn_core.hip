@@ -127,6 +127,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_fwd_kernel(const CoreAr
     __syncthreads();
     if (t + 1 < n_tiles) load_tile(t + 1);
     const int kv0 = t * kBKV;
+    if (a.causal && kv0 > q0 + 31) continue;  // every key of the tile lies after this wavefront's last query row
 
     // scores, transposed: st[kb][qb][r] = S[query qb*16 + lane%16][key kv0 + kb*16 + (lane/16)*4 + r]
     f32x4 st[4][2];
@@ -142,24 +143,31 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_fwd_kernel(const CoreAr
       }
     }
 
+    // only tiles that reach past the sequence end or past this wavefront's first query row (causal) need
+    // the mask; the test is the same for the whole wavefront
+    const bool edge = kv0 + kBKV > S || (a.causal && kv0 + kBKV - 1 > q0);
     bf16x8 pf[2][2];  // P as operand B of the second product, per query block and 32-key step
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
       const int qrow = q0 + qb * 16 + lq;
+      if (edge) {
+#pragma unroll
+        for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int key = kv0 + kb * 16 + lh * 4 + r;
+            if (key >= S || (a.causal && key > qrow)) st[kb][qb][r] = -INFINITY;
+          }
+      }
+      // the scale is positive: the maximum can be taken on the raw scores
       float mx = -INFINITY;
 #pragma unroll
       for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int key = kv0 + kb * 16 + lh * 4 + r;
-          float s = st[kb][qb][r] * a.scale_log2;
-          if (key >= S || (a.causal && key > qrow)) s = -INFINITY;
-          st[kb][qb][r] = s;
-          mx = fmaxf(mx, s);
-        }
-      mx = xor_max(mx);
+        for (int r = 0; r < 4; ++r) mx = fmaxf(mx, st[kb][qb][r]);
+      mx = xor_max(mx) * a.scale_log2;
       const float m_new = fmaxf(m_run[qb], mx);
-      // a row with no visible key yet (only rows past the end of a causal tile's diagonal) keeps m = -inf: use 0 there
+      // a row with no visible key so far keeps m = -inf: use 0 there
       const float m_use = m_new == -INFINITY ? 0.f : m_new;
       const float alpha = exp2f(m_run[qb] - m_use);
       float ls = 0.f;
@@ -168,13 +176,16 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_fwd_kernel(const CoreAr
       for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          p[kb][r] = exp2f(st[kb][qb][r] - m_use);
+          p[kb][r] = exp2f(fmaf(st[kb][qb][r], a.scale_log2, -m_use));
           ls += p[kb][r];
         }
       l_run[qb] = l_run[qb] * alpha + ls;  // per-lane partial sum; the four lane groups are added at the end
       m_run[qb] = m_new;
+      // the running maximum rarely moves after the first tiles: skip the rescale when no lane needs it
+      if (__any(alpha != 1.0f)) {
 #pragma unroll
-      for (int db = 0; db < DB; ++db) acc[qb][db] *= alpha;
+        for (int db = 0; db < DB; ++db) acc[qb][db] *= alpha;
+      }
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {
         bf16x8 f;
@@ -334,6 +345,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dq_kernel(const Cor
     __syncthreads();
     if (t + 1 < n_tiles) load_tile(t + 1);
     const int kv0 = t * kBKV;
+    if (a.causal && kv0 > q0 + 31) continue;  // nothing of this tile is visible to the wavefront's rows
     // S^T and dP^T blocks: [key kb*16 + (lane/16)*4 + r][query qb*16 + lane%16]
     f32x4 st[4][2], dpt[4][2];
 #pragma unroll
@@ -354,6 +366,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dq_kernel(const Cor
         }
       }
     }
+    const bool edge = kv0 + kBKV > S || (a.causal && kv0 + kBKV - 1 > q0);
     bf16x8 dsf[2][2];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
@@ -362,12 +375,20 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dq_kernel(const Cor
 #pragma unroll
       for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int key = kv0 + kb * 16 + lh * 4 + r;
-          const bool seen = key < S && !(a.causal && key > qrow);
-          const float p = seen ? exp2f(st[kb][qb][r] * a.scale_log2 - lse2[qb]) : 0.f;
-          ds[kb][r] = p * (dpt[kb][qb][r] - delta[qb]);
-        }
+        for (int r = 0; r < 4; ++r) ds[kb][r] = exp2f(fmaf(st[kb][qb][r], a.scale_log2, -lse2[qb]));
+      if (edge) {
+#pragma unroll
+        for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int key = kv0 + kb * 16 + lh * 4 + r;
+            if (key >= S || (a.causal && key > qrow)) ds[kb][r] = 0.f;
+          }
+      }
+#pragma unroll
+      for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) ds[kb][r] *= dpt[kb][qb][r] - delta[qb];
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {
         bf16x8 f;
@@ -489,6 +510,7 @@ __global__ __launch_bounds__(kThreads) void attn_core_bwd_dkv_kernel(const CoreB
       __syncthreads();
       if (t + 1 < q_tiles) load_tile(t + 1);
       const int qbase = t * kBKV;
+      if (a.causal && qbase + kBKV - 1 < k0) continue;  // every query row of the tile comes before this wavefront's keys
       // S and dP blocks: [query qb*16 + (lane/16)*4 + r][key kb*16 + lane%16]
       f32x4 sc[4][KB], dp[4][KB];
 #pragma unroll
@@ -509,6 +531,9 @@ __global__ __launch_bounds__(kThreads) void attn_core_bwd_dkv_kernel(const CoreB
           }
         }
       }
+      // the mask is needed only where the tile reaches past the sequence end, or (causal) where some query
+      // row of the tile comes before the wavefront's last key
+      const bool edge = qbase + kBKV > S || k0 + 16 * KB > S || (a.causal && qbase < k0 + 16 * KB - 1);
       bf16x8 pf[KB][2], dsf[KB][2];
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb) {
@@ -520,12 +545,23 @@ __global__ __launch_bounds__(kThreads) void attn_core_bwd_dkv_kernel(const CoreB
           const f32x4 d4 = *reinterpret_cast<const f32x4*>(sD + qb * 16 + lh * 4);
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
-            const int qrow = qbase + qb * 16 + lh * 4 + r;
-            const bool seen = qrow < S && key < S && !(a.causal && key > qrow);
-            p[qb][r] = seen ? exp2f(sc[qb][kb][r] * a.scale_log2 - l4[r]) : 0.f;
-            ds[qb][r] = p[qb][r] * (dp[qb][kb][r] - d4[r]);
+            p[qb][r] = exp2f(fmaf(sc[qb][kb][r], a.scale_log2, -l4[r]));
+            ds[qb][r] = dp[qb][kb][r] - d4[r];
           }
         }
+        if (edge) {
+#pragma unroll
+          for (int qb = 0; qb < 4; ++qb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const int qrow = qbase + qb * 16 + lh * 4 + r;
+              if (qrow >= S || key >= S || (a.causal && key > qrow)) p[qb][r] = 0.f;
+            }
+        }
+#pragma unroll
+        for (int qb = 0; qb < 4; ++qb)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) ds[qb][r] *= p[qb][r];
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
           bf16x8 f, h;
