@@ -5,7 +5,7 @@
 
 #include "ntp_internal.h"
 
-extern "C" int ntp_version(void) { return 100; }
+extern "C" int ntp_version(void) { return 110; }
 
 extern "C" const char* ntp_status_string(int status) {
   switch (status) {
