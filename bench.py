@@ -34,7 +34,9 @@ def build_state(torch, N):
     _, n_r = N.ntp_shard_plan(FFN, T_RED, RANK)
     ap = N.ntp_attn_shard_plan(HEADS, HEADS, HEAD_DIM, T_RED, RANK)
     wq, wo = ap["w_qkv"], ap["w_o"]
-    ld = (n_r + 7) // 8 * 8
+    # leading dimension of P, Y, dP: rows start on 128-byte lines (the library needs only a multiple of 8;
+    # whole lines make the row-wise DMA of these matrices cheaper)
+    ld = (n_r + 63) // 64 * 64
 
     def bf(name, shape, std):
         bits, _ = I.normal_bf16(0, "bench." + name, shape, std)
