@@ -56,14 +56,16 @@ __device__ __forceinline__ float xor_sum(float v) {
 // (two wavefronts per SIMD: one's softmax arithmetic overlaps the other's matrix instructions)
 template <int D>
 __global__ __launch_bounds__(kThreads, 2) void attn_core_fwd_kernel(const CoreArgs a) {
-  constexpr int LDT = D + 8;        // LDS row stride (elements): 16 rows x 16 bytes land on distinct banks
+  // LDS row stride (elements): rows shift by 8 banks, so the 8 rows that a 16-byte fragment read touches per
+  // cycle and the 4 rows x 32 bytes that a transposing read touches per cycle land on distinct banks
+  constexpr int LDT = D + 16, LDV = D + 16;
   constexpr int KS = D / 32;        // K-steps of the score product
   constexpr int DB = D / 16;        // 16-column blocks of the output
   constexpr int CPR = D / 8;        // 16-byte chunks per tile row
   constexpr int NLD = kBKV * CPR / kThreads;  // chunks per thread and tile
   static_assert(D % 32 == 0 && (kBKV * CPR) % kThreads == 0, "tile copy: whole chunks per thread");
   __shared__ __attribute__((aligned(16))) uint16_t sK[kBKV * LDT];
-  __shared__ __attribute__((aligned(16))) uint16_t sV[kBKV * LDT];
+  __shared__ __attribute__((aligned(16))) uint16_t sV[kBKV * LDV];
 
   // workgroup -> (head, sequence, query tile); consecutive workgroups share a head's keys and values.
   // With the causal mask the late tiles have the most keys: they go first.
@@ -118,9 +120,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_fwd_kernel(const CoreAr
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
       const int c = threadIdx.x + i * kThreads;
-      const int o = (c / CPR) * LDT + (c % CPR) * 8;
-      *reinterpret_cast<ntp_gemm::u16x8*>(sK + o) = rk[i];
-      *reinterpret_cast<ntp_gemm::u16x8*>(sV + o) = rv[i];
+      *reinterpret_cast<ntp_gemm::u16x8*>(sK + (c / CPR) * LDT + (c % CPR) * 8) = rk[i];
+      *reinterpret_cast<ntp_gemm::u16x8*>(sV + (c / CPR) * LDV + (c % CPR) * 8) = rv[i];
     }
   };
 
@@ -211,9 +212,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_fwd_kernel(const CoreAr
       for (int s2 = 0; s2 < 2; ++s2) {
         // transposing read: in a 16-lane group, lane s points at 4 consecutive columns of key line (s >> 2);
         // the group hands lane L the 4 keys of column L
-        const uint16_t* vp = sV + (s2 * 32 + lh * 4 + (lq >> 2)) * LDT + db * 16 + (lq & 3) * 4;
+        const uint16_t* vp = sV + (s2 * 32 + lh * 4 + (lq >> 2)) * LDV + db * 16 + (lq & 3) * 4;
         const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp));
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp + 16 * LDT));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp + 16 * LDV));
         const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
         const bf16x8 vf = __builtin_bit_cast(bf16x8, both);
         acc[0][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[0][s2], acc[0][db], 0, 0, 0);
@@ -277,7 +278,7 @@ __device__ __forceinline__ bf16x8 tr_frag(const uint16_t* tile, int ldt, int r0,
 // dQ (and delta): a workgroup takes 128 query rows of one (sequence, head), a wavefront 32 of them.
 template <int D>
 __global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dq_kernel(const CoreBwdArgs a) {
-  constexpr int LDT = D + 8, KS = D / 32, DB = D / 16, CPR = D / 8, NLD = kBKV * CPR / kThreads;
+  constexpr int LDT = D + 16, KS = D / 32, DB = D / 16, CPR = D / 8, NLD = kBKV * CPR / kThreads;
   __shared__ __attribute__((aligned(16))) uint16_t sK[kBKV * LDT];
   __shared__ __attribute__((aligned(16))) uint16_t sV[kBKV * LDT];
   const int qt = a.causal ? a.tiles - 1 - int(blockIdx.x % a.tiles) : int(blockIdx.x % a.tiles);
@@ -434,7 +435,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dq_kernel(const Cor
 // the matrix work per LDS read; KB = 1 gives twice the workgroups when there are few heads.
 template <int D, int KB>
 __global__ __launch_bounds__(kThreads) void attn_core_bwd_dkv_kernel(const CoreBwdArgs a) {
-  constexpr int LDT = D + 8, KS = D / 32, DB = D / 16, CPR = D / 8, NLD = kBKV * CPR / kThreads;
+  constexpr int LDT = D + 16, KS = D / 32, DB = D / 16, CPR = D / 8, NLD = kBKV * CPR / kThreads;
   __shared__ __attribute__((aligned(16))) uint16_t sQ[kBKV * LDT];
   __shared__ __attribute__((aligned(16))) uint16_t sG[kBKV * LDT];
   __shared__ __attribute__((aligned(16))) float sL[kBKV];
