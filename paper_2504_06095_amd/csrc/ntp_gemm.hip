@@ -49,10 +49,13 @@ int launch_generic(GemmArgs g, int epi, hipStream_t s) {
 // on large problems with operands streaming from HBM): smaller wavefront tiles read more LDS fragments
 // per MFMA, smaller workgroup tiles move more bytes per flop, and the K-strided layouts pay two
 // transposing reads per fragment (their 256 x 256 variant is also short of registers).
-//                                             256x256 256x224 224x256 256x192 192x256 256x128 128x256 128x128
-constexpr double kTileRate[3][kNumTileShapes] = {{1.000, 0.957, 0.969, 0.917, 0.923, 0.761, 0.754, 0.65},   // A, B K-contiguous
-                                                 {1.000, 0.929, 0.986, 0.908, 0.944, 0.770, 0.749, 0.65},   // B K-strided
-                                                 {0.850, 0.984, 1.000, 0.956, 0.962, 0.797, 0.779, 0.65}};  // both K-strided (256 x 256 spills registers in its loop)
+// The 4-wavefront 128 x 128 variant reaches its rate with two workgroups on a compute unit; alone on one
+// (at most 256 tiles) it runs at kLoneSmallTileRate, where the 8-wavefront variant of the same tile is faster.
+//                                             256x256 256x224 224x256 256x192 192x256 256x128 128x256 128x128 128x128w8
+constexpr double kTileRate[3][kNumTileShapes] = {{1.000, 0.957, 0.969, 0.917, 0.923, 0.761, 0.754, 0.65, 0.53},   // A, B K-contiguous
+                                                 {1.000, 0.929, 0.986, 0.908, 0.944, 0.770, 0.749, 0.65, 0.53},   // B K-strided
+                                                 {0.923, 0.984, 1.000, 0.956, 0.962, 0.797, 0.779, 0.65, 0.53}};  // both K-strided
+constexpr double kLoneSmallTileRate = 0.43;
 constexpr int kComputeUnits = 256;
 
 // Pick the tile shape with the least estimated time: the busiest compute unit's number of
@@ -64,13 +67,20 @@ int choose_tile(int64_t M, int64_t N, int layout) {
     const TileShape& ts = kTileShapes[i];
     const int64_t tiles = ((M + ts.bm - 1) / ts.bm) * ((N + ts.bn - 1) / ts.bn);
     const int64_t cu_load = (tiles + kComputeUnits - 1) / kComputeUnits;
-    const double t = double(cu_load) * ts.bm * ts.bn / kTileRate[layout][i];
+    const double rate = ts.waves == 4 && tiles <= kComputeUnits ? kLoneSmallTileRate : kTileRate[layout][i];
+    const double t = double(cu_load) * ts.bm * ts.bn / rate;
     if (t < best_t) {
       best_t = t;
       best = i;
     }
   }
   return best;
+}
+
+void variant_name(int v, char* out, size_t n) {
+  if (v < 0) snprintf(out, n, "generic128");
+  else if (kTileShapes[v].bm == 128 && kTileShapes[v].bn == 128 && kTileShapes[v].waves == 8) snprintf(out, n, "128x128w8");
+  else snprintf(out, n, "%dx%d", kTileShapes[v].bm, kTileShapes[v].bn);
 }
 
 // Variant used for a shape: -1 = generic kernel, else an index into kTileShapes.  The environment
@@ -81,7 +91,7 @@ int choose_variant(const GemmArgs& g, bool ring_ok, int layout) {
     if (!ring_ok || !strcmp(f, "generic")) return -1;
     for (int i = 0; i < kNumTileShapes; ++i) {
       char name[16];
-      snprintf(name, sizeof(name), "%dx%d", kTileShapes[i].bm, kTileShapes[i].bn);
+      variant_name(i, name, sizeof(name));
       if (!strcmp(f, name)) return i;
     }
   }
@@ -89,11 +99,6 @@ int choose_variant(const GemmArgs& g, bool ring_ok, int layout) {
   if (int64_t(g.M) * g.N < 128 * 128 * 64 || g.K < 128) return -1;
   if (!ring_ok) return -1;
   return choose_tile(g.M, g.n_store, layout);
-}
-
-void variant_name(int v, char* out, size_t n) {
-  if (v < 0) snprintf(out, n, "generic128");
-  else snprintf(out, n, "%dx%d", kTileShapes[v].bm, kTileShapes[v].bn);
 }
 
 // (layout, epilogue) pairs the shard layers use have ring instantiations; anything else runs on

@@ -19,6 +19,7 @@ struct TileShape {
 };
 constexpr TileShape kTileShapes[] = {
     {256, 256, 8}, {256, 224, 8}, {224, 256, 8}, {256, 192, 8}, {192, 256, 8}, {256, 128, 8}, {128, 256, 8}, {128, 128, 4},
+    {128, 128, 8},  // the same tile on 8 wavefronts: one workgroup per compute unit, for at most 256 tiles
 };
 constexpr int kNumTileShapes = int(sizeof(kTileShapes) / sizeof(kTileShapes[0]));
 
@@ -54,6 +55,7 @@ int launch_ring_tile(const GemmArgs& g, int tile, hipStream_t s) {
     case 5: return launch_ring_one<AKC, BKC, EPI, 256, 128, 4, 2>(g, s);
     case 6: return launch_ring_one<AKC, BKC, EPI, 128, 256, 2, 4>(g, s);
     case 7: return launch_ring_one<AKC, BKC, EPI, 128, 128, 2, 2>(g, s);
+    case 8: return launch_ring_one<AKC, BKC, EPI, 128, 128, 2, 4>(g, s);
     default: return NTP_ERR_INVALID_ARG;
   }
 }
@@ -70,6 +72,7 @@ int launch_ring_tile(const GemmArgs& g, int tile, hipStream_t s) {
   template __global__ void gemm_ring_kernel<AKC, BKC, EPI, 192, 256, 2, 4>(const GemmArgs);        \
   template __global__ void gemm_ring_kernel<AKC, BKC, EPI, 256, 128, 4, 2>(const GemmArgs);        \
   template __global__ void gemm_ring_kernel<AKC, BKC, EPI, 128, 256, 2, 4>(const GemmArgs);        \
-  template __global__ void gemm_ring_kernel<AKC, BKC, EPI, 128, 128, 2, 2>(const GemmArgs);
+  template __global__ void gemm_ring_kernel<AKC, BKC, EPI, 128, 128, 2, 2>(const GemmArgs);        \
+  template __global__ void gemm_ring_kernel<AKC, BKC, EPI, 128, 128, 2, 4>(const GemmArgs);
 
 #endif  // NTP_GEMM_LAUNCH_H_

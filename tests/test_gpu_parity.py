@@ -173,7 +173,7 @@ def test_attn_halves_can_be_skipped():
 
 
 # ---- every GEMM tile variant, reached through the tuning override, on ragged shapes --------------
-RING_TILES = ["256x256", "256x224", "224x256", "256x192", "192x256", "256x128", "128x256", "128x128"]
+RING_TILES = ["256x256", "256x224", "224x256", "256x192", "192x256", "256x128", "128x256", "128x128", "128x128w8"]
 
 
 @pytest.mark.parametrize("variant", ["generic"] + RING_TILES)
