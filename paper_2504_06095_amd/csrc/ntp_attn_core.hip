@@ -432,9 +432,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dq_kernel(const Cor
 
 // dK and dV: a workgroup takes 64 KB keys of one (sequence, KV head), a wavefront 16 KB of them, and walks
 // over the query rows (tiles of 64) of every local query head that reads this KV head.  KB = 2 does twice
-// the matrix work per LDS read; KB = 1 gives twice the workgroups when there are few heads.
+// the matrix work per LDS read but needs 440 registers (one wavefront per SIMD); KB = 1 fits in 256, two
+// workgroups share a compute unit and it measured 7-35 % faster at every size: only KB = 1 is built.
 template <int D, int KB>
-__global__ __launch_bounds__(kThreads) void attn_core_bwd_dkv_kernel(const CoreBwdArgs a) {
+__global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dkv_kernel(const CoreBwdArgs a) {
   constexpr int LDT = D + 16, KS = D / 32, DB = D / 16, CPR = D / 8, NLD = kBKV * CPR / kThreads;
   __shared__ __attribute__((aligned(16))) uint16_t sQ[kBKV * LDT];
   __shared__ __attribute__((aligned(16))) uint16_t sG[kBKV * LDT];
@@ -709,9 +710,7 @@ extern "C" int ntp_attn_core_shard_bwd(const ntp_attn_core_shape_t* s, const voi
   a.group = s->group;
   a.causal = s->causal ? 1 : 0;
   a.tiles = (s->seq_len + kBQ - 1) / kBQ;
-  // keys per workgroup of the dK/dV kernel: 128, or 64 when 128 would leave CUs without a workgroup
-  const int64_t wide_blocks = int64_t((s->seq_len + 127) / 128) * s->n_seq * s->kv_cnt;
-  const int kb = wide_blocks >= 256 ? 2 : 1;
+  constexpr int kb = 1;  // 64 keys per workgroup of the dK/dV kernel
   const int32_t key_tiles = (s->seq_len + 64 * kb - 1) / (64 * kb);
   a.scale = float(1.0 / std::sqrt(double(s->head_dim)));
   a.scale_log2 = float(1.4426950408889634 / std::sqrt(double(s->head_dim)));
@@ -735,14 +734,10 @@ extern "C" int ntp_attn_core_shard_bwd(const ntp_attn_core_shape_t* s, const voi
     // dK and dV: four products per pair
     if (ntp::timing_on()) ntp::timing_begin(stream, "attn_core_bwd_dkv", 4.0 * pair_flops, 0.0);
     a.tiles = key_tiles;
-    if (s->head_dim == 128 && kb == 2)
-      hipLaunchKernelGGL((attn_core_bwd_dkv_kernel<128, 2>), dim3(uint32_t(bk)), dim3(kThreads), 0, hs, a);
-    else if (s->head_dim == 128)
-      hipLaunchKernelGGL((attn_core_bwd_dkv_kernel<128, 1>), dim3(uint32_t(bk)), dim3(kThreads), 0, hs, a);
-    else if (kb == 2)
-      hipLaunchKernelGGL((attn_core_bwd_dkv_kernel<64, 2>), dim3(uint32_t(bk)), dim3(kThreads), 0, hs, a);
+    if (s->head_dim == 128)
+      hipLaunchKernelGGL((attn_core_bwd_dkv_kernel<128, kb>), dim3(uint32_t(bk)), dim3(kThreads), 0, hs, a);
     else
-      hipLaunchKernelGGL((attn_core_bwd_dkv_kernel<64, 1>), dim3(uint32_t(bk)), dim3(kThreads), 0, hs, a);
+      hipLaunchKernelGGL((attn_core_bwd_dkv_kernel<64, kb>), dim3(uint32_t(bk)), dim3(kThreads), 0, hs, a);
     ok = hipGetLastError() == hipSuccess;
     ntp::timing_end(stream);
   }
