@@ -53,9 +53,10 @@ __device__ __forceinline__ float xor_sum(float v) {
   return v + __shfl_xor(v, 32);
 }
 
-// (two wavefronts per SIMD: one's softmax arithmetic overlaps the other's matrix instructions)
-template <int D>
-__global__ __launch_bounds__(kThreads, 2) void attn_core_fwd_kernel(const CoreArgs a) {
+// (two or three wavefronts per SIMD: one's softmax arithmetic overlaps the others' matrix instructions)
+template <int D, int QB>
+__global__ __launch_bounds__(kThreads, QB == 1 ? 3 : 2) void attn_core_fwd_kernel(const CoreArgs a) {
+  constexpr int kRows = 64 * QB;  // query rows per workgroup: 16 QB per wavefront
   // LDS row stride (elements): rows shift by 8 banks, so the 8 rows that a 16-byte fragment read touches per
   // cycle and the 4 rows x 32 bytes that a transposing read touches per cycle land on distinct banks
   constexpr int LDT = D + 16, LDV = D + 16;
@@ -77,31 +78,36 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_fwd_kernel(const CoreAr
   const int64_t tok0 = int64_t(seq) * S;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lq = lane & 15, lh = lane >> 4;
-  const int q0 = qt * kBQ + wave * 32;  // first query row (in the sequence) of this wavefront
+  const int q0 = qt * kRows + wave * (16 * QB);  // first query row (in the sequence) of this wavefront
 
   const uint16_t* Qp = a.QKV + int64_t(head) * D;
   const uint16_t* Kp = a.QKV + int64_t(a.q_cnt + g) * D;
   const uint16_t* Vp = a.QKV + int64_t(a.q_cnt + a.kv_cnt + g) * D;
 
   // query fragments: operand B[k][j] with j = query row (lane % 16), k = 8 consecutive columns
-  bf16x8 qf[2][KS];
+  bf16x8 qf[QB][KS];
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
+  for (int qb = 0; qb < QB; ++qb) {
     const int qr = min(q0 + qb * 16 + lq, S - 1);  // rows past the end repeat the last one (never stored)
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
       qf[qb][ks] = *reinterpret_cast<const bf16x8*>(Qp + (tok0 + qr) * a.ld + ks * 32 + lh * 8);
   }
 
-  f32x4 acc[2][DB];
+  f32x4 acc[QB][DB];
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb)
+  for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
     for (int db = 0; db < DB; ++db) acc[qb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+  float m_run[QB], l_run[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    m_run[qb] = -INFINITY;
+    l_run[qb] = 0.f;
+  }
 
   // keys this workgroup needs: all of the sequence, or up to its last query row
-  const int kv_end = a.causal ? min(S, qt * kBQ + kBQ) : S;
+  const int kv_end = a.causal ? min(S, qt * kRows + kRows) : S;
   const int n_tiles = (kv_end + kBKV - 1) / kBKV;
 
   // tile copy: global -> registers -> LDS, the next tile's loads in flight during the products
@@ -132,28 +138,28 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_fwd_kernel(const CoreAr
     __syncthreads();
     if (t + 1 < n_tiles) load_tile(t + 1);
     const int kv0 = t * kBKV;
-    if (a.causal && kv0 > q0 + 31) continue;  // every key of the tile lies after this wavefront's last query row
+    if (a.causal && kv0 > q0 + 16 * QB - 1) continue;  // every key of the tile lies after this wavefront's last query row
 
     // scores, transposed: st[kb][qb][r] = S[query qb*16 + lane%16][key kv0 + kb*16 + (lane/16)*4 + r]
-    f32x4 st[4][2];
+    f32x4 st[4][QB];
 #pragma unroll
     for (int kb = 0; kb < 4; ++kb) {
-      st[kb][0] = f32x4{0.f, 0.f, 0.f, 0.f};
-      st[kb][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) st[kb][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         const bf16x8 kf = *reinterpret_cast<const bf16x8*>(sK + (kb * 16 + lq) * LDT + ks * 32 + lh * 8);
-        st[kb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[0][ks], st[kb][0], 0, 0, 0);
-        st[kb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[1][ks], st[kb][1], 0, 0, 0);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) st[kb][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[qb][ks], st[kb][qb], 0, 0, 0);
       }
     }
 
     // only tiles that reach past the sequence end or past this wavefront's first query row (causal) need
     // the mask; the test is the same for the whole wavefront
     const bool edge = kv0 + kBKV > S || (a.causal && kv0 + kBKV - 1 > q0);
-    bf16x8 pf[2][2];  // P as operand B of the second product, per query block and 32-key step
+    bf16x8 pf[QB][2];  // P as operand B of the second product, per query block and 32-key step
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < QB; ++qb) {
       const int qrow = q0 + qb * 16 + lq;
       if (edge) {
 #pragma unroll
@@ -217,15 +223,15 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_fwd_kernel(const CoreAr
         const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp + 16 * LDV));
         const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
         const bf16x8 vf = __builtin_bit_cast(bf16x8, both);
-        acc[0][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[0][s2], acc[0][db], 0, 0, 0);
-        acc[1][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[1][s2], acc[1][db], 0, 0, 0);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) acc[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[qb][s2], acc[qb][db], 0, 0, 0);
       }
     }
   }
 
   // normalise and store: lane holds output columns db*16 + (lane/16)*4 .. +3 of query row lane % 16
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
+  for (int qb = 0; qb < QB; ++qb) {
     const int qrow = q0 + qb * 16 + lq;
     const float l = xor_sum(l_run[qb]);
     const float inv = 1.0f / l;
@@ -659,7 +665,11 @@ extern "C" int ntp_attn_core_shard_fwd(const ntp_attn_core_shape_t* s, const voi
   a.kv_off = s->kv_off;
   a.group = s->group;
   a.causal = s->causal ? 1 : 0;
-  a.q_tiles = (s->seq_len + kBQ - 1) / kBQ;
+  // 16-row query blocks per wavefront: two (twice the matrix work per LDS read, two workgroups per CU), or
+  // one (three workgroups per CU, twice as many of them) when two would leave compute units short of work
+  const int64_t blocks2 = int64_t((s->seq_len + 127) / 128) * s->n_seq * s->q_cnt;
+  const int qbw = blocks2 < (s->causal ? 1024 : 384) ? 1 : 2;
+  a.q_tiles = (s->seq_len + 64 * qbw - 1) / (64 * qbw);
   a.scale_log2 = float(1.4426950408889634 / std::sqrt(double(s->head_dim)));
   const int64_t blocks = int64_t(a.q_tiles) * s->n_seq * s->q_cnt;
   if (blocks > 0x7fffffffll) return NTP_ERR_UNSUPPORTED;
@@ -667,10 +677,14 @@ extern "C" int ntp_attn_core_shard_fwd(const ntp_attn_core_shape_t* s, const voi
   if (ntp::timing_on())
     ntp::timing_begin(stream, s->causal ? "attn_core_fwd_causal" : "attn_core_fwd",
                       (s->causal ? 2.0 : 4.0) * double(s->n_seq) * double(s->seq_len) * double(s->seq_len) * s->head_dim * s->q_cnt, 0.0);
-  if (s->head_dim == 128)
-    hipLaunchKernelGGL(attn_core_fwd_kernel<128>, dim3(uint32_t(blocks)), dim3(kThreads), 0, hs, a);
+  if (s->head_dim == 128 && qbw == 2)
+    hipLaunchKernelGGL((attn_core_fwd_kernel<128, 2>), dim3(uint32_t(blocks)), dim3(kThreads), 0, hs, a);
+  else if (s->head_dim == 128)
+    hipLaunchKernelGGL((attn_core_fwd_kernel<128, 1>), dim3(uint32_t(blocks)), dim3(kThreads), 0, hs, a);
+  else if (qbw == 2)
+    hipLaunchKernelGGL((attn_core_fwd_kernel<64, 2>), dim3(uint32_t(blocks)), dim3(kThreads), 0, hs, a);
   else
-    hipLaunchKernelGGL(attn_core_fwd_kernel<64>, dim3(uint32_t(blocks)), dim3(kThreads), 0, hs, a);
+    hipLaunchKernelGGL((attn_core_fwd_kernel<64, 1>), dim3(uint32_t(blocks)), dim3(kThreads), 0, hs, a);
   const bool ok = hipGetLastError() == hipSuccess;
   ntp::timing_end(stream);
   return ok ? NTP_OK : NTP_ERR_LAUNCH;
