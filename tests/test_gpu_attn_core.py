@@ -70,6 +70,13 @@ def test_attn_core_fwd_matches_oracle(n_q, n_kv, tp, rank, d, n_seq, S, causal):
     _case(n_q, n_kv, tp, rank, d, n_seq, S, causal)
 
 
+@pytest.mark.parametrize("n_q,tp,n_seq,S,causal", [(24, 1, 4, 512, False), (32, 1, 8, 512, True)])
+def test_attn_core_fwd_many_workgroups(n_q, tp, n_seq, S, causal):
+    # enough (sequence, head, tile) workgroups for the variant with 32 query rows per wavefront
+    _say(f"attn core fwd, many workgroups: heads {n_q} n_seq {n_seq} S {S} causal {causal}")
+    _case(n_q, n_q, tp, 0, 128, n_seq, S, causal, seed=2)
+
+
 def _bwd_case(n_q, n_kv, tp, rank, d, n_seq, S, causal, seed=1, pad=0):
     import torch
     import paper_2504_06095_amd as N
