@@ -26,7 +26,6 @@ using ntp_gemm::s16x4;
 using ntp_gemm::s16x8;
 using ntp_gemm::u16x4;
 
-constexpr int kBQ = 128;   // query rows per workgroup
 constexpr int kBKV = 64;   // keys per tile
 constexpr int kThreads = 256;
 
@@ -281,9 +280,10 @@ __device__ __forceinline__ bf16x8 tr_frag(const uint16_t* tile, int ldt, int r0,
   return __builtin_bit_cast(bf16x8, both);
 }
 
-// dQ (and delta): a workgroup takes 128 query rows of one (sequence, head), a wavefront 32 of them.
-template <int D>
-__global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dq_kernel(const CoreBwdArgs a) {
+// dQ (and delta): a workgroup takes 64 QB query rows of one (sequence, head), a wavefront 16 QB of them.
+template <int D, int QB>
+__global__ __launch_bounds__(kThreads, QB == 1 ? 3 : 2) void attn_core_bwd_dq_kernel(const CoreBwdArgs a) {
+  constexpr int kRows = 64 * QB;
   constexpr int LDT = D + 16, KS = D / 32, DB = D / 16, CPR = D / 8, NLD = kBKV * CPR / kThreads;
   __shared__ __attribute__((aligned(16))) uint16_t sK[kBKV * LDT];
   __shared__ __attribute__((aligned(16))) uint16_t sV[kBKV * LDT];
@@ -295,16 +295,16 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dq_kernel(const Cor
   const int64_t tok0 = int64_t(seq) * S, Mtot = int64_t(a.n_seq) * S;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lq = lane & 15, lh = lane >> 4;
-  const int q0 = qt * kBQ + wave * 32;
+  const int q0 = qt * kRows + wave * (16 * QB);
   const uint16_t* Qp = a.QKV + int64_t(head) * D;
   const uint16_t* Kp = a.QKV + int64_t(a.q_cnt + g) * D;
   const uint16_t* Vp = a.QKV + int64_t(a.q_cnt + a.kv_cnt + g) * D;
 
   // query and output-gradient fragments (operand B: j = query row), delta and the log-sum-exp of the rows
-  bf16x8 qf[2][KS], gf[2][KS];
-  float lse2[2], delta[2];
+  bf16x8 qf[QB][KS], gf[QB][KS];
+  float lse2[QB], delta[QB];
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
+  for (int qb = 0; qb < QB; ++qb) {
     const int qr = min(q0 + qb * 16 + lq, S - 1);
     float part = 0.f;
 #pragma unroll
@@ -320,13 +320,13 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dq_kernel(const Cor
     if (lh == 0 && q0 + qb * 16 + lq < S) a.Delta[int64_t(head) * Mtot + tok0 + qr] = delta[qb];
   }
 
-  f32x4 acc[2][DB];
+  f32x4 acc[QB][DB];
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb)
+  for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
     for (int db = 0; db < DB; ++db) acc[qb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  const int kv_end = a.causal ? min(S, qt * kBQ + kBQ) : S;
+  const int kv_end = a.causal ? min(S, qt * kRows + kRows) : S;
   const int n_tiles = (kv_end + kBKV - 1) / kBKV;
   ntp_gemm::u16x8 rk[NLD], rv[NLD];
   auto load_tile = [&](int t) {
@@ -356,13 +356,13 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dq_kernel(const Cor
     __syncthreads();
     if (t + 1 < n_tiles) load_tile(t + 1);
     const int kv0 = t * kBKV;
-    if (a.causal && kv0 > q0 + 31) continue;  // nothing of this tile is visible to the wavefront's rows
+    if (a.causal && kv0 > q0 + 16 * QB - 1) continue;  // nothing of this tile is visible to the wavefront's rows
     // S^T and dP^T blocks: [key kb*16 + (lane/16)*4 + r][query qb*16 + lane%16]
-    f32x4 st[4][2], dpt[4][2];
+    f32x4 st[4][QB], dpt[4][QB];
 #pragma unroll
     for (int kb = 0; kb < 4; ++kb) {
 #pragma unroll
-      for (int qb = 0; qb < 2; ++qb) {
+      for (int qb = 0; qb < QB; ++qb) {
         st[kb][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
         dpt[kb][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
       }
@@ -371,16 +371,16 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dq_kernel(const Cor
         const bf16x8 kf = *reinterpret_cast<const bf16x8*>(sK + (kb * 16 + lq) * LDT + ks * 32 + lh * 8);
         const bf16x8 vf = *reinterpret_cast<const bf16x8*>(sV + (kb * 16 + lq) * LDT + ks * 32 + lh * 8);
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
+        for (int qb = 0; qb < QB; ++qb) {
           st[kb][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[qb][ks], st[kb][qb], 0, 0, 0);
           dpt[kb][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, gf[qb][ks], dpt[kb][qb], 0, 0, 0);
         }
       }
     }
     const bool edge = kv0 + kBKV > S || (a.causal && kv0 + kBKV - 1 > q0);
-    bf16x8 dsf[2][2];
+    bf16x8 dsf[QB][2];
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < QB; ++qb) {
       const int qrow = q0 + qb * 16 + lq;
       float ds[4][4];
 #pragma unroll
@@ -417,12 +417,12 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dq_kernel(const Cor
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {
         const bf16x8 kt = tr_frag(sK, LDT, s2 * 32, db * 16, lq, lh);
-        acc[0][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kt, dsf[0][s2], acc[0][db], 0, 0, 0);
-        acc[1][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kt, dsf[1][s2], acc[1][db], 0, 0, 0);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) acc[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kt, dsf[qb][s2], acc[qb][db], 0, 0, 0);
       }
   }
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
+  for (int qb = 0; qb < QB; ++qb) {
     const int qrow = q0 + qb * 16 + lq;
     if (qrow >= S) continue;
     uint16_t* op = a.dQKV + (tok0 + qrow) * a.ldd + int64_t(head) * D + lh * 4;
@@ -723,7 +723,10 @@ extern "C" int ntp_attn_core_shard_bwd(const ntp_attn_core_shape_t* s, const voi
   a.kv_off = s->kv_off;
   a.group = s->group;
   a.causal = s->causal ? 1 : 0;
-  a.tiles = (s->seq_len + kBQ - 1) / kBQ;
+  // the dQ kernel with 16 query rows per wavefront (three workgroups per CU, no register spills) measured
+  // faster than with 32 at almost every size: only that variant is built
+  constexpr int qbw = 1;
+  a.tiles = (s->seq_len + 64 * qbw - 1) / (64 * qbw);
   constexpr int kb = 1;  // 64 keys per workgroup of the dK/dV kernel
   const int32_t key_tiles = (s->seq_len + 64 * kb - 1) / (64 * kb);
   a.scale = float(1.0 / std::sqrt(double(s->head_dim)));
@@ -737,9 +740,9 @@ extern "C" int ntp_attn_core_shard_bwd(const ntp_attn_core_shape_t* s, const voi
     // dQ and delta: three products per (query, key) pair
     if (ntp::timing_on()) ntp::timing_begin(stream, "attn_core_bwd_dq", 3.0 * pair_flops, 0.0);
     if (s->head_dim == 128)
-      hipLaunchKernelGGL(attn_core_bwd_dq_kernel<128>, dim3(uint32_t(bq)), dim3(kThreads), 0, hs, a);
+      hipLaunchKernelGGL((attn_core_bwd_dq_kernel<128, qbw>), dim3(uint32_t(bq)), dim3(kThreads), 0, hs, a);
     else
-      hipLaunchKernelGGL(attn_core_bwd_dq_kernel<64>, dim3(uint32_t(bq)), dim3(kThreads), 0, hs, a);
+      hipLaunchKernelGGL((attn_core_bwd_dq_kernel<64, qbw>), dim3(uint32_t(bq)), dim3(kThreads), 0, hs, a);
     ok = hipGetLastError() == hipSuccess;
     ntp::timing_end(stream);
     if (!ok) return NTP_ERR_LAUNCH;
