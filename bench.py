@@ -358,6 +358,68 @@ def attn_core_bench(torch, N):
     return out
 
 
+def config_table(torch, N, iters=10):
+    """`--config-table`: throughput of the shard calls at each of the five benchmark configurations (1: tiny MLP
+    shard; 2: GPT-3-175B-shape MLP shard; 3: grouped-query attention shard at TP 30 of 32, projections and core;
+    4: 405B-shape MLP shard at TP 71 of 72; 5 is the reshard stress of the default run)."""
+    dev = "cuda"
+    bf = dict(dtype=torch.bfloat16, device=dev)
+    e = lambda r, c, dt=torch.bfloat16: torch.empty(r, c, dtype=dt, device=dev)
+    rows = []
+
+    def mlp(tag, Mt, Hd, ffn, tp, rank):
+        n_r = N.ntp_shard_plan(ffn, tp, rank)[1]
+        ld = (n_r + 63) // 64 * 64
+        X, dZ = torch.randn(Mt, Hd, **bf), torch.randn(Mt, Hd, **bf)
+        At, B = torch.randn(n_r, Hd, **bf) * 0.02, torch.randn(n_r, Hd, **bf) * 0.02
+        P, Y, dP = e(Mt, ld)[:, :n_r], e(Mt, ld)[:, :n_r], e(Mt, ld)[:, :n_r]
+        Z, dX = e(Mt, Hd), e(Mt, Hd)
+        dA, dB = e(n_r, Hd, torch.float32), e(n_r, Hd, torch.float32)
+        fwd = lambda: N.ntp_mlp_shard_fwd(X, At, B, P, Y, Z, n_r)
+        bwd = lambda: N.ntp_mlp_shard_bwd(dZ, X, At, B, P, Y, dP, dX, dA, dB, n_r)
+        for _ in range(3):
+            fwd(); bwd()
+        tf, tb = timed(torch, fwd, iters), timed(torch, bwd, iters)
+        fl = 4.0 * Mt * Hd * n_r
+        rows.append(dict(config=tag, call="mlp shard", tokens=Mt, hidden=Hd, width=n_r, fwd_ms=tf, fwd_TFLOPs=fl / tf / 1e9,
+                         bwd_ms=tb, bwd_TFLOPs=2 * fl / tb / 1e9, fwd_bwd_frac_of_peak=3 * fl / (tf + tb) / 1e9 / BF16_MFMA_PEAK_TFLOPS))
+
+    def attn(tag, Mt, Hd, n_q, n_kv, d, tp, rank):
+        plan = N.ntp_attn_shard_plan(n_q, n_kv, d, tp, rank)
+        wq, wo, q = plan["w_qkv"], plan["w_o"], plan["q_cnt"]
+        X, dZ = torch.randn(Mt, Hd, **bf), torch.randn(Mt, Hd, **bf)
+        Wqkv, Wo = torch.randn(wq, Hd, **bf) * 0.02, torch.randn(wo, Hd, **bf) * 0.02
+        QKV, Cc, Z, dC, dX, dQKV = e(Mt, wq), e(Mt, wo), e(Mt, Hd), e(Mt, wo), e(Mt, Hd), e(Mt, wq)
+        dWq, dWo = e(wq, Hd, torch.float32), e(wo, Hd, torch.float32)
+        LSE, Delta = e(q, Mt, torch.float32), e(q, Mt, torch.float32)
+        shp = N.attn_core_shape(1, Mt, plan, n_q // n_kv, True)
+
+        def fwd():
+            N.ntp_attn_proj_shard_fwd(Mt, Hd, wq, wo, X, Wqkv, QKV, None, None, None)
+            N.ntp_attn_core_shard_fwd(shp, QKV, Cc, LSE)
+            N.ntp_attn_proj_shard_fwd(Mt, Hd, wq, wo, None, None, None, Cc, Wo, Z)
+
+        def bwd():
+            N.ntp_attn_proj_shard_bwd(Mt, Hd, wq, wo, dZ, None, None, Cc, None, Wo, dC, None, None, dWo)
+            N.ntp_attn_core_shard_bwd(shp, QKV, Cc, dC, LSE, Delta, dQKV)
+            N.ntp_attn_proj_shard_bwd(Mt, Hd, wq, wo, None, dQKV, X, None, Wqkv, None, None, dX, dWq, None)
+        for _ in range(3):
+            fwd(); bwd()
+        tf, tb = timed(torch, fwd, iters), timed(torch, bwd, iters)
+        proj = 2.0 * Mt * Hd * (wq + wo)
+        core = 2.0 * Mt * Mt * d * q  # causal: half of 4 S^2 d per head
+        rows.append(dict(config=tag, call="attention shard (projections + causal core)", tokens=Mt, hidden=Hd, heads=q, w_qkv=wq,
+                         fwd_ms=tf, fwd_TFLOPs=(proj + core) / tf / 1e9, bwd_ms=tb, bwd_TFLOPs=(2 * proj + 2.5 * core) / tb / 1e9,
+                         fwd_bwd_frac_of_peak=(3 * proj + 3.5 * core) / (tf + tb) / 1e9 / BF16_MFMA_PEAK_TFLOPS))
+
+    mlp("c1", 512, 1024, 4096, 7, 0)
+    mlp("c2", 2048, 12288, 49152, 7, 0)
+    attn("c3 rank 0 (3 heads)", 4096, 8192, 64, 8, 128, 30, 0)
+    attn("c3 rank 29 (2 heads)", 4096, 8192, 64, 8, 128, 30, 29)
+    mlp("c4", 8192, 16384, 53248, 71, 0)
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -368,6 +430,8 @@ def main():
     ap.add_argument("--no-mapped-reshard", action="store_true")
     ap.add_argument("--no-fused-step", action="store_true")
     ap.add_argument("--no-attn-core", action="store_true")
+    ap.add_argument("--config-table", action="store_true",
+                    help="time the shard calls at each benchmark configuration instead and print a JSON line of its own")
     ap.add_argument("--imbalance-sweep", action="store_true",
                     help="run the second workload instead (all ranks of TP 8 degraded to 7, 6, 4 at the prototype's shapes) "
                          "and print its own JSON line")
@@ -384,6 +448,10 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+    if args.config_table:
+        print(json.dumps({"metric": "shard fwd / bwd TFLOP/s per benchmark configuration", "unit": "TFLOP/s", "n_gpus": 1,
+                          "dtype": "bf16", "data": "synthetic", "rows": config_table(torch, N)}))
+        return
     if args.imbalance_sweep:
         rows = imbalance_sweep(torch, N)
         print(json.dumps({"metric": "layer shard time of the slowest rank over the mean over ranks (MLP + attention "
