@@ -437,6 +437,8 @@ def main():
                          "and print its own JSON line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB dense copy (calibration_copy_kernel): the yardstick for profiler byte counters")
+    ap.add_argument("--no-workspace", action="store_true",
+                    help="do not register a split-K workspace (skinny shard GEMMs then run unsplit)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the shard hot path of a single rank); --gpus must be 1",
@@ -448,6 +450,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+    if not args.no_workspace:
+        # 1 GiB for the fp32 partial sums of split-K shard GEMMs, held for the whole run
+        N.ntp_set_workspace(torch.empty(256 << 20, dtype=torch.float32, device="cuda"))
     if args.config_table:
         print(json.dumps({"metric": "shard fwd / bwd TFLOP/s per benchmark configuration", "unit": "TFLOP/s", "n_gpus": 1,
                           "dtype": "bf16", "data": "synthetic", "rows": config_table(torch, N)}))

@@ -377,6 +377,20 @@ typedef struct ntp_kernel_time {
 int ntp_kernel_timing_enable(int32_t on);
 int ntp_kernel_timing_read(ntp_kernel_time_t* out, int64_t max_records, int64_t* count);
 
+/* Workspace for split-K (Sec. 3.1: at a high TP degree a column-parallel shard X A_i or
+ * X W_qkv,i is a skinny GEMM with fewer output tiles than the GPU has compute units).
+ * With a workspace registered, a shard GEMM whose output tiles would leave most compute
+ * units idle is also cut along its contraction axis: fp32 partial sums go to the
+ * workspace and a second kernel adds them in a fixed order and applies the epilogue
+ * (results stay deterministic; they differ from the unsplit GEMM by fp32 rounding order).
+ *   workspace  device pointer, 256-byte aligned; NULL with bytes == 0 unregisters
+ *   bytes      its size; a GEMM is split only if splits * M * round_up(N, 16) * 4 fits
+ * The caller owns the memory and keeps it alive while registered.  One workspace per
+ * process: shard calls that may split must not overlap in time (same stream, or
+ * ordered across streams), on one device.  Without a workspace nothing is ever split.
+ * Errors: NTP_ERR_INVALID_ARG (misaligned, negative size, NULL with bytes > 0). */
+int ntp_set_workspace(void* workspace, int64_t bytes);
+
 /* Measurement aid: a plain dense device-to-device copy of `bytes` bytes (dst, src:
  * device, 16-byte aligned, bytes % 16 == 0, not overlapping) by a kernel named
  * calibration_copy_kernel.  Its known traffic (bytes read, bytes written) is what

@@ -29,6 +29,7 @@ EXPORTS = (
     "ntp_comp_sync_plan", "ntp_reshard_plan_create", "ntp_reshard_plan_segments", "ntp_reshard_plan_splits",
     "ntp_reshard_plan_table", "ntp_reshard_plan_run", "ntp_reshard_plan_destroy", "ntp_reshard_row_segments",
     "ntp_mlp_shard_bwd_resharded", "ntp_attn_proj_shard_bwd_resharded", "ntp_attn_core_shard_fwd", "ntp_attn_core_shard_bwd",
+    "ntp_set_workspace",
 )
 
 
@@ -124,6 +125,7 @@ def lib() -> C.CDLL:
         L.ntp_kernel_timing_enable.argtypes = [C.c_int32]
         L.ntp_kernel_timing_read.argtypes = [C.POINTER(KernelTime), i64, C.POINTER(i64)]
         L.ntp_calibration_copy.argtypes = [vp, vp, i64, vp]
+        L.ntp_set_workspace.argtypes = [vp, i64]
         for name in EXPORTS:
             getattr(L, name)  # AttributeError if a declared symbol is not exported
         _lib = L
@@ -436,3 +438,19 @@ def ntp_calibration_copy(dst, src) -> None:
     if dst.numel() * dst.element_size() != nbytes or not (src.is_contiguous() and dst.is_contiguous()):
         raise ValueError("expected two contiguous tensors of equal byte size")
     _check(lib().ntp_calibration_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream()), "ntp_calibration_copy")
+
+
+_workspace = None  # keeps the registered tensor alive
+
+
+def ntp_set_workspace(workspace) -> None:
+    """Register a device tensor (any dtype, contiguous) as the split-K workspace, or None to unregister."""
+    global _workspace
+    if workspace is None:
+        _check(lib().ntp_set_workspace(None, 0), "ntp_set_workspace")
+        _workspace = None
+        return
+    if not workspace.is_contiguous():
+        raise ValueError("expected a contiguous tensor")
+    _check(lib().ntp_set_workspace(workspace.data_ptr(), workspace.numel() * workspace.element_size()), "ntp_set_workspace")
+    _workspace = workspace

@@ -12,8 +12,11 @@
 //                            permuted the same way on the V side, read transposed from LDS).
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdint>
+#include <cstdio>
+#include <cstdlib>
 
 #include "ntp_gemm_kernels.h"
 #include "ntp_internal.h"
@@ -37,6 +40,11 @@ struct CoreArgs {
   int32_t n_seq, seq_len, q_cnt, kv_cnt, q_off, kv_off, group, causal;
   int32_t q_tiles;      // per sequence
   float scale_log2;     // log2(e) / sqrt(d)
+  // n_parts > 1 (16 query rows per wavefront only): each workgroup's walk over the key tiles is cut into
+  // n_parts pieces, one workgroup each, which store their unnormalised output rows, running maximum and
+  // sum to part_sums ([workgroup][piece][64 rows][D + 4]: D outputs, maximum, sum); a second kernel merges them
+  float* part_sums;
+  int32_t n_parts;
 };
 
 // 2^x by the hardware instruction alone: results below the normal range flush to zero, which is what a
@@ -69,8 +77,10 @@ __global__ __launch_bounds__(kThreads, QB == 1 ? 3 : 2) void attn_core_fwd_kerne
 
   // workgroup -> (head, sequence, query tile); consecutive workgroups share a head's keys and values.
   // With the causal mask the late tiles have the most keys: they go first.
-  const int qt = a.causal ? a.q_tiles - 1 - int(blockIdx.x % a.q_tiles) : int(blockIdx.x % a.q_tiles);
-  const int sh = blockIdx.x / a.q_tiles;
+  const int piece = a.n_parts > 1 ? int(blockIdx.x % a.n_parts) : 0;
+  const int blk = a.n_parts > 1 ? int(blockIdx.x / a.n_parts) : int(blockIdx.x);
+  const int qt = a.causal ? a.q_tiles - 1 - blk % a.q_tiles : blk % a.q_tiles;
+  const int sh = blk / a.q_tiles;
   const int seq = sh % a.n_seq, head = sh / a.n_seq;
   const int g = (a.q_off + head) / a.group - a.kv_off;  // local KV head
   const int S = a.seq_len;
@@ -130,12 +140,15 @@ __global__ __launch_bounds__(kThreads, QB == 1 ? 3 : 2) void attn_core_fwd_kerne
     }
   };
 
-  load_tile(0);
-  for (int t = 0; t < n_tiles; ++t) {
+  // this workgroup's share of the key tiles (all of them unless the walk is cut)
+  const int t_lo = a.n_parts > 1 ? int(int64_t(piece) * n_tiles / a.n_parts) : 0;
+  const int t_hi = a.n_parts > 1 ? int(int64_t(piece + 1) * n_tiles / a.n_parts) : n_tiles;
+  if (t_lo < t_hi) load_tile(t_lo);
+  for (int t = t_lo; t < t_hi; ++t) {
     __syncthreads();  // everyone has finished reading the previous tile
     store_tile();
     __syncthreads();
-    if (t + 1 < n_tiles) load_tile(t + 1);
+    if (t + 1 < t_hi) load_tile(t + 1);
     const int kv0 = t * kBKV;
     if (a.causal && kv0 > q0 + 16 * QB - 1) continue;  // every key of the tile lies after this wavefront's last query row
 
@@ -228,6 +241,21 @@ __global__ __launch_bounds__(kThreads, QB == 1 ? 3 : 2) void attn_core_fwd_kerne
     }
   }
 
+  if (a.n_parts > 1) {
+    // this piece's unnormalised rows, maximum (in log2 units) and sum
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      float* pp = a.part_sums + ((int64_t(blk) * a.n_parts + piece) * kRows + wave * (16 * QB) + qb * 16 + lq) * (D + 4);
+#pragma unroll
+      for (int db = 0; db < DB; ++db) *reinterpret_cast<f32x4*>(pp + db * 16 + lh * 4) = acc[qb][db];
+      const float l = xor_sum(l_run[qb]);
+      if (lh == 0) {
+        pp[D] = m_run[qb];
+        pp[D + 1] = l;
+      }
+    }
+    return;
+  }
   // normalise and store: lane holds output columns db*16 + (lane/16)*4 .. +3 of query row lane % 16
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
@@ -248,6 +276,40 @@ __global__ __launch_bounds__(kThreads, QB == 1 ? 3 : 2) void attn_core_fwd_kerne
   }
 }
 
+// Merges the pieces of a cut forward walk: with m = max_p m_p, the row is sum_p 2^(m_p - m) O_p over
+// sum_p 2^(m_p - m) l_p.  One thread per 4 output values; a piece that saw no key has m_p = -inf, l_p = 0.
+template <int D>
+__global__ __launch_bounds__(256) void attn_core_fwd_merge_kernel(const CoreArgs a, int64_t n_blk) {
+  constexpr int Q = D / 4, W = D + 4;
+  const int64_t idx = int64_t(blockIdx.x) * 256 + threadIdx.x;
+  const int c = int(idx % Q) * 4, row = int((idx / Q) % 64);
+  const int64_t blk = idx / (Q * 64);
+  if (blk >= n_blk) return;
+  const int qt = a.causal ? a.q_tiles - 1 - int(blk % a.q_tiles) : int(blk % a.q_tiles);
+  const int64_t sh = blk / a.q_tiles;
+  const int seq = int(sh % a.n_seq), head = int(sh / a.n_seq);
+  const int qrow = qt * 64 + row;
+  if (qrow >= a.seq_len) return;
+  const float* p = a.part_sums + (blk * a.n_parts * 64 + row) * W;
+  float m = -INFINITY;
+  for (int i = 0; i < a.n_parts; ++i) m = fmaxf(m, p[int64_t(i) * 64 * W + D]);
+  f32x4 o = {0.f, 0.f, 0.f, 0.f};
+  float l = 0.f;
+  for (int i = 0; i < a.n_parts; ++i) {
+    const float* pi = p + int64_t(i) * 64 * W;
+    const float w = fast_exp2(pi[D] - m);  // every row sees at least one key, so m is finite
+    o = o + *reinterpret_cast<const f32x4*>(pi + c) * w;
+    l += pi[D + 1] * w;
+  }
+  const float inv = 1.0f / l;
+  u16x4 out;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) out[r] = ntp_gemm::f32_to_bf16(o[r] * inv);
+  const int64_t tok = int64_t(seq) * a.seq_len + qrow;
+  *reinterpret_cast<u16x4*>(a.C + tok * a.ldc + int64_t(head) * D + c) = out;
+  if (c == 0 && a.LSE) a.LSE[int64_t(head) * (int64_t(a.n_seq) * a.seq_len) + tok] = (m + log2f(l)) * 0.6931471805599453f;
+}
+
 // ---- backward ---------------------------------------------------------------------------------
 // With P = softmax rows (rebuilt from the saved log-sum-exp), dP = dC V^T and
 // delta_i = sum_d dC_id C_id:  dS = P .* (dP - delta),  dQ = dS K / sqrt(d),  dK = dS^T Q / sqrt(d),
@@ -266,6 +328,10 @@ struct CoreBwdArgs {
   int32_t tiles;        // query tiles (dQ kernel) or key tiles (dK/dV kernel) per sequence
   float scale_log2;     // log2(e) / sqrt(d)
   float scale;          // 1 / sqrt(d)
+  // n_parts > 1: the walk of every workgroup is cut into n_parts pieces, one workgroup each, which store
+  // their fp32 sums to part_sums ([workgroup][part][64 rows][row length]); a second kernel adds them
+  float* part_sums;
+  int32_t n_parts;
 };
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4_t;
@@ -287,8 +353,10 @@ __global__ __launch_bounds__(kThreads, QB == 1 ? 3 : 2) void attn_core_bwd_dq_ke
   constexpr int LDT = D + 16, KS = D / 32, DB = D / 16, CPR = D / 8, NLD = kBKV * CPR / kThreads;
   __shared__ __attribute__((aligned(16))) uint16_t sK[kBKV * LDT];
   __shared__ __attribute__((aligned(16))) uint16_t sV[kBKV * LDT];
-  const int qt = a.causal ? a.tiles - 1 - int(blockIdx.x % a.tiles) : int(blockIdx.x % a.tiles);
-  const int sh = blockIdx.x / a.tiles;
+  const int piece = a.n_parts > 1 ? int(blockIdx.x % a.n_parts) : 0;
+  const int blk = a.n_parts > 1 ? int(blockIdx.x / a.n_parts) : int(blockIdx.x);
+  const int qt = a.causal ? a.tiles - 1 - blk % a.tiles : blk % a.tiles;
+  const int sh = blk / a.tiles;
   const int seq = sh % a.n_seq, head = sh / a.n_seq;
   const int g = (a.q_off + head) / a.group - a.kv_off;
   const int S = a.seq_len;
@@ -317,7 +385,7 @@ __global__ __launch_bounds__(kThreads, QB == 1 ? 3 : 2) void attn_core_bwd_dq_ke
     }
     delta[qb] = xor_sum(part);
     lse2[qb] = a.LSE[int64_t(head) * Mtot + tok0 + qr] * 1.4426950408889634f;
-    if (lh == 0 && q0 + qb * 16 + lq < S) a.Delta[int64_t(head) * Mtot + tok0 + qr] = delta[qb];
+    if (lh == 0 && piece == 0 && q0 + qb * 16 + lq < S) a.Delta[int64_t(head) * Mtot + tok0 + qr] = delta[qb];
   }
 
   f32x4 acc[QB][DB];
@@ -349,12 +417,15 @@ __global__ __launch_bounds__(kThreads, QB == 1 ? 3 : 2) void attn_core_bwd_dq_ke
     }
   };
 
-  load_tile(0);
-  for (int t = 0; t < n_tiles; ++t) {
+  // this workgroup's share of the key tiles (all of them unless the walk is cut into parts)
+  const int t_lo = a.n_parts > 1 ? int(int64_t(piece) * n_tiles / a.n_parts) : 0;
+  const int t_hi = a.n_parts > 1 ? int(int64_t(piece + 1) * n_tiles / a.n_parts) : n_tiles;
+  if (t_lo < t_hi) load_tile(t_lo);
+  for (int t = t_lo; t < t_hi; ++t) {
     __syncthreads();
     store_tile();
     __syncthreads();
-    if (t + 1 < n_tiles) load_tile(t + 1);
+    if (t + 1 < t_hi) load_tile(t + 1);
     const int kv0 = t * kBKV;
     if (a.causal && kv0 > q0 + 16 * QB - 1) continue;  // nothing of this tile is visible to the wavefront's rows
     // S^T and dP^T blocks: [key kb*16 + (lane/16)*4 + r][query qb*16 + lane%16]
@@ -421,6 +492,16 @@ __global__ __launch_bounds__(kThreads, QB == 1 ? 3 : 2) void attn_core_bwd_dq_ke
         for (int qb = 0; qb < QB; ++qb) acc[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kt, dsf[qb][s2], acc[qb][db], 0, 0, 0);
       }
   }
+  if (a.n_parts > 1) {
+    // unscaled fp32 sums of this part: row (wavefront, block, lane % 16) of the workgroup's 64 QB rows
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      float* pp = a.part_sums + ((int64_t(blk) * a.n_parts + piece) * kRows + wave * (16 * QB) + qb * 16 + lq) * D + lh * 4;
+#pragma unroll
+      for (int db = 0; db < DB; ++db) *reinterpret_cast<f32x4*>(pp + db * 16) = acc[qb][db];
+    }
+    return;
+  }
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     const int qrow = q0 + qb * 16 + lq;
@@ -447,8 +528,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dkv_kernel(const Co
   __shared__ __attribute__((aligned(16))) uint16_t sG[kBKV * LDT];
   __shared__ __attribute__((aligned(16))) float sL[kBKV];
   __shared__ __attribute__((aligned(16))) float sD[kBKV];
-  const int kt = blockIdx.x % a.tiles;
-  const int sh = blockIdx.x / a.tiles;
+  const int part = a.n_parts > 1 ? int(blockIdx.x % a.n_parts) : 0;
+  const int blk = a.n_parts > 1 ? int(blockIdx.x / a.n_parts) : int(blockIdx.x);
+  const int kt = blk % a.tiles;
+  const int sh = blk / a.tiles;
   const int seq = sh % a.n_seq, g = sh / a.n_seq;  // g: local KV head
   const int S = a.seq_len;
   const int64_t tok0 = int64_t(seq) * S, Mtot = int64_t(a.n_seq) * S;
@@ -481,10 +564,23 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dkv_kernel(const Co
   // query tiles this workgroup needs: all, or from the tile that holds its first key on
   const int q_first = a.causal ? (kt * (64 * KB)) / kBKV : 0;
   const int q_tiles = (S + kBKV - 1) / kBKV;
+  // The walk is a list of (query head, query tile) units, head-major; part p of n_parts takes an even,
+  // contiguous share of it.
+  const int nt = max(q_tiles - q_first, 0);
+  int heads_here = 0;
+  for (int head = 0; head < a.q_cnt; ++head) heads_here += (a.q_off + head) / a.group - a.kv_off == g ? 1 : 0;
+  const int units = heads_here * nt;
+  const int u_lo = a.n_parts > 1 ? int(int64_t(part) * units / a.n_parts) : 0;
+  const int u_hi = a.n_parts > 1 ? int(int64_t(part + 1) * units / a.n_parts) : units;
+  int head_idx = 0;
   ntp_gemm::u16x8 rq[NLD], rg[NLD];
   float rl = 0.f, rd = 0.f;
   for (int head = 0; head < a.q_cnt; ++head) {
     if ((a.q_off + head) / a.group - a.kv_off != g) continue;  // the same for the whole workgroup
+    const int u_base = head_idx * nt;
+    ++head_idx;
+    const int t_lo = q_first + max(u_lo - u_base, 0), t_hi = q_first + min(u_hi - u_base, nt);
+    if (t_lo >= t_hi) continue;
     const uint16_t* Qp = a.QKV + int64_t(head) * D;
     const uint16_t* Gp = a.dC + int64_t(head) * D;
     auto load_tile = [&](int t) {
@@ -514,13 +610,12 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dkv_kernel(const Co
         sD[threadIdx.x] = rd;
       }
     };
-    if (q_first >= q_tiles) continue;
-    load_tile(q_first);
-    for (int t = q_first; t < q_tiles; ++t) {
+    load_tile(t_lo);
+    for (int t = t_lo; t < t_hi; ++t) {
       __syncthreads();
       store_tile();
       __syncthreads();
-      if (t + 1 < q_tiles) load_tile(t + 1);
+      if (t + 1 < t_hi) load_tile(t + 1);
       const int qbase = t * kBKV;
       if (a.causal && qbase + kBKV - 1 < k0) continue;  // every query row of the tile comes before this wavefront's keys
       // S and dP blocks: [query qb*16 + (lane/16)*4 + r][key kb*16 + lane%16]
@@ -604,6 +699,19 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dkv_kernel(const Co
     }
     __syncthreads();  // the next head's first tile overwrites LDS
   }
+  if (a.n_parts > 1) {
+    // unscaled fp32 sums of this part: per key a row of [dK | dV]
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb) {
+      float* pp = a.part_sums + ((int64_t(blk) * a.n_parts + part) * (64 * KB) + wave * (16 * KB) + kb * 16 + lq) * (2 * D) + lh * 4;
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        *reinterpret_cast<f32x4*>(pp + db * 16) = dk[kb][db];
+        *reinterpret_cast<f32x4*>(pp + D + db * 16) = dv[kb][db];
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int kb = 0; kb < KB; ++kb) {
     const int key = k0 + kb * 16 + lq;
@@ -622,6 +730,47 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dkv_kernel(const Co
       *reinterpret_cast<u16x4*>(vp + db * 16) = ov;
     }
   }
+}
+
+// Adds the parts of a cut walk and stores the gradient as bf16.  `rows` rows per workgroup of the cut
+// kernel, `width` fp32 values per row: D (dQ) or 2 D ([dK | dV]).  One thread per 4 values.
+template <int D, bool DKV>
+__global__ __launch_bounds__(256) void attn_core_part_reduce_kernel(const CoreBwdArgs a, int64_t n_blk) {
+  constexpr int W = DKV ? 2 * D : D, Q = W / 4;
+  const int64_t idx = int64_t(blockIdx.x) * 256 + threadIdx.x;
+  const int c = int(idx % Q) * 4, row = int((idx / Q) % 64);
+  const int64_t blk = idx / (Q * 64);
+  if (blk >= n_blk) return;
+  const int tile = DKV || !a.causal ? int(blk % a.tiles) : a.tiles - 1 - int(blk % a.tiles);
+  const int64_t sh = blk / a.tiles;
+  const int seq = int(sh % a.n_seq), hd = int(sh / a.n_seq);  // local KV head (dK, dV) or query head (dQ)
+  const int tok = tile * 64 + row;
+  if (tok >= a.seq_len) return;
+  const float* p = a.part_sums + (blk * a.n_parts * 64 + row) * W + c;
+  f32x4 sum = *reinterpret_cast<const f32x4*>(p);
+  for (int part = 1; part < a.n_parts; ++part) sum = sum + *reinterpret_cast<const f32x4*>(p + int64_t(part) * 64 * W);
+  const bool is_v = DKV && c >= D;
+  const int col = is_v ? c - D : c;
+  const int64_t slot = DKV ? int64_t(a.q_cnt) + (is_v ? a.kv_cnt : 0) + hd : hd;
+  const float f = is_v ? 1.0f : a.scale;
+  u16x4 o;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) o[r] = ntp_gemm::f32_to_bf16(sum[r] * f);
+  *reinterpret_cast<u16x4*>(a.dQKV + (int64_t(seq) * a.seq_len + tok) * a.ldd + slot * D + col) = o;
+}
+
+// Parts to cut each workgroup's walk into, so that a launch of `blocks` workgroups whose longest walk has
+// `walk` tiles fills the GPU: 1 (no cut) unless a workspace is registered that holds the partial sums.
+int choose_parts(int64_t blocks, int64_t walk, int64_t bytes_per_block_part) {
+  int64_t ws_bytes = 0;
+  if (!ntp::workspace(&ws_bytes) || blocks <= 0) return 1;
+  if (blocks >= 512 && !getenv("NTP_ATTN_PARTS")) return 1;
+  // about 1024 workgroups measured best at 64 to 192 uncut ones; beyond 12 parts the merge costs more than it gains
+  int64_t parts = std::min<int64_t>({12, (1024 + blocks - 1) / blocks, walk / 4});
+  // tests reach every cut through this override (1..16 parts at any size)
+  if (const char* f = getenv("NTP_ATTN_PARTS")) parts = std::min(16, std::max(1, atoi(f)));
+  while (parts > 1 && blocks * parts * bytes_per_block_part > ws_bytes) --parts;
+  return int(std::max<int64_t>(parts, 1));
 }
 
 int check_core_shape(const ntp_attn_core_shape_t* s) {
@@ -668,24 +817,42 @@ extern "C" int ntp_attn_core_shard_fwd(const ntp_attn_core_shape_t* s, const voi
   // 16-row query blocks per wavefront: two (twice the matrix work per LDS read, two workgroups per CU), or
   // one (three workgroups per CU, twice as many of them) when two would leave compute units short of work
   const int64_t blocks2 = int64_t((s->seq_len + 127) / 128) * s->n_seq * s->q_cnt;
-  const int qbw = blocks2 < (s->causal ? 1024 : 384) ? 1 : 2;
+  int qbw = blocks2 < (s->causal ? 1024 : 384) ? 1 : 2;
+  // with few heads even the 64-row workgroups leave compute units idle while each walks over up to
+  // seq_len / 64 key tiles: cut the walks then (needs a registered workspace)
+  const int64_t blocks1 = int64_t((s->seq_len + 63) / 64) * s->n_seq * s->q_cnt;
+  a.part_sums = static_cast<float*>(ntp::workspace(nullptr));
+  a.n_parts = choose_parts(blocks1, (s->seq_len + kBKV - 1) / kBKV, int64_t(64) * (s->head_dim + 4) * 4);
+  if (a.n_parts > 1) qbw = 1;
   a.q_tiles = (s->seq_len + 64 * qbw - 1) / (64 * qbw);
   a.scale_log2 = float(1.4426950408889634 / std::sqrt(double(s->head_dim)));
   const int64_t blocks = int64_t(a.q_tiles) * s->n_seq * s->q_cnt;
-  if (blocks > 0x7fffffffll) return NTP_ERR_UNSUPPORTED;
+  if (blocks * std::max(a.n_parts, 1) > 0x7fffffffll) return NTP_ERR_UNSUPPORTED;
   hipStream_t hs = static_cast<hipStream_t>(stream);
-  if (ntp::timing_on())
-    ntp::timing_begin(stream, s->causal ? "attn_core_fwd_causal" : "attn_core_fwd",
+  if (ntp::timing_on()) {
+    char name[48];
+    snprintf(name, sizeof(name), "attn_core_fwd%s%s", s->causal ? "_causal" : "", a.n_parts > 1 ? "_cut" : "");
+    ntp::timing_begin(stream, name,
                       (s->causal ? 2.0 : 4.0) * double(s->n_seq) * double(s->seq_len) * double(s->seq_len) * s->head_dim * s->q_cnt, 0.0);
+  }
+  const dim3 grid(uint32_t(blocks * std::max(a.n_parts, 1)));
   if (s->head_dim == 128 && qbw == 2)
-    hipLaunchKernelGGL((attn_core_fwd_kernel<128, 2>), dim3(uint32_t(blocks)), dim3(kThreads), 0, hs, a);
+    hipLaunchKernelGGL((attn_core_fwd_kernel<128, 2>), grid, dim3(kThreads), 0, hs, a);
   else if (s->head_dim == 128)
-    hipLaunchKernelGGL((attn_core_fwd_kernel<128, 1>), dim3(uint32_t(blocks)), dim3(kThreads), 0, hs, a);
+    hipLaunchKernelGGL((attn_core_fwd_kernel<128, 1>), grid, dim3(kThreads), 0, hs, a);
   else if (qbw == 2)
-    hipLaunchKernelGGL((attn_core_fwd_kernel<64, 2>), dim3(uint32_t(blocks)), dim3(kThreads), 0, hs, a);
+    hipLaunchKernelGGL((attn_core_fwd_kernel<64, 2>), grid, dim3(kThreads), 0, hs, a);
   else
-    hipLaunchKernelGGL((attn_core_fwd_kernel<64, 1>), dim3(uint32_t(blocks)), dim3(kThreads), 0, hs, a);
-  const bool ok = hipGetLastError() == hipSuccess;
+    hipLaunchKernelGGL((attn_core_fwd_kernel<64, 1>), grid, dim3(kThreads), 0, hs, a);
+  bool ok = hipGetLastError() == hipSuccess;
+  if (ok && a.n_parts > 1) {
+    const dim3 rgrid(uint32_t((blocks * 64 * (s->head_dim / 4) + 255) / 256));
+    if (s->head_dim == 128)
+      hipLaunchKernelGGL((attn_core_fwd_merge_kernel<128>), rgrid, dim3(256), 0, hs, a, blocks);
+    else
+      hipLaunchKernelGGL((attn_core_fwd_merge_kernel<64>), rgrid, dim3(256), 0, hs, a, blocks);
+    ok = hipGetLastError() == hipSuccess;
+  }
   ntp::timing_end(stream);
   return ok ? NTP_OK : NTP_ERR_LAUNCH;
 }
@@ -736,26 +903,50 @@ extern "C" int ntp_attn_core_shard_bwd(const ntp_attn_core_shape_t* s, const voi
   bool ok = true;
   const int64_t bq = int64_t(a.tiles) * s->n_seq * s->q_cnt, bk = int64_t(key_tiles) * s->n_seq * s->kv_cnt;
   if (bq > 0x7fffffffll || bk > 0x7fffffffll) return NTP_ERR_UNSUPPORTED;
+  a.part_sums = static_cast<float*>(ntp::workspace(nullptr));
   if (bq > 0) {
-    // dQ and delta: three products per (query, key) pair
-    if (ntp::timing_on()) ntp::timing_begin(stream, "attn_core_bwd_dq", 3.0 * pair_flops, 0.0);
+    // dQ and delta: three products per (query, key) pair.  With few heads the launch is short of
+    // workgroups and each walks over up to seq_len / 64 key tiles: cut the walks then.
+    a.n_parts = choose_parts(bq, a.tiles, int64_t(64) * s->head_dim * 4);
+    if (ntp::timing_on()) ntp::timing_begin(stream, a.n_parts > 1 ? "attn_core_bwd_dq_cut" : "attn_core_bwd_dq", 3.0 * pair_flops, 0.0);
+    const dim3 grid(uint32_t(bq * a.n_parts));
     if (s->head_dim == 128)
-      hipLaunchKernelGGL((attn_core_bwd_dq_kernel<128, qbw>), dim3(uint32_t(bq)), dim3(kThreads), 0, hs, a);
+      hipLaunchKernelGGL((attn_core_bwd_dq_kernel<128, qbw>), grid, dim3(kThreads), 0, hs, a);
     else
-      hipLaunchKernelGGL((attn_core_bwd_dq_kernel<64, qbw>), dim3(uint32_t(bq)), dim3(kThreads), 0, hs, a);
+      hipLaunchKernelGGL((attn_core_bwd_dq_kernel<64, qbw>), grid, dim3(kThreads), 0, hs, a);
     ok = hipGetLastError() == hipSuccess;
+    if (ok && a.n_parts > 1) {
+      const dim3 rgrid(uint32_t((bq * 64 * (s->head_dim / 4) + 255) / 256));
+      if (s->head_dim == 128)
+        hipLaunchKernelGGL((attn_core_part_reduce_kernel<128, false>), rgrid, dim3(256), 0, hs, a, bq);
+      else
+        hipLaunchKernelGGL((attn_core_part_reduce_kernel<64, false>), rgrid, dim3(256), 0, hs, a, bq);
+      ok = hipGetLastError() == hipSuccess;
+    }
     ntp::timing_end(stream);
     if (!ok) return NTP_ERR_LAUNCH;
   }
   if (bk > 0) {
     // dK and dV: four products per pair
-    if (ntp::timing_on()) ntp::timing_begin(stream, "attn_core_bwd_dkv", 4.0 * pair_flops, 0.0);
+    // a workgroup walks over the query tiles of every query head that reads its KV head
     a.tiles = key_tiles;
+    const int64_t heads_per_kv = std::min<int64_t>(s->group, s->q_cnt);
+    a.n_parts = choose_parts(bk, heads_per_kv * ((s->seq_len + kBKV - 1) / kBKV), int64_t(64) * 2 * s->head_dim * 4);
+    if (ntp::timing_on()) ntp::timing_begin(stream, a.n_parts > 1 ? "attn_core_bwd_dkv_cut" : "attn_core_bwd_dkv", 4.0 * pair_flops, 0.0);
+    const dim3 grid(uint32_t(bk * a.n_parts));
     if (s->head_dim == 128)
-      hipLaunchKernelGGL((attn_core_bwd_dkv_kernel<128, kb>), dim3(uint32_t(bk)), dim3(kThreads), 0, hs, a);
+      hipLaunchKernelGGL((attn_core_bwd_dkv_kernel<128, kb>), grid, dim3(kThreads), 0, hs, a);
     else
-      hipLaunchKernelGGL((attn_core_bwd_dkv_kernel<64, kb>), dim3(uint32_t(bk)), dim3(kThreads), 0, hs, a);
+      hipLaunchKernelGGL((attn_core_bwd_dkv_kernel<64, kb>), grid, dim3(kThreads), 0, hs, a);
     ok = hipGetLastError() == hipSuccess;
+    if (ok && a.n_parts > 1) {
+      const dim3 rgrid(uint32_t((bk * 64 * (2 * s->head_dim / 4) + 255) / 256));
+      if (s->head_dim == 128)
+        hipLaunchKernelGGL((attn_core_part_reduce_kernel<128, true>), rgrid, dim3(256), 0, hs, a, bk);
+      else
+        hipLaunchKernelGGL((attn_core_part_reduce_kernel<64, true>), rgrid, dim3(256), 0, hs, a, bk);
+      ok = hipGetLastError() == hipSuccess;
+    }
     ntp::timing_end(stream);
   }
   return ok ? NTP_OK : NTP_ERR_LAUNCH;

@@ -110,11 +110,91 @@ bool ring_combo(bool a_kc, bool b_kc, int epi) {
   return false;
 }
 
+// ---- split-K ---------------------------------------------------------------------
+// A column-parallel shard at a high TP degree is a skinny GEMM: few output tiles, long K.  With
+// fewer tiles than compute units the K axis is cut as well: `splits` workgroups per tile store fp32
+// partial sums to a caller-provided workspace, and a second kernel adds the slices in ascending
+// order and applies the epilogue.
+void* g_workspace = nullptr;
+int64_t g_workspace_bytes = 0;
+
+struct SplitChoice {
+  int tile, splits, k_chunk;
+};
+
+constexpr double kTileCycles = 2650.0;      // one 256 x 256 x 64 K tile on one compute unit at rate 1
+constexpr int kTileOverhead = 4;            // prologue and epilogue of an output tile, in K tiles
+constexpr double kReduceBytesPerCycle = 2000.0, kReduceFixedCycles = 6000.0;
+constexpr int kMaxSplits = 8, kMinSplitTiles = 8;
+
+double tile_time(int64_t M, int64_t N, int64_t ktiles, int layout, int i, int splits) {
+  const TileShape& ts = kTileShapes[i];
+  const int64_t tiles = ((M + ts.bm - 1) / ts.bm) * ((N + ts.bn - 1) / ts.bn);
+  const int64_t cu_load = (tiles * splits + kComputeUnits - 1) / kComputeUnits;
+  const double rate = ts.waves == 4 && tiles <= kComputeUnits ? kLoneSmallTileRate : kTileRate[layout][i];
+  const int64_t kt = (ktiles + splits - 1) / splits + kTileOverhead;
+  return double(cu_load) * double(kt) * kTileCycles * (ts.bm * ts.bn / 65536.0) / rate;
+}
+
+// Least estimated time over (tile shape, splits); splits == 1 means: leave the GEMM as it is.
+SplitChoice choose_split(int64_t M, int64_t N, int64_t K, int layout, int plain_tile, int64_t ldw) {
+  SplitChoice best{plain_tile, 1, 0};
+  const int64_t ktiles = (K + 63) / 64;
+  int forced = 0;
+  if (const char* f = getenv("NTP_GEMM_SPLIT")) forced = atoi(f);  // 1: never split; n > 1: n chunks if they fit
+  if (!g_workspace || forced == 1) return best;
+  // splitting has to beat the plain launch by a margin: the estimate is coarse
+  double best_t = plain_tile >= 0 ? 0.85 * tile_time(M, N, ktiles, layout, plain_tile, 1) : 1e300;
+  if (forced > 1) best_t = 1e300;
+  for (int i = 0; i < kNumTileShapes; ++i) {
+    if (!kSplitTile[i]) continue;
+    if (const char* f = getenv("NTP_GEMM_TILE")) {
+      char name[16];
+      variant_name(i, name, sizeof(name));
+      if (strcmp(f, name)) continue;
+    }
+    for (int sp = 2; sp <= kMaxSplits; ++sp) {
+      if (forced > 1 && sp != forced) continue;
+      const int64_t chunk_tiles = (ktiles + sp - 1) / sp;
+      if (forced <= 1 && chunk_tiles < kMinSplitTiles) break;
+      if ((sp - 1) * chunk_tiles * 64 >= K) continue;  // the last chunk would be empty
+      if (int64_t(sp) * M * ldw * 4 > g_workspace_bytes) break;
+      const double reduce = kReduceFixedCycles + double(M) * double(N) * (4.0 * sp + 4.0) / kReduceBytesPerCycle;
+      const double t = tile_time(M, N, ktiles, layout, i, sp) + reduce;
+      if (t < best_t) {
+        best_t = t;
+        best = SplitChoice{i, sp, int(chunk_tiles * 64)};
+      }
+    }
+  }
+  return best;
+}
+
+// Adds the partial-sum slices of a split-K launch and applies the GEMM's own epilogue.
+template <int EPI>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmArgs g, const float* __restrict__ ws, int64_t slice,
+                                                            int64_t ldw, int splits) {
+  const int quads = g.n_store >> 2;  // n_store is a multiple of 4
+  const int64_t idx = int64_t(blockIdx.x) * 256 + threadIdx.x;
+  const int64_t m = idx / quads;
+  if (m >= g.M) return;
+  const int n0 = int(idx - m * quads) * 4;
+  const float* p = ws + m * ldw + n0;
+  f32x4 acc = *reinterpret_cast<const f32x4*>(p);
+  for (int s = 1; s < splits; ++s) acc = acc + *reinterpret_cast<const f32x4*>(p + s * slice);
+  store4<EPI>(g, int(m), n0, acc);
+}
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 }  // namespace
 
 namespace ntp {
+
+void* workspace(int64_t* bytes) {
+  if (bytes) *bytes = g_workspace_bytes;
+  return g_workspace;
+}
 
 int gemm_launch(const GemmDesc& d, void* stream) {
   if (d.M < 0 || d.N < 0 || d.K < 0) return NTP_ERR_INVALID_ARG;
@@ -193,15 +273,45 @@ int gemm_launch(const GemmDesc& d, void* stream) {
   const int64_t a_rows = d.a_kc ? d.M : d.K, b_rows = d.b_kc ? d.N : d.K;
   const bool ring_ok = ring_combo(d.a_kc, d.b_kc, d.epilogue) && a_rows * d.lda * 2 < (int64_t(1) << 32) &&
                        b_rows * d.ldb * 2 < (int64_t(1) << 32);
-  const int variant = choose_variant(g, ring_ok, d.a_kc ? (d.b_kc ? 0 : 1) : 2);
+  const int layout = d.a_kc ? (d.b_kc ? 0 : 1) : 2;
+  int variant = choose_variant(g, ring_ok, layout);
+  // split-K: any (layout, epilogue) whose operands the ring kernel can address, except B K-contiguous
+  // with A K-strided (no ring kernel)
+  const bool split_ok = a_rows * d.lda * 2 < (int64_t(1) << 32) && b_rows * d.ldb * 2 < (int64_t(1) << 32) &&
+                        (d.a_kc || !d.b_kc) && int64_t(d.M) * d.N >= 128 * 128 * 64;
+  const int64_t ldw = (n_store + 15) / 16 * 16;
+  SplitChoice sc{variant, 1, 0};
+  if (split_ok) sc = choose_split(d.M, n_store, d.K, layout, variant, ldw);
+  if (sc.splits > 1) variant = sc.tile;
   if (ntp::timing_on()) {
-    char name[48], vn[16];
+    char name[48], vn[16], sn[8] = "";
     variant_name(variant, vn, sizeof(vn));
-    snprintf(name, sizeof(name), "gemm_%c%c_%s_%s", d.a_kc ? 'n' : 't', d.b_kc ? 't' : 'n', kEpiName[d.epilogue], vn);
+    if (sc.splits > 1) snprintf(sn, sizeof(sn), "k%d", sc.splits);
+    snprintf(name, sizeof(name), "gemm_%c%c_%s_%s%s", d.a_kc ? 'n' : 't', d.b_kc ? 't' : 'n', kEpiName[d.epilogue], vn, sn);
     ntp::timing_begin(stream, name, 2.0 * double(d.M) * double(d.N) * double(d.K), 0.0);
   }
   int st;
-  if (variant >= 0) {
+  if (sc.splits > 1) {
+    GemmArgs gp = g;  // the partial-sum launch: fp32 to the workspace, no row segments
+    gp.C = g_workspace;
+    gp.ldc = ldw;
+    gp.n_segs = 0;
+    gp.k_splits = sc.splits;
+    gp.k_chunk = sc.k_chunk;
+    gp.split_stride = int64_t(d.M) * ldw;
+    if (d.a_kc && d.b_kc) st = launch_ring_split_nt(gp, variant, s);
+    else if (d.a_kc) st = launch_ring_split_nn(gp, variant, s);
+    else st = launch_ring_split_tn(gp, variant, s);
+    if (st == NTP_OK) {
+      const int64_t threads = int64_t(d.M) * (n_store / 4);
+      const dim3 grid(uint32_t((threads + 255) / 256)), block(256);
+      const float* ws = static_cast<const float*>(g_workspace);
+      st = dispatch_epilogue(d.epilogue, [&](auto e) {
+        hipLaunchKernelGGL((splitk_reduce_kernel<decltype(e)::value>), grid, block, 0, s, g, ws, gp.split_stride, ldw, sc.splits);
+        return hipGetLastError() == hipSuccess ? NTP_OK : NTP_ERR_LAUNCH;
+      });
+    }
+  } else if (variant >= 0) {
     if (d.a_kc && d.b_kc) st = launch_ring_nt(g, d.epilogue, variant, s);
     else if (d.a_kc) st = launch_ring_nn(g, d.epilogue, variant, s);
     else st = launch_ring_tn(g, d.epilogue, variant, s);
@@ -214,3 +324,10 @@ int gemm_launch(const GemmDesc& d, void* stream) {
 }
 
 }  // namespace ntp
+
+extern "C" int ntp_set_workspace(void* workspace, int64_t bytes) {
+  if (bytes < 0 || (bytes > 0 && !workspace) || (reinterpret_cast<uintptr_t>(workspace) & 255)) return NTP_ERR_INVALID_ARG;
+  g_workspace = bytes > 0 ? workspace : nullptr;
+  g_workspace_bytes = bytes > 0 ? bytes : 0;
+  return NTP_OK;
+}

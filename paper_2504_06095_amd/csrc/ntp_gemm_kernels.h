@@ -37,6 +37,10 @@ struct GemmArgs {
     float* ptr;
     int64_t ld;
   } seg[kMaxRowSegs];
+  // split-K launches only: number of K chunks, chunk length (elements, a multiple of 64) and the
+  // distance in floats between the partial-sum slices that start at C
+  int32_t k_splits, k_chunk;
+  int64_t split_stride;
 };
 
 __device__ __forceinline__ float gelu_fwd(float x, int mode) {

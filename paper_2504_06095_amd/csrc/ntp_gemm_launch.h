@@ -29,6 +29,13 @@ constexpr int kNumTileShapes = int(sizeof(kTileShapes) / sizeof(kTileShapes[0]))
 int launch_ring_nt(GemmArgs g, int epilogue, int tile, hipStream_t s);  // A [M x K], B [N x K]
 int launch_ring_nn(GemmArgs g, int epilogue, int tile, hipStream_t s);  // A [M x K], B [K x N]
 int launch_ring_tn(GemmArgs g, int epilogue, int tile, hipStream_t s);  // A [K x M], B [K x N]
+// Split-K form (tile shapes with kSplitTile set): g.C is the fp32 workspace, g.ldc its row length,
+// g.k_splits / g.k_chunk / g.split_stride describe the chunks; partial sums only, no epilogue.
+int launch_ring_split_nt(GemmArgs g, int tile, hipStream_t s);
+int launch_ring_split_nn(GemmArgs g, int tile, hipStream_t s);
+int launch_ring_split_tn(GemmArgs g, int tile, hipStream_t s);
+// tile shapes that have a split-K instantiation
+constexpr bool kSplitTile[] = {true, false, false, true, true, true, true, false, false};
 
 template <bool AKC, bool BKC, int EPI, int BM_, int BN_, int WGM, int WGN>
 int launch_ring_one(GemmArgs g, hipStream_t s) {
@@ -42,6 +49,31 @@ int launch_ring_one(GemmArgs g, hipStream_t s) {
   const dim3 grid(nblk < kResident ? nblk : kResident), block(64 * WGM * WGN);
   hipLaunchKernelGGL((gemm_ring_kernel<AKC, BKC, EPI, BM_, BN_, WGM, WGN>), grid, block, 0, s, g);
   return hipGetLastError() == hipSuccess ? NTP_OK : NTP_ERR_LAUNCH;
+}
+
+template <bool AKC, bool BKC, int BM_, int BN_, int WGM, int WGN>
+int launch_ring_split_one(GemmArgs g, hipStream_t s) {
+  g.tiles_m = (g.M + BM_ - 1) / BM_;
+  g.tiles_n = (g.n_store + BN_ - 1) / BN_;
+  const int64_t per_split = (int64_t(g.tiles_m) * g.tiles_n + 7) / 8 * 8;
+  if (g.k_splits < 1 || g.k_chunk < 64 || g.k_chunk % 64 || int64_t(g.k_splits - 1) * g.k_chunk >= g.K ||
+      per_split * g.k_splits > 0x7fffffff)
+    return NTP_ERR_INVALID_ARG;
+  const dim3 grid(uint32_t(per_split * g.k_splits)), block(64 * WGM * WGN);
+  hipLaunchKernelGGL((gemm_ring_kernel<AKC, BKC, ntp::EPI_F32, BM_, BN_, WGM, WGN, true>), grid, block, 0, s, g);
+  return hipGetLastError() == hipSuccess ? NTP_OK : NTP_ERR_LAUNCH;
+}
+
+template <bool AKC, bool BKC>
+int launch_ring_split_tile(const GemmArgs& g, int tile, hipStream_t s) {
+  switch (tile) {
+    case 0: return launch_ring_split_one<AKC, BKC, 256, 256, 2, 4>(g, s);
+    case 3: return launch_ring_split_one<AKC, BKC, 256, 192, 4, 2>(g, s);
+    case 4: return launch_ring_split_one<AKC, BKC, 192, 256, 2, 4>(g, s);
+    case 5: return launch_ring_split_one<AKC, BKC, 256, 128, 4, 2>(g, s);
+    case 6: return launch_ring_split_one<AKC, BKC, 128, 256, 2, 4>(g, s);
+    default: return NTP_ERR_INVALID_ARG;
+  }
 }
 
 template <bool AKC, bool BKC, int EPI>
@@ -74,5 +106,12 @@ int launch_ring_tile(const GemmArgs& g, int tile, hipStream_t s) {
   template __global__ void gemm_ring_kernel<AKC, BKC, EPI, 128, 256, 2, 4>(const GemmArgs);        \
   template __global__ void gemm_ring_kernel<AKC, BKC, EPI, 128, 128, 2, 2>(const GemmArgs);        \
   template __global__ void gemm_ring_kernel<AKC, BKC, EPI, 128, 128, 2, 4>(const GemmArgs);
+
+#define NTP_RING_INSTANTIATE_SPLIT(AKC, BKC)                                                                   \
+  template __global__ void gemm_ring_kernel<AKC, BKC, ntp::EPI_F32, 256, 256, 2, 4, true>(const GemmArgs);     \
+  template __global__ void gemm_ring_kernel<AKC, BKC, ntp::EPI_F32, 256, 192, 4, 2, true>(const GemmArgs);     \
+  template __global__ void gemm_ring_kernel<AKC, BKC, ntp::EPI_F32, 192, 256, 2, 4, true>(const GemmArgs);     \
+  template __global__ void gemm_ring_kernel<AKC, BKC, ntp::EPI_F32, 256, 128, 4, 2, true>(const GemmArgs);     \
+  template __global__ void gemm_ring_kernel<AKC, BKC, ntp::EPI_F32, 128, 256, 2, 4, true>(const GemmArgs);
 
 #endif  // NTP_GEMM_LAUNCH_H_

@@ -6,6 +6,9 @@
 namespace ntp_gemm {
 
 NTP_RING_INSTANTIATE(true, false, ntp::EPI_BF16)
+NTP_RING_INSTANTIATE_SPLIT(true, false)
+
+int launch_ring_split_nn(GemmArgs g, int tile, hipStream_t s) { return launch_ring_split_tile<true, false>(g, tile, s); }
 
 int launch_ring_nn(GemmArgs g, int epilogue, int tile, hipStream_t s) {
   switch (epilogue) {

@@ -8,6 +8,9 @@ namespace ntp_gemm {
 NTP_RING_INSTANTIATE(true, true, ntp::EPI_BF16)
 NTP_RING_INSTANTIATE(true, true, ntp::EPI_GELU)
 NTP_RING_INSTANTIATE(true, true, ntp::EPI_DGELU)
+NTP_RING_INSTANTIATE_SPLIT(true, true)
+
+int launch_ring_split_nt(GemmArgs g, int tile, hipStream_t s) { return launch_ring_split_tile<true, true>(g, tile, s); }
 
 int launch_ring_nt(GemmArgs g, int epilogue, int tile, hipStream_t s) {
   switch (epilogue) {

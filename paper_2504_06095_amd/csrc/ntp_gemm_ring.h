@@ -174,8 +174,13 @@ struct FragAddr {
 template <int I>
 using Int = std::integral_constant<int, I>;
 
-template <bool AKC, bool BKC, int EPI, int BM_, int BN_, int WGM, int WGN>
+// SPLIT: the K axis is cut into g.k_splits chunks of g.k_chunk (a multiple of the K tile; the last
+// chunk takes what is left).  The grid holds k_splits groups of round_up(tiles, 8) workgroups; group
+// s computes every output tile over chunk s and stores the fp32 partial sums to slice s of a
+// workspace (g.C + s * g.split_stride floats, rows of g.ldc).  Nothing is persistent in this form.
+template <bool AKC, bool BKC, int EPI, int BM_, int BN_, int WGM, int WGN, bool SPLIT = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArgs g) {
+  static_assert(!SPLIT || EPI == ntp::EPI_F32, "partial sums are stored as fp32");
   constexpr int NW = WGM * WGN;
   constexpr int TM = BM_ / WGM, TN = BN_ / WGN;  // wavefront tile
   constexpr int MI = TM / 16, NI = TN / 16;      // 16 x 16 accumulator blocks
@@ -234,6 +239,18 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
     return p;
   };
   int vblk = blockIdx.x;
+  int split = 0;
+  if constexpr (SPLIT) {
+    const int per_split = (nblk + 7) & ~7;  // keeps (workgroup index & 7) == (tile index & 7)
+    split = blockIdx.x / per_split;
+    vblk = blockIdx.x - split * per_split;
+    if (vblk >= nblk) return;  // padding workgroup (the whole workgroup leaves, before any barrier)
+  }
+  // this workgroup's share of the K axis: everything below addresses the operands from opA / opB
+  const int64_t k_first = SPLIT ? int64_t(split) * g.k_chunk : 0;
+  const int K = SPLIT ? min(g.k_chunk, g.K - int(k_first)) : g.K;
+  const uint16_t* const opA = g.A + (AKC ? k_first : k_first * g.lda);
+  const uint16_t* const opB = g.B + (BKC ? k_first : k_first * g.ldb);
   TilePos pos = place(vblk);
   int row0 = pos.row0, col0 = pos.col0;
 
@@ -242,8 +259,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
   OpB b;
   const int64_t astep = AKC ? DK : DK * g.lda, bstep = BKC ? DK : DK * g.ldb;  // elements per K tile
   // buffer views of the operands for the DMA (the host checks that each operand spans < 4 GiB)
-  const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(g.A), 0, -1, 0x00020000);
-  const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(g.B), 0, -1, 0x00020000);
+  const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(opA), 0, -1, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(opB), 0, -1, 0x00020000);
   const uint32_t astep_b = uint32_t(astep) * 2, bstep_b = uint32_t(bstep) * 2;
   FragAddr<AKC, RA, MI> fra;
   FragAddr<BKC, RB, NI> frb;
@@ -253,7 +270,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
 #ifdef NTP_GEMM_CLOCK_PROBE
   const long long probe_c0 = clock64();
 #endif
-  const int nfull = g.K / DK;  // complete K tiles: all go through the ring
+  const int nfull = K / DK;  // complete K tiles: all go through the ring
 
   // L2 prefetch, PFD tiles ahead.  An A tile is shared by the workgroups of this XCD that have the
   // same tile_m (about four, with different tile_n), a B tile by those with the same tile_n (eight
@@ -270,7 +287,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
   const bool pf_is_a = wave < 4;
   const int pf_mask = pf_is_a ? 3 : 7;
   const bool pf_ok = pf_is_a ? (AKC || g.M >= 2) : (BKC || g.N >= 2);
-  const char* const pf_base = reinterpret_cast<const char*>(pf_is_a ? g.A : g.B);
+  const char* const pf_base = reinterpret_cast<const char*>(pf_is_a ? opA : opB);
   const int64_t pf_step = (pf_is_a ? astep : bstep) * 2;  // bytes per K tile
   int pf_turn = 0, pf_turn_next = -1;  // -1: there is no next output tile
   uint32_t pf_voff = 0, pf_voff_next = 0;
@@ -420,7 +437,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
   first_dma();
   while (true) {
     const int vnext = vblk + int(gridDim.x);
-    const bool more = vnext < nblk;
+    const bool more = !SPLIT && vnext < nblk;
     const TilePos npos = more ? place(vnext) : pos;
     if (more) pf_params(npos, pf_turn_next, pf_voff_next);
     else pf_turn_next = -1;
@@ -448,10 +465,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
     }
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // the clamped DMA instructions of the last tiles
     // K tail (K % 64 != 0) through registers with element masks, not overlapped
-    if (nfull * DK < g.K) {
+    if (nfull * DK < K) {
       __syncthreads();
-      a.tail(g.A, astep, nfull, g.K, r0, wave, lane);
-      b.tail(g.B, bstep, nfull, g.K, r1, wave, lane);
+      a.tail(opA, astep, nfull, K, r0, wave, lane);
+      b.tail(opB, bstep, nfull, K, r1, wave, lane);
       __syncthreads();
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks) {
@@ -487,7 +504,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
 #pragma unroll
       for (int j = 0; j < NI; ++j) {
         const int n0 = ecol0 + wn * TN + j * 16 + (lane >> 4) * 4;
-        store4<EPI>(g, m, n0, acc[i][j]);
+        if constexpr (SPLIT) {
+          if (m < g.M && n0 < g.n_store)
+            *reinterpret_cast<f32x4*>(static_cast<float*>(g.C) + int64_t(split) * g.split_stride + int64_t(m) * g.ldc + n0) = acc[i][j];
+        } else {
+          store4<EPI>(g, m, n0, acc[i][j]);
+        }
       }
     }
     if (!more) break;

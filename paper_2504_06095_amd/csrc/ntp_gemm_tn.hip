@@ -6,6 +6,9 @@ namespace ntp_gemm {
 
 NTP_RING_INSTANTIATE(false, false, ntp::EPI_F32)
 NTP_RING_INSTANTIATE(false, false, ntp::EPI_F32_ACCUM)
+NTP_RING_INSTANTIATE_SPLIT(false, false)
+
+int launch_ring_split_tn(GemmArgs g, int tile, hipStream_t s) { return launch_ring_split_tile<false, false>(g, tile, s); }
 
 int launch_ring_tn(GemmArgs g, int epilogue, int tile, hipStream_t s) {
   switch (epilogue) {

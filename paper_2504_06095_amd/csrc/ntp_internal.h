@@ -78,6 +78,9 @@ struct GemmDesc {
   int32_t n_segs;
 };
 
+// The workspace registered with ntp_set_workspace (NULL if none) and, through `bytes`, its size.
+void* workspace(int64_t* bytes);
+
 // Validates and enqueues one GEMM on `stream`.  Returns an NTP_* status.
 int gemm_launch(const GemmDesc& d, void* stream);
 

@@ -118,6 +118,72 @@ def test_attn_core_bwd_matches_oracle(n_q, n_kv, tp, rank, d, n_seq, S, causal):
     _bwd_case(n_q, n_kv, tp, rank, d, n_seq, S, causal)
 
 
+@pytest.fixture
+def workspace():
+    """A registered workspace full of NaN (partial sums must all be written before they are read), timing on."""
+    import torch
+    import paper_2504_06095_amd as N
+    ws = torch.full((32 << 20,), float("nan"), dtype=torch.float32, device="cuda")  # 128 MiB
+    N.ntp_set_workspace(ws)
+    N.ntp_kernel_timing_enable(1)
+    N.ntp_kernel_timing_read()
+    yield ws
+    N.ntp_kernel_timing_enable(0)
+    N.ntp_kernel_timing_read()
+    N.ntp_set_workspace(None)
+
+
+def _core_names():
+    import paper_2504_06095_amd as N
+    return [r["name"] for r in N.ntp_kernel_timing_read() if r["name"].startswith("attn_core")]
+
+
+@pytest.mark.parametrize("parts", [2, 5, 16])
+@pytest.mark.parametrize("causal", [False, True], ids=["full", "causal"])
+@pytest.mark.parametrize("n_q,n_kv,tp,rank,d,n_seq,S", [CASES[0], CASES[2], CASES[3], CASES[5], CASES[6]])
+def test_attn_core_bwd_cut_walks(workspace, monkeypatch, n_q, n_kv, tp, rank, d, n_seq, S, causal, parts):
+    """Each workgroup's walk cut into 2, 5 and 16 parts (more parts than tiles leaves some empty), fp32 partial
+    sums added by the second kernel."""
+    _say(f"attn core bwd cut into {parts}: n_q={n_q} n_kv={n_kv} tp={tp} rank={rank} d={d} n_seq={n_seq} S={S} causal={causal}")
+    monkeypatch.setenv("NTP_ATTN_PARTS", str(parts))
+    _bwd_case(n_q, n_kv, tp, rank, d, n_seq, S, causal)
+    names = _core_names()
+    assert "attn_core_bwd_dq_cut" in names and "attn_core_bwd_dkv_cut" in names, names
+
+
+@pytest.mark.parametrize("parts", [2, 5, 16])
+@pytest.mark.parametrize("causal", [False, True], ids=["full", "causal"])
+@pytest.mark.parametrize("n_q,n_kv,tp,rank,d,n_seq,S", [CASES[0], CASES[1], CASES[2], CASES[5], CASES[6]])
+def test_attn_core_fwd_cut_walks(workspace, monkeypatch, n_q, n_kv, tp, rank, d, n_seq, S, causal, parts):
+    """The forward walk over the key tiles cut into pieces that are merged by their running maxima and sums."""
+    _say(f"attn core fwd cut into {parts}: n_q={n_q} n_kv={n_kv} tp={tp} rank={rank} d={d} n_seq={n_seq} S={S} causal={causal}")
+    monkeypatch.setenv("NTP_ATTN_PARTS", str(parts))
+    _case(n_q, n_kv, tp, rank, d, n_seq, S, causal)
+    assert _core_names() == ["attn_core_fwd_causal_cut" if causal else "attn_core_fwd_cut"]
+
+
+def test_attn_core_fwd_cut_peaked_scores(workspace, monkeypatch):
+    """Large scores: the pieces' maxima differ by hundreds, so most pieces merge with weight zero."""
+    _say("attn core fwd cut: peaked scores")
+    monkeypatch.setenv("NTP_ATTN_PARTS", "7")
+    _case(8, 2, 3, 1, 128, 1, 700, False, seed=4, std=6.0)
+    _case(8, 2, 3, 1, 128, 1, 700, True, seed=4, std=6.0)
+
+
+def test_attn_core_bwd_cut_chosen_for_few_heads(workspace):
+    """No override: 3 heads of a 4096-token causal sequence are 192 (dQ) and 64 (dK, dV) workgroups with walks of
+    up to 64 and 192 tiles, so both are cut; without a workspace neither is."""
+    import paper_2504_06095_amd as N
+    _say("attn core bwd: cut chosen at the config-3 shape")
+    _bwd_case(64, 8, 30, 0, 128, 1, 4096, True, seed=5)
+    names = _core_names()
+    assert names == ["attn_core_fwd_causal_cut", "attn_core_bwd_dq_cut", "attn_core_bwd_dkv_cut"], names
+    N.ntp_set_workspace(None)
+    _bwd_case(64, 8, 30, 0, 128, 1, 1024, True, seed=5)
+    names = _core_names()
+    assert names == ["attn_core_fwd_causal", "attn_core_bwd_dq", "attn_core_bwd_dkv"], names
+
+
 def test_attn_core_bwd_padded_rows():
     _say("attn core bwd: padded leading dimensions")
     _bwd_case(8, 2, 3, 1, 128, 1, 300, True, seed=3, pad=8)

@@ -1,0 +1,116 @@
+"""Split-K form of the shard GEMMs (partial sums to a registered workspace, then a reduce kernel with the
+epilogue): every layout and epilogue against the oracle, with the K axis cut into 2..5 chunks including
+ragged last chunks, and the automatic choice on a skinny column-parallel shape.  On a real MI355X."""
+import sys
+
+import numpy as np
+import pytest
+
+from tests.helpers import TOL, AttnCase, MlpCase, rel_err
+
+pytestmark = pytest.mark.gpu
+MLP_NAMES = ["P", "Y", "Z", "dP", "dX", "dA_t", "dB"]
+ATTN_NAMES = ["QKV", "Z", "dC", "dX", "dWqkv", "dWo"]
+SPLIT_TILES = ["256x256", "256x192", "192x256", "256x128", "128x256"]
+
+
+def _say(msg):
+    print(f"[gpu-case] {msg}", file=sys.stderr, flush=True)
+
+
+def _check_all(got, want, names):
+    for k in names:
+        assert got[k].shape == want[k].shape, k
+        assert np.isfinite(got[k]).all(), f"{k}: non-finite output"
+        e = rel_err(got[k], want[k])
+        assert e <= TOL, f"{k}: rel err {e:.3e} > {TOL}"
+
+
+@pytest.fixture
+def workspace():
+    import torch
+    import paper_2504_06095_amd as N
+    ws = torch.full((96 << 20,), float("nan"), dtype=torch.float32, device="cuda")  # 384 MiB, poisoned
+    N.ntp_set_workspace(ws)
+    N.ntp_kernel_timing_enable(1)
+    N.ntp_kernel_timing_read()
+    yield ws
+    N.ntp_kernel_timing_enable(0)
+    N.ntp_kernel_timing_read()
+    N.ntp_set_workspace(None)
+
+
+def _gemm_names():
+    import paper_2504_06095_amd as N
+    return [r["name"] for r in N.ntp_kernel_timing_read() if r["name"].startswith("gemm_")]
+
+
+@pytest.mark.parametrize("splits", [2, 3, 5])
+@pytest.mark.parametrize("tile", SPLIT_TILES)
+def test_mlp_split_k_every_tile(workspace, monkeypatch, tile, splits):
+    # H = 1096 = 17 K tiles + 8, n_r = 1171 = 18 K tiles + 19: ragged last chunks in every layout; M = 1100
+    _say(f"mlp split-K tile {tile} splits {splits}")
+    monkeypatch.setenv("NTP_GEMM_TILE", tile)
+    monkeypatch.setenv("NTP_GEMM_SPLIT", str(splits))
+    case = MlpCase(1100, 1096, 8197, 7, 0)
+    assert case.n_r == 1171
+    got, raw = case.run_gpu(accumulate_twice=True)
+    names = _gemm_names()
+    assert len(names) == 10 and all(n.endswith(f"{tile}k{splits}") for n in names), names
+    want = case.oracle()
+    want["dA_t"], want["dB"] = 2 * want["dA_t"], 2 * want["dB"]
+    _check_all(got, want, MLP_NAMES)
+    for name in ("P", "Y", "dP"):
+        assert (raw[name][:, 1171:1176].float().cpu().numpy() == 0).all()
+
+
+@pytest.mark.parametrize("splits", [2, 4])
+def test_attn_proj_split_k(workspace, monkeypatch, splits):
+    _say(f"attention projections split-K splits {splits}")
+    monkeypatch.setenv("NTP_GEMM_SPLIT", str(splits))
+    case = AttnCase(2200, 1544, 32, 4, 64, 3, 1)  # w_qkv = 960, w_o = 704; K tails of 8, 24 and 0
+    got = case.run_gpu()
+    names = _gemm_names()
+    assert len(names) == 6 and all(n.endswith(f"k{splits}") for n in names), names
+    _check_all(got, case.oracle(), ATTN_NAMES)
+
+
+def test_split_k_chosen_for_skinny_shard_only(workspace):
+    """No override: a column-parallel shard with 48 output tiles of 256 x 256 and K = 8192 is split; one
+    with enough tiles to fill the GPU is not, and neither is anything without a workspace."""
+    import paper_2504_06095_amd as N
+    _say("split-K automatic choice")
+    skinny = MlpCase(4096, 8192, 640 * 3, 3, 0)
+    got, _ = skinny.run_gpu()
+    names = _gemm_names()
+    assert "k" in names[0].split("_")[-1], names  # X A_i: 4096 x 640 over K = 8192
+    _check_all(got, skinny.oracle(), MLP_NAMES)
+    wide = MlpCase(8192, 1024, 8192, 1, 0)
+    wide.run_gpu()
+    names = _gemm_names()
+    assert "k" not in names[0].split("_")[-1], names  # X A_i: 8192 x 8192, 1024 tiles
+    N.ntp_set_workspace(None)
+    skinny.run_gpu()
+    names = _gemm_names()
+    assert all("k" not in n.split("_")[-1] for n in names), names
+
+
+def test_split_k_skipped_when_workspace_too_small(monkeypatch):
+    import torch
+    import paper_2504_06095_amd as N
+    _say("split-K small workspace")
+    ws = torch.zeros(1 << 18, dtype=torch.float32, device="cuda")  # 1 MiB: no partial sums fit
+    N.ntp_set_workspace(ws)
+    N.ntp_kernel_timing_enable(1)
+    N.ntp_kernel_timing_read()
+    try:
+        monkeypatch.setenv("NTP_GEMM_SPLIT", "2")
+        case = MlpCase(1100, 1096, 8197, 7, 0)
+        got, _ = case.run_gpu()
+        names = _gemm_names()
+        assert all("k" not in n.split("_")[-1] for n in names), names
+        _check_all(got, case.oracle(), MLP_NAMES)
+    finally:
+        N.ntp_kernel_timing_enable(0)
+        N.ntp_kernel_timing_read()
+        N.ntp_set_workspace(None)

@@ -142,3 +142,13 @@ def test_layer_argument_errors_without_launch():
     assert lib.ntp_mlp_shard_fwd(None, *z, None) == Bd.NTP_ERR_INVALID_ARG
     ashape = Bd.AttnShape(4, 16, 12, 8)  # w_qkv not a multiple of 8
     assert lib.ntp_attn_proj_shard_fwd(C.byref(ashape), *z, None) == Bd.NTP_ERR_ALIGNMENT
+
+
+def test_set_workspace_checks_its_arguments():
+    """No device memory is touched by registering: only pointer alignment and size are checked."""
+    L = Bd.lib()
+    assert L.ntp_set_workspace(None, 0) == 0
+    assert L.ntp_set_workspace(None, 16) == Bd.NTP_ERR_INVALID_ARG
+    assert L.ntp_set_workspace(0x1010, 1 << 20) == Bd.NTP_ERR_INVALID_ARG  # not 256-byte aligned
+    assert L.ntp_set_workspace(0x1000, -1) == Bd.NTP_ERR_INVALID_ARG
+    assert L.ntp_set_workspace(None, 0) == 0
