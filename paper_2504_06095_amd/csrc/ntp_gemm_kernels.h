@@ -168,6 +168,58 @@ __device__ __forceinline__ void store4(const GemmArgs& g, int m, int n0, f32x4 a
   }
 }
 
+// bf16 epilogues of the ring kernel, two adjacent 16 x 16 accumulator blocks at once.  Lane l holds row
+// l % 16 and columns 4 (l / 16) + {0..3} of both blocks (a0: columns from nb, a1: from nb + 16), 8 bytes of
+// bf16 each.  After the element-wise part, the four 16-lane rows trade halves (v_permlane16_swap: odd rows
+// of the first register against even rows of the second), so that a lane ends up with 8 consecutive
+// columns, 16 bytes: rows 0 / 2 take columns 0-7 / 8-15 of the first block, rows 1 / 3 those of the second.
+// A store instruction then writes 64 contiguous bytes per output row instead of 32, and there are half as many.
+template <int EPI>
+__device__ __forceinline__ void store8_pair(const GemmArgs& g, int m, int nb, int lh, f32x4 a0, f32x4 a1) {
+  const int n0 = nb + lh * 4, n1 = n0 + 16;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    if (n0 + j >= g.N) a0[j] = 0.0f;
+    if (n1 + j >= g.N) a1[j] = 0.0f;
+  }
+  if constexpr (EPI == ntp::EPI_DGELU) {
+    u16x4 p0 = {0, 0, 0, 0}, p1 = {0, 0, 0, 0};
+    if (m < g.M && n0 < g.n_store) p0 = *reinterpret_cast<const u16x4*>(g.AUX + int64_t(m) * g.ldaux + n0);
+    if (m < g.M && n1 < g.n_store) p1 = *reinterpret_cast<const u16x4*>(g.AUX + int64_t(m) * g.ldaux + n1);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      a0[j] = (n0 + j < g.N) ? a0[j] * gelu_bwd(bf16_to_f32(p0[j]), g.gelu_mode) : 0.0f;
+      a1[j] = (n1 + j < g.N) ? a1[j] * gelu_bwd(bf16_to_f32(p1[j]), g.gelu_mode) : 0.0f;
+    }
+  }
+  auto pack = [](float lo, float hi) { return uint32_t(f32_to_bf16(lo)) | (uint32_t(f32_to_bf16(hi)) << 16); };
+  // the lane's 8 output columns after the trade, and the trade itself
+  const int c = nb + (lh & 1) * 16 + (lh >> 1) * 8;
+  auto trade_store = [&](void* base, int64_t ld, uint32_t x0, uint32_t x1, uint32_t y0, uint32_t y1) {
+    const auto r0 = __builtin_amdgcn_permlane16_swap(x0, y0, false, false);
+    const auto r1 = __builtin_amdgcn_permlane16_swap(x1, y1, false, false);
+    if (m >= g.M) return;
+    uint16_t* dst = static_cast<uint16_t*>(base) + int64_t(m) * ld + c;
+    if (c + 8 <= g.n_store) {
+      typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+      *reinterpret_cast<u32x4*>(dst) = u32x4{r0[0], r1[0], r0[1], r1[1]};
+    } else if (c + 4 <= g.n_store) {
+      typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+      *reinterpret_cast<u32x2*>(dst) = u32x2{r0[0], r1[0]};
+    }
+  };
+  trade_store(g.C, g.ldc, pack(a0[0], a0[1]), pack(a0[2], a0[3]), pack(a1[0], a1[1]), pack(a1[2], a1[3]));
+  if constexpr (EPI == ntp::EPI_GELU) {
+    float y0[4], y1[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      y0[j] = gelu_fwd(a0[j], g.gelu_mode);
+      y1[j] = gelu_fwd(a1[j], g.gelu_mode);
+    }
+    trade_store(g.C2, g.ldc2, pack(y0[0], y0[1]), pack(y0[2], y0[3]), pack(y1[0], y1[1]), pack(y1[2], y1[3]));
+  }
+}
+
 template <bool AKC, bool BKC, int EPI>
 __global__ __launch_bounds__(256) void gemm_generic_kernel(const GemmArgs g) {
   __shared__ __attribute__((aligned(16))) uint16_t sA[BM * LDS_LD];

@@ -432,7 +432,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
     }
   };
   // vector memory instructions a wavefront issues in the epilogue of an interior tile
-  constexpr int NEPI = MI * NI * ((EPI == ntp::EPI_BF16 || EPI == ntp::EPI_F32) ? 1 : 2);
+  // (bf16 outputs go out two blocks at a time, see store8_pair; an odd last block goes alone)
+  constexpr bool PAIRED = !SPLIT && (EPI == ntp::EPI_BF16 || EPI == ntp::EPI_GELU || EPI == ntp::EPI_DGELU);
+  constexpr int NPAIR = NI / 2, NODD = NI & 1;
+  constexpr int NEPI = EPI == ntp::EPI_BF16    ? MI * (NPAIR + NODD)
+                       : EPI == ntp::EPI_GELU  ? MI * 2 * (NPAIR + NODD)
+                       : EPI == ntp::EPI_DGELU ? MI * (3 * NPAIR + 2 * NODD)
+                       : EPI == ntp::EPI_F32   ? MI * NI
+                                               : MI * NI * 2;
   bool stores_in_flight = false;
   first_dma();
   while (true) {
@@ -501,8 +508,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
       const int m = erow0 + wm * TM + i * 16 + (lane & 15);
+      if constexpr (PAIRED) {
 #pragma unroll
-      for (int j = 0; j < NI; ++j) {
+        for (int j = 0; j + 1 < NI; j += 2) store8_pair<EPI>(g, m, ecol0 + wn * TN + j * 16, lane >> 4, acc[i][j], acc[i][j + 1]);
+      }
+#pragma unroll
+      for (int j = PAIRED ? NI - NODD : 0; j < NI; ++j) {
         const int n0 = ecol0 + wn * TN + j * 16 + (lane >> 4) * 4;
         if constexpr (SPLIT) {
           if (m < g.M && n0 < g.n_store)
