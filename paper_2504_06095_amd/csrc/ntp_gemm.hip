@@ -54,7 +54,7 @@ int launch_generic(GemmArgs g, int epi, hipStream_t s) {
 //                                             256x256 256x224 224x256 256x192 192x256 256x128 128x256 128x128 128x128w8
 constexpr double kTileRate[3][kNumTileShapes] = {{1.000, 0.957, 0.969, 0.917, 0.923, 0.761, 0.754, 0.65, 0.53},   // A, B K-contiguous
                                                  {1.000, 0.929, 0.986, 0.908, 0.944, 0.770, 0.749, 0.65, 0.53},   // B K-strided
-                                                 {0.923, 0.984, 1.000, 0.956, 0.962, 0.797, 0.779, 0.65, 0.53}};  // both K-strided
+                                                 {1.100, 0.984, 1.000, 0.956, 0.962, 0.797, 0.779, 0.65, 0.53}};  // both K-strided (256x256: its non-persistent form)
 constexpr double kLoneSmallTileRate = 0.43;
 constexpr int kComputeUnits = 256;
 
@@ -292,7 +292,15 @@ int gemm_launch(const GemmDesc& d, void* stream) {
     ntp::timing_begin(stream, name, 2.0 * double(d.M) * double(d.N) * double(d.K), 0.0);
   }
   int st;
-  if (sc.splits > 1) {
+  if (layout == 2 && variant == 0 && sc.splits == 1 && ring_ok) {
+    // The 256 x 256 weight-gradient tile runs one workgroup per output tile: its persistent form is short of
+    // registers (27 spilled, some inside the K loop) and measured 17 % slower (307 against 254 us at
+    // 5376 x 12288 x 2048), more than the overlap of one tile's stores with the next tile's first loads gains.
+    GemmArgs gp = g;
+    gp.k_splits = 1;
+    gp.k_chunk = int32_t((d.K + 63) / 64 * 64);
+    st = launch_ring_split_tn(gp, d.epilogue, variant, s);
+  } else if (sc.splits > 1) {
     GemmArgs gp = g;  // the partial-sum launch: fp32 to the workspace, no row segments
     gp.C = g_workspace;
     gp.ldc = ldw;
@@ -302,7 +310,7 @@ int gemm_launch(const GemmDesc& d, void* stream) {
     gp.split_stride = int64_t(d.M) * ldw;
     if (d.a_kc && d.b_kc) st = launch_ring_split_nt(gp, variant, s);
     else if (d.a_kc) st = launch_ring_split_nn(gp, variant, s);
-    else st = launch_ring_split_tn(gp, variant, s);
+    else st = launch_ring_split_tn(gp, EPI_F32, variant, s);
     if (st == NTP_OK) {
       const int64_t threads = int64_t(d.M) * (n_store / 4);
       const dim3 grid(uint32_t((threads + 255) / 256)), block(256);

@@ -29,13 +29,15 @@ constexpr int kNumTileShapes = int(sizeof(kTileShapes) / sizeof(kTileShapes[0]))
 int launch_ring_nt(GemmArgs g, int epilogue, int tile, hipStream_t s);  // A [M x K], B [N x K]
 int launch_ring_nn(GemmArgs g, int epilogue, int tile, hipStream_t s);  // A [M x K], B [K x N]
 int launch_ring_tn(GemmArgs g, int epilogue, int tile, hipStream_t s);  // A [K x M], B [K x N]
-// Split-K form (tile shapes with kSplitTile set): g.C is the fp32 workspace, g.ldc its row length,
-// g.k_splits / g.k_chunk / g.split_stride describe the chunks; partial sums only, no epilogue.
+// Non-persistent form (tile shapes with kSplitTile set).  g.k_splits > 1: split-K, g.C is the fp32
+// workspace, g.ldc its row length, g.k_chunk / g.split_stride describe the chunks; partial sums only, no
+// epilogue.  g.k_splits == 1 (weight-gradient layout only): the whole GEMM with its fp32 epilogue; the
+// accumulating epilogue exists for the 256 x 256 tile only.
 int launch_ring_split_nt(GemmArgs g, int tile, hipStream_t s);
 int launch_ring_split_nn(GemmArgs g, int tile, hipStream_t s);
-int launch_ring_split_tn(GemmArgs g, int tile, hipStream_t s);
+int launch_ring_split_tn(GemmArgs g, int epilogue, int tile, hipStream_t s);
 // tile shapes that have a split-K instantiation
-constexpr bool kSplitTile[] = {true, false, false, true, true, true, true, false, false};
+constexpr bool kSplitTile[] = {true, true, true, true, true, true, true, false, false};
 
 template <bool AKC, bool BKC, int EPI, int BM_, int BN_, int WGM, int WGN>
 int launch_ring_one(GemmArgs g, hipStream_t s) {
@@ -51,7 +53,7 @@ int launch_ring_one(GemmArgs g, hipStream_t s) {
   return hipGetLastError() == hipSuccess ? NTP_OK : NTP_ERR_LAUNCH;
 }
 
-template <bool AKC, bool BKC, int BM_, int BN_, int WGM, int WGN>
+template <bool AKC, bool BKC, int BM_, int BN_, int WGM, int WGN, int EPI = ntp::EPI_F32>
 int launch_ring_split_one(GemmArgs g, hipStream_t s) {
   g.tiles_m = (g.M + BM_ - 1) / BM_;
   g.tiles_n = (g.n_store + BN_ - 1) / BN_;
@@ -60,7 +62,7 @@ int launch_ring_split_one(GemmArgs g, hipStream_t s) {
       per_split * g.k_splits > 0x7fffffff)
     return NTP_ERR_INVALID_ARG;
   const dim3 grid(uint32_t(per_split * g.k_splits)), block(64 * WGM * WGN);
-  hipLaunchKernelGGL((gemm_ring_kernel<AKC, BKC, ntp::EPI_F32, BM_, BN_, WGM, WGN, true>), grid, block, 0, s, g);
+  hipLaunchKernelGGL((gemm_ring_kernel<AKC, BKC, EPI, BM_, BN_, WGM, WGN, true>), grid, block, 0, s, g);
   return hipGetLastError() == hipSuccess ? NTP_OK : NTP_ERR_LAUNCH;
 }
 
@@ -68,6 +70,8 @@ template <bool AKC, bool BKC>
 int launch_ring_split_tile(const GemmArgs& g, int tile, hipStream_t s) {
   switch (tile) {
     case 0: return launch_ring_split_one<AKC, BKC, 256, 256, 2, 4>(g, s);
+    case 1: return launch_ring_split_one<AKC, BKC, 256, 224, 4, 2>(g, s);
+    case 2: return launch_ring_split_one<AKC, BKC, 224, 256, 2, 4>(g, s);
     case 3: return launch_ring_split_one<AKC, BKC, 256, 192, 4, 2>(g, s);
     case 4: return launch_ring_split_one<AKC, BKC, 192, 256, 2, 4>(g, s);
     case 5: return launch_ring_split_one<AKC, BKC, 256, 128, 4, 2>(g, s);
@@ -109,6 +113,8 @@ int launch_ring_tile(const GemmArgs& g, int tile, hipStream_t s) {
 
 #define NTP_RING_INSTANTIATE_SPLIT(AKC, BKC)                                                                   \
   template __global__ void gemm_ring_kernel<AKC, BKC, ntp::EPI_F32, 256, 256, 2, 4, true>(const GemmArgs);     \
+  template __global__ void gemm_ring_kernel<AKC, BKC, ntp::EPI_F32, 256, 224, 4, 2, true>(const GemmArgs);     \
+  template __global__ void gemm_ring_kernel<AKC, BKC, ntp::EPI_F32, 224, 256, 2, 4, true>(const GemmArgs);     \
   template __global__ void gemm_ring_kernel<AKC, BKC, ntp::EPI_F32, 256, 192, 4, 2, true>(const GemmArgs);     \
   template __global__ void gemm_ring_kernel<AKC, BKC, ntp::EPI_F32, 192, 256, 2, 4, true>(const GemmArgs);     \
   template __global__ void gemm_ring_kernel<AKC, BKC, ntp::EPI_F32, 256, 128, 4, 2, true>(const GemmArgs);     \

@@ -174,13 +174,15 @@ struct FragAddr {
 template <int I>
 using Int = std::integral_constant<int, I>;
 
-// SPLIT: the K axis is cut into g.k_splits chunks of g.k_chunk (a multiple of the K tile; the last
-// chunk takes what is left).  The grid holds k_splits groups of round_up(tiles, 8) workgroups; group
-// s computes every output tile over chunk s and stores the fp32 partial sums to slice s of a
-// workspace (g.C + s * g.split_stride floats, rows of g.ldc).  Nothing is persistent in this form.
+// SPLIT: the non-persistent form, one workgroup per unit of work.  The K axis is cut into g.k_splits
+// chunks of g.k_chunk (a multiple of the K tile; the last chunk takes what is left).  The grid holds
+// k_splits groups of round_up(tiles, 8) workgroups; group s computes every output tile over chunk s.
+// With several chunks the fp32 partial sums go to slice s of a workspace (g.C + s * g.split_stride
+// floats, rows of g.ldc); with one chunk the tile gets its normal epilogue.  Without the cross-tile state
+// of the persistent loop this form needs about 30 registers less.
 template <bool AKC, bool BKC, int EPI, int BM_, int BN_, int WGM, int WGN, bool SPLIT = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArgs g) {
-  static_assert(!SPLIT || EPI == ntp::EPI_F32, "partial sums are stored as fp32");
+  static_assert(!SPLIT || EPI == ntp::EPI_F32 || EPI == ntp::EPI_F32_ACCUM, "partial sums are stored as fp32");
   constexpr int NW = WGM * WGN;
   constexpr int TM = BM_ / WGM, TN = BN_ / WGN;  // wavefront tile
   constexpr int MI = TM / 16, NI = TN / 16;      // 16 x 16 accumulator blocks
@@ -516,8 +518,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
       for (int j = PAIRED ? NI - NODD : 0; j < NI; ++j) {
         const int n0 = ecol0 + wn * TN + j * 16 + (lane >> 4) * 4;
         if constexpr (SPLIT) {
-          if (m < g.M && n0 < g.n_store)
-            *reinterpret_cast<f32x4*>(static_cast<float*>(g.C) + int64_t(split) * g.split_stride + int64_t(m) * g.ldc + n0) = acc[i][j];
+          if (g.k_splits > 1) {
+            if (m < g.M && n0 < g.n_store)
+              *reinterpret_cast<f32x4*>(static_cast<float*>(g.C) + int64_t(split) * g.split_stride + int64_t(m) * g.ldc + n0) = acc[i][j];
+          } else {
+            store4<EPI>(g, m, n0, acc[i][j]);
+          }
         } else {
           store4<EPI>(g, m, n0, acc[i][j]);
         }

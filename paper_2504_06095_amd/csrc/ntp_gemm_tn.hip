@@ -8,7 +8,14 @@ NTP_RING_INSTANTIATE(false, false, ntp::EPI_F32)
 NTP_RING_INSTANTIATE(false, false, ntp::EPI_F32_ACCUM)
 NTP_RING_INSTANTIATE_SPLIT(false, false)
 
-int launch_ring_split_tn(GemmArgs g, int tile, hipStream_t s) { return launch_ring_split_tile<false, false>(g, tile, s); }
+template __global__ void gemm_ring_kernel<false, false, ntp::EPI_F32_ACCUM, 256, 256, 2, 4, true>(const GemmArgs);
+
+int launch_ring_split_tn(GemmArgs g, int epilogue, int tile, hipStream_t s) {
+  if (epilogue == ntp::EPI_F32) return launch_ring_split_tile<false, false>(g, tile, s);
+  if (epilogue == ntp::EPI_F32_ACCUM && tile == 0 && g.k_splits == 1)
+    return launch_ring_split_one<false, false, 256, 256, 2, 4, ntp::EPI_F32_ACCUM>(g, s);
+  return NTP_ERR_UNSUPPORTED;
+}
 
 int launch_ring_tn(GemmArgs g, int epilogue, int tile, hipStream_t s) {
   switch (epilogue) {
