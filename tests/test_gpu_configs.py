@@ -1,5 +1,6 @@
-"""Parity at the full sizes of the five benchmark configurations, in the launch configuration
-bench.py times (automatic tile choice), on a real MI355X.
+"""Parity at the full sizes of the five benchmark configurations, in the launch configurations
+bench.py times (automatic tile choice; with the 1 GiB split-K workspace it registers by default, and
+without one), on a real MI355X.
 
 Configs 1-4 compare every output element with the float64 oracle (numpy matmul finishes each
 in seconds).  Config 5 (20 GB of gradients) checks the round trip bit-for-bit on the device and
@@ -33,13 +34,24 @@ def _check(got, want, names):
 MLP_NAMES = ["P", "Y", "Z", "dP", "dX", "dA_t", "dB"]
 
 
+@pytest.fixture(params=["no workspace", "1 GiB workspace"])
+def launch_config(request):
+    """bench.py's two launch configurations: nothing registered, or 1 GiB for split-K partial sums."""
+    import torch
+    import paper_2504_06095_amd as N
+    if request.param == "1 GiB workspace":
+        N.ntp_set_workspace(torch.full((256 << 20,), float("nan"), dtype=torch.float32, device="cuda"))
+    yield request.param
+    N.ntp_set_workspace(None)
+
+
 @pytest.mark.parametrize("w,tp,rank,n_r", [
     (I.C1_MLP, 7, 0, 586),
     (I.C2_MLP, 7, 0, 7022), (I.C2_MLP, 7, 6, 7021), (I.C2_MLP, 8, 0, 6144),
     (I.C4_MLP, 71, 0, 750), (I.C4_MLP, 71, 70, 749), (I.C4_MLP, 72, 0, 740),
 ])
-def test_mlp_config_full_size(w, tp, rank, n_r):
-    _say(f"{w.name} tp={tp} rank={rank} n_r={n_r}")
+def test_mlp_config_full_size(launch_config, w, tp, rank, n_r):
+    _say(f"{w.name} tp={tp} rank={rank} n_r={n_r}, {launch_config}")
     case = MlpCase(w.M, w.H, w.n, tp, rank, tag=w.name)
     assert case.n_r == n_r
     got, _ = case.run_gpu()
@@ -47,9 +59,9 @@ def test_mlp_config_full_size(w, tp, rank, n_r):
 
 
 @pytest.mark.parametrize("tp,rank,w_qkv,w_o", [(30, 0, 640, 384), (30, 2, 896, 384), (30, 4, 512, 256), (32, 0, 512, 256)])
-def test_attn_config_full_size(tp, rank, w_qkv, w_o):
+def test_attn_config_full_size(launch_config, tp, rank, w_qkv, w_o):
     w = I.C3_ATTN
-    _say(f"{w.name} tp={tp} rank={rank}")
+    _say(f"{w.name} tp={tp} rank={rank}, {launch_config}")
     case = AttnCase(w.M, w.H, w.n_q, w.n_kv, w.d, tp, rank, tag=w.name)
     assert (case.w_qkv, case.w_o) == (w_qkv, w_o)
     _check(case.run_gpu(), case.oracle(), ["QKV", "Z", "dC", "dX", "dWqkv", "dWo"])
