@@ -391,6 +391,23 @@ int ntp_kernel_timing_read(ntp_kernel_time_t* out, int64_t max_records, int64_t*
  * Errors: NTP_ERR_INVALID_ARG (misaligned, negative size, NULL with bytes > 0). */
 int ntp_set_workspace(void* workspace, int64_t bytes);
 
+/* Diagnostic aid (host only, touches no device memory): which GEMM kernel a shard GEMM
+ * of this shape would run, with the workspace registered at the time of the call and
+ * tightly packed operands.  layout: 0 both operands K-contiguous (column-parallel
+ * forward, activation gradients of row-parallel layers), 1 A K-contiguous and B
+ * K-strided (row-parallel forward, partial input gradients), 2 both K-strided (weight
+ * gradients).  M, N >= 1, K >= 0.
+ *   tile_m, tile_n  output tile of a workgroup
+ *   wavefronts      wavefronts per workgroup
+ *   ring            1: the LDS-ring kernel; 0: the small generic kernel
+ *   k_splits        > 1: split-K with that many chunks, followed by the reduce kernel
+ *   persistent      1: one workgroup per compute unit walks over the tiles
+ * Errors: NTP_ERR_INVALID_ARG. */
+typedef struct ntp_gemm_choice {
+  int32_t tile_m, tile_n, wavefronts, ring, k_splits, persistent;
+} ntp_gemm_choice_t;
+int ntp_gemm_choice(int32_t layout, int64_t M, int64_t N, int64_t K, ntp_gemm_choice_t* out);
+
 /* Measurement aid: a plain dense device-to-device copy of `bytes` bytes (dst, src:
  * device, 16-byte aligned, bytes % 16 == 0, not overlapping) by a kernel named
  * calibration_copy_kernel.  Its known traffic (bytes read, bytes written) is what

@@ -29,8 +29,12 @@ EXPORTS = (
     "ntp_comp_sync_plan", "ntp_reshard_plan_create", "ntp_reshard_plan_segments", "ntp_reshard_plan_splits",
     "ntp_reshard_plan_table", "ntp_reshard_plan_run", "ntp_reshard_plan_destroy", "ntp_reshard_row_segments",
     "ntp_mlp_shard_bwd_resharded", "ntp_attn_proj_shard_bwd_resharded", "ntp_attn_core_shard_fwd", "ntp_attn_core_shard_bwd",
-    "ntp_set_workspace",
+    "ntp_set_workspace", "ntp_gemm_choice",
 )
+
+
+class GemmChoice(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("tile_m", "tile_n", "wavefronts", "ring", "k_splits", "persistent")]
 
 
 class NtpError(RuntimeError):
@@ -126,6 +130,7 @@ def lib() -> C.CDLL:
         L.ntp_kernel_timing_read.argtypes = [C.POINTER(KernelTime), i64, C.POINTER(i64)]
         L.ntp_calibration_copy.argtypes = [vp, vp, i64, vp]
         L.ntp_set_workspace.argtypes = [vp, i64]
+        L.ntp_gemm_choice.argtypes = [C.c_int32, i64, i64, i64, C.POINTER(GemmChoice)]
         for name in EXPORTS:
             getattr(L, name)  # AttributeError if a declared symbol is not exported
         _lib = L
@@ -454,3 +459,10 @@ def ntp_set_workspace(workspace) -> None:
         raise ValueError("expected a contiguous tensor")
     _check(lib().ntp_set_workspace(workspace.data_ptr(), workspace.numel() * workspace.element_size()), "ntp_set_workspace")
     _workspace = workspace
+
+
+def ntp_gemm_choice(layout: int, M: int, N: int, K: int) -> dict:
+    """Kernel variant a shard GEMM of this shape would run (host only); layout 0 nt, 1 nn, 2 tn."""
+    out = GemmChoice()
+    _check(lib().ntp_gemm_choice(layout, M, N, K, C.byref(out)), "ntp_gemm_choice")
+    return {n: getattr(out, n) for n, _ in GemmChoice._fields_}

@@ -186,6 +186,13 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmArgs g, co
   store4<EPI>(g, int(m), n0, acc);
 }
 
+// Kernel variant (-1 generic, else a tile shape) and K chunks for a GEMM (g: M, N, K, n_store).
+SplitChoice plan_gemm(const GemmArgs& g, int layout, bool ring_ok, bool split_ok, int64_t ldw) {
+  SplitChoice sc{choose_variant(g, ring_ok, layout), 1, 0};
+  if (split_ok && int64_t(g.M) * g.N >= 128 * 128 * 8) sc = choose_split(g.M, g.n_store, g.K, layout, sc.tile, ldw);
+  return sc;
+}
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 }  // namespace
@@ -275,15 +282,12 @@ int gemm_launch(const GemmDesc& d, void* stream) {
   const bool ring_ok = ring_combo(d.a_kc, d.b_kc, d.epilogue) && a_rows * d.lda * 2 < (int64_t(1) << 32) &&
                        b_rows * d.ldb * 2 < (int64_t(1) << 32);
   const int layout = d.a_kc ? (d.b_kc ? 0 : 1) : 2;
-  int variant = choose_variant(g, ring_ok, layout);
   // split-K: any (layout, epilogue) whose operands the ring kernel can address, except B K-contiguous
   // with A K-strided (no ring kernel)
-  const bool split_ok = a_rows * d.lda * 2 < (int64_t(1) << 32) && b_rows * d.ldb * 2 < (int64_t(1) << 32) &&
-                        (d.a_kc || !d.b_kc) && int64_t(d.M) * d.N >= 128 * 128 * 8;
+  const bool split_ok = a_rows * d.lda * 2 < (int64_t(1) << 32) && b_rows * d.ldb * 2 < (int64_t(1) << 32) && (d.a_kc || !d.b_kc);
   const int64_t ldw = (n_store + 15) / 16 * 16;
-  SplitChoice sc{variant, 1, 0};
-  if (split_ok) sc = choose_split(d.M, n_store, d.K, layout, variant, ldw);
-  if (sc.splits > 1) variant = sc.tile;
+  const SplitChoice sc = plan_gemm(g, layout, ring_ok, split_ok, ldw);
+  const int variant = sc.tile;
   if (ntp::timing_on()) {
     char name[48], vn[16], sn[8] = "";
     variant_name(variant, vn, sizeof(vn));
@@ -333,6 +337,31 @@ int gemm_launch(const GemmDesc& d, void* stream) {
 }
 
 }  // namespace ntp
+
+extern "C" int ntp_gemm_choice(int32_t layout, int64_t M, int64_t N, int64_t K, ntp_gemm_choice_t* out) {
+  if (!out || layout < 0 || layout > 2 || M < 1 || N < 1 || K < 0 || M > 0x7fffff00 || N > 0x7fffff00 || K > 0x7fffff00)
+    return NTP_ERR_INVALID_ARG;
+  GemmArgs g{};
+  g.M = int32_t(M);
+  g.N = int32_t(N);
+  g.K = int32_t(K);
+  g.n_store = int32_t((N + 7) / 8 * 8);
+  const SplitChoice sc = plan_gemm(g, layout, true, true, (g.n_store + 15) / 16 * 16);
+  *out = ntp_gemm_choice_t{};
+  out->k_splits = sc.splits;
+  if (sc.tile < 0) {
+    out->tile_m = out->tile_n = 128;
+    out->wavefronts = 4;
+    out->ring = 0;
+  } else {
+    out->tile_m = kTileShapes[sc.tile].bm;
+    out->tile_n = kTileShapes[sc.tile].bn;
+    out->wavefronts = kTileShapes[sc.tile].waves;
+    out->ring = 1;
+  }
+  out->persistent = sc.tile >= 0 && sc.splits == 1 && !(layout == 2 && sc.tile == 0) ? 1 : 0;
+  return NTP_OK;
+}
 
 extern "C" int ntp_set_workspace(void* workspace, int64_t bytes) {
   if (bytes < 0 || (bytes > 0 && !workspace) || (reinterpret_cast<uintptr_t>(workspace) & 255)) return NTP_ERR_INVALID_ARG;
