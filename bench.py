@@ -367,6 +367,17 @@ def config_table(torch, N, iters=10):
     e = lambda r, c, dt=torch.bfloat16: torch.empty(r, c, dtype=dt, device=dev)
     rows = []
 
+    def graphed(fwd, bwd):
+        """ms of fwd + bwd replayed as one captured graph (what a launch-bound small layer gains from capture)."""
+        side, graph = torch.cuda.Stream(), torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            fwd(); bwd()
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                fwd(); bwd()
+        torch.cuda.synchronize()
+        return timed(torch, graph.replay, iters)
+
     def mlp(tag, Mt, Hd, ffn, tp, rank):
         n_r = N.ntp_shard_plan(ffn, tp, rank)[1]
         ld = (n_r + 63) // 64 * 64
@@ -382,7 +393,8 @@ def config_table(torch, N, iters=10):
         tf, tb = timed(torch, fwd, iters), timed(torch, bwd, iters)
         fl = 4.0 * Mt * Hd * n_r
         rows.append(dict(config=tag, call="mlp shard", tokens=Mt, hidden=Hd, width=n_r, fwd_ms=tf, fwd_TFLOPs=fl / tf / 1e9,
-                         bwd_ms=tb, bwd_TFLOPs=2 * fl / tb / 1e9, fwd_bwd_frac_of_peak=3 * fl / (tf + tb) / 1e9 / BF16_MFMA_PEAK_TFLOPS))
+                         bwd_ms=tb, bwd_TFLOPs=2 * fl / tb / 1e9, fwd_bwd_frac_of_peak=3 * fl / (tf + tb) / 1e9 / BF16_MFMA_PEAK_TFLOPS,
+                         graph_fwd_bwd_ms=graphed(fwd, bwd)))
 
     def attn(tag, Mt, Hd, n_q, n_kv, d, tp, rank):
         plan = N.ntp_attn_shard_plan(n_q, n_kv, d, tp, rank)
@@ -410,7 +422,8 @@ def config_table(torch, N, iters=10):
         core = 2.0 * Mt * Mt * d * q  # causal: half of 4 S^2 d per head
         rows.append(dict(config=tag, call="attention shard (projections + causal core)", tokens=Mt, hidden=Hd, heads=q, w_qkv=wq,
                          fwd_ms=tf, fwd_TFLOPs=(proj + core) / tf / 1e9, bwd_ms=tb, bwd_TFLOPs=(2 * proj + 2.5 * core) / tb / 1e9,
-                         fwd_bwd_frac_of_peak=(3 * proj + 3.5 * core) / (tf + tb) / 1e9 / BF16_MFMA_PEAK_TFLOPS))
+                         fwd_bwd_frac_of_peak=(3 * proj + 3.5 * core) / (tf + tb) / 1e9 / BF16_MFMA_PEAK_TFLOPS,
+                         graph_fwd_bwd_ms=graphed(fwd, bwd)))
 
     mlp("c1", 512, 1024, 4096, 7, 0)
     mlp("c2", 2048, 12288, 49152, 7, 0)
