@@ -72,8 +72,12 @@ __global__ __launch_bounds__(kThreads, QB == 1 ? 3 : 2) void attn_core_fwd_kerne
   constexpr int CPR = D / 8;        // 16-byte chunks per tile row
   constexpr int NLD = kBKV * CPR / kThreads;  // chunks per thread and tile
   static_assert(D % 32 == 0 && (kBKV * CPR) % kThreads == 0, "tile copy: whole chunks per thread");
-  __shared__ __attribute__((aligned(16))) uint16_t sK[kBKV * LDT];
-  __shared__ __attribute__((aligned(16))) uint16_t sV[kBKV * LDV];
+  // The 32-row variant (two workgroups per CU) double-buffers the key / value tiles: the next tile is
+  // written to the other buffer while this one is multiplied, one barrier per tile.  The 16-row variant
+  // keeps one buffer (a second one would cost it the third workgroup per CU) and two barriers.
+  constexpr int NBUF = QB == 2 ? 2 : 1;
+  __shared__ __attribute__((aligned(16))) uint16_t sKb[NBUF][kBKV * LDT];
+  __shared__ __attribute__((aligned(16))) uint16_t sVb[NBUF][kBKV * LDV];
 
   // workgroup -> (head, sequence, query tile); consecutive workgroups share a head's keys and values.
   // With the causal mask the late tiles have the most keys: they go first.
@@ -131,12 +135,12 @@ __global__ __launch_bounds__(kThreads, QB == 1 ? 3 : 2) void attn_core_fwd_kerne
       rv[i] = *reinterpret_cast<const ntp_gemm::u16x8*>(Vp + off);
     }
   };
-  auto store_tile = [&]() {
+  auto store_tile = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
       const int c = threadIdx.x + i * kThreads;
-      *reinterpret_cast<ntp_gemm::u16x8*>(sK + (c / CPR) * LDT + (c % CPR) * 8) = rk[i];
-      *reinterpret_cast<ntp_gemm::u16x8*>(sV + (c / CPR) * LDV + (c % CPR) * 8) = rv[i];
+      *reinterpret_cast<ntp_gemm::u16x8*>(sKb[buf] + (c / CPR) * LDT + (c % CPR) * 8) = rk[i];
+      *reinterpret_cast<ntp_gemm::u16x8*>(sVb[buf] + (c / CPR) * LDV + (c % CPR) * 8) = rv[i];
     }
   };
 
@@ -144,13 +148,37 @@ __global__ __launch_bounds__(kThreads, QB == 1 ? 3 : 2) void attn_core_fwd_kerne
   const int t_lo = a.n_parts > 1 ? int(int64_t(piece) * n_tiles / a.n_parts) : 0;
   const int t_hi = a.n_parts > 1 ? int(int64_t(piece + 1) * n_tiles / a.n_parts) : n_tiles;
   if (t_lo < t_hi) load_tile(t_lo);
+  if constexpr (NBUF == 2) {
+    if (t_lo < t_hi) store_tile(0);
+  }
   for (int t = t_lo; t < t_hi; ++t) {
-    __syncthreads();  // everyone has finished reading the previous tile
-    store_tile();
-    __syncthreads();
-    if (t + 1 < t_hi) load_tile(t + 1);
+    const uint16_t* sK;
+    const uint16_t* sV;
+    if constexpr (NBUF == 2) {
+      // tile t sits in buffer (t - t_lo) & 1, written before the barrier; tile t + 1 goes from global memory
+      // to registers now and to the other buffer at the end of this iteration (its last readers, of tile
+      // t - 1, passed this barrier)
+      __syncthreads();
+      if (t + 1 < t_hi) load_tile(t + 1);
+      sK = sKb[(t - t_lo) & 1];
+      sV = sVb[(t - t_lo) & 1];
+    } else {
+      __syncthreads();  // everyone has finished reading the previous tile
+      store_tile(0);
+      __syncthreads();
+      if (t + 1 < t_hi) load_tile(t + 1);
+      sK = sKb[0];
+      sV = sVb[0];
+    }
     const int kv0 = t * kBKV;
-    if (a.causal && kv0 > q0 + 16 * QB - 1) continue;  // every key of the tile lies after this wavefront's last query row
+    // every key of the tile lies after this wavefront's last query row: nothing to do but pass the tile on
+    const bool skip = a.causal && kv0 > q0 + 16 * QB - 1;
+    if (skip) {
+      if constexpr (NBUF == 2) {
+        if (t + 1 < t_hi) store_tile((t + 1 - t_lo) & 1);
+      }
+      continue;
+    }
 
     // scores, transposed: st[kb][qb][r] = S[query qb*16 + lane%16][key kv0 + kb*16 + (lane/16)*4 + r]
     f32x4 st[4][QB];
@@ -238,6 +266,9 @@ __global__ __launch_bounds__(kThreads, QB == 1 ? 3 : 2) void attn_core_fwd_kerne
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) acc[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[qb][s2], acc[qb][db], 0, 0, 0);
       }
+    }
+    if constexpr (NBUF == 2) {
+      if (t + 1 < t_hi) store_tile((t + 1 - t_lo) & 1);
     }
   }
 
@@ -761,12 +792,16 @@ __global__ __launch_bounds__(256) void attn_core_part_reduce_kernel(const CoreBw
 
 // Parts to cut each workgroup's walk into, so that a launch of `blocks` workgroups whose longest walk has
 // `walk` tiles fills the GPU: 1 (no cut) unless a workspace is registered that holds the partial sums.
-int choose_parts(int64_t blocks, int64_t walk, int64_t bytes_per_block_part) {
+int choose_parts(int64_t blocks, int64_t walk, int64_t bytes_per_block_part, bool causal) {
   int64_t ws_bytes = 0;
   if (!ntp::workspace(&ws_bytes) || blocks <= 0) return 1;
-  if (blocks >= 512 && !getenv("NTP_ATTN_PARTS")) return 1;
-  // about 1024 workgroups measured best at 64 to 192 uncut ones; beyond 12 parts the merge costs more than it gains
-  int64_t parts = std::min<int64_t>({12, (1024 + blocks - 1) / blocks, walk / 4});
+  // Up to 256 workgroups (no more than compute units): about 1024 parts in all measured best at 64 to 192
+  // workgroups; beyond 12 parts per workgroup the merge costs more than it gains.  Between 256 and 512 workgroups
+  // two parts still pay under the causal mask (uneven walks: 448 workgroups, 63 -> 58 us forward) and cost
+  // 10 % without it.
+  int64_t parts = 1;
+  if (blocks <= 256) parts = std::min<int64_t>({12, (1024 + blocks - 1) / blocks, walk / 4});
+  else if (causal && blocks < 512) parts = std::min<int64_t>(2, walk / 4);
   // tests reach every cut through this override (1..16 parts at any size)
   if (const char* f = getenv("NTP_ATTN_PARTS")) parts = std::min(16, std::max(1, atoi(f)));
   while (parts > 1 && blocks * parts * bytes_per_block_part > ws_bytes) --parts;
@@ -822,7 +857,7 @@ extern "C" int ntp_attn_core_shard_fwd(const ntp_attn_core_shape_t* s, const voi
   // seq_len / 64 key tiles: cut the walks then (needs a registered workspace)
   const int64_t blocks1 = int64_t((s->seq_len + 63) / 64) * s->n_seq * s->q_cnt;
   a.part_sums = static_cast<float*>(ntp::workspace(nullptr));
-  a.n_parts = choose_parts(blocks1, (s->seq_len + kBKV - 1) / kBKV, int64_t(64) * (s->head_dim + 4) * 4);
+  a.n_parts = choose_parts(blocks1, (s->seq_len + kBKV - 1) / kBKV, int64_t(64) * (s->head_dim + 4) * 4, s->causal != 0);
   if (a.n_parts > 1) qbw = 1;
   a.q_tiles = (s->seq_len + 64 * qbw - 1) / (64 * qbw);
   a.scale_log2 = float(1.4426950408889634 / std::sqrt(double(s->head_dim)));
@@ -907,7 +942,7 @@ extern "C" int ntp_attn_core_shard_bwd(const ntp_attn_core_shape_t* s, const voi
   if (bq > 0) {
     // dQ and delta: three products per (query, key) pair.  With few heads the launch is short of
     // workgroups and each walks over up to seq_len / 64 key tiles: cut the walks then.
-    a.n_parts = choose_parts(bq, a.tiles, int64_t(64) * s->head_dim * 4);
+    a.n_parts = choose_parts(bq, a.tiles, int64_t(64) * s->head_dim * 4, s->causal != 0);
     if (ntp::timing_on()) ntp::timing_begin(stream, a.n_parts > 1 ? "attn_core_bwd_dq_cut" : "attn_core_bwd_dq", 3.0 * pair_flops, 0.0);
     const dim3 grid(uint32_t(bq * a.n_parts));
     if (s->head_dim == 128)
@@ -931,7 +966,7 @@ extern "C" int ntp_attn_core_shard_bwd(const ntp_attn_core_shape_t* s, const voi
     // a workgroup walks over the query tiles of every query head that reads its KV head
     a.tiles = key_tiles;
     const int64_t heads_per_kv = std::min<int64_t>(s->group, s->q_cnt);
-    a.n_parts = choose_parts(bk, heads_per_kv * ((s->seq_len + kBKV - 1) / kBKV), int64_t(64) * 2 * s->head_dim * 4);
+    a.n_parts = choose_parts(bk, heads_per_kv * ((s->seq_len + kBKV - 1) / kBKV), int64_t(64) * 2 * s->head_dim * 4, s->causal != 0);
     if (ntp::timing_on()) ntp::timing_begin(stream, a.n_parts > 1 ? "attn_core_bwd_dkv_cut" : "attn_core_bwd_dkv", 4.0 * pair_flops, 0.0);
     const dim3 grid(uint32_t(bk * a.n_parts));
     if (s->head_dim == 128)
