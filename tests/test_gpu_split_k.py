@@ -64,6 +64,20 @@ def test_mlp_split_k_every_tile(workspace, monkeypatch, tile, splits):
         assert (raw[name][:, 1171:1176].float().cpu().numpy() == 0).all()
 
 
+@pytest.mark.parametrize("tile", ["256x256", "224x256", "128x256"])
+def test_split_k_last_chunk_shorter_than_a_k_tile(workspace, monkeypatch, tile):
+    """Five chunks of 256 (320) over K = 1032 (1288): the last chunk has 8 values, no whole K tile, in every layout
+    (tokens, hidden size and shard width are each the K of some GEMM of the layer)."""
+    _say(f"split-K with a last chunk of 8, tile {tile}")
+    monkeypatch.setenv("NTP_GEMM_TILE", tile)
+    monkeypatch.setenv("NTP_GEMM_SPLIT", "5")
+    case = MlpCase(1032, 1032, 1288, 1, 0)
+    got, _ = case.run_gpu()
+    names = _gemm_names()
+    assert len(names) == 6 and all(n.endswith(f"{tile}k5") for n in names), names
+    _check_all(got, case.oracle(), MLP_NAMES)
+
+
 @pytest.mark.parametrize("splits", [2, 4])
 def test_attn_proj_split_k(workspace, monkeypatch, splits):
     _say(f"attention projections split-K splits {splits}")
