@@ -128,3 +128,21 @@ def test_split_k_skipped_when_workspace_too_small(monkeypatch):
         N.ntp_kernel_timing_enable(0)
         N.ntp_kernel_timing_read()
         N.ntp_set_workspace(None)
+
+
+def test_automatic_choice_on_seeded_random_shapes(workspace):
+    """Eight seeded random layer shapes through the launcher's own choice of tile, chunks and persistence
+    (workspace registered, no override): whatever it picks must match the oracle."""
+    rng = np.random.default_rng(20250406)
+    picked = set()
+    for i in range(8):
+        M = int(rng.integers(130, 2600))
+        H = int(rng.integers(17, 400)) * 8
+        n_r = int(rng.integers(130, 1400))
+        _say(f"random shape {i}: M={M} H={H} n_r={n_r}")
+        case = MlpCase(M, H, n_r, 1, 0, seed=100 + i, tag=f"rnd{i}")
+        got, _ = case.run_gpu()
+        picked.update(n.split("_", 3)[-1] for n in _gemm_names())
+        _check_all(got, case.oracle(), MLP_NAMES)
+    _say(f"variants picked: {sorted(picked)}")
+    assert len(picked) >= 3
