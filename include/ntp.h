@@ -338,6 +338,9 @@ int ntp_comp_sync_plan(int64_t k, int32_t full_tp, int32_t reduced_tp, int32_t* 
  *   16 bytes per sub-shard) on the current device and waits for its upload;
  *   later runs must use the same device (else INVALID_ARG) and allocate
  *   nothing.  Everything else is copied sub-shard by sub-shard.
+ * ntp_reshard_plan_prepare: does that allocation and upload now, on the current
+ *   device, so that no run of the plan allocates or waits (a run can then be
+ *   captured into a HIP graph).  A plan that has no table is left as it is.
  * ntp_reshard_plan_destroy: frees the handle and its device table; no run of
  *   the plan may still be in flight.  NULL is accepted. */
 typedef struct ntp_reshard_plan ntp_reshard_plan_t;
@@ -353,6 +356,7 @@ int ntp_reshard_plan_segments(const ntp_reshard_plan_t* plan, ntp_segment_t* out
 int ntp_reshard_plan_splits(const ntp_reshard_plan_t* plan, int64_t* units);
 int ntp_reshard_plan_table(const ntp_reshard_plan_t* plan, ntp_unit_source_t* out,
                            int64_t max_units, int64_t* count);
+int ntp_reshard_plan_prepare(ntp_reshard_plan_t* plan);
 int ntp_reshard_plan_run(ntp_reshard_plan_t* plan, const void* const* src_shards,
                          const int64_t* src_ld, void* const* dst_shards, const int64_t* dst_ld,
                          void* stream);

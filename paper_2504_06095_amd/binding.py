@@ -27,7 +27,7 @@ EXPORTS = (
     "ntp_mlp_shard_bwd", "ntp_attn_proj_shard_fwd", "ntp_attn_proj_shard_bwd", "ntp_reshard_segments",
     "ntp_reshard_grad", "ntp_kernel_timing_enable", "ntp_kernel_timing_read", "ntp_calibration_copy",
     "ntp_comp_sync_plan", "ntp_reshard_plan_create", "ntp_reshard_plan_segments", "ntp_reshard_plan_splits",
-    "ntp_reshard_plan_table", "ntp_reshard_plan_run", "ntp_reshard_plan_destroy", "ntp_reshard_row_segments",
+    "ntp_reshard_plan_table", "ntp_reshard_plan_prepare", "ntp_reshard_plan_run", "ntp_reshard_plan_destroy", "ntp_reshard_row_segments",
     "ntp_mlp_shard_bwd_resharded", "ntp_attn_proj_shard_bwd_resharded", "ntp_attn_core_shard_fwd", "ntp_attn_core_shard_bwd",
     "ntp_set_workspace", "ntp_gemm_choice",
 )
@@ -115,6 +115,7 @@ def lib() -> C.CDLL:
         L.ntp_reshard_plan_segments.argtypes = [vp, C.POINTER(Segment), i64, C.POINTER(i64)]
         L.ntp_reshard_plan_splits.argtypes = [vp, C.POINTER(i64)]
         L.ntp_reshard_plan_table.argtypes = [vp, C.POINTER(UnitSource), i64, C.POINTER(i64)]
+        L.ntp_reshard_plan_prepare.argtypes = [vp]
         L.ntp_reshard_plan_run.argtypes = [vp, C.POINTER(vp), C.POINTER(i64), C.POINTER(vp), C.POINTER(i64), vp]
         L.ntp_reshard_plan_destroy.argtypes = [vp]
         segp = C.POINTER(RowSegment)
@@ -396,6 +397,10 @@ class ReshardPlan:
         buf = (UnitSource * max(1, self.n_units))()
         _check(lib().ntp_reshard_plan_table(self._h, buf, self.n_units, C.byref(n)), "ntp_reshard_plan_table")
         return [(e.src_rank, e.src_unit) for e in buf[: n.value]]
+
+    def ntp_reshard_plan_prepare(self) -> None:
+        """Upload the run table now, so that no run of the plan allocates (needed before a graph capture)."""
+        _check(lib().ntp_reshard_plan_prepare(self._h), "ntp_reshard_plan_prepare")
 
     def ntp_reshard_plan_run(self, src_shards, dst_shards) -> None:
         sp, sl, dp, dl = _shard_arrays(self.spec, self.src_tp, self.dst_tp, src_shards, dst_shards)

@@ -953,6 +953,37 @@ bool units_path_ok(const ntp_reshard_plan* p, const void* const* src_shards, con
 
 }  // namespace
 
+namespace {
+
+// The plan's run table on the current device: uploaded once (allocates and waits for the copy).
+int ensure_table(ntp_reshard_plan_t* plan) {
+  int cur = -1;
+  if (hipGetDevice(&cur) != hipSuccess) return NTP_ERR_LAUNCH;
+  if (plan->dev_table) return cur == plan->dev ? NTP_OK : NTP_ERR_INVALID_ARG;  // the table lives on one device
+  const size_t runs_bytes = plan->runs.size() * sizeof(RunDev), idx_bytes = plan->run_of_unit.size() * sizeof(uint16_t);
+  if (hipMalloc(&plan->dev_table, runs_bytes + idx_bytes) != hipSuccess) {
+    plan->dev_table = nullptr;
+    return NTP_ERR_LAUNCH;
+  }
+  if (hipMemcpy(plan->dev_table, plan->runs.data(), runs_bytes, hipMemcpyHostToDevice) != hipSuccess ||
+      hipMemcpy(static_cast<char*>(plan->dev_table) + runs_bytes, plan->run_of_unit.data(), idx_bytes,
+                hipMemcpyHostToDevice) != hipSuccess) {
+    (void)hipFree(plan->dev_table);
+    plan->dev_table = nullptr;
+    return NTP_ERR_LAUNCH;
+  }
+  plan->dev = cur;
+  return NTP_OK;
+}
+
+}  // namespace
+
+extern "C" int ntp_reshard_plan_prepare(ntp_reshard_plan_t* plan) {
+  if (!plan) return NTP_ERR_INVALID_ARG;
+  if (!plan->runs_ok || plan->runs.empty()) return NTP_OK;  // this plan never uses a table
+  return ensure_table(plan);
+}
+
 extern "C" int ntp_reshard_plan_run(ntp_reshard_plan_t* plan, const void* const* src_shards, const int64_t* src_ld,
                                     void* const* dst_shards, const int64_t* dst_ld, void* stream) {
   if (!plan) return NTP_ERR_INVALID_ARG;
@@ -964,26 +995,8 @@ extern "C" int ntp_reshard_plan_run(ntp_reshard_plan_t* plan, const void* const*
     return ntp::reshard_launch(&plan->spec, plan->segs, plan->src_units, plan->dst_units, src_shards, src_ld, dst_shards,
                                dst_ld, stream);
 
-  int cur = -1;
-  if (hipGetDevice(&cur) != hipSuccess) return NTP_ERR_LAUNCH;
-  if (!plan->dev_table) {
-    // first run: the table goes to the current device (allocates and waits for the copy)
-    const size_t runs_bytes = plan->runs.size() * sizeof(RunDev), idx_bytes = plan->run_of_unit.size() * sizeof(uint16_t);
-    if (hipMalloc(&plan->dev_table, runs_bytes + idx_bytes) != hipSuccess) {
-      plan->dev_table = nullptr;
-      return NTP_ERR_LAUNCH;
-    }
-    if (hipMemcpy(plan->dev_table, plan->runs.data(), runs_bytes, hipMemcpyHostToDevice) != hipSuccess ||
-        hipMemcpy(static_cast<char*>(plan->dev_table) + runs_bytes, plan->run_of_unit.data(), idx_bytes,
-                  hipMemcpyHostToDevice) != hipSuccess) {
-      (void)hipFree(plan->dev_table);
-      plan->dev_table = nullptr;
-      return NTP_ERR_LAUNCH;
-    }
-    plan->dev = cur;
-  } else if (cur != plan->dev) {
-    return NTP_ERR_INVALID_ARG;  // the plan's table lives on another device
-  }
+  // first run of an unprepared plan: the table goes to the current device
+  if ((st = ensure_table(plan)) != NTP_OK) return st;
 
   const ntp_tensor_spec_t& sp = plan->spec;
   hipStream_t hs = static_cast<hipStream_t>(stream);

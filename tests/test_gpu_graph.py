@@ -87,3 +87,39 @@ def test_layer_calls_replay_in_a_graph(with_workspace):
                 assert same, f"replay {rep}: {k} differs from the eager result"
     finally:
         N.ntp_set_workspace(None)
+
+
+def test_prepared_reshard_plan_replays_in_a_graph():
+    """A reshard between the comp and sync layouts of the rank assignment (Alg. 1), prepared so that its run
+    allocates nothing, captured and replayed with new gradients each time."""
+    import numpy as np
+    import torch
+    import paper_2504_06095_amd as N
+    _say("graph capture of a prepared reshard plan")
+    k, t, tr, rows = 4096, 8, 7, 512
+    comp, sync = N.ntp_comp_sync_plan(k, t, tr)
+    comp, sync = np.asarray(comp), np.asarray(sync)
+    plan = N.ntp_reshard_plan_create(N.tensor_spec(rows, k, 1, 1, 4), t, comp, tr, sync)
+    try:
+        src = [torch.zeros(rows, int((comp == r).sum()), dtype=torch.float32, device="cuda") for r in range(t)]
+        dst = [torch.zeros(rows, int((sync == r).sum()), dtype=torch.float32, device="cuda") for r in range(tr)]
+        plan.ntp_reshard_plan_prepare()
+        side, graph = torch.cuda.Stream(), torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                plan.ntp_reshard_plan_run(src, dst)
+        torch.cuda.synchronize()
+        for rep in range(3):
+            G = torch.randn(rows, k, device="cuda", generator=torch.Generator(device="cuda").manual_seed(rep))
+            for r in range(t):
+                src[r].copy_(G[:, torch.from_numpy(np.nonzero(comp == r)[0]).cuda()])
+            for d in dst:
+                d.fill_(-1.0)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            for r in range(tr):
+                want = G[:, torch.from_numpy(np.nonzero(sync == r)[0]).cuda()]
+                assert torch.equal(dst[r], want), f"replay {rep}: destination shard {r}"
+    finally:
+        plan.destroy()
