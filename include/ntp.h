@@ -102,7 +102,11 @@ typedef struct ntp_mlp_shape {
  * rank's partial sum; the TP all-reduce is the caller's).
  *   in   X [M x H] bf16, A_t [n_r x H] bf16, B [n_r x H] bf16        (device)
  *   out  P, Y [M x n_r] bf16 with ldp, ldy >= n_r and % 8 == 0; columns from
- *        n_r up to the next multiple of 8 are written with zeros      (device)
+ *        n_r up to the next multiple of 8 are written with zeros; if both
+ *        ldp and ldy reach the next multiple of 64, up to that one (the second
+ *        GEMM then needs no special case for the end of its contraction axis).
+ *        Every row, the last one included, must be backed by its pad columns
+ *        as far as they are written                                  (device)
  *   out  Zpart [M x H] bf16                                           (device)
  * P and Y are kept for the backward call.  No buffer may alias another. */
 int ntp_mlp_shard_fwd(const ntp_mlp_shape_t* shape, const void* X, int64_t ldx, const void* A_t,
@@ -116,7 +120,8 @@ int ntp_mlp_shard_fwd(const ntp_mlp_shape_t* shape, const void* X, int64_t ldx, 
  *   dA_t   = dP_i^T X                      [n_r x H] fp32 (= (X^T dP_i)^T)
  *   dXpart = dP_i A_i^T                    [M x H]  bf16, partial sum
  * in: dZ [M x H] bf16 and X, A_t, B, P, Y as in the forward call (P, Y as it
- * wrote them).  accumulate != 0 adds into dA_t / dB instead of overwriting
+ * wrote them).  dP's pad columns are zeroed like P's (up to the next multiple
+ * of 8, or of 64 if lddp and ldp reach it).  accumulate != 0 adds into dA_t / dB instead of overwriting
  * (gradient accumulation over micro-batches before the reshard, Sec. 4.1). */
 int ntp_mlp_shard_bwd(const ntp_mlp_shape_t* shape, const void* dZ, int64_t lddz, const void* X,
                       int64_t ldx, const void* A_t, int64_t lda, const void* B, int64_t ldb,

@@ -226,7 +226,7 @@ int gemm_launch(const GemmDesc& d, void* stream) {
     if (!to_segs && (!aligned16(d.C) || d.ldc % 4)) return NTP_ERR_ALIGNMENT;
   } else {
     if (to_segs) return NTP_ERR_INVALID_ARG;
-    if (d.zero_pad_n) n_store = (d.N + 7) / 8 * 8;
+    if (d.zero_pad_n) n_store = d.pad_n_64 ? (d.N + 63) / 64 * 64 : (d.N + 7) / 8 * 8;
     if (n_store % 4) return NTP_ERR_ALIGNMENT;
     if (!aligned16(d.C) || d.ldc % 8) return NTP_ERR_ALIGNMENT;
     if (d.epilogue == EPI_GELU && (!aligned16(d.C2) || d.ldc2 % 8 || d.ldc2 < n_store)) return NTP_ERR_ALIGNMENT;
@@ -282,6 +282,18 @@ int gemm_launch(const GemmDesc& d, void* stream) {
   const bool ring_ok = ring_combo(d.a_kc, d.b_kc, d.epilogue) && a_rows * d.lda * 2 < (int64_t(1) << 32) &&
                        b_rows * d.ldb * 2 < (int64_t(1) << 32);
   const int layout = d.a_kc ? (d.b_kc ? 0 : 1) : 2;
+  // K tail through the ring (row-parallel layout; K is the ragged shard width): B's lines past K lie past its
+  // extent and read as zeros, A's columns past K are zeros by the caller's word.  NTP_GEMM_RING_TAIL=0
+  // switches it off (tests, tuning).
+  g.b_extent = 0xFFFFFFFFu;
+  {
+    const char* sw = getenv("NTP_GEMM_RING_TAIL");
+    if (layout == 1 && ring_ok && d.a_k_pad_64 && d.K % 64 != 0 && d.K >= 128 && d.lda >= (d.K + 63) / 64 * 64 &&
+        !(sw && sw[0] == '0')) {
+      g.ring_tail = 1;
+      g.b_extent = uint32_t(d.K * d.ldb * 2);  // < 4 GiB: ring_ok
+    }
+  }
   // split-K: any (layout, epilogue) whose operands the ring kernel can address, except B K-contiguous
   // with A K-strided (no ring kernel)
   const bool split_ok = a_rows * d.lda * 2 < (int64_t(1) << 32) && b_rows * d.ldb * 2 < (int64_t(1) << 32) && (d.a_kc || !d.b_kc);
@@ -306,6 +318,8 @@ int gemm_launch(const GemmDesc& d, void* stream) {
     st = launch_ring_split_tn(gp, d.epilogue, variant, s);
   } else if (sc.splits > 1) {
     GemmArgs gp = g;  // the partial-sum launch: fp32 to the workspace, no row segments
+    gp.ring_tail = 0;
+    gp.b_extent = 0xFFFFFFFFu;
     gp.C = g_workspace;
     gp.ldc = ldw;
     gp.n_segs = 0;

@@ -41,6 +41,11 @@ struct GemmArgs {
   // distance in floats between the partial-sum slices that start at C
   int32_t k_splits, k_chunk;
   int64_t split_stride;
+  // ring kernel, A K-contiguous and B K-strided: the K tail goes through the ring as one more tile.  A's rows
+  // hold zeros from K up to the next multiple of 64; b_extent is B's size in bytes, so that the lines of
+  // the tail tile at k >= K, which lie past it, read as zeros (0xffffffff when ring_tail is 0: no check)
+  int32_t ring_tail;
+  uint32_t b_extent;
 };
 
 __device__ __forceinline__ float gelu_fwd(float x, int mode) {

@@ -262,7 +262,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
   const int64_t astep = AKC ? DK : DK * g.lda, bstep = BKC ? DK : DK * g.ldb;  // elements per K tile
   // buffer views of the operands for the DMA (the host checks that each operand spans < 4 GiB)
   const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(opA), 0, -1, 0x00020000);
-  const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(opB), 0, -1, 0x00020000);
+  // (the range check of a buffer load covers vector + scalar offset; what lies past the extent reads as zero)
+  constexpr bool RT = AKC && !BKC && !SPLIT;
+  const __amdgpu_buffer_rsrc_t rb =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(opB), 0, RT ? int(g.b_extent) : -1, 0x00020000);
   const uint32_t astep_b = uint32_t(astep) * 2, bstep_b = uint32_t(bstep) * 2;
   FragAddr<AKC, RA, MI> fra;
   FragAddr<BKC, RB, NI> frb;
@@ -273,6 +276,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
   const long long probe_c0 = clock64();
 #endif
   const int nfull = K / DK;  // complete K tiles: all go through the ring
+  // The K tail goes through the ring as one more tile when the host says that both operands read as zeros
+  // past K there (g.ring_tail); otherwise it is loaded through registers after the loop.
+  const bool ring_tail = RT && g.ring_tail != 0 && nfull * DK < K;
+  const int nk = nfull + (ring_tail ? 1 : 0);
 
   // L2 prefetch, PFD tiles ahead.  An A tile is shared by the workgroups of this XCD that have the
   // same tile_m (about four, with different tile_n), a B tile by those with the same tile_n (eight
@@ -386,7 +393,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
     // Past the last tile the schedule keeps running on the last tile's data (clamped index): the
     // slots written are free, nobody reads them, and the instruction counts that the waits rely on
     // stay the same in every tile.
-    const int t1 = min(t + 1, nfull - 1), t2 = min(t + 2, nfull - 1);
+    const int t1 = min(t + 1, nk - 1), t2 = min(t + 2, nk - 1);
     auto dmaS1 = [&](int i) { if (i < NS) dmaS(t1, nss, i); };
     auto dmaL2 = [&](int i) { if (i < NL) dmaL(t2, fsl, i); };
     auto dmaS2 = [&](int i) { if (i < NS) dmaS(t2, sl, i); };
@@ -421,12 +428,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
 
   // first DMA instructions of an output tile: K tile 0 whole, A of K tile 1 whole, first part of B of K tile 1
   auto first_dma = [&] {
-    if (nfull > 0) {
+    if (nk > 0) {
 #pragma unroll
       for (int i = 0; i < NL; ++i) dmaL(0, r0, i);
 #pragma unroll
       for (int i = 0; i < NS; ++i) dmaS(0, r1, i);
-      const int p1 = min(1, nfull - 1);
+      const int p1 = min(1, nk - 1);
 #pragma unroll
       for (int i = 0; i < NL; ++i) dmaL(p1, r2, i);
 #pragma unroll
@@ -454,7 +461,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
     for (int i = 0; i < MI; ++i)
 #pragma unroll
       for (int j = 0; j < NI; ++j) acc[i][j] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-    if (nfull > 0) {
+    if (nk > 0) {
       // The first DMA instructions of this output tile have landed.  After the first output tile the
       // previous tile's stores (and the loads of its epilogue) sit in the same in-order counter,
       // issued after those DMA instructions: when that tile was an interior one, every wavefront
@@ -465,16 +472,16 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
       read_a(0, r0, 0);
       read_b(0, r1, 0);
     }
-    for (int t = 0; t < nfull; t += 5) {
+    for (int t = 0; t < nk; t += 5) {
       body(Int<0>{}, t);
-      if (t + 1 < nfull) body(Int<1>{}, t + 1);
-      if (t + 2 < nfull) body(Int<2>{}, t + 2);
-      if (t + 3 < nfull) body(Int<3>{}, t + 3);
-      if (t + 4 < nfull) body(Int<4>{}, t + 4);
+      if (t + 1 < nk) body(Int<1>{}, t + 1);
+      if (t + 2 < nk) body(Int<2>{}, t + 2);
+      if (t + 3 < nk) body(Int<3>{}, t + 3);
+      if (t + 4 < nk) body(Int<4>{}, t + 4);
     }
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // the clamped DMA instructions of the last tiles
     // K tail (K % 64 != 0) through registers with element masks, not overlapped
-    if (nfull * DK < K) {
+    if (!ring_tail && nfull * DK < K) {
       __syncthreads();
       a.tail(opA, astep, nfull, K, r0, wave, lane);
       b.tail(opB, bstep, nfull, K, r1, wave, lane);

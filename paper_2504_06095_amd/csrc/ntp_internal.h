@@ -72,6 +72,10 @@ struct GemmDesc {
   int64_t ldaux;
   int32_t gelu_mode;
   bool zero_pad_n;  // bf16 outputs: also write zeros to columns [N, round_up(N, 8))
+  bool pad_n_64;    // ... up to round_up(N, 64) (every leading dimension of an output must reach that far)
+  // A is K-contiguous, lda >= round_up(K, 64), and every row of A holds zeros in columns [K, round_up(K, 64)):
+  // with B K-strided, the K tail can then go through the ring like a whole K tile
+  bool a_k_pad_64;
   // fp32 epilogues: when n_segs > 0 the output rows go to these destinations instead of C
   // (host array; a row that no segment lists is not stored)
   const ntp_row_segment_t* segs;

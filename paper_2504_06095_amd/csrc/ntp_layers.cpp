@@ -40,6 +40,9 @@ extern "C" int ntp_mlp_shard_fwd(const ntp_mlp_shape_t* s, const void* X, int64_
   if (s->M == 0 || s->H == 0) return NTP_OK;
   if (!X || !Zpart || (s->n_r > 0 && (!A_t || !B || !P || !Y))) return NTP_ERR_INVALID_ARG;
   int st = NTP_OK;
+  // rows long enough: the pad columns are zeroed up to the next multiple of 64 (a whole K tile of the second GEMM)
+  const int64_t n64 = (s->n_r + 63) / 64 * 64;
+  const bool pad64 = s->n_r > 0 && ldp >= n64 && ldy >= n64;
   if (s->n_r > 0) {
     // P = X A_i (A_t holds A_i's columns as rows), Y = GeLU(P); pad columns zeroed
     GemmDesc d = gemm(X, ldx, true, A_t, lda, true, s->M, s->n_r, s->H, ntp::EPI_GELU, P, ldp);
@@ -47,10 +50,12 @@ extern "C" int ntp_mlp_shard_fwd(const ntp_mlp_shape_t* s, const void* X, int64_
     d.ldc2 = ldy;
     d.gelu_mode = s->gelu_mode;
     d.zero_pad_n = true;
+    d.pad_n_64 = pad64;
     if ((st = ntp::gemm_launch(d, stream)) != NTP_OK) return st;
   }
   // Zpart = Y B_i, contraction over the ragged shard width
   GemmDesc d2 = gemm(Y, ldy, true, B, ldb, false, s->M, s->H, s->n_r, ntp::EPI_BF16, Zpart, ldz);
+  d2.a_k_pad_64 = pad64;  // Y's pad columns were zeroed just above
   return ntp::gemm_launch(d2, stream);
 }
 
@@ -68,6 +73,8 @@ int mlp_bwd(const ntp_mlp_shape_t* s, const void* dZ, int64_t lddz, const void* 
   if (s->M > 0 && (!dZ || !X || !dXpart || (s->n_r > 0 && (!P || !Y || !dP)))) return NTP_ERR_INVALID_ARG;
   const int32_t wepi = accumulate ? ntp::EPI_F32_ACCUM : ntp::EPI_F32;
   int st = NTP_OK;
+  const int64_t n64 = (s->n_r + 63) / 64 * 64;
+  const bool pad64 = s->n_r > 0 && s->M > 0 && lddp >= n64 && ldp >= n64;  // as in the forward call, for dP
   if (s->n_r > 0 && s->M > 0) {
     // dP = (dZ B_i^T) .* GeLU'(P)
     GemmDesc d = gemm(dZ, lddz, true, B, ldb, true, s->M, s->n_r, s->H, ntp::EPI_DGELU, dP, lddp);
@@ -75,6 +82,7 @@ int mlp_bwd(const ntp_mlp_shape_t* s, const void* dZ, int64_t lddz, const void* 
     d.ldaux = ldp;
     d.gelu_mode = s->gelu_mode;
     d.zero_pad_n = true;
+    d.pad_n_64 = pad64;
     if ((st = ntp::gemm_launch(d, stream)) != NTP_OK) return st;
   }
   if (s->n_r > 0) {
@@ -91,6 +99,7 @@ int mlp_bwd(const ntp_mlp_shape_t* s, const void* dZ, int64_t lddz, const void* 
   if (s->M == 0) return NTP_OK;
   // dXpart = dP A_i^T, contraction over the ragged shard width
   GemmDesc dx = gemm(dP, lddp, true, A_t, lda, false, s->M, s->H, s->n_r, ntp::EPI_BF16, dXpart, lddx);
+  dx.a_k_pad_64 = pad64;  // dP's pad columns were zeroed above
   return ntp::gemm_launch(dx, stream);
 }
 

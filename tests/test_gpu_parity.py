@@ -189,6 +189,49 @@ def test_mlp_every_tile_variant_ragged(variant, monkeypatch):
         assert (raw[name][:, 1001:1008].float().cpu().numpy() == 0).all()
 
 
+@pytest.mark.parametrize("ring_tail", ["1", "0"], ids=["tail through the ring", "tail through registers"])
+@pytest.mark.parametrize("variant", ["auto"] + RING_TILES)
+def test_mlp_rows_padded_to_64_every_tile_variant(variant, ring_tail, monkeypatch):
+    """P, Y, dP with leading dimensions that reach the next multiple of 64: their pad columns are zeroed that far
+    and the row-parallel GEMMs (fc2, dX: K = n_r = 1001 = 15 K tiles + 41) take the K tail through the ring."""
+    _say(f"mlp rows padded to 64, variant {variant}, ring tail {ring_tail}")
+    if variant != "auto":
+        monkeypatch.setenv("NTP_GEMM_TILE", variant)
+    monkeypatch.setenv("NTP_GEMM_RING_TAIL", ring_tail)
+    case = MlpCase(777, 1096, 2003, 2, 1)
+    got, raw = case.run_gpu(pad_to=64)
+    assert raw["ld"] == 1024
+    _check_all(got, case.oracle(), MLP_NAMES)
+    for name in ("P", "Y", "dP"):
+        assert (raw[name][:, 1001:1024].float().cpu().numpy() == 0).all(), name
+
+
+def test_mlp_ring_tail_needs_no_finite_values_past_the_weights():
+    """The weight shard B_i [n_r x H] ends exactly where its allocation ends: what the K tail tile would read past
+    it comes back as zeros from the load's range check, not from memory.  NaN-filled neighbours must not leak in."""
+    import torch
+    import paper_2504_06095_amd as N
+    _say("mlp ring tail: weights at the end of a NaN-filled arena")
+    case = MlpCase(520, 1032, 1500, 1, 0, seed=9, tag="arena")  # n_r = 1500 = 23 K tiles + 28
+    from tests.helpers import dev_bf16_to_f64, to_dev_bf16
+    M, H, n_r, ld = case.M, case.H, case.n_r, 1536
+    arena = torch.full((3 * n_r * H + 4096,), float("nan"), dtype=torch.bfloat16, device="cuda")
+    B = arena[n_r * H:2 * n_r * H].view(n_r, H)   # NaN before and after
+    At = arena[2 * n_r * H + 2048:3 * n_r * H + 2048].view(n_r, H)
+    B.copy_(to_dev_bf16(case.B_bits))
+    At.copy_(to_dev_bf16(case.At_bits))
+    X, dZ = to_dev_bf16(case.X_bits), to_dev_bf16(case.dZ_bits)
+    mk = lambda r, c: torch.full((r, c), float("nan"), dtype=torch.bfloat16, device="cuda")
+    P, Y, dP, Z, dX = mk(M, ld), mk(M, ld), mk(M, ld), mk(M, H), mk(M, H)
+    dA, dB = torch.zeros(n_r, H, device="cuda"), torch.zeros(n_r, H, device="cuda")
+    N.ntp_mlp_shard_fwd(X, At, B, P[:, :n_r], Y[:, :n_r], Z, n_r, 0)
+    N.ntp_mlp_shard_bwd(dZ, X, At, B, P[:, :n_r], Y[:, :n_r], dP[:, :n_r], dX, dA, dB, n_r, 0, False)
+    torch.cuda.synchronize()
+    want = case.oracle()
+    got = dict(Z=dev_bf16_to_f64(Z), dX=dev_bf16_to_f64(dX))
+    _check_all(got, want, ["Z", "dX"])
+
+
 @pytest.mark.parametrize("variant", RING_TILES)
 def test_attn_every_tile_variant(variant, monkeypatch):
     _say(f"attn variant {variant}")
