@@ -83,7 +83,10 @@ int launch_ring_split_tile(const GemmArgs& g, int tile, hipStream_t s) {
 template <bool AKC, bool BKC, int EPI>
 int launch_ring_tile(const GemmArgs& g, int tile, hipStream_t s) {
   switch (tile) {
-    case 0: return launch_ring_one<AKC, BKC, EPI, 256, 256, 2, 4>(g, s);
+    case 0:
+      // (the weight-gradient layout has this tile in the non-persistent form only)
+      if constexpr (AKC || BKC) return launch_ring_one<AKC, BKC, EPI, 256, 256, 2, 4>(g, s);
+      else return NTP_ERR_INVALID_ARG;
     case 1: return launch_ring_one<AKC, BKC, EPI, 256, 224, 4, 2>(g, s);
     case 2: return launch_ring_one<AKC, BKC, EPI, 224, 256, 2, 4>(g, s);
     case 3: return launch_ring_one<AKC, BKC, EPI, 256, 192, 4, 2>(g, s);
@@ -102,6 +105,8 @@ int launch_ring_tile(const GemmArgs& g, int tile, hipStream_t s) {
 // lists the pairs it owns (implicit instantiation alone does not emit all host-side launch stubs).
 #define NTP_RING_INSTANTIATE(AKC, BKC, EPI)                                                        \
   template __global__ void gemm_ring_kernel<AKC, BKC, EPI, 256, 256, 2, 4>(const GemmArgs);        \
+  NTP_RING_INSTANTIATE_BELOW_256(AKC, BKC, EPI)
+#define NTP_RING_INSTANTIATE_BELOW_256(AKC, BKC, EPI)                                              \
   template __global__ void gemm_ring_kernel<AKC, BKC, EPI, 256, 224, 4, 2>(const GemmArgs);        \
   template __global__ void gemm_ring_kernel<AKC, BKC, EPI, 224, 256, 2, 4>(const GemmArgs);        \
   template __global__ void gemm_ring_kernel<AKC, BKC, EPI, 256, 192, 4, 2>(const GemmArgs);        \

@@ -4,8 +4,8 @@
 
 namespace ntp_gemm {
 
-NTP_RING_INSTANTIATE(false, false, ntp::EPI_F32)
-NTP_RING_INSTANTIATE(false, false, ntp::EPI_F32_ACCUM)
+NTP_RING_INSTANTIATE_BELOW_256(false, false, ntp::EPI_F32)
+NTP_RING_INSTANTIATE_BELOW_256(false, false, ntp::EPI_F32_ACCUM)
 NTP_RING_INSTANTIATE_SPLIT(false, false)
 
 template __global__ void gemm_ring_kernel<false, false, ntp::EPI_F32_ACCUM, 256, 256, 2, 4, true>(const GemmArgs);
