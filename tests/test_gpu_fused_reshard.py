@@ -99,6 +99,27 @@ def test_mlp_bwd_resharded_every_kernel_family(monkeypatch, tile):
     _mlp_case(1024, 2048, 8192, 7, 8, 2, 5, 0, tile == "256x256")
 
 
+@pytest.mark.parametrize("splits,accumulate", [(2, False), (3, True)])
+def test_mlp_bwd_resharded_with_split_k(monkeypatch, splits, accumulate):
+    """The gradient GEMMs cut along the token axis: the kernel that adds the partial sums stores them through the
+    same row segments (two destination shards per gradient here), overwriting or accumulating."""
+    import torch
+    import paper_2504_06095_amd as N
+    _say(f"mlp bwd resharded with split-K, {splits} chunks, accumulate {accumulate}")
+    N.ntp_set_workspace(torch.full((32 << 20,), float("nan"), dtype=torch.float32, device="cuda"))
+    N.ntp_kernel_timing_enable(1)
+    N.ntp_kernel_timing_read()
+    try:
+        monkeypatch.setenv("NTP_GEMM_SPLIT", str(splits))
+        _mlp_case(1100, 1096, 8197, 7, 8, 3, 6, 4, accumulate)
+        names = [r["name"] for r in N.ntp_kernel_timing_read() if r["name"].startswith("gemm_tn")]
+        assert names and all(n.endswith(f"k{splits}") for n in names), names
+    finally:
+        N.ntp_kernel_timing_enable(0)
+        N.ntp_kernel_timing_read()
+        N.ntp_set_workspace(None)
+
+
 @pytest.mark.parametrize("a,b,rank", [(5, 7, 0), (5, 7, 2), (7, 5, 6), (4, 4, 1), (3, 16, 1)])
 def test_attn_bwd_resharded_matches_unfused(a, b, rank):
     import torch
