@@ -417,6 +417,17 @@ typedef struct ntp_gemm_choice {
 } ntp_gemm_choice_t;
 int ntp_gemm_choice(int32_t layout, int64_t M, int64_t N, int64_t K, ntp_gemm_choice_t* out);
 
+/* Diagnostic aid (host only): launch decisions of the attention core kernels for a shape,
+ * with the workspace registered at the time of the call.
+ *   fwd_rows_per_wavefront  16 or 32 query rows per wavefront in the forward kernel
+ *   fwd_parts, dq_parts, dkv_parts  > 1: every workgroup's walk is cut into that many parts
+ *                                   (fp32 partial results in the workspace, merged by a second kernel)
+ * Errors: as for ntp_attn_core_shard_fwd's shape checks. */
+typedef struct ntp_attn_core_choice {
+  int32_t fwd_rows_per_wavefront, fwd_parts, dq_parts, dkv_parts;
+} ntp_attn_core_choice_t;
+int ntp_attn_core_choice(const ntp_attn_core_shape_t* shape, ntp_attn_core_choice_t* out);
+
 /* Measurement aid: a plain dense device-to-device copy of `bytes` bytes (dst, src:
  * device, 16-byte aligned, bytes % 16 == 0, not overlapping) by a kernel named
  * calibration_copy_kernel.  Its known traffic (bytes read, bytes written) is what

@@ -29,12 +29,16 @@ EXPORTS = (
     "ntp_comp_sync_plan", "ntp_reshard_plan_create", "ntp_reshard_plan_segments", "ntp_reshard_plan_splits",
     "ntp_reshard_plan_table", "ntp_reshard_plan_prepare", "ntp_reshard_plan_run", "ntp_reshard_plan_destroy", "ntp_reshard_row_segments",
     "ntp_mlp_shard_bwd_resharded", "ntp_attn_proj_shard_bwd_resharded", "ntp_attn_core_shard_fwd", "ntp_attn_core_shard_bwd",
-    "ntp_set_workspace", "ntp_gemm_choice",
+    "ntp_set_workspace", "ntp_gemm_choice", "ntp_attn_core_choice",
 )
 
 
 class GemmChoice(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("tile_m", "tile_n", "wavefronts", "ring", "k_splits", "persistent")]
+
+
+class AttnCoreChoice(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("fwd_rows_per_wavefront", "fwd_parts", "dq_parts", "dkv_parts")]
 
 
 class NtpError(RuntimeError):
@@ -132,6 +136,7 @@ def lib() -> C.CDLL:
         L.ntp_calibration_copy.argtypes = [vp, vp, i64, vp]
         L.ntp_set_workspace.argtypes = [vp, i64]
         L.ntp_gemm_choice.argtypes = [C.c_int32, i64, i64, i64, C.POINTER(GemmChoice)]
+        L.ntp_attn_core_choice.argtypes = [C.POINTER(AttnCoreShape), C.POINTER(AttnCoreChoice)]
         for name in EXPORTS:
             getattr(L, name)  # AttributeError if a declared symbol is not exported
         _lib = L
@@ -471,3 +476,10 @@ def ntp_gemm_choice(layout: int, M: int, N: int, K: int) -> dict:
     out = GemmChoice()
     _check(lib().ntp_gemm_choice(layout, M, N, K, C.byref(out)), "ntp_gemm_choice")
     return {n: getattr(out, n) for n, _ in GemmChoice._fields_}
+
+
+def ntp_attn_core_choice(shape) -> dict:
+    """Launch decisions of the attention core kernels for an AttnCoreShape (host only)."""
+    out = AttnCoreChoice()
+    _check(lib().ntp_attn_core_choice(C.byref(shape), C.byref(out)), "ntp_attn_core_choice")
+    return {n: getattr(out, n) for n, _ in AttnCoreChoice._fields_}

@@ -808,6 +808,30 @@ int choose_parts(int64_t blocks, int64_t walk, int64_t bytes_per_block_part, boo
   return int(std::max<int64_t>(parts, 1));
 }
 
+// Launch decisions of the three kernels for a (checked) shape.
+struct CoreChoice {
+  int fwd_rows;  // query rows per wavefront of the forward kernel: 16 or 32
+  int fwd_parts, dq_parts, dkv_parts;
+};
+CoreChoice choose_core(const ntp_attn_core_shape_t* s) {
+  CoreChoice c{16, 1, 1, 1};
+  const int64_t tiles = (s->seq_len + kBKV - 1) / kBKV;
+  // 16-row query blocks per wavefront: two (twice the matrix work per LDS read, two workgroups per CU), or
+  // one (three workgroups per CU, twice as many of them) when two would leave compute units short of work
+  const int64_t blocks2 = int64_t((s->seq_len + 127) / 128) * s->n_seq * s->q_cnt;
+  c.fwd_rows = blocks2 < (s->causal ? 1024 : 384) ? 16 : 32;
+  // with few heads even the 64-row workgroups leave compute units idle while each walks over up to
+  // seq_len / 64 key tiles: cut the walks then (needs a registered workspace)
+  const int64_t bq = tiles * s->n_seq * s->q_cnt, bk = tiles * s->n_seq * s->kv_cnt;
+  c.fwd_parts = choose_parts(bq, tiles, int64_t(64) * (s->head_dim + 4) * 4, s->causal != 0);
+  if (c.fwd_parts > 1) c.fwd_rows = 16;
+  c.dq_parts = choose_parts(bq, tiles, int64_t(64) * s->head_dim * 4, s->causal != 0);
+  // a dK/dV workgroup walks over the query tiles of every query head that reads its KV head
+  const int64_t heads_per_kv = std::min<int64_t>(s->group, s->q_cnt);
+  c.dkv_parts = choose_parts(bk, heads_per_kv * tiles, int64_t(64) * 2 * s->head_dim * 4, s->causal != 0);
+  return c;
+}
+
 int check_core_shape(const ntp_attn_core_shape_t* s) {
   if (!s || s->n_seq < 0 || s->seq_len < 0 || s->q_cnt < 0 || s->kv_cnt < 0 || s->group < 1 || s->q_off < 0 || s->kv_off < 0)
     return NTP_ERR_INVALID_ARG;
@@ -822,6 +846,15 @@ int check_core_shape(const ntp_attn_core_shape_t* s) {
 }
 
 }  // namespace
+
+extern "C" int ntp_attn_core_choice(const ntp_attn_core_shape_t* s, ntp_attn_core_choice_t* out) {
+  const int st = check_core_shape(s);
+  if (st != NTP_OK) return st;
+  if (!out) return NTP_ERR_INVALID_ARG;
+  const CoreChoice c = choose_core(s);
+  *out = ntp_attn_core_choice_t{c.fwd_rows, c.fwd_parts, c.dq_parts, c.dkv_parts};
+  return NTP_OK;
+}
 
 extern "C" int ntp_attn_core_shard_fwd(const ntp_attn_core_shape_t* s, const void* QKV, int64_t ldqkv, void* C,
                                        int64_t ldc, float* LSE, void* stream) {
@@ -851,14 +884,10 @@ extern "C" int ntp_attn_core_shard_fwd(const ntp_attn_core_shape_t* s, const voi
   a.causal = s->causal ? 1 : 0;
   // 16-row query blocks per wavefront: two (twice the matrix work per LDS read, two workgroups per CU), or
   // one (three workgroups per CU, twice as many of them) when two would leave compute units short of work
-  const int64_t blocks2 = int64_t((s->seq_len + 127) / 128) * s->n_seq * s->q_cnt;
-  int qbw = blocks2 < (s->causal ? 1024 : 384) ? 1 : 2;
-  // with few heads even the 64-row workgroups leave compute units idle while each walks over up to
-  // seq_len / 64 key tiles: cut the walks then (needs a registered workspace)
-  const int64_t blocks1 = int64_t((s->seq_len + 63) / 64) * s->n_seq * s->q_cnt;
+  const CoreChoice cc = choose_core(s);
+  const int qbw = cc.fwd_rows / 16;
   a.part_sums = static_cast<float*>(ntp::workspace(nullptr));
-  a.n_parts = choose_parts(blocks1, (s->seq_len + kBKV - 1) / kBKV, int64_t(64) * (s->head_dim + 4) * 4, s->causal != 0);
-  if (a.n_parts > 1) qbw = 1;
+  a.n_parts = cc.fwd_parts;
   a.q_tiles = (s->seq_len + 64 * qbw - 1) / (64 * qbw);
   a.scale_log2 = float(1.4426950408889634 / std::sqrt(double(s->head_dim)));
   const int64_t blocks = int64_t(a.q_tiles) * s->n_seq * s->q_cnt;
@@ -942,7 +971,7 @@ extern "C" int ntp_attn_core_shard_bwd(const ntp_attn_core_shape_t* s, const voi
   if (bq > 0) {
     // dQ and delta: three products per (query, key) pair.  With few heads the launch is short of
     // workgroups and each walks over up to seq_len / 64 key tiles: cut the walks then.
-    a.n_parts = choose_parts(bq, a.tiles, int64_t(64) * s->head_dim * 4, s->causal != 0);
+    a.n_parts = choose_core(s).dq_parts;
     if (ntp::timing_on()) ntp::timing_begin(stream, a.n_parts > 1 ? "attn_core_bwd_dq_cut" : "attn_core_bwd_dq", 3.0 * pair_flops, 0.0);
     const dim3 grid(uint32_t(bq * a.n_parts));
     if (s->head_dim == 128)
@@ -965,8 +994,7 @@ extern "C" int ntp_attn_core_shard_bwd(const ntp_attn_core_shape_t* s, const voi
     // dK and dV: four products per pair
     // a workgroup walks over the query tiles of every query head that reads its KV head
     a.tiles = key_tiles;
-    const int64_t heads_per_kv = std::min<int64_t>(s->group, s->q_cnt);
-    a.n_parts = choose_parts(bk, heads_per_kv * ((s->seq_len + kBKV - 1) / kBKV), int64_t(64) * 2 * s->head_dim * 4, s->causal != 0);
+    a.n_parts = choose_core(s).dkv_parts;
     if (ntp::timing_on()) ntp::timing_begin(stream, a.n_parts > 1 ? "attn_core_bwd_dkv_cut" : "attn_core_bwd_dkv", 4.0 * pair_flops, 0.0);
     const dim3 grid(uint32_t(bk * a.n_parts));
     if (s->head_dim == 128)
