@@ -392,10 +392,16 @@ int ntp_kernel_timing_read(ntp_kernel_time_t* out, int64_t max_records, int64_t*
  * units idle is also cut along its contraction axis: fp32 partial sums go to the
  * workspace and a second kernel adds them in a fixed order and applies the epilogue
  * (results stay deterministic; they differ from the unsplit GEMM by fp32 rounding order).
+ * The attention core uses it the same way when a rank has few heads (Eq. 5 on 2-3
+ * heads of a long sequence is fewer workgroups than compute units): every workgroup's
+ * walk over the key (or query) tiles is cut into parts that store fp32 partial results,
+ * merged by a second kernel (forward: by running maximum and sum).
  *   workspace  device pointer, 256-byte aligned; NULL with bytes == 0 unregisters
- *   bytes      its size; a GEMM is split only if splits * M * round_up(N, 16) * 4 fits
+ *   bytes      its size; a GEMM is split only if splits * M * round_up(N, 16) * 4 fits,
+ *              a walk cut only if workgroups * parts * 64 rows * row bytes fits
+ *              (ntp_gemm_choice / ntp_attn_core_choice tell what a shape gets)
  * The caller owns the memory and keeps it alive while registered.  One workspace per
- * process: shard calls that may split must not overlap in time (same stream, or
+ * process: shard calls that may use it must not overlap in time (same stream, or
  * ordered across streams), on one device.  Without a workspace nothing is ever split.
  * Errors: NTP_ERR_INVALID_ARG (misaligned, negative size, NULL with bytes > 0). */
 int ntp_set_workspace(void* workspace, int64_t bytes);
