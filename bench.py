@@ -520,7 +520,8 @@ def main():
                                "fwd+bwd + attention projections (96 heads x 128, 14 on this rank) fwd+bwd + reshard "
                                "of the rank's dW (fp32) into the TP-8 layout",
                    "tokens": M, "hidden": H, "ffn": FFN, "n_r": s["n_r"], "w_qkv": s["wq"], "w_o": s["wo"],
-                   "full_tp": T_FULL, "reduced_tp": T_RED, "rank": RANK},
+                   "full_tp": T_FULL, "reduced_tp": T_RED, "rank": RANK,
+                   "split_k_workspace_bytes": 0 if args.no_workspace else 1 << 30},
         "frac_of_bf16_peak": value / BF16_MFMA_PEAK_TFLOPS,
         "roofline": roofline, "parts": parts, "kernels": kernels,
     }
