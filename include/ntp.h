@@ -11,10 +11,19 @@
  *
  * Conventions shared by every call
  *   - "device" pointers are HIP device memory owned by the caller; "host"
- *     pointers are ordinary process memory.  The library allocates nothing,
- *     keeps no pointer after a call returns, and never synchronises: kernels
- *     are enqueued on `stream` (a hipStream_t passed as void*, NULL = the
- *     default stream) and the call returns at once.
+ *     pointers are ordinary process memory.  Calls that enqueue work take a
+ *     handle (ntp_create), allocate no device memory, keep no pointer after
+ *     they return, and never synchronise: kernels are enqueued on `stream` (a
+ *     hipStream_t passed as void*, NULL = the default stream) and the call
+ *     returns at once.  The three exceptions say so where they are declared:
+ *     ntp_reshard_plan_prepare (one device allocation and a blocking upload per
+ *     plan), ntp_kernel_timing_* (HIP events, off by default) and the static
+ *     scratch entry point at the end of this file.
+ *   - The library holds no global state.  What a device call reads besides its
+ *     arguments (device size, workspace, tuning overrides) is in the handle;
+ *     calls on different handles may run concurrently, on any streams; calls on
+ *     ONE handle must come from one thread at a time, and those that may use
+ *     its workspace must be ordered on the device (same stream, or events).
  *   - Matrices are row-major with an explicit leading dimension `ld*` counted
  *     in ELEMENTS.  bf16 matrices need a 16-byte aligned base pointer and
  *     ld % 8 == 0; fp32 gradient matrices need a 16-byte aligned base and
@@ -50,6 +59,8 @@ extern "C" {
 #define NTP_ERR_ALIGNMENT (-2)   /* base pointer or leading dimension not aligned as required   */
 #define NTP_ERR_LAUNCH (-3)      /* the HIP runtime refused a kernel launch                      */
 #define NTP_ERR_UNSUPPORTED (-4) /* a size beyond what the kernels index (see each call)         */
+#define NTP_ERR_NOT_PREPARED (-5) /* ntp_reshard_plan_run before ntp_reshard_plan_prepare        */
+#define NTP_ERR_NO_DEVICE (-6)   /* a device call on a handle created with no device visible    */
 
 #define NTP_GELU_ERF 0  /* x * Phi(x)                                  */
 #define NTP_GELU_TANH 1 /* 0.5 x (1 + tanh(sqrt(2/pi)(x + 0.044715 x^3))) */
@@ -59,6 +70,38 @@ int ntp_version(void);
 
 /* Static string naming a status code.  Never NULL. */
 const char* ntp_status_string(int status);
+
+/* ---------------------------------------------------------------------------
+ * Handle.  ntp_create queries the CURRENT HIP device (its ordinal and number of
+ * compute units, which the launchers size their grids by) and returns a handle
+ * owned by the caller until ntp_destroy; it allocates host memory only.  With no
+ * device visible the handle still serves the host-only calls (ntp_gemm_choice,
+ * ntp_attn_core_choice, ntp_workspace_bytes) with an MI355X's 256 compute units.
+ * Device calls must be made with the handle's device current.
+ * ntp_device_info reports what was found (device -1: none). */
+typedef struct ntp_handle ntp_handle_t;
+int ntp_create(ntp_handle_t** out);
+int ntp_destroy(ntp_handle_t* h); /* NULL is accepted; no call on h may still be running on the host */
+int ntp_device_info(const ntp_handle_t* h, int32_t* device, int32_t* compute_units);
+
+/* Tuning overrides of one handle.  Every option is 0 by default = the library's
+ * own choice.  They exist so that tests and tuning runs can reach every kernel
+ * variant at any size; a forced variant computes the same result to within fp32
+ * summation order (bit-identical for the reshard options).
+ * Errors: unknown option or value out of range -> INVALID_ARG. */
+#define NTP_OPT_GEMM_TILE 0          /* 1: the small generic kernel; 2 + i: ring tile shape i in the order 256x256,
+                                        256x224, 224x256, 256x192, 192x256, 256x128, 128x256, 128x128 (4 wavefronts),
+                                        128x128 (8 wavefronts)                                                       */
+#define NTP_OPT_GEMM_SPLIT 1         /* 1: never cut the contraction axis; 2..8: that many chunks where they fit   */
+#define NTP_OPT_GEMM_NO_RING_TAIL 2  /* 1: the K tail of row-parallel GEMMs goes through registers                 */
+#define NTP_OPT_ATTN_PARTS 3         /* 1..16: parts per attention-core walk where the workspace holds them        */
+#define NTP_OPT_RESHARD_BLOCK 4      /* bytes per workgroup of the row-wise gather kernel                           */
+#define NTP_OPT_RESHARD_FLAT_BLOCK 5 /* bytes per workgroup of the flat-destination kernel                          */
+#define NTP_OPT_RESHARD_TABLE_BLOCK 6 /* bytes per block of the run-table kernel                                    */
+#define NTP_OPT_RESHARD_NO_FLAT 7    /* 1: column-partitioned tensors never take the flat-destination kernel       */
+#define NTP_OPT_RESHARD_NO_TABLE 8   /* 1: plans never take the run-table kernel                                   */
+#define NTP_OPT_COUNT_ 9
+int ntp_set_option(ntp_handle_t* h, int32_t option, int64_t value);
 
 /* ---------------------------------------------------------------------------
  * Shard plan (Sec. 3.1, closing paragraph of "Attention blocks": the partition
@@ -109,7 +152,7 @@ typedef struct ntp_mlp_shape {
  *        as far as they are written                                  (device)
  *   out  Zpart [M x H] bf16                                           (device)
  * P and Y are kept for the backward call.  No buffer may alias another. */
-int ntp_mlp_shard_fwd(const ntp_mlp_shape_t* shape, const void* X, int64_t ldx, const void* A_t,
+int ntp_mlp_shard_fwd(ntp_handle_t* h, const ntp_mlp_shape_t* shape, const void* X, int64_t ldx, const void* A_t,
                       int64_t lda, const void* B, int64_t ldb, void* P, int64_t ldp, void* Y,
                       int64_t ldy, void* Zpart, int64_t ldz, void* stream);
 
@@ -123,7 +166,7 @@ int ntp_mlp_shard_fwd(const ntp_mlp_shape_t* shape, const void* X, int64_t ldx, 
  * wrote them).  dP's pad columns are zeroed like P's (up to the next multiple
  * of 8, or of 64 if lddp and ldp reach it).  accumulate != 0 adds into dA_t / dB instead of overwriting
  * (gradient accumulation over micro-batches before the reshard, Sec. 4.1). */
-int ntp_mlp_shard_bwd(const ntp_mlp_shape_t* shape, const void* dZ, int64_t lddz, const void* X,
+int ntp_mlp_shard_bwd(ntp_handle_t* h, const ntp_mlp_shape_t* shape, const void* dZ, int64_t lddz, const void* X,
                       int64_t ldx, const void* A_t, int64_t lda, const void* B, int64_t ldb,
                       const void* P, int64_t ldp, const void* Y, int64_t ldy, void* dP,
                       int64_t lddp, void* dXpart, int64_t lddx, float* dA_t, int64_t ldda,
@@ -142,7 +185,7 @@ typedef struct ntp_attn_shape {
  * row-parallel half: Zpart = C Wo [M x H] bf16 (Eq. 4) with C [M x w_o] the
  * attention output of this rank's heads.  A half is skipped when its output
  * pointer (QKV resp. Zpart) is NULL. */
-int ntp_attn_proj_shard_fwd(const ntp_attn_shape_t* shape, const void* X, int64_t ldx,
+int ntp_attn_proj_shard_fwd(ntp_handle_t* h, const ntp_attn_shape_t* shape, const void* X, int64_t ldx,
                             const void* Wqkv, int64_t ldwqkv, void* QKV, int64_t ldqkv,
                             const void* C, int64_t ldc, const void* Wo, int64_t ldwo, void* Zpart,
                             int64_t ldz, void* stream);
@@ -153,7 +196,7 @@ int ntp_attn_proj_shard_fwd(const ntp_attn_shape_t* shape, const void* X, int64_
  *   dXpart = dQKV Wqkv [M x H] bf16 (partial sum),  dWqkv = dQKV^T X [w_qkv x H] fp32.
  * The dW of a KV head replicated on several ranks is each rank's partial sum.
  * accumulate != 0 adds into dWqkv / dWo. */
-int ntp_attn_proj_shard_bwd(const ntp_attn_shape_t* shape, const void* dZ, int64_t lddz,
+int ntp_attn_proj_shard_bwd(ntp_handle_t* h, const ntp_attn_shape_t* shape, const void* dZ, int64_t lddz,
                             const void* dQKV, int64_t lddqkv, const void* X, int64_t ldx,
                             const void* C, int64_t ldc, const void* Wqkv, int64_t ldwqkv,
                             const void* Wo, int64_t ldwo, void* dC, int64_t lddc, void* dXpart,
@@ -203,7 +246,7 @@ int ntp_reshard_segments(const ntp_tensor_spec_t* spec, int32_t src_tp, int32_t 
  * either order.  Source and destination must not overlap (checked: INVALID_ARG).
  * Only 2-byte alignment (elem_size 2) or 4-byte alignment (elem_size 4) of
  * pointers is required; 16-byte aligned rows copy fastest. */
-int ntp_reshard_grad(const ntp_tensor_spec_t* spec, int32_t src_tp, int32_t dst_tp,
+int ntp_reshard_grad(ntp_handle_t* h, const ntp_tensor_spec_t* spec, int32_t src_tp, int32_t dst_tp,
                      const void* const* src_shards, const int64_t* src_ld,
                      void* const* dst_shards, const int64_t* dst_ld, void* stream);
 
@@ -231,7 +274,7 @@ typedef struct ntp_attn_core_shape {
   int32_t head_dim;
   int32_t causal;
 } ntp_attn_core_shape_t;
-int ntp_attn_core_shard_fwd(const ntp_attn_core_shape_t* shape, const void* QKV, int64_t ldqkv,
+int ntp_attn_core_shard_fwd(ntp_handle_t* h, const ntp_attn_core_shape_t* shape, const void* QKV, int64_t ldqkv,
                             void* C, int64_t ldc, float* LSE, void* stream);
 /* Gradient of the above: given dC [M x q_cnt head_dim] (what ntp_attn_proj_shard_bwd
  * returns), the forward call's QKV, C and LSE, writes dQKV [M x (q_cnt + 2 kv_cnt)
@@ -240,7 +283,7 @@ int ntp_attn_core_shard_fwd(const ntp_attn_core_shape_t* shape, const void* QKV,
  * that none reads.  Delta: DEVICE scratch, fp32 [q_cnt x M], overwritten (per head
  * and token the dot product of the rows of dC and C).  All matrices bf16, 16-byte
  * aligned, leading dimensions multiples of 8; QKV and dQKV must not overlap. */
-int ntp_attn_core_shard_bwd(const ntp_attn_core_shape_t* shape, const void* QKV, int64_t ldqkv,
+int ntp_attn_core_shard_bwd(ntp_handle_t* h, const ntp_attn_core_shape_t* shape, const void* QKV, int64_t ldqkv,
                             const void* C, int64_t ldc, const void* dC, int64_t lddc,
                             const float* LSE, float* Delta, void* dQKV, int64_t lddqkv,
                             void* stream);
@@ -280,14 +323,14 @@ typedef struct ntp_row_segment {
 int ntp_reshard_row_segments(const ntp_tensor_spec_t* spec, int32_t src_tp, int32_t src_rank,
                              int32_t dst_tp, void* const* dst_shards, const int64_t* dst_ld,
                              ntp_row_segment_t* out, int64_t max_segments, int64_t* count);
-int ntp_mlp_shard_bwd_resharded(const ntp_mlp_shape_t* shape, const void* dZ, int64_t lddz,
+int ntp_mlp_shard_bwd_resharded(ntp_handle_t* h, const ntp_mlp_shape_t* shape, const void* dZ, int64_t lddz,
                                 const void* X, int64_t ldx, const void* A_t, int64_t lda,
                                 const void* B, int64_t ldb, const void* P, int64_t ldp,
                                 const void* Y, int64_t ldy, void* dP, int64_t lddp, void* dXpart,
                                 int64_t lddx, const ntp_row_segment_t* dA_segs, int32_t n_dA_segs,
                                 const ntp_row_segment_t* dB_segs, int32_t n_dB_segs,
                                 int32_t accumulate, void* stream);
-int ntp_attn_proj_shard_bwd_resharded(const ntp_attn_shape_t* shape, const void* dZ, int64_t lddz,
+int ntp_attn_proj_shard_bwd_resharded(ntp_handle_t* h, const ntp_attn_shape_t* shape, const void* dZ, int64_t lddz,
                                       const void* dQKV, int64_t lddqkv, const void* X, int64_t ldx,
                                       const void* C, int64_t ldc, const void* Wqkv, int64_t ldwqkv,
                                       const void* Wo, int64_t ldwo, void* dC, int64_t lddc,
@@ -335,17 +378,22 @@ int ntp_comp_sync_plan(int64_t k, int32_t full_tp, int32_t reduced_tp, int32_t* 
  *   splits of s).  HOST array of src_tp * dst_tp entries, written.
  * ntp_reshard_plan_table: for every destination unit, destination shards one
  *   after the other, the source rank and the local unit in its shard.
+ * ntp_reshard_plan_prepare: makes the plan ready to run on the CURRENT device.
+ *   Plans of column-partitioned tensors of 4-byte elements have a run table (2
+ *   bytes per unit + 16 bytes per sub-shard) that one of the copy kernels reads
+ *   from device memory: this call allocates it (hipMalloc) and waits for its
+ *   upload.  It is the only call of the library that allocates device memory or
+ *   blocks; every plan needs it once before its first run (for plans without a
+ *   table it only records the device).  Calling it again on the same device does
+ *   nothing; on another device -> INVALID_ARG.
  * ntp_reshard_plan_run: enqueue the copy; shard arrays, NULL shards, alignment
- *   and aliasing rules as for ntp_reshard_grad.  Column-partitioned tensors of
+ *   and aliasing rules as for ntp_reshard_grad.  Allocates nothing and never
+ *   waits, so a run can be captured into a HIP graph.  A plan that was not
+ *   prepared, or was prepared on another device than the current one ->
+ *   NTP_ERR_NOT_PREPARED, nothing is enqueued.  Column-partitioned tensors of
  *   4-byte elements whose shards are all on this GPU, with dense 64-byte aligned
- *   destinations, go through a kernel that reads the plan's run table from
- *   device memory: the FIRST such run allocates the table (2 bytes per unit +
- *   16 bytes per sub-shard) on the current device and waits for its upload;
- *   later runs must use the same device (else INVALID_ARG) and allocate
- *   nothing.  Everything else is copied sub-shard by sub-shard.
- * ntp_reshard_plan_prepare: does that allocation and upload now, on the current
- *   device, so that no run of the plan allocates or waits (a run can then be
- *   captured into a HIP graph).  A plan that has no table is left as it is.
+ *   destinations, go through the run-table kernel; everything else is copied
+ *   sub-shard by sub-shard.
  * ntp_reshard_plan_destroy: frees the handle and its device table; no run of
  *   the plan may still be in flight.  NULL is accepted. */
 typedef struct ntp_reshard_plan ntp_reshard_plan_t;
@@ -362,7 +410,7 @@ int ntp_reshard_plan_splits(const ntp_reshard_plan_t* plan, int64_t* units);
 int ntp_reshard_plan_table(const ntp_reshard_plan_t* plan, ntp_unit_source_t* out,
                            int64_t max_units, int64_t* count);
 int ntp_reshard_plan_prepare(ntp_reshard_plan_t* plan);
-int ntp_reshard_plan_run(ntp_reshard_plan_t* plan, const void* const* src_shards,
+int ntp_reshard_plan_run(ntp_handle_t* h, ntp_reshard_plan_t* plan, const void* const* src_shards,
                          const int64_t* src_ld, void* const* dst_shards, const int64_t* dst_ld,
                          void* stream);
 int ntp_reshard_plan_destroy(ntp_reshard_plan_t* plan);
@@ -373,9 +421,9 @@ int ntp_reshard_plan_destroy(ntp_reshard_plan_t* plan);
  * recorded with its algorithmic work: flops = 2 M N K on the logical GEMM
  * dimensions, bytes = bytes read + bytes written by a reshard launch.  This is
  * the only part of the library that creates HIP objects (events); it is off by
- * default.  ntp_kernel_timing_read waits for the recorded kernels, writes at
- * most max_records entries (launch order), stores the number of launches
- * recorded in *count and clears the list. */
+ * default and per handle.  ntp_kernel_timing_read waits for the recorded
+ * kernels, writes at most max_records entries (launch order), stores the number
+ * of launches recorded in *count and clears the list. */
 typedef struct ntp_kernel_time {
   char name[48]; /* kernel family and variant, e.g. "gemm_tn_f32"  */
   double flops;  /* algorithmic flops of this launch (0 for copies)  */
@@ -383,32 +431,46 @@ typedef struct ntp_kernel_time {
   float ms;      /* duration between the two events                  */
   int32_t pad_;
 } ntp_kernel_time_t;
-int ntp_kernel_timing_enable(int32_t on);
-int ntp_kernel_timing_read(ntp_kernel_time_t* out, int64_t max_records, int64_t* count);
+int ntp_kernel_timing_enable(ntp_handle_t* h, int32_t on);
+int ntp_kernel_timing_read(ntp_handle_t* h, ntp_kernel_time_t* out, int64_t max_records, int64_t* count);
 
 /* Workspace for split-K (Sec. 3.1: at a high TP degree a column-parallel shard X A_i or
  * X W_qkv,i is a skinny GEMM with fewer output tiles than the GPU has compute units).
- * With a workspace registered, a shard GEMM whose output tiles would leave most compute
- * units idle is also cut along its contraction axis: fp32 partial sums go to the
+ * With a workspace set on the handle, a shard GEMM whose output tiles would leave most
+ * compute units idle is also cut along its contraction axis: fp32 partial sums go to the
  * workspace and a second kernel adds them in a fixed order and applies the epilogue
  * (results stay deterministic; they differ from the unsplit GEMM by fp32 rounding order).
  * The attention core uses it the same way when a rank has few heads (Eq. 5 on 2-3
  * heads of a long sequence is fewer workgroups than compute units): every workgroup's
  * walk over the key (or query) tiles is cut into parts that store fp32 partial results,
  * merged by a second kernel (forward: by running maximum and sum).
- *   workspace  device pointer, 256-byte aligned; NULL with bytes == 0 unregisters
+ *   workspace  device pointer, 256-byte aligned; NULL with bytes == 0 removes it
  *   bytes      its size; a GEMM is split only if splits * M * round_up(N, 16) * 4 fits,
  *              a walk cut only if workgroups * parts * 64 rows * row bytes fits
- *              (ntp_gemm_choice / ntp_attn_core_choice tell what a shape gets)
- * The caller owns the memory and keeps it alive while registered.  One workspace per
- * process: shard calls that may use it must not overlap in time (same stream, or
- * ordered across streams), on one device.  Without a workspace nothing is ever split.
- * Errors: NTP_ERR_INVALID_ARG (misaligned, negative size, NULL with bytes > 0). */
-int ntp_set_workspace(void* workspace, int64_t bytes);
+ * The caller owns the memory and keeps it alive while it is set.  The workspace belongs
+ * to the handle: calls on this handle that may use it must be ordered on the device
+ * (one stream, or events between streams); to run shard calls concurrently on several
+ * streams (the gradient sync beside the backward pass, Sec. 4.1), give each stream a
+ * handle and a workspace of its own.  Without a workspace nothing is ever split.
+ * Errors: NTP_ERR_INVALID_ARG (misaligned, negative size, NULL with bytes > 0).
+ *
+ * ntp_workspace_bytes (host only): the largest workspace that the forward or backward
+ * call of a shape can use on this handle's device, i.e. what its launch decisions would
+ * take if the workspace were unlimited (0: nothing would be split); a smaller workspace
+ * is legal and leaves some launches unsplit.  call / shape:
+ *   NTP_CALL_MLP_SHARD        const ntp_mlp_shape_t*        ntp_mlp_shard_fwd, _bwd, _bwd_resharded
+ *   NTP_CALL_ATTN_PROJ_SHARD  const ntp_attn_shape_t*       ntp_attn_proj_shard_fwd, _bwd, _bwd_resharded
+ *   NTP_CALL_ATTN_CORE_SHARD  const ntp_attn_core_shape_t*  ntp_attn_core_shard_fwd, _bwd
+ * Errors: NTP_ERR_INVALID_ARG (NULL, unknown call, a shape the call itself would refuse). */
+#define NTP_CALL_MLP_SHARD 0
+#define NTP_CALL_ATTN_PROJ_SHARD 1
+#define NTP_CALL_ATTN_CORE_SHARD 2
+int ntp_workspace_bytes(const ntp_handle_t* h, int32_t call, const void* shape, int64_t* bytes);
+int ntp_set_workspace(ntp_handle_t* h, void* workspace, int64_t bytes);
 
 /* Diagnostic aid (host only, touches no device memory): which GEMM kernel a shard GEMM
- * of this shape would run, with the workspace registered at the time of the call and
- * tightly packed operands.  layout: 0 both operands K-contiguous (column-parallel
+ * of this shape would run on this handle (its compute units, workspace and options at
+ * the time of the call), with tightly packed operands.  layout: 0 both operands K-contiguous (column-parallel
  * forward, activation gradients of row-parallel layers), 1 A K-contiguous and B
  * K-strided (row-parallel forward, partial input gradients), 2 both K-strided (weight
  * gradients).  M, N >= 1, K >= 0.
@@ -421,10 +483,10 @@ int ntp_set_workspace(void* workspace, int64_t bytes);
 typedef struct ntp_gemm_choice {
   int32_t tile_m, tile_n, wavefronts, ring, k_splits, persistent;
 } ntp_gemm_choice_t;
-int ntp_gemm_choice(int32_t layout, int64_t M, int64_t N, int64_t K, ntp_gemm_choice_t* out);
+int ntp_gemm_choice(const ntp_handle_t* h, int32_t layout, int64_t M, int64_t N, int64_t K, ntp_gemm_choice_t* out);
 
 /* Diagnostic aid (host only): launch decisions of the attention core kernels for a shape,
- * with the workspace registered at the time of the call.
+ * on this handle (its workspace and options at the time of the call).
  *   fwd_rows_per_wavefront  16 or 32 query rows per wavefront in the forward kernel
  *   fwd_parts, dq_parts, dkv_parts  > 1: every workgroup's walk is cut into that many parts
  *                                   (fp32 partial results in the workspace, merged by a second kernel)
@@ -432,13 +494,13 @@ int ntp_gemm_choice(int32_t layout, int64_t M, int64_t N, int64_t K, ntp_gemm_ch
 typedef struct ntp_attn_core_choice {
   int32_t fwd_rows_per_wavefront, fwd_parts, dq_parts, dkv_parts;
 } ntp_attn_core_choice_t;
-int ntp_attn_core_choice(const ntp_attn_core_shape_t* shape, ntp_attn_core_choice_t* out);
+int ntp_attn_core_choice(const ntp_handle_t* h, const ntp_attn_core_shape_t* shape, ntp_attn_core_choice_t* out);
 
 /* Measurement aid: a plain dense device-to-device copy of `bytes` bytes (dst, src:
  * device, 16-byte aligned, bytes % 16 == 0, not overlapping) by a kernel named
  * calibration_copy_kernel.  Its known traffic (bytes read, bytes written) is what
  * the profiler's HBM byte counters are scaled by when a kernel's traffic is reported. */
-int ntp_calibration_copy(void* dst, const void* src, int64_t bytes, void* stream);
+int ntp_calibration_copy(ntp_handle_t* h, void* dst, const void* src, int64_t bytes, void* stream);
 
 #ifdef __cplusplus
 }

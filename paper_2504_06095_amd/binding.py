@@ -17,6 +17,23 @@ NTP_ERR_INVALID_ARG = -1
 NTP_ERR_ALIGNMENT = -2
 NTP_ERR_LAUNCH = -3
 NTP_ERR_UNSUPPORTED = -4
+NTP_ERR_NOT_PREPARED = -5
+NTP_ERR_NO_DEVICE = -6
+NTP_OPT_GEMM_TILE = 0
+NTP_OPT_GEMM_SPLIT = 1
+NTP_OPT_GEMM_NO_RING_TAIL = 2
+NTP_OPT_ATTN_PARTS = 3
+NTP_OPT_RESHARD_BLOCK = 4
+NTP_OPT_RESHARD_FLAT_BLOCK = 5
+NTP_OPT_RESHARD_TABLE_BLOCK = 6
+NTP_OPT_RESHARD_NO_FLAT = 7
+NTP_OPT_RESHARD_NO_TABLE = 8
+NTP_CALL_MLP_SHARD = 0
+NTP_CALL_ATTN_PROJ_SHARD = 1
+NTP_CALL_ATTN_CORE_SHARD = 2
+# NTP_OPT_GEMM_TILE values by name
+GEMM_TILES = {"auto": 0, "generic": 1, "256x256": 2, "256x224": 3, "224x256": 4, "256x192": 5, "192x256": 6,
+              "256x128": 7, "128x256": 8, "128x128": 9, "128x128w8": 10}
 NTP_GELU_ERF = 0
 NTP_GELU_TANH = 1
 NTP_KIND_PLAIN = 0
@@ -29,7 +46,8 @@ EXPORTS = (
     "ntp_comp_sync_plan", "ntp_reshard_plan_create", "ntp_reshard_plan_segments", "ntp_reshard_plan_splits",
     "ntp_reshard_plan_table", "ntp_reshard_plan_prepare", "ntp_reshard_plan_run", "ntp_reshard_plan_destroy", "ntp_reshard_row_segments",
     "ntp_mlp_shard_bwd_resharded", "ntp_attn_proj_shard_bwd_resharded", "ntp_attn_core_shard_fwd", "ntp_attn_core_shard_bwd",
-    "ntp_set_workspace", "ntp_gemm_choice", "ntp_attn_core_choice",
+    "ntp_set_workspace", "ntp_gemm_choice", "ntp_attn_core_choice", "ntp_create", "ntp_destroy", "ntp_device_info",
+    "ntp_set_option", "ntp_workspace_bytes",
 )
 
 
@@ -105,13 +123,18 @@ def lib() -> C.CDLL:
         L.ntp_shard_plan.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
         L.ntp_attn_shard_plan.argtypes = [C.c_int32] * 5 + [C.POINTER(AttnPlan)]
         vp, i64 = C.c_void_p, C.c_int64
-        L.ntp_mlp_shard_fwd.argtypes = [C.POINTER(MlpShape)] + [vp, i64] * 6 + [vp]
-        L.ntp_mlp_shard_bwd.argtypes = [C.POINTER(MlpShape)] + [vp, i64] * 10 + [C.c_int32, vp]
-        L.ntp_attn_proj_shard_fwd.argtypes = [C.POINTER(AttnShape)] + [vp, i64] * 6 + [vp]
-        L.ntp_attn_proj_shard_bwd.argtypes = [C.POINTER(AttnShape)] + [vp, i64] * 10 + [C.c_int32, vp]
+        L.ntp_create.argtypes = [C.POINTER(vp)]
+        L.ntp_destroy.argtypes = [vp]
+        L.ntp_device_info.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+        L.ntp_set_option.argtypes = [vp, C.c_int32, i64]
+        L.ntp_workspace_bytes.argtypes = [vp, C.c_int32, vp, C.POINTER(i64)]
+        L.ntp_mlp_shard_fwd.argtypes = [vp, C.POINTER(MlpShape)] + [vp, i64] * 6 + [vp]
+        L.ntp_mlp_shard_bwd.argtypes = [vp, C.POINTER(MlpShape)] + [vp, i64] * 10 + [C.c_int32, vp]
+        L.ntp_attn_proj_shard_fwd.argtypes = [vp, C.POINTER(AttnShape)] + [vp, i64] * 6 + [vp]
+        L.ntp_attn_proj_shard_bwd.argtypes = [vp, C.POINTER(AttnShape)] + [vp, i64] * 10 + [C.c_int32, vp]
         L.ntp_reshard_segments.argtypes = [C.POINTER(TensorSpec), C.c_int32, C.c_int32, C.POINTER(Segment), i64,
                                            C.POINTER(i64)]
-        L.ntp_reshard_grad.argtypes = [C.POINTER(TensorSpec), C.c_int32, C.c_int32, C.POINTER(vp), C.POINTER(i64),
+        L.ntp_reshard_grad.argtypes = [vp, C.POINTER(TensorSpec), C.c_int32, C.c_int32, C.POINTER(vp), C.POINTER(i64),
                                        C.POINTER(vp), C.POINTER(i64), vp]
         i32p = C.POINTER(C.c_int32)
         L.ntp_comp_sync_plan.argtypes = [i64, C.c_int32, C.c_int32, i32p, i32p]
@@ -120,23 +143,23 @@ def lib() -> C.CDLL:
         L.ntp_reshard_plan_splits.argtypes = [vp, C.POINTER(i64)]
         L.ntp_reshard_plan_table.argtypes = [vp, C.POINTER(UnitSource), i64, C.POINTER(i64)]
         L.ntp_reshard_plan_prepare.argtypes = [vp]
-        L.ntp_reshard_plan_run.argtypes = [vp, C.POINTER(vp), C.POINTER(i64), C.POINTER(vp), C.POINTER(i64), vp]
+        L.ntp_reshard_plan_run.argtypes = [vp, vp, C.POINTER(vp), C.POINTER(i64), C.POINTER(vp), C.POINTER(i64), vp]
         L.ntp_reshard_plan_destroy.argtypes = [vp]
         segp = C.POINTER(RowSegment)
         L.ntp_reshard_row_segments.argtypes = [C.POINTER(TensorSpec), C.c_int32, C.c_int32, C.c_int32, C.POINTER(vp),
                                                C.POINTER(i64), segp, i64, C.POINTER(i64)]
-        L.ntp_mlp_shard_bwd_resharded.argtypes = ([C.POINTER(MlpShape)] + [vp, i64] * 8 + [segp, C.c_int32, segp, C.c_int32]
+        L.ntp_mlp_shard_bwd_resharded.argtypes = ([vp, C.POINTER(MlpShape)] + [vp, i64] * 8 + [segp, C.c_int32, segp, C.c_int32]
                                                   + [C.c_int32, vp])
-        L.ntp_attn_proj_shard_bwd_resharded.argtypes = ([C.POINTER(AttnShape)] + [vp, i64] * 8
+        L.ntp_attn_proj_shard_bwd_resharded.argtypes = ([vp, C.POINTER(AttnShape)] + [vp, i64] * 8
                                                         + [segp, C.c_int32, segp, C.c_int32] + [C.c_int32, vp])
-        L.ntp_attn_core_shard_fwd.argtypes = [C.POINTER(AttnCoreShape), vp, i64, vp, i64, vp, vp]
-        L.ntp_attn_core_shard_bwd.argtypes = [C.POINTER(AttnCoreShape), vp, i64, vp, i64, vp, i64, vp, vp, vp, i64, vp]
-        L.ntp_kernel_timing_enable.argtypes = [C.c_int32]
-        L.ntp_kernel_timing_read.argtypes = [C.POINTER(KernelTime), i64, C.POINTER(i64)]
-        L.ntp_calibration_copy.argtypes = [vp, vp, i64, vp]
-        L.ntp_set_workspace.argtypes = [vp, i64]
-        L.ntp_gemm_choice.argtypes = [C.c_int32, i64, i64, i64, C.POINTER(GemmChoice)]
-        L.ntp_attn_core_choice.argtypes = [C.POINTER(AttnCoreShape), C.POINTER(AttnCoreChoice)]
+        L.ntp_attn_core_shard_fwd.argtypes = [vp, C.POINTER(AttnCoreShape), vp, i64, vp, i64, vp, vp]
+        L.ntp_attn_core_shard_bwd.argtypes = [vp, C.POINTER(AttnCoreShape), vp, i64, vp, i64, vp, i64, vp, vp, vp, i64, vp]
+        L.ntp_kernel_timing_enable.argtypes = [vp, C.c_int32]
+        L.ntp_kernel_timing_read.argtypes = [vp, C.POINTER(KernelTime), i64, C.POINTER(i64)]
+        L.ntp_calibration_copy.argtypes = [vp, vp, vp, i64, vp]
+        L.ntp_set_workspace.argtypes = [vp, vp, i64]
+        L.ntp_gemm_choice.argtypes = [vp, C.c_int32, i64, i64, i64, C.POINTER(GemmChoice)]
+        L.ntp_attn_core_choice.argtypes = [vp, C.POINTER(AttnCoreShape), C.POINTER(AttnCoreChoice)]
         for name in EXPORTS:
             getattr(L, name)  # AttributeError if a declared symbol is not exported
         _lib = L
@@ -168,6 +191,76 @@ def _mat(t, dtype=None):
     if not t.is_cuda:
         raise ValueError("expected a device tensor")
     return t.data_ptr(), int(t.stride(0))
+
+
+# ---- handle ----------------------------------------------------------------------
+class Handle:
+    """An ntp_handle_t (ntp_create / ntp_destroy); keeps the workspace tensor it was given alive."""
+
+    def __init__(self):
+        self._h = C.c_void_p()
+        self.workspace = None
+        _check(lib().ntp_create(C.byref(self._h)), "ntp_create")
+
+    @property
+    def ptr(self):
+        return self._h
+
+    def destroy(self) -> None:
+        if self._h:
+            _check(lib().ntp_destroy(self._h), "ntp_destroy")
+            self._h = C.c_void_p()
+            self.workspace = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+_default = None
+
+
+def default_handle() -> Handle:
+    """The handle that calls without a `handle=` argument use (created on first use, on the device that is
+    current then)."""
+    global _default
+    if _default is None:
+        _default = Handle()
+    return _default
+
+
+def _h(handle):
+    return (handle or default_handle()).ptr
+
+
+def ntp_create() -> Handle:
+    return Handle()
+
+
+def ntp_destroy(handle: Handle) -> None:
+    handle.destroy()
+
+
+def ntp_device_info(handle: Handle | None = None) -> dict:
+    dev, cus = C.c_int32(), C.c_int32()
+    _check(lib().ntp_device_info(_h(handle), C.byref(dev), C.byref(cus)), "ntp_device_info")
+    return dict(device=dev.value, compute_units=cus.value)
+
+
+def ntp_set_option(option: int, value, handle: Handle | None = None) -> None:
+    """Tuning override of a handle; NTP_OPT_GEMM_TILE also takes a name from GEMM_TILES."""
+    if option == NTP_OPT_GEMM_TILE and isinstance(value, str):
+        value = GEMM_TILES[value]
+    _check(lib().ntp_set_option(_h(handle), option, int(value)), "ntp_set_option")
+
+
+def ntp_workspace_bytes(call: int, shape, handle: Handle | None = None) -> int:
+    """Largest workspace the call of this shape (MlpShape, AttnShape or AttnCoreShape) can use."""
+    n = C.c_int64()
+    _check(lib().ntp_workspace_bytes(_h(handle), call, C.byref(shape), C.byref(n)), "ntp_workspace_bytes")
+    return n.value
 
 
 # ---- host-only calls -------------------------------------------------------------
@@ -202,7 +295,7 @@ def ntp_reshard_segments(spec: TensorSpec, src_tp: int, dst_tp: int) -> list[tup
 
 
 # ---- device calls ----------------------------------------------------------------
-def ntp_mlp_shard_fwd(X, A_t, B, P, Y, Zpart, n_r: int, gelu_mode: int = NTP_GELU_ERF) -> None:
+def ntp_mlp_shard_fwd(X, A_t, B, P, Y, Zpart, n_r: int, gelu_mode: int = NTP_GELU_ERF, handle=None) -> None:
     """X [M,H], A_t [n_r,H], B [n_r,H] bf16 -> P, Y [M, >=n_r] and Zpart [M,H] bf16 (all preallocated)."""
     import torch
     bf = torch.bfloat16
@@ -210,11 +303,11 @@ def ntp_mlp_shard_fwd(X, A_t, B, P, Y, Zpart, n_r: int, gelu_mode: int = NTP_GEL
     args = []
     for t in (X, A_t, B, P, Y, Zpart):
         args += list(_mat(t, bf))
-    _check(lib().ntp_mlp_shard_fwd(C.byref(shape), *args, _stream()), "ntp_mlp_shard_fwd")
+    _check(lib().ntp_mlp_shard_fwd(_h(handle), C.byref(shape), *args, _stream()), "ntp_mlp_shard_fwd")
 
 
 def ntp_mlp_shard_bwd(dZ, X, A_t, B, P, Y, dP, dXpart, dA_t, dB, n_r: int, gelu_mode: int = NTP_GELU_ERF,
-                      accumulate: bool = False) -> None:
+                      accumulate: bool = False, handle=None) -> None:
     import torch
     bf, f32 = torch.bfloat16, torch.float32
     shape = MlpShape(X.shape[0], X.shape[1], n_r, gelu_mode)
@@ -223,21 +316,21 @@ def ntp_mlp_shard_bwd(dZ, X, A_t, B, P, Y, dP, dXpart, dA_t, dB, n_r: int, gelu_
         args += list(_mat(t, bf))
     for t in (dA_t, dB):
         args += list(_mat(t, f32))
-    _check(lib().ntp_mlp_shard_bwd(C.byref(shape), *args, int(bool(accumulate)), _stream()), "ntp_mlp_shard_bwd")
+    _check(lib().ntp_mlp_shard_bwd(_h(handle), C.byref(shape), *args, int(bool(accumulate)), _stream()), "ntp_mlp_shard_bwd")
 
 
-def ntp_attn_proj_shard_fwd(M, H, w_qkv, w_o, X=None, Wqkv=None, QKV=None, C_=None, Wo=None, Zpart=None) -> None:
+def ntp_attn_proj_shard_fwd(M, H, w_qkv, w_o, X=None, Wqkv=None, QKV=None, C_=None, Wo=None, Zpart=None, handle=None) -> None:
     import torch
     bf = torch.bfloat16
     shape = AttnShape(M, H, w_qkv, w_o)
     args = []
     for t in (X, Wqkv, QKV, C_, Wo, Zpart):
         args += list(_mat(t, bf))
-    _check(lib().ntp_attn_proj_shard_fwd(C.byref(shape), *args, _stream()), "ntp_attn_proj_shard_fwd")
+    _check(lib().ntp_attn_proj_shard_fwd(_h(handle), C.byref(shape), *args, _stream()), "ntp_attn_proj_shard_fwd")
 
 
 def ntp_attn_proj_shard_bwd(M, H, w_qkv, w_o, dZ=None, dQKV=None, X=None, C_=None, Wqkv=None, Wo=None, dC=None,
-                            dXpart=None, dWqkv=None, dWo=None, accumulate: bool = False) -> None:
+                            dXpart=None, dWqkv=None, dWo=None, accumulate: bool = False, handle=None) -> None:
     import torch
     bf, f32 = torch.bfloat16, torch.float32
     shape = AttnShape(M, H, w_qkv, w_o)
@@ -246,7 +339,7 @@ def ntp_attn_proj_shard_bwd(M, H, w_qkv, w_o, dZ=None, dQKV=None, X=None, C_=Non
         args += list(_mat(t, bf))
     for t in (dWqkv, dWo):
         args += list(_mat(t, f32))
-    _check(lib().ntp_attn_proj_shard_bwd(C.byref(shape), *args, int(bool(accumulate)), _stream()),
+    _check(lib().ntp_attn_proj_shard_bwd(_h(handle), C.byref(shape), *args, int(bool(accumulate)), _stream()),
            "ntp_attn_proj_shard_bwd")
 
 
@@ -256,7 +349,7 @@ def attn_core_shape(n_seq, seq_len, plan: dict, group: int, causal: bool = False
                          plan["head_dim"], int(bool(causal)))
 
 
-def ntp_attn_core_shard_fwd(shape: AttnCoreShape, QKV, C_, LSE=None) -> None:
+def ntp_attn_core_shard_fwd(shape: AttnCoreShape, QKV, C_, LSE=None, handle=None) -> None:
     """QKV [M, (q_cnt + 2 kv_cnt) d] bf16 -> C_ [M, q_cnt d] bf16 and LSE [q_cnt, M] fp32 (optional)."""
     import torch
     q, ldq = _mat(QKV, torch.bfloat16)
@@ -266,10 +359,10 @@ def ntp_attn_core_shard_fwd(shape: AttnCoreShape, QKV, C_, LSE=None) -> None:
         if LSE.dtype != torch.float32 or not LSE.is_contiguous():
             raise TypeError("LSE: contiguous fp32 expected")
         lse = LSE.data_ptr()
-    _check(lib().ntp_attn_core_shard_fwd(C.byref(shape), q, ldq, c, ldc, lse, _stream()), "ntp_attn_core_shard_fwd")
+    _check(lib().ntp_attn_core_shard_fwd(_h(handle), C.byref(shape), q, ldq, c, ldc, lse, _stream()), "ntp_attn_core_shard_fwd")
 
 
-def ntp_attn_core_shard_bwd(shape: AttnCoreShape, QKV, C_, dC, LSE, Delta, dQKV) -> None:
+def ntp_attn_core_shard_bwd(shape: AttnCoreShape, QKV, C_, dC, LSE, Delta, dQKV, handle=None) -> None:
     """Gradient of the attention core: dQKV (QKV's layout) from dC; LSE from the forward call, Delta scratch
     (both contiguous fp32 [q_cnt, M])."""
     import torch
@@ -281,7 +374,7 @@ def ntp_attn_core_shard_bwd(shape: AttnCoreShape, QKV, C_, dC, LSE, Delta, dQKV)
     for t in (LSE, Delta):
         if t.dtype != torch.float32 or not t.is_contiguous() or not t.is_cuda:
             raise TypeError("LSE / Delta: contiguous fp32 device tensors expected")
-    _check(lib().ntp_attn_core_shard_bwd(C.byref(shape), q, ldq, c, ldc, g, ldg, LSE.data_ptr(), Delta.data_ptr(), d, ldd,
+    _check(lib().ntp_attn_core_shard_bwd(_h(handle), C.byref(shape), q, ldq, c, ldc, g, ldg, LSE.data_ptr(), Delta.data_ptr(), d, ldd,
                                          _stream()), "ntp_attn_core_shard_bwd")
 
 
@@ -319,7 +412,7 @@ def row_segments(items):
 
 
 def ntp_mlp_shard_bwd_resharded(dZ, X, A_t, B, P, Y, dP, dXpart, dA_segs, dB_segs, n_r: int,
-                                gelu_mode: int = NTP_GELU_ERF, accumulate: bool = False) -> None:
+                                gelu_mode: int = NTP_GELU_ERF, accumulate: bool = False, handle=None) -> None:
     """As ntp_mlp_shard_bwd; dA_segs / dB_segs are ctypes arrays of RowSegment."""
     import torch
     bf = torch.bfloat16
@@ -327,12 +420,13 @@ def ntp_mlp_shard_bwd_resharded(dZ, X, A_t, B, P, Y, dP, dXpart, dA_segs, dB_seg
     args = []
     for t in (dZ, X, A_t, B, P, Y, dP, dXpart):
         args += list(_mat(t, bf))
-    _check(lib().ntp_mlp_shard_bwd_resharded(C.byref(shape), *args, dA_segs, len(dA_segs), dB_segs, len(dB_segs),
+    _check(lib().ntp_mlp_shard_bwd_resharded(_h(handle), C.byref(shape), *args, dA_segs, len(dA_segs), dB_segs, len(dB_segs),
                                              int(bool(accumulate)), _stream()), "ntp_mlp_shard_bwd_resharded")
 
 
 def ntp_attn_proj_shard_bwd_resharded(M, H, w_qkv, w_o, dZ=None, dQKV=None, X=None, C_=None, Wqkv=None, Wo=None, dC=None,
-                                      dXpart=None, dWqkv_segs=None, dWo_segs=None, accumulate: bool = False) -> None:
+                                      dXpart=None, dWqkv_segs=None, dWo_segs=None, accumulate: bool = False,
+                                      handle=None) -> None:
     """As ntp_attn_proj_shard_bwd; dWqkv_segs / dWo_segs are ctypes arrays of RowSegment."""
     import torch
     bf = torch.bfloat16
@@ -342,7 +436,7 @@ def ntp_attn_proj_shard_bwd_resharded(M, H, w_qkv, w_o, dZ=None, dQKV=None, X=No
         args += list(_mat(t, bf))
     q = dWqkv_segs if dWqkv_segs is not None else (RowSegment * 0)()
     o = dWo_segs if dWo_segs is not None else (RowSegment * 0)()
-    _check(lib().ntp_attn_proj_shard_bwd_resharded(C.byref(shape), *args, q, len(q), o, len(o), int(bool(accumulate)),
+    _check(lib().ntp_attn_proj_shard_bwd_resharded(_h(handle), C.byref(shape), *args, q, len(q), o, len(o), int(bool(accumulate)),
                                                    _stream()), "ntp_attn_proj_shard_bwd_resharded")
 
 
@@ -364,10 +458,10 @@ def _shard_arrays(spec: TensorSpec, src_tp: int, dst_tp: int, src_shards, dst_sh
     return sp, sl, dp, dl
 
 
-def ntp_reshard_grad(spec: TensorSpec, src_tp: int, dst_tp: int, src_shards, dst_shards) -> None:
+def ntp_reshard_grad(spec: TensorSpec, src_tp: int, dst_tp: int, src_shards, dst_shards, handle=None) -> None:
     """src_shards / dst_shards: lists of 2-D device tensors (or None for "not on this GPU")."""
     sp, sl, dp, dl = _shard_arrays(spec, src_tp, dst_tp, src_shards, dst_shards)
-    _check(lib().ntp_reshard_grad(C.byref(spec), src_tp, dst_tp, sp, sl, dp, dl, _stream()), "ntp_reshard_grad")
+    _check(lib().ntp_reshard_grad(_h(handle), C.byref(spec), src_tp, dst_tp, sp, sl, dp, dl, _stream()), "ntp_reshard_grad")
 
 
 class ReshardPlan:
@@ -404,12 +498,12 @@ class ReshardPlan:
         return [(e.src_rank, e.src_unit) for e in buf[: n.value]]
 
     def ntp_reshard_plan_prepare(self) -> None:
-        """Upload the run table now, so that no run of the plan allocates (needed before a graph capture)."""
+        """Make the plan ready to run on the current device (uploads its run table); needed once before the first run."""
         _check(lib().ntp_reshard_plan_prepare(self._h), "ntp_reshard_plan_prepare")
 
-    def ntp_reshard_plan_run(self, src_shards, dst_shards) -> None:
+    def ntp_reshard_plan_run(self, src_shards, dst_shards, handle=None) -> None:
         sp, sl, dp, dl = _shard_arrays(self.spec, self.src_tp, self.dst_tp, src_shards, dst_shards)
-        _check(lib().ntp_reshard_plan_run(self._h, sp, sl, dp, dl, _stream()), "ntp_reshard_plan_run")
+        _check(lib().ntp_reshard_plan_run(_h(handle), self._h, sp, sl, dp, dl, _stream()), "ntp_reshard_plan_run")
 
     def destroy(self) -> None:
         if self._h:
@@ -435,51 +529,48 @@ def ntp_reshard_plan_create(spec: TensorSpec, src_tp: int, src_rank_of_unit, dst
 
 
 # ---- measurement aid ---------------------------------------------------------------
-def ntp_kernel_timing_enable(on: bool) -> None:
-    _check(lib().ntp_kernel_timing_enable(int(bool(on))), "ntp_kernel_timing_enable")
+def ntp_kernel_timing_enable(on: bool, handle=None) -> None:
+    _check(lib().ntp_kernel_timing_enable(_h(handle), int(bool(on))), "ntp_kernel_timing_enable")
 
 
-def ntp_kernel_timing_read(max_records: int = 4096) -> list[dict]:
+def ntp_kernel_timing_read(max_records: int = 4096, handle=None) -> list[dict]:
     """Waits for the recorded launches; returns [{name, flops, bytes, ms}] in launch order."""
     buf = (KernelTime * max_records)()
     n = C.c_int64()
-    _check(lib().ntp_kernel_timing_read(buf, max_records, C.byref(n)), "ntp_kernel_timing_read")
+    _check(lib().ntp_kernel_timing_read(_h(handle), buf, max_records, C.byref(n)), "ntp_kernel_timing_read")
     return [dict(name=r.name.decode(), flops=r.flops, bytes=r.bytes, ms=r.ms) for r in buf[: min(n.value, max_records)]]
 
 
-def ntp_calibration_copy(dst, src) -> None:
+def ntp_calibration_copy(dst, src, handle=None) -> None:
     """Plain dense copy src -> dst (contiguous device tensors of equal byte size)."""
     nbytes = src.numel() * src.element_size()
     if dst.numel() * dst.element_size() != nbytes or not (src.is_contiguous() and dst.is_contiguous()):
         raise ValueError("expected two contiguous tensors of equal byte size")
-    _check(lib().ntp_calibration_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream()), "ntp_calibration_copy")
+    _check(lib().ntp_calibration_copy(_h(handle), dst.data_ptr(), src.data_ptr(), nbytes, _stream()), "ntp_calibration_copy")
 
 
-_workspace = None  # keeps the registered tensor alive
-
-
-def ntp_set_workspace(workspace) -> None:
-    """Register a device tensor (any dtype, contiguous) as the split-K workspace, or None to unregister."""
-    global _workspace
+def ntp_set_workspace(workspace, handle: Handle | None = None) -> None:
+    """Give the handle a device tensor (any dtype, contiguous) as its workspace, or None to remove it."""
+    hd = handle or default_handle()
     if workspace is None:
-        _check(lib().ntp_set_workspace(None, 0), "ntp_set_workspace")
-        _workspace = None
+        _check(lib().ntp_set_workspace(hd.ptr, None, 0), "ntp_set_workspace")
+        hd.workspace = None
         return
     if not workspace.is_contiguous():
         raise ValueError("expected a contiguous tensor")
-    _check(lib().ntp_set_workspace(workspace.data_ptr(), workspace.numel() * workspace.element_size()), "ntp_set_workspace")
-    _workspace = workspace
+    _check(lib().ntp_set_workspace(hd.ptr, workspace.data_ptr(), workspace.numel() * workspace.element_size()), "ntp_set_workspace")
+    hd.workspace = workspace
 
 
-def ntp_gemm_choice(layout: int, M: int, N: int, K: int) -> dict:
+def ntp_gemm_choice(layout: int, M: int, N: int, K: int, handle=None) -> dict:
     """Kernel variant a shard GEMM of this shape would run (host only); layout 0 nt, 1 nn, 2 tn."""
     out = GemmChoice()
-    _check(lib().ntp_gemm_choice(layout, M, N, K, C.byref(out)), "ntp_gemm_choice")
+    _check(lib().ntp_gemm_choice(_h(handle), layout, M, N, K, C.byref(out)), "ntp_gemm_choice")
     return {n: getattr(out, n) for n, _ in GemmChoice._fields_}
 
 
-def ntp_attn_core_choice(shape) -> dict:
+def ntp_attn_core_choice(shape, handle=None) -> dict:
     """Launch decisions of the attention core kernels for an AttnCoreShape (host only)."""
     out = AttnCoreChoice()
-    _check(lib().ntp_attn_core_choice(C.byref(shape), C.byref(out)), "ntp_attn_core_choice")
+    _check(lib().ntp_attn_core_choice(_h(handle), C.byref(shape), C.byref(out)), "ntp_attn_core_choice")
     return {n: getattr(out, n) for n, _ in AttnCoreChoice._fields_}

@@ -791,19 +791,19 @@ __global__ __launch_bounds__(256) void attn_core_part_reduce_kernel(const CoreBw
 }
 
 // Parts to cut each workgroup's walk into, so that a launch of `blocks` workgroups whose longest walk has
-// `walk` tiles fills the GPU: 1 (no cut) unless a workspace is registered that holds the partial sums.
-int choose_parts(int64_t blocks, int64_t walk, int64_t bytes_per_block_part, bool causal) {
-  int64_t ws_bytes = 0;
-  if (!ntp::workspace(&ws_bytes) || blocks <= 0) return 1;
-  // Up to 256 workgroups (no more than compute units): about 1024 parts in all measured best at 64 to 192
-  // workgroups; beyond 12 parts per workgroup the merge costs more than it gains.  Between 256 and 512 workgroups
+// `walk` tiles fills the GPU: 1 (no cut) unless ws_bytes of workspace hold the partial sums.
+int choose_parts(const ntp_handle* h, int64_t ws_bytes, int64_t blocks, int64_t walk, int64_t bytes_per_block_part, bool causal) {
+  if (ws_bytes <= 0 || blocks <= 0) return 1;
+  // Up to one workgroup per compute unit: about 4 parts per compute unit in all measured best at 64 to 192
+  // workgroups; beyond 12 parts per workgroup the merge costs more than it gains.  Up to twice as many workgroups
   // two parts still pay under the causal mask (uneven walks: 448 workgroups, 63 -> 58 us forward) and cost
   // 10 % without it.
+  const int64_t cus = h->compute_units;
   int64_t parts = 1;
-  if (blocks <= 256) parts = std::min<int64_t>({12, (1024 + blocks - 1) / blocks, walk / 4});
-  else if (causal && blocks < 512) parts = std::min<int64_t>(2, walk / 4);
+  if (blocks <= cus) parts = std::min<int64_t>({12, (4 * cus + blocks - 1) / blocks, walk / 4});
+  else if (causal && blocks < 2 * cus) parts = std::min<int64_t>(2, walk / 4);
   // tests reach every cut through this override (1..16 parts at any size)
-  if (const char* f = getenv("NTP_ATTN_PARTS")) parts = std::min(16, std::max(1, atoi(f)));
+  if (const int64_t f = h->opt[NTP_OPT_ATTN_PARTS]) parts = std::min<int64_t>(16, std::max<int64_t>(1, f));
   while (parts > 1 && blocks * parts * bytes_per_block_part > ws_bytes) --parts;
   return int(std::max<int64_t>(parts, 1));
 }
@@ -812,23 +812,28 @@ int choose_parts(int64_t blocks, int64_t walk, int64_t bytes_per_block_part, boo
 struct CoreChoice {
   int fwd_rows;  // query rows per wavefront of the forward kernel: 16 or 32
   int fwd_parts, dq_parts, dkv_parts;
+  int64_t ws_bytes;  // workspace bytes the cut launches use (the largest of the three)
 };
-CoreChoice choose_core(const ntp_attn_core_shape_t* s) {
-  CoreChoice c{16, 1, 1, 1};
+CoreChoice choose_core(const ntp_handle* h, int64_t ws_bytes, const ntp_attn_core_shape_t* s) {
+  CoreChoice c{16, 1, 1, 1, 0};
   const int64_t tiles = (s->seq_len + kBKV - 1) / kBKV;
   // 16-row query blocks per wavefront: two (twice the matrix work per LDS read, two workgroups per CU), or
   // one (three workgroups per CU, twice as many of them) when two would leave compute units short of work
   const int64_t blocks2 = int64_t((s->seq_len + 127) / 128) * s->n_seq * s->q_cnt;
-  c.fwd_rows = blocks2 < (s->causal ? 1024 : 384) ? 16 : 32;
+  c.fwd_rows = blocks2 < (s->causal ? 4 : 1.5) * h->compute_units ? 16 : 32;
   // with few heads even the 64-row workgroups leave compute units idle while each walks over up to
-  // seq_len / 64 key tiles: cut the walks then (needs a registered workspace)
+  // seq_len / 64 key tiles: cut the walks then (needs a workspace)
   const int64_t bq = tiles * s->n_seq * s->q_cnt, bk = tiles * s->n_seq * s->kv_cnt;
-  c.fwd_parts = choose_parts(bq, tiles, int64_t(64) * (s->head_dim + 4) * 4, s->causal != 0);
+  const int64_t bf = int64_t(64) * (s->head_dim + 4) * 4, bdq = int64_t(64) * s->head_dim * 4, bdkv = int64_t(64) * 2 * s->head_dim * 4;
+  c.fwd_parts = choose_parts(h, ws_bytes, bq, tiles, bf, s->causal != 0);
   if (c.fwd_parts > 1) c.fwd_rows = 16;
-  c.dq_parts = choose_parts(bq, tiles, int64_t(64) * s->head_dim * 4, s->causal != 0);
+  c.dq_parts = choose_parts(h, ws_bytes, bq, tiles, bdq, s->causal != 0);
   // a dK/dV workgroup walks over the query tiles of every query head that reads its KV head
   const int64_t heads_per_kv = std::min<int64_t>(s->group, s->q_cnt);
-  c.dkv_parts = choose_parts(bk, heads_per_kv * tiles, int64_t(64) * 2 * s->head_dim * 4, s->causal != 0);
+  c.dkv_parts = choose_parts(h, ws_bytes, bk, heads_per_kv * tiles, bdkv, s->causal != 0);
+  if (c.fwd_parts > 1) c.ws_bytes = std::max(c.ws_bytes, bq * c.fwd_parts * bf);
+  if (c.dq_parts > 1) c.ws_bytes = std::max(c.ws_bytes, bq * c.dq_parts * bdq);
+  if (c.dkv_parts > 1) c.ws_bytes = std::max(c.ws_bytes, bk * c.dkv_parts * bdkv);
   return c;
 }
 
@@ -847,21 +852,30 @@ int check_core_shape(const ntp_attn_core_shape_t* s) {
 
 }  // namespace
 
-extern "C" int ntp_attn_core_choice(const ntp_attn_core_shape_t* s, ntp_attn_core_choice_t* out) {
+int ntp::attn_core_workspace_wish(const ntp_handle* h, const ntp_attn_core_shape_t* s, int64_t* bytes) {
+  const int st = check_core_shape(s);
+  if (st != NTP_OK) return st == NTP_ERR_UNSUPPORTED ? NTP_ERR_INVALID_ARG : st;
+  *bytes = choose_core(h, INT64_MAX / 2, s).ws_bytes;
+  return NTP_OK;
+}
+
+extern "C" int ntp_attn_core_choice(const ntp_handle_t* h, const ntp_attn_core_shape_t* s, ntp_attn_core_choice_t* out) {
   const int st = check_core_shape(s);
   if (st != NTP_OK) return st;
-  if (!out) return NTP_ERR_INVALID_ARG;
-  const CoreChoice c = choose_core(s);
+  if (!h || !out) return NTP_ERR_INVALID_ARG;
+  const CoreChoice c = choose_core(h, h->workspace ? h->workspace_bytes : 0, s);
   *out = ntp_attn_core_choice_t{c.fwd_rows, c.fwd_parts, c.dq_parts, c.dkv_parts};
   return NTP_OK;
 }
 
-extern "C" int ntp_attn_core_shard_fwd(const ntp_attn_core_shape_t* s, const void* QKV, int64_t ldqkv, void* C,
-                                       int64_t ldc, float* LSE, void* stream) {
+extern "C" int ntp_attn_core_shard_fwd(ntp_handle_t* h, const ntp_attn_core_shape_t* s, const void* QKV, int64_t ldqkv,
+                                       void* C, int64_t ldc, float* LSE, void* stream) {
   int st = check_core_shape(s);
   if (st != NTP_OK) return st;
+  if (!h) return NTP_ERR_INVALID_ARG;
   const int64_t M = int64_t(s->n_seq) * s->seq_len;
   if (M == 0 || s->q_cnt == 0) return NTP_OK;
+  if (h->device < 0) return NTP_ERR_NO_DEVICE;
   if (!QKV || !C) return NTP_ERR_INVALID_ARG;
   const int64_t wq = int64_t(s->q_cnt + 2 * s->kv_cnt) * s->head_dim, wo = int64_t(s->q_cnt) * s->head_dim;
   if (ldqkv < wq || ldc < wo) return NTP_ERR_INVALID_ARG;
@@ -884,19 +898,19 @@ extern "C" int ntp_attn_core_shard_fwd(const ntp_attn_core_shape_t* s, const voi
   a.causal = s->causal ? 1 : 0;
   // 16-row query blocks per wavefront: two (twice the matrix work per LDS read, two workgroups per CU), or
   // one (three workgroups per CU, twice as many of them) when two would leave compute units short of work
-  const CoreChoice cc = choose_core(s);
+  const CoreChoice cc = choose_core(h, h->workspace ? h->workspace_bytes : 0, s);
   const int qbw = cc.fwd_rows / 16;
-  a.part_sums = static_cast<float*>(ntp::workspace(nullptr));
+  a.part_sums = static_cast<float*>(h->workspace);
   a.n_parts = cc.fwd_parts;
   a.q_tiles = (s->seq_len + 64 * qbw - 1) / (64 * qbw);
   a.scale_log2 = float(1.4426950408889634 / std::sqrt(double(s->head_dim)));
   const int64_t blocks = int64_t(a.q_tiles) * s->n_seq * s->q_cnt;
   if (blocks * std::max(a.n_parts, 1) > 0x7fffffffll) return NTP_ERR_UNSUPPORTED;
   hipStream_t hs = static_cast<hipStream_t>(stream);
-  if (ntp::timing_on()) {
+  if (ntp::timing_on(h)) {
     char name[48];
     snprintf(name, sizeof(name), "attn_core_fwd%s%s", s->causal ? "_causal" : "", a.n_parts > 1 ? "_cut" : "");
-    ntp::timing_begin(stream, name,
+    ntp::timing_begin(h, stream, name,
                       (s->causal ? 2.0 : 4.0) * double(s->n_seq) * double(s->seq_len) * double(s->seq_len) * s->head_dim * s->q_cnt, 0.0);
   }
   const dim3 grid(uint32_t(blocks * std::max(a.n_parts, 1)));
@@ -917,17 +931,19 @@ extern "C" int ntp_attn_core_shard_fwd(const ntp_attn_core_shape_t* s, const voi
       hipLaunchKernelGGL((attn_core_fwd_merge_kernel<64>), rgrid, dim3(256), 0, hs, a, blocks);
     ok = hipGetLastError() == hipSuccess;
   }
-  ntp::timing_end(stream);
+  ntp::timing_end(h, stream);
   return ok ? NTP_OK : NTP_ERR_LAUNCH;
 }
 
-extern "C" int ntp_attn_core_shard_bwd(const ntp_attn_core_shape_t* s, const void* QKV, int64_t ldqkv, const void* C,
-                                       int64_t ldc, const void* dC, int64_t lddc, const float* LSE, float* Delta,
-                                       void* dQKV, int64_t lddqkv, void* stream) {
+extern "C" int ntp_attn_core_shard_bwd(ntp_handle_t* h, const ntp_attn_core_shape_t* s, const void* QKV, int64_t ldqkv,
+                                       const void* C, int64_t ldc, const void* dC, int64_t lddc, const float* LSE,
+                                       float* Delta, void* dQKV, int64_t lddqkv, void* stream) {
   int st = check_core_shape(s);
   if (st != NTP_OK) return st;
+  if (!h) return NTP_ERR_INVALID_ARG;
   const int64_t M = int64_t(s->n_seq) * s->seq_len;
   if (M == 0 || (s->q_cnt == 0 && s->kv_cnt == 0)) return NTP_OK;
+  if (h->device < 0) return NTP_ERR_NO_DEVICE;
   if (!QKV || !dQKV || (s->q_cnt > 0 && (!C || !dC || !LSE || !Delta))) return NTP_ERR_INVALID_ARG;
   const int64_t wq = int64_t(s->q_cnt + 2 * s->kv_cnt) * s->head_dim, wo = int64_t(s->q_cnt) * s->head_dim;
   if (ldqkv < wq || lddqkv < wq || ldc < wo || lddc < wo) return NTP_ERR_INVALID_ARG;
@@ -967,12 +983,13 @@ extern "C" int ntp_attn_core_shard_bwd(const ntp_attn_core_shape_t* s, const voi
   bool ok = true;
   const int64_t bq = int64_t(a.tiles) * s->n_seq * s->q_cnt, bk = int64_t(key_tiles) * s->n_seq * s->kv_cnt;
   if (bq > 0x7fffffffll || bk > 0x7fffffffll) return NTP_ERR_UNSUPPORTED;
-  a.part_sums = static_cast<float*>(ntp::workspace(nullptr));
+  a.part_sums = static_cast<float*>(h->workspace);
+  const CoreChoice cc = choose_core(h, h->workspace ? h->workspace_bytes : 0, s);
   if (bq > 0) {
     // dQ and delta: three products per (query, key) pair.  With few heads the launch is short of
     // workgroups and each walks over up to seq_len / 64 key tiles: cut the walks then.
-    a.n_parts = choose_core(s).dq_parts;
-    if (ntp::timing_on()) ntp::timing_begin(stream, a.n_parts > 1 ? "attn_core_bwd_dq_cut" : "attn_core_bwd_dq", 3.0 * pair_flops, 0.0);
+    a.n_parts = cc.dq_parts;
+    if (ntp::timing_on(h)) ntp::timing_begin(h, stream, a.n_parts > 1 ? "attn_core_bwd_dq_cut" : "attn_core_bwd_dq", 3.0 * pair_flops, 0.0);
     const dim3 grid(uint32_t(bq * a.n_parts));
     if (s->head_dim == 128)
       hipLaunchKernelGGL((attn_core_bwd_dq_kernel<128, qbw>), grid, dim3(kThreads), 0, hs, a);
@@ -987,15 +1004,15 @@ extern "C" int ntp_attn_core_shard_bwd(const ntp_attn_core_shape_t* s, const voi
         hipLaunchKernelGGL((attn_core_part_reduce_kernel<64, false>), rgrid, dim3(256), 0, hs, a, bq);
       ok = hipGetLastError() == hipSuccess;
     }
-    ntp::timing_end(stream);
+    ntp::timing_end(h, stream);
     if (!ok) return NTP_ERR_LAUNCH;
   }
   if (bk > 0) {
     // dK and dV: four products per pair
     // a workgroup walks over the query tiles of every query head that reads its KV head
     a.tiles = key_tiles;
-    a.n_parts = choose_core(s).dkv_parts;
-    if (ntp::timing_on()) ntp::timing_begin(stream, a.n_parts > 1 ? "attn_core_bwd_dkv_cut" : "attn_core_bwd_dkv", 4.0 * pair_flops, 0.0);
+    a.n_parts = cc.dkv_parts;
+    if (ntp::timing_on(h)) ntp::timing_begin(h, stream, a.n_parts > 1 ? "attn_core_bwd_dkv_cut" : "attn_core_bwd_dkv", 4.0 * pair_flops, 0.0);
     const dim3 grid(uint32_t(bk * a.n_parts));
     if (s->head_dim == 128)
       hipLaunchKernelGGL((attn_core_bwd_dkv_kernel<128, kb>), grid, dim3(kThreads), 0, hs, a);
@@ -1010,7 +1027,7 @@ extern "C" int ntp_attn_core_shard_bwd(const ntp_attn_core_shape_t* s, const voi
         hipLaunchKernelGGL((attn_core_part_reduce_kernel<64, true>), rgrid, dim3(256), 0, hs, a, bk);
       ok = hipGetLastError() == hipSuccess;
     }
-    ntp::timing_end(stream);
+    ntp::timing_end(h, stream);
   }
   return ok ? NTP_OK : NTP_ERR_LAUNCH;
 }

@@ -9,7 +9,7 @@
 
 #include <algorithm>
 #include <cstdio>
-#include <cstdlib>
+#include <cstdint>
 #include <cstring>
 #include <type_traits>
 
@@ -56,18 +56,17 @@ constexpr double kTileRate[3][kNumTileShapes] = {{1.000, 0.957, 0.969, 0.917, 0.
                                                  {1.000, 0.929, 0.986, 0.908, 0.944, 0.770, 0.749, 0.65, 0.53},   // B K-strided
                                                  {1.100, 0.984, 1.000, 0.956, 0.962, 0.797, 0.779, 0.65, 0.53}};  // both K-strided (256x256: its non-persistent form)
 constexpr double kLoneSmallTileRate = 0.43;
-constexpr int kComputeUnits = 256;
 
 // Pick the tile shape with the least estimated time: the busiest compute unit's number of
 // workgroups (they are dealt evenly; co-resident ones share its throughput) times tile area over rate.
-int choose_tile(int64_t M, int64_t N, int layout) {
+int choose_tile(int64_t M, int64_t N, int layout, int cus) {
   int best = 0;
   double best_t = 1e300;
   for (int i = 0; i < kNumTileShapes; ++i) {
     const TileShape& ts = kTileShapes[i];
     const int64_t tiles = ((M + ts.bm - 1) / ts.bm) * ((N + ts.bn - 1) / ts.bn);
-    const int64_t cu_load = (tiles + kComputeUnits - 1) / kComputeUnits;
-    const double rate = ts.waves == 4 && tiles <= kComputeUnits ? kLoneSmallTileRate : kTileRate[layout][i];
+    const int64_t cu_load = (tiles + cus - 1) / cus;
+    const double rate = ts.waves == 4 && tiles <= cus ? kLoneSmallTileRate : kTileRate[layout][i];
     const double t = double(cu_load) * ts.bm * ts.bn / rate;
     if (t < best_t) {
       best_t = t;
@@ -83,23 +82,18 @@ void variant_name(int v, char* out, size_t n) {
   else snprintf(out, n, "%dx%d", kTileShapes[v].bm, kTileShapes[v].bn);
 }
 
-// Variant used for a shape: -1 = generic kernel, else an index into kTileShapes.  The environment
-// variable NTP_GEMM_TILE (generic | 256x256 | 256x224 | ...) overrides the choice; it exists so
-// that tests and tuning runs can reach every variant at any size.
-int choose_variant(const GemmArgs& g, bool ring_ok, int layout) {
-  if (const char* f = getenv("NTP_GEMM_TILE")) {
-    if (!ring_ok || !strcmp(f, "generic")) return -1;
-    for (int i = 0; i < kNumTileShapes; ++i) {
-      char name[16];
-      variant_name(i, name, sizeof(name));
-      if (!strcmp(f, name)) return i;
-    }
+// Variant used for a shape: -1 = generic kernel, else an index into kTileShapes.  The handle's
+// NTP_OPT_GEMM_TILE overrides the choice (1: generic, 2 + i: tile shape i).
+int choose_variant(const ntp_handle* h, const GemmArgs& g, bool ring_ok, int layout) {
+  if (const int64_t f = h->opt[NTP_OPT_GEMM_TILE]) {
+    if (!ring_ok || f == 1) return -1;
+    if (f - 2 < kNumTileShapes) return int(f - 2);
   }
   // the generic 128x128x32 kernel only below two output tiles or two K tiles: from there on the ring kernel
-  // measured faster (config 1, 512 x 586 x 1024: 15 us against 31 us per GEMM)
+  // measured faster (512 x 586 x 1024: 15 us against 31 us per GEMM)
   if (int64_t(g.M) * g.N < 128 * 128 * 2 || g.K < 128) return -1;
   if (!ring_ok) return -1;
-  return choose_tile(g.M, g.n_store, layout);
+  return choose_tile(g.M, g.n_store, layout, h->compute_units);
 }
 
 // (layout, epilogue) pairs the shard layers use have ring instantiations; anything else runs on
@@ -116,9 +110,6 @@ bool ring_combo(bool a_kc, bool b_kc, int epi) {
 // fewer tiles than compute units the K axis is cut as well: `splits` workgroups per tile store fp32
 // partial sums to a caller-provided workspace, and a second kernel adds the slices in ascending
 // order and applies the epilogue.
-void* g_workspace = nullptr;
-int64_t g_workspace_bytes = 0;
-
 struct SplitChoice {
   int tile, splits, k_chunk;
 };
@@ -128,40 +119,39 @@ constexpr int kTileOverhead = 4;            // prologue and epilogue of an outpu
 constexpr double kReduceBytesPerCycle = 2000.0, kReduceFixedCycles = 6000.0;
 constexpr int kMaxSplits = 8, kMinSplitTiles = 8;
 
-double tile_time(int64_t M, int64_t N, int64_t ktiles, int layout, int i, int splits) {
+double tile_time(int64_t M, int64_t N, int64_t ktiles, int layout, int i, int splits, int cus) {
   const TileShape& ts = kTileShapes[i];
   const int64_t tiles = ((M + ts.bm - 1) / ts.bm) * ((N + ts.bn - 1) / ts.bn);
-  const int64_t cu_load = (tiles * splits + kComputeUnits - 1) / kComputeUnits;
-  const double rate = ts.waves == 4 && tiles <= kComputeUnits ? kLoneSmallTileRate : kTileRate[layout][i];
+  const int64_t cu_load = (tiles * splits + cus - 1) / cus;
+  const double rate = ts.waves == 4 && tiles <= cus ? kLoneSmallTileRate : kTileRate[layout][i];
   const int64_t kt = (ktiles + splits - 1) / splits + kTileOverhead;
   return double(cu_load) * double(kt) * kTileCycles * (ts.bm * ts.bn / 65536.0) / rate;
 }
 
 // Least estimated time over (tile shape, splits); splits == 1 means: leave the GEMM as it is.
-SplitChoice choose_split(int64_t M, int64_t N, int64_t K, int layout, int plain_tile, int64_t ldw) {
+// ws_bytes: room for the partial sums (0: never split).
+SplitChoice choose_split(const ntp_handle* h, int64_t ws_bytes, int64_t M, int64_t N, int64_t K, int layout, int plain_tile,
+                         int64_t ldw) {
   SplitChoice best{plain_tile, 1, 0};
   const int64_t ktiles = (K + 63) / 64;
-  int forced = 0;
-  if (const char* f = getenv("NTP_GEMM_SPLIT")) forced = atoi(f);  // 1: never split; n > 1: n chunks if they fit
-  if (!g_workspace || forced == 1) return best;
+  const int cus = h->compute_units;
+  const int forced = int(h->opt[NTP_OPT_GEMM_SPLIT]);  // 1: never split; n > 1: n chunks if they fit
+  const int64_t forced_tile = h->opt[NTP_OPT_GEMM_TILE];
+  if (ws_bytes <= 0 || forced == 1) return best;
   // splitting has to beat the plain launch by a margin: the estimate is coarse
-  double best_t = plain_tile >= 0 ? 0.85 * tile_time(M, N, ktiles, layout, plain_tile, 1) : 1e300;
+  double best_t = plain_tile >= 0 ? 0.85 * tile_time(M, N, ktiles, layout, plain_tile, 1, cus) : 1e300;
   if (forced > 1) best_t = 1e300;
   for (int i = 0; i < kNumTileShapes; ++i) {
     if (!kSplitTile[i]) continue;
-    if (const char* f = getenv("NTP_GEMM_TILE")) {
-      char name[16];
-      variant_name(i, name, sizeof(name));
-      if (strcmp(f, name)) continue;
-    }
+    if (forced_tile >= 2 && forced_tile - 2 != i) continue;
     for (int sp = 2; sp <= kMaxSplits; ++sp) {
       if (forced > 1 && sp != forced) continue;
       const int64_t chunk_tiles = (ktiles + sp - 1) / sp;
       if (forced <= 1 && chunk_tiles < kMinSplitTiles) break;
       if ((sp - 1) * chunk_tiles * 64 >= K) continue;  // the last chunk would be empty
-      if (int64_t(sp) * M * ldw * 4 > g_workspace_bytes) break;
+      if (int64_t(sp) * M * ldw * 4 > ws_bytes) break;
       const double reduce = kReduceFixedCycles + double(M) * double(N) * (4.0 * sp + 4.0) / kReduceBytesPerCycle;
-      const double t = tile_time(M, N, ktiles, layout, i, sp) + reduce;
+      const double t = tile_time(M, N, ktiles, layout, i, sp, cus) + reduce;
       if (t < best_t) {
         best_t = t;
         best = SplitChoice{i, sp, int(chunk_tiles * 64)};
@@ -187,9 +177,10 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmArgs g, co
 }
 
 // Kernel variant (-1 generic, else a tile shape) and K chunks for a GEMM (g: M, N, K, n_store).
-SplitChoice plan_gemm(const GemmArgs& g, int layout, bool ring_ok, bool split_ok, int64_t ldw) {
-  SplitChoice sc{choose_variant(g, ring_ok, layout), 1, 0};
-  if (split_ok && int64_t(g.M) * g.N >= 128 * 128 * 8) sc = choose_split(g.M, g.n_store, g.K, layout, sc.tile, ldw);
+SplitChoice plan_gemm(const ntp_handle* h, int64_t ws_bytes, const GemmArgs& g, int layout, bool ring_ok, bool split_ok,
+                      int64_t ldw) {
+  SplitChoice sc{choose_variant(h, g, ring_ok, layout), 1, 0};
+  if (split_ok && int64_t(g.M) * g.N >= 128 * 128 * 8) sc = choose_split(h, ws_bytes, g.M, g.n_store, g.K, layout, sc.tile, ldw);
   return sc;
 }
 
@@ -199,14 +190,22 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 namespace ntp {
 
-void* workspace(int64_t* bytes) {
-  if (bytes) *bytes = g_workspace_bytes;
-  return g_workspace;
+int64_t gemm_workspace_wish(const ntp_handle* h, int layout, int64_t M, int64_t N, int64_t n_store, int64_t K) {
+  if (M < 1 || N < 1 || K < 1 || M > 0x7fffff00 || N > 0x7fffff00 || K > 0x7fffff00) return 0;
+  GemmArgs g{};
+  g.M = int32_t(M);
+  g.N = int32_t(N);
+  g.K = int32_t(K);
+  g.n_store = int32_t(n_store);
+  const int64_t ldw = (n_store + 15) / 16 * 16;
+  const SplitChoice sc = plan_gemm(h, INT64_MAX / 2, g, layout, true, true, ldw);
+  return sc.splits > 1 ? int64_t(sc.splits) * M * ldw * 4 : 0;
 }
 
-int gemm_launch(const GemmDesc& d, void* stream) {
-  if (d.M < 0 || d.N < 0 || d.K < 0) return NTP_ERR_INVALID_ARG;
+int gemm_launch(ntp_handle* h, const GemmDesc& d, void* stream) {
+  if (!h || d.M < 0 || d.N < 0 || d.K < 0) return NTP_ERR_INVALID_ARG;
   if (d.M == 0 || d.N == 0) return NTP_OK;
+  if (h->device < 0) return NTP_ERR_NO_DEVICE;
   if (d.M > 0x7fffff00 || d.N > 0x7fffff00 || d.K > 0x7fffff00) return NTP_ERR_UNSUPPORTED;
   const bool to_segs = d.n_segs > 0;
   if ((!d.C && !to_segs) || (d.K > 0 && (!d.A || !d.B))) return NTP_ERR_INVALID_ARG;
@@ -283,29 +282,27 @@ int gemm_launch(const GemmDesc& d, void* stream) {
                        b_rows * d.ldb * 2 < (int64_t(1) << 32);
   const int layout = d.a_kc ? (d.b_kc ? 0 : 1) : 2;
   // K tail through the ring (row-parallel layout; K is the ragged shard width): B's lines past K lie past its
-  // extent and read as zeros, A's columns past K are zeros by the caller's word.  NTP_GEMM_RING_TAIL=0
+  // extent and read as zeros, A's columns past K are zeros by the caller's word.  NTP_OPT_GEMM_NO_RING_TAIL
   // switches it off (tests, tuning).
-  g.b_extent = 0xFFFFFFFFu;
-  {
-    const char* sw = getenv("NTP_GEMM_RING_TAIL");
-    if (layout == 1 && ring_ok && d.a_k_pad_64 && d.K % 64 != 0 && d.K >= 128 && d.lda >= (d.K + 63) / 64 * 64 &&
-        !(sw && sw[0] == '0')) {
-      g.ring_tail = 1;
-      g.b_extent = uint32_t(d.K * d.ldb * 2);  // < 4 GiB: ring_ok
-    }
-  }
+  if (layout == 1 && ring_ok && d.a_k_pad_64 && d.K % 64 != 0 && d.K >= 128 && d.lda >= (d.K + 63) / 64 * 64 &&
+      !h->opt[NTP_OPT_GEMM_NO_RING_TAIL])
+    g.ring_tail = 1;
+  // what the DMA loads are range-checked against (< 4 GiB when ring_ok)
+  g.a_extent = uint32_t(std::min<int64_t>(0xFFFFFFFFll, operand_extent_bytes(d.a_kc, d.M, d.K, d.lda, g.ring_tail != 0)));
+  g.b_extent = uint32_t(std::min<int64_t>(0xFFFFFFFFll, operand_extent_bytes(d.b_kc, d.N, d.K, d.ldb, false)));
+  g.resident = h->compute_units;
   // split-K: any (layout, epilogue) whose operands the ring kernel can address, except B K-contiguous
   // with A K-strided (no ring kernel)
   const bool split_ok = a_rows * d.lda * 2 < (int64_t(1) << 32) && b_rows * d.ldb * 2 < (int64_t(1) << 32) && (d.a_kc || !d.b_kc);
   const int64_t ldw = (n_store + 15) / 16 * 16;
-  const SplitChoice sc = plan_gemm(g, layout, ring_ok, split_ok, ldw);
+  const SplitChoice sc = plan_gemm(h, h->workspace ? h->workspace_bytes : 0, g, layout, ring_ok, split_ok, ldw);
   const int variant = sc.tile;
-  if (ntp::timing_on()) {
+  if (ntp::timing_on(h)) {
     char name[48], vn[16], sn[8] = "";
     variant_name(variant, vn, sizeof(vn));
     if (sc.splits > 1) snprintf(sn, sizeof(sn), "k%d", sc.splits);
     snprintf(name, sizeof(name), "gemm_%c%c_%s_%s%s", d.a_kc ? 'n' : 't', d.b_kc ? 't' : 'n', kEpiName[d.epilogue], vn, sn);
-    ntp::timing_begin(stream, name, 2.0 * double(d.M) * double(d.N) * double(d.K), 0.0);
+    ntp::timing_begin(h, stream, name, 2.0 * double(d.M) * double(d.N) * double(d.K), 0.0);
   }
   int st;
   if (layout == 2 && variant == 0 && sc.splits == 1 && ring_ok) {
@@ -319,8 +316,8 @@ int gemm_launch(const GemmDesc& d, void* stream) {
   } else if (sc.splits > 1) {
     GemmArgs gp = g;  // the partial-sum launch: fp32 to the workspace, no row segments
     gp.ring_tail = 0;
-    gp.b_extent = 0xFFFFFFFFu;
-    gp.C = g_workspace;
+    gp.a_extent = uint32_t(operand_extent_bytes(d.a_kc, d.M, d.K, d.lda, false));
+    gp.C = h->workspace;
     gp.ldc = ldw;
     gp.n_segs = 0;
     gp.k_splits = sc.splits;
@@ -332,7 +329,7 @@ int gemm_launch(const GemmDesc& d, void* stream) {
     if (st == NTP_OK) {
       const int64_t threads = int64_t(d.M) * (n_store / 4);
       const dim3 grid(uint32_t((threads + 255) / 256)), block(256);
-      const float* ws = static_cast<const float*>(g_workspace);
+      const float* ws = static_cast<const float*>(h->workspace);
       st = dispatch_epilogue(d.epilogue, [&](auto e) {
         hipLaunchKernelGGL((splitk_reduce_kernel<decltype(e)::value>), grid, block, 0, s, g, ws, gp.split_stride, ldw, sc.splits);
         return hipGetLastError() == hipSuccess ? NTP_OK : NTP_ERR_LAUNCH;
@@ -346,21 +343,21 @@ int gemm_launch(const GemmDesc& d, void* stream) {
   else if (d.a_kc && !d.b_kc) st = launch_generic<true, false>(g, d.epilogue, s);
   else if (!d.a_kc && !d.b_kc) st = launch_generic<false, false>(g, d.epilogue, s);
   else st = launch_generic<false, true>(g, d.epilogue, s);
-  ntp::timing_end(stream);
+  ntp::timing_end(h, stream);
   return st;
 }
 
 }  // namespace ntp
 
-extern "C" int ntp_gemm_choice(int32_t layout, int64_t M, int64_t N, int64_t K, ntp_gemm_choice_t* out) {
-  if (!out || layout < 0 || layout > 2 || M < 1 || N < 1 || K < 0 || M > 0x7fffff00 || N > 0x7fffff00 || K > 0x7fffff00)
+extern "C" int ntp_gemm_choice(const ntp_handle_t* h, int32_t layout, int64_t M, int64_t N, int64_t K, ntp_gemm_choice_t* out) {
+  if (!h || !out || layout < 0 || layout > 2 || M < 1 || N < 1 || K < 0 || M > 0x7fffff00 || N > 0x7fffff00 || K > 0x7fffff00)
     return NTP_ERR_INVALID_ARG;
   GemmArgs g{};
   g.M = int32_t(M);
   g.N = int32_t(N);
   g.K = int32_t(K);
   g.n_store = int32_t((N + 7) / 8 * 8);
-  const SplitChoice sc = plan_gemm(g, layout, true, true, (g.n_store + 15) / 16 * 16);
+  const SplitChoice sc = plan_gemm(h, h->workspace ? h->workspace_bytes : 0, g, layout, true, true, (g.n_store + 15) / 16 * 16);
   *out = ntp_gemm_choice_t{};
   out->k_splits = sc.splits;
   if (sc.tile < 0) {
@@ -374,12 +371,5 @@ extern "C" int ntp_gemm_choice(int32_t layout, int64_t M, int64_t N, int64_t K, 
     out->ring = 1;
   }
   out->persistent = sc.tile >= 0 && sc.splits == 1 && !(layout == 2 && sc.tile == 0) ? 1 : 0;
-  return NTP_OK;
-}
-
-extern "C" int ntp_set_workspace(void* workspace, int64_t bytes) {
-  if (bytes < 0 || (bytes > 0 && !workspace) || (reinterpret_cast<uintptr_t>(workspace) & 255)) return NTP_ERR_INVALID_ARG;
-  g_workspace = bytes > 0 ? workspace : nullptr;
-  g_workspace_bytes = bytes > 0 ? bytes : 0;
   return NTP_OK;
 }

@@ -41,11 +41,16 @@ struct GemmArgs {
   // distance in floats between the partial-sum slices that start at C
   int32_t k_splits, k_chunk;
   int64_t split_stride;
+  // ring kernel: bytes of A and of B from their first element to the end of the last chunk the kernel may
+  // read (operand_extent_bytes); its DMA loads are range-checked against them
+  uint32_t a_extent, b_extent;
   // ring kernel, A K-contiguous and B K-strided: the K tail goes through the ring as one more tile.  A's rows
-  // hold zeros from K up to the next multiple of 64; b_extent is B's size in bytes, so that the lines of
-  // the tail tile at k >= K, which lie past it, read as zeros (0xffffffff when ring_tail is 0: no check)
+  // hold zeros from K up to the next multiple of 64 (a_extent reaches that far); the lines of B's tail tile at
+  // k >= K lie past b_extent and read as zeros
   int32_t ring_tail;
-  uint32_t b_extent;
+  // persistent launches: workgroups that are resident at a time (compute units of the device, times two for
+  // the 4-wavefront tile)
+  int32_t resident;
 };
 
 __device__ __forceinline__ float gelu_fwd(float x, int mode) {

@@ -46,9 +46,10 @@ int launch_ring_one(GemmArgs g, hipStream_t s) {
   if (int64_t(g.tiles_m) * g.tiles_n > 0x7fffffff) return NTP_ERR_UNSUPPORTED;
   // persistent workgroups: one per compute unit (two for the 4-wavefront tile, whose LDS ring is half
   // as large), each walking over its share of the output tiles
-  constexpr uint32_t kResident = 256 * (WGM * WGN == 4 ? 2 : 1);
+  // (a grid of several blocks per workgroup has to be a multiple of 8, the tile walk's XCD stride)
+  const uint32_t resident = uint32_t(g.resident > 8 ? g.resident & ~7 : 8) * (WGM * WGN == 4 ? 2 : 1);
   const uint32_t nblk = uint32_t(g.tiles_m) * uint32_t(g.tiles_n);
-  const dim3 grid(nblk < kResident ? nblk : kResident), block(64 * WGM * WGN);
+  const dim3 grid(nblk < resident ? nblk : resident), block(64 * WGM * WGN);
   hipLaunchKernelGGL((gemm_ring_kernel<AKC, BKC, EPI, BM_, BN_, WGM, WGN>), grid, block, 0, s, g);
   return hipGetLastError() == hipSuccess ? NTP_OK : NTP_ERR_LAUNCH;
 }

@@ -31,20 +31,16 @@
 
 #include <type_traits>
 
+#include "ntp_gemm_addr.h"
 #include "ntp_gemm_kernels.h"
 
 namespace ntp_gemm {
-
-constexpr int DK = 64;  // K extent of a tile
 
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) const void global_cvoid;
 
 constexpr int vmcnt_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | 0x0F70; }       // s_waitcnt vmcnt(n) alone
 constexpr int vmcnt_lgkm0_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | 0x0070; }  // s_waitcnt vmcnt(n) lgkmcnt(0)
-
-// chunk permutation of a K-strided slot line
-__device__ __forceinline__ constexpr int kline_swz(int k) { return ((k & 3) | (((k >> 3) & 1) << 2)) << 1; }
 
 // One operand (R rows of the tile, rounded up to a multiple of 64) as seen by the DMA.
 template <bool KC, int R, int NW>
@@ -59,15 +55,7 @@ struct DmaOperand {
   uint32_t off[NINST];  // byte offset (from the operand base at K tile 0) of this lane's chunk per instruction
 
   // chunk position `pos` of a slot -> (line, chunk) it holds; see the layout above
-  __device__ __forceinline__ static void slot_src(int pos, int& line, int& chunk) {
-    if constexpr (KC) {
-      line = pos >> 3;
-      chunk = (pos & 7) ^ ((line >> 1) & 7);
-    } else {
-      line = pos / CPL;
-      chunk = (pos % CPL) ^ kline_swz(line);
-    }
-  }
+  __device__ __forceinline__ static void slot_src(int pos, int& line, int& chunk) { ntp_gemm::slot_src<KC, R>(pos, line, chunk); }
 
   // row0: first row of the tile, lim: extent of the operand's non-K dimension
   __device__ __forceinline__ void init(int64_t ld, int row0, int lim, int wave, int lane) {
@@ -75,13 +63,7 @@ struct DmaOperand {
     for (int i = 0; i < NINST; ++i) {
       int line, chunk;
       slot_src((wave * NINST + i) * 64 + lane, line, chunk);
-      if constexpr (KC) {
-        const int row = min(row0 + line, lim - 1);  // rows past the edge repeat the last one
-        off[i] = uint32_t((int64_t(row) * ld + chunk * 8) * 2);
-      } else {
-        const int col = min(row0 + chunk * 8, ((lim - 1) >> 3) << 3);
-        off[i] = uint32_t((int64_t(line) * ld + col) * 2);
-      }
+      off[i] = dma_offset<KC>(ld, row0, lim, line, chunk);
     }
   }
 
@@ -190,8 +172,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
   constexpr int MH = (MI + 1) / 2;               // block rows in the first half of a K-step
   // rows moved per operand and K tile: whole DMA instructions; a K-strided slot line must hold a
   // power-of-two number of chunks for its chunk permutation (rows past the tile are never read)
-  constexpr int RA = AKC ? (BM_ + 63) / 64 * 64 : (BM_ <= 128 ? 128 : 256);
-  constexpr int RB = BKC ? (BN_ + 63) / 64 * 64 : (BN_ <= 128 ? 128 : 256);
+  constexpr int RA = slot_rows(AKC, BM_), RB = slot_rows(BKC, BN_);
   static_assert(BM_ <= 256 && BN_ <= 256, "tile sides up to 256");
   using OpA = DmaOperand<AKC, RA, NW>;
   using OpB = DmaOperand<BKC, RB, NW>;
@@ -227,18 +208,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
     int tile_m, tile_n, row0, col0;
   };
   auto place = [&](int v) {
-    const int xq = nblk >> 3, xr = nblk & 7, xcd = v & 7;
-    const int L = xcd * xq + min(xcd, xr) + (v >> 3);
-    constexpr int GM = 8;
-    const int width = GM * g.tiles_n;
-    const int first_m = (L / width) * GM;
-    const int gsz = min(g.tiles_m - first_m, GM);
-    TilePos p;
-    p.tile_m = first_m + (L % width) % gsz;
-    p.tile_n = (L % width) / gsz;
-    p.row0 = p.tile_m * BM_;
-    p.col0 = p.tile_n * BN_;
-    return p;
+    const ntp_gemm::TilePos t = place_tile(v, g.tiles_m, g.tiles_n);
+    return TilePos{t.tile_m, t.tile_n, t.tile_m * BM_, t.tile_n * BN_};
   };
   int vblk = blockIdx.x;
   int split = 0;
@@ -260,21 +231,20 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
   OpA a;
   OpB b;
   const int64_t astep = AKC ? DK : DK * g.lda, bstep = BKC ? DK : DK * g.ldb;  // elements per K tile
-  // buffer views of the operands for the DMA (the host checks that each operand spans < 4 GiB)
-  const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(opA), 0, -1, 0x00020000);
-  // (the range check of a buffer load covers vector + scalar offset; what lies past the extent reads as zero)
+  // Buffer views of the operands for the DMA, each ending where the operand ends (the host checks that an
+  // operand spans < 4 GiB and passes the bytes from g.A / g.B on; a K chunk's view starts later and is that much
+  // shorter).  The range check of a buffer load covers vector + scalar offset, and what lies past the extent
+  // reads as zeros: no offset this kernel can form reaches memory outside the operands.
   constexpr bool RT = AKC && !BKC && !SPLIT;
-  const __amdgpu_buffer_rsrc_t rb =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(opB), 0, RT ? int(g.b_extent) : -1, 0x00020000);
+  const uint32_t a_shift = uint32_t((AKC ? k_first : k_first * g.lda) * 2), b_shift = uint32_t((BKC ? k_first : k_first * g.ldb) * 2);
+  const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(opA), 0, int(g.a_extent - a_shift), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(opB), 0, int(g.b_extent - b_shift), 0x00020000);
   const uint32_t astep_b = uint32_t(astep) * 2, bstep_b = uint32_t(bstep) * 2;
   FragAddr<AKC, RA, MI> fra;
   FragAddr<BKC, RB, NI> frb;
   fra.init(wm * TM, lane);
   frb.init(wn * TN, lane);
 
-#ifdef NTP_GEMM_CLOCK_PROBE
-  const long long probe_c0 = clock64();
-#endif
   const int nfull = K / DK;  // complete K tiles: all go through the ring
   // The K tail goes through the ring as one more tile when the host says that both operands read as zeros
   // past K there (g.ring_tail); otherwise it is loaded through registers after the loop.
@@ -539,9 +509,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_ring_kernel(const GemmArg
     if (!more) break;
   }
   asm volatile("" : "+v"(pf_sink));  // the prefetch register stays reserved up to here
-#ifdef NTP_GEMM_CLOCK_PROBE
-  if (g.C2 && lane == 0) reinterpret_cast<long long*>(g.C2)[blockIdx.x * 8 + wave] = clock64() - probe_c0;
-#endif
 }
 
 }  // namespace ntp_gemm

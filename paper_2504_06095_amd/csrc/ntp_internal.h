@@ -4,9 +4,30 @@
 
 #include <stdint.h>
 
+#include <mutex>
 #include <vector>
 
 #include "ntp.h"
+
+// The library's per-caller state.  Everything a device call reads besides its arguments lives here: the
+// device it was created on and its size, the caller's workspace, the tuning overrides and the timing list.
+// The library has no file-scope mutable state; two handles never share anything.
+struct ntp_handle {
+  int device = -1;          // HIP device ordinal the handle was created on (-1: no device was visible)
+  int compute_units = 256;  // of that device (an MI355X has 256; the value used when none was visible)
+  void* workspace = nullptr;
+  int64_t workspace_bytes = 0;
+  int64_t opt[NTP_OPT_COUNT_] = {};  // ntp_set_option values; 0 everywhere = the library's own choices
+  // measurement aid (ntp_kernel_timing_*)
+  struct Pending {
+    void* start;
+    void* stop;
+    ntp_kernel_time_t rec;
+  };
+  std::mutex timing_mu;
+  bool timing_on = false;
+  std::vector<Pending> timing_pending;
+};
 
 namespace ntp {
 
@@ -33,15 +54,15 @@ int check_shards(const ntp_tensor_spec_t* spec, const std::vector<int64_t>& src_
                  void* const* dst_shards, const int64_t* dst_ld);
 // Device side of a reshard: checks the shards (shape, alignment, aliasing) and enqueues the copies
 // of `segs` (destination order).  src_units / dst_units: partition units held by each rank.
-int reshard_launch(const ntp_tensor_spec_t* spec, const std::vector<ntp_segment_t>& segs,
+int reshard_launch(ntp_handle* h, const ntp_tensor_spec_t* spec, const std::vector<ntp_segment_t>& segs,
                    const std::vector<int64_t>& src_units, const std::vector<int64_t>& dst_units,
                    const void* const* src_shards, const int64_t* src_ld, void* const* dst_shards,
                    const int64_t* dst_ld, void* stream);
 
 // ---- optional per-kernel timing (measurement aid) ------------------------------
-bool timing_on();
-void timing_begin(void* stream, const char* name, double flops, double bytes);
-void timing_end(void* stream);
+inline bool timing_on(const ntp_handle* h) { return h->timing_on; }
+void timing_begin(ntp_handle* h, void* stream, const char* name, double flops, double bytes);
+void timing_end(ntp_handle* h, void* stream);
 
 // ---- GEMM family -------------------------------------------------------------
 // C[M x N] = op(A) op(B), bf16 operands, fp32 accumulation on the matrix cores.
@@ -82,11 +103,13 @@ struct GemmDesc {
   int32_t n_segs;
 };
 
-// The workspace registered with ntp_set_workspace (NULL if none) and, through `bytes`, its size.
-void* workspace(int64_t* bytes);
-
 // Validates and enqueues one GEMM on `stream`.  Returns an NTP_* status.
-int gemm_launch(const GemmDesc& d, void* stream);
+int gemm_launch(ntp_handle* h, const GemmDesc& d, void* stream);
+// Largest workspace (bytes) a GEMM of this shape could use, i.e. what the split-K choice would take if the
+// workspace were unlimited (0: it would not split).  layout as for ntp_gemm_choice; n_store: columns stored.
+// The same for the three attention core kernels of a shape (checked like the calls check it).
+int attn_core_workspace_wish(const ntp_handle* h, const ntp_attn_core_shape_t* shape, int64_t* bytes);
+int64_t gemm_workspace_wish(const ntp_handle* h, int layout, int64_t M, int64_t N, int64_t n_store, int64_t K);
 
 }  // namespace ntp
 

@@ -5,7 +5,7 @@
 
 #include "ntp_internal.h"
 
-extern "C" int ntp_version(void) { return 110; }
+extern "C" int ntp_version(void) { return 200; }
 
 extern "C" const char* ntp_status_string(int status) {
   switch (status) {
@@ -14,6 +14,8 @@ extern "C" const char* ntp_status_string(int status) {
     case NTP_ERR_ALIGNMENT: return "pointer or leading dimension not aligned as required";
     case NTP_ERR_LAUNCH: return "HIP kernel launch failed";
     case NTP_ERR_UNSUPPORTED: return "size not supported";
+    case NTP_ERR_NOT_PREPARED: return "reshard plan not prepared on this device";
+    case NTP_ERR_NO_DEVICE: return "the handle was created with no device visible";
     default: return "unknown status";
   }
 }
@@ -124,7 +126,7 @@ int build_segments(const ntp_tensor_spec_t* spec, int32_t src_tp, int32_t dst_tp
       const int64_t end = d.first + d.count;
       for (int32_t r = 0; r < src_tp && cur < end; ++r) {
         for (const Run& a : src[r]) {
-          if (a.first <= cur && cur < a.first + a.count) {
+          if (cur < end && a.first <= cur && cur < a.first + a.count) {
             const int64_t stop = std::min(end, a.first + a.count);
             segs->push_back({r, s, a.local + (cur - a.first), d.local + (cur - d.first), stop - cur});
             cur = stop;

@@ -533,8 +533,8 @@ struct Extent {
   uintptr_t lo, hi;
 };
 
-int64_t gather_block_bytes() {
-  if (const char* e = getenv("NTP_RESHARD_BLOCK")) return std::max<int64_t>(1024, atoll(e));
+int64_t gather_block_bytes(const ntp_handle* h) {
+  if (const int64_t e = h->opt[NTP_OPT_RESHARD_BLOCK]) return std::max<int64_t>(1024, e);
   return kBlockBytes;
 }
 
@@ -547,24 +547,25 @@ __global__ __launch_bounds__(256) void calibration_copy_kernel(const u32x4* __re
 
 }  // namespace
 
-extern "C" int ntp_calibration_copy(void* dst, const void* src, int64_t bytes, void* stream) {
-  if (!dst || !src || bytes < 0) return NTP_ERR_INVALID_ARG;
+extern "C" int ntp_calibration_copy(ntp_handle_t* h, void* dst, const void* src, int64_t bytes, void* stream) {
+  if (!h || !dst || !src || bytes < 0) return NTP_ERR_INVALID_ARG;
+  if (h->device < 0) return NTP_ERR_NO_DEVICE;
   if (bytes % 16 || reinterpret_cast<uintptr_t>(dst) % 16 || reinterpret_cast<uintptr_t>(src) % 16) return NTP_ERR_ALIGNMENT;
   if (bytes == 0) return NTP_OK;
   const int64_t words = bytes / 16;
-  const uint32_t blocks = uint32_t(std::min<int64_t>((words + 255) / 256, 256 * 32));
-  if (ntp::timing_on()) ntp::timing_begin(stream, "calibration_copy", 0.0, 2.0 * double(bytes));
+  const uint32_t blocks = uint32_t(std::min<int64_t>((words + 255) / 256, int64_t(h->compute_units) * 32));
+  if (ntp::timing_on(h)) ntp::timing_begin(h, stream, "calibration_copy", 0.0, 2.0 * double(bytes));
   hipLaunchKernelGGL(calibration_copy_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
                      static_cast<const u32x4*>(src), static_cast<u32x4*>(dst), words);
   const bool ok = hipGetLastError() == hipSuccess;
-  ntp::timing_end(stream);
+  ntp::timing_end(h, stream);
   return ok ? NTP_OK : NTP_ERR_LAUNCH;
 }
 
-extern "C" int ntp_reshard_grad(const ntp_tensor_spec_t* spec, int32_t src_tp, int32_t dst_tp,
+extern "C" int ntp_reshard_grad(ntp_handle_t* h, const ntp_tensor_spec_t* spec, int32_t src_tp, int32_t dst_tp,
                                 const void* const* src_shards, const int64_t* src_ld,
                                 void* const* dst_shards, const int64_t* dst_ld, void* stream) {
-  if (!src_shards || !dst_shards || !src_ld || !dst_ld) return NTP_ERR_INVALID_ARG;
+  if (!h || !src_shards || !dst_shards || !src_ld || !dst_ld) return NTP_ERR_INVALID_ARG;
   std::vector<ntp_segment_t> segs;
   int st = ntp::build_segments(spec, src_tp, dst_tp, &segs);
   if (st != NTP_OK) return st;
@@ -575,7 +576,7 @@ extern "C" int ntp_reshard_grad(const ntp_tensor_spec_t* spec, int32_t src_tp, i
     if ((st = ntp::shard_units(spec, n_units, src_tp, r, &su[r])) != NTP_OK) return st;
   for (int32_t r = 0; r < dst_tp; ++r)
     if ((st = ntp::shard_units(spec, n_units, dst_tp, r, &du[r])) != NTP_OK) return st;
-  return ntp::reshard_launch(spec, segs, su, du, src_shards, src_ld, dst_shards, dst_ld, stream);
+  return ntp::reshard_launch(h, spec, segs, su, du, src_shards, src_ld, dst_shards, dst_ld, stream);
 }
 
 int ntp::check_shards(const ntp_tensor_spec_t* spec, const std::vector<int64_t>& src_units,
@@ -611,12 +612,13 @@ int ntp::check_shards(const ntp_tensor_spec_t* spec, const std::vector<int64_t>&
   return NTP_OK;
 }
 
-int ntp::reshard_launch(const ntp_tensor_spec_t* spec, const std::vector<ntp_segment_t>& segs,
+int ntp::reshard_launch(ntp_handle* h, const ntp_tensor_spec_t* spec, const std::vector<ntp_segment_t>& segs,
                         const std::vector<int64_t>& src_units, const std::vector<int64_t>& dst_units,
                         const void* const* src_shards, const int64_t* src_ld, void* const* dst_shards,
                         const int64_t* dst_ld, void* stream) {
   const int st = check_shards(spec, src_units, dst_units, src_shards, src_ld, dst_shards, dst_ld);
   if (st != NTP_OK) return st;
+  if (h->device < 0) return NTP_ERR_NO_DEVICE;
   const int64_t esz = spec->elem_size;
   const bool by_rows = spec->partition_dim == 0;
 
@@ -654,7 +656,9 @@ int ntp::reshard_launch(const ntp_tensor_spec_t* spec, const std::vector<ntp_seg
       cur_end = c1;
     }
     // jobs whose destination is a dense, 64-byte aligned shard go to the flat kernel
-    const int64_t kFlatBlock = getenv("NTP_RESHARD_FLAT_BLOCK") ? std::min<int64_t>(kFlatBlockMax, std::max<int64_t>(1024, atoll(getenv("NTP_RESHARD_FLAT_BLOCK")) & ~63ll)) : 16384;
+    const int64_t kFlatBlock = h->opt[NTP_OPT_RESHARD_FLAT_BLOCK]
+                                   ? std::min<int64_t>(kFlatBlockMax, std::max<int64_t>(1024, h->opt[NTP_OPT_RESHARD_FLAT_BLOCK] & ~63ll))
+                                   : 16384;
     std::vector<GatherJob> flat, rowwise;
     for (const GatherJob& j : jobs) {
       const int64_t W = j.piece[j.npieces - 1].end;
@@ -662,7 +666,7 @@ int ntp::reshard_launch(const ntp_tensor_spec_t* spec, const std::vector<ntp_seg
       for (uint32_t p = 0; p < j.npieces; ++p) smax = std::max(smax, j.piece[p].src_stride);
       const bool ok = j.dst_stride == W && (reinterpret_cast<uintptr_t>(j.dst) & 63) == 0 &&
                       (int64_t(kFlatBlock) + W + 16) * W <= (int64_t(1) << 32) &&
-                      smax * (int64_t(kFlatBlock) / W + 2) < (int64_t(1) << 32) && !getenv("NTP_RESHARD_NO_FLAT");
+                      smax * (int64_t(kFlatBlock) / W + 2) < (int64_t(1) << 32) && !h->opt[NTP_OPT_RESHARD_NO_FLAT];
       (ok ? flat : rowwise).push_back(j);
     }
     for (size_t base = 0; base < flat.size(); base += kMaxJobs) {
@@ -681,10 +685,10 @@ int ntp::reshard_launch(const ntp_tensor_spec_t* spec, const std::vector<ntp_seg
       const uint64_t blocks = uint64_t(nblk) * uint64_t(batch.njobs);
       if (blocks > 0x7fffffffull) return NTP_ERR_UNSUPPORTED;
       if (blocks == 0) continue;
-      if (ntp::timing_on()) ntp::timing_begin(stream, "reshard_flat", 0.0, bytes);
+      if (ntp::timing_on(h)) ntp::timing_begin(h, stream, "reshard_flat", 0.0, bytes);
       hipLaunchKernelGGL(reshard_flat_kernel, dim3(uint32_t(blocks)), dim3(kThreads), 0, hs, batch);
       const bool ok = hipGetLastError() == hipSuccess;
-      ntp::timing_end(stream);
+      ntp::timing_end(h, stream);
       if (!ok) return NTP_ERR_LAUNCH;
     }
     jobs.swap(rowwise);
@@ -700,7 +704,7 @@ int ntp::reshard_launch(const ntp_tensor_spec_t* spec, const std::vector<ntp_seg
         const int64_t row_bytes = j.piece[j.npieces - 1].end;
         int64_t stride = j.dst_stride;
         for (uint32_t p = 0; p < j.npieces; ++p) stride = std::max(stride, j.piece[p].src_stride);
-        rpb = std::min(rpb, std::max<int64_t>(1, gather_block_bytes() / row_bytes));
+        rpb = std::min(rpb, std::max<int64_t>(1, gather_block_bytes(h) / row_bytes));
         rpb = std::min(rpb, std::max<int64_t>(1, (int64_t(1) << 31) / std::max<int64_t>(stride, 1)));
         bytes += 2.0 * double(j.rows) * double(row_bytes);
         batch.job[i] = j;
@@ -710,10 +714,10 @@ int ntp::reshard_launch(const ntp_tensor_spec_t* spec, const std::vector<ntp_seg
       const uint64_t blocks = uint64_t((spec->rows + rpb - 1) / rpb) * uint64_t(batch.njobs);
       if (blocks > 0x7fffffffull) return NTP_ERR_UNSUPPORTED;
       if (blocks == 0) continue;
-      if (ntp::timing_on()) ntp::timing_begin(stream, "reshard_gather", 0.0, bytes);
+      if (ntp::timing_on(h)) ntp::timing_begin(h, stream, "reshard_gather", 0.0, bytes);
       hipLaunchKernelGGL(reshard_gather_kernel, dim3(uint32_t(blocks)), dim3(kThreads), 0, hs, batch);
       const bool ok = hipGetLastError() == hipSuccess;
-      ntp::timing_end(stream);
+      ntp::timing_end(h, stream);
       if (!ok) return NTP_ERR_LAUNCH;
     }
     return NTP_OK;
@@ -785,10 +789,10 @@ int ntp::reshard_launch(const ntp_tensor_spec_t* spec, const std::vector<ntp_seg
       bytes += 2.0 * double(r.bytes);
       batch.r[i] = r;
     }
-    if (ntp::timing_on()) ntp::timing_begin(stream, "reshard_dense", 0.0, bytes);
+    if (ntp::timing_on(h)) ntp::timing_begin(h, stream, "reshard_dense", 0.0, bytes);
     hipLaunchKernelGGL(reshard_dense_kernel, dim3(uint32_t(blocks)), dim3(kThreads), 0, hs, batch);
     const bool ok = hipGetLastError() == hipSuccess;
-    ntp::timing_end(stream);
+    ntp::timing_end(h, stream);
     if (!ok) return NTP_ERR_LAUNCH;
   }
   for (size_t base = 0; base < copies.size(); base += kMaxSegs) {
@@ -810,14 +814,14 @@ int ntp::reshard_launch(const ntp_tensor_spec_t* spec, const std::vector<ntp_seg
       batch.seg[i] = c;
     }
     if (blocks == 0) continue;
-    if (ntp::timing_on()) {
+    if (ntp::timing_on(h)) {
       double bytes = 0.0;
       for (int i = 0; i < batch.nseg; ++i) bytes += 2.0 * double(batch.seg[i].rows) * double(batch.seg[i].row_bytes);
-      ntp::timing_begin(stream, "reshard_copy", 0.0, bytes);
+      ntp::timing_begin(h, stream, "reshard_copy", 0.0, bytes);
     }
     hipLaunchKernelGGL(reshard_copy_kernel, dim3(uint32_t(blocks)), dim3(kThreads), 0, hs, batch);
     const bool ok = hipGetLastError() == hipSuccess;
-    ntp::timing_end(stream);
+    ntp::timing_end(h, stream);
     if (!ok) return NTP_ERR_LAUNCH;
   }
   return NTP_OK;
@@ -837,8 +841,8 @@ struct ntp_reshard_plan {
   std::vector<RunDev> runs;                   // runs of all destination shards, one shard after the other
   std::vector<int64_t> runs_first;            // first run of each destination shard
   std::vector<uint16_t> run_of_unit;          // per destination unit (indexed like `table`): run number in its shard
-  void* dev_table = nullptr;                  // `runs` then `run_of_unit` on device `dev`, made by the first run
-  int dev = -1;
+  void* dev_table = nullptr;                  // `runs` then `run_of_unit` on device `dev`, made by ntp_reshard_plan_prepare
+  int dev = -1;                               // device the plan was prepared on (-1: not prepared)
 };
 
 extern "C" int ntp_reshard_plan_create(const ntp_tensor_spec_t* spec, int64_t map_len, int32_t src_tp,
@@ -928,10 +932,10 @@ extern "C" int ntp_reshard_plan_table(const ntp_reshard_plan_t* plan, ntp_unit_s
 namespace {
 
 // Whether the run-table kernel can take this call with blocks of `block` bytes.
-bool units_path_ok(const ntp_reshard_plan* p, const void* const* src_shards, const int64_t* src_ld,
+bool units_path_ok(const ntp_handle* h, const ntp_reshard_plan* p, const void* const* src_shards, const int64_t* src_ld,
                    void* const* dst_shards, const int64_t* dst_ld, int64_t block) {
   const ntp_tensor_spec_t& sp = p->spec;
-  if (!p->runs_ok || sp.rows == 0 || getenv("NTP_RESHARD_NO_TABLE")) return false;
+  if (!p->runs_ok || !p->dev_table || sp.rows == 0 || h->opt[NTP_OPT_RESHARD_NO_TABLE]) return false;
   if (p->src_tp > kMaxRanks || sp.rows > 0x7fffffffll) return false;
   for (int32_t r = 0; r < p->src_tp; ++r) {
     if (p->src_units[r] == 0) continue;
@@ -955,11 +959,8 @@ bool units_path_ok(const ntp_reshard_plan* p, const void* const* src_shards, con
 
 namespace {
 
-// The plan's run table on the current device: uploaded once (allocates and waits for the copy).
-int ensure_table(ntp_reshard_plan_t* plan) {
-  int cur = -1;
-  if (hipGetDevice(&cur) != hipSuccess) return NTP_ERR_LAUNCH;
-  if (plan->dev_table) return cur == plan->dev ? NTP_OK : NTP_ERR_INVALID_ARG;  // the table lives on one device
+// The plan's run table goes to the current device (allocates and waits for the copy).
+int upload_table(ntp_reshard_plan_t* plan) {
   const size_t runs_bytes = plan->runs.size() * sizeof(RunDev), idx_bytes = plan->run_of_unit.size() * sizeof(uint16_t);
   if (hipMalloc(&plan->dev_table, runs_bytes + idx_bytes) != hipSuccess) {
     plan->dev_table = nullptr;
@@ -972,7 +973,6 @@ int ensure_table(ntp_reshard_plan_t* plan) {
     plan->dev_table = nullptr;
     return NTP_ERR_LAUNCH;
   }
-  plan->dev = cur;
   return NTP_OK;
 }
 
@@ -980,23 +980,32 @@ int ensure_table(ntp_reshard_plan_t* plan) {
 
 extern "C" int ntp_reshard_plan_prepare(ntp_reshard_plan_t* plan) {
   if (!plan) return NTP_ERR_INVALID_ARG;
-  if (!plan->runs_ok || plan->runs.empty()) return NTP_OK;  // this plan never uses a table
-  return ensure_table(plan);
+  int cur = -1;
+  if (hipGetDevice(&cur) != hipSuccess || cur < 0) {
+    (void)hipGetLastError();
+    return NTP_ERR_NO_DEVICE;
+  }
+  if (plan->dev >= 0) return cur == plan->dev ? NTP_OK : NTP_ERR_INVALID_ARG;  // a plan lives on one device
+  if (plan->runs_ok && !plan->runs.empty()) {
+    const int st = upload_table(plan);
+    if (st != NTP_OK) return st;
+  }
+  plan->dev = cur;
+  return NTP_OK;
 }
 
-extern "C" int ntp_reshard_plan_run(ntp_reshard_plan_t* plan, const void* const* src_shards, const int64_t* src_ld,
-                                    void* const* dst_shards, const int64_t* dst_ld, void* stream) {
-  if (!plan) return NTP_ERR_INVALID_ARG;
+extern "C" int ntp_reshard_plan_run(ntp_handle_t* h, ntp_reshard_plan_t* plan, const void* const* src_shards,
+                                    const int64_t* src_ld, void* const* dst_shards, const int64_t* dst_ld, void* stream) {
+  if (!h || !plan) return NTP_ERR_INVALID_ARG;
   int st = ntp::check_shards(&plan->spec, plan->src_units, plan->dst_units, src_shards, src_ld, dst_shards, dst_ld);
   if (st != NTP_OK) return st;
+  if (h->device < 0) return NTP_ERR_NO_DEVICE;
+  if (plan->dev != h->device) return NTP_ERR_NOT_PREPARED;
   int64_t block = 16384;
-  if (const char* e = getenv("NTP_RESHARD_TABLE_BLOCK")) block = std::min<int64_t>(1 << 20, std::max<int64_t>(1024, atoll(e) & ~63ll));
-  if (!units_path_ok(plan, src_shards, src_ld, dst_shards, dst_ld, block))
-    return ntp::reshard_launch(&plan->spec, plan->segs, plan->src_units, plan->dst_units, src_shards, src_ld, dst_shards,
+  if (const int64_t e = h->opt[NTP_OPT_RESHARD_TABLE_BLOCK]) block = std::min<int64_t>(1 << 20, std::max<int64_t>(1024, e & ~63ll));
+  if (!units_path_ok(h, plan, src_shards, src_ld, dst_shards, dst_ld, block))
+    return ntp::reshard_launch(h, &plan->spec, plan->segs, plan->src_units, plan->dst_units, src_shards, src_ld, dst_shards,
                                dst_ld, stream);
-
-  // first run of an unprepared plan: the table goes to the current device
-  if ((st = ensure_table(plan)) != NTP_OK) return st;
 
   const ntp_tensor_spec_t& sp = plan->spec;
   hipStream_t hs = static_cast<hipStream_t>(stream);
@@ -1028,12 +1037,12 @@ extern "C" int ntp_reshard_plan_run(ntp_reshard_plan_t* plan, const void* const*
     // workgroups per destination shard: enough of them to fill the chip, each walking over several blocks
     // workgroups per destination shard: one per block, or fewer that walk over several blocks each when
     // the shards are very large (the tables are copied into LDS once per workgroup)
-    const int64_t slots = std::max<int64_t>(1, std::min<int64_t>(nblk, (256 * int64_t(kUnitBlocksPerCu) + batch.ndst - 1) / batch.ndst));
+    const int64_t slots = std::max<int64_t>(1, std::min<int64_t>(nblk, (int64_t(h->compute_units) * int64_t(kUnitBlocksPerCu) + batch.ndst - 1) / batch.ndst));
     const uint64_t blocks = uint64_t(slots) * batch.ndst;
-    if (ntp::timing_on()) ntp::timing_begin(stream, "reshard_table", 0.0, bytes);
+    if (ntp::timing_on(h)) ntp::timing_begin(h, stream, "reshard_table", 0.0, bytes);
     hipLaunchKernelGGL(reshard_units_kernel, dim3(uint32_t(blocks)), dim3(kThreads), lds, hs, batch);
     const bool ok = hipGetLastError() == hipSuccess;
-    ntp::timing_end(stream);
+    ntp::timing_end(h, stream);
     if (!ok) return NTP_ERR_LAUNCH;
   }
   return NTP_OK;

@@ -15,3 +15,18 @@ def pytest_configure(config):
 @pytest.fixture(scope="session")
 def golden_dir():
     return os.path.join(ROOT, "tests", "golden")
+
+
+@pytest.fixture
+def opts():
+    """Sets tuning overrides (ntp_set_option) on the default handle for one test and clears them afterwards."""
+    import paper_2504_06095_amd as N
+    touched = []
+
+    def set_option(option, value):
+        N.ntp_set_option(option, value)
+        touched.append(option)
+
+    yield set_option
+    for option in touched:
+        N.ntp_set_option(option, 0)

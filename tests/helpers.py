@@ -61,8 +61,10 @@ class MlpCase:
         dP, dX, dA, dB = O.mlp_shard_bwd(self.dZ, self.X, self.A_i, self.B_i, mode)
         return dict(P=P, Y=Y, Z=Z, dP=dP, dX=dX, dA_t=dA.T, dB=dB)
 
-    def run_gpu(self, mode=0, accumulate_twice=False, pad_to=8, poison=True):
-        """Runs ntp_mlp_shard_fwd + bwd; returns host float64 arrays plus the raw padded buffers."""
+    def run_gpu(self, mode=0, accumulate_twice=False, pad_to=8, poison=True, handle=None, sync=True):
+        """Runs ntp_mlp_shard_fwd + bwd (on `handle`, else the default one, on torch's current stream); returns
+        host float64 arrays plus the raw padded buffers.  sync=False: returns (device tensors, raw) without
+        waiting, for callers that overlap several runs."""
         import torch
         import paper_2504_06095_amd as N
         M, H, n_r = self.M, self.H, self.n_r
@@ -74,15 +76,19 @@ class MlpCase:
         Z, dX = mk(M, H), mk(M, H)
         dA_t = torch.full((n_r, H), fill, dtype=torch.float32, device="cuda")
         dB = torch.full((n_r, H), fill, dtype=torch.float32, device="cuda")
-        N.ntp_mlp_shard_fwd(X, At, B, P[:, :n_r], Y[:, :n_r], Z, n_r, mode)
-        N.ntp_mlp_shard_bwd(dZ, X, At, B, P[:, :n_r], Y[:, :n_r], dP[:, :n_r], dX, dA_t, dB, n_r, mode, False)
+        N.ntp_mlp_shard_fwd(X, At, B, P[:, :n_r], Y[:, :n_r], Z, n_r, mode, handle=handle)
+        N.ntp_mlp_shard_bwd(dZ, X, At, B, P[:, :n_r], Y[:, :n_r], dP[:, :n_r], dX, dA_t, dB, n_r, mode, False, handle=handle)
         if accumulate_twice:
-            N.ntp_mlp_shard_bwd(dZ, X, At, B, P[:, :n_r], Y[:, :n_r], dP[:, :n_r], dX, dA_t, dB, n_r, mode, True)
+            N.ntp_mlp_shard_bwd(dZ, X, At, B, P[:, :n_r], Y[:, :n_r], dP[:, :n_r], dX, dA_t, dB, n_r, mode, True,
+                                handle=handle)
+        raw = dict(P=P, Y=Y, dP=dP, ld=ld)
+        if not sync:
+            return dict(P=P[:, :n_r], Y=Y[:, :n_r], Z=Z, dP=dP[:, :n_r], dX=dX, dA_t=dA_t, dB=dB,
+                        _keep=(X, At, B, dZ)), raw
         torch.cuda.synchronize()
         out = dict(P=dev_bf16_to_f64(P[:, :n_r]), Y=dev_bf16_to_f64(Y[:, :n_r]), Z=dev_bf16_to_f64(Z),
                    dP=dev_bf16_to_f64(dP[:, :n_r]), dX=dev_bf16_to_f64(dX),
                    dA_t=dA_t.cpu().numpy().astype(np.float64), dB=dB.cpu().numpy().astype(np.float64))
-        raw = dict(P=P, Y=Y, dP=dP, ld=ld)
         return out, raw
 
 

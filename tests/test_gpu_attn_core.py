@@ -6,6 +6,8 @@ import sys
 import numpy as np
 import pytest
 
+from paper_2504_06095_amd import binding as K
+
 from oracle import ntp_oracle as O
 from paper_2504_06095_amd import inputs as I
 from tests import helpers as Hh
@@ -141,11 +143,11 @@ def _core_names():
 @pytest.mark.parametrize("parts", [2, 5, 16])
 @pytest.mark.parametrize("causal", [False, True], ids=["full", "causal"])
 @pytest.mark.parametrize("n_q,n_kv,tp,rank,d,n_seq,S", [CASES[0], CASES[2], CASES[3], CASES[5], CASES[6]])
-def test_attn_core_bwd_cut_walks(workspace, monkeypatch, n_q, n_kv, tp, rank, d, n_seq, S, causal, parts):
+def test_attn_core_bwd_cut_walks(workspace, opts, n_q, n_kv, tp, rank, d, n_seq, S, causal, parts):
     """Each workgroup's walk cut into 2, 5 and 16 parts (more parts than tiles leaves some empty), fp32 partial
     sums added by the second kernel."""
     _say(f"attn core bwd cut into {parts}: n_q={n_q} n_kv={n_kv} tp={tp} rank={rank} d={d} n_seq={n_seq} S={S} causal={causal}")
-    monkeypatch.setenv("NTP_ATTN_PARTS", str(parts))
+    opts(K.NTP_OPT_ATTN_PARTS, parts)
     _bwd_case(n_q, n_kv, tp, rank, d, n_seq, S, causal)
     names = _core_names()
     assert "attn_core_bwd_dq_cut" in names and "attn_core_bwd_dkv_cut" in names, names
@@ -154,18 +156,18 @@ def test_attn_core_bwd_cut_walks(workspace, monkeypatch, n_q, n_kv, tp, rank, d,
 @pytest.mark.parametrize("parts", [2, 5, 16])
 @pytest.mark.parametrize("causal", [False, True], ids=["full", "causal"])
 @pytest.mark.parametrize("n_q,n_kv,tp,rank,d,n_seq,S", [CASES[0], CASES[1], CASES[2], CASES[5], CASES[6]])
-def test_attn_core_fwd_cut_walks(workspace, monkeypatch, n_q, n_kv, tp, rank, d, n_seq, S, causal, parts):
+def test_attn_core_fwd_cut_walks(workspace, opts, n_q, n_kv, tp, rank, d, n_seq, S, causal, parts):
     """The forward walk over the key tiles cut into pieces that are merged by their running maxima and sums."""
     _say(f"attn core fwd cut into {parts}: n_q={n_q} n_kv={n_kv} tp={tp} rank={rank} d={d} n_seq={n_seq} S={S} causal={causal}")
-    monkeypatch.setenv("NTP_ATTN_PARTS", str(parts))
+    opts(K.NTP_OPT_ATTN_PARTS, parts)
     _case(n_q, n_kv, tp, rank, d, n_seq, S, causal)
     assert _core_names() == ["attn_core_fwd_causal_cut" if causal else "attn_core_fwd_cut"]
 
 
-def test_attn_core_fwd_cut_peaked_scores(workspace, monkeypatch):
+def test_attn_core_fwd_cut_peaked_scores(workspace, opts):
     """Large scores: the pieces' maxima differ by hundreds, so most pieces merge with weight zero."""
     _say("attn core fwd cut: peaked scores")
-    monkeypatch.setenv("NTP_ATTN_PARTS", "7")
+    opts(K.NTP_OPT_ATTN_PARTS, 7)
     _case(8, 2, 3, 1, 128, 1, 700, False, seed=4, std=6.0)
     _case(8, 2, 3, 1, 128, 1, 700, True, seed=4, std=6.0)
 

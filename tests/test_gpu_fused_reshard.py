@@ -6,6 +6,8 @@ import sys
 import numpy as np
 import pytest
 
+from paper_2504_06095_amd import binding as K
+
 from oracle import ntp_oracle as O
 from tests import helpers as Hh
 
@@ -91,16 +93,16 @@ def test_mlp_bwd_resharded_matches_unfused(M, H, n, a, b, rank, pad, accumulate)
 
 
 @pytest.mark.parametrize("tile", ["auto", "256x256", "224x256", "256x192", "128x256", "128x128", "generic"])
-def test_mlp_bwd_resharded_every_kernel_family(monkeypatch, tile):
+def test_mlp_bwd_resharded_every_kernel_family(opts, tile):
     # large enough for the ring kernel's weight-gradient variants; the tile shape is forced in turn
     _say(f"mlp bwd resharded, gradient GEMM tile {tile}")
     if tile != "auto":
-        monkeypatch.setenv("NTP_GEMM_TILE", tile)
+        opts(K.NTP_OPT_GEMM_TILE, tile)
     _mlp_case(1024, 2048, 8192, 7, 8, 2, 5, 0, tile == "256x256")
 
 
 @pytest.mark.parametrize("splits,accumulate", [(2, False), (3, True)])
-def test_mlp_bwd_resharded_with_split_k(monkeypatch, splits, accumulate):
+def test_mlp_bwd_resharded_with_split_k(opts, splits, accumulate):
     """The gradient GEMMs cut along the token axis: the kernel that adds the partial sums stores them through the
     same row segments (two destination shards per gradient here), overwriting or accumulating."""
     import torch
@@ -110,7 +112,7 @@ def test_mlp_bwd_resharded_with_split_k(monkeypatch, splits, accumulate):
     N.ntp_kernel_timing_enable(1)
     N.ntp_kernel_timing_read()
     try:
-        monkeypatch.setenv("NTP_GEMM_SPLIT", str(splits))
+        opts(K.NTP_OPT_GEMM_SPLIT, splits)
         _mlp_case(1100, 1096, 8197, 7, 8, 3, 6, 4, accumulate)
         names = [r["name"] for r in N.ntp_kernel_timing_read() if r["name"].startswith("gemm_tn")]
         assert names and all(n.endswith(f"k{splits}") for n in names), names

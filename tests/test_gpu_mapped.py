@@ -7,6 +7,8 @@ import sys
 import numpy as np
 import pytest
 
+from paper_2504_06095_amd import binding as K
+
 from oracle import ntp_oracle as O
 
 pytestmark = pytest.mark.gpu
@@ -43,6 +45,7 @@ def _run(G, pd, unit, smap, src_tp, dmap, dst_tp, pad_src=0, pad_dst=0, misalign
     dst = [p[0] for p in dst_pairs]
     spec = N.tensor_spec(G.shape[0], G.shape[1], pd, unit, G.dtype.itemsize)
     plan = N.ntp_reshard_plan_create(spec, src_tp, smap, dst_tp, dmap)
+    plan.ntp_reshard_plan_prepare()
     for _ in range(runs):
         plan.ntp_reshard_plan_run(src, dst)
     torch.cuda.synchronize()
@@ -90,9 +93,9 @@ def test_plan_run_bit_exact(rows, k, unit, t, tr, pd, pad_src, pad_dst, misalign
         assert np.array_equal(got[s], want[s]), f"dst rank {s}"
 
 
-def test_plan_run_without_the_table_kernel(monkeypatch):
+def test_plan_run_without_the_table_kernel(opts):
     _say("plan_run, table kernel switched off")
-    monkeypatch.setenv("NTP_RESHARD_NO_TABLE", "1")
+    opts(K.NTP_OPT_RESHARD_NO_TABLE, 1)
     comp, sync = O.comp_sync_plan(1000, 8, 7)
     G = _logical(200, 1000)
     got, want = _run(G, 1, 1, comp, 8, sync, 7)
@@ -101,9 +104,9 @@ def test_plan_run_without_the_table_kernel(monkeypatch):
 
 
 @pytest.mark.parametrize("block", [1024, 4096, 65536])
-def test_plan_run_block_sizes(monkeypatch, block):
+def test_plan_run_block_sizes(opts, block):
     _say(f"plan_run, table kernel block {block}")
-    monkeypatch.setenv("NTP_RESHARD_TABLE_BLOCK", str(block))
+    opts(K.NTP_OPT_RESHARD_TABLE_BLOCK, block)
     comp, sync = O.comp_sync_plan(999, 8, 6)
     G = _logical(123, 999)
     for smap, a, dmap, b in ((comp, 8, sync, 6), (sync, 6, comp, 8)):
@@ -139,6 +142,7 @@ def test_plan_run_one_gpu_share():
     want = O.reshard_mapped(src_np, 1, 1, comp, t, sync, tr)
     spec = N.tensor_spec(rows, k, 1, 1, 4)
     plan = N.ntp_reshard_plan_create(spec, t, comp, tr, sync)
+    plan.ntp_reshard_plan_prepare()
     # only the offload rank's shard is here: what it sends lands, everything else stays untouched
     src = [None] * t
     src[7] = torch.from_numpy(src_np[7].view(np.int32)).cuda()
@@ -210,6 +214,7 @@ def test_mlp_shard_on_the_comp_layout_sums_to_the_layer():
     # pre-sync reshard of dB (rows partitioned): comp layout -> sync layout, then compare with the cut of the full gradient
     spec = N.tensor_spec(n, H, 0, 1, 4)
     plan = N.ntp_reshard_plan_create(spec, t, comp, tr, sync)
+    plan.ntp_reshard_plan_prepare()
     dst = [torch.empty(O.shard_plan(n, tr, s)[1], H, dtype=torch.float32, device="cuda") for s in range(tr)]
     plan.ntp_reshard_plan_run(dB_shards, dst)
     torch.cuda.synchronize()

@@ -8,6 +8,8 @@ import sys
 import numpy as np
 import pytest
 
+from paper_2504_06095_amd import binding as K
+
 from oracle import ntp_oracle as O
 from tests.helpers import TOL, AttnCase, MlpCase, rel_err
 
@@ -177,10 +179,10 @@ RING_TILES = ["256x256", "256x224", "224x256", "256x192", "192x256", "256x128", 
 
 
 @pytest.mark.parametrize("variant", ["generic"] + RING_TILES)
-def test_mlp_every_tile_variant_ragged(variant, monkeypatch):
+def test_mlp_every_tile_variant_ragged(variant, opts):
     # M = 777 (ragged rows), H = 1096 = 17 * 64 + 8 (K tail of 8), n_r = 1001 (odd: ragged N, K and dW rows)
     _say(f"mlp variant {variant}")
-    monkeypatch.setenv("NTP_GEMM_TILE", variant)
+    opts(K.NTP_OPT_GEMM_TILE, variant)
     case = MlpCase(777, 1096, 2003, 2, 1)
     assert case.n_r == 1001
     got, raw = case.run_gpu()
@@ -191,13 +193,13 @@ def test_mlp_every_tile_variant_ragged(variant, monkeypatch):
 
 @pytest.mark.parametrize("ring_tail", ["1", "0"], ids=["tail through the ring", "tail through registers"])
 @pytest.mark.parametrize("variant", ["auto"] + RING_TILES)
-def test_mlp_rows_padded_to_64_every_tile_variant(variant, ring_tail, monkeypatch):
+def test_mlp_rows_padded_to_64_every_tile_variant(variant, ring_tail, opts):
     """P, Y, dP with leading dimensions that reach the next multiple of 64: their pad columns are zeroed that far
     and the row-parallel GEMMs (fc2, dX: K = n_r = 1001 = 15 K tiles + 41) take the K tail through the ring."""
     _say(f"mlp rows padded to 64, variant {variant}, ring tail {ring_tail}")
     if variant != "auto":
-        monkeypatch.setenv("NTP_GEMM_TILE", variant)
-    monkeypatch.setenv("NTP_GEMM_RING_TAIL", ring_tail)
+        opts(K.NTP_OPT_GEMM_TILE, variant)
+    opts(K.NTP_OPT_GEMM_NO_RING_TAIL, 1 - int(ring_tail))
     case = MlpCase(777, 1096, 2003, 2, 1)
     got, raw = case.run_gpu(pad_to=64)
     assert raw["ld"] == 1024
@@ -233,17 +235,17 @@ def test_mlp_ring_tail_needs_no_finite_values_past_the_weights():
 
 
 @pytest.mark.parametrize("variant", RING_TILES)
-def test_attn_every_tile_variant(variant, monkeypatch):
+def test_attn_every_tile_variant(variant, opts):
     _say(f"attn variant {variant}")
-    monkeypatch.setenv("NTP_GEMM_TILE", variant)
+    opts(K.NTP_OPT_GEMM_TILE, variant)
     case = AttnCase(520, 1032, 16, 2, 64, 5, 0)  # 4 q heads + 2 x 1 kv heads: w_qkv = 384, w_o = 256
     _check_all(case.run_gpu(), case.oracle(), ["QKV", "Z", "dC", "dX", "dWqkv", "dWo"])
 
 
-def test_mlp_tiny_k_and_single_rows_on_fast_tiles(monkeypatch):
+def test_mlp_tiny_k_and_single_rows_on_fast_tiles(opts):
     # degenerate extents through the wide-tile kernel: K = 8, M = 1, n_r = 1
     for variant in ("256x256", "224x256", "256x192", "128x128"):
-        monkeypatch.setenv("NTP_GEMM_TILE", variant)
+        opts(K.NTP_OPT_GEMM_TILE, variant)
         for (M, H, n, tp, rank) in [(1, 8, 3, 3, 0), (3, 72, 17, 1, 0), (65, 64, 64, 1, 0)]:
             _say(f"mlp degenerate {variant} M={M} H={H} n={n}")
             case = MlpCase(M, H, n, tp, rank)

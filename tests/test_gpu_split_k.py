@@ -6,6 +6,8 @@ import sys
 import numpy as np
 import pytest
 
+from paper_2504_06095_amd import binding as K
+
 from tests.helpers import TOL, AttnCase, MlpCase, rel_err
 
 pytestmark = pytest.mark.gpu
@@ -47,11 +49,11 @@ def _gemm_names():
 
 @pytest.mark.parametrize("splits", [2, 3, 5])
 @pytest.mark.parametrize("tile", SPLIT_TILES)
-def test_mlp_split_k_every_tile(workspace, monkeypatch, tile, splits):
+def test_mlp_split_k_every_tile(workspace, opts, tile, splits):
     # H = 1096 = 17 K tiles + 8, n_r = 1171 = 18 K tiles + 19: ragged last chunks in every layout; M = 1100
     _say(f"mlp split-K tile {tile} splits {splits}")
-    monkeypatch.setenv("NTP_GEMM_TILE", tile)
-    monkeypatch.setenv("NTP_GEMM_SPLIT", str(splits))
+    opts(K.NTP_OPT_GEMM_TILE, tile)
+    opts(K.NTP_OPT_GEMM_SPLIT, splits)
     case = MlpCase(1100, 1096, 8197, 7, 0)
     assert case.n_r == 1171
     got, raw = case.run_gpu(accumulate_twice=True)
@@ -65,12 +67,12 @@ def test_mlp_split_k_every_tile(workspace, monkeypatch, tile, splits):
 
 
 @pytest.mark.parametrize("tile", ["256x256", "224x256", "128x256"])
-def test_split_k_last_chunk_shorter_than_a_k_tile(workspace, monkeypatch, tile):
+def test_split_k_last_chunk_shorter_than_a_k_tile(workspace, opts, tile):
     """Five chunks of 256 (320) over K = 1032 (1288): the last chunk has 8 values, no whole K tile, in every layout
     (tokens, hidden size and shard width are each the K of some GEMM of the layer)."""
     _say(f"split-K with a last chunk of 8, tile {tile}")
-    monkeypatch.setenv("NTP_GEMM_TILE", tile)
-    monkeypatch.setenv("NTP_GEMM_SPLIT", "5")
+    opts(K.NTP_OPT_GEMM_TILE, tile)
+    opts(K.NTP_OPT_GEMM_SPLIT, 5)
     case = MlpCase(1032, 1032, 1288, 1, 0)
     got, _ = case.run_gpu()
     names = _gemm_names()
@@ -79,9 +81,9 @@ def test_split_k_last_chunk_shorter_than_a_k_tile(workspace, monkeypatch, tile):
 
 
 @pytest.mark.parametrize("splits", [2, 4])
-def test_attn_proj_split_k(workspace, monkeypatch, splits):
+def test_attn_proj_split_k(workspace, opts, splits):
     _say(f"attention projections split-K splits {splits}")
-    monkeypatch.setenv("NTP_GEMM_SPLIT", str(splits))
+    opts(K.NTP_OPT_GEMM_SPLIT, splits)
     case = AttnCase(2200, 1544, 32, 4, 64, 3, 1)  # w_qkv = 960, w_o = 704; K tails of 8, 24 and 0
     got = case.run_gpu()
     names = _gemm_names()
@@ -109,7 +111,7 @@ def test_split_k_chosen_for_skinny_shard_only(workspace):
     assert all("k" not in n.split("_")[-1] for n in names), names
 
 
-def test_split_k_skipped_when_workspace_too_small(monkeypatch):
+def test_split_k_skipped_when_workspace_too_small(opts):
     import torch
     import paper_2504_06095_amd as N
     _say("split-K small workspace")
@@ -118,7 +120,7 @@ def test_split_k_skipped_when_workspace_too_small(monkeypatch):
     N.ntp_kernel_timing_enable(1)
     N.ntp_kernel_timing_read()
     try:
-        monkeypatch.setenv("NTP_GEMM_SPLIT", "2")
+        opts(K.NTP_OPT_GEMM_SPLIT, 2)
         case = MlpCase(1100, 1096, 8197, 7, 0)
         got, _ = case.run_gpu()
         names = _gemm_names()
@@ -146,3 +148,38 @@ def test_automatic_choice_on_seeded_random_shapes(workspace):
         _check_all(got, case.oracle(), MLP_NAMES)
     _say(f"variants picked: {sorted(picked)}")
     assert len(picked) >= 3
+
+
+def test_two_handles_on_two_streams_split_concurrently():
+    """The gradient sync runs on a second stream beside the backward pass (Sec. 4.1): two handles, each with a
+    workspace of its own, enqueue split-K shard calls on two streams with nothing ordering them against each
+    other; both results must match the oracle (a shared workspace would mix their partial sums)."""
+    import torch
+    import paper_2504_06095_amd as N
+    _say("two handles, two streams, split-K on both")
+    ha, hb = N.ntp_create(), N.ntp_create()
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    wsa = torch.full((24 << 20,), float("nan"), dtype=torch.float32, device="cuda")
+    wsb = torch.full((24 << 20,), float("nan"), dtype=torch.float32, device="cuda")
+    N.ntp_set_workspace(wsa, handle=ha)
+    N.ntp_set_workspace(wsb, handle=hb)
+    for hd in (ha, hb):
+        N.ntp_set_option(K.NTP_OPT_GEMM_SPLIT, 3, handle=hd)
+    ca, cb = MlpCase(1100, 1096, 8197, 7, 0, tag="strm.a"), MlpCase(1100, 1096, 8197, 7, 3, seed=5, tag="strm.b")
+    assert K.ntp_gemm_choice(0, 1100, ca.n_r, 1096, handle=ha)["k_splits"] == 3
+    torch.cuda.synchronize()
+    outs = []
+    for rep in range(3):  # several rounds, so that the two streams' kernels really interleave
+        with torch.cuda.stream(sa):
+            ga, _ = ca.run_gpu(handle=ha, sync=False)
+        with torch.cuda.stream(sb):
+            gb, _ = cb.run_gpu(handle=hb, sync=False)
+        outs.append((ga, gb))
+    torch.cuda.synchronize()
+    wa, wb = ca.oracle(), cb.oracle()
+    for ga, gb in outs:
+        for got, want in ((ga, wa), (gb, wb)):
+            host = {k: got[k].float().cpu().numpy().astype(np.float64) for k in MLP_NAMES}
+            _check_all(host, want, MLP_NAMES)
+    N.ntp_destroy(ha)
+    N.ntp_destroy(hb)

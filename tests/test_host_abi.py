@@ -127,28 +127,131 @@ def test_reshard_argument_errors_without_launch():
     assert lib.ntp_reshard_segments(C.byref(ok), 0, 3, None, 0, C.byref(n)) == Bd.NTP_ERR_INVALID_ARG
     assert lib.ntp_reshard_segments(C.byref(ok), 2, 3, None, 0, None) == Bd.NTP_ERR_INVALID_ARG
     # null arrays are rejected before anything touches the GPU
-    assert lib.ntp_reshard_grad(C.byref(ok), 2, 3, None, None, None, None, None) == Bd.NTP_ERR_INVALID_ARG
+    h = Bd.default_handle().ptr
+    assert lib.ntp_reshard_grad(h, C.byref(ok), 2, 3, None, None, None, None, None) == Bd.NTP_ERR_INVALID_ARG
+    assert lib.ntp_reshard_grad(None, C.byref(ok), 2, 3, None, None, None, None, None) == Bd.NTP_ERR_INVALID_ARG
 
 
 def test_layer_argument_errors_without_launch():
     lib = Bd.lib()
+    h = Bd.default_handle().ptr
     shape = Bd.MlpShape(4, 12, 3, 0)  # H not a multiple of 8
     z = [None, 0] * 6
-    assert lib.ntp_mlp_shard_fwd(C.byref(shape), *z, None) == Bd.NTP_ERR_ALIGNMENT
+    assert lib.ntp_mlp_shard_fwd(h, C.byref(shape), *z, None) == Bd.NTP_ERR_ALIGNMENT
     shape = Bd.MlpShape(4, 16, 3, 9)  # unknown GeLU mode
-    assert lib.ntp_mlp_shard_fwd(C.byref(shape), *z, None) == Bd.NTP_ERR_INVALID_ARG
+    assert lib.ntp_mlp_shard_fwd(h, C.byref(shape), *z, None) == Bd.NTP_ERR_INVALID_ARG
     shape = Bd.MlpShape(4, 16, 3, 0)  # null tensors
-    assert lib.ntp_mlp_shard_fwd(C.byref(shape), *z, None) == Bd.NTP_ERR_INVALID_ARG
-    assert lib.ntp_mlp_shard_fwd(None, *z, None) == Bd.NTP_ERR_INVALID_ARG
+    assert lib.ntp_mlp_shard_fwd(h, C.byref(shape), *z, None) == Bd.NTP_ERR_INVALID_ARG
+    assert lib.ntp_mlp_shard_fwd(h, None, *z, None) == Bd.NTP_ERR_INVALID_ARG
+    assert lib.ntp_mlp_shard_fwd(None, C.byref(shape), *z, None) == Bd.NTP_ERR_INVALID_ARG  # no handle
     ashape = Bd.AttnShape(4, 16, 12, 8)  # w_qkv not a multiple of 8
-    assert lib.ntp_attn_proj_shard_fwd(C.byref(ashape), *z, None) == Bd.NTP_ERR_ALIGNMENT
+    assert lib.ntp_attn_proj_shard_fwd(h, C.byref(ashape), *z, None) == Bd.NTP_ERR_ALIGNMENT
 
 
 def test_set_workspace_checks_its_arguments():
-    """No device memory is touched by registering: only pointer alignment and size are checked."""
+    """No device memory is touched by setting a workspace: only pointer alignment and size are checked."""
     L = Bd.lib()
-    assert L.ntp_set_workspace(None, 0) == 0
-    assert L.ntp_set_workspace(None, 16) == Bd.NTP_ERR_INVALID_ARG
-    assert L.ntp_set_workspace(0x1010, 1 << 20) == Bd.NTP_ERR_INVALID_ARG  # not 256-byte aligned
-    assert L.ntp_set_workspace(0x1000, -1) == Bd.NTP_ERR_INVALID_ARG
-    assert L.ntp_set_workspace(None, 0) == 0
+    h = Bd.ntp_create()
+    assert L.ntp_set_workspace(h.ptr, None, 0) == 0
+    assert L.ntp_set_workspace(h.ptr, None, 16) == Bd.NTP_ERR_INVALID_ARG
+    assert L.ntp_set_workspace(h.ptr, 0x1010, 1 << 20) == Bd.NTP_ERR_INVALID_ARG  # not 256-byte aligned
+    assert L.ntp_set_workspace(h.ptr, 0x1000, -1) == Bd.NTP_ERR_INVALID_ARG
+    assert L.ntp_set_workspace(None, 0x1000, 256) == Bd.NTP_ERR_INVALID_ARG  # no handle
+    assert L.ntp_set_workspace(h.ptr, None, 0) == 0
+    Bd.ntp_destroy(h)
+
+
+def test_handles_are_independent():
+    """Workspace and options belong to one handle: what a second handle chooses does not change."""
+    a, b = Bd.ntp_create(), Bd.ntp_create()
+    assert a.ptr.value != b.ptr.value
+    info = Bd.ntp_device_info(a)
+    assert info["compute_units"] >= 1 and (info["device"] >= 0 or info["compute_units"] == 256)
+    assert Bd.lib().ntp_set_workspace(a.ptr, 0x10000000, 1 << 30) == 0
+    skinny = (0, 4096, 640, 8192)  # 48 output tiles of 256 x 256 over K = 8192
+    assert Bd.ntp_gemm_choice(*skinny, handle=a)["k_splits"] > 1
+    assert Bd.ntp_gemm_choice(*skinny, handle=b)["k_splits"] == 1
+    Bd.ntp_set_option(Bd.NTP_OPT_GEMM_TILE, "256x192", handle=b)
+    cb = Bd.ntp_gemm_choice(0, 2048, 7022, 12288, handle=b)
+    ca = Bd.ntp_gemm_choice(0, 2048, 7022, 12288, handle=a)
+    assert (cb["tile_m"], cb["tile_n"]) == (256, 192) and (ca["tile_m"], ca["tile_n"]) == (256, 224)
+    Bd.ntp_set_option(Bd.NTP_OPT_GEMM_SPLIT, 1, handle=a)
+    assert Bd.ntp_gemm_choice(*skinny, handle=a)["k_splits"] == 1
+    Bd.ntp_destroy(a)
+    Bd.ntp_destroy(b)
+    Bd.ntp_destroy(b)  # destroying twice through the binding is harmless (the pointer is cleared)
+    assert Bd.lib().ntp_destroy(None) == 0
+
+
+def test_set_option_checks_its_arguments():
+    L = Bd.lib()
+    h = Bd.ntp_create()
+    assert L.ntp_set_option(None, Bd.NTP_OPT_GEMM_TILE, 0) == Bd.NTP_ERR_INVALID_ARG
+    assert L.ntp_set_option(h.ptr, -1, 0) == Bd.NTP_ERR_INVALID_ARG
+    assert L.ntp_set_option(h.ptr, 9, 0) == Bd.NTP_ERR_INVALID_ARG
+    assert L.ntp_set_option(h.ptr, Bd.NTP_OPT_GEMM_TILE, 11) == Bd.NTP_ERR_INVALID_ARG
+    assert L.ntp_set_option(h.ptr, Bd.NTP_OPT_GEMM_SPLIT, 9) == Bd.NTP_ERR_INVALID_ARG
+    assert L.ntp_set_option(h.ptr, Bd.NTP_OPT_ATTN_PARTS, 17) == Bd.NTP_ERR_INVALID_ARG
+    assert L.ntp_set_option(h.ptr, Bd.NTP_OPT_RESHARD_NO_TABLE, 2) == Bd.NTP_ERR_INVALID_ARG
+    assert L.ntp_set_option(h.ptr, Bd.NTP_OPT_RESHARD_BLOCK, -4) == Bd.NTP_ERR_INVALID_ARG
+    for opt in range(9):
+        assert L.ntp_set_option(h.ptr, opt, 1) == 0
+        assert L.ntp_set_option(h.ptr, opt, 0) == 0
+    Bd.ntp_destroy(h)
+
+
+def test_workspace_bytes_is_what_an_unlimited_workspace_would_be_used_for():
+    """ntp_workspace_bytes: 0 where nothing would be split; otherwise exactly the bytes below which the launcher's
+    choice changes (one byte less and the largest split no longer fits)."""
+    h = Bd.ntp_create()
+    L = Bd.lib()
+    # GPT-3 shape MLP shard at TP 7: every GEMM fills the GPU, nothing to split except maybe nothing at all
+    big = Bd.MlpShape(2048, 12288, 7022, 0)
+    assert Bd.ntp_workspace_bytes(Bd.NTP_CALL_MLP_SHARD, big, handle=h) == 0
+    # 405B shape at TP 71: X A_i is 8192 x 750 over K = 16384 -> split; the wish is splits * M * round_up(N64, 16) * 4
+    skinny = Bd.MlpShape(8192, 16384, 750, 0)
+    need = Bd.ntp_workspace_bytes(Bd.NTP_CALL_MLP_SHARD, skinny, handle=h)
+    assert need > 0 and need % (8192 * 768 * 4) == 0
+    assert L.ntp_set_workspace(h.ptr, 0x10000000, need) == 0
+    with_all = Bd.ntp_gemm_choice(0, 8192, 750, 16384, handle=h)
+    assert with_all["k_splits"] * 8192 * 768 * 4 <= need and with_all["k_splits"] > 1
+    assert L.ntp_set_workspace(h.ptr, 0x10000000, 8192 * 752 * 4 * 2 - 256) == 0  # (ntp_gemm_choice packs rows to 752)
+    assert Bd.ntp_gemm_choice(0, 8192, 750, 16384, handle=h)["k_splits"] == 1
+    # attention projections of 3 heads at TP 30 (4096 tokens, hidden 8192) and their core
+    att = Bd.AttnShape(4096, 8192, 640, 384)
+    assert Bd.ntp_workspace_bytes(Bd.NTP_CALL_ATTN_PROJ_SHARD, att, handle=h) > 0
+    plan = N.ntp_attn_shard_plan(64, 8, 128, 30, 0)
+    core = N.attn_core_shape(1, 4096, plan, 8, True)
+    need_core = Bd.ntp_workspace_bytes(Bd.NTP_CALL_ATTN_CORE_SHARD, core, handle=h)
+    assert need_core > 0
+    assert L.ntp_set_workspace(h.ptr, 0x10000000, need_core) == 0
+    c = Bd.ntp_attn_core_choice(core, handle=h)
+    assert max(c["fwd_parts"], c["dq_parts"], c["dkv_parts"]) > 1
+    many = N.attn_core_shape(4, 4096, N.ntp_attn_shard_plan(96, 96, 128, 7, 0), 1, False)  # 14 heads x 4 sequences: never cut
+    assert Bd.ntp_workspace_bytes(Bd.NTP_CALL_ATTN_CORE_SHARD, many, handle=h) == 0
+    # errors
+    n = C.c_int64()
+    assert L.ntp_workspace_bytes(h.ptr, 7, C.byref(big), C.byref(n)) == Bd.NTP_ERR_INVALID_ARG
+    assert L.ntp_workspace_bytes(h.ptr, 0, None, C.byref(n)) == Bd.NTP_ERR_INVALID_ARG
+    assert L.ntp_workspace_bytes(None, 0, C.byref(big), C.byref(n)) == Bd.NTP_ERR_INVALID_ARG
+    assert L.ntp_workspace_bytes(h.ptr, 0, C.byref(Bd.MlpShape(4, 12, 3, 0)), C.byref(n)) == Bd.NTP_ERR_INVALID_ARG
+    Bd.ntp_destroy(h)
+
+
+def test_unprepared_reshard_plan_refuses_to_run():
+    """ntp_reshard_plan_run never allocates: a plan that was not prepared returns NOT_PREPARED (or, with no
+    device visible, NO_DEVICE) after its argument checks and enqueues nothing."""
+    comp, sync = N.ntp_comp_sync_plan(12, 4, 3)
+    plan = N.ntp_reshard_plan_create(N.tensor_spec(8, 12, 1), 4, comp, 3, sync)
+    L = Bd.lib()
+    h = Bd.default_handle()
+    vp, i64 = C.c_void_p, C.c_int64
+    # fake, non-overlapping, aligned shard addresses: nothing dereferences them before the prepared check
+    sp = (vp * 4)(*[0x10000000 + 0x10000 * r for r in range(4)])
+    sl = (i64 * 4)(*[3] * 4)
+    dp = (vp * 3)(*[0x20000000 + 0x10000 * r for r in range(3)])
+    dl = (i64 * 3)(*[4] * 3)
+    st = L.ntp_reshard_plan_run(h.ptr, plan._h, sp, sl, dp, dl, None)
+    assert st in (Bd.NTP_ERR_NOT_PREPARED, Bd.NTP_ERR_NO_DEVICE)
+    assert L.ntp_reshard_plan_run(None, plan._h, sp, sl, dp, dl, None) == Bd.NTP_ERR_INVALID_ARG
+    plan.destroy()

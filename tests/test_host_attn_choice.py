@@ -14,9 +14,9 @@ def _shape(n_q, n_kv, tp, rank, n_seq, S, causal, d=128):
 
 @pytest.fixture
 def workspace_1gib():
-    assert Bd.lib().ntp_set_workspace(FAKE_WS, 1 << 30) == 0
+    assert Bd.lib().ntp_set_workspace(Bd.default_handle().ptr, FAKE_WS, 1 << 30) == 0
     yield
-    assert Bd.lib().ntp_set_workspace(None, 0) == 0
+    assert Bd.lib().ntp_set_workspace(Bd.default_handle().ptr, None, 0) == 0
 
 
 def test_nothing_is_cut_without_a_workspace():
@@ -51,14 +51,14 @@ def test_short_walks_are_not_cut(workspace_1gib):
 
 
 def test_parts_respect_the_workspace_size():
-    assert Bd.lib().ntp_set_workspace(FAKE_WS, 16 << 20) == 0  # 16 MiB
+    assert Bd.lib().ntp_set_workspace(Bd.default_handle().ptr, FAKE_WS, 16 << 20) == 0  # 16 MiB
     try:
         c = N.ntp_attn_core_choice(_shape(64, 8, 30, 0, 1, 4096, True))
         # per part: forward 192 workgroups x 64 rows x 132 floats = 6.5 MB, dQ 192 x 64 x 128 floats = 6.3 MB,
         # dK/dV 64 workgroups x 64 rows x 256 floats = 4 MiB
         assert (c["fwd_parts"], c["dq_parts"], c["dkv_parts"]) == (2, 2, 4)
     finally:
-        assert Bd.lib().ntp_set_workspace(None, 0) == 0
+        assert Bd.lib().ntp_set_workspace(Bd.default_handle().ptr, None, 0) == 0
 
 
 def test_choice_rejects_bad_shapes():

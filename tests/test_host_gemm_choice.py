@@ -14,9 +14,9 @@ FAKE_WS = 0x10000000  # an aligned address: registering touches no memory
 
 @pytest.fixture
 def workspace_1gib():
-    assert Bd.lib().ntp_set_workspace(FAKE_WS, 1 << 30) == 0
+    assert Bd.lib().ntp_set_workspace(Bd.default_handle().ptr, FAKE_WS, 1 << 30) == 0
     yield 1 << 30
-    assert Bd.lib().ntp_set_workspace(None, 0) == 0
+    assert Bd.lib().ntp_set_workspace(Bd.default_handle().ptr, None, 0) == 0
 
 
 def _tiles(c, M, N):
@@ -61,11 +61,11 @@ def test_split_k_only_for_skinny_long_k(workspace_1gib):
 
 
 def test_split_k_respects_the_workspace_size():
-    assert Bd.lib().ntp_set_workspace(FAKE_WS, 8 << 20) == 0  # 8 MiB: two slices of 4096 x 640 fp32 would need 21 MB
+    assert Bd.lib().ntp_set_workspace(Bd.default_handle().ptr, FAKE_WS, 8 << 20) == 0  # 8 MiB: two slices of 4096 x 640 fp32 would need 21 MB
     try:
         assert N.ntp_gemm_choice(0, 4096, 640, 8192)["k_splits"] == 1
     finally:
-        assert Bd.lib().ntp_set_workspace(None, 0) == 0
+        assert Bd.lib().ntp_set_workspace(Bd.default_handle().ptr, None, 0) == 0
 
 
 def test_choice_rejects_bad_arguments():
