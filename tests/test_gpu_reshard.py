@@ -158,4 +158,4 @@ def test_reshard_one_gpu_share_and_alias_check():
     import ctypes as C
     sp, sl = (C.c_void_p * a)(*[t.data_ptr() for t in full]), (C.c_int64 * a)(*[1] * a)
     dp, dl = (C.c_void_p * b)(*[t.data_ptr() for t in dst]), (C.c_int64 * b)(*[t.stride(0) for t in dst])
-    assert lib.ntp_reshard_grad(C.byref(spec), a, b, sp, sl, dp, dl, None) == N.binding.NTP_ERR_INVALID_ARG
+    assert lib.ntp_reshard_grad(N.default_handle().ptr, C.byref(spec), a, b, sp, sl, dp, dl, None) == N.binding.NTP_ERR_INVALID_ARG
