@@ -61,6 +61,7 @@ extern "C" {
 #define NTP_ERR_UNSUPPORTED (-4) /* a size beyond what the kernels index (see each call)         */
 #define NTP_ERR_NOT_PREPARED (-5) /* ntp_reshard_plan_run before ntp_reshard_plan_prepare        */
 #define NTP_ERR_NO_DEVICE (-6)   /* a device call on a handle created with no device visible    */
+#define NTP_ERR_SCRATCH_TOO_SMALL (-7) /* the shape needs more than NTP_STATIC_SCRATCH_BYTES      */
 
 #define NTP_GELU_ERF 0  /* x * Phi(x)                                  */
 #define NTP_GELU_TANH 1 /* 0.5 x (1 + tanh(sqrt(2/pi)(x + 0.044715 x^3))) */
@@ -501,6 +502,28 @@ int ntp_attn_core_choice(const ntp_handle_t* h, const ntp_attn_core_shape_t* sha
  * calibration_copy_kernel.  Its known traffic (bytes read, bytes written) is what
  * the profiler's HBM byte counters are scaled by when a kernel's traffic is reported. */
 int ntp_calibration_copy(ntp_handle_t* h, void* dst, const void* src, int64_t bytes, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * For callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc) and so cannot give the
+ * handle a workspace: ntp_attn_proj_shard_fwd with the split-K partial sums kept
+ * in a static device array of NTP_STATIC_SCRATCH_BYTES that is part of the
+ * library's code object (each GPU the library runs on holds it until the process
+ * ends).  Arguments, results and errors as for ntp_attn_proj_shard_fwd; the
+ * handle's own workspace is ignored.  The call allocates nothing and makes the same
+ * launch decisions as ntp_attn_proj_shard_fwd would with a workspace of
+ * NTP_STATIC_SCRATCH_BYTES, so results are bit-identical to that.  A shape whose
+ * launches could use more room than that (ntp_workspace_bytes restricted to the
+ * halves this call runs) returns NTP_ERR_SCRATCH_TOO_SMALL and launches nothing.
+ * Every call on one GPU, through any handle, uses that GPU's one array: calls
+ * that may overlap in time on a GPU race; order them on one stream or with events.
+ * Nothing in the array has to be cleared between calls (every partial sum that is
+ * read was written by the same call). */
+#define NTP_STATIC_SCRATCH_BYTES (32 << 20)
+int ntp_attn_proj_shard_fwd_static(ntp_handle_t* h, const ntp_attn_shape_t* shape, const void* X, int64_t ldx,
+                                   const void* Wqkv, int64_t ldwqkv, void* QKV, int64_t ldqkv,
+                                   const void* C, int64_t ldc, const void* Wo, int64_t ldwo, void* Zpart,
+                                   int64_t ldz, void* stream);
 
 #ifdef __cplusplus
 }

@@ -19,6 +19,8 @@ NTP_ERR_LAUNCH = -3
 NTP_ERR_UNSUPPORTED = -4
 NTP_ERR_NOT_PREPARED = -5
 NTP_ERR_NO_DEVICE = -6
+NTP_ERR_SCRATCH_TOO_SMALL = -7
+NTP_STATIC_SCRATCH_BYTES = 32 << 20
 NTP_OPT_GEMM_TILE = 0
 NTP_OPT_GEMM_SPLIT = 1
 NTP_OPT_GEMM_NO_RING_TAIL = 2
@@ -47,7 +49,7 @@ EXPORTS = (
     "ntp_reshard_plan_table", "ntp_reshard_plan_prepare", "ntp_reshard_plan_run", "ntp_reshard_plan_destroy", "ntp_reshard_row_segments",
     "ntp_mlp_shard_bwd_resharded", "ntp_attn_proj_shard_bwd_resharded", "ntp_attn_core_shard_fwd", "ntp_attn_core_shard_bwd",
     "ntp_set_workspace", "ntp_gemm_choice", "ntp_attn_core_choice", "ntp_create", "ntp_destroy", "ntp_device_info",
-    "ntp_set_option", "ntp_workspace_bytes",
+    "ntp_set_option", "ntp_workspace_bytes", "ntp_attn_proj_shard_fwd_static",
 )
 
 
@@ -132,6 +134,7 @@ def lib() -> C.CDLL:
         L.ntp_mlp_shard_bwd.argtypes = [vp, C.POINTER(MlpShape)] + [vp, i64] * 10 + [C.c_int32, vp]
         L.ntp_attn_proj_shard_fwd.argtypes = [vp, C.POINTER(AttnShape)] + [vp, i64] * 6 + [vp]
         L.ntp_attn_proj_shard_bwd.argtypes = [vp, C.POINTER(AttnShape)] + [vp, i64] * 10 + [C.c_int32, vp]
+        L.ntp_attn_proj_shard_fwd_static.argtypes = L.ntp_attn_proj_shard_fwd.argtypes
         L.ntp_reshard_segments.argtypes = [C.POINTER(TensorSpec), C.c_int32, C.c_int32, C.POINTER(Segment), i64,
                                            C.POINTER(i64)]
         L.ntp_reshard_grad.argtypes = [vp, C.POINTER(TensorSpec), C.c_int32, C.c_int32, C.POINTER(vp), C.POINTER(i64),
@@ -327,6 +330,18 @@ def ntp_attn_proj_shard_fwd(M, H, w_qkv, w_o, X=None, Wqkv=None, QKV=None, C_=No
     for t in (X, Wqkv, QKV, C_, Wo, Zpart):
         args += list(_mat(t, bf))
     _check(lib().ntp_attn_proj_shard_fwd(_h(handle), C.byref(shape), *args, _stream()), "ntp_attn_proj_shard_fwd")
+
+
+def ntp_attn_proj_shard_fwd_static(M, H, w_qkv, w_o, X=None, Wqkv=None, QKV=None, C_=None, Wo=None, Zpart=None,
+                                   handle=None) -> None:
+    """ntp_attn_proj_shard_fwd with the split-K partial sums in the library's static device array."""
+    import torch
+    bf = torch.bfloat16
+    shape = AttnShape(M, H, w_qkv, w_o)
+    args = []
+    for t in (X, Wqkv, QKV, C_, Wo, Zpart):
+        args += list(_mat(t, bf))
+    _check(lib().ntp_attn_proj_shard_fwd_static(_h(handle), C.byref(shape), *args, _stream()), "ntp_attn_proj_shard_fwd_static")
 
 
 def ntp_attn_proj_shard_bwd(M, H, w_qkv, w_o, dZ=None, dQKV=None, X=None, C_=None, Wqkv=None, Wo=None, dC=None,

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libntp.so")
 
-SOURCES = ["ntp_plan.cpp", "ntp_handle.cpp", "ntp_layers.cpp", "ntp_timing.cpp", "ntp_gemm.hip", "ntp_gemm_nt.hip", "ntp_gemm_nn.hip",
+SOURCES = ["ntp_plan.cpp", "ntp_handle.hip", "ntp_layers.cpp", "ntp_timing.cpp", "ntp_gemm.hip", "ntp_gemm_nt.hip", "ntp_gemm_nn.hip",
            "ntp_gemm_tn.hip", "ntp_reshard.hip", "ntp_attn_core.hip"]
 
 # -packed-fp32-ops is switched off: the compiler must not form packed fp32 VALU ops.

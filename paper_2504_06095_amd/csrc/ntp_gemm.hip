@@ -295,7 +295,9 @@ int gemm_launch(ntp_handle* h, const GemmDesc& d, void* stream) {
   // with A K-strided (no ring kernel)
   const bool split_ok = a_rows * d.lda * 2 < (int64_t(1) << 32) && b_rows * d.ldb * 2 < (int64_t(1) << 32) && (d.a_kc || !d.b_kc);
   const int64_t ldw = (n_store + 15) / 16 * 16;
-  const SplitChoice sc = plan_gemm(h, h->workspace ? h->workspace_bytes : 0, g, layout, ring_ok, split_ok, ldw);
+  void* const ws_ptr = d.ws_override ? d.ws_override : h->workspace;
+  const int64_t ws_bytes = d.ws_override ? d.ws_override_bytes : (h->workspace ? h->workspace_bytes : 0);
+  const SplitChoice sc = plan_gemm(h, ws_ptr ? ws_bytes : 0, g, layout, ring_ok, split_ok, ldw);
   const int variant = sc.tile;
   if (ntp::timing_on(h)) {
     char name[48], vn[16], sn[8] = "";
@@ -317,7 +319,7 @@ int gemm_launch(ntp_handle* h, const GemmDesc& d, void* stream) {
     GemmArgs gp = g;  // the partial-sum launch: fp32 to the workspace, no row segments
     gp.ring_tail = 0;
     gp.a_extent = uint32_t(operand_extent_bytes(d.a_kc, d.M, d.K, d.lda, false));
-    gp.C = h->workspace;
+    gp.C = ws_ptr;
     gp.ldc = ldw;
     gp.n_segs = 0;
     gp.k_splits = sc.splits;
@@ -329,7 +331,7 @@ int gemm_launch(ntp_handle* h, const GemmDesc& d, void* stream) {
     if (st == NTP_OK) {
       const int64_t threads = int64_t(d.M) * (n_store / 4);
       const dim3 grid(uint32_t((threads + 255) / 256)), block(256);
-      const float* ws = static_cast<const float*>(h->workspace);
+      const float* ws = static_cast<const float*>(ws_ptr);
       st = dispatch_epilogue(d.epilogue, [&](auto e) {
         hipLaunchKernelGGL((splitk_reduce_kernel<decltype(e)::value>), grid, block, 0, s, g, ws, gp.split_stride, ldw, sc.splits);
         return hipGetLastError() == hipSuccess ? NTP_OK : NTP_ERR_LAUNCH;

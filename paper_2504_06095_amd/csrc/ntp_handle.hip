@@ -1,7 +1,14 @@
-// The library handle: device query, the caller's workspace, tuning overrides.  Host code only.
-#include <hip/hip_runtime_api.h>
+// The library handle: device query, the caller's workspace, tuning overrides; and the static device scratch
+// array that serves callers who cannot allocate a workspace.
+#include <hip/hip_runtime.h>
 
 #include "ntp_internal.h"
+
+// Device memory that belongs to the library's code object: every GPU the library runs on holds one copy of it
+// from the moment the code object is loaded there until the process ends.  In host code this name is only a
+// stand-in for the symbol; the memory's device address is looked up once per handle (ntp_create, with the
+// handle's device current) and only that address is ever passed to a kernel.
+static __device__ __align__(256) unsigned char scratch[NTP_STATIC_SCRATCH_BYTES];
 
 extern "C" int ntp_create(ntp_handle_t** out) {
   if (!out) return NTP_ERR_INVALID_ARG;
@@ -11,6 +18,13 @@ extern "C" int ntp_create(ntp_handle_t** out) {
       hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0) {
     h->device = dev;
     h->compute_units = cus;
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      delete h;
+      return NTP_ERR_LAUNCH;
+    }
+    h->static_scratch = ptr;  // this device's copy of the array
   } else {
     (void)hipGetLastError();  // no device visible: a handle for the host-only calls
   }

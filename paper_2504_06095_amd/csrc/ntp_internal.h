@@ -17,6 +17,7 @@ struct ntp_handle {
   int compute_units = 256;  // of that device (an MI355X has 256; the value used when none was visible)
   void* workspace = nullptr;
   int64_t workspace_bytes = 0;
+  void* static_scratch = nullptr;  // device address of the library's static scratch array on `device`
   int64_t opt[NTP_OPT_COUNT_] = {};  // ntp_set_option values; 0 everywhere = the library's own choices
   // measurement aid (ntp_kernel_timing_*)
   struct Pending {
@@ -101,6 +102,9 @@ struct GemmDesc {
   // (host array; a row that no segment lists is not stored)
   const ntp_row_segment_t* segs;
   int32_t n_segs;
+  // when set, the split-K partial sums go here instead of to the handle's workspace
+  void* ws_override;
+  int64_t ws_override_bytes;
 };
 
 // Validates and enqueues one GEMM on `stream`.  Returns an NTP_* status.

@@ -137,25 +137,58 @@ bool bad_attn_shape(const ntp_attn_shape_t* s) {
 }
 }  // namespace
 
-// Eq. 6 (column-parallel QKV) and Eq. 4 (row-parallel output projection).
-extern "C" int ntp_attn_proj_shard_fwd(ntp_handle_t* h, const ntp_attn_shape_t* s, const void* X, int64_t ldx,
-                                       const void* Wqkv, int64_t ldwqkv, void* QKV, int64_t ldqkv,
-                                       const void* C, int64_t ldc, const void* Wo, int64_t ldwo,
-                                       void* Zpart, int64_t ldz, void* stream) {
+namespace {
+
+// Eq. 6 (column-parallel QKV) and Eq. 4 (row-parallel output projection).  ws != NULL: split-K partial sums
+// go there instead of to the handle's workspace.
+int attn_fwd(ntp_handle_t* h, const ntp_attn_shape_t* s, const void* X, int64_t ldx, const void* Wqkv, int64_t ldwqkv,
+             void* QKV, int64_t ldqkv, const void* C, int64_t ldc, const void* Wo, int64_t ldwo, void* Zpart, int64_t ldz,
+             void* ws, int64_t ws_bytes, void* stream) {
   if (!h || bad_attn_shape(s)) return NTP_ERR_INVALID_ARG;
   if (s->H % 8 || s->w_qkv % 8 || s->w_o % 8) return NTP_ERR_ALIGNMENT;
   int st = NTP_OK;
   if (QKV) {
     if (s->M > 0 && s->w_qkv > 0 && s->H > 0 && (!X || !Wqkv)) return NTP_ERR_INVALID_ARG;
     GemmDesc d = gemm(X, ldx, true, Wqkv, ldwqkv, true, s->M, s->w_qkv, s->H, ntp::EPI_BF16, QKV, ldqkv);
+    d.ws_override = ws;
+    d.ws_override_bytes = ws_bytes;
     if ((st = ntp::gemm_launch(h, d, stream)) != NTP_OK) return st;
   }
   if (Zpart) {
     if (s->M > 0 && s->w_o > 0 && s->H > 0 && (!C || !Wo)) return NTP_ERR_INVALID_ARG;
     GemmDesc d = gemm(C, ldc, true, Wo, ldwo, false, s->M, s->H, s->w_o, ntp::EPI_BF16, Zpart, ldz);
+    d.ws_override = ws;
+    d.ws_override_bytes = ws_bytes;
     if ((st = ntp::gemm_launch(h, d, stream)) != NTP_OK) return st;
   }
   return NTP_OK;
+}
+
+}  // namespace
+
+extern "C" int ntp_attn_proj_shard_fwd(ntp_handle_t* h, const ntp_attn_shape_t* s, const void* X, int64_t ldx,
+                                       const void* Wqkv, int64_t ldwqkv, void* QKV, int64_t ldqkv,
+                                       const void* C, int64_t ldc, const void* Wo, int64_t ldwo,
+                                       void* Zpart, int64_t ldz, void* stream) {
+  return attn_fwd(h, s, X, ldx, Wqkv, ldwqkv, QKV, ldqkv, C, ldc, Wo, ldwo, Zpart, ldz, nullptr, 0, stream);
+}
+
+// The same call for callers that cannot allocate: the split-K partial sums go to the library's static device
+// array (this device's copy, whose address ntp_create looked up) instead of a caller-provided workspace.
+extern "C" int ntp_attn_proj_shard_fwd_static(ntp_handle_t* h, const ntp_attn_shape_t* s, const void* X, int64_t ldx,
+                                              const void* Wqkv, int64_t ldwqkv, void* QKV, int64_t ldqkv,
+                                              const void* C, int64_t ldc, const void* Wo, int64_t ldwo,
+                                              void* Zpart, int64_t ldz, void* stream) {
+  if (!h || bad_attn_shape(s)) return NTP_ERR_INVALID_ARG;
+  if (s->H % 8 || s->w_qkv % 8 || s->w_o % 8) return NTP_ERR_ALIGNMENT;
+  if (h->device < 0 || !h->static_scratch) return NTP_ERR_NO_DEVICE;
+  // a shape whose launches would want more partial-sum room than the array has is refused, not run unsplit
+  int64_t wish = 0;
+  if (QKV) wish = std::max(wish, ntp::gemm_workspace_wish(h, 0, s->M, s->w_qkv, s->w_qkv, s->H));
+  if (Zpart) wish = std::max(wish, ntp::gemm_workspace_wish(h, 1, s->M, s->H, s->H, s->w_o));
+  if (wish > int64_t(NTP_STATIC_SCRATCH_BYTES)) return NTP_ERR_SCRATCH_TOO_SMALL;
+  return attn_fwd(h, s, X, ldx, Wqkv, ldwqkv, QKV, ldqkv, C, ldc, Wo, ldwo, Zpart, ldz, h->static_scratch,
+                  int64_t(NTP_STATIC_SCRATCH_BYTES), stream);
 }
 
 namespace {

@@ -16,6 +16,7 @@ extern "C" const char* ntp_status_string(int status) {
     case NTP_ERR_UNSUPPORTED: return "size not supported";
     case NTP_ERR_NOT_PREPARED: return "reshard plan not prepared on this device";
     case NTP_ERR_NO_DEVICE: return "the handle was created with no device visible";
+    case NTP_ERR_SCRATCH_TOO_SMALL: return "the shape needs more partial-sum room than the static scratch array has";
     default: return "unknown status";
   }
 }
