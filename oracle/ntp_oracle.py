@@ -345,6 +345,36 @@ def reshard(src_shards, partition_dim, unit, kind, src_tp, dst_tp, n_units, n_q=
     return out
 
 
+def replica_sum(shards, partition_dim, unit, kind, tp, n_units, n_q=0, n_kv=0):
+    """Sum of a replicated unit over the ranks that hold it, written back to every holder.
+
+    With grouped KV heads a KV head sits on every rank whose query heads read it
+    (attn_shard_plan), and each of those ranks' weight-gradient GEMMs yields only
+    the contribution of its own query heads: the gradient of the head is the sum
+    of the holders' blocks (chain rule on Eq. 5-6: dW_K,g = sum over the query
+    heads h of group g of X^T dK_g^(h)).  Units held by one rank are left alone.
+    Returns new float64 shards; the inputs are not modified."""
+    holders = {}
+    for r in range(tp):
+        for local, u in enumerate(unit_list(kind, n_units, tp, r, n_q, n_kv)):
+            holders.setdefault(u, []).append((r, local))
+    out = [np.array(sh, dtype=np.float64, copy=True) for sh in shards]
+
+    def block(arrs, r, local):
+        sl = [slice(None)] * arrs[r].ndim
+        sl[partition_dim] = slice(local * unit, (local + 1) * unit)
+        return tuple(sl)
+    for u, where in holders.items():
+        if len(where) < 2:
+            continue
+        total = np.zeros_like(out[where[0][0]][block(out, *where[0])])
+        for r, local in where:  # ascending rank order
+            total = total + np.asarray(shards[r], dtype=np.float64)[block(shards, r, local)]
+        for r, local in where:
+            out[r][block(out, r, local)] = total
+    return out
+
+
 def reshard_source_of(kind, n_units, src_tp, dst_tp, dst_rank, dst_local_unit, n_q=0, n_kv=0):
     """Where one destination unit comes from: (src_rank, src_local_unit).  Used
     to check sampled outputs at sizes where `reshard` itself is too slow."""

@@ -114,3 +114,59 @@ def test_reshard_source_of_agrees_with_reshard():
         for lu in range(dst[s].shape[1]):
             r, sl = O.reshard_source_of(O.PLAIN, 97, 7, 8, s, lu)
             assert np.array_equal(dst[s][:, lu], src[r][:, sl])
+
+
+def test_replica_sum_by_hand():
+    """4 query heads, 1 KV head, 2 ranks: logical units [q0 q1 q2 q3 | k0 | v0]; each rank holds 2 query heads and a
+    copy of k0 and v0.  The copies become the sum of both ranks' blocks; query heads are left alone."""
+    a = np.array([[1., 2., 10., 100.]])   # rank 0: q0 q1 k0 v0
+    b = np.array([[3., 4., 20., 200.]])   # rank 1: q2 q3 k0 v0
+    got = O.replica_sum([a, b], 1, 1, O.QKV_GQA, 2, 6, 4, 1)
+    assert np.array_equal(got[0], [[1., 2., 30., 300.]]) and np.array_equal(got[1], [[3., 4., 30., 300.]])
+    assert np.array_equal(a, [[1., 2., 10., 100.]])  # inputs untouched
+    # a layout without replication, and a PLAIN tensor, come back unchanged
+    c = [np.arange(6.).reshape(1, 6)]
+    assert np.array_equal(O.replica_sum(c, 1, 1, O.QKV_GQA, 1, 6, 4, 1)[0], c[0])
+    p = [np.arange(4.).reshape(4, 1), np.arange(3.).reshape(3, 1)]
+    assert all(np.array_equal(x, y) for x, y in zip(O.replica_sum(p, 0, 1, O.PLAIN, 2, 7), p))
+
+
+@pytest.mark.parametrize("n_q,n_kv,tp,dst_tp", [(8, 2, 3, 4), (16, 4, 7, 8), (64, 8, 30, 32), (12, 12, 5, 7), (4, 1, 4, 2)])
+def test_resharded_qkv_gradient_tiles_the_unsharded_gradient(n_q, n_kv, tp, dst_tp):
+    """The invariant the reshard of a weight gradient has to keep (Sec. 3.1: gradients are sharded like their
+    weights): every rank's dW_qkv,i = X^T dQKV_i, where dQKV_i holds, for a KV head, only what the rank's own query
+    heads contribute; after replica_sum and reshard, EVERY destination rank's block of every unit, replicated K/V
+    copies included, equals that unit's columns of the unsharded gradient X^T dQKV.  Without replica_sum the K/V
+    blocks of a head that several source ranks hold would miss the other holders' contributions."""
+    rng = np.random.default_rng(n_q * 100 + tp)
+    M, H, d = 5, 6, 2
+    group = n_q // n_kv
+    X = rng.standard_normal((M, H))
+    # per query head h: its own dQ_h and the dK, dV contributions it makes to its KV head (attention core backward
+    # per head; arbitrary values here: only linearity matters)
+    dQ = rng.standard_normal((n_q, M, d))
+    dKc = rng.standard_normal((n_q, M, d))
+    dVc = rng.standard_normal((n_q, M, d))
+    dK = np.stack([dKc[g * group:(g + 1) * group].sum(0) for g in range(n_kv)])
+    dV = np.stack([dVc[g * group:(g + 1) * group].sum(0) for g in range(n_kv)])
+    full = X.T @ np.concatenate([np.concatenate(list(dQ), 1), np.concatenate(list(dK), 1), np.concatenate(list(dV), 1)], 1)
+    n_units = n_q + 2 * n_kv
+    shards = []
+    for r in range(tp):
+        p = O.attn_shard_plan(n_q, n_kv, tp, r)
+        mine = range(p["q_off"], p["q_off"] + p["q_cnt"])
+        cols = [dQ[h] for h in mine]
+        for contrib in (dKc, dVc):
+            for g in range(p["kv_off"], p["kv_off"] + p["kv_cnt"]):
+                cols.append(sum((contrib[h] for h in mine if h // group == g), np.zeros((M, d))))
+        dQKV_i = np.concatenate(cols, 1) if cols else np.zeros((M, 0))
+        shards.append(O.attn_proj_shard_bwd(np.zeros((M, H)), dQKV_i, X, np.zeros((M, p["q_cnt"] * d)),
+                                            np.zeros((H, dQKV_i.shape[1])), np.zeros((p["q_cnt"] * d, H)))[2])
+    summed = O.replica_sum(shards, 1, d, O.QKV_GQA, tp, n_units, n_q, n_kv)
+    out = O.reshard(summed, 1, d, O.QKV_GQA, tp, dst_tp, n_units, n_q, n_kv)
+    for s_ in range(dst_tp):
+        want = O.cut_shard(full, 1, d, O.QKV_GQA, dst_tp, s_, n_q, n_kv)
+        assert np.allclose(out[s_], want, rtol=1e-12, atol=1e-12)
+    if n_kv < tp and n_q != n_kv:  # some head is replicated: leaving the sum out must show
+        plain = O.reshard(shards, 1, d, O.QKV_GQA, tp, dst_tp, n_units, n_q, n_kv)
+        assert any(not np.allclose(plain[s_], O.cut_shard(full, 1, d, O.QKV_GQA, dst_tp, s_, n_q, n_kv)) for s_ in range(dst_tp))
