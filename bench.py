@@ -138,21 +138,30 @@ def mfma_roofline(table, steps, section):
 
 
 class ClockSampler:
-    """Samples the GPU's shader clock from sysfs while the timed work runs (hwmon freq1_input, Hz); reports None
-    where the file is not readable."""
+    """Samples the GPU's shader clock while the timed work runs, from the driver's sysfs file pp_dpm_sclk (the line
+    marked with * is the clock the power management runs the shader engines at just then); reports None where
+    the file is not readable."""
 
     def __init__(self):
-        paths = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/freq1_input"))
+        paths = sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))
         self.path = paths[0] if paths else None
         self.samples, self._stop, self._thr = [], threading.Event(), None
+
+    def _read(self):
+        for line in open(self.path).read().splitlines():
+            if "*" in line:
+                return float(line.split(":")[1].lower().replace("mhz", "").replace("*", "").strip())
+        return None
 
     def _run(self):
         while not self._stop.is_set():
             try:
-                self.samples.append(int(open(self.path).read().strip()) / 1e6)
+                v = self._read()
+                if v:
+                    self.samples.append(v)
             except Exception:
                 pass
-            time.sleep(0.002)
+            time.sleep(0.001)
 
     def __enter__(self):
         if self.path:
@@ -169,7 +178,8 @@ class ClockSampler:
         if not self.samples:
             return None
         s = sorted(self.samples)
-        return dict(median_mhz=s[len(s) // 2], min_mhz=s[0], max_mhz=s[-1], samples=len(s), source=self.path)
+        return dict(median_mhz=s[len(s) // 2], min_mhz=s[0], max_mhz=s[-1], samples=len(s), source=self.path,
+                    nominal_mhz=2400.0)
 
 
 # ---- the step ---------------------------------------------------------------------------------

@@ -195,7 +195,8 @@ int ntp_attn_proj_shard_fwd(ntp_handle_t* h, const ntp_attn_shape_t* shape, cons
  *   dC = dZ Wo^T [M x w_o] bf16,  dWo = C^T dZ [w_o x H] fp32.
  * Column-parallel half (skipped when dQKV is NULL):
  *   dXpart = dQKV Wqkv [M x H] bf16 (partial sum),  dWqkv = dQKV^T X [w_qkv x H] fp32.
- * The dW of a KV head replicated on several ranks is each rank's partial sum.
+ * The dW of a KV head replicated on several ranks is each rank's partial sum
+ * (over its own query heads); ntp_replica_sum completes it.
  * accumulate != 0 adds into dWqkv / dWo. */
 int ntp_attn_proj_shard_bwd(ntp_handle_t* h, const ntp_attn_shape_t* shape, const void* dZ, int64_t lddz,
                             const void* dQKV, int64_t lddqkv, const void* X, int64_t ldx,
@@ -238,6 +239,21 @@ typedef struct ntp_segment {
 int ntp_reshard_segments(const ntp_tensor_spec_t* spec, int32_t src_tp, int32_t dst_tp,
                          ntp_segment_t* out, int64_t max_segments, int64_t* count);
 
+/* Sum of replicated units (grouped KV heads; Sec. 3.1 keeps a head's W_Q, W_K, W_V, W_O together, so a KV
+ * head sits on every rank whose query heads read it).  ntp_attn_proj_shard_bwd leaves, on each of those ranks,
+ * only the share of the head's gradient that the rank's own query heads contribute; the gradient itself is the
+ * sum over the holders.  This call adds the holders' [unit]-blocks of every unit of an NTP_KIND_QKV_GQA tensor
+ * that more than one rank of the TP = tp layout holds, in ascending rank order (fp32, fixed order:
+ * deterministic), and writes the sum back into every holder's block, in place.  It is the one-GPU form of the
+ * all-reduce among the holders, and it must run before ntp_reshard_grad, which copies a replicated unit from
+ * one holder only.  NTP_KIND_PLAIN tensors have no replicated units: the call does nothing.
+ *   shards / ld   HOST arrays of tp DEVICE pointers (fp32, 4-byte aligned; 16-byte aligned blocks with
+ *                 ld % 4 == 0 go fastest) and leading dimensions, as for ntp_reshard_grad; a NULL shard is
+ *                 "not on this GPU" and takes no part; shards must not overlap (INVALID_ARG)
+ * Errors: elem_size != 4 -> INVALID_ARG; more than 96 holders of one unit -> UNSUPPORTED. */
+int ntp_replica_sum(ntp_handle_t* h, const ntp_tensor_spec_t* spec, int32_t tp, void* const* shards,
+                    const int64_t* ld, void* stream);
+
 /* Enqueue the copy.  src_shards[src_tp] / dst_shards[dst_tp] are HOST arrays of
  * DEVICE pointers, one per rank, each a row-major matrix shaped like that
  * rank's shard with leading dimension src_ld[r] / dst_ld[s] (host arrays,
@@ -245,6 +261,8 @@ int ntp_reshard_segments(const ntp_tensor_spec_t* spec, int32_t src_tp, int32_t 
  * that touches it is skipped, which is how one GPU's share of the exchange is
  * expressed; shards of width 0 may be NULL.  src_tp and dst_tp may be in
  * either order.  Source and destination must not overlap (checked: INVALID_ARG).
+ * A unit that several source ranks hold is read from the lowest of them: the
+ * copies must agree (weights do; gradients after ntp_replica_sum).
  * Only 2-byte alignment (elem_size 2) or 4-byte alignment (elem_size 4) of
  * pointers is required; 16-byte aligned rows copy fastest. */
 int ntp_reshard_grad(ntp_handle_t* h, const ntp_tensor_spec_t* spec, int32_t src_tp, int32_t dst_tp,
@@ -307,7 +325,10 @@ int ntp_attn_core_shard_bwd(ntp_handle_t* h, const ntp_attn_core_shape_t* shape,
  *   destination shards (HOST array of dst_tp DEVICE pointers and leading
  *   dimensions, as for ntp_reshard_grad; sub-shards whose destination shard
  *   is NULL, "not on this GPU", are left out).  Writes at most max_segments
- *   entries and the full count.
+ *   entries and the full count.  NTP_KIND_QKV_GQA specs in which a KV head of
+ *   src_rank is also held by another source rank return UNSUPPORTED: there each
+ *   holder's GEMM yields a partial sum, which ntp_replica_sum has to complete
+ *   before a reshard (use the unfused calls).
  * ntp_mlp_shard_bwd_resharded / ntp_attn_proj_shard_bwd_resharded: as
  *   ntp_mlp_shard_bwd / ntp_attn_proj_shard_bwd, with the gradient outputs
  *   given as HOST arrays of segments (at most 16 per gradient: UNSUPPORTED

@@ -49,7 +49,7 @@ EXPORTS = (
     "ntp_reshard_plan_table", "ntp_reshard_plan_prepare", "ntp_reshard_plan_run", "ntp_reshard_plan_destroy", "ntp_reshard_row_segments",
     "ntp_mlp_shard_bwd_resharded", "ntp_attn_proj_shard_bwd_resharded", "ntp_attn_core_shard_fwd", "ntp_attn_core_shard_bwd",
     "ntp_set_workspace", "ntp_gemm_choice", "ntp_attn_core_choice", "ntp_create", "ntp_destroy", "ntp_device_info",
-    "ntp_set_option", "ntp_workspace_bytes", "ntp_attn_proj_shard_fwd_static",
+    "ntp_set_option", "ntp_workspace_bytes", "ntp_attn_proj_shard_fwd_static", "ntp_replica_sum",
 )
 
 
@@ -137,6 +137,7 @@ def lib() -> C.CDLL:
         L.ntp_attn_proj_shard_fwd_static.argtypes = L.ntp_attn_proj_shard_fwd.argtypes
         L.ntp_reshard_segments.argtypes = [C.POINTER(TensorSpec), C.c_int32, C.c_int32, C.POINTER(Segment), i64,
                                            C.POINTER(i64)]
+        L.ntp_replica_sum.argtypes = [vp, C.POINTER(TensorSpec), C.c_int32, C.POINTER(vp), C.POINTER(i64), vp]
         L.ntp_reshard_grad.argtypes = [vp, C.POINTER(TensorSpec), C.c_int32, C.c_int32, C.POINTER(vp), C.POINTER(i64),
                                        C.POINTER(vp), C.POINTER(i64), vp]
         i32p = C.POINTER(C.c_int32)
@@ -477,6 +478,20 @@ def ntp_reshard_grad(spec: TensorSpec, src_tp: int, dst_tp: int, src_shards, dst
     """src_shards / dst_shards: lists of 2-D device tensors (or None for "not on this GPU")."""
     sp, sl, dp, dl = _shard_arrays(spec, src_tp, dst_tp, src_shards, dst_shards)
     _check(lib().ntp_reshard_grad(_h(handle), C.byref(spec), src_tp, dst_tp, sp, sl, dp, dl, _stream()), "ntp_reshard_grad")
+
+
+def ntp_replica_sum(spec: TensorSpec, tp: int, shards, handle=None) -> None:
+    """shards: list of 2-D fp32 device tensors of the TP = tp layout (or None for "not on this GPU"), updated in place."""
+    vp, i64 = C.c_void_p, C.c_int64
+    if len(shards) != tp:
+        raise ValueError("one entry per rank expected")
+    sp, sl = (vp * tp)(), (i64 * tp)()
+    for i, t in enumerate(shards):
+        if t is None or t.numel() == 0:
+            sp[i], sl[i] = None, 0
+        else:
+            sp[i], sl[i] = _mat(t)
+    _check(lib().ntp_replica_sum(_h(handle), C.byref(spec), tp, sp, sl, _stream()), "ntp_replica_sum")
 
 
 class ReshardPlan:

@@ -223,6 +223,17 @@ extern "C" int ntp_reshard_row_segments(const ntp_tensor_spec_t* spec, int32_t s
   const int st = ntp::build_segments(spec, src_tp, dst_tp, &segs);
   if (st != NTP_OK) return st;
   if (src_rank < 0 || src_rank >= src_tp || spec->partition_dim != 0 || spec->elem_size != 4) return NTP_ERR_INVALID_ARG;
+  if (spec->kind == NTP_KIND_QKV_GQA) {
+    // A KV head that several source ranks hold: each holder's gradient GEMM yields only its own query heads'
+    // share, so storing one holder's rows would drop the others'.  That layout needs the separate pass
+    // (ntp_replica_sum, then ntp_reshard_grad).
+    ntp_attn_plan_t mine, other;
+    if (ntp_attn_shard_plan(spec->n_q, spec->n_kv, 1, src_tp, src_rank, &mine) != NTP_OK) return NTP_ERR_INVALID_ARG;
+    for (int32_t r = 0; r < src_tp && mine.kv_cnt > 0; ++r) {
+      if (r == src_rank || ntp_attn_shard_plan(spec->n_q, spec->n_kv, 1, src_tp, r, &other) != NTP_OK || other.kv_cnt == 0) continue;
+      if (other.kv_off < mine.kv_off + mine.kv_cnt && mine.kv_off < other.kv_off + other.kv_cnt) return NTP_ERR_UNSUPPORTED;
+    }
+  }
   int64_t n = 0;
   for (const ntp_segment_t& g : segs) {
     if (g.src_rank != src_rank || g.units == 0) continue;

@@ -14,6 +14,7 @@
 
 #include <algorithm>
 #include <cstdlib>
+#include <utility>
 #include <vector>
 
 #include "ntp_internal.h"
@@ -560,6 +561,110 @@ extern "C" int ntp_calibration_copy(ntp_handle_t* h, void* dst, const void* src,
   const bool ok = hipGetLastError() == hipSuccess;
   ntp::timing_end(h, stream);
   return ok ? NTP_OK : NTP_ERR_LAUNCH;
+}
+
+// ---- sum of replicated units over their holders --------------------------------------------------
+namespace {
+
+constexpr int kMaxHolders = 96;  // ranks that may hold one unit (kernel argument space)
+
+// One replicated unit: a [rows x cols] fp32 block in each of n holders' shards.
+struct ReplicaGroup {
+  float* ptr[kMaxHolders];
+  int64_t ld[kMaxHolders];
+  int32_t n, rows, cols, vec4;  // vec4: every pointer is 16-byte aligned, cols % 4 == 0, every ld % 4 == 0
+};
+
+// Every element: the holders' values added in ascending rank order (a fixed order, so the result is
+// deterministic), then written back to all of them.  One thread owns an element (or four) in every holder, so
+// the update in place is safe.
+__global__ __launch_bounds__(256) void replica_sum_kernel(const ReplicaGroup g) {
+  const int64_t per_row = g.vec4 ? g.cols / 4 : g.cols;
+  const int64_t total = int64_t(g.rows) * per_row, stride = int64_t(gridDim.x) * blockDim.x;
+  for (int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; i < total; i += stride) {
+    const int64_t r = i / per_row, c = i - r * per_row;
+    if (g.vec4) {
+      typedef float f4 __attribute__((ext_vector_type(4)));
+      f4 sum = *reinterpret_cast<const f4*>(g.ptr[0] + r * g.ld[0] + c * 4);
+      for (int k = 1; k < g.n; ++k) sum = sum + *reinterpret_cast<const f4*>(g.ptr[k] + r * g.ld[k] + c * 4);
+      for (int k = 0; k < g.n; ++k) *reinterpret_cast<f4*>(g.ptr[k] + r * g.ld[k] + c * 4) = sum;
+    } else {
+      float sum = g.ptr[0][r * g.ld[0] + c];
+      for (int k = 1; k < g.n; ++k) sum += g.ptr[k][r * g.ld[k] + c];
+      for (int k = 0; k < g.n; ++k) g.ptr[k][r * g.ld[k] + c] = sum;
+    }
+  }
+}
+
+}  // namespace
+
+extern "C" int ntp_replica_sum(ntp_handle_t* h, const ntp_tensor_spec_t* spec, int32_t tp, void* const* shards,
+                               const int64_t* ld, void* stream) {
+  if (!h || !shards || !ld) return NTP_ERR_INVALID_ARG;
+  int64_t n_units = 0;
+  int st = ntp::check_spec(spec, tp, tp, &n_units);
+  if (st != NTP_OK) return st;
+  if (spec->elem_size != 4) return NTP_ERR_INVALID_ARG;  // the sum is fp32 arithmetic
+  if (spec->kind == NTP_KIND_PLAIN) return NTP_OK;       // every unit has one holder
+  // shape and alignment of the shards, and: no two shards may overlap
+  std::vector<int64_t> units(tp), none;
+  for (int32_t r = 0; r < tp; ++r)
+    if ((st = ntp::shard_units(spec, n_units, tp, r, &units[r])) != NTP_OK) return st;
+  std::vector<void*> no_dst;
+  {
+    std::vector<Extent> ext(tp, Extent{0, 0});
+    const bool by_rows = spec->partition_dim == 0;
+    for (int32_t r = 0; r < tp; ++r) {
+      if (!shards[r] || units[r] == 0) continue;
+      const int64_t srows = by_rows ? units[r] * spec->unit : spec->rows, scols = by_rows ? spec->cols : units[r] * spec->unit;
+      if (srows == 0 || scols == 0) continue;
+      if (ld[r] < scols) return NTP_ERR_INVALID_ARG;
+      const uintptr_t p = reinterpret_cast<uintptr_t>(shards[r]);
+      if (p % 4) return NTP_ERR_ALIGNMENT;
+      ext[r] = Extent{p, p + uintptr_t(((srows - 1) * ld[r] + scols) * 4)};
+    }
+    for (int32_t a = 0; a < tp; ++a)
+      for (int32_t b = a + 1; b < tp; ++b)
+        if (ext[a].hi > ext[a].lo && ext[b].hi > ext[b].lo && ext[a].lo < ext[b].hi && ext[b].lo < ext[a].hi) return NTP_ERR_INVALID_ARG;
+  }
+  if (h->device < 0) return NTP_ERR_NO_DEVICE;
+  // holders of every logical unit, ascending rank order
+  std::vector<std::vector<std::pair<int32_t, int64_t>>> holders(static_cast<size_t>(n_units));
+  std::vector<ntp::Run> runs;
+  for (int32_t r = 0; r < tp; ++r) {
+    if ((st = ntp::rank_runs(spec, n_units, tp, r, &runs)) != NTP_OK) return st;
+    for (const ntp::Run& run : runs)
+      for (int64_t i = 0; i < run.count; ++i) holders[size_t(run.first + i)].push_back({r, run.local + i});
+  }
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  const bool by_rows = spec->partition_dim == 0;
+  for (int64_t u = 0; u < n_units; ++u) {
+    const auto& hd = holders[size_t(u)];
+    if (hd.size() < 2) continue;
+    if (hd.size() > size_t(kMaxHolders)) return NTP_ERR_UNSUPPORTED;
+    ReplicaGroup g{};
+    g.rows = int32_t(by_rows ? spec->unit : spec->rows);
+    g.cols = int32_t(by_rows ? spec->cols : spec->unit);
+    if ((by_rows ? spec->cols : spec->rows) > 0x7fffffffll) return NTP_ERR_UNSUPPORTED;
+    g.vec4 = g.cols % 4 == 0;
+    for (const auto& [r, local] : hd) {
+      if (!shards[r]) continue;  // a holder that is not on this GPU takes no part
+      float* base = static_cast<float*>(shards[r]);
+      g.ptr[g.n] = by_rows ? base + local * spec->unit * ld[r] : base + local * spec->unit;
+      g.ld[g.n] = ld[r];
+      if ((reinterpret_cast<uintptr_t>(g.ptr[g.n]) & 15) || ld[r] % 4) g.vec4 = 0;
+      ++g.n;
+    }
+    if (g.n < 2 || g.rows == 0 || g.cols == 0) continue;
+    const int64_t work = int64_t(g.rows) * (g.vec4 ? g.cols / 4 : g.cols);
+    const uint32_t blocks = uint32_t(std::max<int64_t>(1, std::min<int64_t>((work + 255) / 256, int64_t(h->compute_units) * 16)));
+    if (ntp::timing_on(h)) ntp::timing_begin(h, stream, "replica_sum", 0.0, 2.0 * 4.0 * double(g.n) * double(g.rows) * double(g.cols));
+    hipLaunchKernelGGL(replica_sum_kernel, dim3(blocks), dim3(256), 0, hs, g);
+    const bool ok = hipGetLastError() == hipSuccess;
+    ntp::timing_end(h, stream);
+    if (!ok) return NTP_ERR_LAUNCH;
+  }
+  return NTP_OK;
 }
 
 extern "C" int ntp_reshard_grad(ntp_handle_t* h, const ntp_tensor_spec_t* spec, int32_t src_tp, int32_t dst_tp,

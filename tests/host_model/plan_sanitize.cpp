@@ -78,7 +78,9 @@ int main() {
         for (int32_t r = 0; r < a; ++r) {
           std::vector<ntp_row_segment_t> rows(4);
           int64_t cnt = -1;
-          CHECK(ntp_reshard_row_segments(&spec, a, r, b, dst.data(), ld.data(), rows.data(), 4, &cnt) == NTP_OK && cnt >= 0);
+          const int rs = ntp_reshard_row_segments(&spec, a, r, b, dst.data(), ld.data(), rows.data(), 4, &cnt);
+          if (rs == NTP_ERR_UNSUPPORTED && c.kind == NTP_KIND_QKV_GQA) continue;  // a KV head of this rank has other holders
+          CHECK(rs == NTP_OK && cnt >= 0);
           for (int64_t i = 0; i < std::min<int64_t>(cnt, 4); ++i)
             CHECK(rows[size_t(i)].row_begin >= 0 && rows[size_t(i)].row_begin + rows[size_t(i)].rows <= su[r] * c.unit);
         }

@@ -122,7 +122,21 @@ def test_mlp_bwd_resharded_with_split_k(opts, splits, accumulate):
         N.ntp_set_workspace(None)
 
 
-@pytest.mark.parametrize("a,b,rank", [(5, 7, 0), (5, 7, 2), (7, 5, 6), (4, 4, 1), (3, 16, 1)])
+def test_attn_bwd_resharded_refuses_replicated_kv_heads():
+    """16 query heads, 4 KV heads over 5 ranks: rank 2 holds heads 7-9, i.e. KV heads 1 and 2, which ranks 1 and 3
+    hold too.  Its dW rows of those heads are partial sums; the fused store would drop the other holders' shares."""
+    import paper_2504_06095_amd as N
+    K = N.binding
+    spec_q = N.tensor_spec((16 + 8) * 32, 512, 0, 32, 4, K.NTP_KIND_QKV_GQA, 16, 4)
+    dst = [(0x10000000 + 0x1000000 * r, 512) for r in range(7)]
+    with pytest.raises(N.NtpError) as e:
+        N.ntp_reshard_row_segments(spec_q, 5, 2, 7, dst)
+    assert e.value.status == K.NTP_ERR_UNSUPPORTED
+    assert len(N.ntp_reshard_row_segments(spec_q, 5, 0, 7, dst)) > 0  # rank 0 holds KV head 0 alone
+
+
+# (source ranks whose KV heads no other source rank holds)
+@pytest.mark.parametrize("a,b,rank", [(5, 7, 0), (4, 7, 2), (4, 4, 1), (2, 7, 1), (1, 5, 0)])
 def test_attn_bwd_resharded_matches_unfused(a, b, rank):
     import torch
     import paper_2504_06095_amd as N

@@ -4,7 +4,7 @@ import pytest
 
 import paper_2504_06095_amd as N
 from oracle import ntp_oracle as O
-from paper_2504_06095_amd.binding import NTP_KIND_PLAIN, NTP_KIND_QKV_GQA, NtpError
+from paper_2504_06095_amd.binding import NTP_ERR_UNSUPPORTED, NTP_KIND_PLAIN, NTP_KIND_QKV_GQA, NtpError
 
 BASE, STEP = 1 << 40, 1 << 32  # fake, well separated device addresses of the destination shards
 
@@ -16,6 +16,15 @@ def _check(rows, cols, unit, kind, a, b, n_q=0, n_kv=0, absent=()):
     ld = cols + 4
     dst = [None if d in absent else (BASE + d * STEP, ld) for d in range(b)]
     for r in range(a):
+        if okind == O.QKV_GQA:
+            # a KV head that another source rank holds too: this rank's rows are a partial sum, the fused path refuses
+            mine = {u for u in O.unit_list(okind, n_units, a, r, n_q, n_kv) if u >= n_q}
+            shared = any(mine & set(O.unit_list(okind, n_units, a, o, n_q, n_kv)) for o in range(a) if o != r)
+            if shared:
+                with pytest.raises(NtpError) as e:
+                    N.ntp_reshard_row_segments(spec, a, r, b, dst)
+                assert e.value.status == NTP_ERR_UNSUPPORTED
+                continue
         segs = N.ntp_reshard_row_segments(spec, a, r, b, dst)
         got = {}
         for s in segs:
@@ -43,10 +52,11 @@ def test_row_segments_plain(a, b):
     _check(96, 8, 4, NTP_KIND_PLAIN, a, b)
 
 
-@pytest.mark.parametrize("a,b", [(5, 7), (7, 5), (16, 3), (3, 16), (4, 4)])
+@pytest.mark.parametrize("a,b", [(5, 7), (7, 5), (16, 3), (3, 16), (4, 4), (2, 7), (4, 16), (1, 3)])
 def test_row_segments_gqa(a, b):
     n_q, n_kv, d = 16, 4, 8
     _check((n_q + 2 * n_kv) * d, 24, d, NTP_KIND_QKV_GQA, a, b, n_q, n_kv)
+    _check(3 * 12 * d, 24, d, NTP_KIND_QKV_GQA, a, b, 12, 12)  # one KV head per query head: nothing is replicated
 
 
 def test_row_segments_absent_destinations_and_errors():
