@@ -67,6 +67,24 @@ def test_attn_config_full_size(launch_config, tp, rank, w_qkv, w_o):
     _check(case.run_gpu(), case.oracle(), ["QKV", "Z", "dC", "dX", "dWqkv", "dWo"])
 
 
+@pytest.mark.parametrize("hidden,rank", [(6144, 0), (6144, 6), (12288, 0), (12288, 6)])
+def test_imbalance_sweep_shapes(launch_config, hidden, rank):
+    """The second workload's shapes (Sec. 5.1 "Prototype evaluation": hidden 6144 / 12288, FFN 4 x hidden, head
+    dimension 128, 4096 tokens), a TP-8 replica degraded to TP 7: the widest rank (0: 3511 / 7022 FFN columns, 7 / 14
+    heads) and the narrowest (6: 3510 / 7021 columns, 6 / 13 heads), MLP shard and attention projections, every
+    output against the oracle."""
+    heads = hidden // 128
+    _say(f"imbalance sweep shape hidden={hidden} rank={rank} of TP 7, {launch_config}")
+    mlp = MlpCase(4096, hidden, 4 * hidden, 7, rank, tag=f"imb{hidden}")
+    assert mlp.n_r == {(6144, 0): 3511, (6144, 6): 3510, (12288, 0): 7022, (12288, 6): 7021}[(hidden, rank)]
+    got, _ = mlp.run_gpu()
+    _check(got, mlp.oracle(), MLP_NAMES)
+    del got
+    att = AttnCase(4096, hidden, heads, heads, 128, 7, rank, tag=f"imb{hidden}")
+    assert att.plan["q_cnt"] == {(6144, 0): 7, (6144, 6): 6, (12288, 0): 14, (12288, 6): 13}[(hidden, rank)]
+    _check(att.run_gpu(), att.oracle(), ["QKV", "Z", "dC", "dX", "dWqkv", "dWo"])
+
+
 def test_config1_reshard_after_backward():
     """Config 1 end to end: the dA_t / dB that the GPU backward produced for EVERY rank of TP 7 are
     repacked into the TP 8 layout; the result must equal the unsharded gradient cut at TP 8."""
