@@ -39,7 +39,7 @@ WARM, TIMED = 5, 20             # per-call timing: warm-up and timed iterations
 # workload of the step: GPT-3-175B-shape layer, full TP 8, degraded to TP 7, this GPU = rank 0
 M, H, FFN, HEADS, HEAD_DIM, T_FULL, T_RED, RANK = 2048, 12288, 49152, 96, 128, 8, 7, 0
 
-ALL_SECTIONS = ("step", "fused", "configs", "imbalance", "reshard", "mapped", "attn", "cpu")
+ALL_SECTIONS = ("step", "fused", "configs", "imbalance", "reshard", "mapped", "attn", "ceiling", "cpu")
 
 
 # ---- seeded inputs ------------------------------------------------------------------------
@@ -602,6 +602,24 @@ def attn_core_bench(torch, N):
     return out
 
 
+def ceiling_probes(torch, N):
+    """What the device sustains on the matrix pipe and on LDS reads, alone and in the GEMM kernels' own mix, with
+    no global memory traffic (ntp_probe_rates): the bound that the power-limited clock and the LDS put on any
+    schedule of the GEMM inner loop."""
+    K = N.binding
+    scratch = torch.empty(1 << 20, dtype=torch.float32, device="cuda")
+    names = (("mfma_only", K.NTP_PROBE_MFMA), ("lds_read_b128", K.NTP_PROBE_LDS_B128), ("lds_read_tr_b64", K.NTP_PROBE_LDS_TR_B64),
+             ("mfma_plus_lds_b128", K.NTP_PROBE_MFMA_LDS_B128), ("mfma_plus_lds_tr_b64", K.NTP_PROBE_MFMA_LDS_TR_B64))
+    out = {}
+    for name, which in names:
+        N.ntp_probe_rates(which, scratch)  # settle the clock on this loop
+        r = N.ntp_probe_rates(which, scratch)
+        out[name] = dict(TFLOPs=r["tflops"] or None, frac_of_bf16_peak=(r["tflops"] / BF16_MFMA_PEAK_TFLOPS) or None,
+                         lds_read_GBps_per_cu=r["lds_gbps_per_cu"] or None, mfma_per_turn=r["mfma_per_turn"],
+                         lds_reads_per_turn=r["reads_per_turn"], ms=r["ms"])
+    return out
+
+
 def workspace_wish(N):
     """As much workspace as any shard call that this benchmark times can use (ntp_workspace_bytes)."""
     from paper_2504_06095_amd import inputs as I
@@ -631,6 +649,8 @@ def main():
                          "shapes) and print its own JSON line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB dense copy (calibration_copy_kernel): the yardstick for profiler byte counters")
+    ap.add_argument("--gemm-schedule", type=int, default=None,
+                    help="NTP_OPT_GEMM_SCHEDULE override for A/B runs (1: the ring kernel's default schedule everywhere, 2: ping-pong)")
     ap.add_argument("--no-workspace", action="store_true",
                     help="give the handle no split-K workspace (skinny shard GEMMs then run unsplit)")
     args = ap.parse_args()
@@ -649,6 +669,8 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+    if args.gemm_schedule is not None:
+        N.ntp_set_option(N.binding.NTP_OPT_GEMM_SCHEDULE, args.gemm_schedule)
     ws_bytes = 0
     if not args.no_workspace:
         ws_bytes = workspace_wish(N)
@@ -762,6 +784,8 @@ def main():
             achieved=worst, peak=BF16_MFMA_PEAK_TFLOPS, unit="TFLOP/s", frac=worst / BF16_MFMA_PEAK_TFLOPS, traffic=None,
             cases=ac)
         torch.cuda.empty_cache()
+    if "ceiling" in sections:
+        out["device_ceiling"] = ceiling_probes(torch, N)
     if "reshard" in sections:
         st, kern = reshard_stress(torch, N)
         worst = min(st.values(), key=lambda v: v["GBps"])

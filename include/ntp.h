@@ -101,7 +101,9 @@ int ntp_device_info(const ntp_handle_t* h, int32_t* device, int32_t* compute_uni
 #define NTP_OPT_RESHARD_TABLE_BLOCK 6 /* bytes per block of the run-table kernel                                    */
 #define NTP_OPT_RESHARD_NO_FLAT 7    /* 1: column-partitioned tensors never take the flat-destination kernel       */
 #define NTP_OPT_RESHARD_NO_TABLE 8   /* 1: plans never take the run-table kernel                                   */
-#define NTP_OPT_COUNT_ 9
+#define NTP_OPT_GEMM_SCHEDULE 9      /* schedule of the ring kernel's K loop: 1 the default one everywhere, 2 the
+                                        ping-pong one wherever it exists (8-wavefront tiles, persistent form)        */
+#define NTP_OPT_COUNT_ 10
 int ntp_set_option(ntp_handle_t* h, int32_t option, int64_t value);
 
 /* ---------------------------------------------------------------------------
@@ -501,9 +503,11 @@ int ntp_set_workspace(ntp_handle_t* h, void* workspace, int64_t bytes);
  *   ring            1: the LDS-ring kernel; 0: the small generic kernel
  *   k_splits        > 1: split-K with that many chunks, followed by the reduce kernel
  *   persistent      1: one workgroup per compute unit walks over the tiles
+ *   pingpong        1: the K loop runs the ping-pong schedule (the two wavefronts of a SIMD alternate between
+ *                   matrix instructions and LDS reads / DMA issue), 0: the default schedule
  * Errors: NTP_ERR_INVALID_ARG. */
 typedef struct ntp_gemm_choice {
-  int32_t tile_m, tile_n, wavefronts, ring, k_splits, persistent;
+  int32_t tile_m, tile_n, wavefronts, ring, k_splits, persistent, pingpong;
 } ntp_gemm_choice_t;
 int ntp_gemm_choice(const ntp_handle_t* h, int32_t layout, int64_t M, int64_t N, int64_t K, ntp_gemm_choice_t* out);
 
@@ -523,6 +527,28 @@ int ntp_attn_core_choice(const ntp_handle_t* h, const ntp_attn_core_shape_t* sha
  * calibration_copy_kernel.  Its known traffic (bytes read, bytes written) is what
  * the profiler's HBM byte counters are scaled by when a kernel's traffic is reported. */
 int ntp_calibration_copy(ntp_handle_t* h, void* dst, const void* src, int64_t bytes, void* stream);
+
+/* Measurement aid (blocking; creates HIP events; launches on the default stream): what this device sustains,
+ * at its power limit, on the two resources the GEMM kernels' inner loop uses, with no global memory traffic:
+ * one workgroup of 8 wavefronts per compute unit runs a loop of
+ *   NTP_PROBE_MFMA              64 bf16 16x16x32 matrix instructions per turn on pseudo-random operands
+ *   NTP_PROBE_LDS_B128          24 conflict-free 128-bit LDS reads per turn
+ *   NTP_PROBE_LDS_TR_B64        44 transposing 64-bit LDS reads per turn
+ *   NTP_PROBE_MFMA_LDS_B128     64 matrix instructions + 24 128-bit reads (the mix of a K tile of the
+ *                               K-contiguous GEMM kernels, per wavefront)
+ *   NTP_PROBE_MFMA_LDS_TR_B64   56 matrix instructions + 44 transposing reads (weight-gradient kernels)
+ * scratch: DEVICE, at least compute_units * 2048 bytes, overwritten.  out (HOST): average milliseconds per
+ * launch, matrix TFLOP/s of the whole device, LDS read GB/s per compute unit. */
+#define NTP_PROBE_MFMA 0
+#define NTP_PROBE_LDS_B128 1
+#define NTP_PROBE_LDS_TR_B64 2
+#define NTP_PROBE_MFMA_LDS_B128 3
+#define NTP_PROBE_MFMA_LDS_TR_B64 4
+typedef struct ntp_probe_result {
+  double ms, tflops, lds_gbps_per_cu;
+  int32_t mfma_per_turn, reads_per_turn;
+} ntp_probe_result_t;
+int ntp_probe_rates(ntp_handle_t* h, int32_t which, void* scratch, int64_t scratch_bytes, ntp_probe_result_t* out);
 
 /* ---------------------------------------------------------------------------
  * For callers that cannot allocate device memory (code under HIP graph capture,

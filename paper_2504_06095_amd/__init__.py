@@ -11,5 +11,5 @@ from .binding import (  # noqa: F401
     ntp_attn_proj_shard_bwd_resharded, ntp_comp_sync_plan, ntp_gemm_choice, ntp_reshard_plan_create, ntp_attn_proj_shard_bwd, ntp_attn_proj_shard_fwd, ntp_attn_shard_plan, ntp_calibration_copy,
     ntp_kernel_timing_enable, ntp_kernel_timing_read, ntp_mlp_shard_bwd,
     ntp_mlp_shard_fwd, ntp_reshard_grad, ntp_reshard_segments, ntp_set_workspace, ntp_shard_plan, ntp_version, tensor_spec,
-    Handle, default_handle, ntp_create, ntp_destroy, ntp_device_info, ntp_set_option, ntp_workspace_bytes, ntp_attn_proj_shard_fwd_static, ntp_replica_sum,
+    Handle, default_handle, ntp_create, ntp_destroy, ntp_device_info, ntp_set_option, ntp_workspace_bytes, ntp_attn_proj_shard_fwd_static, ntp_replica_sum, ntp_probe_rates,
 )

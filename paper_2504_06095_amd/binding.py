@@ -30,6 +30,12 @@ NTP_OPT_RESHARD_FLAT_BLOCK = 5
 NTP_OPT_RESHARD_TABLE_BLOCK = 6
 NTP_OPT_RESHARD_NO_FLAT = 7
 NTP_OPT_RESHARD_NO_TABLE = 8
+NTP_OPT_GEMM_SCHEDULE = 9
+NTP_PROBE_MFMA = 0
+NTP_PROBE_LDS_B128 = 1
+NTP_PROBE_LDS_TR_B64 = 2
+NTP_PROBE_MFMA_LDS_B128 = 3
+NTP_PROBE_MFMA_LDS_TR_B64 = 4
 NTP_CALL_MLP_SHARD = 0
 NTP_CALL_ATTN_PROJ_SHARD = 1
 NTP_CALL_ATTN_CORE_SHARD = 2
@@ -49,12 +55,12 @@ EXPORTS = (
     "ntp_reshard_plan_table", "ntp_reshard_plan_prepare", "ntp_reshard_plan_run", "ntp_reshard_plan_destroy", "ntp_reshard_row_segments",
     "ntp_mlp_shard_bwd_resharded", "ntp_attn_proj_shard_bwd_resharded", "ntp_attn_core_shard_fwd", "ntp_attn_core_shard_bwd",
     "ntp_set_workspace", "ntp_gemm_choice", "ntp_attn_core_choice", "ntp_create", "ntp_destroy", "ntp_device_info",
-    "ntp_set_option", "ntp_workspace_bytes", "ntp_attn_proj_shard_fwd_static", "ntp_replica_sum",
+    "ntp_set_option", "ntp_workspace_bytes", "ntp_attn_proj_shard_fwd_static", "ntp_replica_sum", "ntp_probe_rates",
 )
 
 
 class GemmChoice(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("tile_m", "tile_n", "wavefronts", "ring", "k_splits", "persistent")]
+    _fields_ = [(n, C.c_int32) for n in ("tile_m", "tile_n", "wavefronts", "ring", "k_splits", "persistent", "pingpong")]
 
 
 class AttnCoreChoice(C.Structure):
@@ -104,6 +110,11 @@ class UnitSource(C.Structure):
     _fields_ = [("src_rank", C.c_int32), ("src_unit", C.c_int32)]
 
 
+class ProbeResult(C.Structure):
+    _fields_ = [("ms", C.c_double), ("tflops", C.c_double), ("lds_gbps_per_cu", C.c_double), ("mfma_per_turn", C.c_int32),
+                ("reads_per_turn", C.c_int32)]
+
+
 class KernelTime(C.Structure):
     _fields_ = [("name", C.c_char * 48), ("flops", C.c_double), ("bytes", C.c_double), ("ms", C.c_float),
                 ("pad_", C.c_int32)]
@@ -118,6 +129,9 @@ def lib() -> C.CDLL:
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2504_06095_amd.build`")
+        # PyTorch first: the library and PyTorch must share one HIP runtime in the process, and the one that is
+        # loaded first is the one both use (PyTorch ships its own copy)
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         L.ntp_version.restype = C.c_int
         L.ntp_status_string.restype = C.c_char_p
@@ -137,6 +151,7 @@ def lib() -> C.CDLL:
         L.ntp_attn_proj_shard_fwd_static.argtypes = L.ntp_attn_proj_shard_fwd.argtypes
         L.ntp_reshard_segments.argtypes = [C.POINTER(TensorSpec), C.c_int32, C.c_int32, C.POINTER(Segment), i64,
                                            C.POINTER(i64)]
+        L.ntp_probe_rates.argtypes = [vp, C.c_int32, vp, i64, C.POINTER(ProbeResult)]
         L.ntp_replica_sum.argtypes = [vp, C.POINTER(TensorSpec), C.c_int32, C.POINTER(vp), C.POINTER(i64), vp]
         L.ntp_reshard_grad.argtypes = [vp, C.POINTER(TensorSpec), C.c_int32, C.c_int32, C.POINTER(vp), C.POINTER(i64),
                                        C.POINTER(vp), C.POINTER(i64), vp]
@@ -569,6 +584,14 @@ def ntp_kernel_timing_read(max_records: int = 4096, handle=None) -> list[dict]:
     n = C.c_int64()
     _check(lib().ntp_kernel_timing_read(_h(handle), buf, max_records, C.byref(n)), "ntp_kernel_timing_read")
     return [dict(name=r.name.decode(), flops=r.flops, bytes=r.bytes, ms=r.ms) for r in buf[: min(n.value, max_records)]]
+
+
+def ntp_probe_rates(which: int, scratch, handle=None) -> dict:
+    """Sustained matrix / LDS-read rates of the device (blocking measurement aid); scratch: a device tensor."""
+    out = ProbeResult()
+    _check(lib().ntp_probe_rates(_h(handle), which, scratch.data_ptr(), scratch.numel() * scratch.element_size(), C.byref(out)),
+           "ntp_probe_rates")
+    return {n: getattr(out, n) for n, _ in ProbeResult._fields_}
 
 
 def ntp_calibration_copy(dst, src, handle=None) -> None:

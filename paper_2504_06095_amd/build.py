@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libntp.so")
 
 SOURCES = ["ntp_plan.cpp", "ntp_handle.hip", "ntp_layers.cpp", "ntp_timing.cpp", "ntp_gemm.hip", "ntp_gemm_nt.hip", "ntp_gemm_nn.hip",
-           "ntp_gemm_tn.hip", "ntp_reshard.hip", "ntp_attn_core.hip"]
+           "ntp_gemm_tn.hip", "ntp_gemm_pp_nt.hip", "ntp_gemm_pp_nn.hip", "ntp_gemm_pp_tn.hip", "ntp_reshard.hip", "ntp_attn_core.hip", "ntp_probe.hip"]
 
 # -packed-fp32-ops is switched off: the compiler must not form packed fp32 VALU ops.
 HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
@@ -30,7 +30,7 @@ def _run(cmd: list[str]) -> str:
 def build_library(verbose: bool = False, jobs: int | None = None) -> str:
     """Compile every source (in parallel, one hipcc per file) and link the shared library.  Always recompiles."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    jobs = jobs or min(len(SOURCES), int(os.environ.get("MAX_JOBS", "8")))
+    jobs = jobs or min(len(SOURCES), int(os.environ.get("MAX_JOBS", "8")), os.cpu_count() or 8)
     with tempfile.TemporaryDirectory(prefix="ntp_build_") as tmp:
         def compile_one(src: str) -> tuple[str, str]:
             obj = os.path.join(tmp, src + ".o")

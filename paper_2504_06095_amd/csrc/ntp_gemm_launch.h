@@ -7,6 +7,7 @@
 
 #include <type_traits>
 
+#include "ntp_gemm_pp.h"
 #include "ntp_gemm_ring.h"
 #include "ntp_internal.h"
 
@@ -33,13 +34,17 @@ int launch_ring_tn(GemmArgs g, int epilogue, int tile, hipStream_t s);  // A [K 
 // workspace, g.ldc its row length, g.k_chunk / g.split_stride describe the chunks; partial sums only, no
 // epilogue.  g.k_splits == 1 (weight-gradient layout only): the whole GEMM with its fp32 epilogue; the
 // accumulating epilogue exists for the 256 x 256 tile only.
+// The same with the ping-pong schedule of the K loop (tile shapes 0-6, persistent form).
+int launch_pp_nt(GemmArgs g, int epilogue, int tile, hipStream_t s);
+int launch_pp_nn(GemmArgs g, int epilogue, int tile, hipStream_t s);
+int launch_pp_tn(GemmArgs g, int epilogue, int tile, hipStream_t s);
 int launch_ring_split_nt(GemmArgs g, int tile, hipStream_t s);
 int launch_ring_split_nn(GemmArgs g, int tile, hipStream_t s);
 int launch_ring_split_tn(GemmArgs g, int epilogue, int tile, hipStream_t s);
 // tile shapes that have a split-K instantiation
 constexpr bool kSplitTile[] = {true, true, true, true, true, true, true, false, false};
 
-template <bool AKC, bool BKC, int EPI, int BM_, int BN_, int WGM, int WGN>
+template <bool AKC, bool BKC, int EPI, int BM_, int BN_, int WGM, int WGN, bool PP = false>
 int launch_ring_one(GemmArgs g, hipStream_t s) {
   g.tiles_m = (g.M + BM_ - 1) / BM_;
   g.tiles_n = (g.n_store + BN_ - 1) / BN_;
@@ -50,7 +55,8 @@ int launch_ring_one(GemmArgs g, hipStream_t s) {
   const uint32_t resident = uint32_t(g.resident > 8 ? g.resident & ~7 : 8) * (WGM * WGN == 4 ? 2 : 1);
   const uint32_t nblk = uint32_t(g.tiles_m) * uint32_t(g.tiles_n);
   const dim3 grid(nblk < resident ? nblk : resident), block(64 * WGM * WGN);
-  hipLaunchKernelGGL((gemm_ring_kernel<AKC, BKC, EPI, BM_, BN_, WGM, WGN>), grid, block, 0, s, g);
+  if constexpr (PP) hipLaunchKernelGGL((gemm_pp_kernel<AKC, BKC, EPI, BM_, BN_, WGM, WGN>), grid, block, 0, s, g);
+  else hipLaunchKernelGGL((gemm_ring_kernel<AKC, BKC, EPI, BM_, BN_, WGM, WGN>), grid, block, 0, s, g);
   return hipGetLastError() == hipSuccess ? NTP_OK : NTP_ERR_LAUNCH;
 }
 
@@ -77,6 +83,21 @@ int launch_ring_split_tile(const GemmArgs& g, int tile, hipStream_t s) {
     case 4: return launch_ring_split_one<AKC, BKC, 192, 256, 2, 4>(g, s);
     case 5: return launch_ring_split_one<AKC, BKC, 256, 128, 4, 2>(g, s);
     case 6: return launch_ring_split_one<AKC, BKC, 128, 256, 2, 4>(g, s);
+    default: return NTP_ERR_INVALID_ARG;
+  }
+}
+
+// Ping-pong schedule (8-wavefront tile shapes 0-6).
+template <bool AKC, bool BKC, int EPI>
+int launch_pp_tile(const GemmArgs& g, int tile, hipStream_t s) {
+  switch (tile) {
+    case 0: return launch_ring_one<AKC, BKC, EPI, 256, 256, 2, 4, true>(g, s);
+    case 1: return launch_ring_one<AKC, BKC, EPI, 256, 224, 4, 2, true>(g, s);
+    case 2: return launch_ring_one<AKC, BKC, EPI, 224, 256, 2, 4, true>(g, s);
+    case 3: return launch_ring_one<AKC, BKC, EPI, 256, 192, 4, 2, true>(g, s);
+    case 4: return launch_ring_one<AKC, BKC, EPI, 192, 256, 2, 4, true>(g, s);
+    case 5: return launch_ring_one<AKC, BKC, EPI, 256, 128, 4, 2, true>(g, s);
+    case 6: return launch_ring_one<AKC, BKC, EPI, 128, 256, 2, 4, true>(g, s);
     default: return NTP_ERR_INVALID_ARG;
   }
 }
@@ -116,6 +137,15 @@ int launch_ring_tile(const GemmArgs& g, int tile, hipStream_t s) {
   template __global__ void gemm_ring_kernel<AKC, BKC, EPI, 128, 256, 2, 4>(const GemmArgs);        \
   template __global__ void gemm_ring_kernel<AKC, BKC, EPI, 128, 128, 2, 2>(const GemmArgs);        \
   template __global__ void gemm_ring_kernel<AKC, BKC, EPI, 128, 128, 2, 4>(const GemmArgs);
+
+#define NTP_PP_INSTANTIATE(AKC, BKC, EPI)                                                   \
+  template __global__ void gemm_pp_kernel<AKC, BKC, EPI, 256, 256, 2, 4>(const GemmArgs);   \
+  template __global__ void gemm_pp_kernel<AKC, BKC, EPI, 256, 224, 4, 2>(const GemmArgs);   \
+  template __global__ void gemm_pp_kernel<AKC, BKC, EPI, 224, 256, 2, 4>(const GemmArgs);   \
+  template __global__ void gemm_pp_kernel<AKC, BKC, EPI, 256, 192, 4, 2>(const GemmArgs);   \
+  template __global__ void gemm_pp_kernel<AKC, BKC, EPI, 192, 256, 2, 4>(const GemmArgs);   \
+  template __global__ void gemm_pp_kernel<AKC, BKC, EPI, 256, 128, 4, 2>(const GemmArgs);   \
+  template __global__ void gemm_pp_kernel<AKC, BKC, EPI, 128, 256, 2, 4>(const GemmArgs);
 
 #define NTP_RING_INSTANTIATE_SPLIT(AKC, BKC)                                                                   \
   template __global__ void gemm_ring_kernel<AKC, BKC, ntp::EPI_F32, 256, 256, 2, 4, true>(const GemmArgs);     \

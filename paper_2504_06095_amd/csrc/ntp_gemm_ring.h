@@ -41,6 +41,7 @@ typedef __attribute__((address_space(1))) const void global_cvoid;
 
 constexpr int vmcnt_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | 0x0F70; }       // s_waitcnt vmcnt(n) alone
 constexpr int vmcnt_lgkm0_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | 0x0070; }  // s_waitcnt vmcnt(n) lgkmcnt(0)
+constexpr int lgkm0_imm() { return vmcnt_lgkm0_imm(63); }                               // s_waitcnt lgkmcnt(0) alone
 
 // One operand (R rows of the tile, rounded up to a multiple of 64) as seen by the DMA.
 template <bool KC, int R, int NW>

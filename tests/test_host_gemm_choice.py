@@ -72,3 +72,20 @@ def test_choice_rejects_bad_arguments():
     for args in [(3, 8, 8, 8), (-1, 8, 8, 8), (0, 0, 8, 8), (0, 8, 0, 8), (0, 8, 8, -1), (0, 1 << 31, 8, 8)]:
         with pytest.raises(N.NtpError):
             N.ntp_gemm_choice(*args)
+
+
+def test_schedule_choice_and_override():
+    """K-contiguous layouts get the ping-pong schedule on the persistent 8-wavefront tiles; the option forces either."""
+    h = Bd.ntp_create()
+    c = Bd.ntp_gemm_choice(0, 2048, 7022, 12288, handle=h)
+    assert c["persistent"] == 1 and c["pingpong"] == 1
+    assert Bd.ntp_gemm_choice(1, 2048, 12288, 7022, handle=h)["pingpong"] == 0
+    assert Bd.ntp_gemm_choice(2, 7022, 12288, 2048, handle=h)["pingpong"] == 0
+    assert Bd.ntp_gemm_choice(0, 512, 586, 1024, handle=h)["pingpong"] == 0  # the small 128 x 128 tile has one schedule
+    Bd.ntp_set_option(Bd.NTP_OPT_GEMM_SCHEDULE, 1, handle=h)
+    assert Bd.ntp_gemm_choice(0, 2048, 7022, 12288, handle=h)["pingpong"] == 0
+    Bd.ntp_set_option(Bd.NTP_OPT_GEMM_SCHEDULE, 2, handle=h)
+    assert Bd.ntp_gemm_choice(1, 2048, 12288, 7022, handle=h)["pingpong"] == 1
+    assert Bd.ntp_gemm_choice(2, 5376, 12288, 2048, handle=h)["pingpong"] == 0  # 256 x 256 weight-gradient tile: non-persistent
+    assert Bd.lib().ntp_set_option(h.ptr, Bd.NTP_OPT_GEMM_SCHEDULE, 3) == Bd.NTP_ERR_INVALID_ARG
+    Bd.ntp_destroy(h)
