@@ -651,6 +651,10 @@ def main():
                     help="also run a plain 1 GiB dense copy (calibration_copy_kernel): the yardstick for profiler byte counters")
     ap.add_argument("--gemm-schedule", type=int, default=None,
                     help="NTP_OPT_GEMM_SCHEDULE override for A/B runs (1: the ring kernel's default schedule everywhere, 2: ping-pong)")
+    ap.add_argument("--diagnostic-zero-operands", action="store_true",
+                    help="step section only: run the step on all-zero operands instead (same instructions and memory traffic, almost no "
+                         "switching power in the matrix pipe): shows how far the board's power limit holds the GEMM kernels back. "
+                         "The line is marked as a diagnostic, not a result")
     ap.add_argument("--no-workspace", action="store_true",
                     help="give the handle no split-K workspace (skinny shard GEMMs then run unsplit)")
     args = ap.parse_args()
@@ -703,6 +707,10 @@ def main():
         fn = lambda: step(N, s)
         out["config"].update(n_r=s["n_r"], w_qkv=s["wq"], w_o=s["wo"])
     if "step" in sections:
+        if args.diagnostic_zero_operands:
+            for k in ("X", "dZ", "A_t", "B", "Wqkv", "Wo", "C", "dQKV"):
+                s[k].zero_()
+            out["data"] = "all-zero operands (power diagnostic: not a benchmark result)"
         for _ in range(args.warmup):
             fn()
         with ClockSampler() as clk:
