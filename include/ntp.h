@@ -103,7 +103,10 @@ int ntp_device_info(const ntp_handle_t* h, int32_t* device, int32_t* compute_uni
 #define NTP_OPT_RESHARD_NO_TABLE 8   /* 1: plans never take the run-table kernel                                   */
 #define NTP_OPT_GEMM_SCHEDULE 9      /* schedule of the ring kernel's K loop: 1 the default one everywhere, 2 the
                                         ping-pong one wherever it exists (8-wavefront tiles, persistent form)        */
-#define NTP_OPT_COUNT_ 10
+#define NTP_OPT_GEMM_WORKGROUPS 10   /* persistent GEMM launches use at most this many workgroups (rounded down to a
+                                        multiple of 8, at least 8; 0: one per compute unit).  Fewer workgroups make
+                                        each walk over more output tiles: tests and tuning                            */
+#define NTP_OPT_COUNT_ 11
 int ntp_set_option(ntp_handle_t* h, int32_t option, int64_t value);
 
 /* ---------------------------------------------------------------------------
@@ -285,6 +288,8 @@ int ntp_reshard_grad(ntp_handle_t* h, const ntp_tensor_spec_t* spec, int32_t src
  * its sequence (the paper writes the unmasked form; decoder training masks).
  * head_dim 64 or 128 (UNSUPPORTED otherwise).  bf16 in and out (16-byte aligned,
  * leading dimensions multiples of 8), fp32 arithmetic for scores and sums.
+ * One sequence's rows of QKV (and of dC in the backward call) must span less
+ * than 2 GiB: seq_len * leading dimension * 2 < 2^31 (UNSUPPORTED otherwise).
  * LSE (DEVICE, fp32 [q_cnt x M], may be NULL in the forward call): per head and
  * token the natural logarithm of the sum of exp(score) over the visible keys;
  * the backward call reads it. */

@@ -51,14 +51,62 @@ struct CoreArgs {
 // softmax weight that small is worth
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Maximum / sum over the four lanes l % 16 + {0, 16, 32, 48}, left in all four.  The 16-lane rows trade places in
+// registers (v_permlane16_swap: odd rows of the first operand against even rows of the second, then
+// v_permlane32_swap: upper half of the first against lower half of the second), no LDS round trips.
+// (Each result is copied into a scalar variable before its bits are reinterpreted: a bit cast applied to the vector
+// element itself compiled to the first element in both places.)
+struct SwapPair {
+  float a, b;
+};
+__device__ __forceinline__ SwapPair rows_swap16(float v) {
+  const uint32_t x = __builtin_bit_cast(uint32_t, v);
+  const auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+  const uint32_t r0 = r[0], r1 = r[1];
+  return SwapPair{__builtin_bit_cast(float, r0), __builtin_bit_cast(float, r1)};
+}
+__device__ __forceinline__ SwapPair rows_swap32(float v) {
+  const uint32_t x = __builtin_bit_cast(uint32_t, v);
+  const auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+  const uint32_t r0 = r[0], r1 = r[1];
+  return SwapPair{__builtin_bit_cast(float, r0), __builtin_bit_cast(float, r1)};
+}
 __device__ __forceinline__ float xor_max(float v) {
-  v = fmaxf(v, __shfl_xor(v, 16));
-  return fmaxf(v, __shfl_xor(v, 32));
+  const SwapPair p = rows_swap16(v);
+  const SwapPair q = rows_swap32(fmaxf(p.a, p.b));
+  return fmaxf(q.a, q.b);
 }
 __device__ __forceinline__ float xor_sum(float v) {
-  v += __shfl_xor(v, 16);
-  return v + __shfl_xor(v, 32);
+  const SwapPair p = rows_swap16(v);
+  const SwapPair q = rows_swap32(p.a + p.b);
+  return q.a + q.b;
 }
+
+// Source of the 64-row tiles of a [S x ld] bf16 matrix (D columns from `base` on, the first row of a sequence):
+// one 16-byte buffer load per thread and chunk.  A thread's offsets inside a tile never change (tile_offsets); the
+// tile is chosen by the instruction's scalar offset, so the loop spends no vector arithmetic on addresses.  The
+// view ends with the sequence's last row: rows past it read as zeros.  Needs S * ld * 2 < 2^31 (checked on the host).
+template <int D>
+struct TileSrc {
+  static constexpr int CPR = D / 8, NLD = kBKV * CPR / kThreads;
+  __amdgpu_buffer_rsrc_t rs;
+  uint32_t step;  // bytes from one tile to the next
+  __device__ __forceinline__ void init(const uint16_t* base, int64_t ld, int S) {
+    rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(base), 0, int((int64_t(S - 1) * ld + D) * 2), 0x00020000);
+    step = uint32_t(kBKV * ld * 2);
+  }
+  static __device__ __forceinline__ void tile_offsets(int64_t ld, uint32_t (&voff)[NLD]) {
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const int c = threadIdx.x + i * kThreads;
+      voff[i] = uint32_t(((c / CPR) * ld + (c % CPR) * 8) * 2);
+    }
+  }
+  __device__ __forceinline__ void load(int t, const uint32_t (&voff)[NLD], ntp_gemm::u16x8 (&r)[NLD]) const {
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) r[i] = __builtin_bit_cast(ntp_gemm::u16x8, __builtin_amdgcn_raw_buffer_load_b128(rs, voff[i], uint32_t(t) * step, 0));
+  }
+};
 
 // (two or three wavefronts per SIMD: one's softmax arithmetic overlaps the others' matrix instructions)
 template <int D, int QB>
@@ -125,15 +173,14 @@ __global__ __launch_bounds__(kThreads, QB == 1 ? 3 : 2) void attn_core_fwd_kerne
 
   // tile copy: global -> registers -> LDS, the next tile's loads in flight during the products
   ntp_gemm::u16x8 rk[NLD], rv[NLD];
-  auto load_tile = [&](int t) {
-#pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      const int c = threadIdx.x + i * kThreads;
-      const int row = min(t * kBKV + c / CPR, S - 1);  // rows past the end repeat the last one (masked below)
-      const int64_t off = (tok0 + row) * a.ld + (c % CPR) * 8;
-      rk[i] = *reinterpret_cast<const ntp_gemm::u16x8*>(Kp + off);
-      rv[i] = *reinterpret_cast<const ntp_gemm::u16x8*>(Vp + off);
-    }
+  uint32_t voff[NLD];
+  TileSrc<D>::tile_offsets(a.ld, voff);
+  TileSrc<D> srcK, srcV;
+  srcK.init(Kp + tok0 * a.ld, a.ld, S);
+  srcV.init(Vp + tok0 * a.ld, a.ld, S);
+  auto load_tile = [&](int t) {  // rows past the sequence end arrive as zeros (their scores are masked below)
+    srcK.load(t, voff, rk);
+    srcV.load(t, voff, rv);
   };
   auto store_tile = [&](int buf) {
 #pragma unroll
@@ -428,15 +475,14 @@ __global__ __launch_bounds__(kThreads, QB == 1 ? 3 : 2) void attn_core_bwd_dq_ke
   const int kv_end = a.causal ? min(S, qt * kRows + kRows) : S;
   const int n_tiles = (kv_end + kBKV - 1) / kBKV;
   ntp_gemm::u16x8 rk[NLD], rv[NLD];
-  auto load_tile = [&](int t) {
-#pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      const int c = threadIdx.x + i * kThreads;
-      const int row = min(t * kBKV + c / CPR, S - 1);
-      const int64_t off = (tok0 + row) * a.ld + (c % CPR) * 8;
-      rk[i] = *reinterpret_cast<const ntp_gemm::u16x8*>(Kp + off);
-      rv[i] = *reinterpret_cast<const ntp_gemm::u16x8*>(Vp + off);
-    }
+  uint32_t voff[NLD];
+  TileSrc<D>::tile_offsets(a.ld, voff);
+  TileSrc<D> srcK, srcV;
+  srcK.init(Kp + tok0 * a.ld, a.ld, S);
+  srcV.init(Vp + tok0 * a.ld, a.ld, S);
+  auto load_tile = [&](int t) {  // rows past the sequence end arrive as zeros (masked below)
+    srcK.load(t, voff, rk);
+    srcV.load(t, voff, rv);
   };
   auto store_tile = [&]() {
 #pragma unroll
@@ -605,6 +651,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dkv_kernel(const Co
   const int u_hi = a.n_parts > 1 ? int(int64_t(part + 1) * units / a.n_parts) : units;
   int head_idx = 0;
   ntp_gemm::u16x8 rq[NLD], rg[NLD];
+  uint32_t voffq[NLD], voffg[NLD];
+  TileSrc<D>::tile_offsets(a.ld, voffq);
+  TileSrc<D>::tile_offsets(a.lddc, voffg);
   float rl = 0.f, rd = 0.f;
   for (int head = 0; head < a.q_cnt; ++head) {
     if ((a.q_off + head) / a.group - a.kv_off != g) continue;  // the same for the whole workgroup
@@ -614,14 +663,12 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dkv_kernel(const Co
     if (t_lo >= t_hi) continue;
     const uint16_t* Qp = a.QKV + int64_t(head) * D;
     const uint16_t* Gp = a.dC + int64_t(head) * D;
-    auto load_tile = [&](int t) {
-#pragma unroll
-      for (int i = 0; i < NLD; ++i) {
-        const int c = threadIdx.x + i * kThreads;
-        const int row = min(t * kBKV + c / CPR, S - 1);
-        rq[i] = *reinterpret_cast<const ntp_gemm::u16x8*>(Qp + (tok0 + row) * a.ld + (c % CPR) * 8);
-        rg[i] = *reinterpret_cast<const ntp_gemm::u16x8*>(Gp + (tok0 + row) * a.lddc + (c % CPR) * 8);
-      }
+    TileSrc<D> srcQ, srcG;
+    srcQ.init(Qp + tok0 * a.ld, a.ld, S);
+    srcG.init(Gp + tok0 * a.lddc, a.lddc, S);
+    auto load_tile = [&](int t) {  // rows past the sequence end arrive as zeros (masked below)
+      srcQ.load(t, voffq, rq);
+      srcG.load(t, voffg, rg);
       if (threadIdx.x < kBKV) {
         const int row = min(t * kBKV + int(threadIdx.x), S - 1);
         rl = a.LSE[int64_t(head) * Mtot + tok0 + row] * 1.4426950408889634f;
@@ -882,6 +929,8 @@ extern "C" int ntp_attn_core_shard_fwd(ntp_handle_t* h, const ntp_attn_core_shap
   if ((reinterpret_cast<uintptr_t>(QKV) & 15) || (reinterpret_cast<uintptr_t>(C) & 15) || ldqkv % 8 || ldc % 8 ||
       (reinterpret_cast<uintptr_t>(LSE) & 3))
     return NTP_ERR_ALIGNMENT;
+  // the tile loads address one sequence's rows with 32-bit byte offsets
+  if (int64_t(s->seq_len) * ldqkv * 2 > 0x7fffffffll) return NTP_ERR_UNSUPPORTED;
   CoreArgs a{};
   a.QKV = static_cast<const uint16_t*>(QKV);
   a.C = static_cast<uint16_t*>(C);
@@ -951,6 +1000,7 @@ extern "C" int ntp_attn_core_shard_bwd(ntp_handle_t* h, const ntp_attn_core_shap
   if (mis(QKV) || mis(dQKV) || mis(C) || mis(dC) || ldqkv % 8 || lddqkv % 8 || ldc % 8 || lddc % 8 ||
       (reinterpret_cast<uintptr_t>(LSE) & 3) || (reinterpret_cast<uintptr_t>(Delta) & 3))
     return NTP_ERR_ALIGNMENT;
+  if (int64_t(s->seq_len) * std::max(ldqkv, lddc) * 2 > 0x7fffffffll) return NTP_ERR_UNSUPPORTED;
   CoreBwdArgs a{};
   a.QKV = static_cast<const uint16_t*>(QKV);
   a.C = static_cast<const uint16_t*>(C);

@@ -304,6 +304,7 @@ int gemm_launch(ntp_handle* h, const GemmDesc& d, void* stream) {
   g.a_extent = uint32_t(std::min<int64_t>(0xFFFFFFFFll, operand_extent_bytes(d.a_kc, d.M, d.K, d.lda, g.ring_tail != 0)));
   g.b_extent = uint32_t(std::min<int64_t>(0xFFFFFFFFll, operand_extent_bytes(d.b_kc, d.N, d.K, d.ldb, false)));
   g.resident = h->compute_units;
+  if (const int64_t cap = h->opt[NTP_OPT_GEMM_WORKGROUPS]) g.resident = int32_t(std::min<int64_t>(cap, h->compute_units));
   // split-K: any (layout, epilogue) whose operands the ring kernel can address, except B K-contiguous
   // with A K-strided (no ring kernel)
   const bool split_ok = a_rows * d.lda * 2 < (int64_t(1) << 32) && b_rows * d.ldb * 2 < (int64_t(1) << 32) && (d.a_kc || !d.b_kc);

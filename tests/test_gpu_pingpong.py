@@ -1,6 +1,7 @@
 """The ping-pong schedule of the ring GEMM kernel (NTP_OPT_GEMM_SCHEDULE = 2) against the oracle: every 8-wavefront
 tile shape on ragged shapes (K tails through registers and through the ring, rows and columns past the edge), and
-a shape with more output tiles than compute units (workgroups walk over several tiles).  On a real MI355X."""
+a shape with more output tiles than compute units (workgroups walk over several tiles), and short K with the grid
+capped at 8 workgroups (each walks over many output tiles of 1 to 6 K tiles).  On a real MI355X."""
 import sys
 
 import numpy as np
@@ -62,6 +63,23 @@ def test_attn_pingpong(pingpong, opts, tile):
     opts(K.NTP_OPT_GEMM_TILE, tile)
     case = AttnCase(520, 1032, 16, 2, 64, 5, 0)
     _check_all(case.run_gpu(), case.oracle(), ["QKV", "Z", "dC", "dX", "dWqkv", "dWo"])
+
+
+@pytest.mark.parametrize("schedule", [1, 2])
+@pytest.mark.parametrize("k_tiles", [1, 2, 3, 5, 6])
+def test_few_k_tiles_many_output_tiles_per_workgroup(opts, schedule, k_tiles):
+    """One K of the layer = 64 k_tiles and the persistent grid capped at 8 workgroups (NTP_OPT_GEMM_WORKGROUPS): each
+    workgroup walks over 5 to 13 output tiles whose K loops are shorter than the ring's look-ahead, under either schedule."""
+    kk = 64 * k_tiles
+    _say(f"schedule {schedule}, {k_tiles} K tiles per output tile, 8 workgroups")
+    opts(K.NTP_OPT_GEMM_SCHEDULE, schedule)
+    opts(K.NTP_OPT_GEMM_TILE, "224x256")
+    opts(K.NTP_OPT_GEMM_WORKGROUPS, 8)
+    # fc1 / dP: K = H; fc2 / dX: K = n_r; dA / dB: K = M -> three cases, each with one short K and longer other sides
+    for (M, H, n) in [(1500, kk, 1700), (1500, 1696, kk), (kk, 1504, 1700)]:
+        case = MlpCase(M, H, n, 1, 0, tag=f"pp.k{k_tiles}.{M}.{H}")
+        got, _ = case.run_gpu(pad_to=64)
+        _check_all(got, case.oracle(), MLP_NAMES)
 
 
 def test_mlp_pingpong_many_tiles_per_workgroup(pingpong):
