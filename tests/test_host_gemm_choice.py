@@ -80,7 +80,10 @@ def test_schedule_choice_and_override():
     c = Bd.ntp_gemm_choice(0, 2048, 7022, 12288, handle=h)
     assert c["persistent"] == 1 and c["pingpong"] == 1
     assert Bd.ntp_gemm_choice(1, 2048, 12288, 7022, handle=h)["pingpong"] == 0
-    assert Bd.ntp_gemm_choice(2, 7022, 12288, 2048, handle=h)["pingpong"] == 0
+    c = Bd.ntp_gemm_choice(2, 7022, 12288, 2048, handle=h)  # weight gradient on the 224 x 256 tile: ping-pong too
+    assert (c["tile_m"], c["tile_n"], c["pingpong"]) == (224, 256, 1)
+    c = Bd.ntp_gemm_choice(2, 1792, 12288, 2048, handle=h)  # ... on the 192 x 256 tile: default schedule
+    assert (c["tile_m"], c["tile_n"], c["pingpong"]) == (192, 256, 0)
     assert Bd.ntp_gemm_choice(0, 512, 586, 1024, handle=h)["pingpong"] == 0  # the small 128 x 128 tile has one schedule
     Bd.ntp_set_option(Bd.NTP_OPT_GEMM_SCHEDULE, 1, handle=h)
     assert Bd.ntp_gemm_choice(0, 2048, 7022, 12288, handle=h)["pingpong"] == 0
