@@ -247,3 +247,8 @@ def test_attn_core_rejects_bad_arguments():
     with pytest.raises(N.NtpError) as e:  # QKV narrower than the heads need
         N.ntp_attn_core_shard_fwd(N.attn_core_shape(1, 64, plan, 2), torch.zeros(64, 384, dtype=torch.bfloat16, device="cuda"), Cc)
     assert e.value.status == K.NTP_ERR_INVALID_ARG
+    # one sequence's rows of QKV spanning 2 GiB or more (2^21 rows of 512 values): refused before anything is launched
+    import ctypes as C
+    big = N.attn_core_shape(1, 1 << 21, plan, 2)
+    st = K.lib().ntp_attn_core_shard_fwd(N.default_handle().ptr, C.byref(big), QKV.data_ptr(), 512, Cc.data_ptr(), 256, None, None)
+    assert st == K.NTP_ERR_UNSUPPORTED
