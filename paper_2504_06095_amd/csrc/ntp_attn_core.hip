@@ -17,6 +17,7 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstdlib>
+#include <type_traits>
 
 #include "ntp_gemm_kernels.h"
 #include "ntp_internal.h"
@@ -45,6 +46,10 @@ struct CoreArgs {
   // sum to part_sums ([workgroup][piece][64 rows][D + 4]: D outputs, maximum, sum); a second kernel merges them
   float* part_sums;
   int32_t n_parts;
+  // pairs > 0 (causal mask): a workgroup takes two query tiles one after the other, number pairs - 1 - u from the
+  // end and number u from the start, so that every workgroup walks over the same number of key tiles
+  // (q_tiles + 1, cut into n_parts); pairs = (q_tiles + 1) / 2 workgroups per (sequence, head)
+  int32_t pairs;
 };
 
 // 2^x by the hardware instruction alone: results below the normal range flush to zero, which is what a
@@ -109,8 +114,11 @@ struct TileSrc {
 };
 
 // (two or three wavefronts per SIMD: one's softmax arithmetic overlaps the others' matrix instructions)
-template <int D, int QB>
-__global__ __launch_bounds__(kThreads, QB == 1 ? 3 : 2) void attn_core_fwd_kernel(const CoreArgs a) {
+// (the register budget is pinned to that occupancy: left free, the compiler squeezes the 16-row variant into 128
+// registers for a fourth wavefront per SIMD that these launches never have, and the loop runs 10 % slower)
+template <int D, int QB, bool PAIRED>
+__global__ __attribute__((amdgpu_flat_work_group_size(kThreads, kThreads), amdgpu_waves_per_eu(QB == 1 ? 3 : 2, QB == 1 ? 3 : 2))) void
+attn_core_fwd_kernel(const CoreArgs a) {
   constexpr int kRows = 64 * QB;  // query rows per workgroup: 16 QB per wavefront
   // LDS row stride (elements): rows shift by 8 banks, so the 8 rows that a 16-byte fragment read touches per
   // cycle and the 4 rows x 32 bytes that a transposing read touches per cycle land on distinct banks
@@ -131,19 +139,35 @@ __global__ __launch_bounds__(kThreads, QB == 1 ? 3 : 2) void attn_core_fwd_kerne
   // With the causal mask the late tiles have the most keys: they go first.
   const int piece = a.n_parts > 1 ? int(blockIdx.x % a.n_parts) : 0;
   const int blk = a.n_parts > 1 ? int(blockIdx.x / a.n_parts) : int(blockIdx.x);
-  const int qt = a.causal ? a.q_tiles - 1 - blk % a.q_tiles : blk % a.q_tiles;
-  const int sh = blk / a.q_tiles;
+  const int per_seq = PAIRED ? a.pairs : a.q_tiles;  // workgroups per (sequence, head) and piece
+  const int u = blk % per_seq;
+  const int sh = blk / per_seq;
   const int seq = sh % a.n_seq, head = sh / a.n_seq;
   const int g = (a.q_off + head) / a.group - a.kv_off;  // local KV head
   const int S = a.seq_len;
   const int64_t tok0 = int64_t(seq) * S;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lq = lane & 15, lh = lane >> 4;
-  const int q0 = qt * kRows + wave * (16 * QB);  // first query row (in the sequence) of this wavefront
-
   const uint16_t* Qp = a.QKV + int64_t(head) * D;
   const uint16_t* Kp = a.QKV + int64_t(a.q_cnt + g) * D;
   const uint16_t* Vp = a.QKV + int64_t(a.q_cnt + a.kv_cnt + g) * D;
+  ntp_gemm::u16x8 rk[NLD], rv[NLD];
+  uint32_t voff[NLD];
+  TileSrc<D>::tile_offsets(a.ld, voff);
+  TileSrc<D> srcK, srcV;
+  srcK.init(Kp + tok0 * a.ld, a.ld, S);
+  srcV.init(Vp + tok0 * a.ld, a.ld, S);
+
+  for (int seg = 0; seg < (PAIRED ? 2 : 1); ++seg) {
+  // this pass's query tile; without pairing the late tiles of a causal launch (the most keys) go first
+  const int qt = PAIRED ? (seg == 0 ? a.q_tiles - 1 - u : u) : (a.causal ? a.q_tiles - 1 - u : u);
+  if (seg == 1) {
+    if (qt == a.q_tiles - 1 - u) break;  // odd tile count: the middle tile has no partner
+    __syncthreads();                     // the first pass's last tile has been read by everyone
+  }
+  // the tile's number in the order the merge kernel counts them (late tiles first under the causal mask)
+  const int64_t tblk = int64_t(sh) * a.q_tiles + (a.causal ? a.q_tiles - 1 - qt : qt);
+  const int q0 = qt * kRows + wave * (16 * QB);  // first query row (in the sequence) of this wavefront
 
   // query fragments: operand B[k][j] with j = query row (lane % 16), k = 8 consecutive columns
   bf16x8 qf[QB][KS];
@@ -172,12 +196,6 @@ __global__ __launch_bounds__(kThreads, QB == 1 ? 3 : 2) void attn_core_fwd_kerne
   const int n_tiles = (kv_end + kBKV - 1) / kBKV;
 
   // tile copy: global -> registers -> LDS, the next tile's loads in flight during the products
-  ntp_gemm::u16x8 rk[NLD], rv[NLD];
-  uint32_t voff[NLD];
-  TileSrc<D>::tile_offsets(a.ld, voff);
-  TileSrc<D> srcK, srcV;
-  srcK.init(Kp + tok0 * a.ld, a.ld, S);
-  srcV.init(Vp + tok0 * a.ld, a.ld, S);
   auto load_tile = [&](int t) {  // rows past the sequence end arrive as zeros (their scores are masked below)
     srcK.load(t, voff, rk);
     srcV.load(t, voff, rv);
@@ -323,7 +341,7 @@ __global__ __launch_bounds__(kThreads, QB == 1 ? 3 : 2) void attn_core_fwd_kerne
     // this piece's unnormalised rows, maximum (in log2 units) and sum
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-      float* pp = a.part_sums + ((int64_t(blk) * a.n_parts + piece) * kRows + wave * (16 * QB) + qb * 16 + lq) * (D + 4);
+      float* pp = a.part_sums + ((tblk * a.n_parts + piece) * kRows + wave * (16 * QB) + qb * 16 + lq) * (D + 4);
 #pragma unroll
       for (int db = 0; db < DB; ++db) *reinterpret_cast<f32x4*>(pp + db * 16 + lh * 4) = acc[qb][db];
       const float l = xor_sum(l_run[qb]);
@@ -332,7 +350,7 @@ __global__ __launch_bounds__(kThreads, QB == 1 ? 3 : 2) void attn_core_fwd_kerne
         pp[D + 1] = l;
       }
     }
-    return;
+    continue;
   }
   // normalise and store: lane holds output columns db*16 + (lane/16)*4 .. +3 of query row lane % 16
 #pragma unroll
@@ -352,6 +370,7 @@ __global__ __launch_bounds__(kThreads, QB == 1 ? 3 : 2) void attn_core_fwd_kerne
       if (lh == 0 && a.LSE) a.LSE[int64_t(head) * (int64_t(a.n_seq) * S) + tok0 + qrow] = (m_run[qb] + log2f(l)) * 0.6931471805599453f;
     }
   }
+  }  // the workgroup's passes
 }
 
 // Merges the pieces of a cut forward walk: with m = max_p m_p, the row is sum_p 2^(m_p - m) O_p over
@@ -410,6 +429,10 @@ struct CoreBwdArgs {
   // their fp32 sums to part_sums ([workgroup][part][64 rows][row length]); a second kernel adds them
   float* part_sums;
   int32_t n_parts;
+  // pairs > 0 (causal mask): a workgroup takes two tiles one after the other, one from each end of the sequence, so
+  // that every workgroup's walk has the same length (tiles + 1 tiles, cut into n_parts); pairs = (tiles + 1) / 2
+  // workgroups per (sequence, head)
+  int32_t pairs;
 };
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4_t;
@@ -425,26 +448,43 @@ __device__ __forceinline__ bf16x8 tr_frag(const uint16_t* tile, int ldt, int r0,
 }
 
 // dQ (and delta): a workgroup takes 64 QB query rows of one (sequence, head), a wavefront 16 QB of them.
-template <int D, int QB>
-__global__ __launch_bounds__(kThreads, QB == 1 ? 3 : 2) void attn_core_bwd_dq_kernel(const CoreBwdArgs a) {
+template <int D, int QB, bool PAIRED>
+__global__ __attribute__((amdgpu_flat_work_group_size(kThreads, kThreads), amdgpu_waves_per_eu(QB == 1 ? 3 : 2, QB == 1 ? 3 : 2))) void
+attn_core_bwd_dq_kernel(const CoreBwdArgs a) {
   constexpr int kRows = 64 * QB;
   constexpr int LDT = D + 16, KS = D / 32, DB = D / 16, CPR = D / 8, NLD = kBKV * CPR / kThreads;
   __shared__ __attribute__((aligned(16))) uint16_t sK[kBKV * LDT];
   __shared__ __attribute__((aligned(16))) uint16_t sV[kBKV * LDT];
   const int piece = a.n_parts > 1 ? int(blockIdx.x % a.n_parts) : 0;
   const int blk = a.n_parts > 1 ? int(blockIdx.x / a.n_parts) : int(blockIdx.x);
-  const int qt = a.causal ? a.tiles - 1 - blk % a.tiles : blk % a.tiles;
-  const int sh = blk / a.tiles;
+  const int per_seq = PAIRED ? a.pairs : a.tiles;
+  const int u = blk % per_seq;
+  const int sh = blk / per_seq;
   const int seq = sh % a.n_seq, head = sh / a.n_seq;
   const int g = (a.q_off + head) / a.group - a.kv_off;
   const int S = a.seq_len;
   const int64_t tok0 = int64_t(seq) * S, Mtot = int64_t(a.n_seq) * S;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lq = lane & 15, lh = lane >> 4;
-  const int q0 = qt * kRows + wave * (16 * QB);
   const uint16_t* Qp = a.QKV + int64_t(head) * D;
   const uint16_t* Kp = a.QKV + int64_t(a.q_cnt + g) * D;
   const uint16_t* Vp = a.QKV + int64_t(a.q_cnt + a.kv_cnt + g) * D;
+  ntp_gemm::u16x8 rk[NLD], rv[NLD];
+  uint32_t voff[NLD];
+  TileSrc<D>::tile_offsets(a.ld, voff);
+  TileSrc<D> srcK, srcV;
+  srcK.init(Kp + tok0 * a.ld, a.ld, S);
+  srcV.init(Vp + tok0 * a.ld, a.ld, S);
+
+  for (int seg = 0; seg < (PAIRED ? 2 : 1); ++seg) {
+  const int qt = PAIRED ? (seg == 0 ? a.tiles - 1 - u : u) : (a.causal ? a.tiles - 1 - u : u);
+  if (seg == 1) {
+    if (qt == a.tiles - 1 - u) break;  // odd tile count: the middle tile has no partner
+    __syncthreads();                   // the first pass's last tile has been read by everyone
+  }
+  // the tile's number in the order the reduce kernel counts them (late tiles first under the causal mask)
+  const int64_t tblk = int64_t(sh) * a.tiles + (a.causal ? a.tiles - 1 - qt : qt);
+  const int q0 = qt * kRows + wave * (16 * QB);
 
   // query and output-gradient fragments (operand B: j = query row), delta and the log-sum-exp of the rows
   bf16x8 qf[QB][KS], gf[QB][KS];
@@ -474,12 +514,6 @@ __global__ __launch_bounds__(kThreads, QB == 1 ? 3 : 2) void attn_core_bwd_dq_ke
 
   const int kv_end = a.causal ? min(S, qt * kRows + kRows) : S;
   const int n_tiles = (kv_end + kBKV - 1) / kBKV;
-  ntp_gemm::u16x8 rk[NLD], rv[NLD];
-  uint32_t voff[NLD];
-  TileSrc<D>::tile_offsets(a.ld, voff);
-  TileSrc<D> srcK, srcV;
-  srcK.init(Kp + tok0 * a.ld, a.ld, S);
-  srcV.init(Vp + tok0 * a.ld, a.ld, S);
   auto load_tile = [&](int t) {  // rows past the sequence end arrive as zeros (masked below)
     srcK.load(t, voff, rk);
     srcV.load(t, voff, rv);
@@ -573,11 +607,11 @@ __global__ __launch_bounds__(kThreads, QB == 1 ? 3 : 2) void attn_core_bwd_dq_ke
     // unscaled fp32 sums of this part: row (wavefront, block, lane % 16) of the workgroup's 64 QB rows
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-      float* pp = a.part_sums + ((int64_t(blk) * a.n_parts + piece) * kRows + wave * (16 * QB) + qb * 16 + lq) * D + lh * 4;
+      float* pp = a.part_sums + ((tblk * a.n_parts + piece) * kRows + wave * (16 * QB) + qb * 16 + lq) * D + lh * 4;
 #pragma unroll
       for (int db = 0; db < DB; ++db) *reinterpret_cast<f32x4*>(pp + db * 16) = acc[qb][db];
     }
-    return;
+    continue;
   }
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
@@ -592,13 +626,14 @@ __global__ __launch_bounds__(kThreads, QB == 1 ? 3 : 2) void attn_core_bwd_dq_ke
       *reinterpret_cast<u16x4*>(op + db * 16) = o;
     }
   }
+  }  // the workgroup's passes
 }
 
 // dK and dV: a workgroup takes 64 KB keys of one (sequence, KV head), a wavefront 16 KB of them, and walks
 // over the query rows (tiles of 64) of every local query head that reads this KV head.  KB = 2 does twice
 // the matrix work per LDS read but needs 440 registers (one wavefront per SIMD); KB = 1 fits in 256, two
 // workgroups share a compute unit and it measured 7-35 % faster at every size: only KB = 1 is built.
-template <int D, int KB>
+template <int D, int KB, bool PAIRED>
 __global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dkv_kernel(const CoreBwdArgs a) {
   constexpr int LDT = D + 16, KS = D / 32, DB = D / 16, CPR = D / 8, NLD = kBKV * CPR / kThreads;
   __shared__ __attribute__((aligned(16))) uint16_t sQ[kBKV * LDT];
@@ -607,16 +642,27 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dkv_kernel(const Co
   __shared__ __attribute__((aligned(16))) float sD[kBKV];
   const int part = a.n_parts > 1 ? int(blockIdx.x % a.n_parts) : 0;
   const int blk = a.n_parts > 1 ? int(blockIdx.x / a.n_parts) : int(blockIdx.x);
-  const int kt = blk % a.tiles;
-  const int sh = blk / a.tiles;
+  const int per_seq = PAIRED ? a.pairs : a.tiles;
+  const int u = blk % per_seq;
+  const int sh = blk / per_seq;
   const int seq = sh % a.n_seq, g = sh / a.n_seq;  // g: local KV head
   const int S = a.seq_len;
   const int64_t tok0 = int64_t(seq) * S, Mtot = int64_t(a.n_seq) * S;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lq = lane & 15, lh = lane >> 4;
-  const int k0 = kt * (64 * KB) + wave * (16 * KB);  // first key of this wavefront
   const uint16_t* Kp = a.QKV + int64_t(a.q_cnt + g) * D;
   const uint16_t* Vp = a.QKV + int64_t(a.q_cnt + a.kv_cnt + g) * D;
+  ntp_gemm::u16x8 rq[NLD], rg[NLD];
+  uint32_t voffq[NLD], voffg[NLD];
+  TileSrc<D>::tile_offsets(a.ld, voffq);
+  TileSrc<D>::tile_offsets(a.lddc, voffg);
+
+  for (int seg = 0; seg < (PAIRED ? 2 : 1); ++seg) {
+  // this pass's key tile: with pairing an early one (whose keys most query tiles see), then its partner from the end
+  const int kt = PAIRED && seg == 1 ? a.tiles - 1 - u : u;
+  if (seg == 1 && kt == u) break;  // odd tile count: the middle tile has no partner
+  const int64_t tblk = int64_t(sh) * a.tiles + kt;
+  const int k0 = kt * (64 * KB) + wave * (16 * KB);  // first key of this wavefront
 
   // key and value fragments (operand B: j = key)
   bf16x8 kf[KB][KS], vf[KB][KS];
@@ -650,10 +696,6 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dkv_kernel(const Co
   const int u_lo = a.n_parts > 1 ? int(int64_t(part) * units / a.n_parts) : 0;
   const int u_hi = a.n_parts > 1 ? int(int64_t(part + 1) * units / a.n_parts) : units;
   int head_idx = 0;
-  ntp_gemm::u16x8 rq[NLD], rg[NLD];
-  uint32_t voffq[NLD], voffg[NLD];
-  TileSrc<D>::tile_offsets(a.ld, voffq);
-  TileSrc<D>::tile_offsets(a.lddc, voffg);
   float rl = 0.f, rd = 0.f;
   for (int head = 0; head < a.q_cnt; ++head) {
     if ((a.q_off + head) / a.group - a.kv_off != g) continue;  // the same for the whole workgroup
@@ -781,14 +823,14 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dkv_kernel(const Co
     // unscaled fp32 sums of this part: per key a row of [dK | dV]
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb) {
-      float* pp = a.part_sums + ((int64_t(blk) * a.n_parts + part) * (64 * KB) + wave * (16 * KB) + kb * 16 + lq) * (2 * D) + lh * 4;
+      float* pp = a.part_sums + ((tblk * a.n_parts + part) * (64 * KB) + wave * (16 * KB) + kb * 16 + lq) * (2 * D) + lh * 4;
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
         *reinterpret_cast<f32x4*>(pp + db * 16) = dk[kb][db];
         *reinterpret_cast<f32x4*>(pp + D + db * 16) = dv[kb][db];
       }
     }
-    return;
+    continue;
   }
 #pragma unroll
   for (int kb = 0; kb < KB; ++kb) {
@@ -808,6 +850,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dkv_kernel(const Co
       *reinterpret_cast<u16x4*>(vp + db * 16) = ov;
     }
   }
+  }  // the workgroup's passes
 }
 
 // Adds the parts of a cut walk and stores the gradient as bf16.  `rows` rows per workgroup of the cut
@@ -837,21 +880,25 @@ __global__ __launch_bounds__(256) void attn_core_part_reduce_kernel(const CoreBw
   *reinterpret_cast<u16x4*>(a.dQKV + (int64_t(seq) * a.seq_len + tok) * a.ldd + slot * D + col) = o;
 }
 
-// Parts to cut each workgroup's walk into, so that a launch of `blocks` workgroups whose longest walk has
-// `walk` tiles fills the GPU: 1 (no cut) unless ws_bytes of workspace hold the partial sums.
-int choose_parts(const ntp_handle* h, int64_t ws_bytes, int64_t blocks, int64_t walk, int64_t bytes_per_block_part, bool causal) {
-  if (ws_bytes <= 0 || blocks <= 0) return 1;
-  // Up to one workgroup per compute unit: about 4 parts per compute unit in all measured best at 64 to 192
-  // workgroups; beyond 12 parts per workgroup the merge costs more than it gains.  Up to twice as many workgroups
-  // two parts still pay under the causal mask (uneven walks: 448 workgroups, 63 -> 58 us forward) and cost
-  // 10 % without it.
+// Parts to cut each workgroup's walk into.  wgs: workgroups the launch has uncut; walk: key (or query) tiles each
+// walks over; slots x parts x bytes_per_part must fit ws_bytes (no workspace: no cut).  Measured on 2 to 14 heads x
+// 2048 to 8192 tokens: the best count brings the launch to fill x compute units workgroups (fill = 2 under the causal
+// mask, where paired tiles make all walks equal, and for the dK/dV kernel; 3 for the unmasked forward and dQ
+// kernels), as long as a part keeps at least 6 tiles; launches that already have more workgroups than compute units
+// gain only from parts of more than 16 tiles (the merge pass and the per-workgroup prologue cost more than shorter
+// parts gain); a causal walk of 40 tiles or more per part takes one part more.
+int choose_parts(const ntp_handle* h, int64_t ws_bytes, int64_t wgs, int64_t slots, int64_t walk, int64_t bytes_per_part, double fill,
+                 int64_t cap, bool causal) {
+  if (ws_bytes <= 0 || wgs <= 0) return 1;
   const int64_t cus = h->compute_units;
-  int64_t parts = 1;
-  if (blocks <= cus) parts = std::min<int64_t>({12, (4 * cus + blocks - 1) / blocks, walk / 4});
-  else if (causal && blocks < 2 * cus) parts = std::min<int64_t>(2, walk / 4);
+  int64_t parts = std::min<int64_t>(cap, std::max<int64_t>(1, int64_t(fill * double(cus) / double(wgs) + 0.5)));
+  parts = std::min<int64_t>(parts, std::max<int64_t>(1, walk / 6));
+  if (wgs > cus)
+    while (parts > 1 && walk / parts <= 16) --parts;
+  if (causal && parts < cap && walk / parts >= 40 && wgs * parts < 3 * cus) ++parts;
   // tests reach every cut through this override (1..16 parts at any size)
   if (const int64_t f = h->opt[NTP_OPT_ATTN_PARTS]) parts = std::min<int64_t>(16, std::max<int64_t>(1, f));
-  while (parts > 1 && blocks * parts * bytes_per_block_part > ws_bytes) --parts;
+  while (parts > 1 && slots * parts * bytes_per_part > ws_bytes) --parts;
   return int(std::max<int64_t>(parts, 1));
 }
 
@@ -863,21 +910,28 @@ struct CoreChoice {
 };
 CoreChoice choose_core(const ntp_handle* h, int64_t ws_bytes, const ntp_attn_core_shape_t* s) {
   CoreChoice c{16, 1, 1, 1, 0};
+  const bool causal = s->causal != 0;
   const int64_t tiles = (s->seq_len + kBKV - 1) / kBKV;
+  // under the causal mask a workgroup takes a pair of tiles, one from each end of the sequence
+  const int64_t per_seq = causal ? (tiles + 1) / 2 : tiles, walk = causal ? tiles + 1 : tiles;
   // 16-row query blocks per wavefront: two (twice the matrix work per LDS read, two workgroups per CU), or
   // one (three workgroups per CU, twice as many of them) when two would leave compute units short of work
+  // (the same count with and without the mask: the causal pairs make the 128-row tiles' walks equal, 14 heads x
+  // 8192 tokens causal 375 -> 309 us with two)
   const int64_t blocks2 = int64_t((s->seq_len + 127) / 128) * s->n_seq * s->q_cnt;
-  c.fwd_rows = blocks2 < (s->causal ? 4 : 1.5) * h->compute_units ? 16 : 32;
+  c.fwd_rows = blocks2 < 1.5 * h->compute_units ? 16 : 32;
   // with few heads even the 64-row workgroups leave compute units idle while each walks over up to
   // seq_len / 64 key tiles: cut the walks then (needs a workspace)
-  const int64_t bq = tiles * s->n_seq * s->q_cnt, bk = tiles * s->n_seq * s->kv_cnt;
+  const int64_t bq = tiles * s->n_seq * s->q_cnt, bk = tiles * s->n_seq * s->kv_cnt;  // tiles: one partial-sum slot each
+  const int64_t wq = per_seq * s->n_seq * s->q_cnt, wk = per_seq * s->n_seq * s->kv_cnt;
   const int64_t bf = int64_t(64) * (s->head_dim + 4) * 4, bdq = int64_t(64) * s->head_dim * 4, bdkv = int64_t(64) * 2 * s->head_dim * 4;
-  c.fwd_parts = choose_parts(h, ws_bytes, bq, tiles, bf, s->causal != 0);
+  const double fill = causal ? 2.0 : 3.0;
+  c.fwd_parts = choose_parts(h, ws_bytes, wq, bq, walk, bf, fill, 12, causal);
   if (c.fwd_parts > 1) c.fwd_rows = 16;
-  c.dq_parts = choose_parts(h, ws_bytes, bq, tiles, bdq, s->causal != 0);
+  c.dq_parts = choose_parts(h, ws_bytes, wq, bq, walk, bdq, fill, 12, causal);
   // a dK/dV workgroup walks over the query tiles of every query head that reads its KV head
   const int64_t heads_per_kv = std::min<int64_t>(s->group, s->q_cnt);
-  c.dkv_parts = choose_parts(h, ws_bytes, bk, heads_per_kv * tiles, bdkv, s->causal != 0);
+  c.dkv_parts = choose_parts(h, ws_bytes, wk, bk, heads_per_kv * walk, bdkv, 2.0, 16, false);
   if (c.fwd_parts > 1) c.ws_bytes = std::max(c.ws_bytes, bq * c.fwd_parts * bf);
   if (c.dq_parts > 1) c.ws_bytes = std::max(c.ws_bytes, bq * c.dq_parts * bdq);
   if (c.dkv_parts > 1) c.ws_bytes = std::max(c.ws_bytes, bk * c.dkv_parts * bdkv);
@@ -952,8 +1006,10 @@ extern "C" int ntp_attn_core_shard_fwd(ntp_handle_t* h, const ntp_attn_core_shap
   a.part_sums = static_cast<float*>(h->workspace);
   a.n_parts = cc.fwd_parts;
   a.q_tiles = (s->seq_len + 64 * qbw - 1) / (64 * qbw);
+  a.pairs = s->causal ? (a.q_tiles + 1) / 2 : 0;
   a.scale_log2 = float(1.4426950408889634 / std::sqrt(double(s->head_dim)));
-  const int64_t blocks = int64_t(a.q_tiles) * s->n_seq * s->q_cnt;
+  const int64_t blocks = int64_t(a.q_tiles) * s->n_seq * s->q_cnt;  // query tiles
+  const int64_t wgs = int64_t(a.pairs > 0 ? a.pairs : a.q_tiles) * s->n_seq * s->q_cnt;
   if (blocks * std::max(a.n_parts, 1) > 0x7fffffffll) return NTP_ERR_UNSUPPORTED;
   hipStream_t hs = static_cast<hipStream_t>(stream);
   if (ntp::timing_on(h)) {
@@ -962,15 +1018,19 @@ extern "C" int ntp_attn_core_shard_fwd(ntp_handle_t* h, const ntp_attn_core_shap
     ntp::timing_begin(h, stream, name,
                       (s->causal ? 2.0 : 4.0) * double(s->n_seq) * double(s->seq_len) * double(s->seq_len) * s->head_dim * s->q_cnt, 0.0);
   }
-  const dim3 grid(uint32_t(blocks * std::max(a.n_parts, 1)));
-  if (s->head_dim == 128 && qbw == 2)
-    hipLaunchKernelGGL((attn_core_fwd_kernel<128, 2>), grid, dim3(kThreads), 0, hs, a);
-  else if (s->head_dim == 128)
-    hipLaunchKernelGGL((attn_core_fwd_kernel<128, 1>), grid, dim3(kThreads), 0, hs, a);
-  else if (qbw == 2)
-    hipLaunchKernelGGL((attn_core_fwd_kernel<64, 2>), grid, dim3(kThreads), 0, hs, a);
-  else
-    hipLaunchKernelGGL((attn_core_fwd_kernel<64, 1>), grid, dim3(kThreads), 0, hs, a);
+  const dim3 grid(uint32_t(wgs * std::max(a.n_parts, 1)));
+  auto launch = [&](auto d, auto q, auto paired) {
+    hipLaunchKernelGGL((attn_core_fwd_kernel<decltype(d)::value, decltype(q)::value, decltype(paired)::value>), grid, dim3(kThreads), 0, hs, a);
+  };
+  using std::integral_constant;
+  auto by_pairing = [&](auto d, auto q) {
+    if (a.pairs > 0) launch(d, q, std::true_type{});
+    else launch(d, q, std::false_type{});
+  };
+  if (s->head_dim == 128 && qbw == 2) by_pairing(integral_constant<int, 128>{}, integral_constant<int, 2>{});
+  else if (s->head_dim == 128) by_pairing(integral_constant<int, 128>{}, integral_constant<int, 1>{});
+  else if (qbw == 2) by_pairing(integral_constant<int, 64>{}, integral_constant<int, 2>{});
+  else by_pairing(integral_constant<int, 64>{}, integral_constant<int, 1>{});
   bool ok = hipGetLastError() == hipSuccess;
   if (ok && a.n_parts > 1) {
     const dim3 rgrid(uint32_t((blocks * 64 * (s->head_dim / 4) + 255) / 256));
@@ -1039,12 +1099,17 @@ extern "C" int ntp_attn_core_shard_bwd(ntp_handle_t* h, const ntp_attn_core_shap
     // dQ and delta: three products per (query, key) pair.  With few heads the launch is short of
     // workgroups and each walks over up to seq_len / 64 key tiles: cut the walks then.
     a.n_parts = cc.dq_parts;
+    a.pairs = s->causal ? (a.tiles + 1) / 2 : 0;
     if (ntp::timing_on(h)) ntp::timing_begin(h, stream, a.n_parts > 1 ? "attn_core_bwd_dq_cut" : "attn_core_bwd_dq", 3.0 * pair_flops, 0.0);
-    const dim3 grid(uint32_t(bq * a.n_parts));
-    if (s->head_dim == 128)
-      hipLaunchKernelGGL((attn_core_bwd_dq_kernel<128, qbw>), grid, dim3(kThreads), 0, hs, a);
+    const dim3 grid(uint32_t(int64_t(a.pairs > 0 ? a.pairs : a.tiles) * s->n_seq * s->q_cnt * a.n_parts));
+    if (s->head_dim == 128 && a.pairs > 0)
+      hipLaunchKernelGGL((attn_core_bwd_dq_kernel<128, qbw, true>), grid, dim3(kThreads), 0, hs, a);
+    else if (s->head_dim == 128)
+      hipLaunchKernelGGL((attn_core_bwd_dq_kernel<128, qbw, false>), grid, dim3(kThreads), 0, hs, a);
+    else if (a.pairs > 0)
+      hipLaunchKernelGGL((attn_core_bwd_dq_kernel<64, qbw, true>), grid, dim3(kThreads), 0, hs, a);
     else
-      hipLaunchKernelGGL((attn_core_bwd_dq_kernel<64, qbw>), grid, dim3(kThreads), 0, hs, a);
+      hipLaunchKernelGGL((attn_core_bwd_dq_kernel<64, qbw, false>), grid, dim3(kThreads), 0, hs, a);
     ok = hipGetLastError() == hipSuccess;
     if (ok && a.n_parts > 1) {
       const dim3 rgrid(uint32_t((bq * 64 * (s->head_dim / 4) + 255) / 256));
@@ -1062,12 +1127,17 @@ extern "C" int ntp_attn_core_shard_bwd(ntp_handle_t* h, const ntp_attn_core_shap
     // a workgroup walks over the query tiles of every query head that reads its KV head
     a.tiles = key_tiles;
     a.n_parts = cc.dkv_parts;
+    a.pairs = s->causal ? (a.tiles + 1) / 2 : 0;
     if (ntp::timing_on(h)) ntp::timing_begin(h, stream, a.n_parts > 1 ? "attn_core_bwd_dkv_cut" : "attn_core_bwd_dkv", 4.0 * pair_flops, 0.0);
-    const dim3 grid(uint32_t(bk * a.n_parts));
-    if (s->head_dim == 128)
-      hipLaunchKernelGGL((attn_core_bwd_dkv_kernel<128, kb>), grid, dim3(kThreads), 0, hs, a);
+    const dim3 grid(uint32_t(int64_t(a.pairs > 0 ? a.pairs : a.tiles) * s->n_seq * s->kv_cnt * a.n_parts));
+    if (s->head_dim == 128 && a.pairs > 0)
+      hipLaunchKernelGGL((attn_core_bwd_dkv_kernel<128, kb, true>), grid, dim3(kThreads), 0, hs, a);
+    else if (s->head_dim == 128)
+      hipLaunchKernelGGL((attn_core_bwd_dkv_kernel<128, kb, false>), grid, dim3(kThreads), 0, hs, a);
+    else if (a.pairs > 0)
+      hipLaunchKernelGGL((attn_core_bwd_dkv_kernel<64, kb, true>), grid, dim3(kThreads), 0, hs, a);
     else
-      hipLaunchKernelGGL((attn_core_bwd_dkv_kernel<64, kb>), grid, dim3(kThreads), 0, hs, a);
+      hipLaunchKernelGGL((attn_core_bwd_dkv_kernel<64, kb, false>), grid, dim3(kThreads), 0, hs, a);
     ok = hipGetLastError() == hipSuccess;
     if (ok && a.n_parts > 1) {
       const dim3 rgrid(uint32_t((bk * 64 * (2 * s->head_dim / 4) + 255) / 256));

@@ -27,22 +27,29 @@ def test_nothing_is_cut_without_a_workspace():
 
 
 def test_few_heads_get_cut_walks(workspace_1gib):
-    # config 3, rank 0: 3 query heads on 1 KV head, one causal sequence of 4096 tokens:
-    # 192 forward / dQ workgroups and 64 dK/dV workgroups with walks of 64 and 192 tiles
+    # config 3, rank 0: 3 query heads on 1 KV head, one causal sequence of 4096 tokens (64 tiles, taken in 32 pairs):
+    # 96 forward / dQ workgroups and 32 dK/dV workgroups with walks of 65 and 195 tiles -> about 512 workgroups each
     c = N.ntp_attn_core_choice(_shape(64, 8, 30, 0, 1, 4096, True))
-    assert c == dict(fwd_rows_per_wavefront=16, fwd_parts=6, dq_parts=6, dkv_parts=12)
+    assert c == dict(fwd_rows_per_wavefront=16, fwd_parts=5, dq_parts=5, dkv_parts=16)
+    # the same heads without the mask: 192 and 64 workgroups with walks of 64 and 192 tiles
+    c = N.ntp_attn_core_choice(_shape(64, 8, 30, 0, 1, 4096, False))
+    assert c == dict(fwd_rows_per_wavefront=16, fwd_parts=4, dq_parts=4, dkv_parts=8)
+    # ... and at 8192 tokens (384 workgroups, more than compute units, but parts of 64 tiles still pay)
+    c = N.ntp_attn_core_choice(_shape(64, 8, 30, 0, 1, 8192, False))
+    assert (c["fwd_parts"], c["dq_parts"], c["dkv_parts"]) == (2, 2, 4)
     # many heads and tokens: nothing to gain, and the forward kernel takes 32 rows per wavefront
     c = N.ntp_attn_core_choice(_shape(16, 16, 1, 0, 2, 8192, False))
     assert c == dict(fwd_rows_per_wavefront=32, fwd_parts=1, dq_parts=1, dkv_parts=1)
 
 
 def test_mid_range_is_cut_only_under_the_causal_mask(workspace_1gib):
-    # 14 heads x 2048 tokens: 448 forward workgroups; grouped KV heads leave 64 dK/dV workgroups
+    # 14 heads x 2048 tokens: 448 forward workgroups of 32 tiles each, or 224 of 33 with the causal pairs;
+    # grouped KV heads leave 64 (32) dK/dV workgroups
     causal = N.ntp_attn_core_choice(_shape(96, 8, 7, 0, 1, 2048, True))
     full = N.ntp_attn_core_choice(_shape(96, 8, 7, 0, 1, 2048, False))
     assert (causal["fwd_parts"], causal["dq_parts"]) == (2, 2)
-    assert (full["fwd_parts"], full["dq_parts"]) == (1, 1)
-    assert causal["dkv_parts"] == full["dkv_parts"] == 12
+    assert (full["fwd_parts"], full["dq_parts"]) == (1, 1)  # parts of 16 tiles would not pay for their merge
+    assert (causal["dkv_parts"], full["dkv_parts"]) == (16, 8)
 
 
 def test_short_walks_are_not_cut(workspace_1gib):
