@@ -617,6 +617,16 @@ def ceiling_probes(torch, N):
         out[name] = dict(TFLOPs=r["tflops"] or None, frac_of_bf16_peak=(r["tflops"] / BF16_MFMA_PEAK_TFLOPS) or None,
                          lds_read_GBps_per_cu=r["lds_gbps_per_cu"] or None, mfma_per_turn=r["mfma_per_turn"],
                          lds_reads_per_turn=r["reads_per_turn"], ms=r["ms"])
+    # one wavefront per SIMD doing matrix instructions, one doing a softmax's vector arithmetic, and both together:
+    # how much of the vector work hides behind the matrix pipe (the attention core's ceiling)
+    t = {}
+    for name, which in (("matrix", K.NTP_PROBE_MFMA_1WAVE), ("softmax", K.NTP_PROBE_SOFTMAX_1WAVE), ("both", K.NTP_PROBE_MFMA_AND_SOFTMAX)):
+        N.ntp_probe_rates(which, scratch)
+        t[name] = N.ntp_probe_rates(which, scratch)["ms"]
+    out["matrix_and_softmax_on_one_simd"] = dict(
+        matrix_alone_ms=t["matrix"], softmax_alone_ms=t["softmax"], both_ms=t["both"],
+        softmax_share_hidden=(t["matrix"] + t["softmax"] - t["both"]) / t["softmax"],
+        what="per turn 32 matrix instructions on one wavefront per SIMD and the vector arithmetic of 16 scores per lane on another")
     return out
 
 

@@ -542,6 +542,12 @@ int ntp_calibration_copy(ntp_handle_t* h, void* dst, const void* src, int64_t by
  *   NTP_PROBE_MFMA_LDS_B128     64 matrix instructions + 24 128-bit reads (the mix of a K tile of the
  *                               K-contiguous GEMM kernels, per wavefront)
  *   NTP_PROBE_MFMA_LDS_TR_B64   56 matrix instructions + 44 transposing reads (weight-gradient kernels)
+ * and, for the attention core (does the vector arithmetic of one wavefront's softmax hide behind another wavefront's
+ * matrix instructions on the same SIMD?), with ONE wavefront per SIMD and kind:
+ *   NTP_PROBE_MFMA_1WAVE        wavefronts 0-3: 32 matrix instructions per turn
+ *   NTP_PROBE_SOFTMAX_1WAVE     wavefronts 4-7: per turn the vector work of 16 scores per lane (8 maxima, 16
+ *                               multiply-adds, 16 exponentials, 16 additions), the other four idle
+ *   NTP_PROBE_MFMA_AND_SOFTMAX  both at once: one wavefront of each kind per SIMD
  * scratch: DEVICE, at least compute_units * 2048 bytes, overwritten.  out (HOST): average milliseconds per
  * launch, matrix TFLOP/s of the whole device, LDS read GB/s per compute unit. */
 #define NTP_PROBE_MFMA 0
@@ -549,6 +555,9 @@ int ntp_calibration_copy(ntp_handle_t* h, void* dst, const void* src, int64_t by
 #define NTP_PROBE_LDS_TR_B64 2
 #define NTP_PROBE_MFMA_LDS_B128 3
 #define NTP_PROBE_MFMA_LDS_TR_B64 4
+#define NTP_PROBE_MFMA_1WAVE 5
+#define NTP_PROBE_SOFTMAX_1WAVE 6
+#define NTP_PROBE_MFMA_AND_SOFTMAX 7
 typedef struct ntp_probe_result {
   double ms, tflops, lds_gbps_per_cu;
   int32_t mfma_per_turn, reads_per_turn;

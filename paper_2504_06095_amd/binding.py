@@ -37,6 +37,9 @@ NTP_PROBE_LDS_B128 = 1
 NTP_PROBE_LDS_TR_B64 = 2
 NTP_PROBE_MFMA_LDS_B128 = 3
 NTP_PROBE_MFMA_LDS_TR_B64 = 4
+NTP_PROBE_MFMA_1WAVE = 5
+NTP_PROBE_SOFTMAX_1WAVE = 6
+NTP_PROBE_MFMA_AND_SOFTMAX = 7
 NTP_CALL_MLP_SHARD = 0
 NTP_CALL_ATTN_PROJ_SHARD = 1
 NTP_CALL_ATTN_CORE_SHARD = 2

@@ -77,6 +77,75 @@ __global__ __launch_bounds__(kProbeThreads) void probe_kernel(float* out, int tu
   out[int64_t(blockIdx.x) * kProbeThreads + tid] = sum[0] + sum[1] + sum[2] + sum[3] + extra;
 }
 
+// Wavefronts 0-3 (one per SIMD) run 32 matrix instructions per turn when mode & 1; wavefronts 4-7 (one per SIMD) run,
+// when mode & 2, the vector arithmetic an attention kernel spends on 16 scores per lane: running maximum, scale and
+// subtract, hardware exponential, sum.  With both bits set each SIMD holds one wavefront of each kind; the time
+// against the two alone says how much of the vector work hides behind the matrix instructions.
+__global__ __launch_bounds__(kProbeThreads) void probe_overlap_kernel(float* out, int turns, int mode) {
+  const int tid = threadIdx.x, wave = tid >> 6;
+  float r = 0.f;
+  if (wave < 4) {
+    if (!(mode & 1)) return;
+    f32x4 acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    bf16x8 a, b;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      a[i] = static_cast<__bf16>(0.01f * float((tid * 7 + i) % 13 - 6));
+      b[i] = static_cast<__bf16>(0.02f * float((tid * 5 + i) % 11 - 5));
+    }
+    for (int t = 0; t < turns; ++t) {
+#pragma unroll
+      for (int i = 0; i < 32; ++i) acc[i % 16] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[i % 16], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) r += acc[i][0] + acc[i][3];
+  } else {
+    if (!(mode & 2)) return;
+    float x[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) x[i] = 0.001f * float(tid + i);
+    float m = 0.f, l = 0.f;
+    for (int t = 0; t < turns; ++t) {
+      float mx = m;
+#pragma unroll
+      for (int i = 0; i < 16; i += 2) mx = fmaxf(mx, fmaxf(x[i], x[i + 1]));
+      float s = 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float p = __builtin_amdgcn_exp2f(fmaf(x[i], 0.125f, -mx));
+        s += p;
+        x[i] = fmaf(p, 0.5f, 0.001f * float(i));
+      }
+      l = fmaf(l, 0.5f, s);
+      m = mx * 0.999f;
+    }
+    r = l + m;
+  }
+  out[int64_t(blockIdx.x) * kProbeThreads + tid] = r;
+}
+
+int run_overlap_probe(ntp_handle* h, float* scratch, int mode, int turns, int reps, double* ms_out) {
+  hipEvent_t a, b;
+  if (hipEventCreate(&a) != hipSuccess) return NTP_ERR_LAUNCH;
+  if (hipEventCreate(&b) != hipSuccess) {
+    (void)hipEventDestroy(a);
+    return NTP_ERR_LAUNCH;
+  }
+  const dim3 grid(uint32_t(h->compute_units)), block(kProbeThreads);
+  hipLaunchKernelGGL(probe_overlap_kernel, grid, block, 0, nullptr, scratch, turns / 8, mode);  // warm-up
+  (void)hipEventRecord(a, nullptr);
+  for (int r = 0; r < reps; ++r) hipLaunchKernelGGL(probe_overlap_kernel, grid, block, 0, nullptr, scratch, turns, mode);
+  (void)hipEventRecord(b, nullptr);
+  float ms = 0.f;
+  const bool ok = hipGetLastError() == hipSuccess && hipEventSynchronize(b) == hipSuccess && hipEventElapsedTime(&ms, a, b) == hipSuccess;
+  (void)hipEventDestroy(a);
+  (void)hipEventDestroy(b);
+  *ms_out = double(ms) / reps;
+  return ok ? NTP_OK : NTP_ERR_LAUNCH;
+}
+
 template <int MFMAS, int READS, bool TR>
 int run_probe(ntp_handle* h, float* scratch, int turns, int reps, double* ms_out) {
   hipEvent_t a, b;
@@ -108,6 +177,17 @@ extern "C" int ntp_probe_rates(ntp_handle_t* h, int32_t which, void* scratch, in
   const int turns = 4000, reps = 5;
   int mfmas = 0, reads = 0, read_bytes = 0, st;
   double ms = 0.0;
+  if (which >= NTP_PROBE_MFMA_1WAVE && which <= NTP_PROBE_MFMA_AND_SOFTMAX) {
+    const int mode = which == NTP_PROBE_MFMA_1WAVE ? 1 : which == NTP_PROBE_SOFTMAX_1WAVE ? 2 : 3;
+    st = run_overlap_probe(h, s, mode, 4 * turns, reps, &ms);
+    if (st != NTP_OK) return st;
+    out->ms = ms;
+    out->tflops = mode & 1 ? double(h->compute_units) * 4 * (4.0 * turns) * 32 * 16384.0 / (ms * 1e-3) / 1e12 : 0.0;
+    out->lds_gbps_per_cu = 0.0;
+    out->mfma_per_turn = mode & 1 ? 32 : 0;
+    out->reads_per_turn = 0;
+    return NTP_OK;
+  }
   switch (which) {
     case NTP_PROBE_MFMA: mfmas = 64; st = run_probe<64, 0, false>(h, s, turns, reps, &ms); break;
     case NTP_PROBE_LDS_B128: reads = 24; read_bytes = 1024; st = run_probe<0, 24, false>(h, s, turns, reps, &ms); break;
