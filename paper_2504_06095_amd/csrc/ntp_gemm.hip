@@ -188,15 +188,16 @@ SplitChoice plan_gemm(const ntp_handle* h, int64_t ws_bytes, const GemmArgs& g, 
 // limit the two run within a few percent of each other (with all-zero operands, which draw little switching power,
 // the ping-pong schedule is 6 % faster).  Measured in the GPT-3-shape step: ping-pong +1-4 % where both operands are
 // K-contiguous, -1-8 % where one or both are K-strided (their transposing reads make the memory slots longer), with
-// one exception: the weight-gradient layout on the 224 x 256 and 256 x 224 tiles, +2.5 %, whose ping-pong kernels also
-// need no scratch memory (the default schedule spills 10 and 21 registers there).
+// two exceptions: the weight-gradient layout on the 224 x 256 and 256 x 224 tiles, +2.5 %, whose ping-pong kernels also
+// need no scratch memory (the default schedule spills 10 and 21 registers there), and the row-parallel layout at short
+// K (fc2 / dX of a narrow shard: 8192 x 16384 over K = 750 runs 200-207 us against 215-221 us on the 256 x 256 tile).
 // NTP_OPT_GEMM_SCHEDULE: 1 forces the default schedule, 2 the ping-pong schedule.
-bool use_pingpong(const ntp_handle* h, int layout, int variant) {
+bool use_pingpong(const ntp_handle* h, int layout, int variant, int64_t K) {
   if (variant < 0 || variant > 6) return false;
   const int64_t f = h->opt[NTP_OPT_GEMM_SCHEDULE];
   if (f == 1) return false;
   if (f == 2) return true;
-  return layout == 0 || (layout == 2 && (variant == 1 || variant == 2));
+  return layout == 0 || (layout == 2 && (variant == 1 || variant == 2)) || (layout == 1 && K <= 1024);
 }
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
@@ -319,7 +320,7 @@ int gemm_launch(ntp_handle* h, const GemmDesc& d, void* stream) {
     char name[48], vn[16], sn[8] = "";
     variant_name(variant, vn, sizeof(vn));
     if (sc.splits > 1) snprintf(sn, sizeof(sn), "k%d", sc.splits);
-    const bool pp = sc.splits == 1 && use_pingpong(h, layout, variant) && !(layout == 2 && variant == 0 && ring_ok);
+    const bool pp = sc.splits == 1 && use_pingpong(h, layout, variant, d.K) && !(layout == 2 && variant == 0 && ring_ok);
     snprintf(name, sizeof(name), "gemm_%c%c_%s_%s%s%s", d.a_kc ? 'n' : 't', d.b_kc ? 't' : 'n', kEpiName[d.epilogue], vn, sn,
              pp ? "pp" : "");
     ntp::timing_begin(h, stream, name, 2.0 * double(d.M) * double(d.N) * double(d.K), 0.0);
@@ -355,7 +356,7 @@ int gemm_launch(ntp_handle* h, const GemmDesc& d, void* stream) {
         return hipGetLastError() == hipSuccess ? NTP_OK : NTP_ERR_LAUNCH;
       });
     }
-  } else if (use_pingpong(h, layout, variant)) {
+  } else if (use_pingpong(h, layout, variant, d.K)) {
     if (d.a_kc && d.b_kc) st = launch_pp_nt(g, d.epilogue, variant, s);
     else if (d.a_kc) st = launch_pp_nn(g, d.epilogue, variant, s);
     else st = launch_pp_tn(g, d.epilogue, variant, s);
@@ -395,6 +396,6 @@ extern "C" int ntp_gemm_choice(const ntp_handle_t* h, int32_t layout, int64_t M,
     out->ring = 1;
   }
   out->persistent = sc.tile >= 0 && sc.splits == 1 && !(layout == 2 && sc.tile == 0) ? 1 : 0;
-  out->pingpong = out->persistent && use_pingpong(h, layout, sc.tile) ? 1 : 0;
+  out->pingpong = out->persistent && use_pingpong(h, layout, sc.tile, K) ? 1 : 0;
   return NTP_OK;
 }

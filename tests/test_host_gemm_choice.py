@@ -80,6 +80,7 @@ def test_schedule_choice_and_override():
     c = Bd.ntp_gemm_choice(0, 2048, 7022, 12288, handle=h)
     assert c["persistent"] == 1 and c["pingpong"] == 1
     assert Bd.ntp_gemm_choice(1, 2048, 12288, 7022, handle=h)["pingpong"] == 0
+    assert Bd.ntp_gemm_choice(1, 8192, 16384, 750, handle=h)["pingpong"] == 1  # row-parallel layout at short K
     c = Bd.ntp_gemm_choice(2, 7022, 12288, 2048, handle=h)  # weight gradient on the 224 x 256 tile: ping-pong too
     assert (c["tile_m"], c["tile_n"], c["pingpong"]) == (224, 256, 1)
     c = Bd.ntp_gemm_choice(2, 1792, 12288, 2048, handle=h)  # ... on the 192 x 256 tile: default schedule
