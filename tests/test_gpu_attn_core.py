@@ -164,6 +164,16 @@ def test_attn_core_fwd_cut_walks(workspace, opts, n_q, n_kv, tp, rank, d, n_seq,
     assert _core_names() == ["attn_core_fwd_causal_cut" if causal else "attn_core_fwd_cut"]
 
 
+@pytest.mark.parametrize("parts", [1, 3])
+@pytest.mark.parametrize("n_q,n_kv,tp,rank,d,n_seq,S", [(8, 2, 3, 0, 128, 2, 440), (6, 6, 4, 1, 128, 1, 1100), (4, 4, 2, 0, 64, 3, 1)])
+def test_attn_core_causal_pairs_odd_tile_counts(workspace, opts, n_q, n_kv, tp, rank, d, n_seq, S, parts):
+    """Under the causal mask a workgroup takes a pair of tiles, one from each end of the sequence: 7 and 18 tiles (an odd
+    count leaves the middle tile alone), a single tile, several sequences, whole walks and walks cut in three."""
+    _say(f"attn core causal pairs: n_q={n_q} n_kv={n_kv} d={d} n_seq={n_seq} S={S} parts={parts}")
+    opts(K.NTP_OPT_ATTN_PARTS, parts)
+    _bwd_case(n_q, n_kv, tp, rank, d, n_seq, S, True, seed=11)
+
+
 def test_attn_core_fwd_cut_peaked_scores(workspace, opts):
     """Large scores: the pieces' maxima differ by hundreds, so most pieces merge with weight zero."""
     _say("attn core fwd cut: peaked scores")
