@@ -174,6 +174,14 @@ def test_attn_core_causal_pairs_odd_tile_counts(workspace, opts, n_q, n_kv, tp, 
     _bwd_case(n_q, n_kv, tp, rank, d, n_seq, S, True, seed=11)
 
 
+@pytest.mark.parametrize("causal", [False, True], ids=["full", "causal"])
+def test_attn_core_at_the_step_shape(workspace, causal):
+    """14 heads x 128, one sequence of 2048 tokens (the benchmark step's rank), the launcher's own choices with a
+    workspace registered: forward, log-sum-exp and all three gradients against the oracle."""
+    _say(f"attn core at the step's shape, causal={causal}")
+    _bwd_case(96, 96, 7, 0, 128, 1, 2048, causal, seed=13)
+
+
 def test_attn_core_fwd_cut_peaked_scores(workspace, opts):
     """Large scores: the pieces' maxima differ by hundreds, so most pieces merge with weight zero."""
     _say("attn core fwd cut: peaked scores")

@@ -85,6 +85,15 @@ def test_imbalance_sweep_shapes(launch_config, hidden, rank):
     _check(att.run_gpu(), att.oracle(), ["QKV", "Z", "dC", "dX", "dWqkv", "dWo"])
 
 
+def test_step_attention_projection_shape(launch_config):
+    """The attention projections at the benchmark step's own shape: 2048 tokens, hidden 12288, 96 heads of 128, rank 0
+    of TP 7 (14 heads: w_qkv 5376, w_o 1792), in both launch configurations (with the workspace dC is split along K)."""
+    _say(f"step shape attention projections, {launch_config}")
+    att = AttnCase(2048, 12288, 96, 96, 128, 7, 0, tag="step.attn")
+    assert (att.w_qkv, att.w_o) == (5376, 1792)
+    _check(att.run_gpu(), att.oracle(), ["QKV", "Z", "dC", "dX", "dWqkv", "dWo"])
+
+
 def test_config1_reshard_after_backward():
     """Config 1 end to end: the dA_t / dB that the GPU backward produced for EVERY rank of TP 7 are
     repacked into the TP 8 layout; the result must equal the unsharded gradient cut at TP 8."""
