@@ -20,6 +20,7 @@
 #include <type_traits>
 
 #include "ntp_gemm_kernels.h"
+#include "ntp_gemm_ring.h"
 #include "ntp_internal.h"
 
 namespace {
@@ -368,6 +369,281 @@ attn_core_fwd_kernel(const CoreArgs a) {
         *reinterpret_cast<u16x4*>(cp + db * 16) = o;
       }
       if (lh == 0 && a.LSE) a.LSE[int64_t(head) * (int64_t(a.n_seq) * S) + tok0 + qrow] = (m_run[qb] + log2f(l)) * 0.6931471805599453f;
+    }
+  }
+  }  // the workgroup's passes
+}
+
+// ---- forward kernel with key / value tiles brought to LDS by DMA --------------------------------------------
+// Head dimension 128, 16 query rows per wavefront.  The tiles go global -> LDS by direct buffer loads (1 KiB per
+// instruction, no staging registers, no LDS stores, no vector address arithmetic), two buffers per matrix: the DMA of
+// tile t + 1 flies while tile t is multiplied, one barrier per tile.  A DMA instruction fills 64 consecutive
+// 16-byte chunks, so rows cannot be padded; bank conflicts are avoided by permuting the chunks of each 256-byte row
+// instead: chunk c of row r sits at slot c ^ swz(r), swz(r) = ((r & 7) << 1) | ((r >> 3) & 1).  The 16 lanes of a
+// 128-bit fragment read (same chunk of 16 consecutive rows) then land on 16 distinct slots, and the 8 rows x 32
+// bytes that half a transposing read touches on 8 distinct slot pairs.  LDS reads are inline assembly, all of a
+// product's fragments first and one wait: with DMA in flight the compiler would guard every LDS read it schedules
+// itself with a wait for all of it.
+__device__ __forceinline__ uint32_t row_swz(int r) { return uint32_t(((r & 7) << 1) | ((r >> 3) & 1)); }
+
+typedef uint32_t attn_u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t attn_u32x2 __attribute__((ext_vector_type(2)));
+
+template <int OFF>
+__device__ __forceinline__ attn_u32x4 lds_frag_b128(uint32_t addr) {
+#if !defined(__HIP_DEVICE_COMPILE__)
+  return attn_u32x4{};
+#else
+  attn_u32x4 v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+  return v;
+#endif
+}
+template <int OFF>
+__device__ __forceinline__ attn_u32x2 lds_tr_b64(uint32_t addr) {
+#if !defined(__HIP_DEVICE_COMPILE__)
+  return attn_u32x2{};
+#else
+  attn_u32x2 v;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+  return v;
+#endif
+}
+// The compiler takes an assembly statement's outputs as valid when the statement ends, but an LDS read only
+// requests them.  The wait therefore names the requested registers as operands it rewrites: every use of them
+// then depends on the wait and cannot be scheduled ahead of it.  (Eight registers per statement: the operand
+// limit; the statements after the first emit nothing and only carry the dependence.)
+template <typename V>
+__device__ __forceinline__ void lds_reads_done(V (&r)[8]) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("s_waitcnt lgkmcnt(0)"
+               : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]), "+v"(r[6]), "+v"(r[7])
+               :
+               : "memory");
+#endif
+}
+template <typename V>
+__device__ __forceinline__ void lds_reads_tied(V (&r)[8]) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]), "+v"(r[6]), "+v"(r[7]) : : "memory");
+#endif
+}
+__device__ __forceinline__ void dma_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ void dma_16(__amdgpu_buffer_rsrc_t rs, uint16_t* dst, uint32_t voff, uint32_t soff) {
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (ntp_gemm::lds_void*)dst, 16, voff, soff, 0, 0);
+}
+
+template <bool PAIRED>
+__global__ __attribute__((amdgpu_flat_work_group_size(kThreads, kThreads), amdgpu_waves_per_eu(2, 2))) void
+attn_core_fwd_dma_kernel(const CoreArgs a) {
+  constexpr int D = 128, KS = D / 32, DB = D / 16, kRows = 64;
+  constexpr int TILE = kBKV * D;       // elements of one tile
+  constexpr int NI = TILE * 2 / 1024 / 4;  // DMA instructions per wavefront, matrix and tile
+  __shared__ __attribute__((aligned(1024))) uint16_t sK[2 * TILE];
+  __shared__ __attribute__((aligned(1024))) uint16_t sV[2 * TILE];
+
+  const int piece = a.n_parts > 1 ? int(blockIdx.x % a.n_parts) : 0;
+  const int blk = a.n_parts > 1 ? int(blockIdx.x / a.n_parts) : int(blockIdx.x);
+  const int per_seq = PAIRED ? a.pairs : a.q_tiles;
+  const int u = blk % per_seq;
+  const int sh = blk / per_seq;
+  const int seq = sh % a.n_seq, head = sh / a.n_seq;
+  const int g = (a.q_off + head) / a.group - a.kv_off;
+  const int S = a.seq_len;
+  const int64_t tok0 = int64_t(seq) * S;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lq = lane & 15, lh = lane >> 4;
+  const uint16_t* Qp = a.QKV + int64_t(head) * D;
+  const uint16_t* Kp = a.QKV + int64_t(a.q_cnt + g) * D;
+  const uint16_t* Vp = a.QKV + int64_t(a.q_cnt + a.kv_cnt + g) * D;
+  TileSrc<D> srcK, srcV;
+  srcK.init(Kp + tok0 * a.ld, a.ld, S);
+  srcV.init(Vp + tok0 * a.ld, a.ld, S);
+  // instruction j of this wavefront fills LDS chunks (4 wave + j) 64 + lane of a tile: row = chunk / 16, and the
+  // chunk of that row which belongs in this slot
+  uint32_t voff[NI];
+#pragma unroll
+  for (int j = 0; j < NI; ++j) {
+    const int p = (wave * NI + j) * 64 + lane;
+    const int row = p >> 4, slot = p & 15;
+    voff[j] = uint32_t((int64_t(row) * a.ld + int64_t(uint32_t(slot) ^ row_swz(row)) * 8) * 2);
+  }
+  auto dma_tile = [&](int t, int buf) {  // rows past the sequence end lie outside the buffer views: zeros
+    const uint32_t soff = uint32_t(t) * srcK.step;
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+      dma_16(srcK.rs, sK + buf * TILE + (wave * NI + j) * 512, voff[j], soff);
+      dma_16(srcV.rs, sV + buf * TILE + (wave * NI + j) * 512, voff[j], soff);
+    }
+  };
+  // this lane's read addresses (buffer 0; the other buffer, the 16-row block and the 32-key step are immediates)
+  uint32_t ak[KS], av[DB];
+  {
+    const uint32_t kbase = uint32_t(reinterpret_cast<uintptr_t>(sK)) + uint32_t(lq) * 256u, xk = row_swz(lq);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) ak[ks] = kbase + ((uint32_t(ks * 4 + lh) ^ xk) * 16u);
+    const int rv = lh * 4 + (lq >> 2);
+    const uint32_t vbase = uint32_t(reinterpret_cast<uintptr_t>(sV)) + uint32_t(rv) * 256u + uint32_t(lq & 1) * 8u, xv = row_swz(rv);
+#pragma unroll
+    for (int db = 0; db < DB; ++db) av[db] = vbase + ((uint32_t(db * 2 + ((lq & 3) >> 1)) ^ xv) * 16u);
+  }
+
+  for (int seg = 0; seg < (PAIRED ? 2 : 1); ++seg) {
+  const int qt = PAIRED ? (seg == 0 ? a.q_tiles - 1 - u : u) : (a.causal ? a.q_tiles - 1 - u : u);
+  if (seg == 1) {
+    if (qt == a.q_tiles - 1 - u) break;  // odd tile count: the middle tile has no partner
+    __syncthreads();                     // the first pass's last tile has been read by everyone
+  }
+  const int64_t tblk = int64_t(sh) * a.q_tiles + (a.causal ? a.q_tiles - 1 - qt : qt);
+  const int q0 = qt * kRows + wave * 16;
+
+  bf16x8 qf[KS];
+  {
+    const int qr = min(q0 + lq, S - 1);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(Qp + (tok0 + qr) * a.ld + ks * 32 + lh * 8);
+  }
+  f32x4 acc[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db) acc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m_run = -INFINITY, l_run = 0.f;
+  const int kv_end = a.causal ? min(S, qt * kRows + kRows) : S;
+  const int n_tiles = (kv_end + kBKV - 1) / kBKV;
+  const int t_lo = a.n_parts > 1 ? int(int64_t(piece) * n_tiles / a.n_parts) : 0;
+  const int t_hi = a.n_parts > 1 ? int(int64_t(piece + 1) * n_tiles / a.n_parts) : n_tiles;
+
+  // one key tile out of buffer BUF (a compile-time constant, so that every LDS offset is an immediate)
+  auto tile_step = [&](auto bufc, int t) {
+    constexpr int BUF = decltype(bufc)::value;
+    constexpr int BO = BUF * TILE * 2;  // byte offset of the buffer
+    dma_done();        // this wavefront's share of tile t has landed ...
+    __syncthreads();   // ... and everyone's; everyone has finished reading tile t - 1 in the other buffer
+    if (t + 1 < t_hi) dma_tile(t + 1, BUF ^ 1);
+    const int kv0 = t * kBKV;
+    if (a.causal && kv0 > q0 + 15) return;  // every key of the tile lies after this wavefront's last query row
+    // scores, transposed: st[kb][r] = S[query lane % 16][key kv0 + kb*16 + (lane/16)*4 + r]
+    attn_u32x4 kf[2][8];  // [kb / 2][(kb % 2) * 4 + ks]
+    kf[0][0] = lds_frag_b128<BO + 0 * 4096>(ak[0]); kf[0][1] = lds_frag_b128<BO + 0 * 4096>(ak[1]);
+    kf[0][2] = lds_frag_b128<BO + 0 * 4096>(ak[2]); kf[0][3] = lds_frag_b128<BO + 0 * 4096>(ak[3]);
+    kf[0][4] = lds_frag_b128<BO + 1 * 4096>(ak[0]); kf[0][5] = lds_frag_b128<BO + 1 * 4096>(ak[1]);
+    kf[0][6] = lds_frag_b128<BO + 1 * 4096>(ak[2]); kf[0][7] = lds_frag_b128<BO + 1 * 4096>(ak[3]);
+    kf[1][0] = lds_frag_b128<BO + 2 * 4096>(ak[0]); kf[1][1] = lds_frag_b128<BO + 2 * 4096>(ak[1]);
+    kf[1][2] = lds_frag_b128<BO + 2 * 4096>(ak[2]); kf[1][3] = lds_frag_b128<BO + 2 * 4096>(ak[3]);
+    kf[1][4] = lds_frag_b128<BO + 3 * 4096>(ak[0]); kf[1][5] = lds_frag_b128<BO + 3 * 4096>(ak[1]);
+    kf[1][6] = lds_frag_b128<BO + 3 * 4096>(ak[2]); kf[1][7] = lds_frag_b128<BO + 3 * 4096>(ak[3]);
+    lds_reads_done(kf[0]);
+    lds_reads_tied(kf[1]);
+    f32x4 st[4];
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb) {
+      st[kb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) st[kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[kb >> 1][(kb & 1) * 4 + ks]), qf[ks], st[kb], 0, 0, 0);
+    }
+    // value fragments of the second product: requested now, needed after the softmax
+    attn_u32x2 vf[4][8];  // [db / 2][(db % 2) * 4 + s2 * 2 + half]: keys s2*32 + half*16 .. of the tile
+    vf[0][0] = lds_tr_b64<BO + 0>(av[0]); vf[0][1] = lds_tr_b64<BO + 4096>(av[0]); vf[0][2] = lds_tr_b64<BO + 8192>(av[0]); vf[0][3] = lds_tr_b64<BO + 12288>(av[0]);
+    vf[0][4] = lds_tr_b64<BO + 0>(av[1]); vf[0][5] = lds_tr_b64<BO + 4096>(av[1]); vf[0][6] = lds_tr_b64<BO + 8192>(av[1]); vf[0][7] = lds_tr_b64<BO + 12288>(av[1]);
+    vf[1][0] = lds_tr_b64<BO + 0>(av[2]); vf[1][1] = lds_tr_b64<BO + 4096>(av[2]); vf[1][2] = lds_tr_b64<BO + 8192>(av[2]); vf[1][3] = lds_tr_b64<BO + 12288>(av[2]);
+    vf[1][4] = lds_tr_b64<BO + 0>(av[3]); vf[1][5] = lds_tr_b64<BO + 4096>(av[3]); vf[1][6] = lds_tr_b64<BO + 8192>(av[3]); vf[1][7] = lds_tr_b64<BO + 12288>(av[3]);
+    vf[2][0] = lds_tr_b64<BO + 0>(av[4]); vf[2][1] = lds_tr_b64<BO + 4096>(av[4]); vf[2][2] = lds_tr_b64<BO + 8192>(av[4]); vf[2][3] = lds_tr_b64<BO + 12288>(av[4]);
+    vf[2][4] = lds_tr_b64<BO + 0>(av[5]); vf[2][5] = lds_tr_b64<BO + 4096>(av[5]); vf[2][6] = lds_tr_b64<BO + 8192>(av[5]); vf[2][7] = lds_tr_b64<BO + 12288>(av[5]);
+    vf[3][0] = lds_tr_b64<BO + 0>(av[6]); vf[3][1] = lds_tr_b64<BO + 4096>(av[6]); vf[3][2] = lds_tr_b64<BO + 8192>(av[6]); vf[3][3] = lds_tr_b64<BO + 12288>(av[6]);
+    vf[3][4] = lds_tr_b64<BO + 0>(av[7]); vf[3][5] = lds_tr_b64<BO + 4096>(av[7]); vf[3][6] = lds_tr_b64<BO + 8192>(av[7]); vf[3][7] = lds_tr_b64<BO + 12288>(av[7]);
+
+    const bool edge = kv0 + kBKV > S || (a.causal && kv0 + kBKV - 1 > q0);
+    const int qrow = q0 + lq;
+    if (edge) {
+#pragma unroll
+      for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int key = kv0 + kb * 16 + lh * 4 + r;
+          if (key >= S || (a.causal && key > qrow)) st[kb][r] = -INFINITY;
+        }
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) mx = fmaxf(mx, st[kb][r]);
+    mx = xor_max(mx) * a.scale_log2;
+    const float m_new = fmaxf(m_run, mx);
+    const float m_use = m_new == -INFINITY ? 0.f : m_new;
+    const float alpha = fast_exp2(m_run - m_use);
+    float ls = 0.f;
+    float p[4][4];
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        p[kb][r] = fast_exp2(fmaf(st[kb][r], a.scale_log2, -m_use));
+        ls += p[kb][r];
+      }
+    l_run = l_run * alpha + ls;
+    m_run = m_new;
+    if (__any(alpha != 1.0f)) {
+#pragma unroll
+      for (int db = 0; db < DB; ++db) acc[db] *= alpha;
+    }
+    bf16x8 pf[2];
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) {
+      bf16x8 f;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        f[r] = static_cast<__bf16>(p[2 * s2][r]);
+        f[4 + r] = static_cast<__bf16>(p[2 * s2 + 1][r]);
+      }
+      pf[s2] = f;
+    }
+    lds_reads_done(vf[0]);
+    lds_reads_tied(vf[1]);
+    lds_reads_tied(vf[2]);
+    lds_reads_tied(vf[3]);
+    // O^T += V^T P^T (key slots of a 32-key step in the order the scores sit in the registers: see attn_core_fwd_kernel)
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const attn_u32x2 lo = vf[db >> 1][(db & 1) * 4 + s2 * 2], hi = vf[db >> 1][(db & 1) * 4 + s2 * 2 + 1];
+        const attn_u32x4 both = {lo[0], lo[1], hi[0], hi[1]};
+        acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, both), pf[s2], acc[db], 0, 0, 0);
+      }
+  };
+
+  if (t_lo < t_hi) dma_tile(t_lo, 0);
+  for (int t = t_lo; t < t_hi; t += 2) {
+    tile_step(std::integral_constant<int, 0>{}, t);
+    if (t + 1 < t_hi) tile_step(std::integral_constant<int, 1>{}, t + 1);
+  }
+
+  if (a.n_parts > 1) {
+    float* pp = a.part_sums + ((tblk * a.n_parts + piece) * kRows + wave * 16 + lq) * (D + 4);
+#pragma unroll
+    for (int db = 0; db < DB; ++db) *reinterpret_cast<f32x4*>(pp + db * 16 + lh * 4) = acc[db];
+    const float l = xor_sum(l_run);
+    if (lh == 0) {
+      pp[D] = m_run;
+      pp[D + 1] = l;
+    }
+    continue;
+  }
+  {
+    const int qrow = q0 + lq;
+    const float l = xor_sum(l_run);
+    const float inv = 1.0f / l;
+    if (qrow < S) {
+      uint16_t* cp = a.C + (tok0 + qrow) * a.ldc + int64_t(head) * D + lh * 4;
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        u16x4 o;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) o[r] = ntp_gemm::f32_to_bf16(acc[db][r] * inv);
+        *reinterpret_cast<u16x4*>(cp + db * 16) = o;
+      }
+      if (lh == 0 && a.LSE) a.LSE[int64_t(head) * (int64_t(a.n_seq) * S) + tok0 + qrow] = (m_run + log2f(l)) * 0.6931471805599453f;
     }
   }
   }  // the workgroup's passes
@@ -888,13 +1164,15 @@ __global__ __launch_bounds__(256) void attn_core_part_reduce_kernel(const CoreBw
 // gain only from parts of more than 16 tiles (the merge pass and the per-workgroup prologue cost more than shorter
 // parts gain); a causal walk of 40 tiles or more per part takes one part more.
 int choose_parts(const ntp_handle* h, int64_t ws_bytes, int64_t wgs, int64_t slots, int64_t walk, int64_t bytes_per_part, double fill,
-                 int64_t cap, bool causal) {
+                 int64_t cap, bool causal, int64_t near_full_min = 0) {
   if (ws_bytes <= 0 || wgs <= 0) return 1;
   const int64_t cus = h->compute_units;
   int64_t parts = std::min<int64_t>(cap, std::max<int64_t>(1, int64_t(fill * double(cus) / double(wgs) + 0.5)));
   parts = std::min<int64_t>(parts, std::max<int64_t>(1, walk / 6));
   if (wgs > cus)
     while (parts > 1 && walk / parts <= 16) --parts;
+  else if (wgs * 4 >= cus * 3)  // nearly one workgroup per compute unit already
+    while (parts > 1 && walk / parts <= near_full_min) --parts;
   if (causal && parts < cap && walk / parts >= 40 && wgs * parts < 3 * cus) ++parts;
   // tests reach every cut through this override (1..16 parts at any size)
   if (const int64_t f = h->opt[NTP_OPT_ATTN_PARTS]) parts = std::min<int64_t>(16, std::max<int64_t>(1, f));
@@ -926,7 +1204,11 @@ CoreChoice choose_core(const ntp_handle* h, int64_t ws_bytes, const ntp_attn_cor
   const int64_t wq = per_seq * s->n_seq * s->q_cnt, wk = per_seq * s->n_seq * s->kv_cnt;
   const int64_t bf = int64_t(64) * (s->head_dim + 4) * 4, bdq = int64_t(64) * s->head_dim * 4, bdkv = int64_t(64) * 2 * s->head_dim * 4;
   const double fill = causal ? 2.0 : 3.0;
-  c.fwd_parts = choose_parts(h, ws_bytes, wq, bq, walk, bf, fill, 12, causal);
+  // the forward kernel that copies by DMA spends less per tile, so its merge pass weighs more: with 3/4 of the
+  // compute units busy anyway, parts of 23 tiles or fewer no longer pay (14 heads x 2048 causal: 45 us cut in
+  // two, 42 us whole; 3 heads x 8192 causal, parts of 32 tiles: 97 us against 128 us whole)
+  const bool dma_fwd = s->head_dim == 128 && h->opt[NTP_OPT_ATTN_COPY] != 1;
+  c.fwd_parts = choose_parts(h, ws_bytes, wq, bq, walk, bf, fill, 12, causal, dma_fwd ? 23 : 0);
   if (c.fwd_parts > 1) c.fwd_rows = 16;
   c.dq_parts = choose_parts(h, ws_bytes, wq, bq, walk, bdq, fill, 12, causal);
   // a dK/dV workgroup walks over the query tiles of every query head that reads its KV head
@@ -1027,7 +1309,11 @@ extern "C" int ntp_attn_core_shard_fwd(ntp_handle_t* h, const ntp_attn_core_shap
     if (a.pairs > 0) launch(d, q, std::true_type{});
     else launch(d, q, std::false_type{});
   };
-  if (s->head_dim == 128 && qbw == 2) by_pairing(integral_constant<int, 128>{}, integral_constant<int, 2>{});
+  const bool by_dma = s->head_dim == 128 && qbw == 1 && h->opt[NTP_OPT_ATTN_COPY] != 1;
+  if (by_dma) {
+    if (a.pairs > 0) hipLaunchKernelGGL((attn_core_fwd_dma_kernel<true>), grid, dim3(kThreads), 0, hs, a);
+    else hipLaunchKernelGGL((attn_core_fwd_dma_kernel<false>), grid, dim3(kThreads), 0, hs, a);
+  } else if (s->head_dim == 128 && qbw == 2) by_pairing(integral_constant<int, 128>{}, integral_constant<int, 2>{});
   else if (s->head_dim == 128) by_pairing(integral_constant<int, 128>{}, integral_constant<int, 1>{});
   else if (qbw == 2) by_pairing(integral_constant<int, 64>{}, integral_constant<int, 2>{});
   else by_pairing(integral_constant<int, 64>{}, integral_constant<int, 1>{});

@@ -69,6 +69,9 @@ extern "C" int ntp_set_option(ntp_handle_t* h, int32_t option, int64_t value) {
     case NTP_OPT_GEMM_SCHEDULE:
       if (value < 0 || value > 2) return NTP_ERR_INVALID_ARG;
       break;
+    case NTP_OPT_ATTN_COPY:
+      if (value < 0 || value > 2) return NTP_ERR_INVALID_ARG;
+      break;
     case NTP_OPT_GEMM_WORKGROUPS:
       if (value < 0 || value > 65536) return NTP_ERR_INVALID_ARG;
       break;
