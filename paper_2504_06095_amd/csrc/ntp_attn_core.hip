@@ -905,6 +905,268 @@ attn_core_bwd_dq_kernel(const CoreBwdArgs a) {
   }  // the workgroup's passes
 }
 
+// The dQ kernel with the key / value tiles brought to LDS by DMA (see attn_core_fwd_dma_kernel: the same chunk-permuted
+// rows, two buffers per matrix, one barrier per tile, LDS reads as inline assembly with their waits).  Head
+// dimension 128, 16 query rows per wavefront.
+template <int N, typename V>
+__device__ __forceinline__ void lds_reads_left(V (&r)[8]) {  // at most N later reads may still be in flight
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("s_waitcnt lgkmcnt(%8)"
+               : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]), "+v"(r[6]), "+v"(r[7])
+               : "n"(N)
+               : "memory");
+#endif
+}
+
+template <bool PAIRED>
+__global__ __attribute__((amdgpu_flat_work_group_size(kThreads, kThreads), amdgpu_waves_per_eu(2, 2))) void
+attn_core_bwd_dq_dma_kernel(const CoreBwdArgs a) {
+  constexpr int D = 128, KS = D / 32, DB = D / 16, kRows = 64;
+  constexpr int TILE = kBKV * D;           // elements of one tile
+  constexpr int NI = TILE * 2 / 1024 / 4;  // DMA instructions per wavefront, matrix and tile
+  // key buffers 0 and 1, then value buffers 0 and 1: one base address per lane, the rest are immediates
+  __shared__ __attribute__((aligned(1024))) uint16_t sKV[4 * TILE];
+  const int piece = a.n_parts > 1 ? int(blockIdx.x % a.n_parts) : 0;
+  const int blk = a.n_parts > 1 ? int(blockIdx.x / a.n_parts) : int(blockIdx.x);
+  const int per_seq = PAIRED ? a.pairs : a.tiles;
+  const int u = blk % per_seq;
+  const int sh = blk / per_seq;
+  const int seq = sh % a.n_seq, head = sh / a.n_seq;
+  const int g = (a.q_off + head) / a.group - a.kv_off;
+  const int S = a.seq_len;
+  const int64_t tok0 = int64_t(seq) * S, Mtot = int64_t(a.n_seq) * S;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lq = lane & 15, lh = lane >> 4;
+  const uint16_t* Qp = a.QKV + int64_t(head) * D;
+  const uint16_t* Kp = a.QKV + int64_t(a.q_cnt + g) * D;
+  const uint16_t* Vp = a.QKV + int64_t(a.q_cnt + a.kv_cnt + g) * D;
+  TileSrc<D> srcK, srcV;
+  srcK.init(Kp + tok0 * a.ld, a.ld, S);
+  srcV.init(Vp + tok0 * a.ld, a.ld, S);
+  uint32_t voff[NI];
+#pragma unroll
+  for (int j = 0; j < NI; ++j) {
+    const int p = (wave * NI + j) * 64 + lane;
+    const int row = p >> 4, slot = p & 15;
+    voff[j] = uint32_t((int64_t(row) * a.ld + int64_t(uint32_t(slot) ^ row_swz(row)) * 8) * 2);
+  }
+  auto dma_tile = [&](int t, int buf) {  // rows past the sequence end lie outside the buffer views: zeros
+    const uint32_t soff = uint32_t(t) * srcK.step;
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+      dma_16(srcK.rs, sKV + buf * TILE + (wave * NI + j) * 512, voff[j], soff);
+      dma_16(srcV.rs, sKV + (2 + buf) * TILE + (wave * NI + j) * 512, voff[j], soff);
+    }
+  };
+  uint32_t ak[KS], at[DB];  // addresses of the row-fragment reads and of the transposing reads in key buffer 0
+  {
+    const uint32_t base = uint32_t(reinterpret_cast<uintptr_t>(sKV));
+    const uint32_t xk = row_swz(lq);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) ak[ks] = base + uint32_t(lq) * 256u + ((uint32_t(ks * 4 + lh) ^ xk) * 16u);
+    const int rv = lh * 4 + (lq >> 2);
+    const uint32_t xv = row_swz(rv);
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+      at[db] = base + uint32_t(rv) * 256u + uint32_t(lq & 1) * 8u + ((uint32_t(db * 2 + ((lq & 3) >> 1)) ^ xv) * 16u);
+  }
+
+  for (int seg = 0; seg < (PAIRED ? 2 : 1); ++seg) {
+  const int qt = PAIRED ? (seg == 0 ? a.tiles - 1 - u : u) : (a.causal ? a.tiles - 1 - u : u);
+  if (seg == 1) {
+    if (qt == a.tiles - 1 - u) break;  // odd tile count: the middle tile has no partner
+    __syncthreads();                   // the first pass's last tile has been read by everyone
+  }
+  const int64_t tblk = int64_t(sh) * a.tiles + (a.causal ? a.tiles - 1 - qt : qt);
+  const int q0 = qt * kRows + wave * 16;
+
+  bf16x8 qf[KS], gf[KS];
+  float lse2, delta;
+  {
+    const int qr = min(q0 + lq, S - 1);
+    float part = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      qf[ks] = *reinterpret_cast<const bf16x8*>(Qp + (tok0 + qr) * a.ld + ks * 32 + lh * 8);
+      gf[ks] = *reinterpret_cast<const bf16x8*>(a.dC + (tok0 + qr) * a.lddc + int64_t(head) * D + ks * 32 + lh * 8);
+      const bf16x8 of = *reinterpret_cast<const bf16x8*>(a.C + (tok0 + qr) * a.ldc + int64_t(head) * D + ks * 32 + lh * 8);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) part += float(gf[ks][e]) * float(of[e]);
+    }
+    delta = xor_sum(part);
+    lse2 = a.LSE[int64_t(head) * Mtot + tok0 + qr] * 1.4426950408889634f;
+    if (lh == 0 && piece == 0 && q0 + lq < S) a.Delta[int64_t(head) * Mtot + tok0 + qr] = delta;
+  }
+  f32x4 acc[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db) acc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const int kv_end = a.causal ? min(S, qt * kRows + kRows) : S;
+  const int n_tiles = (kv_end + kBKV - 1) / kBKV;
+  const int t_lo = a.n_parts > 1 ? int(int64_t(piece) * n_tiles / a.n_parts) : 0;
+  const int t_hi = a.n_parts > 1 ? int(int64_t(piece + 1) * n_tiles / a.n_parts) : n_tiles;
+
+  // one key tile out of buffer BUF (a compile-time constant, so that every LDS offset is an immediate)
+  auto tile_step = [&](auto bufc, int t) {
+    constexpr int BUF = decltype(bufc)::value;
+    constexpr int KO = BUF * TILE * 2, VO = (2 + BUF) * TILE * 2;  // byte offsets of the two buffers
+    dma_done();        // this wavefront's share of tile t has landed ...
+    __syncthreads();   // ... and everyone's; everyone has finished reading tile t - 1 in the other buffers
+    if (t + 1 < t_hi) dma_tile(t + 1, BUF ^ 1);
+    const int kv0 = t * kBKV;
+    if (a.causal && kv0 > q0 + 15) return;  // nothing of this tile is visible to the wavefront's rows
+    // S^T and dP^T blocks: [key kb*16 + (lane/16)*4 + r][query lane%16]; key blocks 0-1 first, 2-3 behind them
+    attn_u32x4 k01[8], v01[8], k23[8], v23[8];  // [(kb % 2) * 4 + ks]
+    k01[0] = lds_frag_b128<KO + 0 * 4096>(ak[0]);
+    k01[1] = lds_frag_b128<KO + 0 * 4096>(ak[1]);
+    k01[2] = lds_frag_b128<KO + 0 * 4096>(ak[2]);
+    k01[3] = lds_frag_b128<KO + 0 * 4096>(ak[3]);
+    k01[4] = lds_frag_b128<KO + 1 * 4096>(ak[0]);
+    k01[5] = lds_frag_b128<KO + 1 * 4096>(ak[1]);
+    k01[6] = lds_frag_b128<KO + 1 * 4096>(ak[2]);
+    k01[7] = lds_frag_b128<KO + 1 * 4096>(ak[3]);
+    v01[0] = lds_frag_b128<VO + 0 * 4096>(ak[0]);
+    v01[1] = lds_frag_b128<VO + 0 * 4096>(ak[1]);
+    v01[2] = lds_frag_b128<VO + 0 * 4096>(ak[2]);
+    v01[3] = lds_frag_b128<VO + 0 * 4096>(ak[3]);
+    v01[4] = lds_frag_b128<VO + 1 * 4096>(ak[0]);
+    v01[5] = lds_frag_b128<VO + 1 * 4096>(ak[1]);
+    v01[6] = lds_frag_b128<VO + 1 * 4096>(ak[2]);
+    v01[7] = lds_frag_b128<VO + 1 * 4096>(ak[3]);
+    lds_reads_done(k01);
+    lds_reads_tied(v01);
+    k23[0] = lds_frag_b128<KO + 2 * 4096>(ak[0]);
+    k23[1] = lds_frag_b128<KO + 2 * 4096>(ak[1]);
+    k23[2] = lds_frag_b128<KO + 2 * 4096>(ak[2]);
+    k23[3] = lds_frag_b128<KO + 2 * 4096>(ak[3]);
+    k23[4] = lds_frag_b128<KO + 3 * 4096>(ak[0]);
+    k23[5] = lds_frag_b128<KO + 3 * 4096>(ak[1]);
+    k23[6] = lds_frag_b128<KO + 3 * 4096>(ak[2]);
+    k23[7] = lds_frag_b128<KO + 3 * 4096>(ak[3]);
+    f32x4 st[4], dpt[4];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      st[kb] = f32x4{0.f, 0.f, 0.f, 0.f};
+      dpt[kb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        st[kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k01[kb * 4 + ks]), qf[ks], st[kb], 0, 0, 0);
+        dpt[kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, v01[kb * 4 + ks]), gf[ks], dpt[kb], 0, 0, 0);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    v23[0] = lds_frag_b128<VO + 2 * 4096>(ak[0]);
+    v23[1] = lds_frag_b128<VO + 2 * 4096>(ak[1]);
+    v23[2] = lds_frag_b128<VO + 2 * 4096>(ak[2]);
+    v23[3] = lds_frag_b128<VO + 2 * 4096>(ak[3]);
+    v23[4] = lds_frag_b128<VO + 3 * 4096>(ak[0]);
+    v23[5] = lds_frag_b128<VO + 3 * 4096>(ak[1]);
+    v23[6] = lds_frag_b128<VO + 3 * 4096>(ak[2]);
+    v23[7] = lds_frag_b128<VO + 3 * 4096>(ak[3]);
+    lds_reads_left<8>(k23);
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      st[2 + kb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        st[2 + kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k23[kb * 4 + ks]), qf[ks], st[2 + kb], 0, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    lds_reads_done(v23);
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      dpt[2 + kb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        dpt[2 + kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, v23[kb * 4 + ks]), gf[ks], dpt[2 + kb], 0, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // transposed key fragments of the third product: requested now, needed after the arithmetic on the scores
+    attn_u32x2 kt[4][8];  // [db / 2][(db % 2) * 4 + s2 * 2 + half]: keys s2*32 + half*16 .. of the tile
+    kt[0][0] = lds_tr_b64<KO + 0>(at[0]); kt[0][1] = lds_tr_b64<KO + 4096>(at[0]); kt[0][2] = lds_tr_b64<KO + 8192>(at[0]); kt[0][3] = lds_tr_b64<KO + 12288>(at[0]);
+    kt[0][4] = lds_tr_b64<KO + 0>(at[1]); kt[0][5] = lds_tr_b64<KO + 4096>(at[1]); kt[0][6] = lds_tr_b64<KO + 8192>(at[1]); kt[0][7] = lds_tr_b64<KO + 12288>(at[1]);
+    kt[1][0] = lds_tr_b64<KO + 0>(at[2]); kt[1][1] = lds_tr_b64<KO + 4096>(at[2]); kt[1][2] = lds_tr_b64<KO + 8192>(at[2]); kt[1][3] = lds_tr_b64<KO + 12288>(at[2]);
+    kt[1][4] = lds_tr_b64<KO + 0>(at[3]); kt[1][5] = lds_tr_b64<KO + 4096>(at[3]); kt[1][6] = lds_tr_b64<KO + 8192>(at[3]); kt[1][7] = lds_tr_b64<KO + 12288>(at[3]);
+    kt[2][0] = lds_tr_b64<KO + 0>(at[4]); kt[2][1] = lds_tr_b64<KO + 4096>(at[4]); kt[2][2] = lds_tr_b64<KO + 8192>(at[4]); kt[2][3] = lds_tr_b64<KO + 12288>(at[4]);
+    kt[2][4] = lds_tr_b64<KO + 0>(at[5]); kt[2][5] = lds_tr_b64<KO + 4096>(at[5]); kt[2][6] = lds_tr_b64<KO + 8192>(at[5]); kt[2][7] = lds_tr_b64<KO + 12288>(at[5]);
+    kt[3][0] = lds_tr_b64<KO + 0>(at[6]); kt[3][1] = lds_tr_b64<KO + 4096>(at[6]); kt[3][2] = lds_tr_b64<KO + 8192>(at[6]); kt[3][3] = lds_tr_b64<KO + 12288>(at[6]);
+    kt[3][4] = lds_tr_b64<KO + 0>(at[7]); kt[3][5] = lds_tr_b64<KO + 4096>(at[7]); kt[3][6] = lds_tr_b64<KO + 8192>(at[7]); kt[3][7] = lds_tr_b64<KO + 12288>(at[7]);
+
+    const bool edge = kv0 + kBKV > S || (a.causal && kv0 + kBKV - 1 > q0);
+    const int qrow = q0 + lq;
+    float ds[4][4];
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) ds[kb][r] = fast_exp2(fmaf(st[kb][r], a.scale_log2, -lse2));
+    if (edge) {
+#pragma unroll
+      for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int key = kv0 + kb * 16 + lh * 4 + r;
+          if (key >= S || (a.causal && key > qrow)) ds[kb][r] = 0.f;
+        }
+    }
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) ds[kb][r] *= dpt[kb][r] - delta;
+    bf16x8 dsf[2];
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) {
+      bf16x8 f;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        f[r] = static_cast<__bf16>(ds[2 * s2][r]);
+        f[4 + r] = static_cast<__bf16>(ds[2 * s2 + 1][r]);
+      }
+      dsf[s2] = f;
+    }
+    lds_reads_done(kt[0]);
+    lds_reads_tied(kt[1]);
+    lds_reads_tied(kt[2]);
+    lds_reads_tied(kt[3]);
+    // dQ^T += K^T dS^T
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const attn_u32x2 lo = kt[db >> 1][(db & 1) * 4 + s2 * 2], hi = kt[db >> 1][(db & 1) * 4 + s2 * 2 + 1];
+        const attn_u32x4 both = {lo[0], lo[1], hi[0], hi[1]};
+        acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, both), dsf[s2], acc[db], 0, 0, 0);
+      }
+  };
+
+  if (t_lo < t_hi) dma_tile(t_lo, 0);
+  for (int t = t_lo; t < t_hi; t += 2) {
+    tile_step(std::integral_constant<int, 0>{}, t);
+    if (t + 1 < t_hi) tile_step(std::integral_constant<int, 1>{}, t + 1);
+  }
+
+  if (a.n_parts > 1) {
+    // unscaled fp32 sums of this part: row (wavefront, lane % 16) of the workgroup's 64 rows
+    float* pp = a.part_sums + ((tblk * a.n_parts + piece) * kRows + wave * 16 + lq) * D + lh * 4;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) *reinterpret_cast<f32x4*>(pp + db * 16) = acc[db];
+    continue;
+  }
+  {
+    const int qrow = q0 + lq;
+    if (qrow < S) {
+      uint16_t* op = a.dQKV + (tok0 + qrow) * a.ldd + int64_t(head) * D + lh * 4;
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        u16x4 o;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) o[r] = ntp_gemm::f32_to_bf16(acc[db][r] * a.scale);
+        *reinterpret_cast<u16x4*>(op + db * 16) = o;
+      }
+    }
+  }
+  }  // the workgroup's passes
+}
+
 // dK and dV: a workgroup takes 64 KB keys of one (sequence, KV head), a wavefront 16 KB of them, and walks
 // over the query rows (tiles of 64) of every local query head that reads this KV head.  KB = 2 does twice
 // the matrix work per LDS read but needs 440 registers (one wavefront per SIMD); KB = 1 fits in 256, two
@@ -1185,9 +1447,10 @@ struct CoreChoice {
   int fwd_rows;  // query rows per wavefront of the forward kernel: 16 or 32
   int fwd_parts, dq_parts, dkv_parts;
   int64_t ws_bytes;  // workspace bytes the cut launches use (the largest of the three)
+  bool dq_dma;       // the dQ kernel brings its tiles to LDS by DMA
 };
 CoreChoice choose_core(const ntp_handle* h, int64_t ws_bytes, const ntp_attn_core_shape_t* s) {
-  CoreChoice c{16, 1, 1, 1, 0};
+  CoreChoice c{16, 1, 1, 1, 0, false};
   const bool causal = s->causal != 0;
   const int64_t tiles = (s->seq_len + kBKV - 1) / kBKV;
   // under the causal mask a workgroup takes a pair of tiles, one from each end of the sequence
@@ -1204,13 +1467,18 @@ CoreChoice choose_core(const ntp_handle* h, int64_t ws_bytes, const ntp_attn_cor
   const int64_t wq = per_seq * s->n_seq * s->q_cnt, wk = per_seq * s->n_seq * s->kv_cnt;
   const int64_t bf = int64_t(64) * (s->head_dim + 4) * 4, bdq = int64_t(64) * s->head_dim * 4, bdkv = int64_t(64) * 2 * s->head_dim * 4;
   const double fill = causal ? 2.0 : 3.0;
-  // the forward kernel that copies by DMA spends less per tile, so its merge pass weighs more: with 3/4 of the
-  // compute units busy anyway, parts of 23 tiles or fewer no longer pay (14 heads x 2048 causal: 45 us cut in
-  // two, 42 us whole; 3 heads x 8192 causal, parts of 32 tiles: 97 us against 128 us whole)
-  const bool dma_fwd = s->head_dim == 128 && h->opt[NTP_OPT_ATTN_COPY] != 1;
-  c.fwd_parts = choose_parts(h, ws_bytes, wq, bq, walk, bf, fill, 12, causal, dma_fwd ? 23 : 0);
+  // the kernels that copy by DMA spend less per tile, so the second pass over the parts weighs more: under the
+  // causal mask, with 3/4 of the compute units busy anyway, parts of 23 tiles or fewer no longer pay (14 heads x
+  // 2048: forward 45 us cut in two, 42 us whole, dQ 52 and 48 us; 3 heads x 8192, parts of 32 tiles: forward 97 us
+  // against 128 us whole)
+  const bool dma = s->head_dim == 128 && h->opt[NTP_OPT_ATTN_COPY] != 1;
+  const int64_t near_full_min = dma && causal ? 23 : 0;
+  c.fwd_parts = choose_parts(h, ws_bytes, wq, bq, walk, bf, fill, 12, causal, near_full_min);
   if (c.fwd_parts > 1) c.fwd_rows = 16;
-  c.dq_parts = choose_parts(h, ws_bytes, wq, bq, walk, bdq, fill, 12, causal);
+  c.dq_parts = choose_parts(h, ws_bytes, wq, bq, walk, bdq, fill, 12, causal, near_full_min);
+  // the dQ kernel by DMA holds 64 KB of LDS (two workgroups per compute unit, the other form three): with the many
+  // short workgroups of walks cut in 3 or more the other form measured 3-6 % faster, up to 2 parts this one 2-9 %
+  c.dq_dma = dma && (c.dq_parts <= 2 || h->opt[NTP_OPT_ATTN_COPY] == 2);
   // a dK/dV workgroup walks over the query tiles of every query head that reads its KV head
   const int64_t heads_per_kv = std::min<int64_t>(s->group, s->q_cnt);
   c.dkv_parts = choose_parts(h, ws_bytes, wk, bk, heads_per_kv * walk, bdkv, 2.0, 16, false);
@@ -1388,7 +1656,10 @@ extern "C" int ntp_attn_core_shard_bwd(ntp_handle_t* h, const ntp_attn_core_shap
     a.pairs = s->causal ? (a.tiles + 1) / 2 : 0;
     if (ntp::timing_on(h)) ntp::timing_begin(h, stream, a.n_parts > 1 ? "attn_core_bwd_dq_cut" : "attn_core_bwd_dq", 3.0 * pair_flops, 0.0);
     const dim3 grid(uint32_t(int64_t(a.pairs > 0 ? a.pairs : a.tiles) * s->n_seq * s->q_cnt * a.n_parts));
-    if (s->head_dim == 128 && a.pairs > 0)
+    if (cc.dq_dma) {
+      if (a.pairs > 0) hipLaunchKernelGGL((attn_core_bwd_dq_dma_kernel<true>), grid, dim3(kThreads), 0, hs, a);
+      else hipLaunchKernelGGL((attn_core_bwd_dq_dma_kernel<false>), grid, dim3(kThreads), 0, hs, a);
+    } else if (s->head_dim == 128 && a.pairs > 0)
       hipLaunchKernelGGL((attn_core_bwd_dq_kernel<128, qbw, true>), grid, dim3(kThreads), 0, hs, a);
     else if (s->head_dim == 128)
       hipLaunchKernelGGL((attn_core_bwd_dq_kernel<128, qbw, false>), grid, dim3(kThreads), 0, hs, a);

@@ -180,13 +180,26 @@ def test_attn_core_causal_pairs_odd_tile_counts(workspace, opts, n_q, n_kv, tp, 
 @pytest.mark.parametrize("n_q,n_kv,tp,rank,d,n_seq,S,pad", [(8, 2, 3, 0, 128, 2, 200, 0), (6, 6, 4, 1, 128, 1, 1100, 8),
                                                           (64, 8, 30, 3, 128, 2, 449, 0)])
 def test_attn_core_fwd_both_copy_forms(workspace, opts, n_q, n_kv, tp, rank, d, n_seq, S, pad, causal, parts, copy):
-    """The forward kernel brings key / value tiles to LDS through registers or by DMA (the default at head dimension
+    """The kernels bring key / value tiles to LDS through registers or by DMA (the default at head dimension
     128 with 16 query rows per wavefront): both forms on ragged lengths, odd and even tile counts, grouped KV
     heads, rows with padding between them, whole and cut walks."""
     _say(f"attn core fwd copy form {copy}: n_q={n_q} n_kv={n_kv} d={d} n_seq={n_seq} S={S} pad={pad} causal={causal} parts={parts}")
     opts(K.NTP_OPT_ATTN_PARTS, parts)
     opts(K.NTP_OPT_ATTN_COPY, copy)
     _case(n_q, n_kv, tp, rank, d, n_seq, S, causal, seed=17, pad=pad)
+
+
+@pytest.mark.parametrize("copy", [1, 2], ids=["registers", "dma"])
+@pytest.mark.parametrize("parts", [1, 3])
+@pytest.mark.parametrize("causal", [False, True], ids=["full", "causal"])
+@pytest.mark.parametrize("n_q,n_kv,tp,rank,d,n_seq,S,pad", [(8, 2, 3, 0, 128, 2, 200, 0), (6, 6, 4, 1, 128, 1, 1100, 8),
+                                                          (64, 8, 30, 3, 128, 2, 449, 0)])
+def test_attn_core_bwd_both_copy_forms(workspace, opts, n_q, n_kv, tp, rank, d, n_seq, S, pad, causal, parts, copy):
+    """The same two copy forms in the backward kernels, all three gradients against the oracle."""
+    _say(f"attn core bwd copy form {copy}: n_q={n_q} n_kv={n_kv} d={d} n_seq={n_seq} S={S} pad={pad} causal={causal} parts={parts}")
+    opts(K.NTP_OPT_ATTN_PARTS, parts)
+    opts(K.NTP_OPT_ATTN_COPY, copy)
+    _bwd_case(n_q, n_kv, tp, rank, d, n_seq, S, causal, seed=19, pad=pad)
 
 
 @pytest.mark.parametrize("causal", [False, True], ids=["full", "causal"])
