@@ -106,10 +106,9 @@ int ntp_device_info(const ntp_handle_t* h, int32_t* device, int32_t* compute_uni
 #define NTP_OPT_GEMM_WORKGROUPS 10   /* persistent GEMM launches use at most this many workgroups (rounded down to a
                                         multiple of 8, at least 8; 0: one per compute unit).  Fewer workgroups make
                                         each walk over more output tiles: tests and tuning                            */
-#define NTP_OPT_ATTN_COPY 11         /* how the forward and dQ attention kernels bring key / value tiles to LDS
-                                        where both forms exist (head dimension 128; forward: 16 query rows per
-                                        wavefront): 1 through registers, 2 by DMA into chunk-permuted rows; 0: the
-                                        library's choice                                                              */
+#define NTP_OPT_ATTN_COPY 11         /* how the attention kernels bring their 64-row tiles to LDS where both forms
+                                        exist (head dimension 128; forward: 16 query rows per wavefront): 1 through
+                                        registers, 2 by DMA into chunk-permuted rows; 0: the library's choice          */
 #define NTP_OPT_COUNT_ 12
 int ntp_set_option(ntp_handle_t* h, int32_t option, int64_t value);
 

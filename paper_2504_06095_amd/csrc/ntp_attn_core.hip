@@ -379,12 +379,18 @@ attn_core_fwd_kernel(const CoreArgs a) {
 // instruction, no staging registers, no LDS stores, no vector address arithmetic), two buffers per matrix: the DMA of
 // tile t + 1 flies while tile t is multiplied, one barrier per tile.  A DMA instruction fills 64 consecutive
 // 16-byte chunks, so rows cannot be padded; bank conflicts are avoided by permuting the chunks of each 256-byte row
-// instead: chunk c of row r sits at slot c ^ swz(r), swz(r) = ((r & 7) << 1) | ((r >> 3) & 1).  The 16 lanes of a
-// 128-bit fragment read (same chunk of 16 consecutive rows) then land on 16 distinct slots, and the 8 rows x 32
-// bytes that half a transposing read touches on 8 distinct slot pairs.  LDS reads are inline assembly, all of a
-// product's fragments first and one wait: with DMA in flight the compiler would guard every LDS read it schedules
-// itself with a wait for all of it.
-__device__ __forceinline__ uint32_t row_swz(int r) { return uint32_t(((r & 7) << 1) | ((r >> 3) & 1)); }
+// instead: chunk c of row r sits at slot c ^ swz(r), swz(r) = (r & 7) << 1.  A 128-bit LDS read serves 16 lanes per
+// cycle, and not 16 consecutive ones: lanes of one half of the wavefront whose bits 2, 3 and 4 have the same parity
+// (0-3, 12-15, 20-23, 24-27 come first; measured with reads that collide only for one pair of lane bits at a time).
+// In the fragment reads lane bits 0-3 are the row and bits 4-5 the chunk's low bits, so such a group holds rows
+// r0 .. r0 + 3 of four row quadruples with chunk bit 0 = parity of the quadruple's number: slot bits 1-3 (row bits
+// 0-2) and slot bit 0 (chunk bit 0, which tells rows r and r + 8 apart) are all distinct, no bank conflicts.  (With
+// row bit 3 folded into the permutation as well, rows r and r + 8 of a group met in one slot: 2-way conflicts,
+// SQ_LDS_BANK_CONFLICT 0.33-0.40 of the LDS cycles.)  A transposing 64-bit read serves half a wavefront per cycle: 8
+// rows x 32 bytes, which land on 8 distinct slot pairs.  LDS reads are inline assembly, all of a product's
+// fragments first and one wait: with DMA in flight the compiler would guard every LDS read it schedules itself with a
+// wait for all of it.
+__device__ __forceinline__ uint32_t row_swz(int r) { return uint32_t((r & 7) << 1); }
 
 typedef uint32_t attn_u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t attn_u32x2 __attribute__((ext_vector_type(2)));
@@ -1391,6 +1397,402 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dkv_kernel(const Co
   }  // the workgroup's passes
 }
 
+// The dK / dV kernel with the query and output-gradient tiles brought to LDS by DMA (the layout and the read
+// discipline of attn_core_fwd_dma_kernel; head dimension 128, 16 keys per wavefront).  The walk over (query head, query
+// tile) units is one stream through the two buffers; the rows' log-sum-exp and delta values go through registers
+// into a small LDS array of their own, stored before the tile's barrier.
+template <bool PAIRED>
+__global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dkv_dma_kernel(const CoreBwdArgs a) {
+  constexpr int D = 128, KS = D / 32, DB = D / 16;
+  constexpr int TILE = kBKV * D;           // elements of one tile
+  constexpr int NI = TILE * 2 / 1024 / 4;  // DMA instructions per wavefront, matrix and tile
+  // query buffers 0 and 1, then output-gradient buffers 0 and 1
+  __shared__ __attribute__((aligned(1024))) uint16_t sQG[4 * TILE];
+  __shared__ __attribute__((aligned(16))) float sLD[2 * 2 * kBKV];  // [buffer][log-sum-exp, delta][row]
+  const int part = a.n_parts > 1 ? int(blockIdx.x % a.n_parts) : 0;
+  const int blk = a.n_parts > 1 ? int(blockIdx.x / a.n_parts) : int(blockIdx.x);
+  const int per_seq = PAIRED ? a.pairs : a.tiles;
+  const int u = blk % per_seq;
+  const int sh = blk / per_seq;
+  const int seq = sh % a.n_seq, g = sh / a.n_seq;  // g: local KV head
+  const int S = a.seq_len;
+  const int64_t tok0 = int64_t(seq) * S, Mtot = int64_t(a.n_seq) * S;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lq = lane & 15, lh = lane >> 4;
+  const uint16_t* Kp = a.QKV + int64_t(a.q_cnt + g) * D;
+  const uint16_t* Vp = a.QKV + int64_t(a.q_cnt + a.kv_cnt + g) * D;
+  uint32_t voffq[NI], voffg[NI];
+#pragma unroll
+  for (int j = 0; j < NI; ++j) {
+    const int p = (wave * NI + j) * 64 + lane;
+    const int row = p >> 4, slot = p & 15;
+    const int64_t c8 = int64_t(uint32_t(slot) ^ row_swz(row)) * 8;
+    voffq[j] = uint32_t((int64_t(row) * a.ld + c8) * 2);
+    voffg[j] = uint32_t((int64_t(row) * a.lddc + c8) * 2);
+  }
+  uint32_t ak[KS], at[DB], al;  // read addresses in query buffer 0 and in the first log-sum-exp row
+  {
+    const uint32_t base = uint32_t(reinterpret_cast<uintptr_t>(sQG));
+    const uint32_t xk = row_swz(lq);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) ak[ks] = base + uint32_t(lq) * 256u + ((uint32_t(ks * 4 + lh) ^ xk) * 16u);
+    const int rv = lh * 4 + (lq >> 2);
+    const uint32_t xv = row_swz(rv);
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+      at[db] = base + uint32_t(rv) * 256u + uint32_t(lq & 1) * 8u + ((uint32_t(db * 2 + ((lq & 3) >> 1)) ^ xv) * 16u);
+    al = uint32_t(reinterpret_cast<uintptr_t>(sLD)) + uint32_t(lh) * 16u;
+  }
+  // the local query heads that read this KV head are consecutive
+  int head_first = 0, heads_here = 0;
+  for (int head = a.q_cnt - 1; head >= 0; --head)
+    if ((a.q_off + head) / a.group - a.kv_off == g) {
+      head_first = head;
+      ++heads_here;
+    }
+
+  for (int seg = 0; seg < (PAIRED ? 2 : 1); ++seg) {
+  const int kt = PAIRED && seg == 1 ? a.tiles - 1 - u : u;
+  if (seg == 1) {
+    if (kt == u) break;  // odd tile count: the middle tile has no partner
+    __syncthreads();     // the first pass's last tile has been read by everyone
+  }
+  const int64_t tblk = int64_t(sh) * a.tiles + kt;
+  const int k0 = kt * 64 + wave * 16;  // first key of this wavefront
+
+  bf16x8 kf[KS], vf[KS];  // key and value fragments (operand B: j = key)
+  {
+    const int kr = min(k0 + lq, S - 1);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      kf[ks] = *reinterpret_cast<const bf16x8*>(Kp + (tok0 + kr) * a.ld + ks * 32 + lh * 8);
+      vf[ks] = *reinterpret_cast<const bf16x8*>(Vp + (tok0 + kr) * a.ld + ks * 32 + lh * 8);
+    }
+  }
+  f32x4 dk[DB], dv[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db) {
+    dk[db] = f32x4{0.f, 0.f, 0.f, 0.f};
+    dv[db] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  // query tiles this workgroup needs: all, or from the tile that holds its first key on; the walk is the list of
+  // (query head, query tile) units, head-major, and part p of n_parts takes an even, contiguous share of it
+  const int q_first = a.causal ? (kt * 64) / kBKV : 0;
+  const int q_tiles = (S + kBKV - 1) / kBKV;
+  const int nt = max(q_tiles - q_first, 0);
+  const int units = heads_here * nt;
+  const int u_lo = a.n_parts > 1 ? int(int64_t(part) * units / a.n_parts) : 0;
+  const int u_hi = a.n_parts > 1 ? int(int64_t(part + 1) * units / a.n_parts) : units;
+
+  float rl = 0.f, rd = 0.f;
+  // unit w: DMA of its two tiles into buffer `buf`, and this thread's log-sum-exp / delta value of it into registers
+  auto fetch_unit = [&](int head, int t, int buf) {
+    TileSrc<D> srcQ, srcG;  // rows past the sequence end lie outside the views: zeros
+    srcQ.init(a.QKV + int64_t(head) * D + tok0 * a.ld, a.ld, S);
+    srcG.init(a.dC + int64_t(head) * D + tok0 * a.lddc, a.lddc, S);
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+      dma_16(srcQ.rs, sQG + buf * TILE + (wave * NI + j) * 512, voffq[j], uint32_t(t) * srcQ.step);
+      dma_16(srcG.rs, sQG + (2 + buf) * TILE + (wave * NI + j) * 512, voffg[j], uint32_t(t) * srcG.step);
+    }
+    if (threadIdx.x < kBKV) {  // (buffer loads as well: scalar base, rows past the sequence end read as zeros)
+      const __amdgpu_buffer_rsrc_t rsL = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.LSE + int64_t(head) * Mtot + tok0), 0, S * 4, 0x00020000);
+      const __amdgpu_buffer_rsrc_t rsD = __builtin_amdgcn_make_buffer_rsrc(a.Delta + int64_t(head) * Mtot + tok0, 0, S * 4, 0x00020000);
+      // (used, and scaled, only when the next step stores it: arithmetic here would wait for the DMA issued above)
+      rl = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsL, threadIdx.x * 4u, uint32_t(t) * (kBKV * 4), 0));
+      rd = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsD, threadIdx.x * 4u, uint32_t(t) * (kBKV * 4), 0));
+    }
+  };
+
+  // one unit out of buffer BUF (a compile-time constant, so that every LDS offset is an immediate)
+  auto tile_step = [&](auto bufc, int t, bool more, int head_next, int t_next) {
+    constexpr int BUF = decltype(bufc)::value;
+    constexpr int QO = BUF * TILE * 2, GO = (2 + BUF) * TILE * 2, LO = BUF * 2 * kBKV * 4;  // byte offsets
+    dma_done();  // this wavefront's share of the unit has landed (and rl, rd have arrived) ...
+    if (threadIdx.x < kBKV) {
+      sLD[BUF * 2 * kBKV + threadIdx.x] = rl * 1.4426950408889634f;
+      sLD[BUF * 2 * kBKV + kBKV + threadIdx.x] = rd;
+    }
+    __syncthreads();  // ... and everyone's; everyone has finished reading the unit before in the other buffers
+    if (more) fetch_unit(head_next, t_next, BUF ^ 1);
+    const int qbase = t * kBKV;
+    if (a.causal && qbase + kBKV - 1 < k0) return;  // every query row of the tile comes before this wavefront's keys
+    // S and dP blocks: [query qb*16 + (lane/16)*4 + r][key lane%16]; query blocks 0-1 first, 2-3 behind them
+    attn_u32x4 q01[8], g01[8], q23[8], g23[8];  // [(qb % 2) * 4 + ks]
+    q01[0] = lds_frag_b128<QO + 0 * 4096>(ak[0]);
+    q01[1] = lds_frag_b128<QO + 0 * 4096>(ak[1]);
+    q01[2] = lds_frag_b128<QO + 0 * 4096>(ak[2]);
+    q01[3] = lds_frag_b128<QO + 0 * 4096>(ak[3]);
+    q01[4] = lds_frag_b128<QO + 1 * 4096>(ak[0]);
+    q01[5] = lds_frag_b128<QO + 1 * 4096>(ak[1]);
+    q01[6] = lds_frag_b128<QO + 1 * 4096>(ak[2]);
+    q01[7] = lds_frag_b128<QO + 1 * 4096>(ak[3]);
+    g01[0] = lds_frag_b128<GO + 0 * 4096>(ak[0]);
+    g01[1] = lds_frag_b128<GO + 0 * 4096>(ak[1]);
+    g01[2] = lds_frag_b128<GO + 0 * 4096>(ak[2]);
+    g01[3] = lds_frag_b128<GO + 0 * 4096>(ak[3]);
+    g01[4] = lds_frag_b128<GO + 1 * 4096>(ak[0]);
+    g01[5] = lds_frag_b128<GO + 1 * 4096>(ak[1]);
+    g01[6] = lds_frag_b128<GO + 1 * 4096>(ak[2]);
+    g01[7] = lds_frag_b128<GO + 1 * 4096>(ak[3]);
+    lds_reads_done(q01);
+    lds_reads_tied(g01);
+    q23[0] = lds_frag_b128<QO + 2 * 4096>(ak[0]);
+    q23[1] = lds_frag_b128<QO + 2 * 4096>(ak[1]);
+    q23[2] = lds_frag_b128<QO + 2 * 4096>(ak[2]);
+    q23[3] = lds_frag_b128<QO + 2 * 4096>(ak[3]);
+    q23[4] = lds_frag_b128<QO + 3 * 4096>(ak[0]);
+    q23[5] = lds_frag_b128<QO + 3 * 4096>(ak[1]);
+    q23[6] = lds_frag_b128<QO + 3 * 4096>(ak[2]);
+    q23[7] = lds_frag_b128<QO + 3 * 4096>(ak[3]);
+    f32x4 sc[4], dp[4];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      sc[qb] = f32x4{0.f, 0.f, 0.f, 0.f};
+      dp[qb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        sc[qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, q01[qb * 4 + ks]), kf[ks], sc[qb], 0, 0, 0);
+        dp[qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, g01[qb * 4 + ks]), vf[ks], dp[qb], 0, 0, 0);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    g23[0] = lds_frag_b128<GO + 2 * 4096>(ak[0]);
+    g23[1] = lds_frag_b128<GO + 2 * 4096>(ak[1]);
+    g23[2] = lds_frag_b128<GO + 2 * 4096>(ak[2]);
+    g23[3] = lds_frag_b128<GO + 2 * 4096>(ak[3]);
+    g23[4] = lds_frag_b128<GO + 3 * 4096>(ak[0]);
+    g23[5] = lds_frag_b128<GO + 3 * 4096>(ak[1]);
+    g23[6] = lds_frag_b128<GO + 3 * 4096>(ak[2]);
+    g23[7] = lds_frag_b128<GO + 3 * 4096>(ak[3]);
+    lds_reads_left<8>(q23);
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      sc[2 + qb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        sc[2 + qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, q23[qb * 4 + ks]), kf[ks], sc[2 + qb], 0, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // the rows' log-sum-exp and delta values ([0..3]: log-sum-exp of query block qb, [4..7]: delta), then the
+    // transposed output-gradient fragments of the dV product: needed after the arithmetic on the scores
+    attn_u32x4 ld8[8];
+    ld8[0] = lds_frag_b128<LO + 0>(al);
+    ld8[1] = lds_frag_b128<LO + 64>(al);
+    ld8[2] = lds_frag_b128<LO + 128>(al);
+    ld8[3] = lds_frag_b128<LO + 192>(al);
+    ld8[4] = lds_frag_b128<LO + 256>(al);
+    ld8[5] = lds_frag_b128<LO + 320>(al);
+    ld8[6] = lds_frag_b128<LO + 384>(al);
+    ld8[7] = lds_frag_b128<LO + 448>(al);
+    lds_reads_left<8>(g23);
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      dp[2 + qb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        dp[2 + qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, g23[qb * 4 + ks]), vf[ks], dp[2 + qb], 0, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    lds_reads_done(ld8);
+    // transposed fragments of the last two products, 8 reads (one pair of 16-column blocks) per group: two groups of
+    // the output gradient are requested now and land under the arithmetic on the scores
+    attn_u32x2 gt[4][8], qt[4][8];  // [db / 2][(db % 2) * 4 + s2 * 2 + half]: query rows s2*32 + half*16 .. of the tile
+    gt[0][0] = lds_tr_b64<GO + 0>(at[0]); gt[0][1] = lds_tr_b64<GO + 4096>(at[0]); gt[0][2] = lds_tr_b64<GO + 8192>(at[0]); gt[0][3] = lds_tr_b64<GO + 12288>(at[0]);
+    gt[0][4] = lds_tr_b64<GO + 0>(at[1]); gt[0][5] = lds_tr_b64<GO + 4096>(at[1]); gt[0][6] = lds_tr_b64<GO + 8192>(at[1]); gt[0][7] = lds_tr_b64<GO + 12288>(at[1]);
+    gt[1][0] = lds_tr_b64<GO + 0>(at[2]); gt[1][1] = lds_tr_b64<GO + 4096>(at[2]); gt[1][2] = lds_tr_b64<GO + 8192>(at[2]); gt[1][3] = lds_tr_b64<GO + 12288>(at[2]);
+    gt[1][4] = lds_tr_b64<GO + 0>(at[3]); gt[1][5] = lds_tr_b64<GO + 4096>(at[3]); gt[1][6] = lds_tr_b64<GO + 8192>(at[3]); gt[1][7] = lds_tr_b64<GO + 12288>(at[3]);
+
+    // the mask is needed only where the tile reaches past the sequence end, or (causal) where some query
+    // row of the tile comes before the wavefront's last key
+    const bool edge = qbase + kBKV > S || k0 + 16 > S || (a.causal && qbase < k0 + 15);
+    const int key = k0 + lq;
+    float p[4][4], ds[4][4];
+#pragma unroll
+    for (int qb = 0; qb < 4; ++qb) {
+      const f32x4 l4 = __builtin_bit_cast(f32x4, ld8[qb]);
+      const f32x4 d4 = __builtin_bit_cast(f32x4, ld8[4 + qb]);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        p[qb][r] = fast_exp2(fmaf(sc[qb][r], a.scale_log2, -l4[r]));
+        ds[qb][r] = dp[qb][r] - d4[r];
+      }
+    }
+    if (edge) {
+#pragma unroll
+      for (int qb = 0; qb < 4; ++qb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int qrow = qbase + qb * 16 + lh * 4 + r;
+          if (qrow >= S || key >= S || (a.causal && key > qrow)) p[qb][r] = 0.f;
+        }
+    }
+#pragma unroll
+    for (int qb = 0; qb < 4; ++qb)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) ds[qb][r] *= p[qb][r];
+    bf16x8 pf[2], dsf[2];
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) {
+      bf16x8 f, h;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        f[r] = static_cast<__bf16>(p[2 * s2][r]);
+        f[4 + r] = static_cast<__bf16>(p[2 * s2 + 1][r]);
+        h[r] = static_cast<__bf16>(ds[2 * s2][r]);
+        h[4 + r] = static_cast<__bf16>(ds[2 * s2 + 1][r]);
+      }
+      pf[s2] = f;
+      dsf[s2] = h;
+    }
+    // dV^T += dC^T P, dK^T += Q^T dS (query slots in the order the scores sit in the registers); every group of
+    // reads lands under the matrix instructions of the groups before it
+    lds_reads_done(gt[0]);
+    lds_reads_tied(gt[1]);
+    __builtin_amdgcn_sched_barrier(0);
+    gt[2][0] = lds_tr_b64<GO + 0>(at[4]); gt[2][1] = lds_tr_b64<GO + 4096>(at[4]); gt[2][2] = lds_tr_b64<GO + 8192>(at[4]); gt[2][3] = lds_tr_b64<GO + 12288>(at[4]);
+    gt[2][4] = lds_tr_b64<GO + 0>(at[5]); gt[2][5] = lds_tr_b64<GO + 4096>(at[5]); gt[2][6] = lds_tr_b64<GO + 8192>(at[5]); gt[2][7] = lds_tr_b64<GO + 12288>(at[5]);
+    gt[3][0] = lds_tr_b64<GO + 0>(at[6]); gt[3][1] = lds_tr_b64<GO + 4096>(at[6]); gt[3][2] = lds_tr_b64<GO + 8192>(at[6]); gt[3][3] = lds_tr_b64<GO + 12288>(at[6]);
+    gt[3][4] = lds_tr_b64<GO + 0>(at[7]); gt[3][5] = lds_tr_b64<GO + 4096>(at[7]); gt[3][6] = lds_tr_b64<GO + 8192>(at[7]); gt[3][7] = lds_tr_b64<GO + 12288>(at[7]);
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const attn_u32x2 lo = gt[0][(db & 1) * 4 + s2 * 2], hi = gt[0][(db & 1) * 4 + s2 * 2 + 1];
+        const attn_u32x4 both = {lo[0], lo[1], hi[0], hi[1]};
+        dv[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, both), pf[s2], dv[db], 0, 0, 0);
+      }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int db = 2; db < 4; ++db)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const attn_u32x2 lo = gt[1][(db & 1) * 4 + s2 * 2], hi = gt[1][(db & 1) * 4 + s2 * 2 + 1];
+        const attn_u32x4 both = {lo[0], lo[1], hi[0], hi[1]};
+        dv[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, both), pf[s2], dv[db], 0, 0, 0);
+      }
+    __builtin_amdgcn_sched_barrier(0);
+    qt[0][0] = lds_tr_b64<QO + 0>(at[0]); qt[0][1] = lds_tr_b64<QO + 4096>(at[0]); qt[0][2] = lds_tr_b64<QO + 8192>(at[0]); qt[0][3] = lds_tr_b64<QO + 12288>(at[0]);
+    qt[0][4] = lds_tr_b64<QO + 0>(at[1]); qt[0][5] = lds_tr_b64<QO + 4096>(at[1]); qt[0][6] = lds_tr_b64<QO + 8192>(at[1]); qt[0][7] = lds_tr_b64<QO + 12288>(at[1]);
+    lds_reads_left<8>(gt[2]);
+    lds_reads_tied(gt[3]);
+#pragma unroll
+    for (int db = 4; db < 6; ++db)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const attn_u32x2 lo = gt[2][(db & 1) * 4 + s2 * 2], hi = gt[2][(db & 1) * 4 + s2 * 2 + 1];
+        const attn_u32x4 both = {lo[0], lo[1], hi[0], hi[1]};
+        dv[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, both), pf[s2], dv[db], 0, 0, 0);
+      }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int db = 6; db < 8; ++db)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const attn_u32x2 lo = gt[3][(db & 1) * 4 + s2 * 2], hi = gt[3][(db & 1) * 4 + s2 * 2 + 1];
+        const attn_u32x4 both = {lo[0], lo[1], hi[0], hi[1]};
+        dv[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, both), pf[s2], dv[db], 0, 0, 0);
+      }
+    __builtin_amdgcn_sched_barrier(0);
+    qt[1][0] = lds_tr_b64<QO + 0>(at[2]); qt[1][1] = lds_tr_b64<QO + 4096>(at[2]); qt[1][2] = lds_tr_b64<QO + 8192>(at[2]); qt[1][3] = lds_tr_b64<QO + 12288>(at[2]);
+    qt[1][4] = lds_tr_b64<QO + 0>(at[3]); qt[1][5] = lds_tr_b64<QO + 4096>(at[3]); qt[1][6] = lds_tr_b64<QO + 8192>(at[3]); qt[1][7] = lds_tr_b64<QO + 12288>(at[3]);
+    lds_reads_left<8>(qt[0]);
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const attn_u32x2 lo = qt[0][(db & 1) * 4 + s2 * 2], hi = qt[0][(db & 1) * 4 + s2 * 2 + 1];
+        const attn_u32x4 both = {lo[0], lo[1], hi[0], hi[1]};
+        dk[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, both), dsf[s2], dk[db], 0, 0, 0);
+      }
+    __builtin_amdgcn_sched_barrier(0);
+    qt[2][0] = lds_tr_b64<QO + 0>(at[4]); qt[2][1] = lds_tr_b64<QO + 4096>(at[4]); qt[2][2] = lds_tr_b64<QO + 8192>(at[4]); qt[2][3] = lds_tr_b64<QO + 12288>(at[4]);
+    qt[2][4] = lds_tr_b64<QO + 0>(at[5]); qt[2][5] = lds_tr_b64<QO + 4096>(at[5]); qt[2][6] = lds_tr_b64<QO + 8192>(at[5]); qt[2][7] = lds_tr_b64<QO + 12288>(at[5]);
+    lds_reads_left<8>(qt[1]);
+#pragma unroll
+    for (int db = 2; db < 4; ++db)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const attn_u32x2 lo = qt[1][(db & 1) * 4 + s2 * 2], hi = qt[1][(db & 1) * 4 + s2 * 2 + 1];
+        const attn_u32x4 both = {lo[0], lo[1], hi[0], hi[1]};
+        dk[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, both), dsf[s2], dk[db], 0, 0, 0);
+      }
+    __builtin_amdgcn_sched_barrier(0);
+    qt[3][0] = lds_tr_b64<QO + 0>(at[6]); qt[3][1] = lds_tr_b64<QO + 4096>(at[6]); qt[3][2] = lds_tr_b64<QO + 8192>(at[6]); qt[3][3] = lds_tr_b64<QO + 12288>(at[6]);
+    qt[3][4] = lds_tr_b64<QO + 0>(at[7]); qt[3][5] = lds_tr_b64<QO + 4096>(at[7]); qt[3][6] = lds_tr_b64<QO + 8192>(at[7]); qt[3][7] = lds_tr_b64<QO + 12288>(at[7]);
+    lds_reads_left<8>(qt[2]);
+#pragma unroll
+    for (int db = 4; db < 6; ++db)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const attn_u32x2 lo = qt[2][(db & 1) * 4 + s2 * 2], hi = qt[2][(db & 1) * 4 + s2 * 2 + 1];
+        const attn_u32x4 both = {lo[0], lo[1], hi[0], hi[1]};
+        dk[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, both), dsf[s2], dk[db], 0, 0, 0);
+      }
+    __builtin_amdgcn_sched_barrier(0);
+    lds_reads_done(qt[3]);
+#pragma unroll
+    for (int db = 6; db < 8; ++db)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const attn_u32x2 lo = qt[3][(db & 1) * 4 + s2 * 2], hi = qt[3][(db & 1) * 4 + s2 * 2 + 1];
+        const attn_u32x4 both = {lo[0], lo[1], hi[0], hi[1]};
+        dk[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, both), dsf[s2], dk[db], 0, 0, 0);
+      }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  if (u_lo < u_hi) {
+    // (head, tile) of the unit in hand and of the next one
+    int head = head_first + u_lo / nt, t = q_first + u_lo % nt;
+    fetch_unit(head, t, 0);
+    for (int w = u_lo; w < u_hi; w += 2) {
+      int hn = t + 1 < q_tiles ? head : head + 1, tn = t + 1 < q_tiles ? t + 1 : q_first;
+      tile_step(std::integral_constant<int, 0>{}, t, w + 1 < u_hi, hn, tn);
+      head = hn;
+      t = tn;
+      if (w + 1 < u_hi) {
+        hn = t + 1 < q_tiles ? head : head + 1;
+        tn = t + 1 < q_tiles ? t + 1 : q_first;
+        tile_step(std::integral_constant<int, 1>{}, t, w + 2 < u_hi, hn, tn);
+        head = hn;
+        t = tn;
+      }
+    }
+  }
+
+  if (a.n_parts > 1) {
+    // unscaled fp32 sums of this part: per key a row of [dK | dV]
+    float* pp = a.part_sums + ((tblk * a.n_parts + part) * 64 + wave * 16 + lq) * (2 * D) + lh * 4;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      *reinterpret_cast<f32x4*>(pp + db * 16) = dk[db];
+      *reinterpret_cast<f32x4*>(pp + D + db * 16) = dv[db];
+    }
+    continue;
+  }
+  {
+    const int key = k0 + lq;
+    if (key < S) {
+      uint16_t* kp = a.dQKV + (tok0 + key) * a.ldd + int64_t(a.q_cnt + g) * D + lh * 4;
+      uint16_t* vp = a.dQKV + (tok0 + key) * a.ldd + int64_t(a.q_cnt + a.kv_cnt + g) * D + lh * 4;
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        u16x4 ok, ov;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          ok[r] = ntp_gemm::f32_to_bf16(dk[db][r] * a.scale);
+          ov[r] = ntp_gemm::f32_to_bf16(dv[db][r]);
+        }
+        *reinterpret_cast<u16x4*>(kp + db * 16) = ok;
+        *reinterpret_cast<u16x4*>(vp + db * 16) = ov;
+      }
+    }
+  }
+  }  // the workgroup's passes
+}
+
 // Adds the parts of a cut walk and stores the gradient as bf16.  `rows` rows per workgroup of the cut
 // kernel, `width` fp32 values per row: D (dQ) or 2 D ([dK | dV]).  One thread per 4 values.
 template <int D, bool DKV>
@@ -1447,10 +1849,10 @@ struct CoreChoice {
   int fwd_rows;  // query rows per wavefront of the forward kernel: 16 or 32
   int fwd_parts, dq_parts, dkv_parts;
   int64_t ws_bytes;  // workspace bytes the cut launches use (the largest of the three)
-  bool dq_dma;       // the dQ kernel brings its tiles to LDS by DMA
+  bool dq_dma, dkv_dma;  // the dQ / the dK, dV kernel brings its tiles to LDS by DMA
 };
 CoreChoice choose_core(const ntp_handle* h, int64_t ws_bytes, const ntp_attn_core_shape_t* s) {
-  CoreChoice c{16, 1, 1, 1, 0, false};
+  CoreChoice c{16, 1, 1, 1, 0, false, false};
   const bool causal = s->causal != 0;
   const int64_t tiles = (s->seq_len + kBKV - 1) / kBKV;
   // under the causal mask a workgroup takes a pair of tiles, one from each end of the sequence
@@ -1469,19 +1871,17 @@ CoreChoice choose_core(const ntp_handle* h, int64_t ws_bytes, const ntp_attn_cor
   const double fill = causal ? 2.0 : 3.0;
   // the kernels that copy by DMA spend less per tile, so the second pass over the parts weighs more: under the
   // causal mask, with 3/4 of the compute units busy anyway, parts of 23 tiles or fewer no longer pay (14 heads x
-  // 2048: forward 45 us cut in two, 42 us whole, dQ 52 and 48 us; 3 heads x 8192, parts of 32 tiles: forward 97 us
-  // against 128 us whole)
+  // 2048: forward 42 us cut in two, 39 us whole, dQ 48 and 44 us, dK/dV 64 and 55 us; 3 heads x 8192, parts of 32
+  // tiles: forward 97 us against 128 us whole)
   const bool dma = s->head_dim == 128 && h->opt[NTP_OPT_ATTN_COPY] != 1;
   const int64_t near_full_min = dma && causal ? 23 : 0;
   c.fwd_parts = choose_parts(h, ws_bytes, wq, bq, walk, bf, fill, 12, causal, near_full_min);
   if (c.fwd_parts > 1) c.fwd_rows = 16;
   c.dq_parts = choose_parts(h, ws_bytes, wq, bq, walk, bdq, fill, 12, causal, near_full_min);
-  // the dQ kernel by DMA holds 64 KB of LDS (two workgroups per compute unit, the other form three): with the many
-  // short workgroups of walks cut in 3 or more the other form measured 3-6 % faster, up to 2 parts this one 2-9 %
-  c.dq_dma = dma && (c.dq_parts <= 2 || h->opt[NTP_OPT_ATTN_COPY] == 2);
+  c.dq_dma = c.dkv_dma = dma;
   // a dK/dV workgroup walks over the query tiles of every query head that reads its KV head
   const int64_t heads_per_kv = std::min<int64_t>(s->group, s->q_cnt);
-  c.dkv_parts = choose_parts(h, ws_bytes, wk, bk, heads_per_kv * walk, bdkv, 2.0, 16, false);
+  c.dkv_parts = choose_parts(h, ws_bytes, wk, bk, heads_per_kv * walk, bdkv, 2.0, 16, false, near_full_min);
   if (c.fwd_parts > 1) c.ws_bytes = std::max(c.ws_bytes, bq * c.fwd_parts * bf);
   if (c.dq_parts > 1) c.ws_bytes = std::max(c.ws_bytes, bq * c.dq_parts * bdq);
   if (c.dkv_parts > 1) c.ws_bytes = std::max(c.ws_bytes, bk * c.dkv_parts * bdkv);
@@ -1687,7 +2087,10 @@ extern "C" int ntp_attn_core_shard_bwd(ntp_handle_t* h, const ntp_attn_core_shap
     a.pairs = s->causal ? (a.tiles + 1) / 2 : 0;
     if (ntp::timing_on(h)) ntp::timing_begin(h, stream, a.n_parts > 1 ? "attn_core_bwd_dkv_cut" : "attn_core_bwd_dkv", 4.0 * pair_flops, 0.0);
     const dim3 grid(uint32_t(int64_t(a.pairs > 0 ? a.pairs : a.tiles) * s->n_seq * s->kv_cnt * a.n_parts));
-    if (s->head_dim == 128 && a.pairs > 0)
+    if (cc.dkv_dma) {
+      if (a.pairs > 0) hipLaunchKernelGGL((attn_core_bwd_dkv_dma_kernel<true>), grid, dim3(kThreads), 0, hs, a);
+      else hipLaunchKernelGGL((attn_core_bwd_dkv_dma_kernel<false>), grid, dim3(kThreads), 0, hs, a);
+    } else if (s->head_dim == 128 && a.pairs > 0)
       hipLaunchKernelGGL((attn_core_bwd_dkv_kernel<128, kb, true>), grid, dim3(kThreads), 0, hs, a);
     else if (s->head_dim == 128)
       hipLaunchKernelGGL((attn_core_bwd_dkv_kernel<128, kb, false>), grid, dim3(kThreads), 0, hs, a);

@@ -52,6 +52,18 @@ def test_mid_range_is_cut_only_under_the_causal_mask(workspace_1gib):
     assert (causal["dkv_parts"], full["dkv_parts"]) == (16, 8)
 
 
+def test_step_shape_keeps_whole_walks_with_the_dma_kernels(workspace_1gib):
+    # 14 query and 14 KV heads x 2048 tokens, causal: 224 workgroups of 33 tiles in all three launches
+    c = N.ntp_attn_core_choice(_shape(96, 96, 7, 0, 1, 2048, True))
+    assert c == dict(fwd_rows_per_wavefront=16, fwd_parts=1, dq_parts=1, dkv_parts=1)
+    N.ntp_set_option(Bd.NTP_OPT_ATTN_COPY, 1)
+    try:
+        c = N.ntp_attn_core_choice(_shape(96, 96, 7, 0, 1, 2048, True))
+        assert c == dict(fwd_rows_per_wavefront=16, fwd_parts=2, dq_parts=2, dkv_parts=2)
+    finally:
+        N.ntp_set_option(Bd.NTP_OPT_ATTN_COPY, 0)
+
+
 def test_register_copy_forward_keeps_the_shorter_parts(workspace_1gib):
     N.ntp_set_option(Bd.NTP_OPT_ATTN_COPY, 1)
     try:
