@@ -109,7 +109,10 @@ int ntp_device_info(const ntp_handle_t* h, int32_t* device, int32_t* compute_uni
 #define NTP_OPT_ATTN_COPY 11         /* how the attention kernels bring their 64-row tiles to LDS where both forms
                                         exist (head dimension 128; forward: 16 query rows per wavefront): 1 through
                                         registers, 2 by DMA into chunk-permuted rows; 0: the library's choice          */
-#define NTP_OPT_COUNT_ 12
+#define NTP_OPT_ATTN_BWD_LAUNCHES 12  /* the attention core's dQ and dK/dV kernels: 1 one launch each, 2 one launch for
+                                        both where both copy by DMA (they then share the compute units; a small
+                                        kernel stores the rows' delta values first); 0: the library's choice          */
+#define NTP_OPT_COUNT_ 13
 int ntp_set_option(ntp_handle_t* h, int32_t option, int64_t value);
 
 /* ---------------------------------------------------------------------------

@@ -33,6 +33,7 @@ NTP_OPT_RESHARD_NO_TABLE = 8
 NTP_OPT_GEMM_SCHEDULE = 9
 NTP_OPT_GEMM_WORKGROUPS = 10
 NTP_OPT_ATTN_COPY = 11
+NTP_OPT_ATTN_BWD_LAUNCHES = 12
 NTP_PROBE_MFMA = 0
 NTP_PROBE_LDS_B128 = 1
 NTP_PROBE_LDS_TR_B64 = 2

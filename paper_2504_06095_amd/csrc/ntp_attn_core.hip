@@ -715,6 +715,8 @@ struct CoreBwdArgs {
   // that every workgroup's walk has the same length (tiles + 1 tiles, cut into n_parts); pairs = (tiles + 1) / 2
   // workgroups per (sequence, head)
   int32_t pairs;
+  // 1: the dQ kernel does not store the rows' delta values (a kernel before it has)
+  int32_t delta_stored;
 };
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4_t;
@@ -924,16 +926,17 @@ __device__ __forceinline__ void lds_reads_left(V (&r)[8]) {  // at most N later 
 #endif
 }
 
+constexpr int kDmaTile = kBKV * 128;  // elements of one 64-row tile at head dimension 128
+
+// (bid: the workgroup's number in its launch, or in its share of a launch; sKV: 4 tiles of LDS, key buffers 0 and
+// 1, then value buffers 0 and 1: one base address per lane, the rest are immediates)
 template <bool PAIRED>
-__global__ __attribute__((amdgpu_flat_work_group_size(kThreads, kThreads), amdgpu_waves_per_eu(2, 2))) void
-attn_core_bwd_dq_dma_kernel(const CoreBwdArgs a) {
+__device__ __forceinline__ void bwd_dq_dma_body(const CoreBwdArgs& a, const uint32_t bid, uint16_t* sKV) {
   constexpr int D = 128, KS = D / 32, DB = D / 16, kRows = 64;
-  constexpr int TILE = kBKV * D;           // elements of one tile
+  constexpr int TILE = kDmaTile;           // elements of one tile
   constexpr int NI = TILE * 2 / 1024 / 4;  // DMA instructions per wavefront, matrix and tile
-  // key buffers 0 and 1, then value buffers 0 and 1: one base address per lane, the rest are immediates
-  __shared__ __attribute__((aligned(1024))) uint16_t sKV[4 * TILE];
-  const int piece = a.n_parts > 1 ? int(blockIdx.x % a.n_parts) : 0;
-  const int blk = a.n_parts > 1 ? int(blockIdx.x / a.n_parts) : int(blockIdx.x);
+  const int piece = a.n_parts > 1 ? int(bid % a.n_parts) : 0;
+  const int blk = a.n_parts > 1 ? int(bid / a.n_parts) : int(bid);
   const int per_seq = PAIRED ? a.pairs : a.tiles;
   const int u = blk % per_seq;
   const int sh = blk / per_seq;
@@ -1002,7 +1005,7 @@ attn_core_bwd_dq_dma_kernel(const CoreBwdArgs a) {
     }
     delta = xor_sum(part);
     lse2 = a.LSE[int64_t(head) * Mtot + tok0 + qr] * 1.4426950408889634f;
-    if (lh == 0 && piece == 0 && q0 + lq < S) a.Delta[int64_t(head) * Mtot + tok0 + qr] = delta;
+    if (lh == 0 && piece == 0 && !a.delta_stored && q0 + lq < S) a.Delta[int64_t(head) * Mtot + tok0 + qr] = delta;
   }
   f32x4 acc[DB];
 #pragma unroll
@@ -1401,16 +1404,15 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dkv_kernel(const Co
 // discipline of attn_core_fwd_dma_kernel; head dimension 128, 16 keys per wavefront).  The walk over (query head, query
 // tile) units is one stream through the two buffers; the rows' log-sum-exp and delta values go through registers
 // into a small LDS array of their own, stored before the tile's barrier.
+// (sQG: 4 tiles of LDS, query buffers 0 and 1, then output-gradient buffers 0 and 1; sLD: 4 x 64 floats,
+// [buffer][log-sum-exp, delta][row])
 template <bool PAIRED>
-__global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dkv_dma_kernel(const CoreBwdArgs a) {
+__device__ __forceinline__ void bwd_dkv_dma_body(const CoreBwdArgs& a, const uint32_t bid, uint16_t* sQG, float* sLD) {
   constexpr int D = 128, KS = D / 32, DB = D / 16;
-  constexpr int TILE = kBKV * D;           // elements of one tile
+  constexpr int TILE = kDmaTile;           // elements of one tile
   constexpr int NI = TILE * 2 / 1024 / 4;  // DMA instructions per wavefront, matrix and tile
-  // query buffers 0 and 1, then output-gradient buffers 0 and 1
-  __shared__ __attribute__((aligned(1024))) uint16_t sQG[4 * TILE];
-  __shared__ __attribute__((aligned(16))) float sLD[2 * 2 * kBKV];  // [buffer][log-sum-exp, delta][row]
-  const int part = a.n_parts > 1 ? int(blockIdx.x % a.n_parts) : 0;
-  const int blk = a.n_parts > 1 ? int(blockIdx.x / a.n_parts) : int(blockIdx.x);
+  const int part = a.n_parts > 1 ? int(bid % a.n_parts) : 0;
+  const int blk = a.n_parts > 1 ? int(bid / a.n_parts) : int(bid);
   const int per_seq = PAIRED ? a.pairs : a.tiles;
   const int u = blk % per_seq;
   const int sh = blk / per_seq;
@@ -1793,6 +1795,76 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dkv_dma_kernel(cons
   }  // the workgroup's passes
 }
 
+template <bool PAIRED>
+__global__ __attribute__((amdgpu_flat_work_group_size(kThreads, kThreads), amdgpu_waves_per_eu(2, 2))) void
+attn_core_bwd_dq_dma_kernel(const CoreBwdArgs a) {
+  __shared__ __attribute__((aligned(1024))) uint16_t tiles[4 * kDmaTile];
+  bwd_dq_dma_body<PAIRED>(a, blockIdx.x, tiles);
+}
+
+template <bool PAIRED>
+__global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dkv_dma_kernel(const CoreBwdArgs a) {
+  __shared__ __attribute__((aligned(1024))) uint16_t tiles[4 * kDmaTile];
+  __shared__ __attribute__((aligned(16))) float row_values[2 * 2 * kBKV];
+  bwd_dkv_dma_body<PAIRED>(a, blockIdx.x, tiles, row_values);
+}
+
+// Both backward kernels in one launch: the first n_dkv workgroups are dK/dV workgroups, the rest dQ workgroups.
+// Each kernel alone keeps the matrix pipe and the vector ALU busy in turn; at the launch sizes of a few heads
+// and a few thousand tokens either leaves most SIMDs with one wavefront, and nothing overlaps.  Launched together a
+// compute unit holds one workgroup of each kind (65 KB + 64 KB of LDS), whose phases differ (14 heads x 2048
+// tokens, causal: 50 + 60 us one after the other, 76 us together).  The dK/dV workgroups need every row's delta
+// before they start, so a small kernel stores those first (attn_core_delta_kernel).
+// Order of the workgroups: a compute unit holds two of them, and the kinds should meet there.  Measured, a launch of
+// 224 dK/dV workgroups followed by 224 dQ workgroups behaves like the two kernels on two streams (workgroups are
+// spread one per compute unit before any gets its second), while kinds that alternate every 8 workgroups ran 8 %
+// slower.  So the kinds alternate in chunks of `chunk` = compute units workgroups, dK/dV first, over the first
+// 2 `paired` workgroups (paired: a multiple of chunk, at most either kind's count); the rest of the dK/dV
+// workgroups and then the rest of the dQ workgroups follow.
+struct BothOrder {
+  uint32_t n_dkv, paired, chunk;
+};
+
+template <bool PAIRED>
+__global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_both_kernel(const CoreBwdArgs adq, const CoreBwdArgs adkv, const BothOrder o) {
+  __shared__ __attribute__((aligned(1024))) uint16_t tiles[4 * kDmaTile];
+  __shared__ __attribute__((aligned(16))) float row_values[2 * 2 * kBKV];
+  uint32_t b = blockIdx.x;
+  bool dkv;
+  if (b < 2 * o.paired) {
+    const uint32_t c = b / o.chunk;
+    dkv = (c & 1) == 0;
+    b = (c >> 1) * o.chunk + b % o.chunk;
+  } else {
+    b -= 2 * o.paired;
+    dkv = b < o.n_dkv - o.paired;
+    b = dkv ? o.paired + b : o.paired + b - (o.n_dkv - o.paired);
+  }
+  if (dkv) bwd_dkv_dma_body<PAIRED>(adkv, b, tiles, row_values);
+  else bwd_dq_dma_body<PAIRED>(adq, b, tiles);
+}
+
+// delta[head][row] = sum_d dC[row][head D + d] C[row][head D + d]: 16 lanes per (row, head), 8 values each
+template <int D>
+__global__ __launch_bounds__(256) void attn_core_delta_kernel(const CoreBwdArgs a, int64_t rows) {
+  constexpr int LPR = D / 8;  // lanes per (row, head): 16 or 8
+  const int64_t idx = int64_t(blockIdx.x) * 256 + threadIdx.x;
+  const int c = int(idx % LPR);
+  const int64_t rh = idx / LPR;
+  const int head = int(rh % a.q_cnt);
+  const int64_t row = rh / a.q_cnt;
+  float part = 0.f;
+  if (row < rows) {
+    const bf16x8 g = *reinterpret_cast<const bf16x8*>(a.dC + row * a.lddc + int64_t(head) * D + c * 8);
+    const bf16x8 o = *reinterpret_cast<const bf16x8*>(a.C + row * a.ldc + int64_t(head) * D + c * 8);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) part += float(g[e]) * float(o[e]);
+  }
+#pragma unroll
+  for (int m = LPR / 2; m >= 1; m >>= 1) part += __shfl_xor(part, m);
+  if (c == 0 && row < rows) a.Delta[int64_t(head) * rows + row] = part;
+}
+
 // Adds the parts of a cut walk and stores the gradient as bf16.  `rows` rows per workgroup of the cut
 // kernel, `width` fp32 values per row: D (dQ) or 2 D ([dK | dV]).  One thread per 4 values.
 template <int D, bool DKV>
@@ -1850,9 +1922,11 @@ struct CoreChoice {
   int fwd_parts, dq_parts, dkv_parts;
   int64_t ws_bytes;  // workspace bytes the cut launches use (the largest of the three)
   bool dq_dma, dkv_dma;  // the dQ / the dK, dV kernel brings its tiles to LDS by DMA
+  bool bwd_both;         // both backward kernels go out as one launch
+  int64_t dkv_ws_offset; // then: byte offset of the dK/dV parts in the workspace (behind the dQ parts)
 };
 CoreChoice choose_core(const ntp_handle* h, int64_t ws_bytes, const ntp_attn_core_shape_t* s) {
-  CoreChoice c{16, 1, 1, 1, 0, false, false};
+  CoreChoice c{16, 1, 1, 1, 0, false, false, false, 0};
   const bool causal = s->causal != 0;
   const int64_t tiles = (s->seq_len + kBKV - 1) / kBKV;
   // under the causal mask a workgroup takes a pair of tiles, one from each end of the sequence
@@ -1883,8 +1957,19 @@ CoreChoice choose_core(const ntp_handle* h, int64_t ws_bytes, const ntp_attn_cor
   const int64_t heads_per_kv = std::min<int64_t>(s->group, s->q_cnt);
   c.dkv_parts = choose_parts(h, ws_bytes, wk, bk, heads_per_kv * walk, bdkv, 2.0, 16, false, near_full_min);
   if (c.fwd_parts > 1) c.ws_bytes = std::max(c.ws_bytes, bq * c.fwd_parts * bf);
-  if (c.dq_parts > 1) c.ws_bytes = std::max(c.ws_bytes, bq * c.dq_parts * bdq);
-  if (c.dkv_parts > 1) c.ws_bytes = std::max(c.ws_bytes, bk * c.dkv_parts * bdkv);
+  const int64_t dq_bytes = c.dq_parts > 1 ? bq * c.dq_parts * bdq : 0, dkv_bytes = c.dkv_parts > 1 ? bk * c.dkv_parts * bdkv : 0;
+  // the two DMA kernels share a launch (attn_core_bwd_both_kernel) where the workspace holds both kernels' parts
+  // at once; NTP_OPT_ATTN_BWD_LAUNCHES: 1 always two launches, 2 one launch wherever the kernels allow
+  c.dkv_ws_offset = (dq_bytes + 255) / 256 * 256;
+  // Where it pays (3 and 14-16 heads, 2048-8192 tokens, both masks): launches that together stay under 2.5
+  // workgroups per compute unit (14 heads x 2048 causal: 98 -> 80 us; 16 heads x 2 x 2048 causal 177 -> 168) and
+  // cut walks (3 heads x 4096: 97 -> 93 us causal, 126 -> 121 unmasked); launches that each fill the device
+  // alone lose 1-6 % to the extra kernel and stay apart.
+  const int64_t dq_w = wq * c.dq_parts, dkv_w = wk * c.dkv_parts;
+  const bool pays = (dq_w + dkv_w) * 2 <= 5 * int64_t(h->compute_units) || (c.dq_parts > 1 && c.dkv_parts > 1);
+  c.bwd_both = c.dq_dma && c.dkv_dma && h->opt[NTP_OPT_ATTN_BWD_LAUNCHES] != 1 && (pays || h->opt[NTP_OPT_ATTN_BWD_LAUNCHES] == 2) &&
+               (dkv_bytes == 0 || c.dkv_ws_offset + dkv_bytes <= ws_bytes);
+  c.ws_bytes = std::max(c.ws_bytes, c.bwd_both ? (dkv_bytes ? c.dkv_ws_offset + dkv_bytes : dq_bytes) : std::max(dq_bytes, dkv_bytes));
   return c;
 }
 
@@ -2049,13 +2134,61 @@ extern "C" int ntp_attn_core_shard_bwd(ntp_handle_t* h, const ntp_attn_core_shap
   if (bq > 0x7fffffffll || bk > 0x7fffffffll) return NTP_ERR_UNSUPPORTED;
   a.part_sums = static_cast<float*>(h->workspace);
   const CoreChoice cc = choose_core(h, h->workspace ? h->workspace_bytes : 0, s);
+  const int32_t q_pairs = s->causal ? (a.tiles + 1) / 2 : 0, k_pairs = s->causal ? (key_tiles + 1) / 2 : 0;
+  const int64_t dq_wgs = int64_t(q_pairs > 0 ? q_pairs : a.tiles) * s->n_seq * s->q_cnt * cc.dq_parts;
+  const int64_t dkv_wgs = int64_t(k_pairs > 0 ? k_pairs : key_tiles) * s->n_seq * s->kv_cnt * cc.dkv_parts;
+  auto reduce_parts = [&](auto dkv, int64_t blocks) {
+    constexpr bool DKV = decltype(dkv)::value;
+    const dim3 rgrid(uint32_t((blocks * 64 * ((DKV ? 2 : 1) * s->head_dim / 4) + 255) / 256));
+    if (s->head_dim == 128)
+      hipLaunchKernelGGL((attn_core_part_reduce_kernel<128, DKV>), rgrid, dim3(256), 0, hs, a, blocks);
+    else
+      hipLaunchKernelGGL((attn_core_part_reduce_kernel<64, DKV>), rgrid, dim3(256), 0, hs, a, blocks);
+    return hipGetLastError() == hipSuccess;
+  };
+  const int64_t delta_wgs = (M * s->q_cnt * 16 + 255) / 256;
+  if (dq_wgs > 0x7fffffffll || dkv_wgs > 0x7fffffffll) return NTP_ERR_UNSUPPORTED;
+  if (cc.bwd_both && bq > 0 && bk > 0 && dq_wgs + dkv_wgs <= 0x7fffffffll && delta_wgs <= 0x7fffffffll) {
+    // one launch for both kernels, after the rows' delta values (5 algorithmic + 2 recomputed products per pair)
+    CoreBwdArgs adq = a, adkv = a;
+    adq.n_parts = cc.dq_parts;
+    adq.pairs = q_pairs;
+    adq.delta_stored = 1;
+    adkv.tiles = key_tiles;
+    adkv.n_parts = cc.dkv_parts;
+    adkv.pairs = k_pairs;
+    adkv.part_sums = a.part_sums + cc.dkv_ws_offset / 4;
+    if (ntp::timing_on(h)) ntp::timing_begin(h, stream, cc.dq_parts > 1 || cc.dkv_parts > 1 ? "attn_core_bwd_both_cut" : "attn_core_bwd_both", 7.0 * pair_flops, 0.0);
+    hipLaunchKernelGGL((attn_core_delta_kernel<128>), dim3(uint32_t(delta_wgs)), dim3(256), 0, hs, a, M);
+    ok = hipGetLastError() == hipSuccess;
+    const dim3 grid(uint32_t(dq_wgs + dkv_wgs));
+    if (ok) {
+      BothOrder order;
+      order.n_dkv = uint32_t(dkv_wgs);
+      order.chunk = uint32_t(std::max(h->compute_units, 1));
+      order.paired = uint32_t(std::min(dq_wgs, dkv_wgs) / order.chunk * order.chunk);
+      if (s->causal) hipLaunchKernelGGL((attn_core_bwd_both_kernel<true>), grid, dim3(kThreads), 0, hs, adq, adkv, order);
+      else hipLaunchKernelGGL((attn_core_bwd_both_kernel<false>), grid, dim3(kThreads), 0, hs, adq, adkv, order);
+      ok = hipGetLastError() == hipSuccess;
+    }
+    if (ok && cc.dq_parts > 1) {
+      a = adq;
+      ok = reduce_parts(std::false_type{}, bq);
+    }
+    if (ok && cc.dkv_parts > 1) {
+      a = adkv;
+      ok = reduce_parts(std::true_type{}, bk);
+    }
+    ntp::timing_end(h, stream);
+    return ok ? NTP_OK : NTP_ERR_LAUNCH;
+  }
   if (bq > 0) {
     // dQ and delta: three products per (query, key) pair.  With few heads the launch is short of
     // workgroups and each walks over up to seq_len / 64 key tiles: cut the walks then.
     a.n_parts = cc.dq_parts;
-    a.pairs = s->causal ? (a.tiles + 1) / 2 : 0;
+    a.pairs = q_pairs;
     if (ntp::timing_on(h)) ntp::timing_begin(h, stream, a.n_parts > 1 ? "attn_core_bwd_dq_cut" : "attn_core_bwd_dq", 3.0 * pair_flops, 0.0);
-    const dim3 grid(uint32_t(int64_t(a.pairs > 0 ? a.pairs : a.tiles) * s->n_seq * s->q_cnt * a.n_parts));
+    const dim3 grid{uint32_t(dq_wgs)};
     if (cc.dq_dma) {
       if (a.pairs > 0) hipLaunchKernelGGL((attn_core_bwd_dq_dma_kernel<true>), grid, dim3(kThreads), 0, hs, a);
       else hipLaunchKernelGGL((attn_core_bwd_dq_dma_kernel<false>), grid, dim3(kThreads), 0, hs, a);
@@ -2068,14 +2201,7 @@ extern "C" int ntp_attn_core_shard_bwd(ntp_handle_t* h, const ntp_attn_core_shap
     else
       hipLaunchKernelGGL((attn_core_bwd_dq_kernel<64, qbw, false>), grid, dim3(kThreads), 0, hs, a);
     ok = hipGetLastError() == hipSuccess;
-    if (ok && a.n_parts > 1) {
-      const dim3 rgrid(uint32_t((bq * 64 * (s->head_dim / 4) + 255) / 256));
-      if (s->head_dim == 128)
-        hipLaunchKernelGGL((attn_core_part_reduce_kernel<128, false>), rgrid, dim3(256), 0, hs, a, bq);
-      else
-        hipLaunchKernelGGL((attn_core_part_reduce_kernel<64, false>), rgrid, dim3(256), 0, hs, a, bq);
-      ok = hipGetLastError() == hipSuccess;
-    }
+    if (ok && a.n_parts > 1) ok = reduce_parts(std::false_type{}, bq);
     ntp::timing_end(h, stream);
     if (!ok) return NTP_ERR_LAUNCH;
   }
@@ -2084,9 +2210,9 @@ extern "C" int ntp_attn_core_shard_bwd(ntp_handle_t* h, const ntp_attn_core_shap
     // a workgroup walks over the query tiles of every query head that reads its KV head
     a.tiles = key_tiles;
     a.n_parts = cc.dkv_parts;
-    a.pairs = s->causal ? (a.tiles + 1) / 2 : 0;
+    a.pairs = k_pairs;
     if (ntp::timing_on(h)) ntp::timing_begin(h, stream, a.n_parts > 1 ? "attn_core_bwd_dkv_cut" : "attn_core_bwd_dkv", 4.0 * pair_flops, 0.0);
-    const dim3 grid(uint32_t(int64_t(a.pairs > 0 ? a.pairs : a.tiles) * s->n_seq * s->kv_cnt * a.n_parts));
+    const dim3 grid{uint32_t(dkv_wgs)};
     if (cc.dkv_dma) {
       if (a.pairs > 0) hipLaunchKernelGGL((attn_core_bwd_dkv_dma_kernel<true>), grid, dim3(kThreads), 0, hs, a);
       else hipLaunchKernelGGL((attn_core_bwd_dkv_dma_kernel<false>), grid, dim3(kThreads), 0, hs, a);
@@ -2099,14 +2225,7 @@ extern "C" int ntp_attn_core_shard_bwd(ntp_handle_t* h, const ntp_attn_core_shap
     else
       hipLaunchKernelGGL((attn_core_bwd_dkv_kernel<64, kb, false>), grid, dim3(kThreads), 0, hs, a);
     ok = hipGetLastError() == hipSuccess;
-    if (ok && a.n_parts > 1) {
-      const dim3 rgrid(uint32_t((bk * 64 * (2 * s->head_dim / 4) + 255) / 256));
-      if (s->head_dim == 128)
-        hipLaunchKernelGGL((attn_core_part_reduce_kernel<128, true>), rgrid, dim3(256), 0, hs, a, bk);
-      else
-        hipLaunchKernelGGL((attn_core_part_reduce_kernel<64, true>), rgrid, dim3(256), 0, hs, a, bk);
-      ok = hipGetLastError() == hipSuccess;
-    }
+    if (ok && a.n_parts > 1) ok = reduce_parts(std::true_type{}, bk);
     ntp::timing_end(h, stream);
   }
   return ok ? NTP_OK : NTP_ERR_LAUNCH;

@@ -70,6 +70,7 @@ extern "C" int ntp_set_option(ntp_handle_t* h, int32_t option, int64_t value) {
       if (value < 0 || value > 2) return NTP_ERR_INVALID_ARG;
       break;
     case NTP_OPT_ATTN_COPY:
+    case NTP_OPT_ATTN_BWD_LAUNCHES:
       if (value < 0 || value > 2) return NTP_ERR_INVALID_ARG;
       break;
     case NTP_OPT_GEMM_WORKGROUPS:

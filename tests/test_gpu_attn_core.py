@@ -150,7 +150,10 @@ def test_attn_core_bwd_cut_walks(workspace, opts, n_q, n_kv, tp, rank, d, n_seq,
     opts(K.NTP_OPT_ATTN_PARTS, parts)
     _bwd_case(n_q, n_kv, tp, rank, d, n_seq, S, causal)
     names = _core_names()
-    assert "attn_core_bwd_dq_cut" in names and "attn_core_bwd_dkv_cut" in names, names
+    if d == 128:  # both kernels in one launch
+        assert "attn_core_bwd_both_cut" in names, names
+    else:
+        assert "attn_core_bwd_dq_cut" in names and "attn_core_bwd_dkv_cut" in names, names
 
 
 @pytest.mark.parametrize("parts", [2, 5, 16])
@@ -202,6 +205,45 @@ def test_attn_core_bwd_both_copy_forms(workspace, opts, n_q, n_kv, tp, rank, d, 
     _bwd_case(n_q, n_kv, tp, rank, d, n_seq, S, causal, seed=19, pad=pad)
 
 
+@pytest.mark.parametrize("launches", [1, 2], ids=["two_launches", "one_launch"])
+@pytest.mark.parametrize("parts", [1, 4])
+@pytest.mark.parametrize("causal", [False, True], ids=["full", "causal"])
+@pytest.mark.parametrize("n_q,n_kv,tp,rank,d,n_seq,S,pad", [(8, 2, 3, 0, 128, 2, 200, 0), (6, 6, 4, 1, 128, 1, 1100, 8),
+                                                          (64, 8, 30, 3, 128, 2, 449, 0), (4, 1, 4, 3, 128, 1, 1, 0)])
+def test_attn_core_bwd_one_or_two_launches(workspace, opts, n_q, n_kv, tp, rank, d, n_seq, S, pad, causal, parts, launches):
+    """The dQ and the dK/dV kernel as two launches or as one launch whose workgroups are of both kinds (after a kernel
+    that stores the rows' delta values): grouped and ungrouped KV heads, ragged lengths, whole and cut walks (both
+    kernels' parts side by side in the workspace)."""
+    _say(f"attn core bwd, launches option {launches}: n_q={n_q} n_kv={n_kv} d={d} n_seq={n_seq} S={S} pad={pad} causal={causal} parts={parts}")
+    opts(K.NTP_OPT_ATTN_PARTS, parts)
+    opts(K.NTP_OPT_ATTN_BWD_LAUNCHES, launches)
+    _bwd_case(n_q, n_kv, tp, rank, d, n_seq, S, causal, seed=23, pad=pad)
+    names = [n for n in _core_names() if "bwd" in n]
+    cut = "_cut" if parts > 1 else ""
+    assert names == (["attn_core_bwd_both" + cut] if launches == 2 else ["attn_core_bwd_dq" + cut, "attn_core_bwd_dkv" + cut]), names
+
+
+def test_attn_core_bwd_one_launch_needs_room_for_both_kernels_parts(opts):
+    """With a workspace that holds either kernel's parts but not both, the cut kernels go out as two launches."""
+    import torch
+    import paper_2504_06095_amd as N
+    _say("attn core bwd: workspace too small for one launch")
+    # 3 heads on 1 KV head, 449 x 2 tokens: 16 tiles; 4 parts: dQ 16 x 3 x 4 x 32 KiB = 6 MiB, dK/dV 16 x 4 x 64 KiB = 4 MiB
+    ws = torch.full(((7 << 20) // 4,), float("nan"), dtype=torch.float32, device="cuda")
+    N.ntp_set_workspace(ws)
+    N.ntp_kernel_timing_enable(1)
+    N.ntp_kernel_timing_read()
+    try:
+        opts(K.NTP_OPT_ATTN_PARTS, 4)
+        _bwd_case(64, 8, 30, 3, 128, 2, 449, True, seed=29)
+        names = [n for n in _core_names() if "bwd" in n]
+        assert names == ["attn_core_bwd_dq_cut", "attn_core_bwd_dkv_cut"], names
+    finally:
+        N.ntp_kernel_timing_enable(0)
+        N.ntp_kernel_timing_read()
+        N.ntp_set_workspace(None)
+
+
 @pytest.mark.parametrize("causal", [False, True], ids=["full", "causal"])
 def test_attn_core_at_the_step_shape(workspace, causal):
     """14 heads x 128, one sequence of 2048 tokens (the benchmark step's rank), the launcher's own choices with a
@@ -225,11 +267,11 @@ def test_attn_core_bwd_cut_chosen_for_few_heads(workspace):
     _say("attn core bwd: cut chosen at the config-3 shape")
     _bwd_case(64, 8, 30, 0, 128, 1, 4096, True, seed=5)
     names = _core_names()
-    assert names == ["attn_core_fwd_causal_cut", "attn_core_bwd_dq_cut", "attn_core_bwd_dkv_cut"], names
+    assert names == ["attn_core_fwd_causal_cut", "attn_core_bwd_both_cut"], names
     N.ntp_set_workspace(None)
     _bwd_case(64, 8, 30, 0, 128, 1, 1024, True, seed=5)
     names = _core_names()
-    assert names == ["attn_core_fwd_causal", "attn_core_bwd_dq", "attn_core_bwd_dkv"], names
+    assert names == ["attn_core_fwd_causal", "attn_core_bwd_both"], names
 
 
 def test_attn_core_bwd_padded_rows():

@@ -59,7 +59,7 @@ def test_layer_calls_replay_in_a_graph(with_workspace):
             names = [r["name"] for r in N.ntp_kernel_timing_read()]
             N.ntp_kernel_timing_enable(0)
             assert any(n.startswith("gemm_") and "k" in n.split("_")[-1] for n in names), names
-            assert "attn_core_bwd_dkv_cut" in names, names
+            assert "attn_core_bwd_both_cut" in names, names
         side = torch.cuda.Stream()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.stream(side):

@@ -188,14 +188,14 @@ def test_set_option_checks_its_arguments():
     h = Bd.ntp_create()
     assert L.ntp_set_option(None, Bd.NTP_OPT_GEMM_TILE, 0) == Bd.NTP_ERR_INVALID_ARG
     assert L.ntp_set_option(h.ptr, -1, 0) == Bd.NTP_ERR_INVALID_ARG
-    assert L.ntp_set_option(h.ptr, 12, 0) == Bd.NTP_ERR_INVALID_ARG
+    assert L.ntp_set_option(h.ptr, 13, 0) == Bd.NTP_ERR_INVALID_ARG
     assert L.ntp_set_option(h.ptr, Bd.NTP_OPT_GEMM_TILE, 11) == Bd.NTP_ERR_INVALID_ARG
     assert L.ntp_set_option(h.ptr, Bd.NTP_OPT_GEMM_SPLIT, 9) == Bd.NTP_ERR_INVALID_ARG
     assert L.ntp_set_option(h.ptr, Bd.NTP_OPT_ATTN_PARTS, 17) == Bd.NTP_ERR_INVALID_ARG
     assert L.ntp_set_option(h.ptr, Bd.NTP_OPT_RESHARD_NO_TABLE, 2) == Bd.NTP_ERR_INVALID_ARG
     assert L.ntp_set_option(h.ptr, Bd.NTP_OPT_RESHARD_BLOCK, -4) == Bd.NTP_ERR_INVALID_ARG
     assert L.ntp_set_option(h.ptr, Bd.NTP_OPT_GEMM_WORKGROUPS, 65537) == Bd.NTP_ERR_INVALID_ARG
-    for opt in range(12):
+    for opt in range(13):
         assert L.ntp_set_option(h.ptr, opt, 1) == 0
         assert L.ntp_set_option(h.ptr, opt, 0) == 0
     Bd.ntp_destroy(h)
