@@ -88,6 +88,17 @@ __device__ __forceinline__ float xor_sum(float v) {
   return q.a + q.b;
 }
 
+// Workgroups go to the chip's 8 XCDs in turn (workgroup b to XCD b % 8), and each XCD has an L2 of its own.  The
+// workgroups of one head read the same key / value (or query / output-gradient) rows, 1 MB per head at 2048 tokens:
+// spread over all XCDs every L2 sees every head (14 heads: 15 MB against 4 MB of L2).  So the launch order is
+// renumbered: XCD x takes the x-th contiguous eighth of the logical order, in which a head's workgroups are
+// neighbours.  (Measured gain at 14 heads x 2048 tokens causal: forward 39.4 -> 38.5 us, backward 80 -> 76 us; the
+// tiles that miss L2 come from the 256 MB last-level cache either way.)
+__device__ __forceinline__ uint32_t xcd_major(uint32_t b, uint32_t total) {
+  const uint32_t x = b & 7, q = total >> 3, r = total & 7;
+  return x * q + (x < r ? x : r) + (b >> 3);
+}
+
 // Source of the 64-row tiles of a [S x ld] bf16 matrix (D columns from `base` on, the first row of a sequence):
 // one 16-byte buffer load per thread and chunk.  A thread's offsets inside a tile never change (tile_offsets); the
 // tile is chosen by the instruction's scalar offset, so the loop spends no vector arithmetic on addresses.  The
@@ -138,8 +149,9 @@ attn_core_fwd_kernel(const CoreArgs a) {
 
   // workgroup -> (head, sequence, query tile); consecutive workgroups share a head's keys and values.
   // With the causal mask the late tiles have the most keys: they go first.
-  const int piece = a.n_parts > 1 ? int(blockIdx.x % a.n_parts) : 0;
-  const int blk = a.n_parts > 1 ? int(blockIdx.x / a.n_parts) : int(blockIdx.x);
+  const uint32_t bid = xcd_major(blockIdx.x, gridDim.x);
+  const int piece = a.n_parts > 1 ? int(bid % a.n_parts) : 0;
+  const int blk = a.n_parts > 1 ? int(bid / a.n_parts) : int(bid);
   const int per_seq = PAIRED ? a.pairs : a.q_tiles;  // workgroups per (sequence, head) and piece
   const int u = blk % per_seq;
   const int sh = blk / per_seq;
@@ -392,6 +404,8 @@ attn_core_fwd_kernel(const CoreArgs a) {
 // wait for all of it.
 __device__ __forceinline__ uint32_t row_swz(int r) { return uint32_t((r & 7) << 1); }
 
+constexpr int kDmaTile = kBKV * 128;  // elements of one 64-row tile at head dimension 128
+
 typedef uint32_t attn_u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t attn_u32x2 __attribute__((ext_vector_type(2)));
 
@@ -434,6 +448,15 @@ __device__ __forceinline__ void lds_reads_tied(V (&r)[8]) {
   asm volatile("" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]), "+v"(r[6]), "+v"(r[7]) : : "memory");
 #endif
 }
+template <int N, typename V>
+__device__ __forceinline__ void lds_reads_left(V (&r)[8]) {  // at most N later reads may still be in flight
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("s_waitcnt lgkmcnt(%8)"
+               : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]), "+v"(r[6]), "+v"(r[7])
+               : "n"(N)
+               : "memory");
+#endif
+}
 __device__ __forceinline__ void dma_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 __device__ __forceinline__ void dma_16(__amdgpu_buffer_rsrc_t rs, uint16_t* dst, uint32_t voff, uint32_t soff) {
   __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (ntp_gemm::lds_void*)dst, 16, voff, soff, 0, 0);
@@ -448,8 +471,9 @@ attn_core_fwd_dma_kernel(const CoreArgs a) {
   __shared__ __attribute__((aligned(1024))) uint16_t sK[2 * TILE];
   __shared__ __attribute__((aligned(1024))) uint16_t sV[2 * TILE];
 
-  const int piece = a.n_parts > 1 ? int(blockIdx.x % a.n_parts) : 0;
-  const int blk = a.n_parts > 1 ? int(blockIdx.x / a.n_parts) : int(blockIdx.x);
+  const uint32_t bid = xcd_major(blockIdx.x, gridDim.x);
+  const int piece = a.n_parts > 1 ? int(bid % a.n_parts) : 0;
+  const int blk = a.n_parts > 1 ? int(bid / a.n_parts) : int(bid);
   const int per_seq = PAIRED ? a.pairs : a.q_tiles;
   const int u = blk % per_seq;
   const int sh = blk / per_seq;
@@ -739,8 +763,9 @@ attn_core_bwd_dq_kernel(const CoreBwdArgs a) {
   constexpr int LDT = D + 16, KS = D / 32, DB = D / 16, CPR = D / 8, NLD = kBKV * CPR / kThreads;
   __shared__ __attribute__((aligned(16))) uint16_t sK[kBKV * LDT];
   __shared__ __attribute__((aligned(16))) uint16_t sV[kBKV * LDT];
-  const int piece = a.n_parts > 1 ? int(blockIdx.x % a.n_parts) : 0;
-  const int blk = a.n_parts > 1 ? int(blockIdx.x / a.n_parts) : int(blockIdx.x);
+  const uint32_t bid = xcd_major(blockIdx.x, gridDim.x);
+  const int piece = a.n_parts > 1 ? int(bid % a.n_parts) : 0;
+  const int blk = a.n_parts > 1 ? int(bid / a.n_parts) : int(bid);
   const int per_seq = PAIRED ? a.pairs : a.tiles;
   const int u = blk % per_seq;
   const int sh = blk / per_seq;
@@ -916,22 +941,11 @@ attn_core_bwd_dq_kernel(const CoreBwdArgs a) {
 // The dQ kernel with the key / value tiles brought to LDS by DMA (see attn_core_fwd_dma_kernel: the same chunk-permuted
 // rows, two buffers per matrix, one barrier per tile, LDS reads as inline assembly with their waits).  Head
 // dimension 128, 16 query rows per wavefront.
-template <int N, typename V>
-__device__ __forceinline__ void lds_reads_left(V (&r)[8]) {  // at most N later reads may still be in flight
-#if defined(__HIP_DEVICE_COMPILE__)
-  asm volatile("s_waitcnt lgkmcnt(%8)"
-               : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]), "+v"(r[6]), "+v"(r[7])
-               : "n"(N)
-               : "memory");
-#endif
-}
-
-constexpr int kDmaTile = kBKV * 128;  // elements of one 64-row tile at head dimension 128
-
 // (bid: the workgroup's number in its launch, or in its share of a launch; sKV: 4 tiles of LDS, key buffers 0 and
 // 1, then value buffers 0 and 1: one base address per lane, the rest are immediates)
 template <bool PAIRED>
-__device__ __forceinline__ void bwd_dq_dma_body(const CoreBwdArgs& a, const uint32_t bid, uint16_t* sKV) {
+__device__ __forceinline__ void bwd_dq_dma_body(const CoreBwdArgs& a, const uint32_t b_launch, const uint32_t total, uint16_t* sKV) {
+  const uint32_t bid = xcd_major(b_launch, total);
   constexpr int D = 128, KS = D / 32, DB = D / 16, kRows = 64;
   constexpr int TILE = kDmaTile;           // elements of one tile
   constexpr int NI = TILE * 2 / 1024 / 4;  // DMA instructions per wavefront, matrix and tile
@@ -1187,8 +1201,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dkv_kernel(const Co
   __shared__ __attribute__((aligned(16))) uint16_t sG[kBKV * LDT];
   __shared__ __attribute__((aligned(16))) float sL[kBKV];
   __shared__ __attribute__((aligned(16))) float sD[kBKV];
-  const int part = a.n_parts > 1 ? int(blockIdx.x % a.n_parts) : 0;
-  const int blk = a.n_parts > 1 ? int(blockIdx.x / a.n_parts) : int(blockIdx.x);
+  const uint32_t bid = xcd_major(blockIdx.x, gridDim.x);
+  const int part = a.n_parts > 1 ? int(bid % a.n_parts) : 0;
+  const int blk = a.n_parts > 1 ? int(bid / a.n_parts) : int(bid);
   const int per_seq = PAIRED ? a.pairs : a.tiles;
   const int u = blk % per_seq;
   const int sh = blk / per_seq;
@@ -1407,7 +1422,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dkv_kernel(const Co
 // (sQG: 4 tiles of LDS, query buffers 0 and 1, then output-gradient buffers 0 and 1; sLD: 4 x 64 floats,
 // [buffer][log-sum-exp, delta][row])
 template <bool PAIRED>
-__device__ __forceinline__ void bwd_dkv_dma_body(const CoreBwdArgs& a, const uint32_t bid, uint16_t* sQG, float* sLD) {
+__device__ __forceinline__ void bwd_dkv_dma_body(const CoreBwdArgs& a, const uint32_t b_launch, const uint32_t total, uint16_t* sQG, float* sLD) {
+  const uint32_t bid = xcd_major(b_launch, total);
   constexpr int D = 128, KS = D / 32, DB = D / 16;
   constexpr int TILE = kDmaTile;           // elements of one tile
   constexpr int NI = TILE * 2 / 1024 / 4;  // DMA instructions per wavefront, matrix and tile
@@ -1799,14 +1815,14 @@ template <bool PAIRED>
 __global__ __attribute__((amdgpu_flat_work_group_size(kThreads, kThreads), amdgpu_waves_per_eu(2, 2))) void
 attn_core_bwd_dq_dma_kernel(const CoreBwdArgs a) {
   __shared__ __attribute__((aligned(1024))) uint16_t tiles[4 * kDmaTile];
-  bwd_dq_dma_body<PAIRED>(a, blockIdx.x, tiles);
+  bwd_dq_dma_body<PAIRED>(a, blockIdx.x, gridDim.x, tiles);
 }
 
 template <bool PAIRED>
 __global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_dkv_dma_kernel(const CoreBwdArgs a) {
   __shared__ __attribute__((aligned(1024))) uint16_t tiles[4 * kDmaTile];
   __shared__ __attribute__((aligned(16))) float row_values[2 * 2 * kBKV];
-  bwd_dkv_dma_body<PAIRED>(a, blockIdx.x, tiles, row_values);
+  bwd_dkv_dma_body<PAIRED>(a, blockIdx.x, gridDim.x, tiles, row_values);
 }
 
 // Both backward kernels in one launch: the first n_dkv workgroups are dK/dV workgroups, the rest dQ workgroups.
@@ -1840,8 +1856,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_core_bwd_both_kernel(const C
     dkv = b < o.n_dkv - o.paired;
     b = dkv ? o.paired + b : o.paired + b - (o.n_dkv - o.paired);
   }
-  if (dkv) bwd_dkv_dma_body<PAIRED>(adkv, b, tiles, row_values);
-  else bwd_dq_dma_body<PAIRED>(adq, b, tiles);
+  // (each kind renumbered by itself: its workgroups with equal b % 8 share an XCD whatever the other kind's count)
+  if (dkv) bwd_dkv_dma_body<PAIRED>(adkv, b, o.n_dkv, tiles, row_values);
+  else bwd_dq_dma_body<PAIRED>(adq, b, gridDim.x - o.n_dkv, tiles);
 }
 
 // delta[head][row] = sum_d dC[row][head D + d] C[row][head D + d]: 16 lanes per (row, head), 8 values each

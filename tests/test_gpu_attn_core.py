@@ -181,10 +181,11 @@ def test_attn_core_causal_pairs_odd_tile_counts(workspace, opts, n_q, n_kv, tp, 
 @pytest.mark.parametrize("parts", [1, 3])
 @pytest.mark.parametrize("causal", [False, True], ids=["full", "causal"])
 @pytest.mark.parametrize("n_q,n_kv,tp,rank,d,n_seq,S,pad", [(8, 2, 3, 0, 128, 2, 200, 0), (6, 6, 4, 1, 128, 1, 1100, 8),
-                                                          (64, 8, 30, 3, 128, 2, 449, 0)])
+                                                          (64, 8, 30, 3, 128, 2, 449, 0), (4, 1, 4, 3, 128, 1, 1, 0),
+                                                          (6, 6, 4, 1, 128, 3, 64, 0), (8, 2, 3, 2, 128, 1, 129, 0)])
 def test_attn_core_fwd_both_copy_forms(workspace, opts, n_q, n_kv, tp, rank, d, n_seq, S, pad, causal, parts, copy):
     """The kernels bring key / value tiles to LDS through registers or by DMA (the default at head dimension
-    128 with 16 query rows per wavefront): both forms on ragged lengths, odd and even tile counts, grouped KV
+    128 with 16 query rows per wavefront): both forms on ragged lengths, 1, 2, 3, 4, 8 and 18 key tiles, grouped KV
     heads, rows with padding between them, whole and cut walks."""
     _say(f"attn core fwd copy form {copy}: n_q={n_q} n_kv={n_kv} d={d} n_seq={n_seq} S={S} pad={pad} causal={causal} parts={parts}")
     opts(K.NTP_OPT_ATTN_PARTS, parts)
