@@ -679,6 +679,265 @@ attn_core_fwd_dma_kernel(const CoreArgs a) {
   }  // the workgroup's passes
 }
 
+// ---- forward kernel by DMA, 32 query rows per wavefront ---------------------------------------------------------
+// The form of attn_core_fwd_dma_kernel for launches with many workgroups: a workgroup takes 128 query rows, a wavefront
+// two 16-row blocks, so that every fragment read from LDS feeds two matrix instructions (LDS reads are what a
+// compute unit runs out of first with 16 rows per wavefront).  Two workgroups share a compute unit (64 KB of LDS each).
+template <bool PAIRED>
+__global__ __attribute__((amdgpu_flat_work_group_size(kThreads, kThreads), amdgpu_waves_per_eu(2, 2))) void
+attn_core_fwd_dma2_kernel(const CoreArgs a) {
+  constexpr int D = 128, KS = D / 32, DB = D / 16, QB = 2, kRows = 64 * QB;
+  constexpr int TILE = kDmaTile;
+  constexpr int NI = TILE * 2 / 1024 / 4;  // DMA instructions per wavefront, matrix and tile
+  __shared__ __attribute__((aligned(1024))) uint16_t sK[2 * TILE];
+  __shared__ __attribute__((aligned(1024))) uint16_t sV[2 * TILE];
+
+  const uint32_t bid = xcd_major(blockIdx.x, gridDim.x);
+  const int piece = a.n_parts > 1 ? int(bid % a.n_parts) : 0;
+  const int blk = a.n_parts > 1 ? int(bid / a.n_parts) : int(bid);
+  const int per_seq = PAIRED ? a.pairs : a.q_tiles;
+  const int u = blk % per_seq;
+  const int sh = blk / per_seq;
+  const int seq = sh % a.n_seq, head = sh / a.n_seq;
+  const int g = (a.q_off + head) / a.group - a.kv_off;
+  const int S = a.seq_len;
+  const int64_t tok0 = int64_t(seq) * S;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lq = lane & 15, lh = lane >> 4;
+  const uint16_t* Qp = a.QKV + int64_t(head) * D;
+  const uint16_t* Kp = a.QKV + int64_t(a.q_cnt + g) * D;
+  const uint16_t* Vp = a.QKV + int64_t(a.q_cnt + a.kv_cnt + g) * D;
+  TileSrc<D> srcK, srcV;
+  srcK.init(Kp + tok0 * a.ld, a.ld, S);
+  srcV.init(Vp + tok0 * a.ld, a.ld, S);
+  uint32_t voff[NI];
+#pragma unroll
+  for (int j = 0; j < NI; ++j) {
+    const int p = (wave * NI + j) * 64 + lane;
+    const int row = p >> 4, slot = p & 15;
+    voff[j] = uint32_t((int64_t(row) * a.ld + int64_t(uint32_t(slot) ^ row_swz(row)) * 8) * 2);
+  }
+  auto dma_tile = [&](int t, int buf) {  // rows past the sequence end lie outside the buffer views: zeros
+    const uint32_t soff = uint32_t(t) * srcK.step;
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+      dma_16(srcK.rs, sK + buf * TILE + (wave * NI + j) * 512, voff[j], soff);
+      dma_16(srcV.rs, sV + buf * TILE + (wave * NI + j) * 512, voff[j], soff);
+    }
+  };
+  uint32_t ak[KS], av[DB];
+  {
+    const uint32_t kbase = uint32_t(reinterpret_cast<uintptr_t>(sK)) + uint32_t(lq) * 256u, xk = row_swz(lq);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) ak[ks] = kbase + ((uint32_t(ks * 4 + lh) ^ xk) * 16u);
+    const int rv = lh * 4 + (lq >> 2);
+    const uint32_t vbase = uint32_t(reinterpret_cast<uintptr_t>(sV)) + uint32_t(rv) * 256u + uint32_t(lq & 1) * 8u, xv = row_swz(rv);
+#pragma unroll
+    for (int db = 0; db < DB; ++db) av[db] = vbase + ((uint32_t(db * 2 + ((lq & 3) >> 1)) ^ xv) * 16u);
+  }
+
+  for (int seg = 0; seg < (PAIRED ? 2 : 1); ++seg) {
+  const int qt = PAIRED ? (seg == 0 ? a.q_tiles - 1 - u : u) : (a.causal ? a.q_tiles - 1 - u : u);
+  if (seg == 1) {
+    if (qt == a.q_tiles - 1 - u) break;  // odd tile count: the middle tile has no partner
+    __syncthreads();                     // the first pass's last tile has been read by everyone
+  }
+  const int64_t tblk = int64_t(sh) * a.q_tiles + (a.causal ? a.q_tiles - 1 - qt : qt);
+  const int q0 = qt * kRows + wave * (16 * QB);
+
+  bf16x8 qf[QB][KS];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    const int qr = min(q0 + qb * 16 + lq, S - 1);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = *reinterpret_cast<const bf16x8*>(Qp + (tok0 + qr) * a.ld + ks * 32 + lh * 8);
+  }
+  f32x4 acc[QB][DB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+    for (int db = 0; db < DB; ++db) acc[qb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m_run[QB], l_run[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    m_run[qb] = -INFINITY;
+    l_run[qb] = 0.f;
+  }
+  const int kv_end = a.causal ? min(S, qt * kRows + kRows) : S;
+  const int n_tiles = (kv_end + kBKV - 1) / kBKV;
+  const int t_lo = a.n_parts > 1 ? int(int64_t(piece) * n_tiles / a.n_parts) : 0;
+  const int t_hi = a.n_parts > 1 ? int(int64_t(piece + 1) * n_tiles / a.n_parts) : n_tiles;
+
+  // one key tile out of buffer BUF (a compile-time constant, so that every LDS offset is an immediate)
+  auto tile_step = [&](auto bufc, int t) {
+    constexpr int BUF = decltype(bufc)::value;
+    constexpr int BO = BUF * TILE * 2;  // byte offset of the buffer
+    dma_done();        // this wavefront's share of tile t has landed ...
+    __syncthreads();   // ... and everyone's; everyone has finished reading tile t - 1 in the other buffer
+    if (t + 1 < t_hi) dma_tile(t + 1, BUF ^ 1);
+    const int kv0 = t * kBKV;
+    if (a.causal && kv0 > q0 + 16 * QB - 1) return;  // every key of the tile lies after this wavefront's last query row
+    // scores, transposed: st[kb][qb][r] = S[query qb*16 + lane%16][key kv0 + kb*16 + (lane/16)*4 + r];
+    // key blocks 0-1 first, 2-3 read under their matrix instructions
+    attn_u32x4 k01[8], k23[8];  // [(kb % 2) * 4 + ks]
+    k01[0] = lds_frag_b128<BO + 0 * 4096>(ak[0]); k01[1] = lds_frag_b128<BO + 0 * 4096>(ak[1]); k01[2] = lds_frag_b128<BO + 0 * 4096>(ak[2]); k01[3] = lds_frag_b128<BO + 0 * 4096>(ak[3]);
+    k01[4] = lds_frag_b128<BO + 1 * 4096>(ak[0]); k01[5] = lds_frag_b128<BO + 1 * 4096>(ak[1]); k01[6] = lds_frag_b128<BO + 1 * 4096>(ak[2]); k01[7] = lds_frag_b128<BO + 1 * 4096>(ak[3]);
+    lds_reads_done(k01);
+    k23[0] = lds_frag_b128<BO + 2 * 4096>(ak[0]); k23[1] = lds_frag_b128<BO + 2 * 4096>(ak[1]); k23[2] = lds_frag_b128<BO + 2 * 4096>(ak[2]); k23[3] = lds_frag_b128<BO + 2 * 4096>(ak[3]);
+    k23[4] = lds_frag_b128<BO + 3 * 4096>(ak[0]); k23[5] = lds_frag_b128<BO + 3 * 4096>(ak[1]); k23[6] = lds_frag_b128<BO + 3 * 4096>(ak[2]); k23[7] = lds_frag_b128<BO + 3 * 4096>(ak[3]);
+    f32x4 st[4][QB];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        st[kb][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+          st[kb][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k01[kb * 4 + ks]), qf[qb][ks], st[kb][qb], 0, 0, 0);
+      }
+    __builtin_amdgcn_sched_barrier(0);
+    lds_reads_done(k23);
+    // value fragments of the second product, 8 reads (two 16-column blocks) per group: the first two groups are
+    // requested now and land under the rest of the score product and the softmax
+    attn_u32x2 vf[4][8];  // [db / 2][(db % 2) * 4 + s2 * 2 + half]: keys s2*32 + half*16 .. of the tile
+    vf[0][0] = lds_tr_b64<BO + 0>(av[0]); vf[0][1] = lds_tr_b64<BO + 4096>(av[0]); vf[0][2] = lds_tr_b64<BO + 8192>(av[0]); vf[0][3] = lds_tr_b64<BO + 12288>(av[0]);
+    vf[0][4] = lds_tr_b64<BO + 0>(av[1]); vf[0][5] = lds_tr_b64<BO + 4096>(av[1]); vf[0][6] = lds_tr_b64<BO + 8192>(av[1]); vf[0][7] = lds_tr_b64<BO + 12288>(av[1]);
+#pragma unroll
+    for (int kb = 2; kb < 4; ++kb)
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        st[kb][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+          st[kb][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k23[(kb - 2) * 4 + ks]), qf[qb][ks], st[kb][qb], 0, 0, 0);
+      }
+    __builtin_amdgcn_sched_barrier(0);
+
+    const bool edge = kv0 + kBKV > S || (a.causal && kv0 + kBKV - 1 > q0);
+    bf16x8 pf[QB][2];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      const int qrow = q0 + qb * 16 + lq;
+      if (edge) {
+#pragma unroll
+        for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int key = kv0 + kb * 16 + lh * 4 + r;
+            if (key >= S || (a.causal && key > qrow)) st[kb][qb][r] = -INFINITY;
+          }
+      }
+      float mx = -INFINITY;
+#pragma unroll
+      for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) mx = fmaxf(mx, st[kb][qb][r]);
+      mx = xor_max(mx) * a.scale_log2;
+      const float m_new = fmaxf(m_run[qb], mx);
+      const float m_use = m_new == -INFINITY ? 0.f : m_new;
+      const float alpha = fast_exp2(m_run[qb] - m_use);
+      float ls = 0.f;
+      float pr[4][4];
+#pragma unroll
+      for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          pr[kb][r] = fast_exp2(fmaf(st[kb][qb][r], a.scale_log2, -m_use));
+          ls += pr[kb][r];
+        }
+      l_run[qb] = l_run[qb] * alpha + ls;
+      m_run[qb] = m_new;
+      if (__any(alpha != 1.0f)) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db) acc[qb][db] *= alpha;
+      }
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        bf16x8 f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          f[r] = static_cast<__bf16>(pr[2 * s2][r]);
+          f[4 + r] = static_cast<__bf16>(pr[2 * s2 + 1][r]);
+        }
+        pf[qb][s2] = f;
+      }
+    }
+    // O^T += V^T P^T (key slots of a 32-key step in the order the scores sit in the registers: see
+    // attn_core_fwd_kernel); every group of reads lands under the 8 matrix instructions of the group before it
+    auto pv_group = [&](attn_u32x2 (&f)[8], int db0) {
+#pragma unroll
+      for (int d2 = 0; d2 < 2; ++d2)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          const attn_u32x2 lo = f[d2 * 4 + s2 * 2], hi = f[d2 * 4 + s2 * 2 + 1];
+          const attn_u32x4 both = {lo[0], lo[1], hi[0], hi[1]};
+#pragma unroll
+          for (int qb = 0; qb < QB; ++qb)
+            acc[qb][db0 + d2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, both), pf[qb][s2], acc[qb][db0 + d2], 0, 0, 0);
+        }
+    };
+    lds_reads_done(vf[0]);
+    __builtin_amdgcn_sched_barrier(0);
+    vf[1][0] = lds_tr_b64<BO + 0>(av[2]); vf[1][1] = lds_tr_b64<BO + 4096>(av[2]); vf[1][2] = lds_tr_b64<BO + 8192>(av[2]); vf[1][3] = lds_tr_b64<BO + 12288>(av[2]);
+    vf[1][4] = lds_tr_b64<BO + 0>(av[3]); vf[1][5] = lds_tr_b64<BO + 4096>(av[3]); vf[1][6] = lds_tr_b64<BO + 8192>(av[3]); vf[1][7] = lds_tr_b64<BO + 12288>(av[3]);
+    pv_group(vf[0], 0);
+    __builtin_amdgcn_sched_barrier(0);
+    lds_reads_done(vf[1]);
+    vf[2][0] = lds_tr_b64<BO + 0>(av[4]); vf[2][1] = lds_tr_b64<BO + 4096>(av[4]); vf[2][2] = lds_tr_b64<BO + 8192>(av[4]); vf[2][3] = lds_tr_b64<BO + 12288>(av[4]);
+    vf[2][4] = lds_tr_b64<BO + 0>(av[5]); vf[2][5] = lds_tr_b64<BO + 4096>(av[5]); vf[2][6] = lds_tr_b64<BO + 8192>(av[5]); vf[2][7] = lds_tr_b64<BO + 12288>(av[5]);
+    pv_group(vf[1], 2);
+    __builtin_amdgcn_sched_barrier(0);
+    lds_reads_done(vf[2]);
+    vf[3][0] = lds_tr_b64<BO + 0>(av[6]); vf[3][1] = lds_tr_b64<BO + 4096>(av[6]); vf[3][2] = lds_tr_b64<BO + 8192>(av[6]); vf[3][3] = lds_tr_b64<BO + 12288>(av[6]);
+    vf[3][4] = lds_tr_b64<BO + 0>(av[7]); vf[3][5] = lds_tr_b64<BO + 4096>(av[7]); vf[3][6] = lds_tr_b64<BO + 8192>(av[7]); vf[3][7] = lds_tr_b64<BO + 12288>(av[7]);
+    pv_group(vf[2], 4);
+    __builtin_amdgcn_sched_barrier(0);
+    lds_reads_done(vf[3]);
+    pv_group(vf[3], 6);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  if (t_lo < t_hi) dma_tile(t_lo, 0);
+  for (int t = t_lo; t < t_hi; t += 2) {
+    tile_step(std::integral_constant<int, 0>{}, t);
+    if (t + 1 < t_hi) tile_step(std::integral_constant<int, 1>{}, t + 1);
+  }
+
+  if (a.n_parts > 1) {
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      float* pp = a.part_sums + ((tblk * a.n_parts + piece) * kRows + wave * (16 * QB) + qb * 16 + lq) * (D + 4);
+#pragma unroll
+      for (int db = 0; db < DB; ++db) *reinterpret_cast<f32x4*>(pp + db * 16 + lh * 4) = acc[qb][db];
+      const float l = xor_sum(l_run[qb]);
+      if (lh == 0) {
+        pp[D] = m_run[qb];
+        pp[D + 1] = l;
+      }
+    }
+    continue;
+  }
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    const int qrow = q0 + qb * 16 + lq;
+    const float l = xor_sum(l_run[qb]);
+    const float inv = 1.0f / l;
+    if (qrow < S) {
+      uint16_t* cp = a.C + (tok0 + qrow) * a.ldc + int64_t(head) * D + lh * 4;
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        u16x4 o;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) o[r] = ntp_gemm::f32_to_bf16(acc[qb][db][r] * inv);
+        *reinterpret_cast<u16x4*>(cp + db * 16) = o;
+      }
+      if (lh == 0 && a.LSE) a.LSE[int64_t(head) * (int64_t(a.n_seq) * S) + tok0 + qrow] = (m_run[qb] + log2f(l)) * 0.6931471805599453f;
+    }
+  }
+  }  // the workgroup's passes
+}
+
 // Merges the pieces of a cut forward walk: with m = max_p m_p, the row is sum_p 2^(m_p - m) O_p over
 // sum_p 2^(m_p - m) l_p.  One thread per 4 output values; a piece that saw no key has m_p = -inf, l_p = 0.
 template <int D>
@@ -2083,6 +2342,9 @@ extern "C" int ntp_attn_core_shard_fwd(ntp_handle_t* h, const ntp_attn_core_shap
   if (by_dma) {
     if (a.pairs > 0) hipLaunchKernelGGL((attn_core_fwd_dma_kernel<true>), grid, dim3(kThreads), 0, hs, a);
     else hipLaunchKernelGGL((attn_core_fwd_dma_kernel<false>), grid, dim3(kThreads), 0, hs, a);
+  } else if (s->head_dim == 128 && qbw == 2 && h->opt[NTP_OPT_ATTN_COPY] != 1) {
+    if (a.pairs > 0) hipLaunchKernelGGL((attn_core_fwd_dma2_kernel<true>), grid, dim3(kThreads), 0, hs, a);
+    else hipLaunchKernelGGL((attn_core_fwd_dma2_kernel<false>), grid, dim3(kThreads), 0, hs, a);
   } else if (s->head_dim == 128 && qbw == 2) by_pairing(integral_constant<int, 128>{}, integral_constant<int, 2>{});
   else if (s->head_dim == 128) by_pairing(integral_constant<int, 128>{}, integral_constant<int, 1>{});
   else if (qbw == 2) by_pairing(integral_constant<int, 64>{}, integral_constant<int, 2>{});

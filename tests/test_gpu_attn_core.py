@@ -72,11 +72,18 @@ def test_attn_core_fwd_matches_oracle(n_q, n_kv, tp, rank, d, n_seq, S, causal):
     _case(n_q, n_kv, tp, rank, d, n_seq, S, causal)
 
 
-@pytest.mark.parametrize("n_q,tp,n_seq,S,causal", [(24, 1, 4, 512, False), (32, 1, 8, 512, True)])
-def test_attn_core_fwd_many_workgroups(n_q, tp, n_seq, S, causal):
-    # enough (sequence, head, tile) workgroups for the variant with 32 query rows per wavefront
-    _say(f"attn core fwd, many workgroups: heads {n_q} n_seq {n_seq} S {S} causal {causal}")
-    _case(n_q, n_q, tp, 0, 128, n_seq, S, causal, seed=2)
+@pytest.mark.parametrize("copy", [1, 2], ids=["registers", "dma"])
+@pytest.mark.parametrize("n_q,n_kv,n_seq,S,causal,pad", [(24, 24, 4, 512, False, 0), (32, 32, 8, 512, True, 0), (32, 4, 7, 449, True, 8),
+                                                         (32, 4, 6, 449, False, 8), (48, 48, 3, 1100, True, 0)])
+def test_attn_core_fwd_many_workgroups(opts, n_q, n_kv, n_seq, S, causal, pad, copy):
+    """Enough (sequence, head, tile) workgroups for the variants with 32 query rows per wavefront (tiles copied through
+    registers, or by DMA): whole tiles, ragged lengths with an odd number of 128-row tiles, grouped KV heads, padded rows."""
+    import paper_2504_06095_amd as N
+    _say(f"attn core fwd, many workgroups: heads {n_q}/{n_kv} n_seq {n_seq} S {S} causal {causal} pad {pad} copy {copy}")
+    opts(K.NTP_OPT_ATTN_COPY, copy)
+    plan = N.ntp_attn_shard_plan(n_q, n_kv, 128, 1, 0)
+    assert N.ntp_attn_core_choice(N.attn_core_shape(n_seq, S, plan, n_q // n_kv, causal))["fwd_rows_per_wavefront"] == 32
+    _case(n_q, n_kv, 1, 0, 128, n_seq, S, causal, seed=2, pad=pad)
 
 
 def _bwd_case(n_q, n_kv, tp, rank, d, n_seq, S, causal, seed=1, pad=0):
