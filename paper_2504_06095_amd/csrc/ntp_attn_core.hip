@@ -803,6 +803,8 @@ attn_core_fwd_dma2_kernel(const CoreArgs a) {
     attn_u32x2 vf[4][8];  // [db / 2][(db % 2) * 4 + s2 * 2 + half]: keys s2*32 + half*16 .. of the tile
     vf[0][0] = lds_tr_b64<BO + 0>(av[0]); vf[0][1] = lds_tr_b64<BO + 4096>(av[0]); vf[0][2] = lds_tr_b64<BO + 8192>(av[0]); vf[0][3] = lds_tr_b64<BO + 12288>(av[0]);
     vf[0][4] = lds_tr_b64<BO + 0>(av[1]); vf[0][5] = lds_tr_b64<BO + 4096>(av[1]); vf[0][6] = lds_tr_b64<BO + 8192>(av[1]); vf[0][7] = lds_tr_b64<BO + 12288>(av[1]);
+    vf[1][0] = lds_tr_b64<BO + 0>(av[2]); vf[1][1] = lds_tr_b64<BO + 4096>(av[2]); vf[1][2] = lds_tr_b64<BO + 8192>(av[2]); vf[1][3] = lds_tr_b64<BO + 12288>(av[2]);
+    vf[1][4] = lds_tr_b64<BO + 0>(av[3]); vf[1][5] = lds_tr_b64<BO + 4096>(av[3]); vf[1][6] = lds_tr_b64<BO + 8192>(av[3]); vf[1][7] = lds_tr_b64<BO + 12288>(av[3]);
 #pragma unroll
     for (int kb = 2; kb < 4; ++kb)
 #pragma unroll
@@ -878,19 +880,17 @@ attn_core_fwd_dma2_kernel(const CoreArgs a) {
         }
     };
     lds_reads_done(vf[0]);
+    lds_reads_tied(vf[1]);
     __builtin_amdgcn_sched_barrier(0);
-    vf[1][0] = lds_tr_b64<BO + 0>(av[2]); vf[1][1] = lds_tr_b64<BO + 4096>(av[2]); vf[1][2] = lds_tr_b64<BO + 8192>(av[2]); vf[1][3] = lds_tr_b64<BO + 12288>(av[2]);
-    vf[1][4] = lds_tr_b64<BO + 0>(av[3]); vf[1][5] = lds_tr_b64<BO + 4096>(av[3]); vf[1][6] = lds_tr_b64<BO + 8192>(av[3]); vf[1][7] = lds_tr_b64<BO + 12288>(av[3]);
-    pv_group(vf[0], 0);
-    __builtin_amdgcn_sched_barrier(0);
-    lds_reads_done(vf[1]);
     vf[2][0] = lds_tr_b64<BO + 0>(av[4]); vf[2][1] = lds_tr_b64<BO + 4096>(av[4]); vf[2][2] = lds_tr_b64<BO + 8192>(av[4]); vf[2][3] = lds_tr_b64<BO + 12288>(av[4]);
     vf[2][4] = lds_tr_b64<BO + 0>(av[5]); vf[2][5] = lds_tr_b64<BO + 4096>(av[5]); vf[2][6] = lds_tr_b64<BO + 8192>(av[5]); vf[2][7] = lds_tr_b64<BO + 12288>(av[5]);
-    pv_group(vf[1], 2);
+    pv_group(vf[0], 0);
     __builtin_amdgcn_sched_barrier(0);
-    lds_reads_done(vf[2]);
     vf[3][0] = lds_tr_b64<BO + 0>(av[6]); vf[3][1] = lds_tr_b64<BO + 4096>(av[6]); vf[3][2] = lds_tr_b64<BO + 8192>(av[6]); vf[3][3] = lds_tr_b64<BO + 12288>(av[6]);
     vf[3][4] = lds_tr_b64<BO + 0>(av[7]); vf[3][5] = lds_tr_b64<BO + 4096>(av[7]); vf[3][6] = lds_tr_b64<BO + 8192>(av[7]); vf[3][7] = lds_tr_b64<BO + 12288>(av[7]);
+    pv_group(vf[1], 2);
+    __builtin_amdgcn_sched_barrier(0);
+    lds_reads_left<8>(vf[2]);
     pv_group(vf[2], 4);
     __builtin_amdgcn_sched_barrier(0);
     lds_reads_done(vf[3]);
