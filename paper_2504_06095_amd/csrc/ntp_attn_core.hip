@@ -2176,19 +2176,35 @@ __global__ __launch_bounds__(256) void attn_core_part_reduce_kernel(const CoreBw
 // gain only from parts of more than 16 tiles (the merge pass and the per-workgroup prologue cost more than shorter
 // parts gain); a causal walk of 40 tiles or more per part takes one part more.
 int choose_parts(const ntp_handle* h, int64_t ws_bytes, int64_t wgs, int64_t slots, int64_t walk, int64_t bytes_per_part, double fill,
-                 int64_t cap, bool causal, int64_t near_full_min = 0) {
+                 int64_t cap, bool causal) {
   if (ws_bytes <= 0 || wgs <= 0) return 1;
   const int64_t cus = h->compute_units;
   int64_t parts = std::min<int64_t>(cap, std::max<int64_t>(1, int64_t(fill * double(cus) / double(wgs) + 0.5)));
   parts = std::min<int64_t>(parts, std::max<int64_t>(1, walk / 6));
   if (wgs > cus)
     while (parts > 1 && walk / parts <= 16) --parts;
-  else if (wgs * 4 >= cus * 3)  // nearly one workgroup per compute unit already
-    while (parts > 1 && walk / parts <= near_full_min) --parts;
   if (causal && parts < cap && walk / parts >= 40 && wgs * parts < 3 * cus) ++parts;
   // tests reach every cut through this override (1..16 parts at any size)
   if (const int64_t f = h->opt[NTP_OPT_ATTN_PARTS]) parts = std::min<int64_t>(16, std::max<int64_t>(1, f));
   while (parts > 1 && slots * parts * bytes_per_part > ws_bytes) --parts;
+  return int(std::max<int64_t>(parts, 1));
+}
+
+// The same for the kernels that copy by DMA (two workgroups of 64-65 KB LDS per compute unit), from a sweep over 2 to
+// 32 heads x 1024 to 8192 tokens, both masks, 1-8 parts, one and two backward launches: the walk is cut until the
+// launch has `slots` workgroups (forward: two per compute unit; dQ and dK/dV: one per compute unit each, they share a
+// launch), never into parts of fewer than 8 tiles, and into parts of fewer than `long_part` tiles only while the
+// launch still leaves compute units idle (fewer than `idle` workgroups): short parts cost their second pass and
+// their prologues, and once every compute unit has work they no longer buy anything.
+int choose_parts_dma(const ntp_handle* h, int64_t ws_bytes, int64_t wgs, int64_t slots_ws, int64_t walk, int64_t bytes_per_part,
+                     int64_t slots, int64_t long_part, int64_t idle) {
+  if (ws_bytes <= 0 || wgs <= 0) return 1;
+  const int64_t pmax = std::min<int64_t>(16, std::max<int64_t>(1, slots / wgs));
+  int64_t parts = 1;
+  while (parts + 1 <= pmax && walk / (parts + 1) >= 8 && (walk / (parts + 1) >= long_part || wgs * parts < idle)) ++parts;
+  // tests reach every cut through this override (1..16 parts at any size)
+  if (const int64_t f = h->opt[NTP_OPT_ATTN_PARTS]) parts = std::min<int64_t>(16, std::max<int64_t>(1, f));
+  while (parts > 1 && slots_ws * parts * bytes_per_part > ws_bytes) --parts;
   return int(std::max<int64_t>(parts, 1));
 }
 
@@ -2219,30 +2235,32 @@ CoreChoice choose_core(const ntp_handle* h, int64_t ws_bytes, const ntp_attn_cor
   const int64_t wq = per_seq * s->n_seq * s->q_cnt, wk = per_seq * s->n_seq * s->kv_cnt;
   const int64_t bf = int64_t(64) * (s->head_dim + 4) * 4, bdq = int64_t(64) * s->head_dim * 4, bdkv = int64_t(64) * 2 * s->head_dim * 4;
   const double fill = causal ? 2.0 : 3.0;
-  // the kernels that copy by DMA spend less per tile, so the second pass over the parts weighs more: under the
-  // causal mask, with 3/4 of the compute units busy anyway, parts of 23 tiles or fewer no longer pay (14 heads x
-  // 2048: forward 42 us cut in two, 39 us whole, dQ 48 and 44 us, dK/dV 64 and 55 us; 3 heads x 8192, parts of 32
-  // tiles: forward 97 us against 128 us whole)
   const bool dma = s->head_dim == 128 && h->opt[NTP_OPT_ATTN_COPY] != 1;
-  const int64_t near_full_min = dma && causal ? 23 : 0;
-  c.fwd_parts = choose_parts(h, ws_bytes, wq, bq, walk, bf, fill, 12, causal, near_full_min);
-  if (c.fwd_parts > 1) c.fwd_rows = 16;
-  c.dq_parts = choose_parts(h, ws_bytes, wq, bq, walk, bdq, fill, 12, causal, near_full_min);
-  c.dq_dma = c.dkv_dma = dma;
+  const int64_t cus = h->compute_units;
   // a dK/dV workgroup walks over the query tiles of every query head that reads its KV head
   const int64_t heads_per_kv = std::min<int64_t>(s->group, s->q_cnt);
-  c.dkv_parts = choose_parts(h, ws_bytes, wk, bk, heads_per_kv * walk, bdkv, 2.0, 16, false, near_full_min);
+  if (dma) {
+    // (a launch that occupies 3/4 of the compute units uncut needs parts of 24 tiles to gain from a cut: 14 heads x
+    // 2048 tokens causal forward 42 us cut in two, 39 us whole; 8 heads x 2048 unmasked 36 and 33 us)
+    c.fwd_parts = choose_parts_dma(h, ws_bytes, wq, bq, walk, bf, 2 * cus, wq * 4 >= cus * 3 ? 24 : 16, cus * 3 / 4);
+    c.dq_parts = choose_parts_dma(h, ws_bytes, wq, bq, walk, bdq, cus, 10, cus * 3 / 8);
+    c.dkv_parts = choose_parts_dma(h, ws_bytes, wk, bk, heads_per_kv * walk, bdkv, cus, 10, cus * 3 / 8);
+  } else {
+    c.fwd_parts = choose_parts(h, ws_bytes, wq, bq, walk, bf, fill, 12, causal);
+    c.dq_parts = choose_parts(h, ws_bytes, wq, bq, walk, bdq, fill, 12, causal);
+    c.dkv_parts = choose_parts(h, ws_bytes, wk, bk, heads_per_kv * walk, bdkv, 2.0, 16, false);
+  }
+  if (c.fwd_parts > 1) c.fwd_rows = 16;
+  c.dq_dma = c.dkv_dma = dma;
   if (c.fwd_parts > 1) c.ws_bytes = std::max(c.ws_bytes, bq * c.fwd_parts * bf);
   const int64_t dq_bytes = c.dq_parts > 1 ? bq * c.dq_parts * bdq : 0, dkv_bytes = c.dkv_parts > 1 ? bk * c.dkv_parts * bdkv : 0;
   // the two DMA kernels share a launch (attn_core_bwd_both_kernel) where the workspace holds both kernels' parts
   // at once; NTP_OPT_ATTN_BWD_LAUNCHES: 1 always two launches, 2 one launch wherever the kernels allow
   c.dkv_ws_offset = (dq_bytes + 255) / 256 * 256;
-  // Where it pays (3 and 14-16 heads, 2048-8192 tokens, both masks): launches that together stay under 2.5
-  // workgroups per compute unit (14 heads x 2048 causal: 98 -> 80 us; 16 heads x 2 x 2048 causal 177 -> 168) and
-  // cut walks (3 heads x 4096: 97 -> 93 us causal, 126 -> 121 unmasked); launches that each fill the device
-  // alone lose 1-6 % to the extra kernel and stay apart.
-  const int64_t dq_w = wq * c.dq_parts, dkv_w = wk * c.dkv_parts;
-  const bool pays = (dq_w + dkv_w) * 2 <= 5 * int64_t(h->compute_units) || (c.dq_parts > 1 && c.dkv_parts > 1);
+  // Where it pays (the sweep above): wherever the two launches, uncut, have at most 3 workgroups per compute unit
+  // between them (14 heads x 2048 causal: 98 -> 77 us; 8 heads x 4096 causal 175 -> 143; 4 heads x 4096 unmasked
+  // 146 -> 122); larger launches fill the device on their own and lose 1-4 % to the extra kernel.
+  const bool pays = wq + wk <= 3 * cus;
   c.bwd_both = c.dq_dma && c.dkv_dma && h->opt[NTP_OPT_ATTN_BWD_LAUNCHES] != 1 && (pays || h->opt[NTP_OPT_ATTN_BWD_LAUNCHES] == 2) &&
                (dkv_bytes == 0 || c.dkv_ws_offset + dkv_bytes <= ws_bytes);
   c.ws_bytes = std::max(c.ws_bytes, c.bwd_both ? (dkv_bytes ? c.dkv_ws_offset + dkv_bytes : dq_bytes) : std::max(dq_bytes, dkv_bytes));

@@ -28,47 +28,44 @@ def test_nothing_is_cut_without_a_workspace():
 
 def test_few_heads_get_cut_walks(workspace_1gib):
     # config 3, rank 0: 3 query heads on 1 KV head, one causal sequence of 4096 tokens (64 tiles, taken in 32 pairs):
-    # 96 forward / dQ workgroups and 32 dK/dV workgroups with walks of 65 and 195 tiles -> about 512 workgroups each
+    # 96 forward / dQ workgroups with walks of 65 tiles and 32 dK/dV workgroups with walks of 195.  The forward launch is
+    # cut towards two workgroups per compute unit, the two backward kernels (one launch) towards one each
     c = N.ntp_attn_core_choice(_shape(64, 8, 30, 0, 1, 4096, True))
-    assert c == dict(fwd_rows_per_wavefront=16, fwd_parts=5, dq_parts=5, dkv_parts=16)
+    assert c == dict(fwd_rows_per_wavefront=16, fwd_parts=4, dq_parts=2, dkv_parts=8)
     # the same heads without the mask: 192 and 64 workgroups with walks of 64 and 192 tiles
     c = N.ntp_attn_core_choice(_shape(64, 8, 30, 0, 1, 4096, False))
-    assert c == dict(fwd_rows_per_wavefront=16, fwd_parts=4, dq_parts=4, dkv_parts=8)
-    # ... and at 8192 tokens (384 workgroups, more than compute units, but parts of 64 tiles still pay)
+    assert c == dict(fwd_rows_per_wavefront=16, fwd_parts=2, dq_parts=1, dkv_parts=4)
+    # ... and at 8192 tokens (384 and 128 workgroups)
     c = N.ntp_attn_core_choice(_shape(64, 8, 30, 0, 1, 8192, False))
-    assert (c["fwd_parts"], c["dq_parts"], c["dkv_parts"]) == (2, 2, 4)
+    assert (c["fwd_parts"], c["dq_parts"], c["dkv_parts"]) == (1, 1, 2)
     # many heads and tokens: nothing to gain, and the forward kernel takes 32 rows per wavefront
     c = N.ntp_attn_core_choice(_shape(16, 16, 1, 0, 2, 8192, False))
     assert c == dict(fwd_rows_per_wavefront=32, fwd_parts=1, dq_parts=1, dkv_parts=1)
 
 
-def test_mid_range_is_cut_only_under_the_causal_mask(workspace_1gib):
-    # 14 heads x 2048 tokens: 448 forward workgroups of 32 tiles each, or 224 of 33 with the causal pairs;
-    # grouped KV heads leave 64 (32) dK/dV workgroups
+def test_launches_that_fill_the_device_stay_whole(workspace_1gib):
+    # 14 heads x 2048 tokens: 448 forward workgroups of 32 tiles each, or 224 of 33 with the causal pairs: parts of 16
+    # tiles would not pay; grouped KV heads leave 64 (32) dK/dV workgroups with walks of 7 heads' tiles
     causal = N.ntp_attn_core_choice(_shape(96, 8, 7, 0, 1, 2048, True))
     full = N.ntp_attn_core_choice(_shape(96, 8, 7, 0, 1, 2048, False))
-    assert (causal["fwd_parts"], causal["dq_parts"]) == (1, 1)  # 7/8 of the compute units busy: parts of 16 do not pay either
-    assert (full["fwd_parts"], full["dq_parts"]) == (1, 1)  # parts of 16 tiles would not pay for their merge
-    assert (causal["dkv_parts"], full["dkv_parts"]) == (16, 8)
+    assert (causal["fwd_parts"], causal["dq_parts"]) == (1, 1)
+    assert (full["fwd_parts"], full["dq_parts"]) == (1, 1)
+    assert (causal["dkv_parts"], full["dkv_parts"]) == (8, 4)
 
 
 def test_step_shape_keeps_whole_walks_with_the_dma_kernels(workspace_1gib):
     # 14 query and 14 KV heads x 2048 tokens, causal: 224 workgroups of 33 tiles in all three launches
     c = N.ntp_attn_core_choice(_shape(96, 96, 7, 0, 1, 2048, True))
     assert c == dict(fwd_rows_per_wavefront=16, fwd_parts=1, dq_parts=1, dkv_parts=1)
+
+
+def test_register_copy_kernels_keep_their_own_rule(workspace_1gib):
     N.ntp_set_option(Bd.NTP_OPT_ATTN_COPY, 1)
     try:
         c = N.ntp_attn_core_choice(_shape(96, 96, 7, 0, 1, 2048, True))
         assert c == dict(fwd_rows_per_wavefront=16, fwd_parts=2, dq_parts=2, dkv_parts=2)
-    finally:
-        N.ntp_set_option(Bd.NTP_OPT_ATTN_COPY, 0)
-
-
-def test_register_copy_forward_keeps_the_shorter_parts(workspace_1gib):
-    N.ntp_set_option(Bd.NTP_OPT_ATTN_COPY, 1)
-    try:
-        c = N.ntp_attn_core_choice(_shape(96, 8, 7, 0, 1, 2048, True))
-        assert (c["fwd_parts"], c["dq_parts"]) == (2, 2)
+        c = N.ntp_attn_core_choice(_shape(64, 8, 30, 0, 1, 4096, True))
+        assert c == dict(fwd_rows_per_wavefront=16, fwd_parts=5, dq_parts=5, dkv_parts=16)
     finally:
         N.ntp_set_option(Bd.NTP_OPT_ATTN_COPY, 0)
 
