@@ -260,6 +260,54 @@ def test_attn_core_at_the_step_shape(workspace, causal):
     _bwd_case(96, 96, 7, 0, 128, 1, 2048, causal, seed=13)
 
 
+@pytest.mark.parametrize("causal", [False, True], ids=["full", "causal"])
+def test_attn_core_long_sequence_sampled_rows(workspace, causal):
+    """14 heads x 128, one sequence of 8192 tokens (128 key tiles per walk; the forward kernel with 32 query rows per
+    wavefront, the backward kernels with their longest walks of the benchmark): the oracle computes sampled query rows
+    one by one (Eq. 5 is separable over query rows: row t needs the keys and values it sees and nothing else), output,
+    log-sum-exp and dQ; the rows include the first and last of the sequence and both sides of tile borders."""
+    import torch
+    import paper_2504_06095_amd as N
+    _say(f"attn core, 8192 tokens, sampled rows, causal={causal}")
+    n_q, tp, d, S = 96, 7, 128, 8192
+    plan = N.ntp_attn_shard_plan(n_q, n_q, d, tp, 0)
+    qc = plan["q_cnt"]
+    wq, wo = plan["w_qkv"], plan["w_o"]
+    bits, vals = I.normal_bf16(31, f"core.long.QKV.{causal}", (S, wq), 1.0)
+    gbits, gvals = I.normal_bf16(31, f"core.long.dC.{causal}", (S, wo), 1.0)
+    QKV, dC = Hh.to_dev_bf16(bits, wq), Hh.to_dev_bf16(gbits, wo)
+    nan = lambda r, c: torch.full((r, c), float("nan"), dtype=torch.bfloat16, device="cuda")
+    C, dQKV = nan(S, wo), nan(S, wq)
+    LSE = torch.full((qc, S), float("nan"), dtype=torch.float32, device="cuda")
+    Delta = torch.full((qc, S), float("nan"), dtype=torch.float32, device="cuda")
+    shape = N.attn_core_shape(1, S, plan, 1, causal)
+    assert N.ntp_attn_core_choice(shape)["fwd_rows_per_wavefront"] == 32
+    N.ntp_attn_core_shard_fwd(shape, QKV, C, LSE)
+    N.ntp_attn_core_shard_bwd(shape, QKV, C, dC, LSE, Delta, dQKV)
+    torch.cuda.synchronize()
+    got_c, got_dq = Hh.dev_bf16_to_f64(C), Hh.dev_bf16_to_f64(dQKV)[:, :qc * d]
+    assert np.isfinite(got_c).all() and np.isfinite(Hh.dev_bf16_to_f64(dQKV)).all()
+    lse = LSE.cpu().numpy().astype(np.float64)
+    rows = sorted({0, 1, 15, 16, 63, 64, 65, 127, 128, 129, 4095, 4096, 4097, 8127, 8128, 8190, 8191} |
+                  {int(r) for r in np.random.default_rng(5).integers(0, S, 16)})
+    x, g = vals.astype(np.float64), gvals.astype(np.float64)
+    worst_c = worst_dq = 0.0
+    for j in range(qc):
+        Kh, Vh = x[:, (qc + j) * d:(qc + j + 1) * d], x[:, (2 * qc + j) * d:(2 * qc + j + 1) * d]
+        want_c, want_dq, want_l = [], [], []
+        for t in rows:
+            n = t + 1 if causal else S
+            q = x[t:t + 1, j * d:(j + 1) * d]
+            want_c.append(O.attention_core(q, Kh[:n], Vh[:n])[0])
+            want_l.append(O.attention_lse(q, Kh[:n])[0])
+            want_dq.append(O.attention_core_bwd(q, Kh[:n], Vh[:n], g[t:t + 1, j * d:(j + 1) * d])[0][0])
+        want_c, want_dq, want_l = np.array(want_c), np.array(want_dq), np.array(want_l)
+        worst_c = max(worst_c, Hh.rel_err(got_c[rows, j * d:(j + 1) * d], want_c))
+        worst_dq = max(worst_dq, Hh.rel_err(got_dq[rows, j * d:(j + 1) * d], want_dq))
+        assert np.abs(lse[j, rows] - want_l).max() <= 2e-2 * max(1.0, np.abs(want_l).max()), j
+    assert worst_c <= Hh.TOL and worst_dq <= Hh.TOL, (worst_c, worst_dq)
+
+
 def test_attn_core_fwd_cut_peaked_scores(workspace, opts):
     """Large scores: the pieces' maxima differ by hundreds, so most pieces merge with weight zero."""
     _say("attn core fwd cut: peaked scores")
