@@ -265,7 +265,8 @@ def test_attn_core_long_sequence_sampled_rows(workspace, causal):
     """14 heads x 128, one sequence of 8192 tokens (128 key tiles per walk; the forward kernel with 32 query rows per
     wavefront, the backward kernels with their longest walks of the benchmark): the oracle computes sampled query rows
     one by one (Eq. 5 is separable over query rows: row t needs the keys and values it sees and nothing else), output,
-    log-sum-exp and dQ; the rows include the first and last of the sequence and both sides of tile borders."""
+    log-sum-exp and dQ; the rows include the first and last of the sequence and both sides of tile borders.  One
+    head is also computed in full for dQ, dK and dV."""
     import torch
     import paper_2504_06095_amd as N
     _say(f"attn core, 8192 tokens, sampled rows, causal={causal}")
@@ -306,6 +307,13 @@ def test_attn_core_long_sequence_sampled_rows(workspace, causal):
         worst_dq = max(worst_dq, Hh.rel_err(got_dq[rows, j * d:(j + 1) * d], want_dq))
         assert np.abs(lse[j, rows] - want_l).max() <= 2e-2 * max(1.0, np.abs(want_l).max()), j
     assert worst_c <= Hh.TOL and worst_dq <= Hh.TOL, (worst_c, worst_dq)
+    # one head in full (its 8192 x 8192 scores fit the host): dQ, dK and dV of every token
+    j = 5
+    cols = lambda base: slice((base + j) * d, (base + j + 1) * d)
+    dq, dk, dv = O.attention_core_bwd(x[:, cols(0)], x[:, cols(qc)], x[:, cols(2 * qc)], g[:, cols(0)], causal)
+    got = Hh.dev_bf16_to_f64(dQKV)
+    for name, base, want in (("dQ", 0, dq), ("dK", qc, dk), ("dV", 2 * qc, dv)):
+        assert Hh.rel_err(got[:, cols(base)], want) <= Hh.TOL, (name, Hh.rel_err(got[:, cols(base)], want))
 
 
 def test_attn_core_fwd_cut_peaked_scores(workspace, opts):
